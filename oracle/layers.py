@@ -1,0 +1,88 @@
+"""Textbook layer maths in fp64, with the rounding points of the bf16 mode.
+
+Test infrastructure only (see package docstring).  The paper delegates layer
+compute to its ML worker (Section 4) and gives no formulas, so each routine is
+the standard definition written out:
+
+  Linear          y = x W^T + b,  W[out][in]
+  ReLU            max(y, 0); derivative 1 where the stored output is > 0, else 0
+  softmax-xent    L = mean_rows( logsumexp(z) - z[label] ),  dz = (softmax(z) - onehot) / rows
+
+Precision modes.  "f32": no rounding anywhere (pure fp64; the HIP path computes
+in fp32 and is compared at 1e-4).  "bf16": tensors that the mixed-precision path
+keeps in bfloat16 -- ring weights, activations handed between layers and stages,
+activation gradients -- are rounded to the nearest bfloat16 (ties to even) at
+the moment they are stored; sums, bias add, loss, weight gradients, master
+weights and momentum are not rounded.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """Nearest bfloat16 (8 significand bits), ties to even, returned as float64.
+
+    Goes through float32 first (as hardware that accumulates in fp32 does), then
+    drops the low 16 bits with the usual add-half-then-truncate on the bit pattern.
+    """
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    r = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)) << np.uint64(16)
+    out = (r & np.uint64(0xFFFFFFFF)).astype(np.uint32).view(np.float32).astype(np.float64)
+    nan = np.isnan(f)
+    if nan.any():
+        out = np.where(nan, np.nan, out)
+    return out.reshape(np.shape(x))
+
+
+def quantiser(mode: str):
+    if mode == "f32":
+        return lambda a: np.asarray(a, dtype=np.float64)
+    if mode == "bf16":
+        return round_bf16
+    raise ValueError("mode must be 'f32' or 'bf16'")
+
+
+# ---- Linear (+ optional ReLU) ------------------------------------------------
+
+def linear_forward(x, W, b, relu: bool, q):
+    """x[rows][in], W[out][in], b[out] -> stored output y[rows][out]."""
+    z = x @ W.T + b
+    if relu:
+        z = np.maximum(z, 0.0)
+    return q(z)
+
+
+def linear_backward(x, W, y, dy, relu: bool, need_dx: bool, q):
+    """Gradients of a Linear(+ReLU) given its stored input x, stored output y and dL/dy.
+
+    Returns (dx or None, dW, db).  dW and db stay unrounded; dx is an activation
+    gradient and is rounded when stored.
+    """
+    dz = dy * (y > 0.0) if relu else dy
+    dW = dz.T @ x
+    db = dz.sum(axis=0)
+    dx = q(dz @ W) if need_dx else None
+    return dx, dW, db
+
+
+# ---- softmax cross-entropy ---------------------------------------------------
+
+def softmax_xent_forward(z, labels):
+    """Mean over rows of -log softmax(z)[label]; also returns softmax(z)."""
+    zmax = z.max(axis=1, keepdims=True)
+    e = np.exp(z - zmax)
+    ssum = e.sum(axis=1, keepdims=True)
+    p = e / ssum
+    rows = np.arange(z.shape[0])
+    loss = float(np.mean(np.log(ssum[:, 0]) + zmax[:, 0] - z[rows, labels]))
+    return loss, p
+
+
+def softmax_xent_backward(p, labels, q):
+    """dL/dz for the mean loss: (p - onehot) / rows, stored as an activation gradient."""
+    d = p.copy()
+    d[np.arange(p.shape[0]), labels] -= 1.0
+    return q(d / p.shape[0])

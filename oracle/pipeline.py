@@ -1,0 +1,233 @@
+"""Stage state and the 1F1B weight-stashed step, in the paper's order (Sections 3.3-3.5, 4).
+
+Test infrastructure only (see package docstring).
+
+A stage keeps: ``latest`` (updates applied so far), every weight version it has
+produced (the paper keeps a version until no in-flight minibatch needs it,
+Section 4 "Parameter State"; keeping all of them gives the same numbers and lets
+tests inspect history -- ring-slot reuse is asserted separately), one momentum
+buffer, and a stash per in-flight minibatch holding the version id and the
+layer inputs/outputs its backward needs (Section 4 "Intermediate State").
+
+Update rule (the paper states SGD, momentum 0.9, lr 0.01 in Section 5.1 and the
+plain-SGD equation in Section 3.4; the momentum form is the common one):
+    m <- mu * m + g ;  w_latest <- w_latest - lr * m
+with g the gradient of the minibatch-mean loss, applied once per backward pass to
+the latest weights (not to the stashed ones).
+"""
+from __future__ import annotations
+
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+from . import layers as L
+from .schedule import OP_B, OP_F, OP_U, Op, in_flight_depth, schedule_1f1b
+
+
+def _split_params(layers, flat):
+    """Views (W, b) per parametrised layer into a flat vector laid out layer by layer, W then b."""
+    out, o = [], 0
+    for ly in layers:
+        if ly[0] == "linear":
+            n_in, n_out = ly[1], ly[2]
+            W = flat[o:o + n_in * n_out].reshape(n_out, n_in); o += n_in * n_out
+            b = flat[o:o + n_out]; o += n_out
+            out.append((W, b))
+        else:
+            out.append(None)
+    assert o == flat.size, "parameter vector does not match the layer list"
+    return out
+
+
+class Stage:
+    def __init__(self, layers, params_fp32, depth: int, mode: str = "f32",
+                 lr: float = 0.01, momentum: float = 0.9, stashing: bool = True):
+        self.layers = list(layers)
+        self.depth = int(depth)
+        self.mode = mode
+        self.q = L.quantiser(mode)
+        self.lr, self.mu = float(lr), float(momentum)
+        self.stashing = stashing              # False = the naive pipeline of Section 3.4 (negative control)
+        self.master = np.asarray(params_fp32, dtype=np.float64).copy()
+        self.versions = [self.q(self.master)]  # versions[v] = weights as the layers read them
+        self.mom = np.zeros_like(self.master)
+        self.latest = 0
+        self.stash = {}                       # mb -> dict(version, acts, labels, probs)
+        self.grad = None                      # flat gradient of the last backward, until update() consumes it
+        self.trace: List[Op] = []
+        self.max_in_flight = 0
+
+    # -- F ---------------------------------------------------------------------
+    def forward(self, mb: int, x, labels=None):
+        if len(self.stash) >= self.depth:
+            raise RuntimeError("more minibatches in flight than the stage's depth")
+        v = self.latest                                           # latest version available
+        P = _split_params(self.layers, self.versions[v])
+        acts = [self.q(x)]
+        loss, probs = None, None
+        for ly, p in zip(self.layers, P):
+            if ly[0] == "linear":
+                acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], self.q))
+            elif ly[0] == "softmax_xent":
+                loss, probs = L.softmax_xent_forward(acts[-1], labels)
+            else:
+                raise NotImplementedError(ly[0])
+        self.stash[mb] = dict(version=v, acts=acts, labels=labels, probs=probs)
+        self.max_in_flight = max(self.max_in_flight, len(self.stash))
+        self.trace.append(Op(OP_F, mb, v, v % self.depth))
+        return acts[-1], loss
+
+    # -- B ---------------------------------------------------------------------
+    def backward(self, mb: int, dy=None, need_dx: bool = True):
+        if mb != min(self.stash):
+            raise RuntimeError("backward must take the oldest in-flight minibatch")
+        st = self.stash.pop(mb)                                   # releases the stash (Section 4)
+        v = st["version"] if self.stashing else self.latest       # same version as the forward
+        P = _split_params(self.layers, self.versions[v])
+        g = np.zeros_like(self.master)
+        G = _split_params(self.layers, g)
+        acts = st["acts"]
+        d = None if dy is None else self.q(dy)
+        k = len(acts) - 1                                         # index of the current layer's output
+        for li in range(len(self.layers) - 1, -1, -1):
+            ly = self.layers[li]
+            if ly[0] == "softmax_xent":
+                d = L.softmax_xent_backward(st["probs"], st["labels"], self.q)
+            elif ly[0] == "linear":
+                first = li == 0
+                dx, dW, db = L.linear_backward(acts[k - 1], P[li][0], acts[k], d, ly[3],
+                                               need_dx or not first, self.q)
+                G[li][0][...] = dW
+                G[li][1][...] = db
+                d = dx
+                k -= 1
+        self.grad = g
+        self.trace.append(Op(OP_B, mb, v, v % self.depth))
+        return d
+
+    # -- U ---------------------------------------------------------------------
+    def update(self, mb: int = -1):
+        if self.grad is None:
+            raise RuntimeError("update without a pending gradient")
+        self.mom = self.mu * self.mom + self.grad
+        self.master = self.master - self.lr * self.mom            # onto the latest weights
+        self.grad = None
+        self.latest += 1
+        self.versions.append(self.q(self.master))
+        self.trace.append(Op(OP_U, mb, self.latest, self.latest % self.depth))
+
+    def live_versions(self):
+        """Versions some in-flight minibatch still needs, plus the latest."""
+        return sorted({st["version"] for st in self.stash.values()} | {self.latest})
+
+
+def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels, noam_: int,
+                 mode: str = "f32", lr: float = 0.01, momentum: float = 0.9,
+                 stashing: bool = True, depth_override: int = 0):
+    """All stages, each following its own static op list, run as soon as their data exists.
+
+    inputs[i] / labels[i] belong to minibatch i.  Returns (stages, losses).  Any
+    order that respects the data dependencies gives the same numbers, because each
+    stage's own order is fixed (Section 3.3: the policy is static).
+    """
+    S, M = len(stage_layers), len(inputs)
+    depths = [depth_override or in_flight_depth(S, noam_, M, s) for s in range(S)]
+    stages = [Stage(stage_layers[s], stage_params[s], depths[s], mode, lr, momentum, stashing)
+              for s in range(S)]
+    lists = [schedule_1f1b(S, noam_, M, s, depth_override) for s in range(S)]
+    pos = [0] * S
+    act = {}     # (mb, producing stage) -> activation for the next stage
+    grad = {}    # (mb, producing stage) -> gradient for the previous stage
+    losses: List[Optional[float]] = [None] * M
+    remaining = sum(len(l) for l in lists)
+    while remaining:
+        progressed = False
+        for s in range(S):
+            while pos[s] < len(lists[s]):
+                op = lists[s][pos[s]]
+                st = stages[s]
+                if op.kind == OP_F:
+                    if s > 0 and (op.mb, s - 1) not in act:
+                        break
+                    x = inputs[op.mb] if s == 0 else act.pop((op.mb, s - 1))
+                    y, loss = st.forward(op.mb, x, labels[op.mb] if s == S - 1 else None)
+                    if s == S - 1:
+                        losses[op.mb] = loss
+                    else:
+                        act[(op.mb, s)] = y
+                elif op.kind == OP_B:
+                    if s < S - 1 and (op.mb, s + 1) not in grad:
+                        break
+                    dy = None if s == S - 1 else grad.pop((op.mb, s + 1))
+                    dx = st.backward(op.mb, dy, need_dx=(s > 0))
+                    if s > 0:
+                        grad[(op.mb, s)] = dx
+                else:
+                    st.update(op.mb)
+                # the stage really did what its static list said, version included
+                # (with stashing off, B deliberately reads another version than listed)
+                assert st.trace[-1] == op or (not stashing and op.kind == OP_B), (st.trace[-1], op)
+                pos[s] += 1
+                remaining -= 1
+                progressed = True
+        if not progressed:
+            raise RuntimeError("pipeline deadlock")
+    return stages, losses
+
+
+def flat_loop(stage_layers: Sequence, stage_params: Sequence, inputs, labels, depths: Sequence[int],
+              mode: str = "f32", lr: float = 0.01, momentum: float = 0.9):
+    """The staleness equation of Section 3.4 as a loop, with no schedule at all.
+
+    For t = 0..M-1: every stage s contributes its weights as they were after
+    max(0, t - depth_s + 1) updates; an ordinary whole-model forward and backward of
+    minibatch t runs on that composite; then every stage takes one momentum-SGD
+    step from its *current* weights.  (The clamp at 0 covers start-up, which the
+    equation leaves out.)  Returns (history[s][t], losses).
+    """
+    S, M = len(stage_layers), len(inputs)
+    q = L.quantiser(mode)
+    master = [np.asarray(p, dtype=np.float64).copy() for p in stage_params]
+    hist = [[q(master[s])] for s in range(S)]
+    mom = [np.zeros_like(m) for m in master]
+    losses = []
+    for t in range(M):
+        W = [hist[s][max(0, t - depths[s] + 1)] for s in range(S)]
+        # whole-model forward
+        acts_all, a = [], q(inputs[t])
+        loss = probs = None
+        for s in range(S):
+            P = _split_params(stage_layers[s], W[s])
+            acts = [a]
+            for ly, p in zip(stage_layers[s], P):
+                if ly[0] == "linear":
+                    acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], q))
+                elif ly[0] == "softmax_xent":
+                    loss, probs = L.softmax_xent_forward(acts[-1], labels[t])
+            acts_all.append(acts)
+            a = acts[-1]
+        losses.append(loss)
+        # whole-model backward
+        d = None
+        for s in range(S - 1, -1, -1):
+            P = _split_params(stage_layers[s], W[s])
+            g = np.zeros_like(master[s])
+            G = _split_params(stage_layers[s], g)
+            acts = acts_all[s]
+            k = len(acts) - 1
+            for li in range(len(stage_layers[s]) - 1, -1, -1):
+                ly = stage_layers[s][li]
+                if ly[0] == "softmax_xent":
+                    d = L.softmax_xent_backward(probs, labels[t], q)
+                elif ly[0] == "linear":
+                    need_dx = not (s == 0 and li == 0)
+                    dx, dW, db = L.linear_backward(acts[k - 1], P[li][0], acts[k], d, ly[3], need_dx, q)
+                    G[li][0][...] = dW
+                    G[li][1][...] = db
+                    d = dx
+                    k -= 1
+            mom[s] = momentum * mom[s] + g
+            master[s] = master[s] - lr * mom[s]
+            hist[s].append(q(master[s]))
+    return hist, losses

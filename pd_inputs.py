@@ -1,0 +1,151 @@
+"""Seeded synthetic inputs shared by the CPU oracle's tests and the HIP path's tests/bench.
+
+This module draws numbers and shapes them; it contains none of the method's
+arithmetic (no layer maths, no schedule, no update rule).  Both sides receive
+the *same host arrays* from here, so parity never depends on how the values
+were drawn.
+
+Generator: counter-based.  Element ``k`` of the sub-stream named ``name`` under
+``seed`` is ``splitmix64(hash(seed, name) + k)``; uniforms take the top 53 bits,
+normals use Box-Muller on two consecutive uniforms.  Being counter-based, any
+element can be regenerated alone, and results do not depend on chunking.
+
+The datasets the paper trained on (ILSVRC12 images, MSVD clips; Section 5.1,
+"Datasets") are not available; the tensors produced here stand in for them with
+the same shapes and N(0,1) / uniform-label statistics as the benchmark configs.
+"""
+from __future__ import annotations
+
+import zlib
+
+import numpy as np
+
+BASE_SEED = 1806033770  # + config index
+
+_MASK = np.uint64(0xFFFFFFFFFFFFFFFF)
+
+
+def _splitmix64(x: np.ndarray) -> np.ndarray:
+    """One splitmix64 output per 64-bit counter value (vectorised, wraps mod 2^64)."""
+    with np.errstate(over="ignore"):
+        z = x + np.uint64(0x9E3779B97F4A7C15)
+        z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+        z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+        return z ^ (z >> np.uint64(31))
+
+
+def _stream_base(seed: int, name: str) -> np.uint64:
+    h = zlib.crc32(name.encode("utf-8")) & 0xFFFFFFFF
+    mixed = ((int(seed) & 0xFFFFFFFF) << 32) | h
+    return _splitmix64(np.array([mixed], dtype=np.uint64))[0]
+
+
+def uniform01(seed: int, name: str, n: int, offset: int = 0) -> np.ndarray:
+    """``n`` float64 uniforms in [0, 1) from sub-stream ``name`` starting at counter ``offset``."""
+    out = np.empty(n, dtype=np.float64)
+    base = _stream_base(seed, name)
+    chunk = 1 << 22
+    for lo in range(0, n, chunk):
+        hi = min(n, lo + chunk)
+        with np.errstate(over="ignore"):
+            ctr = base + np.arange(offset + lo, offset + hi, dtype=np.uint64)
+        bits = _splitmix64(ctr) >> np.uint64(11)
+        out[lo:hi] = bits.astype(np.float64) * (1.0 / 9007199254740992.0)
+    return out
+
+
+def normal(seed: int, name: str, shape, dtype=np.float32) -> np.ndarray:
+    """N(0,1) samples (Box-Muller; two uniforms per pair of outputs)."""
+    n = int(np.prod(shape))
+    m = (n + 1) // 2
+    u = uniform01(seed, name, 2 * m)
+    u1 = 1.0 - u[0::2]  # (0, 1]
+    u2 = u[1::2]
+    r = np.sqrt(-2.0 * np.log(u1))
+    z = np.empty(2 * m, dtype=np.float64)
+    z[0::2] = r * np.cos(2.0 * np.pi * u2)
+    z[1::2] = r * np.sin(2.0 * np.pi * u2)
+    return z[:n].reshape(shape).astype(dtype)
+
+
+def uniform(seed: int, name: str, shape, lo: float, hi: float, dtype=np.float32) -> np.ndarray:
+    n = int(np.prod(shape))
+    u = uniform01(seed, name, n)
+    return (lo + (hi - lo) * u).reshape(shape).astype(dtype)
+
+
+def labels(seed: int, name: str, shape, num_classes: int) -> np.ndarray:
+    """Uniform integer labels in [0, num_classes) as int32."""
+    n = int(np.prod(shape))
+    u = uniform01(seed, name, n)
+    return np.minimum((u * num_classes).astype(np.int64), num_classes - 1).astype(np.int32).reshape(shape)
+
+
+# ----------------------------------------------------------------------------
+# Layer lists.  A layer is a tuple whose first item names its kind; the product
+# binding and the oracle each translate this neutral description on their own.
+#   ("linear", in_features, out_features, relu: bool)
+#   ("softmax_xent", classes)
+#   ("conv2d", c_in, c_out, kh, kw, stride, pad_h, pad_w, relu: bool)   (NHWC)
+#   ("maxpool2d", k, stride)
+#   ("lstm", input_size, hidden, seq_len)
+# ----------------------------------------------------------------------------
+
+def param_count(layers) -> int:
+    n = 0
+    for L in layers:
+        if L[0] == "linear":
+            n += L[1] * L[2] + L[2]
+        elif L[0] == "conv2d":
+            n += L[2] * L[3] * L[4] * L[1] + L[2]
+        elif L[0] == "lstm":
+            n += 4 * L[2] * (L[1] + L[2]) + 4 * L[2]
+    return n
+
+
+def init_params(seed: int, name: str, layers) -> np.ndarray:
+    """Flat fp32 parameter vector: per layer, weight then bias.
+
+    Weights are uniform in +-sqrt(6 / fan_in) (the "Kaiming-uniform" the
+    benchmark configs name), biases start at zero.  Layout per layer:
+    linear W[out][in]; conv W[c_out][kh][kw][c_in]; lstm W_ih[4H][I], W_hh[4H][H], b[4H].
+    """
+    parts = []
+    for li, L in enumerate(layers):
+        tag = f"{name}/L{li}"
+        if L[0] == "linear":
+            bound = float(np.sqrt(6.0 / L[1]))
+            parts.append(uniform(seed, tag + "/W", (L[2] * L[1],), -bound, bound))
+            parts.append(np.zeros(L[2], dtype=np.float32))
+        elif L[0] == "conv2d":
+            fan_in = L[1] * L[3] * L[4]
+            bound = float(np.sqrt(6.0 / fan_in))
+            parts.append(uniform(seed, tag + "/W", (L[2] * L[3] * L[4] * L[1],), -bound, bound))
+            parts.append(np.zeros(L[2], dtype=np.float32))
+        elif L[0] == "lstm":
+            bound = float(np.sqrt(6.0 / L[2]))
+            parts.append(uniform(seed, tag + "/Wih", (4 * L[2] * L[1],), -bound, bound))
+            parts.append(uniform(seed, tag + "/Whh", (4 * L[2] * L[2],), -bound, bound))
+            parts.append(np.zeros(4 * L[2], dtype=np.float32))
+    if not parts:
+        return np.zeros(0, dtype=np.float32)
+    return np.concatenate(parts).astype(np.float32)
+
+
+# ----------------------------------------------------------------------------
+# The benchmark configurations (shapes only).
+# ----------------------------------------------------------------------------
+
+def config1_mlp(hidden: int = 256, classes: int = 10, stages: int = 4):
+    """4-stage MLP: each stage one Linear hidden->hidden + ReLU; last stage Linear hidden->classes + loss."""
+    st = [[("linear", hidden, hidden, True)] for _ in range(stages - 1)]
+    st.append([("linear", hidden, classes, False), ("softmax_xent", classes)])
+    return st
+
+
+def config2_vgg_fc(in_features: int = 25088, hidden: int = 4096, classes: int = 1000):
+    """VGG16's classifier as one stage: Linear-ReLU-Linear-ReLU-Linear + loss."""
+    return [("linear", in_features, hidden, True),
+            ("linear", hidden, hidden, True),
+            ("linear", hidden, classes, False),
+            ("softmax_xent", classes)]
