@@ -1,0 +1,168 @@
+#!/usr/bin/env python3
+"""Benchmark of the 1F1B weight-stashed stage step on one MI355X.
+
+A *step* is one steady-state iteration of one stage: B(k), U(k), F(k + depth)
+(backward of the oldest in-flight minibatch against its stashed weight version,
+the momentum-SGD update into the version ring, and the forward that refills the
+freed slot with the newest version).  Default workload: the VGG16 classifier as
+one stage (Linear 25088-4096-4096-1000 + ReLU + softmax cross-entropy), bf16 with
+fp32 accumulation, minibatch 64, ring depth 4, synthetic N(0,1) inputs already
+resident in HBM.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+METRIC = "samples/sec per 1F1B stage step (bf16) + MFMA util % of MI355X peak"
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK = 2.5e15
+UPDATE_BYTES_PER_PARAM = 18  # read fp32 master + momentum, write both, write the bf16 ring copy
+
+
+def cpu_baseline(layers, params, xs, labs, depth, budget_s=20.0, max_steps=3):
+    """The oracle, as it stands, on the host cores: same stage, same step, a bounded number of steps."""
+    import numpy as np
+    from oracle.pipeline import Stage
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    st = Stage(layers, params, depth, "bf16")
+    n = len(xs)
+    for i in range(depth):
+        st.forward(i, xs[i % n].astype(np.float64), labs[i % n])
+    steps, t0 = 0, time.time()
+    while steps < max_steps and (steps == 0 or time.time() - t0 < budget_s):
+        k = steps
+        st.backward(k, None, need_dx=True)
+        st.update(k)
+        st.forward(k + depth, xs[(k + depth) % n].astype(np.float64), labs[(k + depth) % n])
+        steps += 1
+    dt = time.time() - t0
+    B = xs[0].shape[0]
+    return {"value": steps * B / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{steps} steady-state steps (B,U,F) of the same full-size stage, fp64 numpy, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--minibatch", type=int, default=64)
+    ap.add_argument("--depth", type=int, default=4)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs all pipeline stages on ONE GPU; --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_1806_03377_amd as pd
+    import pd_inputs as gen
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible (the HIP path has no CPU fallback)", file=sys.stderr)
+        sys.exit(3)
+    dev = torch.device("cuda:0")
+    B, depth, K, W = args.minibatch, args.depth, args.steps, args.warmup
+    layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
+    n_in, classes = layers[0][1], layers[-1][1]
+    seed = gen.BASE_SEED + 1
+    params = gen.init_params(seed, "vgg_fc", layers)
+    P = int(params.size)
+    n_pool = 8
+    xs = [gen.normal(seed, f"x{i}", (B, n_in)) for i in range(n_pool)]
+    labs = [gen.labels(seed, f"y{i}", (B,), classes) for i in range(n_pool)]
+
+    stream = torch.cuda.Stream(device=dev)
+    cfg = pd.make_config(layers, in_flight_override=depth, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=0.01,
+                         momentum=0.9, stream=stream.cuda_stream)
+    nbytes = pd.pd_stage_query_bytes(cfg)
+    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
+    pd.pd_stage_set_params(h, params)
+    xd = [torch.from_numpy(x).to(dev).to(torch.bfloat16).contiguous() for x in xs]
+    ld = [torch.from_numpy(l).to(dev) for l in labs]
+    dx = torch.empty((B, n_in), dtype=torch.bfloat16, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    mb_next = 0
+
+    def fwd():
+        nonlocal mb_next
+        i = mb_next % n_pool
+        pd.pd_forward(h, mb_next, xd[i].data_ptr(), ld[i].data_ptr(), 0, loss.data_ptr())
+        mb_next += 1
+
+    def step(k, ev=None):
+        pd.pd_backward(h, k, 0, dx.data_ptr())
+        if ev is not None:
+            ev[0].record(stream)
+        pd.pd_update(h)
+        if ev is not None:
+            ev[1].record(stream)
+        fwd()
+
+    for _ in range(depth):
+        fwd()
+    k = 0
+    for _ in range(W):
+        step(k)
+        k += 1
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for j in range(K):
+        step(k, evs[j])
+        k += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    upd_ms = [a.elapsed_time(b) for a, b in evs]
+    upd_ms_avg = float(np.mean(upd_ms))
+    n_launch = sum(1 for L in layers if L[0] == "linear")
+    final_loss = float(loss.item())
+
+    flops = 6.0 * B * sum(L[1] * L[2] for L in layers if L[0] == "linear")
+    value = B / (ms_per_step * 1e-3)
+    achieved_gbs = UPDATE_BYTES_PER_PARAM * P / (upd_ms_avg * 1e-3) / 1e9
+    out = {
+        "metric": METRIC, "value": value, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": ("REDUCED " if args.small else "") +
+                   f"VGG16-FC-shaped stage: Linear {n_in}-{layers[0][2]}-{layers[1][2]}-{classes} + ReLU + "
+                   f"softmax-xent, bf16 w/ fp32 accum, minibatch {B}, weight-version ring depth {depth}, "
+                   "step = B(k) U(k) F(k+depth)",
+                   "params": P, "minibatch": B, "ring_depth": depth},
+        "mfma_util_pct": 100.0 * flops / (ms_per_step * 1e-3) / MFMA_BF16_PEAK,
+        "step_gflop": flops / 1e9,
+        "step_hbm_fraction": (22.0 * P / (ms_per_step * 1e-3) / 1e9) / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "wgrad_update_kernel (dW = dZ^T X fused with momentum-SGD into the ring)",
+                     "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "launches_per_step": n_launch,
+                     "avg_launch_ms": upd_ms_avg / n_launch, "bytes_per_launch_avg": UPDATE_BYTES_PER_PARAM * P / n_launch},
+        "final_loss": final_loss,
+    }
+    pd.pd_stage_destroy(h)
+    del arena
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, params, xs, labs, depth)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,236 @@
+/*
+ * pd.h -- C ABI of the 1F1B weight-stashed pipeline-stage runtime for MI355X (gfx950).
+ *
+ * What it is.  One pipeline *stage* of PipeDream (arXiv 1806.03377): a run of
+ * consecutive layers that executes forward passes (F), backward passes (B) and
+ * weight updates (U) for a stream of minibatches under the one-forward-one-
+ * backward policy (Section 3.3), keeping one weight version per in-flight
+ * minibatch so that a minibatch's backward pass reads exactly the weights its
+ * forward pass read (weight stashing, Section 3.4).  The runtime owns the
+ * stage's parameter and intermediate state in device memory and hands work to
+ * hand-written HIP kernels (Section 4, stage runtime; the paper's ML worker is
+ * replaced by these kernels).  Several stages run on ONE GPU, each on its own
+ * HIP stream, exchanging activations and gradients through device buffers.
+ *
+ * Conventions
+ *   - Every function returns a pd_status (0 = PD_OK, negative = error) and never
+ *     throws.  pd_last_error() gives a thread-local message for the last failure.
+ *     After an error the stage is unchanged unless stated otherwise.
+ *   - "dev" pointers are device memory of the current HIP device; "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer it passes
+ *     (arena, inputs, labels, outputs) and the stream.  The library allocates no
+ *     device memory: all stage state lives in the caller's arena, carved once at
+ *     pd_stage_create (static allocation, Section 3.5).
+ *   - pd_forward / pd_backward / pd_update only ENQUEUE kernels on the stage's
+ *     stream and return; they never synchronise, never memset, and are safe to
+ *     capture into a HIP graph.  Host-side bookkeeping (versions, stash table)
+ *     is advanced at call time, which is valid because a stage's op order is
+ *     static.  pd_stage_set_* / pd_stage_get_* synchronise the stream.
+ *   - Numbering: stages s = 0..S-1, minibatches i = 0,1,2,..., version v = number
+ *     of updates applied so far (v = 0: initial weights).  Ring slot of a version
+ *     = v mod depth; stash slot of a minibatch = i mod depth.
+ *   - Element types.  PD_F32: activations, gradients, weights all float.
+ *     PD_BF16_F32ACC: activations, activation gradients and the ring copies of
+ *     the weights are bfloat16 (round-to-nearest-even from fp32); every sum,
+ *     bias add, the logits of a stage that ends in the loss, the loss, weight
+ *     gradients, master weights and momentum are float.
+ *   - Matrices are row-major.  A minibatch activation is [rows][features] with
+ *     rows = cfg.minibatch.  Linear weights are W[out][in].
+ *   - Flat parameter vector (pd_stage_set_params and friends): layer by layer in
+ *     stage order, each Linear contributing W (out*in values) then b (out values).
+ */
+#ifndef PD_H_
+#define PD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pd_stage pd_stage; /* opaque host-side handle */
+
+typedef enum {
+  PD_OK = 0,
+  PD_EINVAL = -1, /* null pointer, bad shape, bad enum                         */
+  PD_ESTATE = -2, /* call violates the 1F1B protocol (see each function)       */
+  PD_ENOMEM = -3, /* arena or output array too small                           */
+  PD_EHIP = -4    /* a HIP runtime call failed; message holds hipGetErrorString */
+} pd_status;
+
+typedef enum { PD_F32 = 0, PD_BF16_F32ACC = 1 } pd_precision;
+
+typedef enum { PD_OP_F = 0, PD_OP_B = 1, PD_OP_U = 2 } pd_op_kind;
+
+/* One entry of a stage's static schedule (integers only).
+ * F, B: `version` = weight version read; U: `version` = weight version produced.
+ * `slot` = version mod depth (ring slot read, or written for U). */
+typedef struct {
+  int32_t kind, mb_id, version, slot;
+} pd_op;
+
+typedef enum {
+  PD_LINEAR = 0,       /* p[0]=in_features p[1]=out_features p[2]=1: fused ReLU on the output */
+  PD_SOFTMAX_XENT = 1  /* p[0]=classes; must be the last layer, directly after a PD_LINEAR      */
+} pd_layer_kind;
+
+typedef struct {
+  int32_t kind;
+  int32_t p[12];
+} pd_layer_desc;
+
+typedef struct {
+  int32_t stage_index;        /* s, 0-based                                                      */
+  int32_t num_stages;         /* S                                                               */
+  int32_t noam;               /* NUM_OPT_ACTIVE_MINIBATCHES (Section 3.2); depth = max(1, noam-s) */
+  int32_t in_flight_override; /* > 0: use this depth instead (a stage benchmarked alone at
+                                 input-stage depth)                                              */
+  int32_t minibatch;          /* rows per minibatch                                              */
+  int32_t precision;          /* pd_precision                                                    */
+  float lr;                   /* learning rate (constant)                                        */
+  float momentum;             /* mu in  m <- mu*m + g ; w <- w - lr*m  (Section 5.1: 0.9, 0.01)  */
+  int32_t n_layers;
+  const pd_layer_desc* layers; /* host; copied at create                                          */
+  void* stream;               /* hipStream_t, borrowed; all of the stage's kernels run on it      */
+} pd_stage_config;
+
+/* --- schedule (pure host, no GPU touched) -------------------------------------------------
+ * The static per-stage op list of the 1F1B policy (Section 3.3): `depth` forwards at
+ * start-up (depth = max(1, noam - stage_index): the input stage admits NOAM, the output stage
+ * one, Sections 3.3 and 3.5; fewer if the stream is shorter), then alternately the backward of
+ * the oldest in-flight minibatch -- followed at once by its update -- and the next forward;
+ * remaining backwards drain in order at the end.  Versions follow weight stashing (Section
+ * 3.4): F reads the latest version, B the version its F read, U produces latest+1.
+ * Writes up to `cap` ops to `out` (host) and the full count (3 * num_minibatches) to *n_out.
+ * PD_ENOMEM if cap is too small (n_out still set); PD_EINVAL on bad arguments. */
+int pd_schedule_1f1b(int32_t num_stages, int32_t noam, int32_t num_minibatches, int32_t stage_index,
+                     pd_op* out, size_t cap, size_t* n_out);
+/* Same list for an explicitly given in-flight depth (>= 1). */
+int pd_schedule_1f1b_depth(int32_t depth, int32_t num_minibatches, pd_op* out, size_t cap, size_t* n_out);
+
+/* --- stage life cycle (Sections 3.5 and 4: static allocation at initialisation) -----------
+ * pd_stage_query_bytes: bytes of device arena the configuration needs (weight-version ring,
+ * fp32 master weights and momentum, activation stash for `depth` minibatches, input ring,
+ * gradient and split-K workspaces).
+ * pd_stage_create: carves `device_arena` (256-byte aligned, >= query bytes, owned by the
+ * caller, must outlive the stage; contents need not be initialised).  Parameters start
+ * undefined until pd_stage_set_params; momentum starts at zero.  PD_ENOMEM if too small. */
+int pd_stage_query_bytes(const pd_stage_config* cfg, size_t* device_bytes);
+int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena_bytes, pd_stage** out);
+int pd_stage_destroy(pd_stage* st);
+
+/* Number of parameters (length of the flat vector), in-flight depth, input-ring depth. */
+int pd_stage_num_params(const pd_stage* st, size_t* n);
+int pd_stage_depth(const pd_stage* st, int32_t* depth, int32_t* input_ring_depth);
+
+/* Resets the stage to version 0 with these weights (host, fp32, flat layout above), zero
+ * momentum, nothing in flight.  In bf16 mode ring slot 0 = round-to-nearest-even of them. */
+int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n);
+/* Weights of `version` (-1 = latest) as fp32 into host_out.  Latest: the fp32 master.  An older
+ * version must still be in the ring (version > latest - depth), else PD_ESTATE; in bf16 mode
+ * an older version is its bf16 ring copy widened to float.  `ring_copy` != 0 forces the ring
+ * copy also for the latest version. */
+int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float* host_out, size_t n);
+/* Momentum buffer (fp32, flat layout).  set requires nothing in flight. */
+int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n);
+int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n);
+
+/* Overwrites the LATEST version in place: fp32 master <- host_params, its ring slot <- their bf16
+ * rounding (bf16 mode), momentum <- host_mom (either may be NULL to leave it).  Version ids, the
+ * stash and in-flight minibatches are untouched, so a driver can re-synchronise a running stage
+ * with externally computed state (checkpoint restore mid-stream, teacher-forced tests).
+ * PD_ESTATE while a gradient is pending (between pd_backward and pd_update). */
+int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const float* host_mom, size_t n);
+
+/* Version bookkeeping: mb_id = -1 -> latest version; otherwise the version stashed for that
+ * in-flight minibatch (PD_ESTATE if it is not in flight). */
+int pd_stage_version(const pd_stage* st, int32_t mb_id, int32_t* version);
+/* The ops executed so far, in order (same encoding as pd_schedule_1f1b). */
+int pd_stage_trace(const pd_stage* st, pd_op* out, size_t cap, size_t* n_out);
+
+/* Device address of the stage's own input slot for minibatch mb_id ([minibatch][in_features],
+ * element type per precision).  A producer (the previous stage's pd_forward, via y_dev) may
+ * write the activation straight there; pd_forward then takes it without a copy.  The input
+ * ring has depth+1 slots for stage_index > 0 (the producer may run one forward ahead of what
+ * this stage has released) and depth slots for stage 0; slot = mb_id mod that depth. */
+int pd_stage_input_slot(pd_stage* st, int32_t mb_id, void** dev_ptr);
+/* Device address of the buffer that receives dL/d(output) for the backward pass of mb_id
+ * ([minibatch][out_features]); two slots, slot = mb_id mod 2. */
+int pd_stage_grad_slot(pd_stage* st, int32_t mb_id, void** dev_ptr);
+
+/* Test/debug aid: copies one of the stage's intermediate tensors to the host as fp32
+ * (synchronises the stream).  what = 0: stored output of Linear number `layer` (0-based among the
+ * stage's Linear layers) for in-flight minibatch mb_id, [minibatch][out]; 1: the stage's input
+ * slot for mb_id, [minibatch][in]; 2: the output-gradient slot for mb_id, [minibatch][out_last];
+ * 3: dL/d(pre-activation) of Linear `layer` left by the last pd_backward, [minibatch][out];
+ * 4: the stashed dL/dlogits of in-flight minibatch mb_id (loss stages).  n must equal the tensor's
+ * element count.  No state check is made on mb_id beyond >= 0: the caller reads what the slot holds. */
+int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, float* host_out, size_t n);
+
+/* --- the step (Sections 3.3, 3.4, 4) -------------------------------------------------------
+ * pd_forward: F for minibatch mb_id.  Reads the LATEST weight version and records it in the
+ * stash for this minibatch (weight stashing, Section 3.4); runs the layers; keeps each layer's
+ * input/output for the backward pass (Section 4, intermediate state).
+ *   x_dev      [minibatch][in]: the input.  If it is not the stage's own input slot it is
+ *              copied there (on the stream), so the caller may reuse x_dev after that copy.
+ *   labels_dev int32[minibatch], required iff the stage ends in PD_SOFTMAX_XENT; then the loss
+ *              (mean over rows of -log softmax[label], Section 3.1: the output stage computes
+ *              the loss) goes to loss_dev (one float, may be NULL) and dL/dlogits is stashed.
+ *   y_dev      [minibatch][out] output of the last non-loss layer, may be NULL.  On a stage
+ *              that ends in the loss these are the logits and are float in both precisions.
+ * PD_ESTATE if `depth` minibatches are already in flight or mb_id is not the previous
+ * forward's id + 1 (first call after set_params: any id >= 0).
+ *
+ * pd_backward: B for minibatch mb_id, which must be the OLDEST in flight (PD_ESTATE otherwise).
+ * Uses the weight version stashed at its forward.  dy_dev [minibatch][out] = dL/d(output),
+ * NULL iff the stage ends in the loss.  dx_dev [minibatch][in] receives dL/d(input), NULL to
+ * skip it (input stage).  Leaves the weight gradient pending (held in factored form: per layer
+ * dL/d(pre-activation) and the stashed layer input) and releases the minibatch's stash slot.
+ *
+ * pd_update: U.  Consumes the pending gradient: per Linear, dW = dZ^T X and db = colsum(dZ)
+ * are formed tile by tile and, in the same kernel, m <- mu*m + g, w <- w - lr*m is applied to
+ * the LATEST weights (Section 4, parameter state) and the result stored as version latest+1
+ * in ring slot (latest+1) mod depth.  PD_ESTATE without a pending gradient. */
+int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
+               float* loss_dev);
+int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev);
+int pd_update(pd_stage* st);
+
+/* --- all stages of a pipeline on one GPU (Section 3.1 / 3.3) -------------------------------
+ * Runs num_minibatches through stages[0..num_stages-1] (stage k must have stage_index k, all
+ * the same minibatch and precision, matching widths, the last ending in PD_SOFTMAX_XENT).  Each
+ * stage follows its own pd_schedule_1f1b list on its own stream; F(i,s) waits (event) for
+ * F(i,s-1), B(i,s) for B(i,s+1); every reuse of an inter-stage slot waits for its last reader.
+ * Activations go directly into the consumer's input slot, gradients into the producer's grad
+ * slot.  inputs_dev [num_minibatches][minibatch][in0]; labels_dev int32 [num_minibatches]
+ * [minibatch]; losses_dev float[num_minibatches] (may be NULL).  Enqueues everything and
+ * returns; the caller synchronises the streams.  Stages must have nothing in flight; minibatch
+ * ids continue from each stage's last forward (or 0). */
+int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_minibatches,
+                    const void* inputs_dev, const int32_t* labels_dev, float* losses_dev);
+
+/* --- stand-alone kernels of the step, for measurement at other shapes ----------------------
+ * The same GEMM kernels the stage uses, callable on caller buffers (bf16 data, fp32
+ * accumulate), so that MFMA utilisation can be measured at any minibatch size.
+ *   fwd   : y[M][N]  = act(x[M][K] * w[N][K]^T + b[N])       (relu != 0: max(.,0))
+ *   dgrad : dx[M][K] = (dz[M][N] * w[N][K]) .* (mask[M][K] > 0 if mask != NULL)
+ *   wgrad_update: g = dz[M][N]^T x[M][K] (+ column sums for the bias); m <- mu*m+g;
+ *           master <- master - lr*m; ring_out <- bf16(master)
+ * workspace_dev: split-K scratch of at least pd_gemm_workspace_bytes(M,N,K) bytes (fwd, dgrad).
+ * stream: hipStream_t.  All pointers device. */
+size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
+int pd_linear_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, int32_t M, int32_t N,
+                       int32_t K, int32_t relu, void* workspace_dev, size_t workspace_bytes);
+int pd_linear_dgrad_bf16(void* stream, const void* dz, const void* w, const void* mask, void* dx, int32_t M,
+                         int32_t N, int32_t K, void* workspace_dev, size_t workspace_bytes);
+int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, float* master_w, float* mom_w,
+                                void* ring_out_w, float* master_b, float* mom_b, void* ring_out_b, int32_t M,
+                                int32_t N, int32_t K, float lr, float momentum);
+
+const char* pd_last_error(void); /* thread-local, static storage, never NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PD_H_ */

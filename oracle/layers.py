@@ -12,8 +12,9 @@ Precision modes.  "f32": no rounding anywhere (pure fp64; the HIP path computes
 in fp32 and is compared at 1e-4).  "bf16": tensors that the mixed-precision path
 keeps in bfloat16 -- ring weights, activations handed between layers and stages,
 activation gradients -- are rounded to the nearest bfloat16 (ties to even) at
-the moment they are stored; sums, bias add, loss, weight gradients, master
-weights and momentum are not rounded.
+the moment they are stored; sums, bias add, the logits handed to the loss (the
+output of the Linear that feeds softmax cross-entropy), the loss itself, weight
+gradients, master weights and momentum are not rounded.
 """
 from __future__ import annotations
 
@@ -27,10 +28,11 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
     drops the low 16 bits with the usual add-half-then-truncate on the bit pattern.
     """
     f = np.asarray(x, dtype=np.float64).astype(np.float32)
-    u = f.view(np.uint32).astype(np.uint64)
-    lsb = (u >> np.uint64(16)) & np.uint64(1)
-    r = ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)) << np.uint64(16)
-    out = (r & np.uint64(0xFFFFFFFF)).astype(np.uint32).view(np.float32).astype(np.float64)
+    u = f.view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    with np.errstate(over="ignore"):
+        r = (u + np.uint32(0x7FFF) + lsb) & np.uint32(0xFFFF0000)   # finite inputs never wrap
+    out = r.view(np.float32).astype(np.float64)
     nan = np.isnan(f)
     if nan.any():
         out = np.where(nan, np.nan, out)

@@ -40,6 +40,14 @@ def _split_params(layers, flat):
     return out
 
 
+def _out_quantiser(layers, li, q):
+    """Rounding applied to layer li's stored output: logits that go straight into the
+    loss stay in accumulator precision (the loss is computed unrounded); everything else
+    is an activation handed on in the storage type."""
+    feeds_loss = li + 1 < len(layers) and layers[li + 1][0] == "softmax_xent"
+    return (lambda a: a) if feeds_loss else q
+
+
 class Stage:
     def __init__(self, layers, params_fp32, depth: int, mode: str = "f32",
                  lr: float = 0.01, momentum: float = 0.9, stashing: bool = True):
@@ -57,6 +65,8 @@ class Stage:
         self.grad = None                      # flat gradient of the last backward, until update() consumes it
         self.trace: List[Op] = []
         self.max_in_flight = 0
+        self.log = None                       # set to {} to keep, per minibatch, the stored layer outputs
+                                              # ("acts"), the incoming gradient ("dy") and the result ("dx")
 
     # -- F ---------------------------------------------------------------------
     def forward(self, mb: int, x, labels=None):
@@ -66,14 +76,16 @@ class Stage:
         P = _split_params(self.layers, self.versions[v])
         acts = [self.q(x)]
         loss, probs = None, None
-        for ly, p in zip(self.layers, P):
+        for li, (ly, p) in enumerate(zip(self.layers, P)):
             if ly[0] == "linear":
-                acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], self.q))
+                acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], _out_quantiser(self.layers, li, self.q)))
             elif ly[0] == "softmax_xent":
                 loss, probs = L.softmax_xent_forward(acts[-1], labels)
             else:
                 raise NotImplementedError(ly[0])
         self.stash[mb] = dict(version=v, acts=acts, labels=labels, probs=probs)
+        if self.log is not None:
+            self.log[mb] = dict(version=v, acts=acts, loss=loss)
         self.max_in_flight = max(self.max_in_flight, len(self.stash))
         self.trace.append(Op(OP_F, mb, v, v % self.depth))
         return acts[-1], loss
@@ -104,6 +116,8 @@ class Stage:
                 k -= 1
         self.grad = g
         self.trace.append(Op(OP_B, mb, v, v % self.depth))
+        if self.log is not None:
+            self.log[mb]["dx"] = d
         return d
 
     # -- U ---------------------------------------------------------------------
@@ -124,17 +138,26 @@ class Stage:
 
 def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels, noam_: int,
                  mode: str = "f32", lr: float = 0.01, momentum: float = 0.9,
-                 stashing: bool = True, depth_override: int = 0):
+                 stashing: bool = True, depth_override: int = 0, keep_log: bool = False,
+                 out_grads=None, order: Optional[list] = None, input_grad: bool = False):
     """All stages, each following its own static op list, run as soon as their data exists.
 
     inputs[i] / labels[i] belong to minibatch i.  Returns (stages, losses).  Any
     order that respects the data dependencies gives the same numbers, because each
     stage's own order is fixed (Section 3.3: the policy is static).
+
+    ``out_grads[i]``: dL/d(output) of the last stage for minibatch i when that stage
+    does not end in the loss (a stage or sub-pipeline studied on its own).  ``order``,
+    if a list, receives the (stage, Op) pairs in the order they were executed.
+    ``input_grad``: also form dL/d(input) of stage 0 (only visible through the log).
     """
     S, M = len(stage_layers), len(inputs)
-    depths = [depth_override or in_flight_depth(S, noam_, M, s) for s in range(S)]
+    depths = [depth_override or in_flight_depth(S, noam_, s) for s in range(S)]
     stages = [Stage(stage_layers[s], stage_params[s], depths[s], mode, lr, momentum, stashing)
               for s in range(S)]
+    if keep_log:
+        for st in stages:
+            st.log = {}
     lists = [schedule_1f1b(S, noam_, M, s, depth_override) for s in range(S)]
     pos = [0] * S
     act = {}     # (mb, producing stage) -> activation for the next stage
@@ -151,7 +174,7 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                     if s > 0 and (op.mb, s - 1) not in act:
                         break
                     x = inputs[op.mb] if s == 0 else act.pop((op.mb, s - 1))
-                    y, loss = st.forward(op.mb, x, labels[op.mb] if s == S - 1 else None)
+                    y, loss = st.forward(op.mb, x, labels[op.mb] if (s == S - 1 and labels is not None) else None)
                     if s == S - 1:
                         losses[op.mb] = loss
                     else:
@@ -159,8 +182,11 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                 elif op.kind == OP_B:
                     if s < S - 1 and (op.mb, s + 1) not in grad:
                         break
-                    dy = None if s == S - 1 else grad.pop((op.mb, s + 1))
-                    dx = st.backward(op.mb, dy, need_dx=(s > 0))
+                    if s == S - 1:
+                        dy = None if out_grads is None else out_grads[op.mb]
+                    else:
+                        dy = grad.pop((op.mb, s + 1))
+                    dx = st.backward(op.mb, dy, need_dx=(s > 0 or input_grad))
                     if s > 0:
                         grad[(op.mb, s)] = dx
                 else:
@@ -168,6 +194,8 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                 # the stage really did what its static list said, version included
                 # (with stashing off, B deliberately reads another version than listed)
                 assert st.trace[-1] == op or (not stashing and op.kind == OP_B), (st.trace[-1], op)
+                if order is not None:
+                    order.append((s, op))
                 pos[s] += 1
                 remaining -= 1
                 progressed = True
@@ -200,9 +228,9 @@ def flat_loop(stage_layers: Sequence, stage_params: Sequence, inputs, labels, de
         for s in range(S):
             P = _split_params(stage_layers[s], W[s])
             acts = [a]
-            for ly, p in zip(stage_layers[s], P):
+            for li, (ly, p) in enumerate(zip(stage_layers[s], P)):
                 if ly[0] == "linear":
-                    acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], q))
+                    acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], _out_quantiser(stage_layers[s], li, q)))
                 elif ly[0] == "softmax_xent":
                     loss, probs = L.softmax_xent_forward(acts[-1], labels[t])
             acts_all.append(acts)

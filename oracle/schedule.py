@@ -24,17 +24,18 @@ def noam(num_machines: int, input_stage_machines: int) -> int:
     return math.ceil(num_machines / input_stage_machines)
 
 
-def in_flight_depth(num_stages: int, noam_: int, num_minibatches: int, stage: int) -> int:
-    """How many minibatches stage ``stage`` holds between their F and their B.
+def in_flight_depth(num_stages: int, noam_: int, stage: int) -> int:
+    """How many minibatches stage ``stage`` may hold between their F and their B
+    (also the number of weight versions it keeps: the depth of its version ring).
 
     The input stage admits NOAM (Section 3.3); the output stage holds one
     (Section 3.5); the worked example of Section 3.4 (4 stages: three, two, one,
     zero interleaved updates from stage 1 to stage 4) fixes the values between as
-    NOAM - s.  Never below 1, never above the number of minibatches there are.
+    NOAM - s, never below 1.  (A stream shorter than this simply never fills it.)
     """
     if not (0 <= stage < num_stages):
         raise ValueError("stage out of range")
-    return max(1, min(num_minibatches, max(1, noam_ - stage)))
+    return max(1, noam_ - stage)
 
 
 def schedule_1f1b(num_stages: int, noam_: int, num_minibatches: int, stage: int,
@@ -49,8 +50,7 @@ def schedule_1f1b(num_stages: int, noam_: int, num_minibatches: int, stage: int,
     walk, as the runtime would, not from a formula.
     """
     M = num_minibatches
-    depth = depth_override if depth_override > 0 else in_flight_depth(num_stages, noam_, M, stage)
-    depth = max(1, min(depth, M)) if M > 0 else 1
+    depth = depth_override if depth_override > 0 else in_flight_depth(num_stages, noam_, stage)
     ops: List[Op] = []
     latest = 0
     stashed = {}          # mb -> version its forward used

@@ -1,0 +1,273 @@
+"""ctypes binding of libpd.so: same names as include/pd.h, argument marshalling only.
+
+Device pointers are passed as integers (``tensor.data_ptr()``), streams as
+``torch.cuda.Stream.cuda_stream``.  Every call raises ``PdError`` on a non-zero status.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Sequence, Tuple
+
+import numpy as np
+import torch  # noqa: F401  -- must come first: libpd.so then binds to the HIP runtime torch has already loaded
+                #           (same soname), so both share one runtime, one context and the same streams
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpd.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} not found: build it first (python -m paper_1806_03377_amd.build); "
+                      "there is no fallback path")
+_lib = C.CDLL(LIB_PATH)
+
+PD_OK, PD_EINVAL, PD_ESTATE, PD_ENOMEM, PD_EHIP = 0, -1, -2, -3, -4
+PD_F32, PD_BF16_F32ACC = 0, 1
+PD_OP_F, PD_OP_B, PD_OP_U = 0, 1, 2
+PD_LINEAR, PD_SOFTMAX_XENT = 0, 1
+
+
+class PdError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"pd status {status}: {message}")
+        self.status = status
+
+
+class pd_op(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mb_id", C.c_int32), ("version", C.c_int32), ("slot", C.c_int32)]
+
+
+class pd_layer_desc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("p", C.c_int32 * 12)]
+
+
+class pd_stage_config(C.Structure):
+    _fields_ = [("stage_index", C.c_int32), ("num_stages", C.c_int32), ("noam", C.c_int32),
+                ("in_flight_override", C.c_int32), ("minibatch", C.c_int32), ("precision", C.c_int32),
+                ("lr", C.c_float), ("momentum", C.c_float), ("n_layers", C.c_int32),
+                ("layers", C.POINTER(pd_layer_desc)), ("stream", C.c_void_p)]
+
+
+_vp, _sz, _i32, _f32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_float
+_SIGS = {
+    "pd_schedule_1f1b": [_i32, _i32, _i32, _i32, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
+    "pd_schedule_1f1b_depth": [_i32, _i32, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
+    "pd_stage_query_bytes": [C.POINTER(pd_stage_config), C.POINTER(_sz)],
+    "pd_stage_create": [C.POINTER(pd_stage_config), _vp, _sz, C.POINTER(_vp)],
+    "pd_stage_destroy": [_vp],
+    "pd_stage_num_params": [_vp, C.POINTER(_sz)],
+    "pd_stage_depth": [_vp, C.POINTER(_i32), C.POINTER(_i32)],
+    "pd_stage_set_params": [_vp, _vp, _sz],
+    "pd_stage_get_params": [_vp, _i32, _i32, _vp, _sz],
+    "pd_stage_set_momentum": [_vp, _vp, _sz],
+    "pd_stage_get_momentum": [_vp, _vp, _sz],
+    "pd_stage_overwrite_latest": [_vp, _vp, _vp, _sz],
+    "pd_stage_version": [_vp, _i32, C.POINTER(_i32)],
+    "pd_stage_trace": [_vp, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
+    "pd_stage_input_slot": [_vp, _i32, C.POINTER(_vp)],
+    "pd_stage_grad_slot": [_vp, _i32, C.POINTER(_vp)],
+    "pd_stage_debug_read": [_vp, _i32, _i32, _i32, _vp, _sz],
+    "pd_forward": [_vp, _i32, _vp, _vp, _vp, _vp],
+    "pd_backward": [_vp, _i32, _vp, _vp],
+    "pd_update": [_vp],
+    "pd_pipeline_run": [C.POINTER(_vp), _i32, _i32, _vp, _vp, _vp],
+    "pd_linear_fwd_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _sz],
+    "pd_linear_dgrad_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _sz],
+    "pd_linear_wgrad_update_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _f32],
+}
+for _name, _args in _SIGS.items():
+    _f = getattr(_lib, _name)
+    _f.argtypes = _args
+    _f.restype = C.c_int
+_lib.pd_last_error.restype = C.c_char_p
+_lib.pd_last_error.argtypes = []
+_lib.pd_gemm_workspace_bytes.restype = _sz
+_lib.pd_gemm_workspace_bytes.argtypes = [_i32, _i32, _i32]
+
+EXPORTED = sorted(list(_SIGS) + ["pd_last_error", "pd_gemm_workspace_bytes"])
+
+
+def pd_last_error() -> str:
+    return _lib.pd_last_error().decode()
+
+
+def _check(rc: int):
+    if rc != PD_OK:
+        raise PdError(rc, pd_last_error())
+
+
+def _ops(arr, n) -> List[Tuple[int, int, int, int]]:
+    return [(arr[i].kind, arr[i].mb_id, arr[i].version, arr[i].slot) for i in range(n)]
+
+
+def pd_schedule_1f1b(num_stages: int, noam: int, num_minibatches: int, stage_index: int):
+    cap = max(1, 3 * max(0, num_minibatches))
+    arr = (pd_op * cap)()
+    n = _sz(0)
+    _check(_lib.pd_schedule_1f1b(num_stages, noam, num_minibatches, stage_index, arr, cap, C.byref(n)))
+    return _ops(arr, n.value)
+
+
+def pd_schedule_1f1b_depth(depth: int, num_minibatches: int):
+    cap = max(1, 3 * max(0, num_minibatches))
+    arr = (pd_op * cap)()
+    n = _sz(0)
+    _check(_lib.pd_schedule_1f1b_depth(depth, num_minibatches, arr, cap, C.byref(n)))
+    return _ops(arr, n.value)
+
+
+def layer_descs(layers: Sequence[tuple]):
+    """Translate the neutral layer tuples of pd_inputs into pd_layer_desc records."""
+    arr = (pd_layer_desc * len(layers))()
+    for i, L in enumerate(layers):
+        if L[0] == "linear":
+            arr[i].kind = PD_LINEAR
+            arr[i].p[0], arr[i].p[1], arr[i].p[2] = int(L[1]), int(L[2]), int(bool(L[3]))
+        elif L[0] == "softmax_xent":
+            arr[i].kind = PD_SOFTMAX_XENT
+            arr[i].p[0] = int(L[1])
+        else:
+            raise ValueError(f"layer kind {L[0]!r} is not supported by this build")
+    return arr
+
+
+def make_config(layers, *, stage_index=0, num_stages=1, noam=1, in_flight_override=0, minibatch=1,
+                precision=PD_F32, lr=0.01, momentum=0.9, stream=0):
+    descs = layer_descs(layers)
+    cfg = pd_stage_config(stage_index, num_stages, noam, in_flight_override, minibatch, precision, lr, momentum,
+                          len(layers), descs, stream)
+    cfg._keepalive = descs
+    return cfg
+
+
+def pd_stage_query_bytes(cfg) -> int:
+    n = _sz(0)
+    _check(_lib.pd_stage_query_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def pd_stage_create(cfg, device_arena: int, arena_bytes: int) -> int:
+    h = _vp(0)
+    _check(_lib.pd_stage_create(C.byref(cfg), device_arena, arena_bytes, C.byref(h)))
+    return h.value
+
+
+def pd_stage_destroy(stage: int):
+    _check(_lib.pd_stage_destroy(stage))
+
+
+def pd_stage_num_params(stage: int) -> int:
+    n = _sz(0)
+    _check(_lib.pd_stage_num_params(stage, C.byref(n)))
+    return n.value
+
+
+def pd_stage_depth(stage: int) -> Tuple[int, int]:
+    d, i = _i32(0), _i32(0)
+    _check(_lib.pd_stage_depth(stage, C.byref(d), C.byref(i)))
+    return d.value, i.value
+
+
+def _host_f32(a: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def pd_stage_set_params(stage: int, params: np.ndarray):
+    a = _host_f32(params)
+    _check(_lib.pd_stage_set_params(stage, a.ctypes.data, a.size))
+
+
+def pd_stage_get_params(stage: int, version: int = -1, ring_copy: bool = False) -> np.ndarray:
+    out = np.empty(pd_stage_num_params(stage), dtype=np.float32)
+    _check(_lib.pd_stage_get_params(stage, version, int(ring_copy), out.ctypes.data, out.size))
+    return out
+
+
+def pd_stage_set_momentum(stage: int, mom: np.ndarray):
+    a = _host_f32(mom)
+    _check(_lib.pd_stage_set_momentum(stage, a.ctypes.data, a.size))
+
+
+def pd_stage_get_momentum(stage: int) -> np.ndarray:
+    out = np.empty(pd_stage_num_params(stage), dtype=np.float32)
+    _check(_lib.pd_stage_get_momentum(stage, out.ctypes.data, out.size))
+    return out
+
+
+def pd_stage_overwrite_latest(stage: int, params=None, mom=None):
+    a = _host_f32(params) if params is not None else None
+    b = _host_f32(mom) if mom is not None else None
+    n = a.size if a is not None else (b.size if b is not None else 0)
+    _check(_lib.pd_stage_overwrite_latest(stage, a.ctypes.data if a is not None else None,
+                                          b.ctypes.data if b is not None else None, n))
+
+
+def pd_stage_version(stage: int, mb_id: int = -1) -> int:
+    v = _i32(0)
+    _check(_lib.pd_stage_version(stage, mb_id, C.byref(v)))
+    return v.value
+
+
+def pd_stage_trace(stage: int):
+    n = _sz(0)
+    rc = _lib.pd_stage_trace(stage, None, 0, C.byref(n))
+    if n.value == 0:
+        _check(rc)
+        return []
+    arr = (pd_op * n.value)()
+    _check(_lib.pd_stage_trace(stage, arr, n.value, C.byref(n)))
+    return _ops(arr, n.value)
+
+
+def pd_stage_input_slot(stage: int, mb_id: int) -> int:
+    p = _vp(0)
+    _check(_lib.pd_stage_input_slot(stage, mb_id, C.byref(p)))
+    return p.value
+
+
+def pd_stage_grad_slot(stage: int, mb_id: int) -> int:
+    p = _vp(0)
+    _check(_lib.pd_stage_grad_slot(stage, mb_id, C.byref(p)))
+    return p.value
+
+
+def pd_stage_debug_read(stage: int, what: int, mb_id: int, layer: int, shape) -> np.ndarray:
+    out = np.empty(shape, dtype=np.float32)
+    _check(_lib.pd_stage_debug_read(stage, what, mb_id, layer, out.ctypes.data, out.size))
+    return out
+
+
+def pd_forward(stage: int, mb_id: int, x_dev: int, labels_dev: int = 0, y_dev: int = 0, loss_dev: int = 0):
+    _check(_lib.pd_forward(stage, mb_id, x_dev, labels_dev or None, y_dev or None, loss_dev or None))
+
+
+def pd_backward(stage: int, mb_id: int, dy_dev: int = 0, dx_dev: int = 0):
+    _check(_lib.pd_backward(stage, mb_id, dy_dev or None, dx_dev or None))
+
+
+def pd_update(stage: int):
+    _check(_lib.pd_update(stage))
+
+
+def pd_pipeline_run(stages: Sequence[int], num_minibatches: int, inputs_dev: int, labels_dev: int,
+                    losses_dev: int = 0):
+    arr = (_vp * len(stages))(*stages)
+    _check(_lib.pd_pipeline_run(arr, len(stages), num_minibatches, inputs_dev, labels_dev, losses_dev or None))
+
+
+def pd_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return _lib.pd_gemm_workspace_bytes(M, N, K)
+
+
+def pd_linear_fwd_bf16(stream, x, w, b, y, M, N, K, relu, ws=0, ws_bytes=0):
+    _check(_lib.pd_linear_fwd_bf16(stream, x, w, b or None, y, M, N, K, int(relu), ws or None, ws_bytes))
+
+
+def pd_linear_dgrad_bf16(stream, dz, w, mask, dx, M, N, K, ws=0, ws_bytes=0):
+    _check(_lib.pd_linear_dgrad_bf16(stream, dz, w, mask or None, dx, M, N, K, ws or None, ws_bytes))
+
+
+def pd_linear_wgrad_update_bf16(stream, dz, x, master_w, mom_w, ring_w, master_b, mom_b, ring_b, M, N, K, lr, mu):
+    _check(_lib.pd_linear_wgrad_update_bf16(stream, dz, x, master_w, mom_w, ring_w, master_b or None, mom_b or None,
+                                            ring_b or None, M, N, K, lr, mu))

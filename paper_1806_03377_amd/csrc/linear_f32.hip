@@ -1,0 +1,127 @@
+// fp32 Linear kernels (forward, dgrad, wgrad fused with the momentum-SGD update) for the all-fp32
+// precision mode.  One generic 32x32-tile kernel with strided operands covers the three contractions;
+// sums run over the reduction index in ascending order with fp32 FMAs, so results are deterministic.
+// These shapes (a few hundred per side) are launch-latency bound; the kernel is kept simple.
+#include "pd_kernels.h"
+
+namespace pd {
+namespace {
+
+constexpr int T32 = 32;
+enum { EPI_FWD = 0, EPI_DGRAD = 1, EPI_UPDATE = 2 };
+
+struct EpiArgs {
+  const float* bias;   // FWD: bias[j]
+  int relu;            // FWD
+  const float* mask;   // DGRAD: mask[i][j] > 0 keeps the value
+  float* out;          // FWD / DGRAD output [I][J]
+  const float* w_in;   // UPDATE
+  float* w_out;
+  float* mom;
+  const float* b_in;
+  float* b_out;
+  float* mom_b;
+  const float* dz;     // UPDATE: dz[M][N] for the bias column sums
+  int M;
+  float lr, mu;
+};
+
+// C[i][j] = sum_r A(i,r) B(r,j) with A(i,r) = a[i*a_is + r*a_rs], B(r,j) = b[r*b_rs + j*b_js]
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ a, long a_is, long a_rs,
+                                                       const float* __restrict__ b, long b_rs, long b_js, int I,
+                                                       int J, int R, EpiArgs e) {
+  __shared__ float As[T32][T32 + 1];
+  __shared__ float Bs[T32][T32 + 1];
+  const int t = threadIdx.x, tx = t & 31, ty = t >> 5;
+  const int i0 = blockIdx.y * T32, j0 = blockIdx.x * T32;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int r0 = 0; r0 < R; r0 += T32) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = ty + 8 * q;
+      {  // As[i][r]; let tx run along whichever index is contiguous in memory
+        const int ii = (a_rs == 1) ? row : tx, rr = (a_rs == 1) ? tx : row;
+        const int i = i0 + ii, r = r0 + rr;
+        As[ii][rr] = (i < I && r < R) ? a[i * a_is + r * a_rs] : 0.f;
+      }
+      {  // Bs[r][j]
+        const int rr = (b_js == 1) ? row : tx, jj = (b_js == 1) ? tx : row;
+        const int r = r0 + rr, j = j0 + jj;
+        Bs[rr][jj] = (r < R && j < J) ? b[r * b_rs + j * b_js] : 0.f;
+      }
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int r = 0; r < T32; ++r) {
+      const float bv = Bs[r][tx];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[q] = fmaf(As[ty + 8 * q][r], bv, acc[q]);
+    }
+    __syncthreads();
+  }
+  const int j = j0 + tx;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int i = i0 + ty + 8 * q;
+    if (i >= I || j >= J) continue;
+    const size_t off = (size_t)i * J + j;
+    if (EPI == EPI_FWD) {
+      float v = acc[q] + (e.bias ? e.bias[j] : 0.f);
+      if (e.relu) v = fmaxf(v, 0.f);
+      e.out[off] = v;
+    } else if (EPI == EPI_DGRAD) {
+      e.out[off] = (e.mask && !(e.mask[off] > 0.f)) ? 0.f : acc[q];
+    } else {
+      const float m = e.mu * e.mom[off] + acc[q];
+      e.mom[off] = m;
+      e.w_out[off] = e.w_in[off] - e.lr * m;
+    }
+  }
+  if (EPI == EPI_UPDATE && blockIdx.x == 0 && e.b_in && t < T32) {
+    const int n = i0 + t;  // rows of w are output features
+    if (n < I) {
+      float g = 0.f;
+      for (int m = 0; m < e.M; ++m) g += e.dz[(size_t)m * I + n];
+      const float mv = e.mu * e.mom_b[n] + g;
+      e.mom_b[n] = mv;
+      e.b_out[n] = e.b_in[n] - e.lr * mv;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t linear_fwd_f32(hipStream_t s, const float* x, const float* w, const float* b, float* y, int M, int N, int K,
+                          bool relu) {
+  EpiArgs e = {};
+  e.bias = b; e.relu = relu ? 1 : 0; e.out = y;
+  dim3 grid((N + T32 - 1) / T32, (M + T32 - 1) / T32);
+  // y[m][n] = sum_k x[m][k] w[n][k]
+  gemm_f32_kernel<EPI_FWD><<<grid, 256, 0, s>>>(x, K, 1, w, 1, K, M, N, K, e);
+  return hipGetLastError();
+}
+
+hipError_t linear_dgrad_f32(hipStream_t s, const float* dz, const float* w, const float* mask, float* dx, int M, int N,
+                            int K) {
+  EpiArgs e = {};
+  e.mask = mask; e.out = dx;
+  dim3 grid((K + T32 - 1) / T32, (M + T32 - 1) / T32);
+  // dx[m][k] = sum_n dz[m][n] w[n][k]
+  gemm_f32_kernel<EPI_DGRAD><<<grid, 256, 0, s>>>(dz, N, 1, w, K, 1, M, K, N, e);
+  return hipGetLastError();
+}
+
+hipError_t linear_wgrad_update_f32(hipStream_t s, const float* dz, const float* x, const float* w_in, float* w_out,
+                                   float* mom_w, const float* b_in, float* b_out, float* mom_b, int M, int N, int K,
+                                   float lr, float mu) {
+  EpiArgs e = {};
+  e.w_in = w_in; e.w_out = w_out; e.mom = mom_w; e.b_in = b_in; e.b_out = b_out; e.mom_b = mom_b;
+  e.dz = dz; e.M = M; e.lr = lr; e.mu = mu;
+  dim3 grid((K + T32 - 1) / T32, (N + T32 - 1) / T32);
+  // g[n][k] = sum_m dz[m][n] x[m][k]
+  gemm_f32_kernel<EPI_UPDATE><<<grid, 256, 0, s>>>(dz, 1, N, x, K, 1, N, K, M, e);
+  return hipGetLastError();
+}
+
+}  // namespace pd

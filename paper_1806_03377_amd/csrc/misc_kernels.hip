@@ -1,0 +1,157 @@
+// Element-wise helpers and the softmax cross-entropy loss of the output stage.
+#include "pd_kernels.h"
+
+namespace pd {
+namespace {
+
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+__global__ __launch_bounds__(256) void copy_kernel(const uint8_t* __restrict__ src, uint8_t* __restrict__ dst,
+                                                   size_t bytes, int vec_ok) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t done = 0;
+  if (vec_ok) {
+    const size_t n16 = bytes / 16;
+    const uint4* s4 = reinterpret_cast<const uint4*>(src);
+    uint4* d4 = reinterpret_cast<uint4*>(dst);
+    for (size_t i = tid; i < n16; i += stride) d4[i] = s4[i];
+    done = n16 * 16;
+  }
+  for (size_t i = done + tid; i < bytes; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(uint32_t* __restrict__ dst, size_t words) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride) dst[i] = 0u;
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst,
+                                                          size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = f2bf(src[i]);
+}
+__global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst,
+                                                          size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = bf2f(src[i]);
+}
+
+template <bool BF>
+__global__ __launch_bounds__(256) void relu_mask_kernel(const void* __restrict__ dy, const void* __restrict__ y,
+                                                        void* __restrict__ dz, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    if (BF) {
+      const uint16_t yv = static_cast<const uint16_t*>(y)[i];
+      const bool pos = (yv & 0x8000u) == 0 && (yv & 0x7fffu) != 0;
+      static_cast<uint16_t*>(dz)[i] = pos ? static_cast<const uint16_t*>(dy)[i] : (uint16_t)0;
+    } else {
+      static_cast<float*>(dz)[i] = static_cast<const float*>(y)[i] > 0.f ? static_cast<const float*>(dy)[i] : 0.f;
+    }
+  }
+}
+
+// Block-wide reductions in a fixed order (tree over 256 partials held in LDS).
+__device__ __forceinline__ float block_reduce(float v, float* sh, bool is_max) {
+  const int t = threadIdx.x;
+  sh[t] = v;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (t < s) sh[t] = is_max ? fmaxf(sh[t], sh[t + s]) : sh[t] + sh[t + s];
+    __syncthreads();
+  }
+  const float r = sh[0];
+  __syncthreads();
+  return r;
+}
+
+// One workgroup per row: max, sum of exponentials, then dlogits = (p - onehot)/rows and the row's loss.
+template <bool BF>
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ logits,
+                                                           const int32_t* __restrict__ labels,
+                                                           void* __restrict__ dlogits, float* __restrict__ row_loss,
+                                                           int rows, int classes) {
+  __shared__ float sh[256];
+  const int r = blockIdx.x, t = threadIdx.x;
+  const size_t base = (size_t)r * classes;
+  auto ld = [&](int c) -> float { return logits[base + c]; };
+  float mx = -INFINITY;
+  for (int c = t; c < classes; c += 256) mx = fmaxf(mx, ld(c));
+  mx = block_reduce(mx, sh, true);
+  float sum = 0.f;
+  for (int c = t; c < classes; c += 256) sum += expf(ld(c) - mx);
+  sum = block_reduce(sum, sh, false);
+  const float inv = 1.f / sum, invr = 1.f / (float)rows;
+  int lab = labels[r];
+  lab = lab < 0 ? 0 : (lab >= classes ? classes - 1 : lab);  // out-of-range labels are clamped, never dereferenced
+  for (int c = t; c < classes; c += 256) {
+    float d = expf(ld(c) - mx) * inv;
+    if (c == lab) d -= 1.f;
+    d *= invr;
+    if (BF) static_cast<uint16_t*>(dlogits)[base + c] = f2bf(d);
+    else static_cast<float*>(dlogits)[base + c] = d;
+  }
+  if (t == 0) row_loss[r] = logf(sum) + mx - ld(lab);
+}
+
+__global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
+  __shared__ float sh[256];
+  float s = 0.f;
+  for (int i = threadIdx.x; i < n; i += 256) s += v[i];
+  s = block_reduce(s, sh, false);
+  if (threadIdx.x == 0) *out = s / (float)n;
+}
+
+unsigned grid_for(size_t n) {
+  size_t g = (n + 255) / 256;
+  if (g > 4096) g = 4096;
+  if (g < 1) g = 1;
+  return (unsigned)g;
+}
+
+}  // namespace
+
+hipError_t copy_bytes(hipStream_t s, const void* src, void* dst, size_t bytes) {
+  if (bytes == 0) return hipSuccess;
+  const int vec_ok = ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0;
+  copy_kernel<<<grid_for(bytes / 16 + 1), 256, 0, s>>>(static_cast<const uint8_t*>(src), static_cast<uint8_t*>(dst),
+                                                       bytes, vec_ok);
+  return hipGetLastError();
+}
+hipError_t fill_zero(hipStream_t s, void* dst, size_t bytes) {
+  if (bytes == 0) return hipSuccess;
+  zero_kernel<<<grid_for(bytes / 4), 256, 0, s>>>(static_cast<uint32_t*>(dst), bytes / 4);
+  return hipGetLastError();
+}
+hipError_t f32_to_bf16(hipStream_t s, const float* src, bf16_t* dst, size_t n) {
+  if (n == 0) return hipSuccess;
+  f32_to_bf16_kernel<<<grid_for(n), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+hipError_t bf16_to_f32(hipStream_t s, const bf16_t* src, float* dst, size_t n) {
+  if (n == 0) return hipSuccess;
+  bf16_to_f32_kernel<<<grid_for(n), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+hipError_t relu_mask(hipStream_t s, const void* dy, const void* y, void* dz, size_t n, bool is_bf16) {
+  if (n == 0) return hipSuccess;
+  if (is_bf16) relu_mask_kernel<true><<<grid_for(n), 256, 0, s>>>(dy, y, dz, n);
+  else relu_mask_kernel<false><<<grid_for(n), 256, 0, s>>>(dy, y, dz, n);
+  return hipGetLastError();
+}
+hipError_t softmax_xent(hipStream_t s, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
+                        float* loss, int rows, int classes, bool dlogits_bf16) {
+  if (dlogits_bf16) softmax_xent_kernel<true><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
+  else softmax_xent_kernel<false><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
+  if (loss) mean_kernel<<<1, 256, 0, s>>>(row_loss, rows, loss);
+  return hipGetLastError();
+}
+
+}  // namespace pd

@@ -1,0 +1,51 @@
+// Launchers of the HIP kernels behind the stage runtime.  Every launcher only enqueues on the
+// given stream; none allocates, synchronises or memsets.  All pointers are device pointers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pd {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+// ---- bf16 x bf16 -> fp32-accumulate MFMA GEMMs (gemm_bf16.hip) ---------------------------------
+// Bytes of split-K scratch the fwd/dgrad launchers may use for this shape.
+size_t gemm_bf16_workspace_bytes(int M, int N, int K);
+// y[M][N] = act(x[M][K] * w[N][K]^T + b[N]); written as bf16 to y, or unrounded as fp32 to y_f32 if that is
+// not null (then y is not written).
+hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const bf16_t* b, bf16_t* y, float* y_f32,
+                           int M, int N, int K, bool relu, float* ws, size_t ws_bytes);
+// dx[M][K] = (dz[M][N] * w[N][K]) .* (mask[M][K] > 0)   (mask may be null); dx bf16.
+hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
+                             int N, int K, float* ws, size_t ws_bytes);
+// g = dz[M][N]^T x[M][K]; m <- mu*m + g; master <- master - lr*m; ring_out <- bf16(master); same for the bias
+// with g_b = column sums of dz.
+hipError_t linear_wgrad_update_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* master_w, float* mom_w,
+                                    bf16_t* ring_w, float* master_b, float* mom_b, bf16_t* ring_b, int M, int N, int K,
+                                    float lr, float mu);
+
+// ---- fp32 path (linear_f32.hip) ------------------------------------------------------------------
+hipError_t linear_fwd_f32(hipStream_t s, const float* x, const float* w, const float* b, float* y, int M, int N, int K,
+                          bool relu);
+hipError_t linear_dgrad_f32(hipStream_t s, const float* dz, const float* w, const float* mask, float* dx, int M, int N,
+                            int K);
+// w_out <- w_in - lr*(m <- mu*m + dz^T x); w_in may equal w_out.
+hipError_t linear_wgrad_update_f32(hipStream_t s, const float* dz, const float* x, const float* w_in, float* w_out,
+                                   float* mom_w, const float* b_in, float* b_out, float* mom_b, int M, int N, int K,
+                                   float lr, float mu);
+
+// ---- element-wise and loss kernels (misc_kernels.hip) --------------------------------------------
+hipError_t copy_bytes(hipStream_t s, const void* src, void* dst, size_t bytes);  // bytes % 4 == 0 or any
+hipError_t fill_zero(hipStream_t s, void* dst, size_t bytes);
+hipError_t f32_to_bf16(hipStream_t s, const float* src, bf16_t* dst, size_t n);
+hipError_t bf16_to_f32(hipStream_t s, const bf16_t* src, float* dst, size_t n);
+// dz = dy .* (y > 0)   (bf16 or fp32 elements, n elements)
+hipError_t relu_mask(hipStream_t s, const void* dy, const void* y, void* dz, size_t n, bool is_bf16);
+// softmax cross-entropy over rows: dlogits = (softmax - onehot)/rows, row_loss[r] = -log softmax[label];
+// then *loss = mean(row_loss) (summed in row order by one workgroup).  loss may be null.
+// logits are always fp32; dlogits are bf16 if dlogits_bf16, else fp32.
+hipError_t softmax_xent(hipStream_t s, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
+                        float* loss, int rows, int classes, bool dlogits_bf16);
+
+}  // namespace pd

@@ -1,0 +1,754 @@
+// Host side of the stage runtime: the C ABI of include/pd.h.
+//
+// Holds only integers and pointers: the static 1F1B op list (Section 3.3), the weight-version ring and
+// the per-minibatch stash table (Sections 3.4 and 4), the carving of the caller's arena (Section 3.5),
+// and the enqueue order of the HIP kernels.  No arithmetic of the method happens on the host.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/pd.h"
+#include "pd_kernels.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+#define PD_HIP(expr)                                                                           \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) return fail(PD_EHIP, "%s: %s", #expr, hipGetErrorString(e_));        \
+  } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---- schedule ------------------------------------------------------------------------------------
+// Start-up forwards, then for every minibatch k in arrival order: its backward, its update, and the
+// forward that refills the slot it freed.  `latest` is carried along exactly as the stage does.
+void build_schedule(int depth, int M, std::vector<pd_op>& ops) {
+  ops.clear();
+  if (M <= 0) return;
+  const int W = depth < M ? depth : M;  // a short stream never fills the stage
+  std::vector<int> seen(M, 0);
+  int latest = 0;
+  for (int i = 0; i < W; ++i) {
+    seen[i] = latest;
+    ops.push_back({PD_OP_F, i, latest, latest % depth});
+  }
+  for (int k = 0; k < M; ++k) {
+    ops.push_back({PD_OP_B, k, seen[k], seen[k] % depth});
+    ++latest;
+    ops.push_back({PD_OP_U, k, latest, latest % depth});
+    const int nf = k + W;
+    if (nf < M) {
+      seen[nf] = latest;
+      ops.push_back({PD_OP_F, nf, latest, latest % depth});
+    }
+  }
+}
+
+int stage_depth(int num_stages, int noam, int stage_index) {
+  (void)num_stages;
+  const int d = noam - stage_index;
+  return d < 1 ? 1 : d;
+}
+
+int emit_schedule(int depth, int M, pd_op* out, size_t cap, size_t* n_out) {
+  std::vector<pd_op> ops;
+  build_schedule(depth, M, ops);
+  if (n_out) *n_out = ops.size();
+  if (ops.size() > cap) return fail(PD_ENOMEM, "schedule needs %zu entries, capacity %zu", ops.size(), cap);
+  if (!ops.empty()) {
+    if (!out) return fail(PD_EINVAL, "out is null");
+    memcpy(out, ops.data(), ops.size() * sizeof(pd_op));
+  }
+  return PD_OK;
+}
+
+struct Linear {
+  int in, out;
+  bool relu;
+  size_t w_off, b_off;    // element offsets inside one parameter set on the device (padded)
+  size_t flat_w, flat_b;  // element offsets inside the caller's flat vector
+  size_t y_off;           // byte offset of this layer's output inside a stash slot
+  size_t dz_off;          // byte offset of dL/d(pre-activation) inside the gradient workspace
+};
+
+struct InFlight {
+  int mb, version;
+};
+
+}  // namespace
+
+struct pd_stage {
+  int stage_index = 0, num_stages = 1, noam = 1;
+  int depth = 1, in_depth = 1;
+  int B = 0;
+  bool bf16 = false;
+  bool has_loss = false;
+  int classes = 0;
+  float lr = 0.f, mu = 0.f;
+  hipStream_t stream = nullptr;
+  std::vector<Linear> lin;
+  size_t esz = 4;
+  size_t n_params = 0;       // flat length
+  size_t p_pad = 0;          // elements per parameter set on the device
+  size_t in_bytes = 0, out_bytes = 0, stash_slot_bytes = 0, dlogits_off = 0;
+  // device regions (inside the caller's arena)
+  char* ring = nullptr;      // depth parameter sets (bf16 or fp32)
+  float* master = nullptr;   // bf16 mode only
+  float* mom = nullptr;
+  char* in_ring = nullptr;
+  char* stash = nullptr;
+  char* dz = nullptr;
+  char* grad_in = nullptr;   // 2 slots, stages without a loss
+  float* ws = nullptr;
+  size_t ws_bytes = 0;
+  float* row_loss = nullptr;
+  // protocol state
+  int latest = 0;
+  int last_fwd = -1;
+  std::deque<InFlight> in_flight;
+  bool grad_pending = false;
+  int pending_mb = -1;
+  std::vector<pd_op> trace;
+  // events of pd_pipeline_run (grown on demand, reused)
+  std::vector<hipEvent_t> ev_f, ev_b, ev_u;
+
+  char* ring_slot(int version) const { return ring + (size_t)(version % depth) * p_pad * esz; }
+  char* in_slot(int mb) const { return in_ring + (size_t)(mb % in_depth) * in_bytes; }
+  char* stash_slot(int mb) const { return stash + (size_t)(mb % depth) * stash_slot_bytes; }
+  char* grad_slot(int mb) const { return grad_in + (size_t)(mb & 1) * out_bytes; }
+};
+
+namespace {
+
+struct Plan {
+  std::vector<Linear> lin;
+  bool has_loss = false, bf16 = false;
+  int classes = 0, depth = 1, in_depth = 1, B = 0;
+  size_t esz = 4, n_params = 0, p_pad = 0, in_bytes = 0, out_bytes = 0, stash_slot_bytes = 0, dlogits_off = 0;
+  size_t ws_bytes = 0, dz_bytes = 0;
+  // arena offsets
+  size_t o_ring = 0, o_master = 0, o_mom = 0, o_in = 0, o_stash = 0, o_dz = 0, o_grad = 0, o_ws = 0, o_rowloss = 0;
+  size_t total = 0;
+};
+
+int make_plan(const pd_stage_config* c, Plan& p) {
+  if (!c) return fail(PD_EINVAL, "config is null");
+  if (c->num_stages < 1 || c->stage_index < 0 || c->stage_index >= c->num_stages)
+    return fail(PD_EINVAL, "stage_index %d outside [0, %d)", c->stage_index, c->num_stages);
+  if (c->noam < 1) return fail(PD_EINVAL, "noam must be >= 1");
+  if (c->minibatch < 1) return fail(PD_EINVAL, "minibatch must be >= 1");
+  if (c->precision != PD_F32 && c->precision != PD_BF16_F32ACC) return fail(PD_EINVAL, "unknown precision");
+  if (c->n_layers < 1 || !c->layers) return fail(PD_EINVAL, "no layers");
+  p.bf16 = c->precision == PD_BF16_F32ACC;
+  p.esz = p.bf16 ? 2 : 4;
+  p.B = c->minibatch;
+  p.depth = c->in_flight_override > 0 ? c->in_flight_override : stage_depth(c->num_stages, c->noam, c->stage_index);
+  p.in_depth = c->stage_index > 0 ? p.depth + 1 : p.depth;
+  size_t flat = 0, dev = 0, y_off = 0, dz_off = 0;
+  int width = -1;
+  for (int i = 0; i < c->n_layers; ++i) {
+    const pd_layer_desc& d = c->layers[i];
+    if (p.has_loss) return fail(PD_EINVAL, "PD_SOFTMAX_XENT must be the last layer");
+    if (d.kind == PD_LINEAR) {
+      Linear L;
+      L.in = d.p[0]; L.out = d.p[1]; L.relu = d.p[2] != 0;
+      if (L.in < 1 || L.out < 1) return fail(PD_EINVAL, "layer %d: bad Linear shape %dx%d", i, L.out, L.in);
+      if (width >= 0 && L.in != width) return fail(PD_EINVAL, "layer %d: in_features %d != previous width %d", i, L.in, width);
+      if (p.bf16 && ((L.in % 8) || (L.out % 8)))
+        return fail(PD_EINVAL, "layer %d: bf16 mode needs in/out features divisible by 8 (got %d, %d)", i, L.in, L.out);
+      width = L.out;
+      L.flat_w = flat; flat += (size_t)L.in * L.out;
+      L.flat_b = flat; flat += L.out;
+      L.w_off = dev; dev = align_up(dev + (size_t)L.in * L.out, 128);
+      L.b_off = dev; dev = align_up(dev + L.out, 128);
+      L.y_off = y_off; y_off = align_up(y_off + (size_t)p.B * L.out * 4, 256);  // room for fp32 (logits)
+      L.dz_off = dz_off; dz_off = align_up(dz_off + (size_t)p.B * L.out * p.esz, 256);
+      p.lin.push_back(L);
+    } else if (d.kind == PD_SOFTMAX_XENT) {
+      if (p.lin.empty() || i == 0 || c->layers[i - 1].kind != PD_LINEAR)
+        return fail(PD_EINVAL, "PD_SOFTMAX_XENT must follow a PD_LINEAR");
+      if (d.p[0] != width) return fail(PD_EINVAL, "loss classes %d != logits width %d", d.p[0], width);
+      if (p.lin.back().relu) return fail(PD_EINVAL, "the Linear feeding the loss must not have a ReLU");
+      p.has_loss = true;
+      p.classes = width;
+    } else {
+      return fail(PD_EINVAL, "layer %d: unknown kind %d", i, d.kind);
+    }
+  }
+  if (p.lin.empty()) return fail(PD_EINVAL, "stage has no Linear layer");
+  p.n_params = flat;
+  p.p_pad = dev;
+  p.in_bytes = align_up((size_t)p.B * p.lin.front().in * p.esz, 256);
+  p.out_bytes = align_up((size_t)p.B * p.lin.back().out * p.esz, 256);
+  p.dlogits_off = y_off;
+  if (p.has_loss) y_off = align_up(y_off + (size_t)p.B * p.classes * p.esz, 256);
+  p.stash_slot_bytes = y_off;
+  p.dz_bytes = dz_off;
+  if (p.bf16)
+    for (const Linear& L : p.lin) {
+      const size_t w = pd::gemm_bf16_workspace_bytes(p.B, L.out, L.in);
+      if (w > p.ws_bytes) p.ws_bytes = w;
+    }
+  p.ws_bytes = align_up(p.ws_bytes, 256);
+  size_t o = 0;
+  p.o_ring = o; o += align_up((size_t)p.depth * p.p_pad * p.esz, 256);
+  if (p.bf16) { p.o_master = o; o += align_up(p.p_pad * 4, 256); }
+  p.o_mom = o; o += align_up(p.p_pad * 4, 256);
+  p.o_in = o; o += (size_t)p.in_depth * p.in_bytes;
+  p.o_stash = o; o += (size_t)p.depth * p.stash_slot_bytes;
+  p.o_dz = o; o += p.dz_bytes;
+  if (!p.has_loss) { p.o_grad = o; o += 2 * p.out_bytes; }
+  p.o_ws = o; o += p.ws_bytes;
+  p.o_rowloss = o; o += align_up((size_t)p.B * 4, 256);
+  p.total = o;
+  return PD_OK;
+}
+
+int check_stage(const pd_stage* st) { return st ? PD_OK : fail(PD_EINVAL, "stage is null"); }
+
+}  // namespace
+
+extern "C" {
+
+const char* pd_last_error(void) { return g_err.c_str(); }
+
+int pd_schedule_1f1b(int32_t num_stages, int32_t noam, int32_t num_minibatches, int32_t stage_index, pd_op* out,
+                     size_t cap, size_t* n_out) {
+  if (num_stages < 1 || stage_index < 0 || stage_index >= num_stages || noam < 1 || num_minibatches < 0)
+    return fail(PD_EINVAL, "bad schedule arguments (S=%d noam=%d M=%d s=%d)", num_stages, noam, num_minibatches, stage_index);
+  return emit_schedule(stage_depth(num_stages, noam, stage_index), num_minibatches, out, cap, n_out);
+}
+
+int pd_schedule_1f1b_depth(int32_t depth, int32_t num_minibatches, pd_op* out, size_t cap, size_t* n_out) {
+  if (depth < 1 || num_minibatches < 0) return fail(PD_EINVAL, "bad schedule arguments (depth=%d M=%d)", depth, num_minibatches);
+  return emit_schedule(depth, num_minibatches, out, cap, n_out);
+}
+
+int pd_stage_query_bytes(const pd_stage_config* cfg, size_t* device_bytes) {
+  if (!device_bytes) return fail(PD_EINVAL, "device_bytes is null");
+  Plan p;
+  const int rc = make_plan(cfg, p);
+  if (rc != PD_OK) return rc;
+  *device_bytes = p.total;
+  return PD_OK;
+}
+
+int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena_bytes, pd_stage** out) {
+  if (!out) return fail(PD_EINVAL, "out is null");
+  *out = nullptr;
+  Plan p;
+  const int rc = make_plan(cfg, p);
+  if (rc != PD_OK) return rc;
+  if (!device_arena) return fail(PD_EINVAL, "device_arena is null");
+  if (reinterpret_cast<uintptr_t>(device_arena) & 255u) return fail(PD_EINVAL, "device_arena must be 256-byte aligned");
+  if (arena_bytes < p.total) return fail(PD_ENOMEM, "arena has %zu bytes, stage needs %zu", arena_bytes, p.total);
+  pd_stage* st = new (std::nothrow) pd_stage();
+  if (!st) return fail(PD_ENOMEM, "host allocation failed");
+  char* a = static_cast<char*>(device_arena);
+  st->stage_index = cfg->stage_index; st->num_stages = cfg->num_stages; st->noam = cfg->noam;
+  st->depth = p.depth; st->in_depth = p.in_depth; st->B = p.B; st->bf16 = p.bf16; st->has_loss = p.has_loss;
+  st->classes = p.classes; st->lr = cfg->lr; st->mu = cfg->momentum;
+  st->stream = static_cast<hipStream_t>(cfg->stream);
+  st->lin = p.lin; st->esz = p.esz; st->n_params = p.n_params; st->p_pad = p.p_pad;
+  st->in_bytes = p.in_bytes; st->out_bytes = p.out_bytes; st->stash_slot_bytes = p.stash_slot_bytes;
+  st->dlogits_off = p.dlogits_off;
+  st->ring = a + p.o_ring;
+  st->master = p.bf16 ? reinterpret_cast<float*>(a + p.o_master) : nullptr;
+  st->mom = reinterpret_cast<float*>(a + p.o_mom);
+  st->in_ring = a + p.o_in; st->stash = a + p.o_stash; st->dz = a + p.o_dz;
+  st->grad_in = p.has_loss ? nullptr : a + p.o_grad;
+  st->ws = reinterpret_cast<float*>(a + p.o_ws); st->ws_bytes = p.ws_bytes;
+  st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
+  hipError_t e = pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
+  if (e != hipSuccess) {
+    delete st;
+    return fail(PD_EHIP, "clearing momentum: %s", hipGetErrorString(e));
+  }
+  *out = st;
+  return PD_OK;
+}
+
+int pd_stage_destroy(pd_stage* st) {
+  if (!st) return PD_OK;
+  for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u})
+    for (hipEvent_t e : *v) (void)hipEventDestroy(e);
+  delete st;
+  return PD_OK;
+}
+
+int pd_stage_num_params(const pd_stage* st, size_t* n) {
+  if (check_stage(st) || !n) return fail(PD_EINVAL, "null argument");
+  *n = st->n_params;
+  return PD_OK;
+}
+
+int pd_stage_depth(const pd_stage* st, int32_t* depth, int32_t* input_ring_depth) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (depth) *depth = st->depth;
+  if (input_ring_depth) *input_ring_depth = st->in_depth;
+  return PD_OK;
+}
+
+int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
+  if (check_stage(st) || !host_params) return fail(PD_EINVAL, "null argument");
+  if (n != st->n_params) return fail(PD_EINVAL, "expected %zu parameters, got %zu", st->n_params, n);
+  PD_HIP(hipStreamSynchronize(st->stream));
+  float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(st->ring);
+  for (const Linear& L : st->lin) {
+    PD_HIP(hipMemcpy(dst32 + L.w_off, host_params + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
+    PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+    if (st->bf16) {
+      pd::bf16_t* r = reinterpret_cast<pd::bf16_t*>(st->ring);
+      PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, (size_t)L.in * L.out));
+      PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, (size_t)L.out));
+    }
+  }
+  PD_HIP(pd::fill_zero(st->stream, st->mom, st->p_pad * 4));
+  PD_HIP(hipStreamSynchronize(st->stream));
+  st->latest = 0; st->last_fwd = -1; st->in_flight.clear(); st->grad_pending = false; st->trace.clear();
+  return PD_OK;
+}
+
+int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float* host_out, size_t n) {
+  if (check_stage(st) || !host_out) return fail(PD_EINVAL, "null argument");
+  if (n != st->n_params) return fail(PD_EINVAL, "expected %zu parameters, got %zu", st->n_params, n);
+  if (version < 0) version = st->latest;
+  if (version > st->latest || version <= st->latest - st->depth)
+    return fail(PD_ESTATE, "version %d is not in the ring (latest %d, depth %d)", version, st->latest, st->depth);
+  PD_HIP(hipStreamSynchronize(st->stream));
+  const bool from_master = st->bf16 && version == st->latest && !ring_copy;
+  if (!st->bf16 || from_master) {
+    const float* src = from_master ? st->master : reinterpret_cast<const float*>(st->ring_slot(version));
+    for (const Linear& L : st->lin) {
+      PD_HIP(hipMemcpy(host_out + L.flat_w, src + L.w_off, (size_t)L.in * L.out * 4, hipMemcpyDeviceToHost));
+      PD_HIP(hipMemcpy(host_out + L.flat_b, src + L.b_off, (size_t)L.out * 4, hipMemcpyDeviceToHost));
+    }
+    return PD_OK;
+  }
+  const uint16_t* src = reinterpret_cast<const uint16_t*>(st->ring_slot(version));
+  std::vector<uint16_t> tmp;
+  auto widen = [&](size_t dev_off, size_t flat_off, size_t cnt) -> hipError_t {
+    tmp.resize(cnt);
+    hipError_t e = hipMemcpy(tmp.data(), src + dev_off, cnt * 2, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return e;
+    for (size_t i = 0; i < cnt; ++i) {
+      const uint32_t u = (uint32_t)tmp[i] << 16;
+      memcpy(host_out + flat_off + i, &u, 4);
+    }
+    return hipSuccess;
+  };
+  for (const Linear& L : st->lin) {
+    PD_HIP(widen(L.w_off, L.flat_w, (size_t)L.in * L.out));
+    PD_HIP(widen(L.b_off, L.flat_b, (size_t)L.out));
+  }
+  return PD_OK;
+}
+
+int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n) {
+  if (check_stage(st) || !host_mom) return fail(PD_EINVAL, "null argument");
+  if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
+  if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "minibatches in flight");
+  PD_HIP(hipStreamSynchronize(st->stream));
+  for (const Linear& L : st->lin) {
+    PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
+    PD_HIP(hipMemcpy(st->mom + L.b_off, host_mom + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+  }
+  return PD_OK;
+}
+
+int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n) {
+  if (check_stage(st) || !host_out) return fail(PD_EINVAL, "null argument");
+  if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
+  PD_HIP(hipStreamSynchronize(st->stream));
+  for (const Linear& L : st->lin) {
+    PD_HIP(hipMemcpy(host_out + L.flat_w, st->mom + L.w_off, (size_t)L.in * L.out * 4, hipMemcpyDeviceToHost));
+    PD_HIP(hipMemcpy(host_out + L.flat_b, st->mom + L.b_off, (size_t)L.out * 4, hipMemcpyDeviceToHost));
+  }
+  return PD_OK;
+}
+
+int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const float* host_mom, size_t n) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
+  if (st->grad_pending) return fail(PD_ESTATE, "a gradient is pending: call pd_update first");
+  PD_HIP(hipStreamSynchronize(st->stream));
+  char* slot = st->ring_slot(st->latest);
+  float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(slot);
+  for (const Linear& L : st->lin) {
+    if (host_params) {
+      PD_HIP(hipMemcpy(dst32 + L.w_off, host_params + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
+      PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+      if (st->bf16) {
+        pd::bf16_t* r = reinterpret_cast<pd::bf16_t*>(slot);
+        PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, (size_t)L.in * L.out));
+        PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, (size_t)L.out));
+      }
+    }
+    if (host_mom) {
+      PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
+      PD_HIP(hipMemcpy(st->mom + L.b_off, host_mom + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+    }
+  }
+  PD_HIP(hipStreamSynchronize(st->stream));
+  return PD_OK;
+}
+
+int pd_stage_version(const pd_stage* st, int32_t mb_id, int32_t* version) {
+  if (check_stage(st) || !version) return fail(PD_EINVAL, "null argument");
+  if (mb_id < 0) {
+    *version = st->latest;
+    return PD_OK;
+  }
+  for (const InFlight& f : st->in_flight)
+    if (f.mb == mb_id) {
+      *version = f.version;
+      return PD_OK;
+    }
+  return fail(PD_ESTATE, "minibatch %d is not in flight", mb_id);
+}
+
+int pd_stage_trace(const pd_stage* st, pd_op* out, size_t cap, size_t* n_out) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (n_out) *n_out = st->trace.size();
+  if (st->trace.size() > cap) return fail(PD_ENOMEM, "trace has %zu entries, capacity %zu", st->trace.size(), cap);
+  if (!st->trace.empty()) {
+    if (!out) return fail(PD_EINVAL, "out is null");
+    memcpy(out, st->trace.data(), st->trace.size() * sizeof(pd_op));
+  }
+  return PD_OK;
+}
+
+int pd_stage_input_slot(pd_stage* st, int32_t mb_id, void** dev_ptr) {
+  if (check_stage(st) || !dev_ptr || mb_id < 0) return fail(PD_EINVAL, "bad argument");
+  *dev_ptr = st->in_slot(mb_id);
+  return PD_OK;
+}
+
+int pd_stage_grad_slot(pd_stage* st, int32_t mb_id, void** dev_ptr) {
+  if (check_stage(st) || !dev_ptr || mb_id < 0) return fail(PD_EINVAL, "bad argument");
+  if (st->has_loss) return fail(PD_ESTATE, "a stage that ends in the loss takes no output gradient");
+  *dev_ptr = st->grad_slot(mb_id);
+  return PD_OK;
+}
+
+int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, float* host_out, size_t n) {
+  if (check_stage(st) || !host_out || mb_id < 0) return fail(PD_EINVAL, "bad argument");
+  const int nl = (int)st->lin.size();
+  const char* src = nullptr;
+  size_t cnt = 0;
+  switch (what) {
+    case 0:
+      if (layer < 0 || layer >= nl) return fail(PD_EINVAL, "layer %d out of range", layer);
+      src = st->stash_slot(mb_id) + st->lin[layer].y_off;
+      cnt = (size_t)st->B * st->lin[layer].out;
+      break;
+    case 1:
+      src = st->in_slot(mb_id);
+      cnt = (size_t)st->B * st->lin.front().in;
+      break;
+    case 2:
+      if (st->has_loss) return fail(PD_ESTATE, "a stage that ends in the loss has no output-gradient slot");
+      src = st->grad_slot(mb_id);
+      cnt = (size_t)st->B * st->lin.back().out;
+      break;
+    case 3:
+      if (layer < 0 || layer >= nl) return fail(PD_EINVAL, "layer %d out of range", layer);
+      src = (st->has_loss && layer == nl - 1) ? st->stash_slot(mb_id) + st->dlogits_off : st->dz + st->lin[layer].dz_off;
+      cnt = (size_t)st->B * st->lin[layer].out;
+      break;
+    case 4:
+      if (!st->has_loss) return fail(PD_ESTATE, "stage has no loss");
+      src = st->stash_slot(mb_id) + st->dlogits_off;
+      cnt = (size_t)st->B * st->classes;
+      break;
+    default:
+      return fail(PD_EINVAL, "unknown tensor selector %d", what);
+  }
+  if (n != cnt) return fail(PD_EINVAL, "tensor has %zu elements, caller gave %zu", cnt, n);
+  PD_HIP(hipStreamSynchronize(st->stream));
+  if (!st->bf16 || (what == 0 && st->has_loss && layer == nl - 1)) {  // logits are fp32 in either mode
+    PD_HIP(hipMemcpy(host_out, src, cnt * 4, hipMemcpyDeviceToHost));
+    return PD_OK;
+  }
+  std::vector<uint16_t> tmp(cnt);
+  PD_HIP(hipMemcpy(tmp.data(), src, cnt * 2, hipMemcpyDeviceToHost));
+  for (size_t i = 0; i < cnt; ++i) {
+    const uint32_t u = (uint32_t)tmp[i] << 16;
+    memcpy(host_out + i, &u, 4);
+  }
+  return PD_OK;
+}
+
+int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
+               float* loss_dev) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (!x_dev) return fail(PD_EINVAL, "x_dev is null");
+  if (mb_id < 0) return fail(PD_EINVAL, "mb_id must be >= 0");
+  if (st->has_loss && !labels_dev) return fail(PD_EINVAL, "labels_dev is required on a stage that ends in the loss");
+  if (st->grad_pending) return fail(PD_ESTATE, "pd_update must follow pd_backward before the next forward");
+  if ((int)st->in_flight.size() >= st->depth)
+    return fail(PD_ESTATE, "%d minibatches already in flight (depth %d)", (int)st->in_flight.size(), st->depth);
+  if (st->last_fwd >= 0 && mb_id != st->last_fwd + 1)
+    return fail(PD_ESTATE, "forward of minibatch %d after %d: ids must be consecutive", mb_id, st->last_fwd);
+
+  hipStream_t s = st->stream;
+  const int v = st->latest;  // forward reads the latest version and stashes its id
+  char* in = st->in_slot(mb_id);
+  char* slot = st->stash_slot(mb_id);
+  const char* w = st->ring_slot(v);
+  if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->B * st->lin.front().in * st->esz));
+  const char* a = in;
+  for (const Linear& L : st->lin) {
+    char* y = slot + L.y_off;
+    if (st->bf16) {
+      const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
+      const bool logits = st->has_loss && &L == &st->lin.back();  // logits go to the loss unrounded (fp32)
+      PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, wp + L.b_off,
+                                 reinterpret_cast<pd::bf16_t*>(y), logits ? reinterpret_cast<float*>(y) : nullptr,
+                                 st->B, L.out, L.in, L.relu, st->ws, st->ws_bytes));
+    } else {
+      const float* wp = reinterpret_cast<const float*>(w);
+      PD_HIP(pd::linear_fwd_f32(s, reinterpret_cast<const float*>(a), wp + L.w_off, wp + L.b_off,
+                                reinterpret_cast<float*>(y), st->B, L.out, L.in, L.relu));
+    }
+    a = y;
+  }
+  if (y_dev) PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->B * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
+  if (st->has_loss)
+    PD_HIP(pd::softmax_xent(s, reinterpret_cast<const float*>(a), labels_dev, slot + st->dlogits_off, st->row_loss,
+                            loss_dev, st->B, st->classes, st->bf16));
+  st->in_flight.push_back({mb_id, v});
+  st->last_fwd = mb_id;
+  st->trace.push_back({PD_OP_F, mb_id, v, v % st->depth});
+  return PD_OK;
+}
+
+int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (st->grad_pending) return fail(PD_ESTATE, "previous gradient not yet consumed by pd_update");
+  if (st->in_flight.empty()) return fail(PD_ESTATE, "no minibatch in flight");
+  if (st->in_flight.front().mb != mb_id)
+    return fail(PD_ESTATE, "backward of minibatch %d, but the oldest in flight is %d", mb_id, st->in_flight.front().mb);
+  if (st->has_loss && dy_dev) return fail(PD_EINVAL, "dy_dev must be NULL on a stage that ends in the loss");
+  if (!st->has_loss && !dy_dev) return fail(PD_EINVAL, "dy_dev is null");
+
+  hipStream_t s = st->stream;
+  const int v = st->in_flight.front().version;  // the version this minibatch's forward read
+  const char* w = st->ring_slot(v);
+  char* slot = st->stash_slot(mb_id);
+  const int nl = (int)st->lin.size();
+  const Linear& last = st->lin.back();
+  if (!st->has_loss) {
+    const size_t n = (size_t)st->B * last.out;
+    if (last.relu) PD_HIP(pd::relu_mask(s, dy_dev, slot + last.y_off, st->dz + last.dz_off, n, st->bf16));
+    else PD_HIP(pd::copy_bytes(s, dy_dev, st->dz + last.dz_off, n * st->esz));
+  }
+  for (int l = nl - 1; l >= 0; --l) {
+    const Linear& L = st->lin[l];
+    const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
+    char* out;
+    const char* mask = nullptr;
+    if (l > 0) {
+      out = st->dz + st->lin[l - 1].dz_off;
+      if (st->lin[l - 1].relu) mask = slot + st->lin[l - 1].y_off;
+    } else {
+      if (!dx_dev) break;
+      out = static_cast<char*>(dx_dev);
+    }
+    if (st->bf16) {
+      const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
+      PD_HIP(pd::linear_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz), wp + L.w_off,
+                                   reinterpret_cast<const pd::bf16_t*>(mask), reinterpret_cast<pd::bf16_t*>(out),
+                                   st->B, L.out, L.in, st->ws, st->ws_bytes));
+    } else {
+      const float* wp = reinterpret_cast<const float*>(w);
+      PD_HIP(pd::linear_dgrad_f32(s, reinterpret_cast<const float*>(dz), wp + L.w_off,
+                                  reinterpret_cast<const float*>(mask), reinterpret_cast<float*>(out), st->B, L.out,
+                                  L.in));
+    }
+  }
+  st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
+  st->grad_pending = true;
+  st->pending_mb = mb_id;
+  st->trace.push_back({PD_OP_B, mb_id, v, v % st->depth});
+  return PD_OK;
+}
+
+int pd_update(pd_stage* st) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (!st->grad_pending) return fail(PD_ESTATE, "no pending gradient");
+  hipStream_t s = st->stream;
+  const int mb = st->pending_mb;
+  char* slot = st->stash_slot(mb);
+  const int nl = (int)st->lin.size();
+  const int nv = st->latest + 1;
+  for (int l = 0; l < nl; ++l) {
+    const Linear& L = st->lin[l];
+    const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
+    const char* x = l == 0 ? st->in_slot(mb) : slot + st->lin[l - 1].y_off;
+    if (st->bf16) {
+      pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
+      PD_HIP(pd::linear_wgrad_update_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
+                                          reinterpret_cast<const pd::bf16_t*>(x), st->master + L.w_off,
+                                          st->mom + L.w_off, ro + L.w_off, st->master + L.b_off, st->mom + L.b_off,
+                                          ro + L.b_off, st->B, L.out, L.in, st->lr, st->mu));
+    } else {
+      const float* wi = reinterpret_cast<const float*>(st->ring_slot(st->latest));
+      float* wo = reinterpret_cast<float*>(st->ring_slot(nv));
+      PD_HIP(pd::linear_wgrad_update_f32(s, reinterpret_cast<const float*>(dz), reinterpret_cast<const float*>(x),
+                                         wi + L.w_off, wo + L.w_off, st->mom + L.w_off, wi + L.b_off, wo + L.b_off,
+                                         st->mom + L.b_off, st->B, L.out, L.in, st->lr, st->mu));
+    }
+  }
+  st->latest = nv;
+  st->grad_pending = false;
+  st->trace.push_back({PD_OP_U, mb, nv, nv % st->depth});
+  return PD_OK;
+}
+
+int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_minibatches, const void* inputs_dev,
+                    const int32_t* labels_dev, float* losses_dev) {
+  if (!stages || num_stages < 1) return fail(PD_EINVAL, "no stages");
+  if (num_minibatches < 0) return fail(PD_EINVAL, "num_minibatches < 0");
+  if (num_minibatches == 0) return PD_OK;
+  if (!inputs_dev || !labels_dev) return fail(PD_EINVAL, "inputs_dev / labels_dev is null");
+  const int S = num_stages, M = num_minibatches;
+  for (int s = 0; s < S; ++s) {
+    pd_stage* st = stages[s];
+    if (!st) return fail(PD_EINVAL, "stage %d is null", s);
+    if (st->stage_index != s || st->num_stages != S) return fail(PD_EINVAL, "stage %d has index %d of %d", s, st->stage_index, st->num_stages);
+    if (st->B != stages[0]->B || st->bf16 != stages[0]->bf16) return fail(PD_EINVAL, "stage %d: minibatch/precision differ", s);
+    if (s > 0 && st->lin.front().in != stages[s - 1]->lin.back().out) return fail(PD_EINVAL, "stage %d input width mismatch", s);
+    if (st->has_loss != (s == S - 1)) return fail(PD_EINVAL, "only the last stage may (and must) end in the loss");
+    if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "stage %d has minibatches in flight", s);
+    if (st->last_fwd != stages[0]->last_fwd) return fail(PD_ESTATE, "stages disagree on the next minibatch id");
+  }
+  const int base = stages[0]->last_fwd + 1;
+  std::vector<std::vector<pd_op>> ops(S);
+  for (int s = 0; s < S; ++s) {
+    build_schedule(stages[s]->depth, M, ops[s]);
+    for (auto* v : {&stages[s]->ev_f, &stages[s]->ev_b, &stages[s]->ev_u})
+      while ((int)v->size() < M) {
+        hipEvent_t e;
+        PD_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        v->push_back(e);
+      }
+  }
+  // f_rec[s][i] etc: the event has been recorded (in host order) -- an op is only enqueued after every
+  // event it waits for has been recorded, which makes the host's enqueue order a valid global order.
+  std::vector<std::vector<char>> f_rec(S, std::vector<char>(M, 0)), b_rec = f_rec, u_rec = f_rec;
+  std::vector<size_t> pos(S, 0);
+  const size_t in_elems = (size_t)stages[0]->B * stages[0]->lin.front().in * stages[0]->esz;
+  size_t remaining = 0;
+  for (int s = 0; s < S; ++s) remaining += ops[s].size();
+  while (remaining) {
+    bool progressed = false;
+    for (int s = 0; s < S; ++s) {
+      pd_stage* st = stages[s];
+      while (pos[s] < ops[s].size()) {
+        const pd_op op = ops[s][pos[s]];
+        const int i = op.mb_id, mb = base + i;
+        if (op.kind == PD_OP_F) {
+          int reuse = -1;
+          if (s > 0 && !f_rec[s - 1][i]) break;
+          if (s < S - 1) {
+            reuse = i - stages[s + 1]->in_depth;  // last minibatch that used the slot this forward writes into
+            if (reuse >= 0 && !u_rec[s + 1][reuse]) break;
+          }
+          if (s > 0) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_f[i], 0));
+          if (reuse >= 0) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_u[reuse], 0));
+          const void* x = s == 0 ? static_cast<const char*>(inputs_dev) + (size_t)i * in_elems : st->in_slot(mb);
+          void* y = s < S - 1 ? stages[s + 1]->in_slot(mb) : nullptr;
+          const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->B : nullptr;
+          float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
+          const int rc = pd_forward(st, mb, x, lab, y, loss);
+          if (rc != PD_OK) return rc;
+          PD_HIP(hipEventRecord(st->ev_f[i], st->stream));
+          f_rec[s][i] = 1;
+        } else if (op.kind == PD_OP_B) {
+          if (s < S - 1 && !b_rec[s + 1][i]) break;
+          if (s > 0 && i >= 2 && !b_rec[s - 1][i - 2]) break;  // the gradient slot this backward writes into
+          if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_b[i], 0));
+          if (s > 0 && i >= 2) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_b[i - 2], 0));
+          const void* dy = s < S - 1 ? st->grad_slot(mb) : nullptr;
+          void* dx = s > 0 ? stages[s - 1]->grad_slot(mb) : nullptr;
+          const int rc = pd_backward(st, mb, dy, dx);
+          if (rc != PD_OK) return rc;
+          PD_HIP(hipEventRecord(st->ev_b[i], st->stream));
+          b_rec[s][i] = 1;
+        } else {
+          const int rc = pd_update(st);
+          if (rc != PD_OK) return rc;
+          PD_HIP(hipEventRecord(st->ev_u[i], st->stream));
+          u_rec[s][i] = 1;
+        }
+        ++pos[s];
+        --remaining;
+        progressed = true;
+      }
+    }
+    if (!progressed) return fail(PD_ESTATE, "pipeline cannot make progress (dependency cycle)");
+  }
+  return PD_OK;
+}
+
+size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) { return pd::gemm_bf16_workspace_bytes(M, N, K); }
+
+static int check_gemm(const void* a, const void* b, const void* c, int M, int N, int K) {
+  if (!a || !b || !c) return fail(PD_EINVAL, "null pointer");
+  if (M < 1 || N < 1 || K < 1 || (N % 8) || (K % 8)) return fail(PD_EINVAL, "need M,N,K >= 1 and N,K divisible by 8");
+  return PD_OK;
+}
+
+int pd_linear_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, int32_t M, int32_t N,
+                       int32_t K, int32_t relu, void* workspace_dev, size_t workspace_bytes) {
+  if (check_gemm(x, w, y, M, N, K)) return PD_EINVAL;
+  PD_HIP(pd::linear_fwd_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(x),
+                             static_cast<const pd::bf16_t*>(w), static_cast<const pd::bf16_t*>(b),
+                             static_cast<pd::bf16_t*>(y), nullptr, M, N, K, relu != 0,
+                             static_cast<float*>(workspace_dev), workspace_dev ? workspace_bytes : 0));
+  return PD_OK;
+}
+
+int pd_linear_dgrad_bf16(void* stream, const void* dz, const void* w, const void* mask, void* dx, int32_t M, int32_t N,
+                         int32_t K, void* workspace_dev, size_t workspace_bytes) {
+  if (check_gemm(dz, w, dx, M, N, K)) return PD_EINVAL;
+  PD_HIP(pd::linear_dgrad_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(dz),
+                               static_cast<const pd::bf16_t*>(w), static_cast<const pd::bf16_t*>(mask),
+                               static_cast<pd::bf16_t*>(dx), M, N, K, static_cast<float*>(workspace_dev),
+                               workspace_dev ? workspace_bytes : 0));
+  return PD_OK;
+}
+
+int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, float* master_w, float* mom_w,
+                                void* ring_out_w, float* master_b, float* mom_b, void* ring_out_b, int32_t M, int32_t N,
+                                int32_t K, float lr, float momentum) {
+  if (check_gemm(dz, x, master_w, M, N, K)) return PD_EINVAL;
+  if (!mom_w || !ring_out_w) return fail(PD_EINVAL, "null pointer");
+  if (master_b && (!mom_b || !ring_out_b)) return fail(PD_EINVAL, "bias buffers must be given together");
+  PD_HIP(pd::linear_wgrad_update_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(dz),
+                                      static_cast<const pd::bf16_t*>(x), master_w, mom_w,
+                                      static_cast<pd::bf16_t*>(ring_out_w), master_b, mom_b,
+                                      static_cast<pd::bf16_t*>(ring_out_b), M, N, K, lr, momentum));
+  return PD_OK;
+}
+
+}  // extern "C"

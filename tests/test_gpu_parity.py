@@ -1,0 +1,307 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars (stated by the benchmark definition): schedule order and version indices bit-exact;
+fp32 mode <= 1e-4 and bf16 mode (fp32 accumulate) <= 2e-2 max-norm relative error per tensor
+(max|got - ref| / max|ref|), and the same relative bound on every minibatch's loss.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_1806_03377_amd as pd
+import pd_inputs as gen
+from gpu_util import GpuStage, dev, empty_act, labels_dev, rel_err, to_dev, to_host
+from parity_harness import run_case
+from oracle import layers as OL
+from oracle.pipeline import Stage, run_pipeline
+from oracle.schedule import OP_B, OP_F, OP_U, in_flight_depth, schedule_1f1b
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-4
+TOL_BF16 = 2e-2
+SEED = gen.BASE_SEED
+
+
+def _bf(a):
+    return OL.round_bf16(np.asarray(a, dtype=np.float64))
+
+
+# ---------------------------------------------------------------------------------------------
+# kernels on their own (bf16 MFMA): several tiles, ragged tails in every dimension, split-K on/off
+# ---------------------------------------------------------------------------------------------
+SHAPES = [(64, 128, 64), (64, 256, 4096), (64, 200, 264), (40, 136, 72), (1, 8, 8), (130, 1000, 520),
+          (64, 4096, 1024), (96, 24, 2048), (256, 512, 768)]
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_linear_fwd_bf16(M, N, K):
+    x = _bf(gen.normal(SEED, "kx", (M, K)))
+    w = _bf(gen.uniform(SEED, "kw", (N, K), -0.1, 0.1))
+    b = _bf(gen.normal(SEED, "kb", (N,)) * 0.1)
+    s = torch.cuda.current_stream().cuda_stream
+    wsb = pd.pd_gemm_workspace_bytes(M, N, K)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev())
+    xd, wd, bd = to_dev(x, True), to_dev(w, True), to_dev(b, True)
+    for relu in (True, False):
+        for use_ws in (True, False):
+            y = empty_act(M, N, True)
+            pd.pd_linear_fwd_bf16(s, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), y.data_ptr(), M, N, K, relu,
+                                  ws.data_ptr() if use_ws else 0, wsb if use_ws else 0)
+            ref = OL.linear_forward(x, w, b, relu, OL.round_bf16)
+            assert rel_err(to_host(y), ref) <= TOL_BF16, (relu, use_ws)
+            # tighter: never more than one bf16 step away from the oracle's rounding
+            assert np.max(np.abs(to_host(y) - ref) / np.maximum(np.abs(ref), 1e-2)) < 2 ** -6
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_linear_dgrad_bf16(M, N, K):
+    dz = _bf(gen.normal(SEED, "dz", (M, N)) * 0.01)
+    w = _bf(gen.uniform(SEED, "kw", (N, K), -0.1, 0.1))
+    ymask = _bf(np.maximum(gen.normal(SEED, "ym", (M, K)), 0.0))
+    s = torch.cuda.current_stream().cuda_stream
+    wsb = pd.pd_gemm_workspace_bytes(M, N, K)
+    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev())
+    dzd, wd, md = to_dev(dz, True), to_dev(w, True), to_dev(ymask, True)
+    for masked in (True, False):
+        for use_ws in (True, False):
+            dx = empty_act(M, K, True)
+            pd.pd_linear_dgrad_bf16(s, dzd.data_ptr(), wd.data_ptr(), md.data_ptr() if masked else 0, dx.data_ptr(),
+                                    M, N, K, ws.data_ptr() if use_ws else 0, wsb if use_ws else 0)
+            ref = OL.round_bf16(dz @ w)
+            if masked:
+                ref = ref * (ymask > 0)
+            assert rel_err(to_host(dx), ref) <= TOL_BF16, (masked, use_ws)
+
+
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_linear_wgrad_update_bf16(M, N, K):
+    dz = _bf(gen.normal(SEED, "dz", (M, N)) * 0.01)
+    x = _bf(gen.normal(SEED, "kx", (M, K)))
+    w = gen.uniform(SEED, "kw", (N, K), -0.1, 0.1).astype(np.float64)
+    b = (gen.normal(SEED, "kb", (N,)) * 0.1).astype(np.float64)
+    mw = (gen.normal(SEED, "mw", (N, K)) * 0.01).astype(np.float64)
+    mb = (gen.normal(SEED, "mb", (N,)) * 0.01).astype(np.float64)
+    lr, mu = 0.05, 0.9
+    s = torch.cuda.current_stream().cuda_stream
+    dzd, xd = to_dev(dz, True), to_dev(x, True)
+    wd, bd, mwd, mbd = to_dev(w, False), to_dev(b, False), to_dev(mw, False), to_dev(mb, False)
+    rw, rb = empty_act(N, K, True), empty_act(1, N, True)
+    pd.pd_linear_wgrad_update_bf16(s, dzd.data_ptr(), xd.data_ptr(), wd.data_ptr(), mwd.data_ptr(), rw.data_ptr(),
+                                   bd.data_ptr(), mbd.data_ptr(), rb.data_ptr(), M, N, K, lr, mu)
+    # oracle: the Linear backward, then the momentum-SGD step
+    _, dW, db = OL.linear_backward(x, w, None, dz, False, False, OL.round_bf16)
+    w32 = w.astype(np.float32).astype(np.float64); b32 = b.astype(np.float32).astype(np.float64)
+    m32 = mw.astype(np.float32).astype(np.float64); mb32 = mb.astype(np.float32).astype(np.float64)
+    m_ref = mu * m32 + dW; w_ref = w32 - lr * m_ref
+    mb_ref = mu * mb32 + db; b_ref = b32 - lr * mb_ref
+    assert rel_err(to_host(mwd), m_ref) <= TOL_F32
+    assert rel_err(to_host(wd), w_ref) <= TOL_F32
+    assert rel_err(to_host(mbd), mb_ref) <= TOL_F32
+    assert rel_err(to_host(bd), b_ref) <= TOL_F32
+    assert rel_err(to_host(rw), OL.round_bf16(w_ref)) <= TOL_BF16
+    assert rel_err(to_host(rb)[0], OL.round_bf16(b_ref)) <= TOL_BF16
+    # the ring copy is exactly the rounding of the fp32 master the kernel produced
+    assert torch.equal(rw, wd.to(torch.bfloat16))
+
+
+# ---------------------------------------------------------------------------------------------
+# stages and pipelines driven op by op through pd_forward / pd_backward / pd_update, in the
+# oracle's execution order (see parity_harness for what is compared and what is left out)
+# ---------------------------------------------------------------------------------------------
+def _make(stage_layers, B, M, seed, with_loss=True):
+    S = len(stage_layers)
+    n_in = stage_layers[0][0][1]
+    n_out = [l for l in stage_layers[-1] if l[0] == "linear"][-1][2]
+    params = []
+    for s, ly in enumerate(stage_layers):
+        p = gen.init_params(seed, f"s{s}", ly)
+        params.append(p + 0.01 * gen.normal(seed, f"pb{s}", p.shape))        # non-zero biases
+    xs = list(gen.normal(seed, "X", (M, B, n_in)))
+    labs = list(gen.labels(seed, "Y", (M, B), n_out)) if with_loss else None
+    dys = None if with_loss else list(gen.normal(seed, "DY", (M, B, n_out)) * 0.01)
+    return params, xs, labs, dys
+
+
+def _single_stage_case(layers, B, depth, M, precision, lr=0.01, mu=0.9, seed=SEED, with_loss=True, mode=None):
+    params, xs, labs, dys = _make([layers], B, M, seed, with_loss)
+    assert pd.pd_schedule_1f1b_depth(depth, M) == [tuple(o) for o in schedule_1f1b(1, 1, M, 0, depth_override=depth)]
+    if mode is None:   # bf16 trajectories separate by design (see parity_harness): compare op by op on synced weights
+        mode = "forced" if precision == pd.PD_BF16_F32ACC else "free"
+    return run_case([layers], params, xs, labs, noam=1, precision=precision, depth_override=depth,
+                    out_grads=dys, lr=lr, mu=mu, mode=mode)
+
+
+def test_stage_f32_small_shapes():
+    layers = [("linear", 20, 33, True), ("linear", 33, 7, False), ("softmax_xent", 7)]
+    _single_stage_case(layers, B=5, depth=3, M=8, precision=pd.PD_F32, lr=0.05)
+
+
+def test_stage_f32_middle_stage_with_relu_output():
+    layers = [("linear", 48, 40, True), ("linear", 40, 24, True)]
+    _single_stage_case(layers, B=9, depth=2, M=6, precision=pd.PD_F32, lr=0.05, with_loss=False)
+
+
+def test_stage_bf16_reduced_vgg_fc():
+    layers = [("linear", 1096, 520, True), ("linear", 520, 264, True), ("linear", 264, 104, False),
+              ("softmax_xent", 104)]
+    _single_stage_case(layers, B=64, depth=4, M=10, precision=pd.PD_BF16_F32ACC)
+
+
+def test_stage_bf16_free_running_short():
+    # both sides on their own trajectory: every forward and backward reads version 0, four updates follow
+    layers = [("linear", 1096, 520, True), ("linear", 520, 264, True), ("linear", 264, 104, False),
+              ("softmax_xent", 104)]
+    _single_stage_case(layers, B=64, depth=4, M=4, precision=pd.PD_BF16_F32ACC, mode="free")
+
+
+def test_stage_bf16_middle_stage_ragged_rows():
+    layers = [("linear", 136, 200, True), ("linear", 200, 72, True)]
+    _single_stage_case(layers, B=37, depth=3, M=7, precision=pd.PD_BF16_F32ACC, with_loss=False)
+
+
+def test_fewer_minibatches_than_depth():
+    layers = [("linear", 16, 8, False), ("softmax_xent", 8)]
+    _single_stage_case(layers, B=4, depth=4, M=2, precision=pd.PD_BF16_F32ACC)
+    _single_stage_case(layers, B=4, depth=4, M=1, precision=pd.PD_F32)
+
+
+@pytest.mark.timeout(1500)
+def test_config2_vgg_fc_full_size():
+    # the VGG16 classifier stage exactly as configured (25088-4096-4096-1000, minibatch 64, ring depth 4),
+    # in the launch configuration the benchmark times; five minibatches cover start-up, a forward on a
+    # fresh version, backward passes on stashed versions (B4 reads version 1 while the latest is 4), drain
+    print("config 2 full size: oracle + GPU, 5 minibatches", flush=True)
+    params, xs, labs, _ = _make([gen.config2_vgg_fc()], 64, 5, SEED + 1)
+    out = run_case([gen.config2_vgg_fc()], params, xs, labs, noam=1, precision=pd.PD_BF16_F32ACC, depth_override=4,
+                   mode="forced", verbose=True)
+    print("ambiguous ReLU decisions:", out["flips"], flush=True)
+
+
+def test_one_row_minibatch_and_depth_one():
+    layers = [("linear", 24, 16, True), ("linear", 16, 8, False), ("softmax_xent", 8)]
+    _single_stage_case(layers, B=1, depth=1, M=4, precision=pd.PD_BF16_F32ACC)
+    _single_stage_case(layers, B=1, depth=2, M=5, precision=pd.PD_F32)
+
+
+# ---------------------------------------------------------------------------------------------
+# the whole pipeline.  First op by op against the oracle (serialised), then the same run through
+# pd_pipeline_run with one stream per stage: the kernels are deterministic, so the concurrent run
+# must reproduce the serialised one bit for bit -- any missing inter-stream dependency would show.
+# ---------------------------------------------------------------------------------------------
+def _pipeline_case(stage_layers, B, noam, M, precision, lr=0.01, mu=0.9, seed=SEED):
+    bf16 = precision == pd.PD_BF16_F32ACC
+    S = len(stage_layers)
+    n_in = stage_layers[0][0][1]
+    params, xs, labs, _ = _make(stage_layers, B, M, seed)
+    if bf16:
+        run_case(stage_layers, params, xs, labs, noam=noam, precision=precision, lr=lr, mu=mu, mode="forced")
+        ref = run_case(stage_layers, params, xs, labs, noam=noam, precision=precision, lr=lr, mu=mu, compare=False)
+    else:
+        ref = run_case(stage_layers, params, xs, labs, noam=noam, precision=precision, lr=lr, mu=mu, mode="free")
+    streams = [torch.cuda.Stream() for _ in range(S)]
+    gs = [GpuStage(stage_layers[s], params[s], minibatch=B, precision=precision, stage_index=s, num_stages=S,
+                   noam=noam, lr=lr, momentum=mu, stream=streams[s]) for s in range(S)]
+    try:
+        xd = to_dev(np.stack(xs).reshape(M * B, n_in), bf16)
+        ld = labels_dev(np.stack(labs))
+        losses = torch.zeros(M, dtype=torch.float32, device=dev())
+        torch.cuda.synchronize()
+        pd.pd_pipeline_run([g.h for g in gs], M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(losses), ref["losses"])
+        for s in range(S):
+            assert pd.pd_stage_trace(gs[s].h) == pd.pd_schedule_1f1b(S, noam, M, s)
+            assert np.array_equal(pd.pd_stage_get_params(gs[s].h), ref["params"][s]), s
+            assert np.array_equal(pd.pd_stage_get_momentum(gs[s].h), ref["mom"][s]), s
+    finally:
+        for g in gs:
+            g.close()
+
+
+def test_config1_mlp_pipeline_f32_full():
+    # the 4-stage MLP exactly as configured: 256 wide, 10 classes, minibatch 32, NOAM 4, 64 minibatches
+    _pipeline_case(gen.config1_mlp(256, 10, 4), B=32, noam=4, M=64, precision=pd.PD_F32, seed=SEED + 0)
+
+
+def test_pipeline_bf16_mlp():
+    _pipeline_case(gen.config1_mlp(256, 16, 4), B=32, noam=4, M=24, precision=pd.PD_BF16_F32ACC)
+
+
+@pytest.mark.parametrize("S,noam,M", [(1, 1, 5), (2, 2, 7), (3, 1, 4), (4, 2, 9), (3, 3, 2)])
+def test_pipeline_shapes_f32(S, noam, M):
+    _pipeline_case(gen.config1_mlp(40, 6, S), B=6, noam=noam, M=M, precision=pd.PD_F32, lr=0.05)
+
+
+def test_pipeline_run_twice_continues_ids():
+    sl = gen.config1_mlp(32, 8, 3)
+    B, M = 4, 5
+    params = [gen.init_params(SEED, f"s{s}", ly) for s, ly in enumerate(sl)]
+    xs = gen.normal(SEED, "X", (2 * M, B, 32)); labs = gen.labels(SEED, "Y", (2 * M, B), 8)
+    gs = [GpuStage(sl[s], params[s], minibatch=B, precision=pd.PD_F32, stage_index=s, num_stages=3, noam=3,
+                   stream=torch.cuda.Stream()) for s in range(3)]
+    try:
+        xd = to_dev(xs.reshape(2 * M * B, 32), False); ld = labels_dev(labs)
+        losses = torch.zeros(2 * M, dtype=torch.float32, device=dev())
+        torch.cuda.synchronize()
+        hs = [g.h for g in gs]
+        pd.pd_pipeline_run(hs, M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+        pd.pd_pipeline_run(hs, M, xd[M * B:].data_ptr(), ld[M:].data_ptr(), losses[M:].data_ptr())
+        torch.cuda.synchronize()
+        # reference: two drained runs back to back (each run starts with an empty pipeline)
+        o1, l1 = run_pipeline(sl, params, [x.astype(np.float64) for x in xs[:M]], list(labs[:M]), 3)
+        o2, l2 = run_pipeline(sl, [o.master for o in o1], [x.astype(np.float64) for x in xs[M:]], list(labs[M:]), 3)
+        # (momentum carries over on the GPU, so only quantities that depend on the weights alone are compared)
+        lg = to_host(losses)
+        for i in range(M):
+            assert abs(lg[i] - l1[i]) <= TOL_F32 * abs(l1[i])
+        assert abs(lg[M] - l2[0]) <= TOL_F32 * abs(l2[0])   # first loss of run 2 depends on weights only
+        assert [pd.pd_stage_version(h) for h in hs] == [2 * M] * 3
+    finally:
+        for g in gs:
+            g.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# protocol errors come back as status codes and leave the stage usable
+# ---------------------------------------------------------------------------------------------
+def test_protocol_errors():
+    layers = [("linear", 16, 8, False), ("softmax_xent", 8)]
+    params = gen.init_params(SEED, "p", layers)
+    g = GpuStage(layers, params, minibatch=4, precision=pd.PD_F32, in_flight_override=2)
+    try:
+        x = to_dev(gen.normal(SEED, "x", (4, 16)), False); lab = labels_dev(gen.labels(SEED, "y", (4,), 8))
+        dx = empty_act(4, 16, False)
+
+        def status(fn, *a):
+            with pytest.raises(pd.PdError) as e:
+                fn(*a)
+            return e.value.status
+
+        assert status(pd.pd_update, g.h) == pd.PD_ESTATE                      # nothing pending
+        assert status(pd.pd_backward, g.h, 0, 0, dx.data_ptr()) == pd.PD_ESTATE  # nothing in flight
+        assert status(pd.pd_forward, g.h, 0, x.data_ptr(), 0, 0, 0) == pd.PD_EINVAL  # labels missing
+        pd.pd_forward(g.h, 0, x.data_ptr(), lab.data_ptr())
+        assert status(pd.pd_forward, g.h, 2, x.data_ptr(), lab.data_ptr()) == pd.PD_ESTATE  # ids consecutive
+        pd.pd_forward(g.h, 1, x.data_ptr(), lab.data_ptr())
+        assert status(pd.pd_forward, g.h, 2, x.data_ptr(), lab.data_ptr()) == pd.PD_ESTATE  # depth reached
+        assert status(pd.pd_backward, g.h, 1, 0, dx.data_ptr()) == pd.PD_ESTATE  # not the oldest
+        assert status(pd.pd_backward, g.h, 0, x.data_ptr(), dx.data_ptr()) == pd.PD_EINVAL  # dy on a loss stage
+        pd.pd_backward(g.h, 0, 0, dx.data_ptr())
+        assert status(pd.pd_forward, g.h, 2, x.data_ptr(), lab.data_ptr()) == pd.PD_ESTATE  # update first
+        assert status(pd.pd_backward, g.h, 1, 0, dx.data_ptr()) == pd.PD_ESTATE
+        pd.pd_update(g.h)
+        assert status(pd.pd_update, g.h) == pd.PD_ESTATE
+        assert status(pd.pd_stage_get_params, g.h, 5) == pd.PD_ESTATE           # version not in the ring
+        assert pd.pd_stage_version(g.h) == 1 and pd.pd_stage_version(g.h, 1) == 0
+        assert status(pd.pd_stage_version, g.h, 0) == pd.PD_ESTATE
+        pd.pd_forward(g.h, 2, x.data_ptr(), lab.data_ptr())
+        assert pd.pd_stage_version(g.h, 2) == 1
+        # arena too small
+        cfg = pd.make_config(layers, minibatch=4, precision=pd.PD_F32)
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_stage_create(cfg, g.arena.data_ptr() // 256 * 256 + 256, 1024)
+        assert e.value.status == pd.PD_ENOMEM
+        torch.cuda.synchronize()
+    finally:
+        g.close()

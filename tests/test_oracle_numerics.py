@@ -172,7 +172,7 @@ def test_event_driven_equals_staleness_equation(S, NOAM):
     params = _params(sl)
     M = 14
     xs, ys = _data(M, 6, 12, 5)
-    depths = [in_flight_depth(S, NOAM, M, s) for s in range(S)]
+    depths = [in_flight_depth(S, NOAM, s) for s in range(S)]
     stages, losses = run_pipeline(sl, params, xs, ys, NOAM, lr=0.05, momentum=0.9)
     # (a) torch autograd, no schedule, composite weights from history
     ref_p, ref_l = _torch_flat_loop(sl, params, xs, ys, depths, 0.05, 0.9)
@@ -193,7 +193,7 @@ def test_bf16_mode_flat_loop_bit_identical_and_close_to_f32():
     params = _params(sl)
     M = 10
     xs, ys = _data(M, 6, 12, 5)
-    depths = [in_flight_depth(4, 4, M, s) for s in range(4)]
+    depths = [in_flight_depth(4, 4, s) for s in range(4)]
     st_b, loss_b = run_pipeline(sl, params, xs, ys, 4, mode="bf16")
     hist, l2 = flat_loop(sl, params, xs, ys, depths, mode="bf16")
     assert l2 == loss_b
