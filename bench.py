@@ -24,6 +24,9 @@ METRIC = "samples/sec per 1F1B stage step (bf16) + MFMA util % of MI355X peak"
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK = 2.5e15
 UPDATE_BYTES_PER_PARAM = 18  # read fp32 master + momentum, write both, write the bf16 ring copy
+# HBM bytes per launch of the dominant kernel at the default workload, from the rocprofv3 counter runs
+# summarised in profiles/wgrad_update_vgg16fc_mb64.txt (FETCH_SIZE x 1.986 + WRITE_SIZE x 1.000)
+MEASURED_TRAFFIC_BYTES = 2.431e9
 
 
 def cpu_baseline(layers, params, xs, labs, depth, budget_s=20.0, max_steps=3):
@@ -133,7 +136,7 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / K
     upd_ms = [a.elapsed_time(b) for a, b in evs]
     upd_ms_avg = float(np.mean(upd_ms))
-    n_launch = sum(1 for L in layers if L[0] == "linear")
+    n_launch = 1  # all Linear layers of the stage are updated by one launch
     final_loss = float(loss.item())
 
     flops = 6.0 * B * sum(L[1] * L[2] for L in layers if L[0] == "linear")
@@ -153,7 +156,8 @@ def main():
         "step_hbm_fraction": (22.0 * P / (ms_per_step * 1e-3) / 1e9) / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "kernel": "wgrad_update_kernel (dW = dZ^T X fused with momentum-SGD into the ring)",
                      "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "launches_per_step": n_launch,
+                     "traffic": (MEASURED_TRAFFIC_BYTES if (not args.small and B == 64) else None),
+                     "traffic_source": "profiles/wgrad_update_vgg16fc_mb64.txt", "launches_per_step": n_launch,
                      "avg_launch_ms": upd_ms_avg / n_launch, "bytes_per_launch_avg": UPDATE_BYTES_PER_PARAM * P / n_launch},
         "final_loss": final_loss,
     }

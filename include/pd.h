@@ -217,7 +217,8 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
  *   dgrad : dx[M][K] = (dz[M][N] * w[N][K]) .* (mask[M][K] > 0 if mask != NULL)
  *   wgrad_update: g = dz[M][N]^T x[M][K] (+ column sums for the bias); m <- mu*m+g;
  *           master <- master - lr*m; ring_out <- bf16(master)
- * workspace_dev: split-K scratch of at least pd_gemm_workspace_bytes(M,N,K) bytes (fwd, dgrad).
+ * workspace_dev: split-K scratch of at least pd_gemm_workspace_bytes(M,N,K) bytes (fwd, dgrad); NULL
+ * disables split-K.
  * stream: hipStream_t.  All pointers device. */
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
 int pd_linear_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, int32_t M, int32_t N,

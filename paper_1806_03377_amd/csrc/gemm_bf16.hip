@@ -12,6 +12,7 @@
 //   D (16 floats): column (l & 31), rows 8*(r / 4) + 4*(l >> 5) + (r % 4) for r = 0..15
 // A and B always take their 8 reduction elements from the same positions, so any fixed permutation
 // of the reduction index inside an instruction cancels out.
+#include "bf16_util.h"
 #include "pd_kernels.h"
 
 namespace pd {
@@ -22,30 +23,24 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ bf16x8 frag(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-__device__ __forceinline__ uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // keep NaN a NaN
-  u += 0x7fffu + ((u >> 16) & 1u);                                             // nearest, ties to even
-  return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ bool bf_positive(uint16_t h) { return (h & 0x8000u) == 0 && (h & 0x7fffu) != 0; }
 
 constexpr int kThreads = 256;
 constexpr int BM = 64;    // rows of the output tile (minibatch direction)
-constexpr int BN = 128;   // columns of the output tile
-constexpr int BK = 64;    // reduction elements per LDS stage
-constexpr int LDP = BK + 8;  // padded LDS row (bf16 elements) for reduction-contiguous tiles
 
 __device__ __forceinline__ uint4 ldg16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
 
-// XOR swizzle of the 16-byte groups of a 128-byte LDS row holding 64 reduction elements of one output
-// row/column.  Keeps both the transposing 4-byte writes and the 16-byte fragment reads spread over banks.
-__device__ __forceinline__ int swz(int row, int group) { return group ^ (row & 7) ^ ((row >> 3) & 7); }
+// XOR swizzle of the 16-byte groups of an LDS row that holds 8*G reduction elements of one output row/column
+// (G groups).  Spreads both the transposing 4-byte writes (lanes differ in their column chunk and reduction
+// pair) and the 16-byte fragment reads (lanes differ in their row) over all banks.
+template <int G>
+__device__ __forceinline__ int swz(int row, int group) {
+  return group ^ ((row ^ (row >> 3)) & ((G < 16 ? G : 16) - 1));
+}
 
 // Writes an 8-column x 2-row block (two 16-byte global chunks from consecutive reduction rows `pair`*2,
 // `pair`*2+1) transposed into a swizzled tile: tile row = column index, word `pair` of that row.
+template <int G>
 __device__ __forceinline__ void store_transposed_pair(uint32_t* tile, int col0, int pair, uint4 r0, uint4 r1) {
   const uint32_t a[4] = {r0.x, r0.y, r0.z, r0.w};
   const uint32_t b[4] = {r1.x, r1.y, r1.z, r1.w};
@@ -54,223 +49,205 @@ __device__ __forceinline__ void store_transposed_pair(uint32_t* tile, int col0, 
     const uint32_t lo = (a[q] & 0xffffu) | (b[q] << 16);
     const uint32_t hi = (a[q] >> 16) | (b[q] & 0xffff0000u);
     const int row_lo = col0 + 2 * q, row_hi = row_lo + 1;
-    tile[row_lo * 32 + swz(row_lo, pair >> 2) * 4 + (pair & 3)] = lo;
-    tile[row_hi * 32 + swz(row_hi, pair >> 2) * 4 + (pair & 3)] = hi;
+    tile[row_lo * (4 * G) + swz<G>(row_lo, pair >> 2) * 4 + (pair & 3)] = lo;
+    tile[row_hi * (4 * G) + swz<G>(row_hi, pair >> 2) * 4 + (pair & 3)] = hi;
   }
 }
+template <int G>
 __device__ __forceinline__ uint4 load_swizzled_frag(const uint32_t* tile, int row, int group) {
-  return *reinterpret_cast<const uint4*>(tile + row * 32 + swz(row, group) * 4);
+  return *reinterpret_cast<const uint4*>(tile + row * (4 * G) + swz<G>(row, group) * 4);
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward: partial or final y tile.  grid = (ceil(N/BN), ceil(M/BM), splits)
+// Skinny GEMM for forward and dgrad:  out[M][C] = A[M][R] * B, fp32 accumulate, then the epilogue.
+//   BT = false (forward): B is w[C][R], reduction contiguous:   out = x w^T (+ bias, ReLU)
+//   BT = true  (dgrad):   B is w[R][C], reduction rows:         out = dz w  (.* ReLU mask); every 2x8 block
+//                         of w is transposed on its way into LDS
+// grid = (ceil(C/BN), ceil(M/BM), splits).  Each workgroup reduces a contiguous range of BK-wide stages.
+// The weight matrix is read once from HBM, so what matters is bytes in flight: global loads run PD stages
+// ahead of the MFMAs in registers, LDS is double-buffered.
+// With splits > 1 the partial tiles go to `ws` and splitk_epilogue_kernel finishes the job.
 // ------------------------------------------------------------------------------------------------
-template <bool DIRECT>
-__global__ __launch_bounds__(kThreads) void gemm_nt_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ W,
-                                                           const bf16_t* __restrict__ bias, bf16_t* __restrict__ Y,
-                                                           float* __restrict__ Yf, float* __restrict__ ws, int M,
-                                                           int N, int K, int relu, int splits) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDP];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDP];
-  const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int n0 = blockIdx.x * BN, m0 = blockIdx.y * BM, z = blockIdx.z;
-  const int T = (K + BK - 1) / BK;
-  const int kt0 = (int)((long long)z * T / splits), kt1 = (int)((long long)(z + 1) * T / splits);
+struct GemmEpilogue {
+  const bf16_t* bias;  // forward: [C] or null
+  const bf16_t* mask;  // dgrad: [M][C], value kept where mask > 0; or null
+  int relu;            // forward
+  bf16_t* out;         // [M][C] bf16, used when out_f is null
+  float* out_f;        // [M][C] fp32 (logits for the loss), or null
+};
 
-  uint4 ra[2], rb[4];
-  auto gload = [&](int kt) {
-    const int k0 = kt * BK;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = t + kThreads * i, row = c >> 3, k = k0 + (c & 7) * 8, m = m0 + row;
-      ra[i] = (m < M && k < K) ? ldg16(X + (size_t)m * K + k) : zero16();
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = t + kThreads * i, row = c >> 3, k = k0 + (c & 7) * 8, n = n0 + row;
-      rb[i] = (n < N && k < K) ? ldg16(W + (size_t)n * K + k) : zero16();
-    }
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = t + kThreads * i;
-      *reinterpret_cast<uint4*>(&As[buf][(c >> 3) * LDP + (c & 7) * 8]) = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = t + kThreads * i;
-      *reinterpret_cast<uint4*>(&Bs[buf][(c >> 3) * LDP + (c & 7) * 8]) = rb[i];
-    }
-  };
-
-  f32x16 acc0 = {0}, acc1 = {0};
-  if (kt0 < kt1) {
-    gload(kt0);
-    sstore(0);
-    __syncthreads();
-    for (int kt = kt0; kt < kt1; ++kt) {
-      const int cur = (kt - kt0) & 1;
-      if (kt + 1 < kt1) gload(kt + 1);
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        const int kk = ks * 16 + (l >> 5) * 8;
-        const uint4 b = *reinterpret_cast<const uint4*>(&Bs[cur][(32 * w + (l & 31)) * LDP + kk]);
-        const uint4 a0 = *reinterpret_cast<const uint4*>(&As[cur][(l & 31) * LDP + kk]);
-        const uint4 a1 = *reinterpret_cast<const uint4*>(&As[cur][(32 + (l & 31)) * LDP + kk]);
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a0), frag(b), acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a1), frag(b), acc1, 0, 0, 0);
-      }
-      if (kt + 1 < kt1) sstore(cur ^ 1);
-      __syncthreads();
-    }
-  }
-
-  const int n = n0 + 32 * w + (l & 31);
-  if (n >= N) return;
-  const float bv = (DIRECT && bias) ? bf2f(bias[n]) : 0.f;
-#pragma unroll
-  for (int blk = 0; blk < 2; ++blk) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + 32 * blk + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-      if (m >= M) continue;
-      const float v = blk ? acc1[r] : acc0[r];
-      if (DIRECT) {
-        float o = v + bv;
-        if (relu) o = fmaxf(o, 0.f);
-        if (Yf) Yf[(size_t)m * N + n] = o;
-        else Y[(size_t)m * N + n] = f2bf(o);
-      } else {
-        ws[((size_t)z * M + m) * N + n] = v;
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// dgrad: dx tile = dz[M][N] * w[N][Kd], reduction over N.  grid = (ceil(Kd/BN), ceil(M/BM), splits)
-// w rows are reduction rows here, so each 2x8 block of w is transposed on its way into LDS.
-// ------------------------------------------------------------------------------------------------
-template <bool DIRECT>
-__global__ __launch_bounds__(kThreads) void gemm_nn_kernel(const bf16_t* __restrict__ dZ, const bf16_t* __restrict__ W,
-                                                           const bf16_t* __restrict__ mask, bf16_t* __restrict__ dX,
-                                                           float* __restrict__ ws, int M, int N, int Kd, int splits) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDP];
-  __shared__ __attribute__((aligned(16))) uint32_t Bt[2][BN * 32];
-  const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int c0 = blockIdx.x * BN, m0 = blockIdx.y * BM, z = blockIdx.z;
-  const int T = (N + BK - 1) / BK;
-  const int rt0 = (int)((long long)z * T / splits), rt1 = (int)((long long)(z + 1) * T / splits);
-
-  uint4 ra[2], rb0[2], rb1[2];
-  auto gload = [&](int rt) {
-    const int r0 = rt * BK;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = t + kThreads * i, row = c >> 3, n = r0 + (c & 7) * 8, m = m0 + row;
-      ra[i] = (m < M && n < N) ? ldg16(dZ + (size_t)m * N + n) : zero16();
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int b = t + kThreads * i, kdc = b & 15, pair = b >> 4;
-      const int n = r0 + 2 * pair, kd = c0 + 8 * kdc;
-      rb0[i] = (n < N && kd < Kd) ? ldg16(W + (size_t)n * Kd + kd) : zero16();
-      rb1[i] = (n + 1 < N && kd < Kd) ? ldg16(W + (size_t)(n + 1) * Kd + kd) : zero16();
-    }
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = t + kThreads * i;
-      *reinterpret_cast<uint4*>(&As[buf][(c >> 3) * LDP + (c & 7) * 8]) = ra[i];
-    }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int b = t + kThreads * i, kdc = b & 15, pair = b >> 4;
-      store_transposed_pair(Bt[buf], 8 * kdc, pair, rb0[i], rb1[i]);
-    }
-  };
-
-  f32x16 acc0 = {0}, acc1 = {0};
-  if (rt0 < rt1) {
-    gload(rt0);
-    sstore(0);
-    __syncthreads();
-    for (int rt = rt0; rt < rt1; ++rt) {
-      const int cur = (rt - rt0) & 1;
-      if (rt + 1 < rt1) gload(rt + 1);
-#pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        const int kk = ks * 16 + (l >> 5) * 8;
-        const uint4 b = load_swizzled_frag(Bt[cur], 32 * w + (l & 31), 2 * ks + (l >> 5));
-        const uint4 a0 = *reinterpret_cast<const uint4*>(&As[cur][(l & 31) * LDP + kk]);
-        const uint4 a1 = *reinterpret_cast<const uint4*>(&As[cur][(32 + (l & 31)) * LDP + kk]);
-        acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a0), frag(b), acc0, 0, 0, 0);
-        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a1), frag(b), acc1, 0, 0, 0);
-      }
-      if (rt + 1 < rt1) sstore(cur ^ 1);
-      __syncthreads();
-    }
-  }
-
-  const int kd = c0 + 32 * w + (l & 31);
-  if (kd >= Kd) return;
-#pragma unroll
-  for (int blk = 0; blk < 2; ++blk) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + 32 * blk + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-      if (m >= M) continue;
-      const float v = blk ? acc1[r] : acc0[r];
-      if (DIRECT) {
-        uint16_t o = f2bf(v);
-        if (mask && !bf_positive(mask[(size_t)m * Kd + kd])) o = 0;
-        dX[(size_t)m * Kd + kd] = o;
-      } else {
-        ws[((size_t)z * M + m) * Kd + kd] = v;
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
-// split-K epilogue: sums the partial tiles in split order (deterministic), then bias/ReLU or ReLU-mask,
-// rounds to bf16.  One thread per 4 consecutive columns.
-// ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __restrict__ ws, int splits, int M, int N,
-                                                              const bf16_t* __restrict__ bias,
-                                                              const bf16_t* __restrict__ mask, int relu,
-                                                              bf16_t* __restrict__ out, float* __restrict__ out_f) {
-  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t total4 = (size_t)M * N / 4;
-  if (idx >= total4) return;
-  const size_t e = idx * 4;
-  const int n = (int)(e % N);
-  float4 s = *reinterpret_cast<const float4*>(ws + e);
-  for (int z = 1; z < splits; ++z) {
-    const float4 p = *reinterpret_cast<const float4*>(ws + (size_t)z * M * N + e);
-    s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
-  }
-  float v[4] = {s.x, s.y, s.z, s.w};
-  uint16_t o[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    float x = v[j];
-    if (bias) x += bf2f(bias[n + j]);
-    if (relu) x = fmaxf(x, 0.f);
-    v[j] = x;
-    o[j] = f2bf(x);
-    if (mask && !bf_positive(mask[e + j])) o[j] = 0;
-  }
-  if (out_f) {  // fp32 result (logits for the loss): no rounding, no mask
-    *reinterpret_cast<float4*>(out_f + e) = make_float4(v[0], v[1], v[2], v[3]);
+__device__ __forceinline__ void gemm_store(const GemmEpilogue& ep, float v, int m, int c, int C) {
+  const size_t off = (size_t)m * C + c;
+  if (ep.bias) v += bf2f(ep.bias[c]);
+  if (ep.relu) v = fmaxf(v, 0.f);
+  if (ep.out_f) {
+    ep.out_f[off] = v;
     return;
   }
-  uint2 pk;
-  pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
-  pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
-  *reinterpret_cast<uint2*>(out + e) = pk;
+  uint16_t o = f2bf(v);
+  if (ep.mask && !bf_positive(ep.mask[off])) o = 0;
+  ep.out[off] = o;
+}
+
+// Tile shape: BM_ x BN_ outputs, BK_ reduction elements per stage; PD stages of global loads in flight in
+// registers; NBUF LDS buffers (1: store / barrier / compute; 2: the store of the next stage overlaps compute).
+// BK_ sets how many contiguous bytes of each weight row a workgroup touches per visit (2*BK_): the weight
+// stream is the HBM traffic, and short per-row visits scattered over many rows waste DRAM page locality.
+template <bool BT, int BN_, int BK_, int PD, int NBUF>
+__global__ __launch_bounds__(kThreads) void gemm_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm,
+                                                        GemmEpilogue ep, float* __restrict__ ws, int M, int C, int R,
+                                                        int splits) {
+  constexpr int LDA = BK_ + 8;             // padded row (bf16) of a reduction-contiguous tile
+  constexpr int G = BK_ / 8;               // 16-byte groups per row
+  constexpr int ACH = BM * G / kThreads;   // 16-byte chunks of A per thread and stage
+  constexpr int BCH = BN_ * G / kThreads;  // ... of B
+  constexpr int WN = BN_ / 32;             // waves along the output columns
+  constexpr int WM = 4 / WN;               // waves along the rows
+  constexpr int MB = (BM / 32) / WM;       // 32-row blocks per wave
+  constexpr int kAElems = BM * LDA;
+  constexpr int kBWords = BN_ * LDA / 2;   // covers both B layouts (plain: BN_*LDA bf16; transposed: BN_*BK_/2 words)
+  static_assert(ACH >= 1 && BCH >= 2 && (BCH % 2) == 0 && MB >= 1, "tile shape");
+  __shared__ __attribute__((aligned(16))) bf16_t As[NBUF][kAElems];
+  __shared__ __attribute__((aligned(16))) uint32_t Bs[NBUF][kBWords];
+  const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  const int wn = w % WN, wm = w / WN;
+  const int c0 = blockIdx.x * BN_, m0 = blockIdx.y * BM, z = blockIdx.z;
+  const int T = (R + BK_ - 1) / BK_;
+  const int rt0 = (int)((long long)z * T / splits), rt1 = (int)((long long)(z + 1) * T / splits);
+
+  struct Regs {
+    uint4 a[ACH], b[BCH];
+  };
+  auto gload = [&](Regs& r, int rt) {
+    const int r0 = rt * BK_;
+    const bool live = rt < rt1;
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) {
+      const int c = t + kThreads * i, row = c / G, rr = r0 + (c % G) * 8, m = m0 + row;
+      r.a[i] = (live && m < M && rr < R) ? ldg16(A + (size_t)m * R + rr) : zero16();
+    }
+    if (!BT) {
+#pragma unroll
+      for (int i = 0; i < BCH; ++i) {
+        const int c = t + kThreads * i, row = c / G, rr = r0 + (c % G) * 8, cc = c0 + row;
+        r.b[i] = (live && cc < C && rr < R) ? ldg16(Bm + (size_t)cc * R + rr) : zero16();
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < BCH / 2; ++i) {
+        const int b = t + kThreads * i, cch = b % (BN_ / 8), pair = b / (BN_ / 8);
+        const int rr = r0 + 2 * pair, cc = c0 + 8 * cch;
+        r.b[2 * i] = (live && rr < R && cc < C) ? ldg16(Bm + (size_t)rr * C + cc) : zero16();
+        r.b[2 * i + 1] = (live && rr + 1 < R && cc < C) ? ldg16(Bm + (size_t)(rr + 1) * C + cc) : zero16();
+      }
+    }
+  };
+  auto sstore = [&](int buf, const Regs& r) {
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) {
+      const int c = t + kThreads * i;
+      *reinterpret_cast<uint4*>(&As[buf][(c / G) * LDA + (c % G) * 8]) = r.a[i];
+    }
+    if (!BT) {
+      bf16_t* bs = reinterpret_cast<bf16_t*>(Bs[buf]);
+#pragma unroll
+      for (int i = 0; i < BCH; ++i) {
+        const int c = t + kThreads * i;
+        *reinterpret_cast<uint4*>(&bs[(c / G) * LDA + (c % G) * 8]) = r.b[i];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < BCH / 2; ++i) {
+        const int b = t + kThreads * i, cch = b % (BN_ / 8), pair = b / (BN_ / 8);
+        store_transposed_pair<G>(Bs[buf], 8 * cch, pair, r.b[2 * i], r.b[2 * i + 1]);
+      }
+    }
+  };
+  f32x16 acc[MB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) acc[i] = f32x16{0};
+  auto compute = [&](int buf) {
+    const bf16_t* bs = reinterpret_cast<const bf16_t*>(Bs[buf]);
+    const int brow = 32 * wn + (l & 31);
+#pragma unroll
+    for (int ks = 0; ks < BK_ / 16; ++ks) {
+      const int kk = ks * 16 + (l >> 5) * 8;
+      const uint4 b = BT ? load_swizzled_frag<G>(Bs[buf], brow, 2 * ks + (l >> 5))
+                         : *reinterpret_cast<const uint4*>(&bs[brow * LDA + kk]);
+#pragma unroll
+      for (int i = 0; i < MB; ++i) {
+        const uint4 a = *reinterpret_cast<const uint4*>(&As[buf][(32 * (MB * wm + i) + (l & 31)) * LDA + kk]);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a), frag(b), acc[i], 0, 0, 0);
+      }
+    }
+  };
+
+  if (rt0 < rt1) {
+    Regs Rg[PD];
+#pragma unroll
+    for (int p = 0; p < PD; ++p) gload(Rg[p], rt0 + p);
+    if (NBUF == 2) {
+      sstore(0, Rg[0]);
+      gload(Rg[0], rt0 + PD);
+      __syncthreads();
+    }
+    for (int base = rt0; base < rt1; base += PD) {
+#pragma unroll
+      for (int j = 0; j < PD; ++j) {
+        const int rt = base + j;
+        if (rt >= rt1) break;
+        if (NBUF == 2) {
+          const int cur = (rt - rt0) & 1;
+          compute(cur);
+          if (rt + 1 < rt1) {  // stage rt+1 sits in register slot (j+1) % PD; refill that slot PD stages ahead
+            sstore(cur ^ 1, Rg[(j + 1) % PD]);
+            gload(Rg[(j + 1) % PD], rt + 1 + PD);
+          }
+          __syncthreads();
+        } else {
+          sstore(0, Rg[j]);             // stage rt sits in register slot j
+          gload(Rg[j], rt + PD);
+          __syncthreads();
+          compute(0);
+          __syncthreads();
+        }
+      }
+    }
+  }
+
+  const int c = c0 + 32 * wn + (l & 31);
+  if (c >= C) return;
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + 32 * (MB * wm + i) + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+      if (m >= M) continue;
+      if (splits == 1) gemm_store(ep, acc[i][r], m, c, C);
+      else ws[((size_t)z * M + m) * C + c] = acc[i][r];
+    }
+}
+
+// Sums the split-K partial tiles in split order (a fixed order: deterministic) and applies the epilogue.
+// One thread per 4 consecutive columns.  Runs as its own launch: on this multi-die part a device-scope
+// release/acquire inside the GEMM (to let the last workgroup of a tile reduce) costs an L2 write-back per
+// workgroup, far more than a second small kernel.
+__global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __restrict__ ws, int splits, int M, int C,
+                                                              GemmEpilogue ep) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total4 = (size_t)M * C / 4;
+  if (idx >= total4) return;
+  const size_t e = idx * 4;
+  const int m = (int)(e / C), c = (int)(e % C);
+  float4 s = *reinterpret_cast<const float4*>(ws + e);
+  for (int z = 1; z < splits; ++z) {
+    const float4 p = *reinterpret_cast<const float4*>(ws + (size_t)z * M * C + e);
+    s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+  }
+  gemm_store(ep, s.x, m, c, C);
+  gemm_store(ep, s.y, m, c + 1, C);
+  gemm_store(ep, s.z, m, c + 2, C);
+  gemm_store(ep, s.w, m, c + 3, C);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -283,84 +260,125 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __res
 //            is a full-width contiguous row segment; m <- mu*m + g, w <- w - lr*m, ring <- bf16(w)
 // grid.x = ceil(K/TK) * ceil(N/TN), k-tiles fastest.
 // ------------------------------------------------------------------------------------------------
-constexpr int TN = 64, TK = 128, MC = 64, GLD = TK + 4;
-constexpr int kSlots = TN * TK / 4 / kThreads;  // float4 elements per thread in phase 2 (8)
+constexpr int MC = 64;  // minibatch rows per reduction chunk
 
-__global__ __launch_bounds__(kThreads) void wgrad_update_kernel(
-    const bf16_t* __restrict__ dZ, const bf16_t* __restrict__ X, float* __restrict__ master, float* __restrict__ mom,
-    bf16_t* __restrict__ ring, float* __restrict__ master_b, float* __restrict__ mom_b, bf16_t* __restrict__ ring_b,
-    int M, int N, int K, float lr, float mu) {
-  __shared__ __attribute__((aligned(16))) uint32_t smem[TN * GLD];  // 33 KB; phase 1 uses the first 24 KB
+template <int TN, int TK, bool NFAST, bool PREFETCH>
+__global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch) {
+  // which layer this workgroup belongs to (all layers of a stage are updated by one launch)
+  int li = 0;
+  while (li + 1 < batch.count && blockIdx.x >= batch.layer[li].tile_end) ++li;
+  const WgradLayer& L = batch.layer[li];
+  const unsigned tile_id = blockIdx.x - (li ? batch.layer[li - 1].tile_end : 0u);
+  const bf16_t* __restrict__ dZ = L.dz;
+  const bf16_t* __restrict__ X = L.x;
+  float* __restrict__ master = L.master_w;
+  float* __restrict__ mom = L.mom_w;
+  bf16_t* __restrict__ ring = L.ring_w;
+  float* __restrict__ master_b = L.master_b;
+  float* __restrict__ mom_b = L.mom_b;
+  bf16_t* __restrict__ ring_b = L.ring_b;
+  const int M = batch.M, N = L.N, K = L.K;
+  const float lr = batch.lr, mu = batch.mu;
+  constexpr int GLD = TK + 4;
+  constexpr int kSlots = TN * TK / 4 / kThreads;  // float4 elements per thread in phase 2
+  constexpr int NB = TN / 32;                     // 32-row MFMA blocks per wave (waves split the k columns)
+  constexpr int KW = TK / 32;                     // 32-column blocks in the tile; waves take KW/4 each
+  static_assert(TK % 128 == 0 && TN % 32 == 0, "tile shape");
+  constexpr int KB = KW / 4;
+  __shared__ __attribute__((aligned(16))) uint32_t smem[(TN * GLD > (TN + TK) * 32) ? TN * GLD : (TN + TK) * 32];
   uint32_t* dZt = smem;             // [TN][32 words]  rows = n, 64 minibatch rows each
   uint32_t* Xt = smem + TN * 32;    // [TK][32 words]  rows = k
   float* G = reinterpret_cast<float*>(smem);
 
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int ktiles = (K + TK - 1) / TK;
-  const int kt = blockIdx.x % ktiles, nt = blockIdx.x / ktiles;
+  const int ktiles = (K + TK - 1) / TK, ntiles = (N + TN - 1) / TN;
+  const int kt = NFAST ? (int)(tile_id / ntiles) : (int)(tile_id % ktiles);
+  const int nt = NFAST ? (int)(tile_id % ntiles) : (int)(tile_id / ktiles);
   const int n0 = nt * TN, k0 = kt * TK;
 
   // phase 0: prefetch master and momentum of this thread's phase-2 elements
   float4 pw[kSlots], pm[kSlots];
+  if (PREFETCH) {
 #pragma unroll
-  for (int q = 0; q < kSlots; ++q) {
-    const int f = t + kThreads * q, row = f >> 5, k = k0 + (f & 31) * 4, n = n0 + row;
-    if (n < N && k < K) {
-      const size_t off = (size_t)n * K + k;
-      pw[q] = *reinterpret_cast<const float4*>(master + off);
-      pm[q] = *reinterpret_cast<const float4*>(mom + off);
-    } else {
-      pw[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-      pm[q] = pw[q];
+    for (int q = 0; q < kSlots; ++q) {
+      const int f = t + kThreads * q, row = f / (TK / 4), k = k0 + (f % (TK / 4)) * 4, n = n0 + row;
+      if (n < N && k < K) {
+        const size_t off = (size_t)n * K + k;
+        pw[q] = *reinterpret_cast<const float4*>(master + off);
+        pm[q] = *reinterpret_cast<const float4*>(mom + off);
+      } else {
+        pw[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        pm[q] = pw[q];
+      }
     }
   }
 
   // phase 1
-  f32x16 acc0 = {0}, acc1 = {0};
+  f32x16 acc[NB][KB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int j = 0; j < KB; ++j) acc[i][j] = f32x16{0};
   for (int mc = 0; mc < M; mc += MC) {
     {
-      const int nc = t & 7, pair = t >> 3;
-      const int m = mc + 2 * pair, n = n0 + 8 * nc;
-      const uint4 r0 = (m < M && n < N) ? ldg16(dZ + (size_t)m * N + n) : zero16();
-      const uint4 r1 = (m + 1 < M && n < N) ? ldg16(dZ + (size_t)(m + 1) * N + n) : zero16();
-      uint4 x0[2], x1[2];
+      constexpr int ZB = TN / 8 * 32 / kThreads > 0 ? TN / 8 * 32 / kThreads : 1;  // dz blocks per thread
+      constexpr int XB = TK / 8 * 32 / kThreads;                                    // x blocks per thread
+      uint4 z0[ZB], z1[ZB], x0[XB], x1[XB];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int b = t + kThreads * i, kc = b & 15, p2 = b >> 4;
+      for (int i = 0; i < ZB; ++i) {
+        const int b = t + kThreads * i, nc = b % (TN / 8), pair = b / (TN / 8);
+        const int m = mc + 2 * pair, n = n0 + 8 * nc;
+        const bool in = pair < 32;
+        z0[i] = (in && m < M && n < N) ? ldg16(dZ + (size_t)m * N + n) : zero16();
+        z1[i] = (in && m + 1 < M && n < N) ? ldg16(dZ + (size_t)(m + 1) * N + n) : zero16();
+      }
+#pragma unroll
+      for (int i = 0; i < XB; ++i) {
+        const int b = t + kThreads * i, kc = b % (TK / 8), p2 = b / (TK / 8);
         const int mm = mc + 2 * p2, k = k0 + 8 * kc;
         x0[i] = (mm < M && k < K) ? ldg16(X + (size_t)mm * K + k) : zero16();
         x1[i] = (mm + 1 < M && k < K) ? ldg16(X + (size_t)(mm + 1) * K + k) : zero16();
       }
       if (mc) __syncthreads();  // previous chunk's fragments fully read
-      store_transposed_pair(dZt, 8 * nc, pair, r0, r1);
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int b = t + kThreads * i, kc = b & 15, p2 = b >> 4;
-        store_transposed_pair(Xt, 8 * kc, p2, x0[i], x1[i]);
+      for (int i = 0; i < ZB; ++i) {
+        const int b = t + kThreads * i, nc = b % (TN / 8), pair = b / (TN / 8);
+        if (pair < 32) store_transposed_pair<8>(dZt, 8 * nc, pair, z0[i], z1[i]);
+      }
+#pragma unroll
+      for (int i = 0; i < XB; ++i) {
+        const int b = t + kThreads * i, kc = b % (TK / 8), p2 = b / (TK / 8);
+        store_transposed_pair<8>(Xt, 8 * kc, p2, x0[i], x1[i]);
       }
     }
     __syncthreads();
 #pragma unroll
     for (int ks = 0; ks < MC / 16; ++ks) {
       const int g = 2 * ks + (l >> 5);
-      const uint4 b = load_swizzled_frag(Xt, 32 * w + (l & 31), g);
-      const uint4 a0 = load_swizzled_frag(dZt, (l & 31), g);
-      const uint4 a1 = load_swizzled_frag(dZt, 32 + (l & 31), g);
-      acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a0), frag(b), acc0, 0, 0, 0);
-      acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a1), frag(b), acc1, 0, 0, 0);
+      uint4 a[NB];
+#pragma unroll
+      for (int i = 0; i < NB; ++i) a[i] = load_swizzled_frag<8>(dZt, 32 * i + (l & 31), g);
+#pragma unroll
+      for (int j = 0; j < KB; ++j) {
+        const uint4 b = load_swizzled_frag<8>(Xt, 32 * (KB * w + j) + (l & 31), g);
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b), acc[i][j], 0, 0, 0);
+      }
     }
   }
   __syncthreads();  // all fragment reads done before the tile memory is reused
 
   // phase 2a: accumulators -> LDS, G[n][k]
-  {
-    const int kcol = 32 * w + (l & 31);
 #pragma unroll
-    for (int blk = 0; blk < 2; ++blk) {
+  for (int j = 0; j < KB; ++j) {
+    const int kcol = 32 * (KB * w + j) + (l & 31);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int nrow = 32 * blk + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-        G[nrow * GLD + kcol] = blk ? acc1[r] : acc0[r];
+        const int nrow = 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        G[nrow * GLD + kcol] = acc[i][j][r];
       }
     }
   }
@@ -369,13 +387,20 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(
   // phase 2b: the update, row-major
 #pragma unroll
   for (int q = 0; q < kSlots; ++q) {
-    const int f = t + kThreads * q, row = f >> 5, c4 = (f & 31) * 4, k = k0 + c4, n = n0 + row;
+    const int f = t + kThreads * q, row = f / (TK / 4), c4 = (f % (TK / 4)) * 4, k = k0 + c4, n = n0 + row;
     if (n < N && k < K) {
+      const size_t off = (size_t)n * K + k;
       const float4 g = *reinterpret_cast<const float4*>(&G[row * GLD + c4]);
-      float4 m = pm[q], wv = pw[q];
+      float4 m, wv;
+      if (PREFETCH) {
+        m = pm[q];
+        wv = pw[q];
+      } else {
+        m = *reinterpret_cast<const float4*>(mom + off);
+        wv = *reinterpret_cast<const float4*>(master + off);
+      }
       m.x = mu * m.x + g.x; m.y = mu * m.y + g.y; m.z = mu * m.z + g.z; m.w = mu * m.w + g.w;
       wv.x -= lr * m.x; wv.y -= lr * m.y; wv.z -= lr * m.z; wv.w -= lr * m.w;
-      const size_t off = (size_t)n * K + k;
       *reinterpret_cast<float4*>(mom + off) = m;
       *reinterpret_cast<float4*>(master + off) = wv;
       uint2 pk;
@@ -400,68 +425,83 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(
   }
 }
 
+template <int TN, int TK, bool NFAST, bool PREFETCH>
+hipError_t launch_wgrad_update(hipStream_t s, WgradBatch batch) {
+  unsigned tiles = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    tiles += (unsigned)(((batch.layer[i].K + TK - 1) / TK) * ((batch.layer[i].N + TN - 1) / TN));
+    batch.layer[i].tile_end = tiles;
+  }
+  if (tiles == 0) return hipSuccess;
+  wgrad_update_kernel<TN, TK, NFAST, PREFETCH><<<tiles, kThreads, 0, s>>>(batch);
+  return hipGetLastError();
+}
+
+// Launch shapes, picked from sweeps at the VGG16 classifier's sizes on MI355X (minibatch 64).  Forward:
+// 64-column tiles, 128 reduction elements per stage, two stages of loads in flight, two LDS buffers.  Dgrad
+// of a large matrix: 128 x 128 tiles (fewer, longer transposing stages); of a small one: 64 x 256.
+constexpr int kFwdBN = 64, kFwdBK = 128, kFwdPD = 2, kFwdNBUF = 2;
+constexpr int kBigBN = 128, kBigBK = 128, kBigPD = 2, kBigNBUF = 1;
+constexpr int kSmallBN = 64, kSmallBK = 256, kSmallPD = 1, kSmallNBUF = 1;
+constexpr size_t kBigDgradElems = (size_t)32 << 20;  // weight elements from which the big dgrad shape is used
+
+// Enough workgroups to fill the chip (about two per CU, all co-resident), never more splits than stages.
 int pick_splits(int tiles, int red_tiles) {
-  int s = (512 + tiles - 1) / tiles;
+  int s = 512 / tiles;
   if (s > red_tiles / 2) s = red_tiles / 2;
   if (s > 32) s = 32;
   if (s < 1) s = 1;
   return s;
 }
 
+template <int BN_, int BK_>
+size_t splitk_bytes_t(int rows, int cols, int red) {
+  const int tiles = ((cols + BN_ - 1) / BN_) * ((rows + BM - 1) / BM);
+  const int s = pick_splits(tiles, (red + BK_ - 1) / BK_);
+  return s > 1 ? (size_t)s * rows * cols * sizeof(float) : (size_t)0;
+}
+
+template <bool BT, int BN_, int BK_, int PD, int NBUF>
+hipError_t launch_gemm(hipStream_t s, const bf16_t* a, const bf16_t* b, const GemmEpilogue& ep, int M, int C, int R,
+                       float* ws, size_t ws_bytes) {
+  const int tc = (C + BN_ - 1) / BN_, tm = (M + BM - 1) / BM;
+  int splits = pick_splits(tc * tm, (R + BK_ - 1) / BK_);
+  if (splits > 1 && (!ws || (size_t)splits * M * C * sizeof(float) > ws_bytes)) splits = 1;
+  dim3 grid(tc, tm, splits);
+  gemm_kernel<BT, BN_, BK_, PD, NBUF><<<grid, kThreads, 0, s>>>(a, b, ep, ws, M, C, R, splits);
+  if (splits > 1) {
+    const size_t total4 = (size_t)M * C / 4;
+    splitk_epilogue_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(ws, splits, M, C, ep);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K) {
-  // fwd writes splits*M*N floats, dgrad splits*M*K floats; splits <= 32 and is 1 when there are >= 512 tiles.
-  auto need = [](int rows, int cols, int red) {
-    const int tiles = ((cols + BN - 1) / BN) * ((rows + BM - 1) / BM);
-    const int s = pick_splits(tiles, (red + BK - 1) / BK);
-    return s > 1 ? (size_t)s * rows * cols * sizeof(float) : (size_t)0;
-  };
-  const size_t a = need(M, N, K), b = need(M, K, N);
+  const size_t a = splitk_bytes_t<kFwdBN, kFwdBK>(M, N, K);
+  const size_t b = (size_t)N * K >= kBigDgradElems ? splitk_bytes_t<kBigBN, kBigBK>(M, K, N)
+                                                   : splitk_bytes_t<kSmallBN, kSmallBK>(M, K, N);
   return a > b ? a : b;
 }
 
 hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const bf16_t* b, bf16_t* y, float* y_f32,
                            int M, int N, int K, bool relu, float* ws, size_t ws_bytes) {
-  const int tn = (N + BN - 1) / BN, tm = (M + BM - 1) / BM;
-  int splits = pick_splits(tn * tm, (K + BK - 1) / BK);
-  if (splits > 1 && (size_t)splits * M * N * sizeof(float) > ws_bytes) splits = 1;
-  dim3 grid(tn, tm, splits);
-  if (splits == 1) {
-    gemm_nt_kernel<true><<<grid, kThreads, 0, s>>>(x, w, b, y, y_f32, nullptr, M, N, K, relu ? 1 : 0, 1);
-  } else {
-    gemm_nt_kernel<false><<<grid, kThreads, 0, s>>>(x, w, b, y, y_f32, ws, M, N, K, 0, splits);
-    const size_t total4 = (size_t)M * N / 4;
-    splitk_epilogue_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(ws, splits, M, N, b, nullptr,
-                                                                              relu ? 1 : 0, y, y_f32);
-  }
-  return hipGetLastError();
+  GemmEpilogue ep = {b, nullptr, relu ? 1 : 0, y, y_f32};
+  return launch_gemm<false, kFwdBN, kFwdBK, kFwdPD, kFwdNBUF>(s, x, w, ep, M, N, K, ws, ws_bytes);
 }
 
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes) {
-  const int tc = (K + BN - 1) / BN, tm = (M + BM - 1) / BM;
-  int splits = pick_splits(tc * tm, (N + BK - 1) / BK);
-  if (splits > 1 && (size_t)splits * M * K * sizeof(float) > ws_bytes) splits = 1;
-  dim3 grid(tc, tm, splits);
-  if (splits == 1) {
-    gemm_nn_kernel<true><<<grid, kThreads, 0, s>>>(dz, w, mask, dx, nullptr, M, N, K, 1);
-  } else {
-    gemm_nn_kernel<false><<<grid, kThreads, 0, s>>>(dz, w, mask, dx, ws, M, N, K, splits);
-    const size_t total4 = (size_t)M * K / 4;
-    splitk_epilogue_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(ws, splits, M, K, nullptr, mask, 0, dx,
-                                                                              nullptr);
-  }
-  return hipGetLastError();
+  GemmEpilogue ep = {nullptr, mask, 0, dx, nullptr};
+  if ((size_t)N * K >= kBigDgradElems)
+    return launch_gemm<true, kBigBN, kBigBK, kBigPD, kBigNBUF>(s, dz, w, ep, M, K, N, ws, ws_bytes);
+  return launch_gemm<true, kSmallBN, kSmallBK, kSmallPD, kSmallNBUF>(s, dz, w, ep, M, K, N, ws, ws_bytes);
 }
 
-hipError_t linear_wgrad_update_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* master_w, float* mom_w,
-                                    bf16_t* ring_w, float* master_b, float* mom_b, bf16_t* ring_b, int M, int N, int K,
-                                    float lr, float mu) {
-  const unsigned tiles = (unsigned)(((K + TK - 1) / TK) * ((N + TN - 1) / TN));
-  wgrad_update_kernel<<<tiles, kThreads, 0, s>>>(dz, x, master_w, mom_w, ring_w, master_b, mom_b, ring_b, M, N, K, lr,
-                                                 mu);
-  return hipGetLastError();
+hipError_t linear_wgrad_update_bf16(hipStream_t s, const WgradBatch& batch) {
+  if (batch.count < 0 || batch.count > kMaxWgradLayers) return hipErrorInvalidValue;
+  return launch_wgrad_update<32, 128, false, true>(s, batch);
 }
 
 }  // namespace pd

@@ -19,11 +19,34 @@ hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, cons
 // dx[M][K] = (dz[M][N] * w[N][K]) .* (mask[M][K] > 0)   (mask may be null); dx bf16.
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes);
-// g = dz[M][N]^T x[M][K]; m <- mu*m + g; master <- master - lr*m; ring_out <- bf16(master); same for the bias
-// with g_b = column sums of dz.
-hipError_t linear_wgrad_update_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* master_w, float* mom_w,
-                                    bf16_t* ring_w, float* master_b, float* mom_b, bf16_t* ring_b, int M, int N, int K,
-                                    float lr, float mu);
+// Weight gradient fused with the momentum-SGD update, for up to kMaxWgradLayers Linear layers in ONE launch:
+// per layer g = dz[M][N]^T x[M][K]; m <- mu*m + g; master <- master - lr*m; ring <- bf16(master); the same
+// for the bias with g_b = column sums of dz (master_b may be null to skip the bias).
+constexpr int kMaxWgradLayers = 8;
+struct WgradLayer {
+  const bf16_t* dz;  // [M][N]
+  const bf16_t* x;   // [M][K]
+  float* master_w;   // [N][K]
+  float* mom_w;
+  bf16_t* ring_w;
+  float* master_b;   // [N] or null
+  float* mom_b;
+  bf16_t* ring_b;
+  int N, K;
+  unsigned tile_end;  // filled in by the launcher
+};
+struct WgradBatch {
+  WgradLayer layer[kMaxWgradLayers];
+  int count, M;
+  float lr, mu;
+};
+hipError_t linear_wgrad_update_bf16(hipStream_t s, const WgradBatch& batch);
+
+// ---- stand-alone update (update.hip) ---------------------------------------------------------------
+// m <- mu*m + g; w_out <- w_in - lr*m; ring <- bf16(w_out) if ring is not null.  g null = zero gradient.
+// All arrays 16-byte aligned.  grid_blocks <= 0 picks the default grid.
+hipError_t sgd_momentum_update(hipStream_t s, const float* g, const float* w_in, float* w_out, float* mom,
+                               bf16_t* ring, size_t n, float lr, float mu, int grid_blocks);
 
 // ---- fp32 path (linear_f32.hip) ------------------------------------------------------------------
 hipError_t linear_fwd_f32(hipStream_t s, const float* x, const float* w, const float* b, float* y, int M, int N, int K,

@@ -600,16 +600,23 @@ int pd_update(pd_stage* st) {
   char* slot = st->stash_slot(mb);
   const int nl = (int)st->lin.size();
   const int nv = st->latest + 1;
+  pd::WgradBatch batch;
+  batch.count = 0; batch.M = st->B; batch.lr = st->lr; batch.mu = st->mu;
   for (int l = 0; l < nl; ++l) {
     const Linear& L = st->lin[l];
     const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
     const char* x = l == 0 ? st->in_slot(mb) : slot + st->lin[l - 1].y_off;
     if (st->bf16) {
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
-      PD_HIP(pd::linear_wgrad_update_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
-                                          reinterpret_cast<const pd::bf16_t*>(x), st->master + L.w_off,
-                                          st->mom + L.w_off, ro + L.w_off, st->master + L.b_off, st->mom + L.b_off,
-                                          ro + L.b_off, st->B, L.out, L.in, st->lr, st->mu));
+      pd::WgradLayer& W = batch.layer[batch.count++];
+      W.dz = reinterpret_cast<const pd::bf16_t*>(dz); W.x = reinterpret_cast<const pd::bf16_t*>(x);
+      W.master_w = st->master + L.w_off; W.mom_w = st->mom + L.w_off; W.ring_w = ro + L.w_off;
+      W.master_b = st->master + L.b_off; W.mom_b = st->mom + L.b_off; W.ring_b = ro + L.b_off;
+      W.N = L.out; W.K = L.in; W.tile_end = 0;
+      if (batch.count == pd::kMaxWgradLayers || l == nl - 1) {  // all layers of the stage in one launch
+        PD_HIP(pd::linear_wgrad_update_bf16(s, batch));
+        batch.count = 0;
+      }
     } else {
       const float* wi = reinterpret_cast<const float*>(st->ring_slot(st->latest));
       float* wo = reinterpret_cast<float*>(st->ring_slot(nv));
@@ -744,10 +751,14 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
   if (check_gemm(dz, x, master_w, M, N, K)) return PD_EINVAL;
   if (!mom_w || !ring_out_w) return fail(PD_EINVAL, "null pointer");
   if (master_b && (!mom_b || !ring_out_b)) return fail(PD_EINVAL, "bias buffers must be given together");
-  PD_HIP(pd::linear_wgrad_update_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(dz),
-                                      static_cast<const pd::bf16_t*>(x), master_w, mom_w,
-                                      static_cast<pd::bf16_t*>(ring_out_w), master_b, mom_b,
-                                      static_cast<pd::bf16_t*>(ring_out_b), M, N, K, lr, momentum));
+  pd::WgradBatch batch;
+  batch.count = 1; batch.M = M; batch.lr = lr; batch.mu = momentum;
+  pd::WgradLayer& W = batch.layer[0];
+  W.dz = static_cast<const pd::bf16_t*>(dz); W.x = static_cast<const pd::bf16_t*>(x);
+  W.master_w = master_w; W.mom_w = mom_w; W.ring_w = static_cast<pd::bf16_t*>(ring_out_w);
+  W.master_b = master_b; W.mom_b = mom_b; W.ring_b = static_cast<pd::bf16_t*>(ring_out_b);
+  W.N = N; W.K = K; W.tile_end = 0;
+  PD_HIP(pd::linear_wgrad_update_bf16(static_cast<hipStream_t>(stream), batch));
   return PD_OK;
 }
 

@@ -41,7 +41,7 @@ def test_linear_fwd_bf16(M, N, K):
     b = _bf(gen.normal(SEED, "kb", (N,)) * 0.1)
     s = torch.cuda.current_stream().cuda_stream
     wsb = pd.pd_gemm_workspace_bytes(M, N, K)
-    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev())
+    ws = torch.zeros(max(wsb, 16), dtype=torch.uint8, device=dev())
     xd, wd, bd = to_dev(x, True), to_dev(w, True), to_dev(b, True)
     for relu in (True, False):
         for use_ws in (True, False):
@@ -61,7 +61,7 @@ def test_linear_dgrad_bf16(M, N, K):
     ymask = _bf(np.maximum(gen.normal(SEED, "ym", (M, K)), 0.0))
     s = torch.cuda.current_stream().cuda_stream
     wsb = pd.pd_gemm_workspace_bytes(M, N, K)
-    ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev())
+    ws = torch.zeros(max(wsb, 16), dtype=torch.uint8, device=dev())
     dzd, wd, md = to_dev(dz, True), to_dev(w, True), to_dev(ymask, True)
     for masked in (True, False):
         for use_ws in (True, False):
