@@ -7,6 +7,10 @@ the standard definition written out:
   Linear          y = x W^T + b,  W[out][in]
   ReLU            max(y, 0); derivative 1 where the stored output is > 0, else 0
   softmax-xent    L = mean_rows( logsumexp(z) - z[label] ),  dz = (softmax(z) - onehot) / rows
+  Conv2d          cross-correlation, NHWC activations, W[c_out][kh][kw][c_in], zero padding,
+                  y[n,i,j,o] = b[o] + sum_{a,b,c} x[n, i*s + a - ph, j*s + b - pw, c] W[o,a,b,c]
+  MaxPool2d       window k, stride s, no padding; the gradient goes to the FIRST maximum of the
+                  window in row-major order (ties do occur among bf16 values)
 
 Precision modes.  "f32": no rounding anywhere (pure fp64; the HIP path computes
 in fp32 and is compared at 1e-4).  "bf16": tensors that the mixed-precision path
@@ -88,3 +92,82 @@ def softmax_xent_backward(p, labels, q):
     d = p.copy()
     d[np.arange(p.shape[0]), labels] -= 1.0
     return q(d / p.shape[0])
+
+
+# ---- Conv2d (+ optional ReLU), NHWC -------------------------------------------
+
+def _conv_out(size, k, stride, pad):
+    return (size + 2 * pad - k) // stride + 1
+
+
+def _tap_view(xp, a, b, ho, wo, stride):
+    """The input pixels that tap (a, b) of the kernel meets, one per output pixel: [N, ho, wo, C]."""
+    return xp[:, a:a + (ho - 1) * stride + 1:stride, b:b + (wo - 1) * stride + 1:stride, :]
+
+
+def conv2d_forward(x, W, b, stride, pad_h, pad_w, relu: bool, q):
+    """x[N][H][W][Cin], W[Cout][kh][kw][Cin], b[Cout] -> stored output [N][Ho][Wo][Cout].
+
+    Written as the definition: one matrix product per kernel tap over the shifted input.
+    """
+    N, H, Wd, C = x.shape
+    Co, kh, kw, _ = W.shape
+    ho, wo = _conv_out(H, kh, stride, pad_h), _conv_out(Wd, kw, stride, pad_w)
+    xp = np.pad(x, ((0, 0), (pad_h, pad_h), (pad_w, pad_w), (0, 0)))
+    z = np.zeros((N, ho, wo, Co)) + b
+    for a in range(kh):
+        for c in range(kw):
+            z += _tap_view(xp, a, c, ho, wo, stride) @ W[:, a, c, :].T
+    if relu:
+        z = np.maximum(z, 0.0)
+    return q(z)
+
+
+def conv2d_backward(x, W, y, dy, stride, pad_h, pad_w, relu: bool, need_dx: bool, q):
+    """Returns (dx or None, dW, db) for the convolution above."""
+    N, H, Wd, C = x.shape
+    Co, kh, kw, _ = W.shape
+    ho, wo = y.shape[1], y.shape[2]
+    dz = dy * (y > 0.0) if relu else dy
+    xp = np.pad(x, ((0, 0), (pad_h, pad_h), (pad_w, pad_w), (0, 0)))
+    dW = np.zeros_like(W)
+    dxp = np.zeros_like(xp) if need_dx else None
+    dz2 = dz.reshape(-1, Co)
+    for a in range(kh):
+        for c in range(kw):
+            xs = _tap_view(xp, a, c, ho, wo, stride)
+            dW[:, a, c, :] = dz2.T @ xs.reshape(-1, C)
+            if need_dx:
+                _tap_view(dxp, a, c, ho, wo, stride)[...] += dz @ W[:, a, c, :]
+    db = dz2.sum(axis=0)
+    dx = None
+    if need_dx:
+        dx = q(dxp[:, pad_h:pad_h + H, pad_w:pad_w + Wd, :])
+    return dx, dW, db
+
+
+# ---- MaxPool2d, NHWC ----------------------------------------------------------
+
+def maxpool2d_forward(x, k, stride):
+    N, H, Wd, C = x.shape
+    ho, wo = (H - k) // stride + 1, (Wd - k) // stride + 1
+    y = np.full((N, ho, wo, C), -np.inf)
+    for a in range(k):
+        for b in range(k):
+            y = np.maximum(y, x[:, a:a + (ho - 1) * stride + 1:stride, b:b + (wo - 1) * stride + 1:stride, :])
+    return y
+
+
+def maxpool2d_backward(x, y, dy, k, stride):
+    """dL/dx: each output's gradient goes to the first position (row-major in the window) holding the maximum."""
+    N, H, Wd, C = x.shape
+    ho, wo = y.shape[1], y.shape[2]
+    dx = np.zeros_like(x)
+    taken = np.zeros(y.shape, dtype=bool)
+    for a in range(k):
+        for b in range(k):
+            xs = x[:, a:a + (ho - 1) * stride + 1:stride, b:b + (wo - 1) * stride + 1:stride, :]
+            hit = (xs == y) & ~taken
+            dx[:, a:a + (ho - 1) * stride + 1:stride, b:b + (wo - 1) * stride + 1:stride, :] += np.where(hit, dy, 0.0)
+            taken |= hit
+    return dx

@@ -34,10 +34,46 @@ def _split_params(layers, flat):
             W = flat[o:o + n_in * n_out].reshape(n_out, n_in); o += n_in * n_out
             b = flat[o:o + n_out]; o += n_out
             out.append((W, b))
+        elif ly[0] == "conv2d":
+            c_in, c_out, kh, kw = ly[1], ly[2], ly[3], ly[4]
+            n = c_out * kh * kw * c_in
+            W = flat[o:o + n].reshape(c_out, kh, kw, c_in); o += n
+            b = flat[o:o + c_out]; o += c_out
+            out.append((W, b))
         else:
             out.append(None)
     assert o == flat.size, "parameter vector does not match the layer list"
     return out
+
+
+def _layer_forward(layers, li, p, a, q):
+    """Stored output of layer li for stored input a (loss layers are handled by the caller)."""
+    ly = layers[li]
+    if ly[0] == "linear":
+        if a.ndim > 2:
+            a = a.reshape(a.shape[0], -1)          # NHWC flatten
+        return L.linear_forward(a, p[0], p[1], ly[3], _out_quantiser(layers, li, q))
+    if ly[0] == "conv2d":
+        return L.conv2d_forward(a, p[0], p[1], ly[5], ly[6], ly[7], ly[8], q)
+    if ly[0] == "maxpool2d":
+        return L.maxpool2d_forward(a, ly[1], ly[2])
+    raise NotImplementedError(ly[0])
+
+
+def _layer_backward(layers, li, p, x, y, d, need_dx, q):
+    """(dx, dW, db) of layer li; dW/db are None for layers without parameters."""
+    ly = layers[li]
+    if ly[0] == "linear":
+        x2 = x.reshape(x.shape[0], -1)
+        dx, dW, db = L.linear_backward(x2, p[0], y, d, ly[3], need_dx, q)
+        if dx is not None:
+            dx = dx.reshape(x.shape)
+        return dx, dW, db
+    if ly[0] == "conv2d":
+        return L.conv2d_backward(x, p[0], y, d, ly[5], ly[6], ly[7], ly[8], need_dx, q)
+    if ly[0] == "maxpool2d":
+        return (L.maxpool2d_backward(x, y, d, ly[1], ly[2]) if need_dx else None), None, None
+    raise NotImplementedError(ly[0])
 
 
 def _out_quantiser(layers, li, q):
@@ -77,12 +113,10 @@ class Stage:
         acts = [self.q(x)]
         loss, probs = None, None
         for li, (ly, p) in enumerate(zip(self.layers, P)):
-            if ly[0] == "linear":
-                acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], _out_quantiser(self.layers, li, self.q)))
-            elif ly[0] == "softmax_xent":
+            if ly[0] == "softmax_xent":
                 loss, probs = L.softmax_xent_forward(acts[-1], labels)
             else:
-                raise NotImplementedError(ly[0])
+                acts.append(_layer_forward(self.layers, li, p, acts[-1], self.q))
         self.stash[mb] = dict(version=v, acts=acts, labels=labels, probs=probs)
         if self.log is not None:
             self.log[mb] = dict(version=v, acts=acts, loss=loss)
@@ -106,12 +140,13 @@ class Stage:
             ly = self.layers[li]
             if ly[0] == "softmax_xent":
                 d = L.softmax_xent_backward(st["probs"], st["labels"], self.q)
-            elif ly[0] == "linear":
+            else:
                 first = li == 0
-                dx, dW, db = L.linear_backward(acts[k - 1], P[li][0], acts[k], d, ly[3],
-                                               need_dx or not first, self.q)
-                G[li][0][...] = dW
-                G[li][1][...] = db
+                dx, dW, db = _layer_backward(self.layers, li, P[li], acts[k - 1], acts[k], d,
+                                             need_dx or not first, self.q)
+                if dW is not None:
+                    G[li][0][...] = dW
+                    G[li][1][...] = db
                 d = dx
                 k -= 1
         self.grad = g
@@ -229,10 +264,10 @@ def flat_loop(stage_layers: Sequence, stage_params: Sequence, inputs, labels, de
             P = _split_params(stage_layers[s], W[s])
             acts = [a]
             for li, (ly, p) in enumerate(zip(stage_layers[s], P)):
-                if ly[0] == "linear":
-                    acts.append(L.linear_forward(acts[-1], p[0], p[1], ly[3], _out_quantiser(stage_layers[s], li, q)))
-                elif ly[0] == "softmax_xent":
+                if ly[0] == "softmax_xent":
                     loss, probs = L.softmax_xent_forward(acts[-1], labels[t])
+                else:
+                    acts.append(_layer_forward(stage_layers[s], li, p, acts[-1], q))
             acts_all.append(acts)
             a = acts[-1]
         losses.append(loss)
@@ -248,11 +283,12 @@ def flat_loop(stage_layers: Sequence, stage_params: Sequence, inputs, labels, de
                 ly = stage_layers[s][li]
                 if ly[0] == "softmax_xent":
                     d = L.softmax_xent_backward(probs, labels[t], q)
-                elif ly[0] == "linear":
+                else:
                     need_dx = not (s == 0 and li == 0)
-                    dx, dW, db = L.linear_backward(acts[k - 1], P[li][0], acts[k], d, ly[3], need_dx, q)
-                    G[li][0][...] = dW
-                    G[li][1][...] = db
+                    dx, dW, db = _layer_backward(stage_layers[s], li, P[li], acts[k - 1], acts[k], d, need_dx, q)
+                    if dW is not None:
+                        G[li][0][...] = dW
+                        G[li][1][...] = db
                     d = dx
                     k -= 1
             mom[s] = momentum * mom[s] + g
