@@ -35,9 +35,10 @@
  *     bias add, the logits of a stage that ends in the loss, the loss, weight
  *     gradients, master weights and momentum are float.
  *   - Matrices are row-major.  A minibatch activation is [rows][features] with
- *     rows = cfg.minibatch.  Linear weights are W[out][in].
+ *     rows = cfg.minibatch; image activations are [rows][height][width][channels]
+ *     (NHWC).  Linear weights are W[out][in], convolution weights W[c_out][kh][kw][c_in].
  *   - Flat parameter vector (pd_stage_set_params and friends): layer by layer in
- *     stage order, each Linear contributing W (out*in values) then b (out values).
+ *     stage order, each Linear or convolution contributing W then b (out values).
  */
 #ifndef PD_H_
 #define PD_H_
@@ -71,8 +72,20 @@ typedef struct {
 } pd_op;
 
 typedef enum {
-  PD_LINEAR = 0,       /* p[0]=in_features p[1]=out_features p[2]=1: fused ReLU on the output */
-  PD_SOFTMAX_XENT = 1  /* p[0]=classes; must be the last layer, directly after a PD_LINEAR      */
+  PD_LINEAR = 0,       /* p[0]=in_features p[1]=out_features p[2]=1: fused ReLU on the output.  After a
+                          convolution or pooling layer the input is that layer's output flattened in
+                          NHWC order.                                                              */
+  PD_SOFTMAX_XENT = 1, /* p[0]=classes; must be the last layer, directly after a PD_LINEAR          */
+  PD_CONV2D = 2,       /* cross-correlation with zero padding, NHWC activations, weights
+                          W[c_out][kh][kw][c_in], bias per output channel:
+                          p[0]=c_in p[1]=c_out p[2]=kh p[3]=kw p[4]=stride p[5]=pad_h p[6]=pad_w
+                          p[7]=1: fused ReLU  p[8]=in_h p[9]=in_w.  PD_BF16_F32ACC only; c_out and c_in
+                          divisible by 8, except that a layer with kh*kw*c_in <= 32 and c_out <= 64 (the
+                          first layer of an image network) may have any c_in.  dL/d(input) is built for
+                          stride 1.                                                                */
+  PD_MAXPOOL2D = 3     /* p[0]=window p[1]=stride p[2]=channels p[3]=in_h p[4]=in_w; only window 2,
+                          stride 2 (even in_h, in_w; channels divisible by 8).  The gradient goes to the
+                          first maximum of a window in row-major order.                            */
 } pd_layer_kind;
 
 typedef struct {
@@ -160,10 +173,11 @@ int pd_stage_input_slot(pd_stage* st, int32_t mb_id, void** dev_ptr);
 int pd_stage_grad_slot(pd_stage* st, int32_t mb_id, void** dev_ptr);
 
 /* Test/debug aid: copies one of the stage's intermediate tensors to the host as fp32
- * (synchronises the stream).  what = 0: stored output of Linear number `layer` (0-based among the
- * stage's Linear layers) for in-flight minibatch mb_id, [minibatch][out]; 1: the stage's input
+ * (synchronises the stream).  what = 0: stored output of compute layer number `layer` (0-based, the
+ * loss not counted) for in-flight minibatch mb_id, [minibatch][out]; 1: the stage's input
  * slot for mb_id, [minibatch][in]; 2: the output-gradient slot for mb_id, [minibatch][out_last];
- * 3: dL/d(pre-activation) of Linear `layer` left by the last pd_backward, [minibatch][out];
+ * 3: dL/d(pre-activation) of layer `layer` left by the last pd_backward, [minibatch][out] (Linear layers
+ * only: convolution and pooling layers do not keep theirs);
  * 4: the stashed dL/dlogits of in-flight minibatch mb_id (loss stages).  n must equal the tensor's
  * element count.  No state check is made on mb_id beyond >= 0: the caller reads what the slot holds. */
 int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, float* host_out, size_t n);
@@ -185,13 +199,15 @@ int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer
  * pd_backward: B for minibatch mb_id, which must be the OLDEST in flight (PD_ESTATE otherwise).
  * Uses the weight version stashed at its forward.  dy_dev [minibatch][out] = dL/d(output),
  * NULL iff the stage ends in the loss.  dx_dev [minibatch][in] receives dL/d(input), NULL to
- * skip it (input stage).  Leaves the weight gradient pending (held in factored form: per layer
- * dL/d(pre-activation) and the stashed layer input) and releases the minibatch's stash slot.
+ * skip it (input stage).  Leaves the weight gradient pending (Linear: held in factored form, per layer
+ * dL/d(pre-activation) and the stashed layer input; convolution: fp32 partial sums over pixel ranges)
+ * and releases the minibatch's stash slot.
  *
  * pd_update: U.  Consumes the pending gradient: per Linear, dW = dZ^T X and db = colsum(dZ)
  * are formed tile by tile and, in the same kernel, m <- mu*m + g, w <- w - lr*m is applied to
  * the LATEST weights (Section 4, parameter state) and the result stored as version latest+1
- * in ring slot (latest+1) mod depth.  PD_ESTATE without a pending gradient. */
+ * in ring slot (latest+1) mod depth; per convolution the partial sums are added in a fixed order
+ * and the same step applied.  PD_ESTATE without a pending gradient. */
 int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
                float* loss_dev);
 int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev);
@@ -228,6 +244,30 @@ int pd_linear_dgrad_bf16(void* stream, const void* dz, const void* w, const void
 int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, float* master_w, float* mom_w,
                                 void* ring_out_w, float* master_b, float* mom_b, void* ring_out_b, int32_t M,
                                 int32_t N, int32_t K, float lr, float momentum);
+
+/* Convolution and pooling kernels on caller buffers (bf16 NHWC data, fp32 accumulate; all pointers device).
+ * geom = {N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w} (10 ints, host); output size
+ * Ho = (H + 2 pad_h - kh)/stride + 1, Wo likewise.  Shape rules as for PD_CONV2D / PD_MAXPOOL2D.
+ *   conv_fwd  : y[N][Ho][Wo][c_out] = act(conv(x, w) + b)                      (b may be NULL)
+ *   conv_dgrad: dx[N][H][W][c_in]   = convT(dz, w) .* (mask > 0 if mask)       stride 1 only;
+ *               wt_scratch: c_out*kh*kw*c_in bf16 elements of scratch
+ *   conv_wgrad_update: g = dL/dw from dz and x (and column sums for the bias), partial sums over
+ *               pd_conv_wgrad_splits(geom) pixel ranges in part_scratch (that many times
+ *               (c_out*kh*kw*c_in + c_out) floats), added in a fixed order; then m <- mu*m + g;
+ *               master <- master - lr*m; ring_out <- bf16(master)
+ *   maxpool2x2_fwd / _bwd: 2x2 stride-2 max pooling of x[N][H][W][C]; backward routes dy to the first
+ *               maximum of each window and, if relu_mask != 0, zeroes positions where x <= 0 */
+int pd_conv_wgrad_splits(const int32_t* geom, int32_t* splits);
+int pd_conv_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, const int32_t* geom,
+                     int32_t relu);
+int pd_conv_dgrad_bf16(void* stream, const void* dz, const void* w, const void* mask, void* dx, void* wt_scratch,
+                       const int32_t* geom);
+int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float* part_scratch, float* master_w,
+                              float* mom_w, void* ring_out_w, float* master_b, float* mom_b, void* ring_out_b,
+                              const int32_t* geom, float lr, float momentum);
+int pd_maxpool2x2_fwd_bf16(void* stream, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C);
+int pd_maxpool2x2_bwd_bf16(void* stream, const void* x, const void* y, const void* dy, void* dx, int32_t N, int32_t H,
+                           int32_t W, int32_t C, int32_t relu_mask);
 
 const char* pd_last_error(void); /* thread-local, static storage, never NULL */
 

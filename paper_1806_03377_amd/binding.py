@@ -24,7 +24,7 @@ _lib = C.CDLL(LIB_PATH)
 PD_OK, PD_EINVAL, PD_ESTATE, PD_ENOMEM, PD_EHIP = 0, -1, -2, -3, -4
 PD_F32, PD_BF16_F32ACC = 0, 1
 PD_OP_F, PD_OP_B, PD_OP_U = 0, 1, 2
-PD_LINEAR, PD_SOFTMAX_XENT = 0, 1
+PD_LINEAR, PD_SOFTMAX_XENT, PD_CONV2D, PD_MAXPOOL2D = 0, 1, 2, 3
 
 
 class PdError(RuntimeError):
@@ -74,6 +74,12 @@ _SIGS = {
     "pd_linear_fwd_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _sz],
     "pd_linear_dgrad_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _sz],
     "pd_linear_wgrad_update_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _f32],
+    "pd_conv_wgrad_splits": [C.POINTER(_i32), C.POINTER(_i32)],
+    "pd_conv_fwd_bf16": [_vp, _vp, _vp, _vp, _vp, C.POINTER(_i32), _i32],
+    "pd_conv_dgrad_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(_i32)],
+    "pd_conv_wgrad_update_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(_i32), _f32, _f32],
+    "pd_maxpool2x2_fwd_bf16": [_vp, _vp, _vp, _i32, _i32, _i32, _i32],
+    "pd_maxpool2x2_bwd_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -116,9 +122,14 @@ def pd_schedule_1f1b_depth(depth: int, num_minibatches: int):
     return _ops(arr, n.value)
 
 
-def layer_descs(layers: Sequence[tuple]):
-    """Translate the neutral layer tuples of pd_inputs into pd_layer_desc records."""
+def layer_descs(layers: Sequence[tuple], in_hw=None):
+    """Translate the neutral layer tuples of pd_inputs into pd_layer_desc records.
+
+    ``in_hw`` = (height, width) of the stage's input images, needed when the stage has
+    convolution or pooling layers (their descriptors carry the input size)."""
     arr = (pd_layer_desc * len(layers))()
+    hw = tuple(in_hw) if in_hw else None
+    ch = None
     for i, L in enumerate(layers):
         if L[0] == "linear":
             arr[i].kind = PD_LINEAR
@@ -126,14 +137,30 @@ def layer_descs(layers: Sequence[tuple]):
         elif L[0] == "softmax_xent":
             arr[i].kind = PD_SOFTMAX_XENT
             arr[i].p[0] = int(L[1])
+        elif L[0] == "conv2d":
+            if hw is None:
+                raise ValueError("in_hw is required for stages with convolutions")
+            _, c_in, c_out, kh, kw, stride, ph, pw, relu = L
+            arr[i].kind = PD_CONV2D
+            for j, v in enumerate((c_in, c_out, kh, kw, stride, ph, pw, int(bool(relu)), hw[0], hw[1])):
+                arr[i].p[j] = int(v)
+            hw = ((hw[0] + 2 * ph - kh) // stride + 1, (hw[1] + 2 * pw - kw) // stride + 1)
+            ch = c_out
+        elif L[0] == "maxpool2d":
+            if hw is None or ch is None:
+                raise ValueError("a pooling layer must follow a convolution in this description")
+            arr[i].kind = PD_MAXPOOL2D
+            for j, v in enumerate((L[1], L[2], ch, hw[0], hw[1])):
+                arr[i].p[j] = int(v)
+            hw = ((hw[0] - L[1]) // L[2] + 1, (hw[1] - L[1]) // L[2] + 1)
         else:
             raise ValueError(f"layer kind {L[0]!r} is not supported by this build")
     return arr
 
 
 def make_config(layers, *, stage_index=0, num_stages=1, noam=1, in_flight_override=0, minibatch=1,
-                precision=PD_F32, lr=0.01, momentum=0.9, stream=0):
-    descs = layer_descs(layers)
+                precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None):
+    descs = layer_descs(layers, in_hw)
     cfg = pd_stage_config(stage_index, num_stages, noam, in_flight_override, minibatch, precision, lr, momentum,
                           len(layers), descs, stream)
     cfg._keepalive = descs
@@ -271,3 +298,34 @@ def pd_linear_dgrad_bf16(stream, dz, w, mask, dx, M, N, K, ws=0, ws_bytes=0):
 def pd_linear_wgrad_update_bf16(stream, dz, x, master_w, mom_w, ring_w, master_b, mom_b, ring_b, M, N, K, lr, mu):
     _check(_lib.pd_linear_wgrad_update_bf16(stream, dz, x, master_w, mom_w, ring_w, master_b or None, mom_b or None,
                                             ring_b or None, M, N, K, lr, mu))
+
+
+def _geom(N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w):
+    return (_i32 * 10)(N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w)
+
+
+def pd_conv_wgrad_splits(geom) -> int:
+    n = _i32(0)
+    _check(_lib.pd_conv_wgrad_splits(_geom(*geom), C.byref(n)))
+    return n.value
+
+
+def pd_conv_fwd_bf16(stream, x, w, b, y, geom, relu):
+    _check(_lib.pd_conv_fwd_bf16(stream, x, w, b or None, y, _geom(*geom), int(relu)))
+
+
+def pd_conv_dgrad_bf16(stream, dz, w, mask, dx, wt_scratch, geom):
+    _check(_lib.pd_conv_dgrad_bf16(stream, dz, w, mask or None, dx, wt_scratch, _geom(*geom)))
+
+
+def pd_conv_wgrad_update_bf16(stream, dz, x, part, master_w, mom_w, ring_w, master_b, mom_b, ring_b, geom, lr, mu):
+    _check(_lib.pd_conv_wgrad_update_bf16(stream, dz, x, part, master_w, mom_w, ring_w, master_b, mom_b, ring_b,
+                                          _geom(*geom), lr, mu))
+
+
+def pd_maxpool2x2_fwd_bf16(stream, x, y, N, H, W, Cn):
+    _check(_lib.pd_maxpool2x2_fwd_bf16(stream, x, y, N, H, W, Cn))
+
+
+def pd_maxpool2x2_bwd_bf16(stream, x, y, dy, dx, N, H, W, Cn, relu_mask):
+    _check(_lib.pd_maxpool2x2_bwd_bf16(stream, x, y, dy, dx, N, H, W, Cn, int(relu_mask)))

@@ -1,0 +1,643 @@
+// bf16 convolution (NHWC, fp32 accumulate) and max-pooling kernels for gfx950, built on the 32x32x16 MFMA.
+//
+//   conv_igemm_kernel        implicit GEMM: rows = output pixels, columns = output channels, reduction over
+//                            (tap, input channel).  Forward, and dgrad of a stride-1 convolution (the same
+//                            kernel on dL/dy with flipped, transposed weights).  Needs Ci % 8 == 0.
+//   conv_wgrad_kernel        dW[co][tap][ci] = sum over pixels of dz[p][co] * x[pix(p,tap)][ci]: both operands
+//                            are read "sideways" (reduction index = pixel), so 2x8 blocks are transposed on the
+//                            way into LDS; the pixel range is split over workgroups, partial sums go to memory
+//   wgrad_reduce_update      sums the partials in split order and applies the momentum-SGD update
+//   conv_smallk_*            first layer of an image network (kh*kw*Ci <= 32, e.g. 3x3x3): the 27 inputs of an
+//                            output pixel are gathered into one 32-wide reduction row
+//   maxpool2x2_*             2x2/stride-2 max-pooling; backward sends the gradient to the first maximum in
+//                            row-major window order and applies the ReLU mask of the layer below
+#include "bf16_util.h"
+#include "mfma_util.h"
+#include "pd_kernels.h"
+
+namespace pd {
+namespace {
+
+__device__ __forceinline__ void store_out(const ConvEpilogue& ep, float v, size_t off, int c) {
+  if (ep.bias) v += bf2f(ep.bias[c]);
+  if (ep.relu) v = fmaxf(v, 0.f);
+  uint16_t o = f2bf(v);
+  if (ep.mask && !bf_positive(ep.mask[off])) o = 0;
+  ep.out[off] = o;
+}
+
+// ------------------------------------------------------------------------------------------------
+// implicit-GEMM convolution.  grid = (ceil(Co/64), ceil(N*Ho*Wo/128)); tile 128 pixels x 64 channels,
+// 64 reduction elements per stage, two stages of loads in flight, two LDS buffers.
+// ------------------------------------------------------------------------------------------------
+constexpr int CM = 128, CN = 64, CK = 64, CLD = CK + 8, CPD = 2;
+
+__global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __restrict__ X,
+                                                              const bf16_t* __restrict__ Wg, ConvGeom g,
+                                                              ConvEpilogue ep) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][CM * CLD];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][CN * CLD];
+  const int t = threadIdx.x, l = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
+  const int co0 = blockIdx.x * CN;
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  const long long p0 = (long long)blockIdx.y * CM;
+  const int K = g.kh * g.kw * g.Ci;
+  const int T = (K + CK - 1) / CK;
+  const int col = t & 7;
+
+  // the four pixel rows this thread loads in every stage
+  int hi0[4], wi0[4];
+  long long nbase[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const long long p = p0 + (t >> 3) + 32 * i;
+    if (p < P) {
+      const int wo = (int)(p % g.Wo);
+      const long long q = p / g.Wo;
+      const int ho = (int)(q % g.Ho);
+      nbase[i] = (q / g.Ho) * (long long)g.H * g.W * g.Ci;
+      hi0[i] = ho * g.stride - g.ph;
+      wi0[i] = wo * g.stride - g.pw;
+    } else {
+      nbase[i] = -1;
+      hi0[i] = wi0[i] = 0;
+    }
+  }
+
+  struct Regs {
+    uint4 a[4], b[2];
+  };
+  auto gload = [&](Regs& r, int st) {
+    const int k = st * CK + col * 8;
+    const bool live = st < T && k < K;
+    const int tap = live ? k / g.Ci : 0, ci = live ? k - tap * g.Ci : 0;
+    const int ta = tap / g.kw, tb = tap - ta * g.kw;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int hi = hi0[i] + ta, wi = wi0[i] + tb;
+      const bool ok = live && nbase[i] >= 0 && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
+      r.a[i] = ok ? ldg16(X + nbase[i] + ((long long)hi * g.W + wi) * g.Ci + ci) : zero16();
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int co = co0 + (t >> 3) + 32 * i;
+      r.b[i] = (live && co < g.Co) ? ldg16(Wg + (size_t)co * K + k) : zero16();
+    }
+  };
+  auto sstore = [&](int buf, const Regs& r) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(&As[buf][((t >> 3) + 32 * i) * CLD + col * 8]) = r.a[i];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4*>(&Bs[buf][((t >> 3) + 32 * i) * CLD + col * 8]) = r.b[i];
+  };
+
+  f32x16 acc[2] = {f32x16{0}, f32x16{0}};
+  Regs Rg[CPD];
+#pragma unroll
+  for (int p = 0; p < CPD; ++p) gload(Rg[p], p);
+  sstore(0, Rg[0]);
+  gload(Rg[0], CPD);
+  __syncthreads();
+  for (int base = 0; base < T; base += CPD) {
+#pragma unroll
+    for (int j = 0; j < CPD; ++j) {
+      const int st = base + j;
+      if (st >= T) break;
+      const int cur = st & 1;
+#pragma unroll
+      for (int ks = 0; ks < CK / 16; ++ks) {
+        const int kk = ks * 16 + (l >> 5) * 8;
+        const uint4 b = *reinterpret_cast<const uint4*>(&Bs[cur][(32 * wn + (l & 31)) * CLD + kk]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const uint4 a = *reinterpret_cast<const uint4*>(&As[cur][(64 * wm + 32 * i + (l & 31)) * CLD + kk]);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a), frag(b), acc[i], 0, 0, 0);
+        }
+      }
+      if (st + 1 < T) {
+        sstore(cur ^ 1, Rg[(j + 1) % CPD]);
+        gload(Rg[(j + 1) % CPD], st + 1 + CPD);
+      }
+      __syncthreads();
+    }
+  }
+
+  const int c = co0 + 32 * wn + (l & 31);
+  if (c >= g.Co) return;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const long long p = p0 + 64 * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+      if (p < P) store_out(ep, acc[i][r], (size_t)p * g.Co + c, c);
+    }
+}
+
+// wt[ci][kh-1-a][kw-1-b][co] = w[co][a][b][ci]: the weights of the stride-1 convolution that maps dL/dy to dL/dx
+__global__ __launch_bounds__(256) void flip_transpose_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt,
+                                                             int Co, int kh, int kw, int Ci) {
+  const size_t n = (size_t)Co * kh * kw * Ci;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= n) return;
+  const int ci = (int)(idx % Ci);
+  size_t q = idx / Ci;
+  const int b = (int)(q % kw);
+  q /= kw;
+  const int a = (int)(q % kh);
+  const int co = (int)(q / kh);
+  wt[(((size_t)ci * kh + (kh - 1 - a)) * kw + (kw - 1 - b)) * Co + co] = w[idx];
+}
+
+// ------------------------------------------------------------------------------------------------
+// weight gradient, partial over a pixel range.
+// grid.x = co-tiles * ci-tiles * taps (tap fastest), grid.y = splits.  Tile TC x TC of (co, ci) for one tap.
+// part[split][e], e = (co*taps + tap)*Ci + ci for the weights, n_w + co for the bias (column sums of dz,
+// written by the workgroups of tap 0, ci-tile 0).
+// ------------------------------------------------------------------------------------------------
+template <int TC>
+__global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const bf16_t* __restrict__ dZ,
+                                                              const bf16_t* __restrict__ X, float* __restrict__ part,
+                                                              ConvGeom g, int chunks_per_split) {
+  constexpr int NBLK = TC / 8 * 32 / kThreads;  // 2x8 blocks per thread and operand (1 for 64, 2 for 128)
+  constexpr int WB = TC / 64;                   // 32x32 blocks per wave along each side
+  __shared__ __attribute__((aligned(16))) uint32_t Zt[2][TC * 32];  // [co][64 pixels], swizzled
+  __shared__ __attribute__((aligned(16))) uint32_t Xt[2][TC * 32];  // [ci][64 pixels]
+  const int t = threadIdx.x, l = t & 63, w = t >> 6, wr = w >> 1, wc = w & 1;
+  const int taps = g.kh * g.kw;
+  const int ci_tiles = (g.Ci + TC - 1) / TC;
+  const int tap = blockIdx.x % taps;
+  const int ci0 = ((blockIdx.x / taps) % ci_tiles) * TC;
+  const int co0 = (blockIdx.x / taps / ci_tiles) * TC;
+  const int ta = tap / g.kw, tb = tap - ta * g.kw;
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  const long long chunk0 = (long long)blockIdx.y * chunks_per_split;
+  const long long nchunks_total = (P + 63) / 64;
+  long long chunk1 = chunk0 + chunks_per_split;
+  if (chunk1 > nchunks_total) chunk1 = nchunks_total;
+  const bool do_bias = tap == 0 && ci0 == 0;
+
+  struct Regs {
+    uint4 z0[NBLK], z1[NBLK], x0[NBLK], x1[NBLK];
+  };
+  auto gload = [&](Regs& r, long long ch) {
+    const bool live = ch < chunk1;
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) {
+      const int b = t + kThreads * i, cc = b % (TC / 8), pair = b / (TC / 8);
+      const long long p = ch * 64 + 2 * pair;
+      const int co = co0 + 8 * cc, ci = ci0 + 8 * cc;
+      r.z0[i] = (live && p < P && co < g.Co) ? ldg16(dZ + (size_t)p * g.Co + co) : zero16();
+      r.z1[i] = (live && p + 1 < P && co < g.Co) ? ldg16(dZ + (size_t)(p + 1) * g.Co + co) : zero16();
+      uint4 xv[2];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const long long pp = p + h;
+        bool ok = live && pp < P && ci < g.Ci;
+        long long off = 0;
+        if (ok) {
+          const int wo = (int)(pp % g.Wo);
+          const long long q = pp / g.Wo;
+          const int ho = (int)(q % g.Ho);
+          const int hi = ho * g.stride - g.ph + ta, wi = wo * g.stride - g.pw + tb;
+          ok = hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
+          off = (((q / g.Ho) * g.H + hi) * (long long)g.W + wi) * g.Ci + ci;
+        }
+        xv[h] = ok ? ldg16(X + off) : zero16();
+      }
+      r.x0[i] = xv[0];
+      r.x1[i] = xv[1];
+    }
+  };
+  auto sstore = [&](int buf, const Regs& r) {
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) {
+      const int b = t + kThreads * i, cc = b % (TC / 8), pair = b / (TC / 8);
+      store_transposed_pair<8>(Zt[buf], 8 * cc, pair, r.z0[i], r.z1[i]);
+      store_transposed_pair<8>(Xt[buf], 8 * cc, pair, r.x0[i], r.x1[i]);
+    }
+  };
+
+  f32x16 acc[WB][WB];
+#pragma unroll
+  for (int i = 0; i < WB; ++i)
+#pragma unroll
+    for (int j = 0; j < WB; ++j) acc[i][j] = f32x16{0};
+  float bsum = 0.f;
+
+  if (chunk0 < chunk1) {
+    Regs R;
+    gload(R, chunk0);
+    sstore(0, R);
+    __syncthreads();
+    for (long long ch = chunk0; ch < chunk1; ++ch) {
+      const int cur = (int)((ch - chunk0) & 1);
+      gload(R, ch + 1);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int grp = 2 * ks + (l >> 5);
+        uint4 a[WB], b[WB];
+#pragma unroll
+        for (int i = 0; i < WB; ++i) a[i] = load_swizzled_frag<8>(Zt[cur], 32 * (WB * wr + i) + (l & 31), grp);
+#pragma unroll
+        for (int j = 0; j < WB; ++j) b[j] = load_swizzled_frag<8>(Xt[cur], 32 * (WB * wc + j) + (l & 31), grp);
+#pragma unroll
+        for (int i = 0; i < WB; ++i)
+#pragma unroll
+          for (int j = 0; j < WB; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[j]), acc[i][j], 0, 0, 0);
+      }
+      if (do_bias && t < TC) {  // this channel's 64 dz values of the chunk, in pixel order
+#pragma unroll
+        for (int grp = 0; grp < 8; ++grp) {
+          const uint4 v = load_swizzled_frag<8>(Zt[cur], t, grp);
+          const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            bsum += bf2f((uint16_t)(ww[q] & 0xffffu));
+            bsum += bf2f((uint16_t)(ww[q] >> 16));
+          }
+        }
+      }
+      if (ch + 1 < chunk1) sstore(cur ^ 1, R);
+      __syncthreads();
+    }
+  }
+
+  const size_t n_w = (size_t)g.Co * taps * g.Ci;
+  float* out = part + (size_t)blockIdx.y * (n_w + g.Co);
+#pragma unroll
+  for (int j = 0; j < WB; ++j) {
+    const int ci = ci0 + 32 * (WB * wc + j) + (l & 31);
+    if (ci >= g.Ci) continue;
+#pragma unroll
+    for (int i = 0; i < WB; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int co = co0 + 32 * (WB * wr + i) + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        if (co < g.Co) out[((size_t)co * taps + tap) * g.Ci + ci] = acc[i][j][r];
+      }
+  }
+  if (do_bias && t < TC && co0 + t < g.Co) out[n_w + co0 + t] = bsum;
+}
+
+// g[e] = sum over splits of part[s][e] in split order; then m <- mu*m + g; w <- w - lr*m; ring <- bf16(w).
+// e < n_w addresses the weights, e >= n_w the bias.
+__global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* __restrict__ part, int splits,
+                                                                  size_t n_w, int n_b, float* __restrict__ master_w,
+                                                                  float* __restrict__ mom_w, bf16_t* __restrict__ ring_w,
+                                                                  float* __restrict__ master_b, float* __restrict__ mom_b,
+                                                                  bf16_t* __restrict__ ring_b, float lr, float mu) {
+  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t n = n_w + n_b;
+  if (e >= n) return;
+  float gsum = 0.f;
+  for (int s = 0; s < splits; ++s) gsum += part[(size_t)s * n + e];
+  float* ms = e < n_w ? master_w + e : master_b + (e - n_w);
+  float* mm = e < n_w ? mom_w + e : mom_b + (e - n_w);
+  bf16_t* rr = e < n_w ? ring_w + e : ring_b + (e - n_w);
+  const float m = mu * *mm + gsum;
+  const float wv = *ms - lr * m;
+  *mm = m;
+  *ms = wv;
+  *rr = f2bf(wv);
+}
+
+// ------------------------------------------------------------------------------------------------
+// convolutions with a tiny reduction (kh*kw*Ci <= 32): one 32-wide reduction row per output pixel.
+// Forward: 256 pixels per workgroup, all Co <= 64 channels.
+// ------------------------------------------------------------------------------------------------
+constexpr int SK = 32, SLD = SK + 8;
+
+__device__ __forceinline__ void gather_pixel_row(const bf16_t* __restrict__ X, const ConvGeom& g, long long p,
+                                                 long long P, bf16_t* row /* SK entries in LDS, stride 1 */) {
+  const int K = g.kh * g.kw * g.Ci;
+  int ho = 0, wo = 0;
+  long long nb = 0;
+  const bool live = p < P;
+  if (live) {
+    wo = (int)(p % g.Wo);
+    const long long q = p / g.Wo;
+    ho = (int)(q % g.Ho);
+    nb = (q / g.Ho) * (long long)g.H * g.W * g.Ci;
+  }
+  int k = 0;
+  for (int a = 0; a < g.kh; ++a) {
+    const int hi = ho * g.stride - g.ph + a;
+    for (int b = 0; b < g.kw; ++b) {
+      const int wi = wo * g.stride - g.pw + b;
+      const bool ok = live && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
+      const bf16_t* src = X + nb + ((long long)hi * g.W + wi) * g.Ci;
+      for (int c = 0; c < g.Ci; ++c, ++k) row[k] = ok ? src[c] : (bf16_t)0;
+    }
+  }
+  for (; k < SK; ++k) row[k] = 0;
+  (void)K;
+}
+
+__global__ __launch_bounds__(kThreads) void conv_smallk_fwd_kernel(const bf16_t* __restrict__ X,
+                                                                   const bf16_t* __restrict__ Wg, ConvGeom g,
+                                                                   ConvEpilogue ep) {
+  __shared__ __attribute__((aligned(16))) bf16_t As[256 * SLD];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[64 * SLD];
+  const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  const long long p0 = (long long)blockIdx.x * 256;
+  const int K = g.kh * g.kw * g.Ci;
+  gather_pixel_row(X, g, p0 + t, P, &As[t * SLD]);
+  for (int e = t; e < 64 * SK; e += kThreads) {
+    const int co = e / SK, k = e % SK;
+    Bs[co * SLD + k] = (co < g.Co && k < K) ? Wg[(size_t)co * K + k] : (bf16_t)0;
+  }
+  __syncthreads();
+  f32x16 acc[2][2] = {{f32x16{0}, f32x16{0}}, {f32x16{0}, f32x16{0}}};
+#pragma unroll
+  for (int ks = 0; ks < SK / 16; ++ks) {
+    const int kk = ks * 16 + (l >> 5) * 8;
+    uint4 a[2], b[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const uint4*>(&As[(64 * w + 32 * i + (l & 31)) * SLD + kk]);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const uint4*>(&Bs[(32 * j + (l & 31)) * SLD + kk]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[j]), acc[i][j], 0, 0, 0);
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int c = 32 * j + (l & 31);
+    if (c >= g.Co) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const long long p = p0 + 64 * w + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        if (p < P) store_out(ep, acc[i][j][r], (size_t)p * g.Co + c, c);
+      }
+  }
+}
+
+// Weight gradient of the tiny-reduction convolution.  grid.x = splits; each workgroup walks chunks of 256
+// pixels; wave w reduces pixels 64w..64w+63 of every chunk; the four waves' sums are added in wave order.
+// part[split][e] with e = co*K + k (K = kh*kw*Ci) for the weights and n_w + co for the bias.
+__global__ __launch_bounds__(kThreads) void conv_smallk_wgrad_kernel(const bf16_t* __restrict__ dZ,
+                                                                     const bf16_t* __restrict__ X,
+                                                                     float* __restrict__ part, ConvGeom g,
+                                                                     int chunks_per_split) {
+  __shared__ __attribute__((aligned(16))) bf16_t Arow[256 * SLD];   // gathered inputs, [pixel][k]
+  __shared__ __attribute__((aligned(16))) uint32_t Zt[4][64 * 32];  // per wave: [co][64 pixels], swizzled
+  __shared__ __attribute__((aligned(16))) uint32_t At[4][32 * 32];  // per wave: [k][64 pixels], swizzled
+  __shared__ float red[4][64 * 33];
+  __shared__ float bred[4][64];
+  const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  const int K = g.kh * g.kw * g.Ci;
+  const long long nchunks_total = (P + 255) / 256;
+  const long long chunk0 = (long long)blockIdx.x * chunks_per_split;
+  long long chunk1 = chunk0 + chunks_per_split;
+  if (chunk1 > nchunks_total) chunk1 = nchunks_total;
+  f32x16 acc[2] = {f32x16{0}, f32x16{0}};  // [co block][k 0..31]
+  float bsum = 0.f;
+  for (long long ch = chunk0; ch < chunk1; ++ch) {
+    const long long p0 = ch * 256;
+    gather_pixel_row(X, g, p0 + t, P, &Arow[t * SLD]);
+    // dz of this wave's 64 pixels, transposed: 32 pixel pairs x 8 channel chunks = 256 blocks, 4 per lane
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int b = l + 64 * i, cc = b & 7, pair = b >> 3;
+      const long long p = p0 + 64 * w + 2 * pair;
+      const int co = 8 * cc;
+      const uint4 z0 = (p < P && co < g.Co) ? ldg16(dZ + (size_t)p * g.Co + co) : zero16();
+      const uint4 z1 = (p + 1 < P && co < g.Co) ? ldg16(dZ + (size_t)(p + 1) * g.Co + co) : zero16();
+      store_transposed_pair<8>(Zt[w], 8 * cc, pair, z0, z1);
+    }
+    __syncthreads();
+    // gathered rows of this wave's pixels, transposed: At[k][pixel]
+    for (int e = l; e < 32 * 32; e += 64) {
+      const int k = e >> 5, pair = e & 31;
+      const uint32_t lo = Arow[(64 * w + 2 * pair) * SLD + k], hi = Arow[(64 * w + 2 * pair + 1) * SLD + k];
+      At[w][k * 32 + swz<8>(k, pair >> 2) * 4 + (pair & 3)] = lo | (hi << 16);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int grp = 2 * ks + (l >> 5);
+      const uint4 b = load_swizzled_frag<8>(At[w], (l & 31), grp);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const uint4 a = load_swizzled_frag<8>(Zt[w], 32 * i + (l & 31), grp);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a), frag(b), acc[i], 0, 0, 0);
+      }
+    }
+    {  // bias: lane = channel, this wave's 64 pixels in order
+#pragma unroll
+      for (int grp = 0; grp < 8; ++grp) {
+        const uint4 v = load_swizzled_frag<8>(Zt[w], l, grp);
+        const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          bsum += bf2f((uint16_t)(ww[q] & 0xffffu));
+          bsum += bf2f((uint16_t)(ww[q] >> 16));
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // cross-wave reduction in wave order
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int co = 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+      red[w][co * 33 + (l & 31)] = acc[i][r];
+    }
+  bred[w][l] = bsum;
+  __syncthreads();
+  const size_t n_w = (size_t)g.Co * K;
+  float* out = part + (size_t)blockIdx.x * (n_w + g.Co);
+  for (int e = t; e < 64 * 32; e += kThreads) {
+    const int co = e >> 5, k = e & 31;
+    if (co < g.Co && k < K) out[(size_t)co * K + k] = ((red[0][co * 33 + k] + red[1][co * 33 + k]) + red[2][co * 33 + k]) + red[3][co * 33 + k];
+  }
+  if (t < 64 && t < g.Co) out[n_w + t] = ((bred[0][t] + bred[1][t]) + bred[2][t]) + bred[3][t];
+}
+
+// ------------------------------------------------------------------------------------------------
+// 2x2 / stride-2 max pooling over NHWC, 8 channels (16 bytes) per thread.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void unpack8(uint4 v, uint16_t* o) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    o[2 * q] = (uint16_t)(w[q] & 0xffffu);
+    o[2 * q + 1] = (uint16_t)(w[q] >> 16);
+  }
+}
+__device__ __forceinline__ uint4 pack8(const uint16_t* o) {
+  return make_uint4(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16), o[4] | ((uint32_t)o[5] << 16),
+                    o[6] | ((uint32_t)o[7] << 16));
+}
+
+__global__ __launch_bounds__(256) void maxpool2x2_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
+                                                             int N, int H, int W, int C) {
+  const int Ho = H / 2, Wo = W / 2, C8 = C / 8;
+  const size_t total = (size_t)N * Ho * Wo * C8;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c8 = (int)(idx % C8);
+  size_t q = idx / C8;
+  const int wo = (int)(q % Wo);
+  q /= Wo;
+  const int ho = (int)(q % Ho);
+  const size_t n = q / Ho;
+  float best[8];
+  uint16_t bo[8];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      uint16_t v[8];
+      unpack8(ldg16(x + ((n * H + 2 * ho + a) * W + 2 * wo + b) * C + 8 * c8), v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float f = bf2f(v[j]);
+        if ((a == 0 && b == 0) || f > best[j]) {
+          best[j] = f;
+          bo[j] = v[j];
+        }
+      }
+    }
+  *reinterpret_cast<uint4*>(y + ((n * Ho + ho) * Wo + wo) * C + 8 * c8) = pack8(bo);
+}
+
+// dx[window] = dy at the first position whose value equals the window maximum, else 0; with relu_mask also 0
+// where x <= 0 (the ReLU of the layer that produced x).
+__global__ __launch_bounds__(256) void maxpool2x2_bwd_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ y,
+                                                             const bf16_t* __restrict__ dy, bf16_t* __restrict__ dx,
+                                                             int N, int H, int W, int C, int relu_mask) {
+  const int Ho = H / 2, Wo = W / 2, C8 = C / 8;
+  const size_t total = (size_t)N * Ho * Wo * C8;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c8 = (int)(idx % C8);
+  size_t q = idx / C8;
+  const int wo = (int)(q % Wo);
+  q /= Wo;
+  const int ho = (int)(q % Ho);
+  const size_t n = q / Ho;
+  uint16_t yv[8], dv[8];
+  const size_t yoff = ((n * Ho + ho) * Wo + wo) * C + 8 * c8;
+  unpack8(ldg16(y + yoff), yv);
+  unpack8(ldg16(dy + yoff), dv);
+  bool taken[8] = {false, false, false, false, false, false, false, false};
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const size_t xoff = ((n * H + 2 * ho + a) * W + 2 * wo + b) * C + 8 * c8;
+      uint16_t xv[8], o[8];
+      unpack8(ldg16(x + xoff), xv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const bool hit = !taken[j] && bf2f(xv[j]) == bf2f(yv[j]);
+        taken[j] = taken[j] || hit;
+        o[j] = (hit && (!relu_mask || bf_positive(xv[j]))) ? dv[j] : (uint16_t)0;
+      }
+      *reinterpret_cast<uint4*>(dx + xoff) = pack8(o);
+    }
+}
+
+int wgrad_splits(long long chunks, int tiles) {
+  long long s = 3072 / (tiles > 0 ? tiles : 1);
+  if (s > chunks / 16) s = chunks / 16;
+  if (s > 1024) s = 1024;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+}  // namespace
+
+bool conv_is_smallk(const ConvGeom& g) { return g.kh * g.kw * g.Ci <= SK && g.Co <= 64; }
+
+int conv_wgrad_split_count(const ConvGeom& g) {
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  if (conv_is_smallk(g)) return wgrad_splits((P + 255) / 256, 1);
+  const int TC = (g.Co >= 128 && g.Ci >= 128) ? 128 : 64;
+  const int tiles = ((g.Co + TC - 1) / TC) * ((g.Ci + TC - 1) / TC) * g.kh * g.kw;
+  return wgrad_splits((P + 63) / 64, tiles);
+}
+
+hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g,
+                             const ConvEpilogue& ep) {
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  if (conv_is_smallk(g)) {
+    conv_smallk_fwd_kernel<<<(unsigned)((P + 255) / 256), kThreads, 0, s>>>(x, w, g, ep);
+  } else {
+    if (g.Ci % 8) return hipErrorInvalidValue;
+    dim3 grid((g.Co + CN - 1) / CN, (unsigned)((P + CM - 1) / CM));
+    conv_igemm_kernel<<<grid, kThreads, 0, s>>>(x, w, g, ep);
+  }
+  return hipGetLastError();
+}
+
+hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf16_t* wt_scratch, const ConvGeom& g,
+                           const ConvEpilogue& ep) {
+  if (g.stride != 1 || (g.Co % 8)) return hipErrorInvalidValue;
+  const size_t n = (size_t)g.Co * g.kh * g.kw * g.Ci;
+  flip_transpose_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(w, wt_scratch, g.Co, g.kh, g.kw, g.Ci);
+  ConvGeom t = g;  // the transposed convolution: dL/dy [N][Ho][Wo][Co] -> dL/dx [N][H][W][Ci]
+  t.H = g.Ho; t.W = g.Wo; t.Ci = g.Co; t.Ho = g.H; t.Wo = g.W; t.Co = g.Ci;
+  t.ph = g.kh - 1 - g.ph; t.pw = g.kw - 1 - g.pw;
+  const long long P = (long long)t.N * t.Ho * t.Wo;
+  dim3 grid((t.Co + CN - 1) / CN, (unsigned)((P + CM - 1) / CM));
+  conv_igemm_kernel<<<grid, kThreads, 0, s>>>(dz, wt_scratch, t, ep);
+  return hipGetLastError();
+}
+
+hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
+                                   const ConvGeom& g) {
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  if (conv_is_smallk(g)) {
+    const long long chunks = (P + 255) / 256;
+    conv_smallk_wgrad_kernel<<<splits, kThreads, 0, s>>>(dz, x, part, g, (int)((chunks + splits - 1) / splits));
+    return hipGetLastError();
+  }
+  if ((g.Ci % 8) || (g.Co % 8)) return hipErrorInvalidValue;
+  const long long chunks = (P + 63) / 64;
+  const int cps = (int)((chunks + splits - 1) / splits);
+  if (g.Co >= 128 && g.Ci >= 128) {
+    dim3 grid(((g.Co + 127) / 128) * ((g.Ci + 127) / 128) * g.kh * g.kw, splits);
+    conv_wgrad_kernel<128><<<grid, kThreads, 0, s>>>(dz, x, part, g, cps);
+  } else {
+    dim3 grid(((g.Co + 63) / 64) * ((g.Ci + 63) / 64) * g.kh * g.kw, splits);
+    conv_wgrad_kernel<64><<<grid, kThreads, 0, s>>>(dz, x, part, g, cps);
+  }
+  return hipGetLastError();
+}
+
+hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t n_w, int n_b, float* master_w,
+                               float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b, bf16_t* ring_b, float lr,
+                               float mu) {
+  const size_t n = n_w + n_b;
+  wgrad_reduce_update_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, splits, n_w, n_b, master_w, mom_w,
+                                                                         ring_w, master_b, mom_b, ring_b, lr, mu);
+  return hipGetLastError();
+}
+
+hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, int N, int H, int W, int C) {
+  if ((C % 8) || (H % 2) || (W % 2)) return hipErrorInvalidValue;
+  const size_t total = (size_t)N * (H / 2) * (W / 2) * (C / 8);
+  maxpool2x2_fwd_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(x, y, N, H, W, C);
+  return hipGetLastError();
+}
+
+hipError_t maxpool2x2_backward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* y, const bf16_t* dy, bf16_t* dx, int N,
+                                    int H, int W, int C, bool relu_mask) {
+  if ((C % 8) || (H % 2) || (W % 2)) return hipErrorInvalidValue;
+  const size_t total = (size_t)N * (H / 2) * (W / 2) * (C / 8);
+  maxpool2x2_bwd_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(x, y, dy, dx, N, H, W, C, relu_mask ? 1 : 0);
+  return hipGetLastError();
+}
+
+}  // namespace pd

@@ -13,50 +13,13 @@
 // A and B always take their 8 reduction elements from the same positions, so any fixed permutation
 // of the reduction index inside an instruction cancels out.
 #include "bf16_util.h"
+#include "mfma_util.h"
 #include "pd_kernels.h"
 
 namespace pd {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ bf16x8 frag(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-
-constexpr int kThreads = 256;
-constexpr int BM = 64;    // rows of the output tile (minibatch direction)
-
-__device__ __forceinline__ uint4 ldg16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
-__device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
-
-// XOR swizzle of the 16-byte groups of an LDS row that holds 8*G reduction elements of one output row/column
-// (G groups).  Spreads both the transposing 4-byte writes (lanes differ in their column chunk and reduction
-// pair) and the 16-byte fragment reads (lanes differ in their row) over all banks.
-template <int G>
-__device__ __forceinline__ int swz(int row, int group) {
-  return group ^ ((row ^ (row >> 3)) & ((G < 16 ? G : 16) - 1));
-}
-
-// Writes an 8-column x 2-row block (two 16-byte global chunks from consecutive reduction rows `pair`*2,
-// `pair`*2+1) transposed into a swizzled tile: tile row = column index, word `pair` of that row.
-template <int G>
-__device__ __forceinline__ void store_transposed_pair(uint32_t* tile, int col0, int pair, uint4 r0, uint4 r1) {
-  const uint32_t a[4] = {r0.x, r0.y, r0.z, r0.w};
-  const uint32_t b[4] = {r1.x, r1.y, r1.z, r1.w};
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const uint32_t lo = (a[q] & 0xffffu) | (b[q] << 16);
-    const uint32_t hi = (a[q] >> 16) | (b[q] & 0xffff0000u);
-    const int row_lo = col0 + 2 * q, row_hi = row_lo + 1;
-    tile[row_lo * (4 * G) + swz<G>(row_lo, pair >> 2) * 4 + (pair & 3)] = lo;
-    tile[row_hi * (4 * G) + swz<G>(row_hi, pair >> 2) * 4 + (pair & 3)] = hi;
-  }
-}
-template <int G>
-__device__ __forceinline__ uint4 load_swizzled_frag(const uint32_t* tile, int row, int group) {
-  return *reinterpret_cast<const uint4*>(tile + row * (4 * G) + swz<G>(row, group) * 4);
-}
+constexpr int BM = 64;  // rows of the skinny GEMM's output tile (minibatch direction)
 
 // ------------------------------------------------------------------------------------------------
 // Skinny GEMM for forward and dgrad:  out[M][C] = A[M][R] * B, fp32 accumulate, then the epilogue.

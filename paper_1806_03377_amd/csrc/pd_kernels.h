@@ -42,6 +42,40 @@ struct WgradBatch {
 };
 hipError_t linear_wgrad_update_bf16(hipStream_t s, const WgradBatch& batch);
 
+// ---- bf16 convolution and pooling, NHWC (conv_bf16.hip) ------------------------------------------------
+struct ConvGeom {
+  int N, H, W, Ci;   // input  [N][H][W][Ci]
+  int Ho, Wo, Co;    // output [N][Ho][Wo][Co]
+  int kh, kw, stride, ph, pw;
+};
+struct ConvEpilogue {
+  const bf16_t* bias;  // [Co] or null
+  const bf16_t* mask;  // same shape as out: value kept where mask > 0; or null
+  int relu;
+  bf16_t* out;
+};
+// kh*kw*Ci <= 32 and Co <= 64 (first layer of an image network): handled by the gather kernels
+bool conv_is_smallk(const ConvGeom& g);
+// y = act(conv(x, w) + b); w[Co][kh][kw][Ci].  Needs Ci % 8 == 0 unless conv_is_smallk.
+hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g,
+                             const ConvEpilogue& ep);
+// dx = convT(dz, w) .* mask, stride 1 only; wt_scratch holds Co*kh*kw*Ci elements (flipped, transposed weights).
+hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf16_t* wt_scratch, const ConvGeom& g,
+                           const ConvEpilogue& ep);
+// Number of partial sums the weight-gradient kernel produces for this geometry, and the kernel itself:
+// part[split][Co*kh*kw*Ci + Co] (weights in w's layout, then the bias gradient).
+int conv_wgrad_split_count(const ConvGeom& g);
+hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
+                                   const ConvGeom& g);
+// g = sum of the partials in split order; m <- mu*m + g; master <- master - lr*m; ring <- bf16(master).
+hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t n_w, int n_b, float* master_w,
+                               float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b, bf16_t* ring_b, float lr,
+                               float mu);
+hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, int N, int H, int W, int C);
+// dx = dy routed to the first maximum of each window (row-major), times (x > 0) if relu_mask
+hipError_t maxpool2x2_backward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* y, const bf16_t* dy, bf16_t* dx, int N,
+                                    int H, int W, int C, bool relu_mask);
+
 // ---- stand-alone update (update.hip) ---------------------------------------------------------------
 // m <- mu*m + g; w_out <- w_in - lr*m; ring <- bf16(w_out) if ring is not null.  g null = zero gradient.
 // All arrays 16-byte aligned.  grid_blocks <= 0 picks the default grid.

@@ -80,14 +80,25 @@ int emit_schedule(int depth, int M, pd_op* out, size_t cap, size_t* n_out) {
   return PD_OK;
 }
 
-struct Linear {
-  int in, out;
-  bool relu;
-  size_t w_off, b_off;    // element offsets inside one parameter set on the device (padded)
-  size_t flat_w, flat_b;  // element offsets inside the caller's flat vector
-  size_t y_off;           // byte offset of this layer's output inside a stash slot
-  size_t dz_off;          // byte offset of dL/d(pre-activation) inside the gradient workspace
+enum { K_LINEAR = 0, K_CONV = 1, K_POOL = 2 };
+
+// One compute layer of the stage.  Activations are [minibatch][h][w][c] (NHWC); a Linear sees its input
+// flattened in that order: in = ih*iw*ic, out = oc with oh = ow = 1.
+struct Layer {
+  int kind = K_LINEAR;
+  int in = 0, out = 0;     // features per sample in / out
+  int ih = 1, iw = 1, ic = 0, oh = 1, ow = 1, oc = 0;
+  int kh = 1, kw = 1, stride = 1, ph = 0, pw = 0;
+  bool relu = false;
+  size_t n_w = 0, n_b = 0;     // parameter counts (0 for pooling)
+  size_t w_off = 0, b_off = 0;    // element offsets inside one parameter set on the device (padded)
+  size_t flat_w = 0, flat_b = 0;  // element offsets inside the caller's flat vector
+  size_t y_off = 0;           // byte offset of this layer's output inside a stash slot
+  size_t dz_off = 0;          // Linear: byte offset of dL/d(pre-activation) inside the gradient workspace
+  size_t part_off = 0;        // conv: byte offset of the weight-gradient partial sums
+  int splits = 0;             // conv: number of partial sums
 };
+typedef Layer Linear;  // (historic name used below for "a layer")
 
 struct InFlight {
   int mb, version;
@@ -109,6 +120,7 @@ struct pd_stage {
   size_t n_params = 0;       // flat length
   size_t p_pad = 0;          // elements per parameter set on the device
   size_t in_bytes = 0, out_bytes = 0, stash_slot_bytes = 0, dlogits_off = 0;
+  size_t pp_bytes = 0;       // one ping-pong gradient buffer of the conv/pool layers
   // device regions (inside the caller's arena)
   char* ring = nullptr;      // depth parameter sets (bf16 or fp32)
   float* master = nullptr;   // bf16 mode only
@@ -117,6 +129,9 @@ struct pd_stage {
   char* stash = nullptr;
   char* dz = nullptr;
   char* grad_in = nullptr;   // 2 slots, stages without a loss
+  char* pp = nullptr;        // two ping-pong activation-gradient buffers (conv/pool layers)
+  char* part = nullptr;      // conv weight-gradient partial sums, all layers
+  char* wt = nullptr;        // flipped/transposed conv weights for dgrad (largest layer)
   float* ws = nullptr;
   size_t ws_bytes = 0;
   float* row_loss = nullptr;
@@ -143,9 +158,10 @@ struct Plan {
   bool has_loss = false, bf16 = false;
   int classes = 0, depth = 1, in_depth = 1, B = 0;
   size_t esz = 4, n_params = 0, p_pad = 0, in_bytes = 0, out_bytes = 0, stash_slot_bytes = 0, dlogits_off = 0;
-  size_t ws_bytes = 0, dz_bytes = 0;
+  size_t ws_bytes = 0, dz_bytes = 0, pp_bytes = 0, part_bytes = 0, wt_bytes = 0;
   // arena offsets
   size_t o_ring = 0, o_master = 0, o_mom = 0, o_in = 0, o_stash = 0, o_dz = 0, o_grad = 0, o_ws = 0, o_rowloss = 0;
+  size_t o_pp = 0, o_part = 0, o_wt = 0;
   size_t total = 0;
 };
 
@@ -162,25 +178,64 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   p.B = c->minibatch;
   p.depth = c->in_flight_override > 0 ? c->in_flight_override : stage_depth(c->num_stages, c->noam, c->stage_index);
   p.in_depth = c->stage_index > 0 ? p.depth + 1 : p.depth;
-  size_t flat = 0, dev = 0, y_off = 0, dz_off = 0;
-  int width = -1;
+  size_t flat = 0, dev = 0, y_off = 0, dz_off = 0, part_off = 0;
+  int width = -1;               // features per sample produced so far (-1: stage input not yet known)
+  int ch = 0, hh = 1, ww = 1;   // its NHWC shape
   for (int i = 0; i < c->n_layers; ++i) {
     const pd_layer_desc& d = c->layers[i];
     if (p.has_loss) return fail(PD_EINVAL, "PD_SOFTMAX_XENT must be the last layer");
     if (d.kind == PD_LINEAR) {
-      Linear L;
+      Layer L;
+      L.kind = K_LINEAR;
       L.in = d.p[0]; L.out = d.p[1]; L.relu = d.p[2] != 0;
       if (L.in < 1 || L.out < 1) return fail(PD_EINVAL, "layer %d: bad Linear shape %dx%d", i, L.out, L.in);
       if (width >= 0 && L.in != width) return fail(PD_EINVAL, "layer %d: in_features %d != previous width %d", i, L.in, width);
       if (p.bf16 && ((L.in % 8) || (L.out % 8)))
         return fail(PD_EINVAL, "layer %d: bf16 mode needs in/out features divisible by 8 (got %d, %d)", i, L.in, L.out);
-      width = L.out;
-      L.flat_w = flat; flat += (size_t)L.in * L.out;
-      L.flat_b = flat; flat += L.out;
-      L.w_off = dev; dev = align_up(dev + (size_t)L.in * L.out, 128);
-      L.b_off = dev; dev = align_up(dev + L.out, 128);
-      L.y_off = y_off; y_off = align_up(y_off + (size_t)p.B * L.out * 4, 256);  // room for fp32 (logits)
+      L.ic = L.in; L.oc = L.out;
+      L.n_w = (size_t)L.in * L.out; L.n_b = L.out;
+      width = L.out; ch = L.out; hh = ww = 1;
       L.dz_off = dz_off; dz_off = align_up(dz_off + (size_t)p.B * L.out * p.esz, 256);
+      p.lin.push_back(L);
+    } else if (d.kind == PD_CONV2D) {
+      Layer L;
+      L.kind = K_CONV;
+      L.ic = d.p[0]; L.oc = d.p[1]; L.kh = d.p[2]; L.kw = d.p[3]; L.stride = d.p[4]; L.ph = d.p[5]; L.pw = d.p[6];
+      L.relu = d.p[7] != 0; L.ih = d.p[8]; L.iw = d.p[9];
+      if (!p.bf16) return fail(PD_EINVAL, "layer %d: convolution is only built for PD_BF16_F32ACC", i);
+      if (L.ic < 1 || L.oc < 1 || L.kh < 1 || L.kw < 1 || L.stride < 1 || L.ph < 0 || L.pw < 0 || L.ih < 1 || L.iw < 1)
+        return fail(PD_EINVAL, "layer %d: bad convolution geometry", i);
+      L.oh = (L.ih + 2 * L.ph - L.kh) / L.stride + 1;
+      L.ow = (L.iw + 2 * L.pw - L.kw) / L.stride + 1;
+      if (L.oh < 1 || L.ow < 1) return fail(PD_EINVAL, "layer %d: empty convolution output", i);
+      L.in = L.ih * L.iw * L.ic; L.out = L.oh * L.ow * L.oc;
+      if (width >= 0 && (L.in != width || L.ic != ch || L.ih != hh || L.iw != ww))
+        return fail(PD_EINVAL, "layer %d: convolution input %dx%dx%d does not match the previous output %dx%dx%d", i,
+                    L.ih, L.iw, L.ic, hh, ww, ch);
+      const bool smallk = L.kh * L.kw * L.ic <= 32 && L.oc <= 64;
+      if (L.oc % 8 || (!smallk && L.ic % 8))
+        return fail(PD_EINVAL, "layer %d: channel counts must be divisible by 8 (a first layer with kh*kw*Cin <= 32 and "
+                    "Cout <= 64 is exempt on the input side); got %d -> %d", i, L.ic, L.oc);
+      L.n_w = (size_t)L.oc * L.kh * L.kw * L.ic; L.n_b = L.oc;
+      pd::ConvGeom g = {p.B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
+      L.splits = pd::conv_wgrad_split_count(g);
+      L.part_off = part_off; part_off = align_up(part_off + (size_t)L.splits * (L.n_w + L.n_b) * 4, 256);
+      if (L.n_w * 2 > p.wt_bytes) p.wt_bytes = align_up(L.n_w * 2, 256);
+      width = L.out; ch = L.oc; hh = L.oh; ww = L.ow;
+      p.lin.push_back(L);
+    } else if (d.kind == PD_MAXPOOL2D) {
+      Layer L;
+      L.kind = K_POOL;
+      L.kh = L.kw = d.p[0]; L.stride = d.p[1]; L.ic = L.oc = d.p[2]; L.ih = d.p[3]; L.iw = d.p[4];
+      if (!p.bf16) return fail(PD_EINVAL, "layer %d: pooling is only built for PD_BF16_F32ACC", i);
+      if (L.kh != 2 || L.stride != 2) return fail(PD_EINVAL, "layer %d: only 2x2 / stride-2 max pooling is built", i);
+      if (L.ic < 8 || L.ic % 8 || L.ih < 2 || L.iw < 2 || (L.ih % 2) || (L.iw % 2))
+        return fail(PD_EINVAL, "layer %d: pooling needs channels divisible by 8 and even height/width", i);
+      L.oh = L.ih / 2; L.ow = L.iw / 2;
+      L.in = L.ih * L.iw * L.ic; L.out = L.oh * L.ow * L.oc;
+      if (width >= 0 && (L.in != width || L.ic != ch || L.ih != hh || L.iw != ww))
+        return fail(PD_EINVAL, "layer %d: pooling input does not match the previous output", i);
+      width = L.out; ch = L.oc; hh = L.oh; ww = L.ow;
       p.lin.push_back(L);
     } else if (d.kind == PD_SOFTMAX_XENT) {
       if (p.lin.empty() || i == 0 || c->layers[i - 1].kind != PD_LINEAR)
@@ -192,8 +247,23 @@ int make_plan(const pd_stage_config* c, Plan& p) {
     } else {
       return fail(PD_EINVAL, "layer %d: unknown kind %d", i, d.kind);
     }
+    if (d.kind != PD_SOFTMAX_XENT) {
+      Layer& L = p.lin.back();
+      if (L.n_w) {
+        L.flat_w = flat; flat += L.n_w;
+        L.flat_b = flat; flat += L.n_b;
+        L.w_off = dev; dev = align_up(dev + L.n_w, 128);
+        L.b_off = dev; dev = align_up(dev + L.n_b, 128);
+      }
+      L.y_off = y_off; y_off = align_up(y_off + (size_t)p.B * L.out * 4, 256);  // room for fp32 (logits)
+      if (L.kind != K_LINEAR) {
+        const size_t ab = align_up((size_t)p.B * (L.in > L.out ? L.in : L.out) * p.esz, 256);
+        if (ab > p.pp_bytes) p.pp_bytes = ab;
+      }
+    }
   }
-  if (p.lin.empty()) return fail(PD_EINVAL, "stage has no Linear layer");
+  if (p.lin.empty()) return fail(PD_EINVAL, "stage has no compute layer");
+  p.part_bytes = part_off;
   p.n_params = flat;
   p.p_pad = dev;
   p.in_bytes = align_up((size_t)p.B * p.lin.front().in * p.esz, 256);
@@ -203,7 +273,8 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   p.stash_slot_bytes = y_off;
   p.dz_bytes = dz_off;
   if (p.bf16)
-    for (const Linear& L : p.lin) {
+    for (const Layer& L : p.lin) {
+      if (L.kind != K_LINEAR) continue;
       const size_t w = pd::gemm_bf16_workspace_bytes(p.B, L.out, L.in);
       if (w > p.ws_bytes) p.ws_bytes = w;
     }
@@ -217,6 +288,9 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   p.o_dz = o; o += p.dz_bytes;
   if (!p.has_loss) { p.o_grad = o; o += 2 * p.out_bytes; }
   p.o_ws = o; o += p.ws_bytes;
+  p.o_pp = o; o += 2 * p.pp_bytes;
+  p.o_part = o; o += p.part_bytes;
+  p.o_wt = o; o += p.wt_bytes;
   p.o_rowloss = o; o += align_up((size_t)p.B * 4, 256);
   p.total = o;
   return PD_OK;
@@ -277,6 +351,7 @@ int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena
   st->grad_in = p.has_loss ? nullptr : a + p.o_grad;
   st->ws = reinterpret_cast<float*>(a + p.o_ws); st->ws_bytes = p.ws_bytes;
   st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
+  st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
   hipError_t e = pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
   if (e != hipSuccess) {
     delete st;
@@ -313,12 +388,13 @@ int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   PD_HIP(hipStreamSynchronize(st->stream));
   float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(st->ring);
   for (const Linear& L : st->lin) {
-    PD_HIP(hipMemcpy(dst32 + L.w_off, host_params + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
-    PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+    if (!L.n_w) continue;
+    PD_HIP(hipMemcpy(dst32 + L.w_off, host_params + L.flat_w, L.n_w * 4, hipMemcpyHostToDevice));
+    PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, L.n_b * 4, hipMemcpyHostToDevice));
     if (st->bf16) {
       pd::bf16_t* r = reinterpret_cast<pd::bf16_t*>(st->ring);
-      PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, (size_t)L.in * L.out));
-      PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, (size_t)L.out));
+      PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, L.n_w));
+      PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, L.n_b));
     }
   }
   PD_HIP(pd::fill_zero(st->stream, st->mom, st->p_pad * 4));
@@ -338,8 +414,9 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
   if (!st->bf16 || from_master) {
     const float* src = from_master ? st->master : reinterpret_cast<const float*>(st->ring_slot(version));
     for (const Linear& L : st->lin) {
-      PD_HIP(hipMemcpy(host_out + L.flat_w, src + L.w_off, (size_t)L.in * L.out * 4, hipMemcpyDeviceToHost));
-      PD_HIP(hipMemcpy(host_out + L.flat_b, src + L.b_off, (size_t)L.out * 4, hipMemcpyDeviceToHost));
+      if (!L.n_w) continue;
+      PD_HIP(hipMemcpy(host_out + L.flat_w, src + L.w_off, L.n_w * 4, hipMemcpyDeviceToHost));
+      PD_HIP(hipMemcpy(host_out + L.flat_b, src + L.b_off, L.n_b * 4, hipMemcpyDeviceToHost));
     }
     return PD_OK;
   }
@@ -356,8 +433,9 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
     return hipSuccess;
   };
   for (const Linear& L : st->lin) {
-    PD_HIP(widen(L.w_off, L.flat_w, (size_t)L.in * L.out));
-    PD_HIP(widen(L.b_off, L.flat_b, (size_t)L.out));
+    if (!L.n_w) continue;
+    PD_HIP(widen(L.w_off, L.flat_w, L.n_w));
+    PD_HIP(widen(L.b_off, L.flat_b, L.n_b));
   }
   return PD_OK;
 }
@@ -368,8 +446,9 @@ int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n) {
   if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "minibatches in flight");
   PD_HIP(hipStreamSynchronize(st->stream));
   for (const Linear& L : st->lin) {
-    PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
-    PD_HIP(hipMemcpy(st->mom + L.b_off, host_mom + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+    if (!L.n_w) continue;
+    PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, L.n_w * 4, hipMemcpyHostToDevice));
+    PD_HIP(hipMemcpy(st->mom + L.b_off, host_mom + L.flat_b, L.n_b * 4, hipMemcpyHostToDevice));
   }
   return PD_OK;
 }
@@ -379,8 +458,9 @@ int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n) {
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   PD_HIP(hipStreamSynchronize(st->stream));
   for (const Linear& L : st->lin) {
-    PD_HIP(hipMemcpy(host_out + L.flat_w, st->mom + L.w_off, (size_t)L.in * L.out * 4, hipMemcpyDeviceToHost));
-    PD_HIP(hipMemcpy(host_out + L.flat_b, st->mom + L.b_off, (size_t)L.out * 4, hipMemcpyDeviceToHost));
+    if (!L.n_w) continue;
+    PD_HIP(hipMemcpy(host_out + L.flat_w, st->mom + L.w_off, L.n_w * 4, hipMemcpyDeviceToHost));
+    PD_HIP(hipMemcpy(host_out + L.flat_b, st->mom + L.b_off, L.n_b * 4, hipMemcpyDeviceToHost));
   }
   return PD_OK;
 }
@@ -393,18 +473,19 @@ int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const floa
   char* slot = st->ring_slot(st->latest);
   float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(slot);
   for (const Linear& L : st->lin) {
+    if (!L.n_w) continue;
     if (host_params) {
-      PD_HIP(hipMemcpy(dst32 + L.w_off, host_params + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
-      PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+      PD_HIP(hipMemcpy(dst32 + L.w_off, host_params + L.flat_w, L.n_w * 4, hipMemcpyHostToDevice));
+      PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, L.n_b * 4, hipMemcpyHostToDevice));
       if (st->bf16) {
         pd::bf16_t* r = reinterpret_cast<pd::bf16_t*>(slot);
-        PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, (size_t)L.in * L.out));
-        PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, (size_t)L.out));
+        PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, L.n_w));
+        PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, L.n_b));
       }
     }
     if (host_mom) {
-      PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, (size_t)L.in * L.out * 4, hipMemcpyHostToDevice));
-      PD_HIP(hipMemcpy(st->mom + L.b_off, host_mom + L.flat_b, (size_t)L.out * 4, hipMemcpyHostToDevice));
+      PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, L.n_w * 4, hipMemcpyHostToDevice));
+      PD_HIP(hipMemcpy(st->mom + L.b_off, host_mom + L.flat_b, L.n_b * 4, hipMemcpyHostToDevice));
     }
   }
   PD_HIP(hipStreamSynchronize(st->stream));
@@ -471,6 +552,7 @@ int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer
       break;
     case 3:
       if (layer < 0 || layer >= nl) return fail(PD_EINVAL, "layer %d out of range", layer);
+      if (st->lin[layer].kind != K_LINEAR) return fail(PD_ESTATE, "layer %d does not keep its output gradient", layer);
       src = (st->has_loss && layer == nl - 1) ? st->stash_slot(mb_id) + st->dlogits_off : st->dz + st->lin[layer].dz_off;
       cnt = (size_t)st->B * st->lin[layer].out;
       break;
@@ -516,18 +598,28 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
   const char* w = st->ring_slot(v);
   if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->B * st->lin.front().in * st->esz));
   const char* a = in;
-  for (const Linear& L : st->lin) {
+  for (const Layer& L : st->lin) {
     char* y = slot + L.y_off;
-    if (st->bf16) {
+    if (L.kind == K_LINEAR) {
+      if (st->bf16) {
+        const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
+        const bool logits = st->has_loss && &L == &st->lin.back();  // logits go to the loss unrounded (fp32)
+        PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, wp + L.b_off,
+                                   reinterpret_cast<pd::bf16_t*>(y), logits ? reinterpret_cast<float*>(y) : nullptr,
+                                   st->B, L.out, L.in, L.relu, st->ws, st->ws_bytes));
+      } else {
+        const float* wp = reinterpret_cast<const float*>(w);
+        PD_HIP(pd::linear_fwd_f32(s, reinterpret_cast<const float*>(a), wp + L.w_off, wp + L.b_off,
+                                  reinterpret_cast<float*>(y), st->B, L.out, L.in, L.relu));
+      }
+    } else if (L.kind == K_CONV) {
       const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
-      const bool logits = st->has_loss && &L == &st->lin.back();  // logits go to the loss unrounded (fp32)
-      PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, wp + L.b_off,
-                                 reinterpret_cast<pd::bf16_t*>(y), logits ? reinterpret_cast<float*>(y) : nullptr,
-                                 st->B, L.out, L.in, L.relu, st->ws, st->ws_bytes));
+      const pd::ConvGeom g = {st->B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
+      const pd::ConvEpilogue ep = {wp + L.b_off, nullptr, L.relu ? 1 : 0, reinterpret_cast<pd::bf16_t*>(y)};
+      PD_HIP(pd::conv_forward_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, g, ep));
     } else {
-      const float* wp = reinterpret_cast<const float*>(w);
-      PD_HIP(pd::linear_fwd_f32(s, reinterpret_cast<const float*>(a), wp + L.w_off, wp + L.b_off,
-                                reinterpret_cast<float*>(y), st->B, L.out, L.in, L.relu));
+      PD_HIP(pd::maxpool2x2_forward_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), reinterpret_cast<pd::bf16_t*>(y),
+                                         st->B, L.ih, L.iw, L.ic));
     }
     a = y;
   }
@@ -555,35 +647,70 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   const char* w = st->ring_slot(v);
   char* slot = st->stash_slot(mb_id);
   const int nl = (int)st->lin.size();
-  const Linear& last = st->lin.back();
-  if (!st->has_loss) {
+  const Layer& last = st->lin.back();
+  // `cur` = dL/d(output of layer l) with layer l's own ReLU mask already applied.  Linear layers keep it in
+  // their own buffer until pd_update (the weight gradient is formed there); conv/pool layers ping-pong.
+  int pp_next = 0;
+  auto buffer_for = [&](int l) -> char* {
+    if (st->lin[l].kind == K_LINEAR) return st->dz + st->lin[l].dz_off;
+    char* b = st->pp + (size_t)pp_next * st->pp_bytes;
+    pp_next ^= 1;
+    return b;
+  };
+  const char* cur;
+  if (st->has_loss) {
+    cur = slot + st->dlogits_off;
+  } else {
+    char* b = buffer_for(nl - 1);
     const size_t n = (size_t)st->B * last.out;
-    if (last.relu) PD_HIP(pd::relu_mask(s, dy_dev, slot + last.y_off, st->dz + last.dz_off, n, st->bf16));
-    else PD_HIP(pd::copy_bytes(s, dy_dev, st->dz + last.dz_off, n * st->esz));
+    if (last.relu) PD_HIP(pd::relu_mask(s, dy_dev, slot + last.y_off, b, n, st->bf16));
+    else PD_HIP(pd::copy_bytes(s, dy_dev, b, n * st->esz));
+    cur = b;
   }
   for (int l = nl - 1; l >= 0; --l) {
-    const Linear& L = st->lin[l];
-    const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
+    const Layer& L = st->lin[l];
+    const char* x = l == 0 ? st->in_slot(mb_id) : slot + st->lin[l - 1].y_off;
+    if (L.kind == K_CONV) {  // weight-gradient partial sums; pd_update reduces them and applies the update
+      const pd::ConvGeom g = {st->B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
+      PD_HIP(pd::conv_wgrad_partial_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur),
+                                         reinterpret_cast<const pd::bf16_t*>(x),
+                                         reinterpret_cast<float*>(st->part + L.part_off), L.splits, g));
+    }
     char* out;
     const char* mask = nullptr;
     if (l > 0) {
-      out = st->dz + st->lin[l - 1].dz_off;
+      out = buffer_for(l - 1);
       if (st->lin[l - 1].relu) mask = slot + st->lin[l - 1].y_off;
     } else {
       if (!dx_dev) break;
       out = static_cast<char*>(dx_dev);
     }
-    if (st->bf16) {
+    if (L.kind == K_LINEAR) {
+      if (st->bf16) {
+        const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
+        PD_HIP(pd::linear_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur), wp + L.w_off,
+                                     reinterpret_cast<const pd::bf16_t*>(mask), reinterpret_cast<pd::bf16_t*>(out),
+                                     st->B, L.out, L.in, st->ws, st->ws_bytes));
+      } else {
+        const float* wp = reinterpret_cast<const float*>(w);
+        PD_HIP(pd::linear_dgrad_f32(s, reinterpret_cast<const float*>(cur), wp + L.w_off,
+                                    reinterpret_cast<const float*>(mask), reinterpret_cast<float*>(out), st->B, L.out,
+                                    L.in));
+      }
+    } else if (L.kind == K_CONV) {
       const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
-      PD_HIP(pd::linear_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz), wp + L.w_off,
-                                   reinterpret_cast<const pd::bf16_t*>(mask), reinterpret_cast<pd::bf16_t*>(out),
-                                   st->B, L.out, L.in, st->ws, st->ws_bytes));
+      const pd::ConvGeom g = {st->B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
+      const pd::ConvEpilogue ep = {nullptr, reinterpret_cast<const pd::bf16_t*>(mask), 0,
+                                   reinterpret_cast<pd::bf16_t*>(out)};
+      PD_HIP(pd::conv_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur), wp + L.w_off,
+                                 reinterpret_cast<pd::bf16_t*>(st->wt), g, ep));
     } else {
-      const float* wp = reinterpret_cast<const float*>(w);
-      PD_HIP(pd::linear_dgrad_f32(s, reinterpret_cast<const float*>(dz), wp + L.w_off,
-                                  reinterpret_cast<const float*>(mask), reinterpret_cast<float*>(out), st->B, L.out,
-                                  L.in));
+      PD_HIP(pd::maxpool2x2_backward_bf16(s, reinterpret_cast<const pd::bf16_t*>(x),
+                                          reinterpret_cast<const pd::bf16_t*>(slot + L.y_off),
+                                          reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out),
+                                          st->B, L.ih, L.iw, L.ic, mask != nullptr));
     }
+    cur = out;
   }
   st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
   st->grad_pending = true;
@@ -603,7 +730,15 @@ int pd_update(pd_stage* st) {
   pd::WgradBatch batch;
   batch.count = 0; batch.M = st->B; batch.lr = st->lr; batch.mu = st->mu;
   for (int l = 0; l < nl; ++l) {
-    const Linear& L = st->lin[l];
+    const Layer& L = st->lin[l];
+    if (L.kind == K_POOL) continue;
+    if (L.kind == K_CONV) {  // partial sums left by pd_backward -> momentum-SGD step into the next ring slot
+      pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
+      PD_HIP(pd::wgrad_reduce_update(s, reinterpret_cast<const float*>(st->part + L.part_off), L.splits, L.n_w,
+                                     (int)L.n_b, st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
+                                     st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr, st->mu));
+      continue;
+    }
     const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
     const char* x = l == 0 ? st->in_slot(mb) : slot + st->lin[l - 1].y_off;
     if (st->bf16) {
@@ -613,7 +748,7 @@ int pd_update(pd_stage* st) {
       W.master_w = st->master + L.w_off; W.mom_w = st->mom + L.w_off; W.ring_w = ro + L.w_off;
       W.master_b = st->master + L.b_off; W.mom_b = st->mom + L.b_off; W.ring_b = ro + L.b_off;
       W.N = L.out; W.K = L.in; W.tile_end = 0;
-      if (batch.count == pd::kMaxWgradLayers || l == nl - 1) {  // all layers of the stage in one launch
+      if (batch.count == pd::kMaxWgradLayers) {
         PD_HIP(pd::linear_wgrad_update_bf16(s, batch));
         batch.count = 0;
       }
@@ -625,6 +760,7 @@ int pd_update(pd_stage* st) {
                                          st->mom + L.b_off, st->B, L.out, L.in, st->lr, st->mu));
     }
   }
+  if (batch.count) PD_HIP(pd::linear_wgrad_update_bf16(s, batch));  // all Linear layers of the stage in one launch
   st->latest = nv;
   st->grad_pending = false;
   st->trace.push_back({PD_OP_U, mb, nv, nv % st->depth});
@@ -759,6 +895,86 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
   W.master_b = master_b; W.mom_b = mom_b; W.ring_b = static_cast<pd::bf16_t*>(ring_out_b);
   W.N = N; W.K = K; W.tile_end = 0;
   PD_HIP(pd::linear_wgrad_update_bf16(static_cast<hipStream_t>(stream), batch));
+  return PD_OK;
+}
+
+static int conv_geom(const int32_t* q, pd::ConvGeom& g) {
+  if (!q) return fail(PD_EINVAL, "geom is null");
+  g.N = q[0]; g.H = q[1]; g.W = q[2]; g.Ci = q[3]; g.Co = q[4]; g.kh = q[5]; g.kw = q[6]; g.stride = q[7];
+  g.ph = q[8]; g.pw = q[9];
+  if (g.N < 1 || g.H < 1 || g.W < 1 || g.Ci < 1 || g.Co < 1 || g.kh < 1 || g.kw < 1 || g.stride < 1 || g.ph < 0 ||
+      g.pw < 0)
+    return fail(PD_EINVAL, "bad convolution geometry");
+  g.Ho = (g.H + 2 * g.ph - g.kh) / g.stride + 1;
+  g.Wo = (g.W + 2 * g.pw - g.kw) / g.stride + 1;
+  if (g.Ho < 1 || g.Wo < 1) return fail(PD_EINVAL, "empty convolution output");
+  if ((g.Co % 8) || (!pd::conv_is_smallk(g) && (g.Ci % 8)))
+    return fail(PD_EINVAL, "channel counts must be divisible by 8 (c_in exempt when kh*kw*c_in <= 32 and c_out <= 64)");
+  return PD_OK;
+}
+
+int pd_conv_wgrad_splits(const int32_t* geom, int32_t* splits) {
+  pd::ConvGeom g;
+  if (conv_geom(geom, g) || !splits) return fail(PD_EINVAL, "bad argument");
+  *splits = pd::conv_wgrad_split_count(g);
+  return PD_OK;
+}
+
+int pd_conv_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, const int32_t* geom,
+                     int32_t relu) {
+  pd::ConvGeom g;
+  if (conv_geom(geom, g)) return PD_EINVAL;
+  if (!x || !w || !y) return fail(PD_EINVAL, "null pointer");
+  const pd::ConvEpilogue ep = {static_cast<const pd::bf16_t*>(b), nullptr, relu ? 1 : 0, static_cast<pd::bf16_t*>(y)};
+  PD_HIP(pd::conv_forward_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(x),
+                               static_cast<const pd::bf16_t*>(w), g, ep));
+  return PD_OK;
+}
+
+int pd_conv_dgrad_bf16(void* stream, const void* dz, const void* w, const void* mask, void* dx, void* wt_scratch,
+                       const int32_t* geom) {
+  pd::ConvGeom g;
+  if (conv_geom(geom, g)) return PD_EINVAL;
+  if (!dz || !w || !dx || !wt_scratch) return fail(PD_EINVAL, "null pointer");
+  if (g.stride != 1) return fail(PD_EINVAL, "dgrad is built for stride 1 only");
+  const pd::ConvEpilogue ep = {nullptr, static_cast<const pd::bf16_t*>(mask), 0, static_cast<pd::bf16_t*>(dx)};
+  PD_HIP(pd::conv_dgrad_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(dz),
+                             static_cast<const pd::bf16_t*>(w), static_cast<pd::bf16_t*>(wt_scratch), g, ep));
+  return PD_OK;
+}
+
+int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float* part_scratch, float* master_w,
+                              float* mom_w, void* ring_out_w, float* master_b, float* mom_b, void* ring_out_b,
+                              const int32_t* geom, float lr, float momentum) {
+  pd::ConvGeom g;
+  if (conv_geom(geom, g)) return PD_EINVAL;
+  if (!dz || !x || !part_scratch || !master_w || !mom_w || !ring_out_w || !master_b || !mom_b || !ring_out_b)
+    return fail(PD_EINVAL, "null pointer");
+  const int splits = pd::conv_wgrad_split_count(g);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  PD_HIP(pd::conv_wgrad_partial_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
+                                     part_scratch, splits, g));
+  PD_HIP(pd::wgrad_reduce_update(s, part_scratch, splits, (size_t)g.Co * g.kh * g.kw * g.Ci, g.Co, master_w, mom_w,
+                                 static_cast<pd::bf16_t*>(ring_out_w), master_b, mom_b,
+                                 static_cast<pd::bf16_t*>(ring_out_b), lr, momentum));
+  return PD_OK;
+}
+
+int pd_maxpool2x2_fwd_bf16(void* stream, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C) {
+  if (!x || !y || N < 1 || H < 2 || W < 2 || C < 8 || (C % 8) || (H % 2) || (W % 2))
+    return fail(PD_EINVAL, "pooling needs even height/width and channels divisible by 8");
+  PD_HIP(pd::maxpool2x2_forward_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(x),
+                                     static_cast<pd::bf16_t*>(y), N, H, W, C));
+  return PD_OK;
+}
+
+int pd_maxpool2x2_bwd_bf16(void* stream, const void* x, const void* y, const void* dy, void* dx, int32_t N, int32_t H,
+                           int32_t W, int32_t C, int32_t relu_mask) {
+  if (!x || !y || !dy || !dx || N < 1 || H < 2 || W < 2 || C < 8 || (C % 8) || (H % 2) || (W % 2))
+    return fail(PD_EINVAL, "pooling needs even height/width and channels divisible by 8");
+  PD_HIP(pd::maxpool2x2_backward_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(x),
+                                      static_cast<const pd::bf16_t*>(y), static_cast<const pd::bf16_t*>(dy),
+                                      static_cast<pd::bf16_t*>(dx), N, H, W, C, relu_mask != 0));
   return PD_OK;
 }
 

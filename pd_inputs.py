@@ -149,3 +149,15 @@ def config2_vgg_fc(in_features: int = 25088, hidden: int = 4096, classes: int = 
             ("linear", hidden, hidden, True),
             ("linear", hidden, classes, False),
             ("softmax_xent", classes)]
+
+
+def config3_vgg_conv(widths=(64, 128, 256)):
+    """VGG16's first three convolution blocks as one stage: 3x3 convolutions (pad 1) with ReLU,
+    2x2 max-pooling after each block: 64-64-pool-128-128-pool-256-256-256-pool on 3-channel images."""
+    a, b, c = widths
+
+    def conv(ci, co):
+        return ("conv2d", ci, co, 3, 3, 1, 1, 1, True)
+
+    return [conv(3, a), conv(a, a), ("maxpool2d", 2, 2), conv(a, b), conv(b, b), ("maxpool2d", 2, 2),
+            conv(b, c), conv(c, c), conv(c, c), ("maxpool2d", 2, 2)]

@@ -41,17 +41,34 @@ TOUCHED_UPDATE = 2.5   # factor for an update whose minibatch had a touched row 
 
 
 def _linears(layers):
-    return [l for l in layers if l[0] == "linear"]
+    """The compute layers of a stage (everything but the loss), in order."""
+    return [l for l in layers if l[0] != "softmax_xent"]
+
+
+def _relu(L):
+    return bool(L[3]) if L[0] == "linear" else (bool(L[8]) if L[0] == "conv2d" else False)
+
+
+def _rows_of(L):
+    """(units, weights per unit) of a parametrised layer: Linear (out, in); conv (c_out, kh*kw*c_in)."""
+    if L[0] == "linear":
+        return L[2], L[1]
+    if L[0] == "conv2d":
+        return L[2], L[3] * L[4] * L[1]
+    return 0, 0
 
 
 def _flat_keep(layers, units):
     """Boolean keep-mask over a stage's flat parameter vector, dropping the rows of flagged units."""
     parts = []
     for li, L in enumerate(_linears(layers)):
-        rows = np.ones(L[2], dtype=bool)
+        n_units, per = _rows_of(L)
+        if not n_units:
+            continue
+        rows = np.ones(n_units, dtype=bool)
         if units.get(li):
             rows[sorted(units[li])] = False
-        parts.append(np.repeat(rows, L[1]))
+        parts.append(np.repeat(rows, per))
         parts.append(rows.copy())
     return np.concatenate(parts)
 
@@ -67,7 +84,7 @@ def _global_order(S, noam, M, depth_override):
 
 
 def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=0, out_grads=None,
-             lr=0.01, mu=0.9, mode="free", compare=True, verbose=False):
+             lr=0.01, mu=0.9, mode="free", compare=True, verbose=False, in_hw=None):
     bf16 = precision == pd.PD_BF16_F32ACC
     omode = "bf16" if bf16 else "f32"
     tol = TOL_BF16 if bf16 else TOL_F32
@@ -80,12 +97,13 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
     if compare:
         for o in os_:
             o.log = {}
+    assert in_hw is None or S == 1, "image stages are driven one at a time here"
     gs = [GpuStage(stage_layers[s], params[s], minibatch=B, precision=precision, stage_index=s, num_stages=S,
-                   noam=noam, in_flight_override=depth_override, lr=lr, momentum=mu) for s in range(S)]
+                   noam=noam, in_flight_override=depth_override, lr=lr, momentum=mu, in_hw=in_hw) for s in range(S)]
     keep = []          # device tensors that must outlive the enqueued work
     losses = torch.zeros(M, dtype=torch.float32, device=dev())
     o_losses = [None] * M
-    o_act, o_grad = {}, {}
+    o_act, o_grad, o_act_size = {}, {}, {}
     touched = {i: set() for i in range(M)}      # rows of minibatch i touched by an ambiguous decision so far
     flips_at, units_at = {}, {}
     n_flips = n_elems = n_strict = n_updates = 0
@@ -103,6 +121,7 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                         o_losses[mb] = loss_o
                     else:
                         o_act[(mb, s)] = y_o
+                        o_act_size[s + 1] = y_o.size // B
                 # ---- GPU ----
                 assert pd.pd_stage_version(g.h) == op.version
                 if s == 0:
@@ -121,10 +140,10 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                 acts_o = o.log[mb]["acts"]
                 rows, units = set(), {}
                 for li, L in enumerate(lin):
-                    y_g = pd.pd_stage_debug_read(g.h, 0, mb, li, (B, L[2])).astype(np.float64)
-                    y_o = acts_o[li + 1]
+                    y_o = acts_o[li + 1].reshape(B, -1)
+                    y_g = pd.pd_stage_debug_read(g.h, 0, mb, li, y_o.shape).astype(np.float64)
                     assert rel_err(y_g, y_o) <= tol, ("forward", s, mb, li, rel_err(y_g, y_o))
-                    if L[3]:
+                    if _relu(L):
                         diff = (y_g > 0) != (y_o > 0)
                         n_elems += diff.size
                         if diff.any():
@@ -132,17 +151,19 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                             lim = tol * np.abs(y_o).max()
                             assert np.all(np.abs(y_g[diff]) <= lim) and np.all(np.abs(y_o[diff]) <= lim)
                             rows |= set(np.nonzero(diff)[0].tolist())
-                            units[li] = set(np.nonzero(diff)[1].tolist())
+                            n_units = _rows_of(L)[0]          # conv: the unit is the output channel
+                            units[li] = set((np.nonzero(diff)[1] % n_units).tolist())
                 flips_at[(s, mb)] = rows
                 units_at[(s, mb)] = units
                 if s < S - 1:   # the hand-off: the next stage's input slot holds exactly this output
-                    nxt = pd.pd_stage_debug_read(gs[s + 1].h, 1, mb, 0, (B, lin[-1][2]))
-                    assert np.array_equal(nxt, pd.pd_stage_debug_read(g.h, 0, mb, len(lin) - 1, (B, lin[-1][2])))
+                    shp = acts_o[-1].reshape(B, -1).shape
+                    nxt = pd.pd_stage_debug_read(gs[s + 1].h, 1, mb, 0, shp)
+                    assert np.array_equal(nxt, pd.pd_stage_debug_read(g.h, 0, mb, len(lin) - 1, shp))
                 if verbose:
                     print(f"F stage {s} mb {mb} v{op.version}: rows with ambiguous ReLU decisions {len(rows)} "
                           f"(total elements {n_flips}/{n_elems})", flush=True)
             elif op.kind == OP_B:
-                n_in = lin[0][1]
+                n_in = int(np.asarray(xs[0]).size // B) if s == 0 else (lin[0][1] if lin[0][0] == "linear" else int(o_act_size[s]))
                 if compare:
                     if s == S - 1:
                         dy_o = None if has_loss else np.asarray(out_grads[mb], dtype=np.float64)
@@ -151,6 +172,7 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                     dx_o = o.backward(mb, dy_o, need_dx=True)
                     if s > 0:
                         o_grad[(mb, s)] = dx_o
+                    dx_o = dx_o.reshape(B, -1)
                 assert pd.pd_stage_version(g.h, mb) == op.version
                 if s == S - 1:
                     dyptr = 0

@@ -185,6 +185,168 @@ def test_one_row_minibatch_and_depth_one():
 
 
 # ---------------------------------------------------------------------------------------------
+# convolution and pooling kernels on their own: identical inputs on both sides, element by element
+# ---------------------------------------------------------------------------------------------
+CONVS = [  # N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w
+    (2, 12, 12, 3, 64, 3, 3, 1, 1, 1),      # first layer of an image network (27-wide reduction)
+    (3, 10, 10, 3, 16, 3, 3, 1, 1, 1),      # same path, fewer channels, ragged pixel count
+    (2, 9, 11, 16, 24, 3, 3, 1, 1, 1),      # generic path, ragged everything
+    (1, 16, 16, 64, 64, 3, 3, 1, 1, 1),
+    (2, 8, 8, 128, 128, 3, 3, 1, 1, 1),     # 128-wide weight-gradient tiles
+    (2, 8, 8, 136, 200, 3, 3, 1, 1, 1),     # ... with ragged channel tiles
+    (2, 12, 12, 32, 48, 1, 1, 1, 0, 0),     # 1x1
+    (2, 17, 17, 16, 16, 1, 7, 1, 0, 3),     # 1x7
+    (2, 17, 17, 16, 16, 7, 1, 1, 3, 0),     # 7x1
+    (1, 40, 40, 8, 8, 3, 3, 1, 1, 1),       # many pixels, few channels
+]
+
+
+def _conv_data(geom):
+    N, H, W, ci, co, kh, kw, stride, ph, pw = geom
+    x = _bf(gen.normal(SEED, "cx", (N, H, W, ci)))
+    w = _bf(gen.uniform(SEED, "cw", (co, kh, kw, ci), -0.2, 0.2))
+    b = _bf(gen.normal(SEED, "cb", (co,)) * 0.1)
+    return x, w, b
+
+
+@pytest.mark.parametrize("geom", CONVS + [(2, 13, 13, 16, 32, 3, 3, 2, 1, 1), (2, 12, 12, 3, 32, 3, 3, 2, 0, 0)])
+def test_conv_fwd_bf16(geom):
+    N, H, W, ci, co, kh, kw, stride, ph, pw = geom
+    x, w, b = _conv_data(geom)
+    s = torch.cuda.current_stream().cuda_stream
+    xd, wd, bd = to_dev(x, True), to_dev(w, True), to_dev(b, True)
+    for relu in (True, False):
+        ref = OL.conv2d_forward(x, w, b, stride, ph, pw, relu, OL.round_bf16)
+        y = torch.empty(ref.shape, dtype=torch.bfloat16, device=dev())
+        pd.pd_conv_fwd_bf16(s, xd.data_ptr(), wd.data_ptr(), bd.data_ptr(), y.data_ptr(), geom, relu)
+        assert rel_err(to_host(y), ref) <= TOL_BF16
+        assert np.max(np.abs(to_host(y) - ref) / np.maximum(np.abs(ref), 1e-2)) < 2 ** -6   # at most one bf16 step
+
+
+@pytest.mark.parametrize("geom", CONVS)
+def test_conv_dgrad_bf16(geom):
+    N, H, W, ci, co, kh, kw, stride, ph, pw = geom
+    x, w, b = _conv_data(geom)
+    y = OL.conv2d_forward(x, w, b, stride, ph, pw, False, OL.round_bf16)
+    dz = _bf(gen.normal(SEED, "cdz", y.shape) * 0.01)
+    xmask = _bf(np.maximum(gen.normal(SEED, "cm", x.shape), 0.0))
+    s = torch.cuda.current_stream().cuda_stream
+    wt = torch.empty(w.size, dtype=torch.bfloat16, device=dev())
+    dzd, wd, md = to_dev(dz, True), to_dev(w, True), to_dev(xmask, True)
+    for masked in (True, False):
+        ref, _, _ = OL.conv2d_backward(x, w, y, dz, stride, ph, pw, False, True, OL.round_bf16)
+        if masked:
+            ref = ref * (xmask > 0)
+        dx = torch.empty(x.shape, dtype=torch.bfloat16, device=dev())
+        pd.pd_conv_dgrad_bf16(s, dzd.data_ptr(), wd.data_ptr(), md.data_ptr() if masked else 0, dx.data_ptr(),
+                              wt.data_ptr(), geom)
+        assert rel_err(to_host(dx), ref) <= TOL_BF16, masked
+
+
+@pytest.mark.parametrize("geom", CONVS + [(2, 13, 13, 16, 32, 3, 3, 2, 1, 1)])
+def test_conv_wgrad_update_bf16(geom):
+    N, H, W, ci, co, kh, kw, stride, ph, pw = geom
+    x, w, b = _conv_data(geom)
+    y = OL.conv2d_forward(x, w, b, stride, ph, pw, False, OL.round_bf16)
+    dz = _bf(gen.normal(SEED, "cdz", y.shape) * 0.01)
+    w32 = gen.uniform(SEED, "cw32", w.shape, -0.2, 0.2).astype(np.float64)
+    b32 = (gen.normal(SEED, "cb32", (co,)) * 0.1).astype(np.float64)
+    mw = (gen.normal(SEED, "cmw", w.shape) * 0.01).astype(np.float64)
+    mb = (gen.normal(SEED, "cmb", (co,)) * 0.01).astype(np.float64)
+    lr, mu = 0.05, 0.9
+    s = torch.cuda.current_stream().cuda_stream
+    splits = pd.pd_conv_wgrad_splits(geom)
+    part = torch.empty(splits * (w.size + co), dtype=torch.float32, device=dev())
+    wd, bd, mwd, mbd = to_dev(w32, False), to_dev(b32, False), to_dev(mw, False), to_dev(mb, False)
+    rw = torch.empty(w.shape, dtype=torch.bfloat16, device=dev()); rb = torch.empty(co, dtype=torch.bfloat16, device=dev())
+    dzd, xd = to_dev(dz, True), to_dev(x, True)
+    pd.pd_conv_wgrad_update_bf16(s, dzd.data_ptr(), xd.data_ptr(), part.data_ptr(),
+                                 wd.data_ptr(), mwd.data_ptr(), rw.data_ptr(), bd.data_ptr(), mbd.data_ptr(),
+                                 rb.data_ptr(), geom, lr, mu)
+    _, dW, db = OL.conv2d_backward(x, w, y, dz, stride, ph, pw, False, False, OL.round_bf16)
+    f32 = lambda a: a.astype(np.float32).astype(np.float64)
+    m_ref = mu * f32(mw) + dW; w_ref = f32(w32) - lr * m_ref
+    mb_ref = mu * f32(mb) + db; b_ref = f32(b32) - lr * mb_ref
+    assert rel_err(to_host(mwd), m_ref) <= TOL_F32
+    assert rel_err(to_host(wd), w_ref) <= TOL_F32
+    assert rel_err(to_host(mbd), mb_ref) <= TOL_F32
+    assert rel_err(to_host(bd), b_ref) <= TOL_F32
+    assert torch.equal(rw, wd.to(torch.bfloat16)) and torch.equal(rb, bd.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("N,H,W,Cn", [(2, 8, 8, 8), (3, 6, 10, 24), (1, 224, 224, 64)])
+def test_maxpool2x2_bf16(N, H, W, Cn):
+    # bf16 values drawn from a coarse grid so that ties inside windows are common
+    x = _bf(np.round(gen.normal(SEED, "px", (N, H, W, Cn)) * 4) / 4)
+    x = np.maximum(x, 0.0) if Cn == 24 else x
+    s = torch.cuda.current_stream().cuda_stream
+    xd = to_dev(x, True)
+    y_ref = OL.maxpool2d_forward(x, 2, 2)
+    y = torch.empty(y_ref.shape, dtype=torch.bfloat16, device=dev())
+    pd.pd_maxpool2x2_fwd_bf16(s, xd.data_ptr(), y.data_ptr(), N, H, W, Cn)
+    assert np.array_equal(to_host(y), y_ref)
+    dy = _bf(gen.normal(SEED, "pdy", y_ref.shape))
+    dyd = to_dev(dy, True)
+    for relu_mask in (False, True):
+        ref = OL.maxpool2d_backward(x, y_ref, dy, 2, 2)
+        if relu_mask:
+            ref = ref * (x > 0)
+        dx = torch.empty(x.shape, dtype=torch.bfloat16, device=dev())
+        pd.pd_maxpool2x2_bwd_bf16(s, xd.data_ptr(), y.data_ptr(), dyd.data_ptr(), dx.data_ptr(), N, H, W, Cn, relu_mask)
+        assert np.array_equal(to_host(dx), ref), relu_mask       # pure routing: bit-exact
+
+
+# ---------------------------------------------------------------------------------------------
+# convolution / pooling stages (bf16): implicit-GEMM forward and dgrad, transposing wgrad with
+# split pixel ranges, the small-reduction first layer, 2x2 pooling with the first-maximum rule
+# ---------------------------------------------------------------------------------------------
+def _image_stage_case(layers, B, hw, c_in, depth, M, seed=SEED + 2, with_loss=True, lr=0.01, mode="forced",
+                      verbose=False):
+    p = gen.init_params(seed, "c", layers)
+    params = [p + 0.01 * gen.normal(seed, "cb", p.shape)]
+    xs = list(gen.normal(seed, "X", (M, B, hw[0], hw[1], c_in)))
+    o_shape = None
+    labs = dys = None
+    if with_loss:
+        classes = layers[-1][1]
+        labs = list(gen.labels(seed, "Y", (M, B), classes))
+    else:
+        from oracle.pipeline import Stage
+        probe = Stage(layers, params[0], 1, "bf16")
+        o_shape = probe.forward(0, xs[0].astype(np.float64))[0].shape
+        dys = list(gen.normal(seed, "DY", (M,) + tuple(o_shape)) * 0.01)
+    return run_case([layers], params, xs, labs, noam=1, precision=pd.PD_BF16_F32ACC, depth_override=depth,
+                    out_grads=dys, lr=lr, mode=mode, in_hw=hw, verbose=verbose)
+
+
+def test_conv_stage_small_vgg_like():
+    layers = [("conv2d", 3, 16, 3, 3, 1, 1, 1, True), ("conv2d", 16, 16, 3, 3, 1, 1, 1, True), ("maxpool2d", 2, 2),
+              ("conv2d", 16, 32, 3, 3, 1, 1, 1, True), ("maxpool2d", 2, 2), ("linear", 3 * 3 * 32, 16, False),
+              ("softmax_xent", 16)]
+    _image_stage_case(layers, B=3, hw=(12, 12), c_in=3, depth=2, M=5, lr=0.05)
+
+
+def test_conv_stage_wide_channels_no_loss():
+    # 128-channel layers take the 128x128 weight-gradient tiles; 10x10 images give ragged pixel tiles
+    layers = [("conv2d", 8, 128, 3, 3, 1, 1, 1, True), ("conv2d", 128, 128, 3, 3, 1, 1, 1, True), ("maxpool2d", 2, 2),
+              ("conv2d", 128, 72, 3, 3, 1, 1, 1, False)]
+    _image_stage_case(layers, B=3, hw=(10, 10), c_in=8, depth=3, M=4, with_loss=False)
+
+
+def test_conv_stage_free_running_short():
+    layers = [("conv2d", 3, 64, 3, 3, 1, 1, 1, True), ("conv2d", 64, 64, 3, 3, 1, 1, 1, True), ("maxpool2d", 2, 2)]
+    _image_stage_case(layers, B=2, hw=(16, 16), c_in=3, depth=2, M=2, with_loss=False, mode="free")
+
+
+@pytest.mark.timeout(1500)
+def test_config3_vgg_conv_full_geometry_reduced_batch():
+    # the VGG16 conv stage at its real geometry (3 x 224 x 224 images, 64-64-P-128-128-P-256x3-P) with two images
+    # per minibatch, the size the oracle finishes in seconds
+    print("config 3 geometry, minibatch 2: oracle + GPU", flush=True)
+    _image_stage_case(gen.config3_vgg_conv(), B=2, hw=(224, 224), c_in=3, depth=2, M=3, with_loss=False, verbose=True)
+
+
+# ---------------------------------------------------------------------------------------------
 # the whole pipeline.  First op by op against the oracle (serialised), then the same run through
 # pd_pipeline_run with one stream per stage: the kernels are deterministic, so the concurrent run
 # must reproduce the serialised one bit for bit -- any missing inter-stream dependency would show.
