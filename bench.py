@@ -55,6 +55,73 @@ def cpu_baseline(layers, params, xs, labs, depth, budget_s=20.0, max_steps=3):
             "sample": f"{steps} steady-state steps (B,U,F) of the same full-size stage, fp64 numpy, {dt:.1f} s"}
 
 
+def bench_conv(args, pd, gen, torch, np, dev):
+    """Secondary workload: the VGG16 conv stage (64-64-P-128-128-P-256x3-P on 3x224x224 images) as the input
+    stage of a pipeline: depth 4, synthetic upstream gradient, no dL/d(input)."""
+    B, depth, K, W = args.minibatch, args.depth, args.steps, args.warmup
+    hw = (64, 64) if args.small else (224, 224)
+    layers = gen.config3_vgg_conv()
+    seed = gen.BASE_SEED + 2
+    params = gen.init_params(seed, "vgg_conv", layers)
+    stream = torch.cuda.Stream(device=dev)
+    cfg = pd.make_config(layers, in_flight_override=depth, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=0.01,
+                         momentum=0.9, stream=stream.cuda_stream, in_hw=hw)
+    nbytes = pd.pd_stage_query_bytes(cfg)
+    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
+    pd.pd_stage_set_params(h, params)
+    n_pool = 2
+    xd = [torch.from_numpy(gen.normal(seed, f"x{i}", (B, hw[0], hw[1], 3))).to(dev).to(torch.bfloat16) for i in range(n_pool)]
+    oh, ow = hw[0] // 8, hw[1] // 8
+    dyd = [(torch.from_numpy(gen.normal(seed, f"dy{i}", (B, oh, ow, 256))) * 0.01).to(dev).to(torch.bfloat16) for i in range(n_pool)]
+    torch.cuda.synchronize()
+    mb_next = 0
+
+    def fwd():
+        nonlocal mb_next
+        pd.pd_forward(h, mb_next, xd[mb_next % n_pool].data_ptr(), 0, 0, 0)
+        mb_next += 1
+
+    def step(k):
+        pd.pd_backward(h, k, dyd[k % n_pool].data_ptr(), 0)
+        pd.pd_update(h)
+        fwd()
+
+    for _ in range(depth):
+        fwd()
+    k = 0
+    for _ in range(W):
+        step(k); k += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step(k); k += 1
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / K
+    # flops: 2 * pixels * 9 * c_in * c_out per conv forward; dgrad and wgrad the same, no dgrad for the first layer
+    f, h_, w_, fl_first = 0.0, hw[0], hw[1], 0.0
+    for L in layers:
+        if L[0] == "conv2d":
+            fl = 2.0 * B * h_ * w_ * 9 * L[1] * L[2]
+            f += 3 * fl
+            if L[1] == 3:
+                f -= fl
+        else:
+            h_, w_ = h_ // 2, w_ // 2
+    out = {"metric": METRIC, "value": B / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": ("REDUCED " if args.small else "") + f"VGG16 conv stage 64-64-P-128-128-P-256x3-P on 3x{hw[0]}x{hw[1]} "
+                      f"images, bf16 w/ fp32 accum, minibatch {B}, ring depth {depth}, step = B(k) U(k) F(k+depth)",
+                      "minibatch": B, "ring_depth": depth},
+           "step_gflop": f / 1e9, "mfma_util_pct": 100.0 * f / (ms * 1e-3) / MFMA_BF16_PEAK,
+           "roofline": {"bound": "mfma", "kernel": "whole step (conv_igemm_kernel + conv_wgrad_kernel dominate)",
+                        "achieved": f / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                        "frac": f / (ms * 1e-3) / MFMA_BF16_PEAK, "traffic": None}}
+    pd.pd_stage_destroy(h)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +131,8 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv"],
+                    help="vgg16_fc (default, the metric's workload) or vgg16_conv (the conv stage, secondary)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs all pipeline stages on ONE GPU; --gpus must be 1", file=sys.stderr)
@@ -80,6 +149,8 @@ def main():
         sys.exit(3)
     dev = torch.device("cuda:0")
     B, depth, K, W = args.minibatch, args.depth, args.steps, args.warmup
+    if args.workload == "vgg16_conv":
+        return bench_conv(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
     n_in, classes = layers[0][1], layers[-1][1]
     seed = gen.BASE_SEED + 1
