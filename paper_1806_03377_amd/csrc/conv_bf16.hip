@@ -27,35 +27,48 @@ __device__ __forceinline__ void store_out(const ConvEpilogue& ep, float v, size_
 }
 
 // ------------------------------------------------------------------------------------------------
-// implicit-GEMM convolution.  grid = (ceil(Co/64), ceil(N*Ho*Wo/128)); tile 128 pixels x 64 channels,
-// 64 reduction elements per stage, two stages of loads in flight, two LDS buffers.
+// implicit-GEMM convolution.  Every wave owns a 64 x 64 block of the output tile (four 32x32 MFMA
+// accumulators: two A and two B fragments feed four MFMAs per 16-wide reduction step).  The workgroup's
+// four waves are stacked WMW x WNW: 256 pixels x 64 channels for narrow layers, 128 x 128 otherwise.
+// grid = (ceil(Co/BN), ceil(N*Ho*Wo/BM)); 64 reduction elements per stage, two stages of loads in flight
+// in registers, two LDS buffers.  The finished tile is rounded to bf16, staged in LDS and written out (and
+// its ReLU mask read) in 16-byte pieces.  All index arithmetic is 32-bit (the launcher checks the sizes).
 // ------------------------------------------------------------------------------------------------
-constexpr int CM = 128, CN = 64, CK = 64, CLD = CK + 8, CPD = 2;
+constexpr int CK = 64, CLD = CK + 8, CPD = 2;
 
+template <int WMW, int WNW>
 __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __restrict__ X,
                                                               const bf16_t* __restrict__ Wg, ConvGeom g,
                                                               ConvEpilogue ep) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[2][CM * CLD];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][CN * CLD];
-  const int t = threadIdx.x, l = t & 63, w = t >> 6, wm = w >> 1, wn = w & 1;
-  const int co0 = blockIdx.x * CN;
-  const long long P = (long long)g.N * g.Ho * g.Wo;
-  const long long p0 = (long long)blockIdx.y * CM;
+  constexpr int BM_ = 64 * WMW, BN_ = 64 * WNW;
+  constexpr int ACH = BM_ / 32, BCH = BN_ / 32;  // 16-byte chunks per thread and stage
+  constexpr int OLD = BN_ + 8;                   // padded row of the output staging tile (bf16)
+  constexpr int kStageElems = (BM_ + BN_) * CLD;
+  constexpr int kSmemElems = 2 * kStageElems > BM_ * OLD ? 2 * kStageElems : BM_ * OLD;
+  __shared__ __attribute__((aligned(16))) bf16_t smem[kSmemElems];
+  bf16_t* const As0 = smem;
+  bf16_t* const Bs0 = smem + 2 * BM_ * CLD;
+  const int t = threadIdx.x, l = t & 63, w = t >> 6, wm = w / WNW, wn = w % WNW;
+  const int co0 = blockIdx.x * BN_;
+  const int P = g.N * g.Ho * g.Wo;
+  const int p0 = blockIdx.y * BM_;
   const int K = g.kh * g.kw * g.Ci;
   const int T = (K + CK - 1) / CK;
-  const int col = t & 7;
+  const int col = t & 7, trow = t >> 3;
+  const bool aligned_ci = (g.Ci % CK) == 0;  // then a stage lies inside one tap
+  const int per_tap = aligned_ci ? g.Ci / CK : 1;
 
-  // the four pixel rows this thread loads in every stage
-  int hi0[4], wi0[4];
-  long long nbase[4];
+  // the pixel rows this thread loads in every stage
+  int hi0[ACH], wi0[ACH], nbase[ACH];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const long long p = p0 + (t >> 3) + 32 * i;
+  for (int i = 0; i < ACH; ++i) {
+    const int p = p0 + trow + 32 * i;
     if (p < P) {
-      const int wo = (int)(p % g.Wo);
-      const long long q = p / g.Wo;
-      const int ho = (int)(q % g.Ho);
-      nbase[i] = (q / g.Ho) * (long long)g.H * g.W * g.Ci;
+      const unsigned q = (unsigned)p / (unsigned)g.Wo;
+      const int wo = p - (int)q * g.Wo;
+      const unsigned n = q / (unsigned)g.Ho;
+      const int ho = (int)q - (int)n * g.Ho;
+      nbase[i] = (int)n * g.H * g.W * g.Ci;
       hi0[i] = ho * g.stride - g.ph;
       wi0[i] = wo * g.stride - g.pw;
     } else {
@@ -65,33 +78,44 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __re
   }
 
   struct Regs {
-    uint4 a[4], b[2];
+    uint4 a[ACH], b[BCH];
   };
   auto gload = [&](Regs& r, int st) {
-    const int k = st * CK + col * 8;
-    const bool live = st < T && k < K;
-    const int tap = live ? k / g.Ci : 0, ci = live ? k - tap * g.Ci : 0;
+    int tap, ci;
+    bool live = st < T;
+    if (aligned_ci) {  // wave-uniform decode
+      tap = st / per_tap;
+      ci = (st - tap * per_tap) * CK + col * 8;
+    } else {
+      const int k = st * CK + col * 8;
+      live = live && k < K;
+      tap = live ? k / g.Ci : 0;
+      ci = live ? k - tap * g.Ci : 0;
+    }
+    const int k = tap * g.Ci + ci;
     const int ta = tap / g.kw, tb = tap - ta * g.kw;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < ACH; ++i) {
       const int hi = hi0[i] + ta, wi = wi0[i] + tb;
-      const bool ok = live && nbase[i] >= 0 && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
-      r.a[i] = ok ? ldg16(X + nbase[i] + ((long long)hi * g.W + wi) * g.Ci + ci) : zero16();
+      const bool ok = live && nbase[i] >= 0 && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W;
+      r.a[i] = ok ? ldg16(X + (nbase[i] + (hi * g.W + wi) * g.Ci + ci)) : zero16();
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int co = co0 + (t >> 3) + 32 * i;
-      r.b[i] = (live && co < g.Co) ? ldg16(Wg + (size_t)co * K + k) : zero16();
+    for (int i = 0; i < BCH; ++i) {
+      const int co = co0 + trow + 32 * i;
+      r.b[i] = (live && co < g.Co) ? ldg16(Wg + ((size_t)co * K + k)) : zero16();
     }
   };
   auto sstore = [&](int buf, const Regs& r) {
+    bf16_t* as = As0 + buf * BM_ * CLD;
+    bf16_t* bs = Bs0 + buf * BN_ * CLD;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(&As[buf][((t >> 3) + 32 * i) * CLD + col * 8]) = r.a[i];
+    for (int i = 0; i < ACH; ++i) *reinterpret_cast<uint4*>(&as[(trow + 32 * i) * CLD + col * 8]) = r.a[i];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) *reinterpret_cast<uint4*>(&Bs[buf][((t >> 3) + 32 * i) * CLD + col * 8]) = r.b[i];
+    for (int i = 0; i < BCH; ++i) *reinterpret_cast<uint4*>(&bs[(trow + 32 * i) * CLD + col * 8]) = r.b[i];
   };
 
-  f32x16 acc[2] = {f32x16{0}, f32x16{0}};
+  f32x16 acc[2][2] = {{f32x16{0}, f32x16{0}}, {f32x16{0}, f32x16{0}}};
   Regs Rg[CPD];
 #pragma unroll
   for (int p = 0; p < CPD; ++p) gload(Rg[p], p);
@@ -104,15 +128,21 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __re
       const int st = base + j;
       if (st >= T) break;
       const int cur = st & 1;
+      const bf16_t* as = As0 + cur * BM_ * CLD;
+      const bf16_t* bs = Bs0 + cur * BN_ * CLD;
 #pragma unroll
       for (int ks = 0; ks < CK / 16; ++ks) {
         const int kk = ks * 16 + (l >> 5) * 8;
-        const uint4 b = *reinterpret_cast<const uint4*>(&Bs[cur][(32 * wn + (l & 31)) * CLD + kk]);
+        uint4 a[2], b[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const uint4 a = *reinterpret_cast<const uint4*>(&As[cur][(64 * wm + 32 * i + (l & 31)) * CLD + kk]);
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a), frag(b), acc[i], 0, 0, 0);
-        }
+        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const uint4*>(&as[(64 * wm + 32 * i + (l & 31)) * CLD + kk]);
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) b[jj] = *reinterpret_cast<const uint4*>(&bs[(64 * wn + 32 * jj + (l & 31)) * CLD + kk]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int jj = 0; jj < 2; ++jj)
+            acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[jj]), acc[i][jj], 0, 0, 0);
       }
       if (st + 1 < T) {
         sstore(cur ^ 1, Rg[(j + 1) % CPD]);
@@ -122,15 +152,73 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __re
     }
   }
 
-  const int c = co0 + 32 * wn + (l & 31);
-  if (c >= g.Co) return;
+  if ((g.Co & 7) == 0) {
+    // bias / ReLU / rounding in registers, then through LDS so that global traffic is 16 bytes per lane
+    bf16_t* ot = smem;  // [BM_][OLD]; all fragment reads are behind the loop's last barrier
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+    for (int jj = 0; jj < 2; ++jj) {
+      const int cl = 64 * wn + 32 * jj + (l & 31), c = co0 + cl;
+      const float bv = (ep.bias && c < g.Co) ? bf2f(ep.bias[c]) : 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const long long p = p0 + 64 * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-      if (p < P) store_out(ep, acc[i][r], (size_t)p * g.Co + c, c);
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = acc[i][jj][r] + bv;
+          if (ep.relu) v = fmaxf(v, 0.f);
+          ot[(64 * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * OLD + cl] = f2bf(v);
+        }
     }
+    __syncthreads();
+    constexpr int CPR = BN_ / 8;  // 16-byte chunks per tile row
+#pragma unroll
+    for (int i = 0; i < BM_ * CPR / kThreads; ++i) {
+      const int c = t + kThreads * i, row = c / CPR, cc = c % CPR;
+      const int p = p0 + row, co = co0 + cc * 8;
+      if (p >= P || co >= g.Co) continue;
+      uint4 v = *reinterpret_cast<const uint4*>(&ot[row * OLD + cc * 8]);
+      const size_t off = (size_t)p * g.Co + co;
+      if (ep.mask) {
+        const uint4 mk = ldg16(ep.mask + off);
+        const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+        uint32_t vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (!bf_positive((uint16_t)(mw[q] & 0xffffu))) vw[q] &= 0xffff0000u;
+          if (!bf_positive((uint16_t)(mw[q] >> 16))) vw[q] &= 0x0000ffffu;
+        }
+        v = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+      }
+      *reinterpret_cast<uint4*>(ep.out + off) = v;
+    }
+    return;
+  }
+  // channel counts that are not a multiple of 8 (e.g. dL/dx of a 3-channel input): element-wise stores
+#pragma unroll
+  for (int jj = 0; jj < 2; ++jj) {
+    const int c = co0 + 64 * wn + 32 * jj + (l & 31);
+    if (c >= g.Co) continue;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int p = p0 + 64 * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        if (p < P) store_out(ep, acc[i][jj][r], (size_t)p * g.Co + c, c);
+      }
+  }
+}
+
+hipError_t launch_igemm(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g, const ConvEpilogue& ep) {
+  const long long P = (long long)g.N * g.Ho * g.Wo;
+  if ((long long)g.N * g.H * g.W * g.Ci >= (1ll << 31) || P * g.Co >= (1ll << 31) || (g.Ci % 8))
+    return hipErrorInvalidValue;
+  if (g.Co <= 64) {
+    dim3 grid(1, (unsigned)((P + 255) / 256));
+    conv_igemm_kernel<4, 1><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+  } else {
+    dim3 grid((g.Co + 127) / 128, (unsigned)((P + 127) / 128));
+    conv_igemm_kernel<2, 2><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+  }
+  return hipGetLastError();
 }
 
 // wt[ci][kh-1-a][kw-1-b][co] = w[co][a][b][ci]: the weights of the stride-1 convolution that maps dL/dy to dL/dx
@@ -574,9 +662,7 @@ hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, co
   if (conv_is_smallk(g)) {
     conv_smallk_fwd_kernel<<<(unsigned)((P + 255) / 256), kThreads, 0, s>>>(x, w, g, ep);
   } else {
-    if (g.Ci % 8) return hipErrorInvalidValue;
-    dim3 grid((g.Co + CN - 1) / CN, (unsigned)((P + CM - 1) / CM));
-    conv_igemm_kernel<<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    return launch_igemm(s, x, w, g, ep);
   }
   return hipGetLastError();
 }
@@ -589,10 +675,7 @@ hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf1
   ConvGeom t = g;  // the transposed convolution: dL/dy [N][Ho][Wo][Co] -> dL/dx [N][H][W][Ci]
   t.H = g.Ho; t.W = g.Wo; t.Ci = g.Co; t.Ho = g.H; t.Wo = g.W; t.Co = g.Ci;
   t.ph = g.kh - 1 - g.ph; t.pw = g.kw - 1 - g.pw;
-  const long long P = (long long)t.N * t.Ho * t.Wo;
-  dim3 grid((t.Co + CN - 1) / CN, (unsigned)((P + CM - 1) / CM));
-  conv_igemm_kernel<<<grid, kThreads, 0, s>>>(dz, wt_scratch, t, ep);
-  return hipGetLastError();
+  return launch_igemm(s, dz, wt_scratch, t, ep);
 }
 
 hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
