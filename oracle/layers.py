@@ -11,6 +11,10 @@ the standard definition written out:
                   y[n,i,j,o] = b[o] + sum_{a,b,c} x[n, i*s + a - ph, j*s + b - pw, c] W[o,a,b,c]
   MaxPool2d       window k, stride s, no padding; the gradient goes to the FIRST maximum of the
                   window in row-major order (ties do occur among bf16 values)
+  LSTM            time-major sequences x[T][B][I] -> h[T][B][H]; gates (i, f, g, o) =
+                  x_t W_ih^T + h_{t-1} W_hh^T + b with W_ih[4H][I], W_hh[4H][H]; i, f, o = sigmoid,
+                  g = tanh; c_t = f c_{t-1} + i g; h_t = o tanh(c_t); h_{-1} = c_{-1} = 0; backward is
+                  full back-propagation through time
 
 Precision modes.  "f32": no rounding anywhere (pure fp64; the HIP path computes
 in fp32 and is compared at 1e-4).  "bf16": tensors that the mixed-precision path
@@ -18,7 +22,10 @@ keeps in bfloat16 -- ring weights, activations handed between layers and stages,
 activation gradients -- are rounded to the nearest bfloat16 (ties to even) at
 the moment they are stored; sums, bias add, the logits handed to the loss (the
 output of the Linear that feeds softmax cross-entropy), the loss itself, weight
-gradients, master weights and momentum are not rounded.
+gradients, master weights and momentum are not rounded.  Inside an LSTM the hidden
+state h_t (an activation, and the next step's matrix operand) and the gate
+pre-activation gradients (matrix operands of the backward pass) are rounded; gate
+values, the cell state c_t, and the recurrent gradients dh, dc are not.
 """
 from __future__ import annotations
 
@@ -78,6 +85,7 @@ def linear_backward(x, W, y, dy, relu: bool, need_dx: bool, q):
 
 def softmax_xent_forward(z, labels):
     """Mean over rows of -log softmax(z)[label]; also returns softmax(z)."""
+    labels = np.asarray(labels).reshape(-1)
     zmax = z.max(axis=1, keepdims=True)
     e = np.exp(z - zmax)
     ssum = e.sum(axis=1, keepdims=True)
@@ -89,6 +97,7 @@ def softmax_xent_forward(z, labels):
 
 def softmax_xent_backward(p, labels, q):
     """dL/dz for the mean loss: (p - onehot) / rows, stored as an activation gradient."""
+    labels = np.asarray(labels).reshape(-1)
     d = p.copy()
     d[np.arange(p.shape[0]), labels] -= 1.0
     return q(d / p.shape[0])
@@ -171,3 +180,55 @@ def maxpool2d_backward(x, y, dy, k, stride):
             dx[:, a:a + (ho - 1) * stride + 1:stride, b:b + (wo - 1) * stride + 1:stride, :] += np.where(hit, dy, 0.0)
             taken |= hit
     return dx
+
+
+# ---- LSTM, time-major -----------------------------------------------------------
+
+def _sigmoid(a):
+    return 1.0 / (1.0 + np.exp(-a))
+
+
+def lstm_forward(x, W_ih, W_hh, b, q):
+    """x[T][B][I] -> (h[T][B][H] stored, cache for the backward pass)."""
+    T, B, _ = x.shape
+    H = W_hh.shape[1]
+    h_prev = np.zeros((B, H))
+    c_prev = np.zeros((B, H))
+    hs, cs, gates = [], [], []
+    for t in range(T):
+        a = x[t] @ W_ih.T + h_prev @ W_hh.T + b
+        i, f, g, o = _sigmoid(a[:, :H]), _sigmoid(a[:, H:2 * H]), np.tanh(a[:, 2 * H:3 * H]), _sigmoid(a[:, 3 * H:])
+        c = f * c_prev + i * g
+        h = q(o * np.tanh(c))
+        hs.append(h); cs.append(c); gates.append((i, f, g, o))
+        h_prev, c_prev = h, c
+    return np.stack(hs), dict(hs=hs, cs=cs, gates=gates)
+
+
+def lstm_backward(x, W_ih, W_hh, cache, dh_out, need_dx: bool, q):
+    """Back-propagation through time.  dh_out[T][B][H] = dL/dh_t from the layer above.
+    Returns (dx or None, dW_ih, dW_hh, db)."""
+    T, B, _ = x.shape
+    H = W_hh.shape[1]
+    dW_ih, dW_hh, db = np.zeros_like(W_ih), np.zeros_like(W_hh), np.zeros(4 * H)
+    dx = np.zeros_like(x) if need_dx else None
+    dh_rec = np.zeros((B, H))
+    dc_next = np.zeros((B, H))
+    for t in range(T - 1, -1, -1):
+        i, f, g, o = cache["gates"][t]
+        c = cache["cs"][t]
+        c_prev = cache["cs"][t - 1] if t > 0 else np.zeros((B, H))
+        h_prev = cache["hs"][t - 1] if t > 0 else np.zeros((B, H))
+        dh = dh_out[t] + dh_rec
+        tc = np.tanh(c)
+        dc = dc_next + dh * o * (1.0 - tc * tc)
+        da = q(np.concatenate([dc * g * i * (1.0 - i), dc * c_prev * f * (1.0 - f), dc * i * (1.0 - g * g),
+                               dh * tc * o * (1.0 - o)], axis=1))
+        dW_ih += da.T @ x[t]
+        dW_hh += da.T @ h_prev
+        db += da.sum(axis=0)
+        if need_dx:
+            dx[t] = q(da @ W_ih)
+        dh_rec = da @ W_hh
+        dc_next = dc * f
+    return dx, dW_ih, dW_hh, db

@@ -40,19 +40,35 @@ def _split_params(layers, flat):
             W = flat[o:o + n].reshape(c_out, kh, kw, c_in); o += n
             b = flat[o:o + c_out]; o += c_out
             out.append((W, b))
+        elif ly[0] == "lstm":
+            I, H = ly[1], ly[2]
+            W_ih = flat[o:o + 4 * H * I].reshape(4 * H, I); o += 4 * H * I
+            W_hh = flat[o:o + 4 * H * H].reshape(4 * H, H); o += 4 * H * H
+            b = flat[o:o + 4 * H]; o += 4 * H
+            out.append((W_ih, W_hh, b))
         else:
             out.append(None)
     assert o == flat.size, "parameter vector does not match the layer list"
     return out
 
 
+_LSTM_CACHE = {}   # id(stored h sequence) -> gate/cell values of its forward pass, until its backward
+
+
 def _layer_forward(layers, li, p, a, q):
-    """Stored output of layer li for stored input a (loss layers are handled by the caller)."""
+    """Stored output of layer li for stored input a (loss layers are handled by the caller).
+    A Linear after an LSTM acts on every time step: rows = T*B of the time-major sequence."""
     ly = layers[li]
     if ly[0] == "linear":
-        if a.ndim > 2:
+        if li > 0 and layers[li - 1][0] == "lstm":
+            a = a.reshape(-1, a.shape[-1])
+        elif a.ndim > 2:
             a = a.reshape(a.shape[0], -1)          # NHWC flatten
         return L.linear_forward(a, p[0], p[1], ly[3], _out_quantiser(layers, li, q))
+    if ly[0] == "lstm":
+        h, cache = L.lstm_forward(a, p[0], p[1], p[2], q)
+        _LSTM_CACHE[id(h)] = cache
+        return h
     if ly[0] == "conv2d":
         return L.conv2d_forward(a, p[0], p[1], ly[5], ly[6], ly[7], ly[8], q)
     if ly[0] == "maxpool2d":
@@ -63,8 +79,12 @@ def _layer_forward(layers, li, p, a, q):
 def _layer_backward(layers, li, p, x, y, d, need_dx, q):
     """(dx, dW, db) of layer li; dW/db are None for layers without parameters."""
     ly = layers[li]
+    if ly[0] == "lstm":
+        cache = _LSTM_CACHE.pop(id(y))
+        dx, dWi, dWh, db = L.lstm_backward(x, p[0], p[1], cache, d.reshape(y.shape), need_dx, q)
+        return dx, (dWi, dWh), db
     if ly[0] == "linear":
-        x2 = x.reshape(x.shape[0], -1)
+        x2 = x.reshape(-1, x.shape[-1]) if (li > 0 and layers[li - 1][0] == "lstm") else x.reshape(x.shape[0], -1)
         dx, dW, db = L.linear_backward(x2, p[0], y, d, ly[3], need_dx, q)
         if dx is not None:
             dx = dx.reshape(x.shape)
@@ -74,6 +94,16 @@ def _layer_backward(layers, li, p, x, y, d, need_dx, q):
     if ly[0] == "maxpool2d":
         return (L.maxpool2d_backward(x, y, d, ly[1], ly[2]) if need_dx else None), None, None
     raise NotImplementedError(ly[0])
+
+
+def _store_grad(views, dW, db):
+    if isinstance(dW, tuple):          # LSTM: (dW_ih, dW_hh), bias last
+        views[0][...] = dW[0]
+        views[1][...] = dW[1]
+        views[2][...] = db
+    else:
+        views[0][...] = dW
+        views[1][...] = db
 
 
 def _out_quantiser(layers, li, q):
@@ -145,8 +175,7 @@ class Stage:
                 dx, dW, db = _layer_backward(self.layers, li, P[li], acts[k - 1], acts[k], d,
                                              need_dx or not first, self.q)
                 if dW is not None:
-                    G[li][0][...] = dW
-                    G[li][1][...] = db
+                    _store_grad(G[li], dW, db)
                 d = dx
                 k -= 1
         self.grad = g
@@ -287,8 +316,7 @@ def flat_loop(stage_layers: Sequence, stage_params: Sequence, inputs, labels, de
                     need_dx = not (s == 0 and li == 0)
                     dx, dW, db = _layer_backward(stage_layers[s], li, P[li], acts[k - 1], acts[k], d, need_dx, q)
                     if dW is not None:
-                        G[li][0][...] = dW
-                        G[li][1][...] = db
+                        _store_grad(G[li], dW, db)
                     d = dx
                     k -= 1
             mom[s] = momentum * mom[s] + g
