@@ -38,7 +38,8 @@
  *     rows = cfg.minibatch; image activations are [rows][height][width][channels]
  *     (NHWC).  Linear weights are W[out][in], convolution weights W[c_out][kh][kw][c_in].
  *   - Flat parameter vector (pd_stage_set_params and friends): layer by layer in
- *     stage order, each Linear or convolution contributing W then b (out values).
+ *     stage order, each Linear or convolution contributing W then b (out values), an
+ *     LSTM W_ih, W_hh, b.
  */
 #ifndef PD_H_
 #define PD_H_
@@ -83,9 +84,17 @@ typedef enum {
                           divisible by 8, except that a layer with kh*kw*c_in <= 32 and c_out <= 64 (the
                           first layer of an image network) may have any c_in.  dL/d(input) is built for
                           stride 1.                                                                */
-  PD_MAXPOOL2D = 3     /* p[0]=window p[1]=stride p[2]=channels p[3]=in_h p[4]=in_w; only window 2,
+  PD_MAXPOOL2D = 3,    /* p[0]=window p[1]=stride p[2]=channels p[3]=in_h p[4]=in_w; only window 2,
                           stride 2 (even in_h, in_w; channels divisible by 8).  The gradient goes to the
                           first maximum of a window in row-major order.                            */
+  PD_LSTM = 4          /* p[0]=input_size p[1]=hidden p[2]=seq_len.  Sequences are TIME-MAJOR:
+                          x[seq_len][minibatch][input_size] -> h[seq_len][minibatch][hidden]; gates in the
+                          order i, f, g, o = x_t W_ih^T + h_{t-1} W_hh^T + b, c_t = f c_{t-1} + i g,
+                          h_t = o tanh(c_t), zero initial state; backward = full back-propagation through
+                          time.  Parameters: W_ih[4H][I], W_hh[4H][H], b[4H].  Must be first in its stage
+                          or follow another LSTM; layers after it see seq_len*minibatch rows (a Linear
+                          acts on every time step; the loss is the mean over all of them, labels
+                          [seq_len][minibatch]).  PD_BF16_F32ACC only; sizes divisible by 8.          */
 } pd_layer_kind;
 
 typedef struct {

@@ -24,7 +24,7 @@ _lib = C.CDLL(LIB_PATH)
 PD_OK, PD_EINVAL, PD_ESTATE, PD_ENOMEM, PD_EHIP = 0, -1, -2, -3, -4
 PD_F32, PD_BF16_F32ACC = 0, 1
 PD_OP_F, PD_OP_B, PD_OP_U = 0, 1, 2
-PD_LINEAR, PD_SOFTMAX_XENT, PD_CONV2D, PD_MAXPOOL2D = 0, 1, 2, 3
+PD_LINEAR, PD_SOFTMAX_XENT, PD_CONV2D, PD_MAXPOOL2D, PD_LSTM = 0, 1, 2, 3, 4
 
 
 class PdError(RuntimeError):
@@ -153,6 +153,9 @@ def layer_descs(layers: Sequence[tuple], in_hw=None):
             for j, v in enumerate((L[1], L[2], ch, hw[0], hw[1])):
                 arr[i].p[j] = int(v)
             hw = ((hw[0] - L[1]) // L[2] + 1, (hw[1] - L[1]) // L[2] + 1)
+        elif L[0] == "lstm":
+            arr[i].kind = PD_LSTM
+            arr[i].p[0], arr[i].p[1], arr[i].p[2] = int(L[1]), int(L[2]), int(L[3])
         else:
             raise ValueError(f"layer kind {L[0]!r} is not supported by this build")
     return arr

@@ -59,7 +59,7 @@ __device__ __forceinline__ void gemm_store(const GemmEpilogue& ep, float v, int 
 template <bool BT, int BN_, int BK_, int PD, int NBUF>
 __global__ __launch_bounds__(kThreads) void gemm_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm,
                                                         GemmEpilogue ep, float* __restrict__ ws, int M, int C, int R,
-                                                        int splits) {
+                                                        int splits, int lda, int partial_only) {
   constexpr int LDA = BK_ + 8;             // padded row (bf16) of a reduction-contiguous tile
   constexpr int G = BK_ / 8;               // 16-byte groups per row
   constexpr int ACH = BM * G / kThreads;   // 16-byte chunks of A per thread and stage
@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const bf16_t* __restrict
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
       const int c = t + kThreads * i, row = c / G, rr = r0 + (c % G) * 8, m = m0 + row;
-      r.a[i] = (live && m < M && rr < R) ? ldg16(A + (size_t)m * R + rr) : zero16();
+      r.a[i] = (live && m < M && rr < R) ? ldg16(A + (size_t)m * lda + rr) : zero16();
     }
     if (!BT) {
 #pragma unroll
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const bf16_t* __restrict
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + 32 * (MB * wm + i) + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
       if (m >= M) continue;
-      if (splits == 1) gemm_store(ep, acc[i][r], m, c, C);
+      if (splits == 1 && !partial_only) gemm_store(ep, acc[i][r], m, c, C);
       else ws[((size_t)z * M + m) * C + c] = acc[i][r];
     }
 }
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
   float* __restrict__ master_b = L.master_b;
   float* __restrict__ mom_b = L.mom_b;
   bf16_t* __restrict__ ring_b = L.ring_b;
-  const int M = batch.M, N = L.N, K = L.K;
+  const int M = L.M ? L.M : batch.M, N = L.N, K = L.K;
   const float lr = batch.lr, mu = batch.mu;
   constexpr int GLD = TK + 4;
   constexpr int kSlots = TN * TK / 4 / kThreads;  // float4 elements per thread in phase 2
@@ -424,14 +424,22 @@ size_t splitk_bytes_t(int rows, int cols, int red) {
   return s > 1 ? (size_t)s * rows * cols * sizeof(float) : (size_t)0;
 }
 
+// lda = row stride of A (0: dense, = R).  splits_out != null: leave the fp32 partial sums ws[split][M][C]
+// (at least one) for the caller's own epilogue and report how many there are.
 template <bool BT, int BN_, int BK_, int PD, int NBUF>
 hipError_t launch_gemm(hipStream_t s, const bf16_t* a, const bf16_t* b, const GemmEpilogue& ep, int M, int C, int R,
-                       float* ws, size_t ws_bytes) {
+                       float* ws, size_t ws_bytes, int lda = 0, int* splits_out = nullptr) {
   const int tc = (C + BN_ - 1) / BN_, tm = (M + BM - 1) / BM;
   int splits = pick_splits(tc * tm, (R + BK_ - 1) / BK_);
   if (splits > 1 && (!ws || (size_t)splits * M * C * sizeof(float) > ws_bytes)) splits = 1;
   dim3 grid(tc, tm, splits);
-  gemm_kernel<BT, BN_, BK_, PD, NBUF><<<grid, kThreads, 0, s>>>(a, b, ep, ws, M, C, R, splits);
+  if (splits_out) {
+    if (!ws || (size_t)M * C * sizeof(float) > ws_bytes) return hipErrorInvalidValue;
+    *splits_out = splits;
+    gemm_kernel<BT, BN_, BK_, PD, NBUF><<<grid, kThreads, 0, s>>>(a, b, ep, ws, M, C, R, splits, lda ? lda : R, 1);
+    return hipGetLastError();
+  }
+  gemm_kernel<BT, BN_, BK_, PD, NBUF><<<grid, kThreads, 0, s>>>(a, b, ep, ws, M, C, R, splits, lda ? lda : R, 0);
   if (splits > 1) {
     const size_t total4 = (size_t)M * C / 4;
     splitk_epilogue_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(ws, splits, M, C, ep);
@@ -460,6 +468,14 @@ hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, c
   if ((size_t)N * K >= kBigDgradElems)
     return launch_gemm<true, kBigBN, kBigBK, kBigPD, kBigNBUF>(s, dz, w, ep, M, K, N, ws, ws_bytes);
   return launch_gemm<true, kSmallBN, kSmallBK, kSmallPD, kSmallNBUF>(s, dz, w, ep, M, K, N, ws, ws_bytes);
+}
+
+hipError_t gemm_partial_bf16(hipStream_t s, bool w_rows_are_reduction, const bf16_t* a, int lda, const bf16_t* w, int M,
+                             int C, int R, float* ws, size_t ws_bytes, int* splits_out) {
+  GemmEpilogue ep = {nullptr, nullptr, 0, nullptr, nullptr};
+  if (!w_rows_are_reduction)
+    return launch_gemm<false, kFwdBN, kFwdBK, kFwdPD, kFwdNBUF>(s, a, w, ep, M, C, R, ws, ws_bytes, lda, splits_out);
+  return launch_gemm<true, kSmallBN, kSmallBK, kSmallPD, kSmallNBUF>(s, a, w, ep, M, C, R, ws, ws_bytes, lda, splits_out);
 }
 
 hipError_t linear_wgrad_update_bf16(hipStream_t s, const WgradBatch& batch) {

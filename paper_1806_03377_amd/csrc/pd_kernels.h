@@ -19,6 +19,11 @@ hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, cons
 // dx[M][K] = (dz[M][N] * w[N][K]) .* (mask[M][K] > 0)   (mask may be null); dx bf16.
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes);
+// out[M][C] = a[M][R] * w as fp32 PARTIAL sums ws[split][M][C] (no epilogue): the caller's own kernel adds them
+// in split order.  a has row stride lda; w is [C][R] (w_rows_are_reduction = false) or [R][C] (true).
+hipError_t gemm_partial_bf16(hipStream_t s, bool w_rows_are_reduction, const bf16_t* a, int lda, const bf16_t* w, int M,
+                             int C, int R, float* ws, size_t ws_bytes, int* splits_out);
+
 // Weight gradient fused with the momentum-SGD update, for up to kMaxWgradLayers Linear layers in ONE launch:
 // per layer g = dz[M][N]^T x[M][K]; m <- mu*m + g; master <- master - lr*m; ring <- bf16(master); the same
 // for the bias with g_b = column sums of dz (master_b may be null to skip the bias).
@@ -32,7 +37,7 @@ struct WgradLayer {
   float* master_b;   // [N] or null
   float* mom_b;
   bf16_t* ring_b;
-  int N, K;
+  int M, N, K;        // M = rows reduced over (0: use the batch's M)
   unsigned tile_end;  // filled in by the launcher
 };
 struct WgradBatch {
@@ -75,6 +80,16 @@ hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, in
 // dx = dy routed to the first maximum of each window (row-major), times (x > 0) if relu_mask
 hipError_t maxpool2x2_backward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* y, const bf16_t* dy, bf16_t* dx, int N,
                                     int H, int W, int C, bool relu_mask);
+
+// ---- LSTM cell kernels (lstm_bf16.hip); gate order i, f, g, o; all [B][.] row-major ---------------------------
+// gates <- act(gates + sum_s rec_part[s]) in place (gates holds x_t W_ih^T + b on entry; rec_part may be null);
+// c <- f*c_prev + i*g; h <- bf16(o*tanh(c)).
+hipError_t lstm_cell_forward(hipStream_t s, float* gates, const float* rec_part, int splits, const float* c_prev, float* c,
+                             bf16_t* h, int B, int H);
+// One step of back-propagation through time: dh = dh_out + sum_s rec_part[s] (either may be null), dc updated
+// in place (on exit dL/dc_{t-1}), da[B][4H] = bf16 gradient w.r.t. the gate pre-activations.
+hipError_t lstm_cell_backward(hipStream_t s, const bf16_t* dh_out, const float* rec_part, int splits, float* dc,
+                              const float* gates, const float* c, const float* c_prev, bf16_t* da, int B, int H);
 
 // ---- stand-alone update (update.hip) ---------------------------------------------------------------
 // m <- mu*m + g; w_out <- w_in - lr*m; ring <- bf16(w_out) if ring is not null.  g null = zero gradient.

@@ -80,13 +80,15 @@ int emit_schedule(int depth, int M, pd_op* out, size_t cap, size_t* n_out) {
   return PD_OK;
 }
 
-enum { K_LINEAR = 0, K_CONV = 1, K_POOL = 2 };
+enum { K_LINEAR = 0, K_CONV = 1, K_POOL = 2, K_LSTM = 3 };
 
 // One compute layer of the stage.  Activations are [minibatch][h][w][c] (NHWC); a Linear sees its input
 // flattened in that order: in = ih*iw*ic, out = oc with oh = ow = 1.
 struct Layer {
   int kind = K_LINEAR;
-  int in = 0, out = 0;     // features per sample in / out
+  int rows = 0;            // rows of the activation matrices: minibatch, or seq_len * minibatch after an LSTM
+  int T = 1;               // LSTM: sequence length
+  int in = 0, out = 0;     // features per row in / out
   int ih = 1, iw = 1, ic = 0, oh = 1, ow = 1, oc = 0;
   int kh = 1, kw = 1, stride = 1, ph = 0, pw = 0;
   bool relu = false;
@@ -97,6 +99,10 @@ struct Layer {
   size_t dz_off = 0;          // Linear: byte offset of dL/d(pre-activation) inside the gradient workspace
   size_t part_off = 0;        // conv: byte offset of the weight-gradient partial sums
   int splits = 0;             // conv: number of partial sums
+  size_t g_off = 0, c_off = 0;  // LSTM: byte offsets inside a stash slot of the gate values [T][B][4H] fp32 and
+                                // the cell states [T+1][B][H] fp32 (slot 0 = zeros); y_off holds [T+1][B][H] hidden
+                                // states (slot 0 = zeros), the layer's output starts at slot 1
+  size_t dc_off = 0;          // LSTM: byte offset of dL/dc [B][H] fp32 inside the gradient workspace
 };
 typedef Layer Linear;  // (historic name used below for "a layer")
 
@@ -149,6 +155,11 @@ struct pd_stage {
   char* in_slot(int mb) const { return in_ring + (size_t)(mb % in_depth) * in_bytes; }
   char* stash_slot(int mb) const { return stash + (size_t)(mb % depth) * stash_slot_bytes; }
   char* grad_slot(int mb) const { return grad_in + (size_t)(mb & 1) * out_bytes; }
+  // stored output of layer l inside a stash slot (an LSTM keeps a zero state in front of its sequence)
+  char* out_of(char* slot, int l) const {
+    const Linear& L = lin[l];
+    return slot + L.y_off + (L.kind == K_LSTM ? (size_t)B * L.out * 2 : 0);
+  }
 };
 
 namespace {
@@ -179,8 +190,10 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   p.depth = c->in_flight_override > 0 ? c->in_flight_override : stage_depth(c->num_stages, c->noam, c->stage_index);
   p.in_depth = c->stage_index > 0 ? p.depth + 1 : p.depth;
   size_t flat = 0, dev = 0, y_off = 0, dz_off = 0, part_off = 0;
-  int width = -1;               // features per sample produced so far (-1: stage input not yet known)
+  int width = -1;               // features per row produced so far (-1: stage input not yet known)
   int ch = 0, hh = 1, ww = 1;   // its NHWC shape
+  int rows = p.B;               // rows of the current activation matrix
+  size_t x_off = 0;             // LSTM extras inside a stash slot
   for (int i = 0; i < c->n_layers; ++i) {
     const pd_layer_desc& d = c->layers[i];
     if (p.has_loss) return fail(PD_EINVAL, "PD_SOFTMAX_XENT must be the last layer");
@@ -195,7 +208,25 @@ int make_plan(const pd_stage_config* c, Plan& p) {
       L.ic = L.in; L.oc = L.out;
       L.n_w = (size_t)L.in * L.out; L.n_b = L.out;
       width = L.out; ch = L.out; hh = ww = 1;
-      L.dz_off = dz_off; dz_off = align_up(dz_off + (size_t)p.B * L.out * p.esz, 256);
+      L.rows = rows;
+      L.dz_off = dz_off; dz_off = align_up(dz_off + (size_t)rows * L.out * p.esz, 256);
+      p.lin.push_back(L);
+    } else if (d.kind == PD_LSTM) {
+      Layer L;
+      L.kind = K_LSTM;
+      L.in = d.p[0]; L.out = d.p[1]; L.T = d.p[2];
+      if (!p.bf16) return fail(PD_EINVAL, "layer %d: the LSTM is only built for PD_BF16_F32ACC", i);
+      if (L.in < 8 || L.out < 8 || (L.in % 8) || (L.out % 8) || L.T < 1)
+        return fail(PD_EINVAL, "layer %d: LSTM needs input and hidden sizes divisible by 8 and seq_len >= 1", i);
+      if (rows != p.B && rows != p.B * L.T) return fail(PD_EINVAL, "layer %d: sequence length differs from the layer below", i);
+      if (width >= 0 && rows == p.B) return fail(PD_EINVAL, "layer %d: an LSTM must be first in its stage or follow an LSTM", i);
+      if (width >= 0 && L.in != width) return fail(PD_EINVAL, "layer %d: LSTM input size %d != previous width %d", i, L.in, width);
+      rows = p.B * L.T;
+      L.rows = rows; L.ic = L.in; L.oc = L.out;
+      L.n_w = (size_t)4 * L.out * L.in + (size_t)4 * L.out * L.out; L.n_b = (size_t)4 * L.out;
+      width = L.out; ch = L.out; hh = ww = 1;
+      L.dz_off = dz_off; dz_off = align_up(dz_off + (size_t)rows * 4 * L.out * 2, 256);
+      L.dc_off = dz_off; dz_off = align_up(dz_off + (size_t)p.B * L.out * 4, 256);
       p.lin.push_back(L);
     } else if (d.kind == PD_CONV2D) {
       Layer L;
@@ -255,27 +286,41 @@ int make_plan(const pd_stage_config* c, Plan& p) {
         L.w_off = dev; dev = align_up(dev + L.n_w, 128);
         L.b_off = dev; dev = align_up(dev + L.n_b, 128);
       }
-      L.y_off = y_off; y_off = align_up(y_off + (size_t)p.B * L.out * 4, 256);  // room for fp32 (logits)
+      if (!L.rows) L.rows = p.B;
+      if (L.kind == K_LSTM) {
+        L.y_off = y_off; y_off = align_up(y_off + (size_t)(L.T + 1) * p.B * L.out * 2, 256);
+        L.g_off = y_off; y_off = align_up(y_off + (size_t)L.rows * 4 * L.out * 4, 256);
+        L.c_off = y_off; y_off = align_up(y_off + (size_t)(L.T + 1) * p.B * L.out * 4, 256);
+      } else {
+        L.y_off = y_off; y_off = align_up(y_off + (size_t)L.rows * L.out * 4, 256);  // room for fp32 (logits)
+      }
       if (L.kind != K_LINEAR) {
-        const size_t ab = align_up((size_t)p.B * (L.in > L.out ? L.in : L.out) * p.esz, 256);
+        const size_t ab = align_up((size_t)L.rows * (L.in > L.out ? L.in : L.out) * p.esz, 256);
         if (ab > p.pp_bytes) p.pp_bytes = ab;
       }
+      (void)x_off;
     }
   }
   if (p.lin.empty()) return fail(PD_EINVAL, "stage has no compute layer");
   p.part_bytes = part_off;
   p.n_params = flat;
   p.p_pad = dev;
-  p.in_bytes = align_up((size_t)p.B * p.lin.front().in * p.esz, 256);
-  p.out_bytes = align_up((size_t)p.B * p.lin.back().out * p.esz, 256);
+  p.in_bytes = align_up((size_t)p.lin.front().rows * p.lin.front().in * p.esz, 256);
+  p.out_bytes = align_up((size_t)p.lin.back().rows * p.lin.back().out * p.esz, 256);
   p.dlogits_off = y_off;
-  if (p.has_loss) y_off = align_up(y_off + (size_t)p.B * p.classes * p.esz, 256);
+  if (p.has_loss) y_off = align_up(y_off + (size_t)p.lin.back().rows * p.classes * p.esz, 256);
   p.stash_slot_bytes = y_off;
   p.dz_bytes = dz_off;
   if (p.bf16)
     for (const Layer& L : p.lin) {
-      if (L.kind != K_LINEAR) continue;
-      const size_t w = pd::gemm_bf16_workspace_bytes(p.B, L.out, L.in);
+      if (L.kind != K_LINEAR && L.kind != K_LSTM) continue;
+      size_t w = pd::gemm_bf16_workspace_bytes(L.rows, L.kind == K_LSTM ? 4 * L.out : L.out, L.in);
+      if (L.kind == K_LSTM) {  // the per-step recurrent products always leave partial sums in the workspace
+        size_t r = pd::gemm_bf16_workspace_bytes(p.B, 4 * L.out, L.out);
+        const size_t one = (size_t)p.B * 4 * L.out * 4;
+        if (r < one) r = one;
+        if (r > w) w = r;
+      }
       if (w > p.ws_bytes) p.ws_bytes = w;
     }
   p.ws_bytes = align_up(p.ws_bytes, 256);
@@ -291,7 +336,7 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   p.o_pp = o; o += 2 * p.pp_bytes;
   p.o_part = o; o += p.part_bytes;
   p.o_wt = o; o += p.wt_bytes;
-  p.o_rowloss = o; o += align_up((size_t)p.B * 4, 256);
+  p.o_rowloss = o; o += align_up((size_t)p.lin.back().rows * 4, 256);
   p.total = o;
   return PD_OK;
 }
@@ -353,9 +398,16 @@ int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena
   st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
   st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
   hipError_t e = pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
+  for (int d = 0; d < st->depth && e == hipSuccess; ++d)
+    for (const Linear& L : st->lin)
+      if (L.kind == K_LSTM && e == hipSuccess) {
+        char* slot = st->stash + (size_t)d * st->stash_slot_bytes;
+        e = pd::fill_zero(st->stream, slot + L.y_off, (size_t)st->B * L.out * 2);
+        if (e == hipSuccess) e = pd::fill_zero(st->stream, slot + L.c_off, (size_t)st->B * L.out * 4);
+      }
   if (e != hipSuccess) {
     delete st;
-    return fail(PD_EHIP, "clearing momentum: %s", hipGetErrorString(e));
+    return fail(PD_EHIP, "clearing momentum and initial states: %s", hipGetErrorString(e));
   }
   *out = st;
   return PD_OK;
@@ -538,28 +590,28 @@ int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer
   switch (what) {
     case 0:
       if (layer < 0 || layer >= nl) return fail(PD_EINVAL, "layer %d out of range", layer);
-      src = st->stash_slot(mb_id) + st->lin[layer].y_off;
-      cnt = (size_t)st->B * st->lin[layer].out;
+      src = st->out_of(st->stash_slot(mb_id), layer);
+      cnt = (size_t)st->lin[layer].rows * st->lin[layer].out;
       break;
     case 1:
       src = st->in_slot(mb_id);
-      cnt = (size_t)st->B * st->lin.front().in;
+      cnt = (size_t)st->lin.front().rows * st->lin.front().in;
       break;
     case 2:
       if (st->has_loss) return fail(PD_ESTATE, "a stage that ends in the loss has no output-gradient slot");
       src = st->grad_slot(mb_id);
-      cnt = (size_t)st->B * st->lin.back().out;
+      cnt = (size_t)st->lin.back().rows * st->lin.back().out;
       break;
     case 3:
       if (layer < 0 || layer >= nl) return fail(PD_EINVAL, "layer %d out of range", layer);
       if (st->lin[layer].kind != K_LINEAR) return fail(PD_ESTATE, "layer %d does not keep its output gradient", layer);
       src = (st->has_loss && layer == nl - 1) ? st->stash_slot(mb_id) + st->dlogits_off : st->dz + st->lin[layer].dz_off;
-      cnt = (size_t)st->B * st->lin[layer].out;
+      cnt = (size_t)st->lin[layer].rows * st->lin[layer].out;
       break;
     case 4:
       if (!st->has_loss) return fail(PD_ESTATE, "stage has no loss");
       src = st->stash_slot(mb_id) + st->dlogits_off;
-      cnt = (size_t)st->B * st->classes;
+      cnt = (size_t)st->lin.back().rows * st->classes;
       break;
     default:
       return fail(PD_EINVAL, "unknown tensor selector %d", what);
@@ -596,21 +648,45 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
   char* in = st->in_slot(mb_id);
   char* slot = st->stash_slot(mb_id);
   const char* w = st->ring_slot(v);
-  if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->B * st->lin.front().in * st->esz));
+  if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->lin.front().rows * st->lin.front().in * st->esz));
   const char* a = in;
-  for (const Layer& L : st->lin) {
-    char* y = slot + L.y_off;
+  for (int li = 0; li < (int)st->lin.size(); ++li) {
+    const Layer& L = st->lin[li];
+    char* y = st->out_of(slot, li);
     if (L.kind == K_LINEAR) {
       if (st->bf16) {
         const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
         const bool logits = st->has_loss && &L == &st->lin.back();  // logits go to the loss unrounded (fp32)
         PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, wp + L.b_off,
                                    reinterpret_cast<pd::bf16_t*>(y), logits ? reinterpret_cast<float*>(y) : nullptr,
-                                   st->B, L.out, L.in, L.relu, st->ws, st->ws_bytes));
+                                   L.rows, L.out, L.in, L.relu, st->ws, st->ws_bytes));
       } else {
         const float* wp = reinterpret_cast<const float*>(w);
         PD_HIP(pd::linear_fwd_f32(s, reinterpret_cast<const float*>(a), wp + L.w_off, wp + L.b_off,
-                                  reinterpret_cast<float*>(y), st->B, L.out, L.in, L.relu));
+                                  reinterpret_cast<float*>(y), L.rows, L.out, L.in, L.relu));
+      }
+    } else if (L.kind == K_LSTM) {
+      // input projection of the whole sequence in one GEMM (bias folded in, fp32), then the recurrence: per
+      // step one skinny GEMM h_{t-1} W_hh^T left as partial sums and one cell kernel that adds them up
+      const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
+      const pd::bf16_t* wih = wp + L.w_off;
+      const pd::bf16_t* whh = wih + (size_t)4 * L.out * L.in;
+      const int B = st->B, H = L.out;
+      float* gates = reinterpret_cast<float*>(slot + L.g_off);
+      float* cbuf = reinterpret_cast<float*>(slot + L.c_off);
+      pd::bf16_t* hbuf = reinterpret_cast<pd::bf16_t*>(slot + L.y_off);
+      PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wih, wp + L.b_off, nullptr, gates, L.rows,
+                                 4 * H, L.in, false, st->ws, st->ws_bytes));
+      for (int t = 0; t < L.T; ++t) {
+        const float* rec = nullptr;
+        int splits = 0;
+        if (t > 0) {
+          PD_HIP(pd::gemm_partial_bf16(s, false, hbuf + (size_t)t * B * H, H, whh, B, 4 * H, H, st->ws, st->ws_bytes,
+                                       &splits));
+          rec = st->ws;
+        }
+        PD_HIP(pd::lstm_cell_forward(s, gates + (size_t)t * B * 4 * H, rec, splits, cbuf + (size_t)t * B * H,
+                                     cbuf + (size_t)(t + 1) * B * H, hbuf + (size_t)(t + 1) * B * H, B, H));
       }
     } else if (L.kind == K_CONV) {
       const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
@@ -623,10 +699,10 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
     }
     a = y;
   }
-  if (y_dev) PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->B * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
+  if (y_dev) PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->lin.back().rows * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
   if (st->has_loss)
     PD_HIP(pd::softmax_xent(s, reinterpret_cast<const float*>(a), labels_dev, slot + st->dlogits_off, st->row_loss,
-                            loss_dev, st->B, st->classes, st->bf16));
+                            loss_dev, st->lin.back().rows, st->classes, st->bf16));
   st->in_flight.push_back({mb_id, v});
   st->last_fwd = mb_id;
   st->trace.push_back({PD_OP_F, mb_id, v, v % st->depth});
@@ -652,7 +728,7 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   // their own buffer until pd_update (the weight gradient is formed there); conv/pool layers ping-pong.
   int pp_next = 0;
   auto buffer_for = [&](int l) -> char* {
-    if (st->lin[l].kind == K_LINEAR) return st->dz + st->lin[l].dz_off;
+    if (st->lin[l].kind == K_LINEAR) return st->dz + st->lin[l].dz_off;  // (an LSTM's own buffer holds dG)
     char* b = st->pp + (size_t)pp_next * st->pp_bytes;
     pp_next ^= 1;
     return b;
@@ -662,25 +738,48 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
     cur = slot + st->dlogits_off;
   } else {
     char* b = buffer_for(nl - 1);
-    const size_t n = (size_t)st->B * last.out;
-    if (last.relu) PD_HIP(pd::relu_mask(s, dy_dev, slot + last.y_off, b, n, st->bf16));
+    const size_t n = (size_t)last.rows * last.out;
+    if (last.relu) PD_HIP(pd::relu_mask(s, dy_dev, st->out_of(slot, nl - 1), b, n, st->bf16));
     else PD_HIP(pd::copy_bytes(s, dy_dev, b, n * st->esz));
     cur = b;
   }
   for (int l = nl - 1; l >= 0; --l) {
     const Layer& L = st->lin[l];
-    const char* x = l == 0 ? st->in_slot(mb_id) : slot + st->lin[l - 1].y_off;
+    const char* x = l == 0 ? st->in_slot(mb_id) : st->out_of(slot, l - 1);
     if (L.kind == K_CONV) {  // weight-gradient partial sums; pd_update reduces them and applies the update
       const pd::ConvGeom g = {st->B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
       PD_HIP(pd::conv_wgrad_partial_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur),
                                          reinterpret_cast<const pd::bf16_t*>(x),
                                          reinterpret_cast<float*>(st->part + L.part_off), L.splits, g));
     }
+    if (L.kind == K_LSTM) {  // back-propagation through time: leaves dL/d(gate pre-activations) for every step
+      const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
+      const pd::bf16_t* whh = wp + L.w_off + (size_t)4 * L.out * L.in;
+      const int B = st->B, H = L.out;
+      pd::bf16_t* dG = reinterpret_cast<pd::bf16_t*>(st->dz + L.dz_off);
+      float* dc = reinterpret_cast<float*>(st->dz + L.dc_off);
+      const float* gates = reinterpret_cast<const float*>(slot + L.g_off);
+      const float* cbuf = reinterpret_cast<const float*>(slot + L.c_off);
+      const pd::bf16_t* dh_out = reinterpret_cast<const pd::bf16_t*>(cur);
+      PD_HIP(pd::fill_zero(s, dc, (size_t)B * H * 4));
+      for (int t = L.T - 1; t >= 0; --t) {
+        const float* rec = nullptr;
+        int splits = 0;
+        if (t < L.T - 1) {
+          PD_HIP(pd::gemm_partial_bf16(s, true, dG + (size_t)(t + 1) * B * 4 * H, 4 * H, whh, B, H, 4 * H, st->ws,
+                                       st->ws_bytes, &splits));
+          rec = st->ws;
+        }
+        PD_HIP(pd::lstm_cell_backward(s, dh_out + (size_t)t * B * H, rec, splits, dc, gates + (size_t)t * B * 4 * H,
+                                      cbuf + (size_t)(t + 1) * B * H, cbuf + (size_t)t * B * H,
+                                      dG + (size_t)t * B * 4 * H, B, H));
+      }
+    }
     char* out;
     const char* mask = nullptr;
     if (l > 0) {
       out = buffer_for(l - 1);
-      if (st->lin[l - 1].relu) mask = slot + st->lin[l - 1].y_off;
+      if (st->lin[l - 1].relu) mask = st->out_of(slot, l - 1);
     } else {
       if (!dx_dev) break;
       out = static_cast<char*>(dx_dev);
@@ -690,13 +789,21 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
         const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
         PD_HIP(pd::linear_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur), wp + L.w_off,
                                      reinterpret_cast<const pd::bf16_t*>(mask), reinterpret_cast<pd::bf16_t*>(out),
-                                     st->B, L.out, L.in, st->ws, st->ws_bytes));
+                                     L.rows, L.out, L.in, st->ws, st->ws_bytes));
       } else {
         const float* wp = reinterpret_cast<const float*>(w);
         PD_HIP(pd::linear_dgrad_f32(s, reinterpret_cast<const float*>(cur), wp + L.w_off,
-                                    reinterpret_cast<const float*>(mask), reinterpret_cast<float*>(out), st->B, L.out,
+                                    reinterpret_cast<const float*>(mask), reinterpret_cast<float*>(out), L.rows, L.out,
                                     L.in));
       }
+    } else if (L.kind == K_LSTM) {
+      const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
+      const pd::bf16_t* wih = wp + L.w_off;
+      const pd::bf16_t* whh = wih + (size_t)4 * L.out * L.in;
+      PD_HIP(pd::linear_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(st->dz + L.dz_off), wih,
+                                   reinterpret_cast<const pd::bf16_t*>(mask), reinterpret_cast<pd::bf16_t*>(out), L.rows,
+                                   4 * L.out, L.in, st->ws, st->ws_bytes));
+      (void)whh;
     } else if (L.kind == K_CONV) {
       const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
       const pd::ConvGeom g = {st->B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
@@ -740,24 +847,37 @@ int pd_update(pd_stage* st) {
       continue;
     }
     const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
-    const char* x = l == 0 ? st->in_slot(mb) : slot + st->lin[l - 1].y_off;
+    const char* x = l == 0 ? st->in_slot(mb) : st->out_of(slot, l - 1);
     if (st->bf16) {
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
+      auto flush_if_full = [&]() -> hipError_t {
+        if (batch.count < pd::kMaxWgradLayers) return hipSuccess;
+        const hipError_t e = pd::linear_wgrad_update_bf16(s, batch);
+        batch.count = 0;
+        return e;
+      };
       pd::WgradLayer& W = batch.layer[batch.count++];
       W.dz = reinterpret_cast<const pd::bf16_t*>(dz); W.x = reinterpret_cast<const pd::bf16_t*>(x);
       W.master_w = st->master + L.w_off; W.mom_w = st->mom + L.w_off; W.ring_w = ro + L.w_off;
       W.master_b = st->master + L.b_off; W.mom_b = st->mom + L.b_off; W.ring_b = ro + L.b_off;
-      W.N = L.out; W.K = L.in; W.tile_end = 0;
-      if (batch.count == pd::kMaxWgradLayers) {
-        PD_HIP(pd::linear_wgrad_update_bf16(s, batch));
-        batch.count = 0;
+      W.M = L.rows; W.N = L.kind == K_LSTM ? 4 * L.out : L.out; W.K = L.in; W.tile_end = 0;
+      PD_HIP(flush_if_full());
+      if (L.kind == K_LSTM) {  // second matrix: W_hh, whose "input" is the hidden sequence shifted by one step
+        const size_t o2 = L.w_off + (size_t)4 * L.out * L.in;
+        pd::WgradLayer& V = batch.layer[batch.count++];
+        V.dz = reinterpret_cast<const pd::bf16_t*>(dz);
+        V.x = reinterpret_cast<const pd::bf16_t*>(slot + L.y_off);
+        V.master_w = st->master + o2; V.mom_w = st->mom + o2; V.ring_w = ro + o2;
+        V.master_b = nullptr; V.mom_b = nullptr; V.ring_b = nullptr;
+        V.M = L.rows; V.N = 4 * L.out; V.K = L.out; V.tile_end = 0;
+        PD_HIP(flush_if_full());
       }
     } else {
       const float* wi = reinterpret_cast<const float*>(st->ring_slot(st->latest));
       float* wo = reinterpret_cast<float*>(st->ring_slot(nv));
       PD_HIP(pd::linear_wgrad_update_f32(s, reinterpret_cast<const float*>(dz), reinterpret_cast<const float*>(x),
                                          wi + L.w_off, wo + L.w_off, st->mom + L.w_off, wi + L.b_off, wo + L.b_off,
-                                         st->mom + L.b_off, st->B, L.out, L.in, st->lr, st->mu));
+                                         st->mom + L.b_off, L.rows, L.out, L.in, st->lr, st->mu));
     }
   }
   if (batch.count) PD_HIP(pd::linear_wgrad_update_bf16(s, batch));  // all Linear layers of the stage in one launch
@@ -779,7 +899,8 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
     if (!st) return fail(PD_EINVAL, "stage %d is null", s);
     if (st->stage_index != s || st->num_stages != S) return fail(PD_EINVAL, "stage %d has index %d of %d", s, st->stage_index, st->num_stages);
     if (st->B != stages[0]->B || st->bf16 != stages[0]->bf16) return fail(PD_EINVAL, "stage %d: minibatch/precision differ", s);
-    if (s > 0 && st->lin.front().in != stages[s - 1]->lin.back().out) return fail(PD_EINVAL, "stage %d input width mismatch", s);
+    if (s > 0 && (st->lin.front().in != stages[s - 1]->lin.back().out || st->lin.front().rows != stages[s - 1]->lin.back().rows))
+      return fail(PD_EINVAL, "stage %d input shape mismatch", s);
     if (st->has_loss != (s == S - 1)) return fail(PD_EINVAL, "only the last stage may (and must) end in the loss");
     if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "stage %d has minibatches in flight", s);
     if (st->last_fwd != stages[0]->last_fwd) return fail(PD_ESTATE, "stages disagree on the next minibatch id");
@@ -799,7 +920,7 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
   // event it waits for has been recorded, which makes the host's enqueue order a valid global order.
   std::vector<std::vector<char>> f_rec(S, std::vector<char>(M, 0)), b_rec = f_rec, u_rec = f_rec;
   std::vector<size_t> pos(S, 0);
-  const size_t in_elems = (size_t)stages[0]->B * stages[0]->lin.front().in * stages[0]->esz;
+  const size_t in_elems = (size_t)stages[0]->lin.front().rows * stages[0]->lin.front().in * stages[0]->esz;
   size_t remaining = 0;
   for (int s = 0; s < S; ++s) remaining += ops[s].size();
   while (remaining) {
@@ -820,7 +941,7 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
           if (reuse >= 0) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_u[reuse], 0));
           const void* x = s == 0 ? static_cast<const char*>(inputs_dev) + (size_t)i * in_elems : st->in_slot(mb);
           void* y = s < S - 1 ? stages[s + 1]->in_slot(mb) : nullptr;
-          const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->B : nullptr;
+          const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->lin.back().rows : nullptr;
           float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
           const int rc = pd_forward(st, mb, x, lab, y, loss);
           if (rc != PD_OK) return rc;
@@ -893,7 +1014,7 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
   W.dz = static_cast<const pd::bf16_t*>(dz); W.x = static_cast<const pd::bf16_t*>(x);
   W.master_w = master_w; W.mom_w = mom_w; W.ring_w = static_cast<pd::bf16_t*>(ring_out_w);
   W.master_b = master_b; W.mom_b = mom_b; W.ring_b = static_cast<pd::bf16_t*>(ring_out_b);
-  W.N = N; W.K = K; W.tile_end = 0;
+  W.M = M; W.N = N; W.K = K; W.tile_end = 0;
   PD_HIP(pd::linear_wgrad_update_bf16(static_cast<hipStream_t>(stream), batch));
   return PD_OK;
 }

@@ -161,3 +161,10 @@ def config3_vgg_conv(widths=(64, 128, 256)):
 
     return [conv(3, a), conv(a, a), ("maxpool2d", 2, 2), conv(a, b), conv(b, b), ("maxpool2d", 2, 2),
             conv(b, c), conv(c, c), conv(c, c), ("maxpool2d", 2, 2)]
+
+
+def config4_s2vt(input_size=4096, hidden=1000, vocab=30000, seq_len=80):
+    """S2VT-shaped two-stage sequence model: stage 0 = LSTM(input -> hidden); stage 1 = LSTM(hidden -> hidden),
+    vocabulary projection on every time step, softmax cross-entropy over all seq_len * minibatch tokens."""
+    return [[("lstm", input_size, hidden, seq_len)],
+            [("lstm", hidden, hidden, seq_len), ("linear", hidden, vocab, False), ("softmax_xent", vocab)]]

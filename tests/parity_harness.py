@@ -62,6 +62,9 @@ def _flat_keep(layers, units):
     """Boolean keep-mask over a stage's flat parameter vector, dropping the rows of flagged units."""
     parts = []
     for li, L in enumerate(_linears(layers)):
+        if L[0] == "lstm":          # no ReLU, never flagged: keep everything
+            parts.append(np.ones(4 * L[2] * (L[1] + L[2]) + 4 * L[2], dtype=bool))
+            continue
         n_units, per = _rows_of(L)
         if not n_units:
             continue
@@ -84,12 +87,12 @@ def _global_order(S, noam, M, depth_override):
 
 
 def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=0, out_grads=None,
-             lr=0.01, mu=0.9, mode="free", compare=True, verbose=False, in_hw=None):
+             lr=0.01, mu=0.9, mode="free", compare=True, verbose=False, in_hw=None, minibatch=None):
     bf16 = precision == pd.PD_BF16_F32ACC
     omode = "bf16" if bf16 else "f32"
     tol = TOL_BF16 if bf16 else TOL_F32
     S, M = len(stage_layers), len(xs)
-    B = xs[0].shape[0]
+    B = minibatch or xs[0].shape[0]     # (time-major sequence inputs are [T][B][I]: pass minibatch)
     has_loss = stage_layers[-1][-1][0] == "softmax_xent"
     depths = [depth_override or in_flight_depth(S, noam, s) for s in range(S)]
     order = _global_order(S, noam, M, depth_override)

@@ -347,6 +347,58 @@ def test_config3_vgg_conv_full_geometry_reduced_batch():
 
 
 # ---------------------------------------------------------------------------------------------
+# LSTM stages (bf16, time-major sequences): input projection GEMM, per-step recurrent GEMM + cell kernel,
+# back-propagation through time, the two weight matrices updated from dG
+# ---------------------------------------------------------------------------------------------
+def _seq_case(stage_layers, B, T, noam, M, seed=SEED + 3, depth_override=0, with_loss=True, lr=0.05, mode="forced",
+              verbose=False):
+    I = stage_layers[0][0][1]
+    params = []
+    for s, ly in enumerate(stage_layers):
+        p = gen.init_params(seed, f"q{s}", ly)
+        params.append(p + 0.01 * gen.normal(seed, f"qb{s}", p.shape))
+    xs = list(gen.normal(seed, "X", (M, T, B, I)))
+    labs = dys = None
+    if with_loss:
+        V = stage_layers[-1][-1][1]
+        labs = list(gen.labels(seed, "Y", (M, T, B), V))
+    else:
+        Hh = stage_layers[-1][-1][2]
+        dys = list(gen.normal(seed, "DY", (M, T, B, Hh)) * 0.01)
+    return run_case(stage_layers, params, xs, labs, noam=noam, precision=pd.PD_BF16_F32ACC,
+                    depth_override=depth_override, out_grads=dys, lr=lr, mode=mode, minibatch=B, verbose=verbose)
+
+
+def test_lstm_single_stage_no_loss():
+    _seq_case([[("lstm", 24, 16, 5)]], B=3, T=5, noam=1, M=4, depth_override=2, with_loss=False)
+
+
+def test_lstm_stage_with_vocab_projection():
+    _seq_case([[("lstm", 16, 24, 6), ("linear", 24, 40, False), ("softmax_xent", 40)]], B=4, T=6, noam=1, M=4,
+              depth_override=2)
+
+
+def test_lstm_two_stacked_in_one_stage_free_running():
+    _seq_case([[("lstm", 16, 16, 4), ("lstm", 16, 8, 4), ("linear", 8, 16, False), ("softmax_xent", 16)]], B=2, T=4,
+              noam=1, M=2, depth_override=2, mode="free")
+
+
+def test_s2vt_shaped_two_stage_pipeline():
+    # the two-stage sequence model at reduced widths: ragged against every tile size
+    sl = gen.config4_s2vt(input_size=136, hidden=72, vocab=200, seq_len=7)
+    _seq_case(sl, B=5, T=7, noam=2, M=5)
+
+
+@pytest.mark.timeout(1500)
+def test_config4_s2vt_full_width_reduced_vocab_and_length():
+    # hidden 1000 and input 4096 as configured, minibatch 64; vocabulary and sequence length reduced so the
+    # oracle finishes in seconds
+    print("config 4 widths (4096 -> 1000 -> 1000), T = 6, vocab 2000", flush=True)
+    sl = gen.config4_s2vt(vocab=2000, seq_len=6)
+    _seq_case(sl, B=64, T=6, noam=2, M=3, lr=0.01, verbose=True)
+
+
+# ---------------------------------------------------------------------------------------------
 # the whole pipeline.  First op by op against the oracle (serialised), then the same run through
 # pd_pipeline_run with one stream per stage: the kernels are deterministic, so the concurrent run
 # must reproduce the serialised one bit for bit -- any missing inter-stream dependency would show.
