@@ -122,6 +122,58 @@ def bench_conv(args, pd, gen, torch, np, dev):
     print(json.dumps(out))
 
 
+def bench_s2vt(args, pd, gen, torch, np, dev):
+    """Secondary workload: the S2VT-shaped model (LSTM 4096->1000 | LSTM 1000->1000 + vocab 30000 + loss), seq 80,
+    minibatch 64, as a 2-stage pipeline on two streams (pd_pipeline_run, NOAM 2).  A step = one minibatch through
+    both stages (F, B, U on each)."""
+    B, K, W = args.minibatch, args.steps, args.warmup
+    T, I, H, V = (8, 256, 128, 1000) if args.small else (80, 4096, 1000, 30000)
+    sl = gen.config4_s2vt(I, H, V, T)
+    seed = gen.BASE_SEED + 3
+    streams = [torch.cuda.Stream(device=dev) for _ in range(2)]
+    hs, arenas = [], []
+    for s in range(2):
+        cfg = pd.make_config(sl[s], stage_index=s, num_stages=2, noam=2, minibatch=B, precision=pd.PD_BF16_F32ACC,
+                             lr=0.01, momentum=0.9, stream=streams[s].cuda_stream)
+        nbytes = pd.pd_stage_query_bytes(cfg)
+        arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
+        pd.pd_stage_set_params(h, gen.init_params(seed, f"s{s}", sl[s]))
+        hs.append(h); arenas.append(arena)
+    M = W + K
+    n_pool = 2
+    x1 = torch.from_numpy(gen.normal(seed, "x", (n_pool, T, B, I))).to(dev).to(torch.bfloat16)
+    l1 = torch.from_numpy(gen.labels(seed, "y", (n_pool, T, B), V)).to(dev)
+    xs = x1.repeat((M + n_pool - 1) // n_pool, 1, 1, 1)[:M].contiguous()
+    ls = l1.repeat((M + n_pool - 1) // n_pool, 1, 1)[:M].contiguous()
+    losses = torch.zeros(M, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    if W:
+        pd.pd_pipeline_run(hs, W, xs.data_ptr(), ls.data_ptr(), losses.data_ptr())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pd.pd_pipeline_run(hs, K, xs[W:].data_ptr(), ls[W:].data_ptr(), losses[W:].data_ptr())
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / K
+    rows = T * B
+    f = 6.0 * rows * (4 * H * I + 4 * H * H) + 6.0 * rows * (4 * H * H + 4 * H * H) + 6.0 * rows * H * V
+    f -= 2.0 * rows * 4 * H * I   # no dL/d(input) on the input stage
+    out = {"metric": METRIC, "value": B / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": ("REDUCED " if args.small else "") + f"S2VT-shaped 2-stage pipeline: LSTM {I}->{H} | LSTM {H}->{H} + "
+                      f"Linear {H}->{V} + softmax-xent, seq {T}, minibatch {B}, NOAM 2, two streams; step = one minibatch "
+                      "through both stages (drained pipeline of `steps` minibatches)", "minibatch": B},
+           "step_gflop": f / 1e9, "mfma_util_pct": 100.0 * f / (ms * 1e-3) / MFMA_BF16_PEAK,
+           "roofline": {"bound": "mfma", "kernel": "whole step", "achieved": f / (ms * 1e-3) / 1e12,
+                        "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": f / (ms * 1e-3) / MFMA_BF16_PEAK,
+                        "traffic": None},
+           "final_loss": float(losses[-1].item())}
+    for h in hs:
+        pd.pd_stage_destroy(h)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,8 +183,9 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv"],
-                    help="vgg16_fc (default, the metric's workload) or vgg16_conv (the conv stage, secondary)")
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt"],
+                    help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
+                         "s2vt (the two LSTM stages as a 2-stream pipeline)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs all pipeline stages on ONE GPU; --gpus must be 1", file=sys.stderr)
@@ -151,6 +204,8 @@ def main():
     B, depth, K, W = args.minibatch, args.depth, args.steps, args.warmup
     if args.workload == "vgg16_conv":
         return bench_conv(args, pd, gen, torch, np, dev)
+    if args.workload == "s2vt":
+        return bench_s2vt(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
     n_in, classes = layers[0][1], layers[-1][1]
     seed = gen.BASE_SEED + 1

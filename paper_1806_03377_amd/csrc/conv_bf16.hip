@@ -371,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const bf16_t* __re
 // g[e] = sum over splits of part[s][e] in split order; then m <- mu*m + g; w <- w - lr*m; ring <- bf16(w).
 // e < n_w addresses the weights, e >= n_w the bias.
 __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* __restrict__ part, int splits,
-                                                                  size_t n_w, int n_b, float* __restrict__ master_w,
+                                                                  size_t stride, size_t n_w, int n_b, float* __restrict__ master_w,
                                                                   float* __restrict__ mom_w, bf16_t* __restrict__ ring_w,
                                                                   float* __restrict__ master_b, float* __restrict__ mom_b,
                                                                   bf16_t* __restrict__ ring_b, float lr, float mu) {
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* _
   const size_t n = n_w + n_b;
   if (e >= n) return;
   float gsum = 0.f;
-  for (int s = 0; s < splits; ++s) gsum += part[(size_t)s * n + e];
+  for (int s = 0; s < splits; ++s) gsum += part[(size_t)s * stride + e];
   float* ms = e < n_w ? master_w + e : master_b + (e - n_w);
   float* mm = e < n_w ? mom_w + e : mom_b + (e - n_w);
   bf16_t* rr = e < n_w ? ring_w + e : ring_b + (e - n_w);
@@ -699,11 +699,12 @@ hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t
   return hipGetLastError();
 }
 
-hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t n_w, int n_b, float* master_w,
-                               float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b, bf16_t* ring_b, float lr,
-                               float mu) {
+hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t stride, size_t n_w, int n_b,
+                               float* master_w, float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b,
+                               bf16_t* ring_b, float lr, float mu) {
   const size_t n = n_w + n_b;
-  wgrad_reduce_update_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, splits, n_w, n_b, master_w, mom_w,
+  if (!stride) stride = n;
+  wgrad_reduce_update_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, splits, stride, n_w, n_b, master_w, mom_w,
                                                                          ring_w, master_b, mom_b, ring_b, lr, mu);
   return hipGetLastError();
 }

@@ -37,6 +37,18 @@ __global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16_t* __restri
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = bf2f(src[i]);
 }
 
+__global__ __launch_bounds__(256) void transpose_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int R,
+                                                        int C) {
+  __shared__ bf16_t tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+  for (int i = ty; i < 32; i += 8)
+    if (r0 + i < R && c0 + tx < C) tile[i][tx] = src[(size_t)(r0 + i) * C + c0 + tx];
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8)
+    if (c0 + i < C && r0 + tx < R) dst[(size_t)(c0 + i) * R + r0 + tx] = tile[tx][i];
+}
+
 template <bool BF>
 __global__ __launch_bounds__(256) void relu_mask_kernel(const void* __restrict__ dy, const void* __restrict__ y,
                                                         void* __restrict__ dz, size_t n) {
@@ -127,6 +139,11 @@ hipError_t fill_zero(hipStream_t s, void* dst, size_t bytes) {
 hipError_t f32_to_bf16(hipStream_t s, const float* src, bf16_t* dst, size_t n) {
   if (n == 0) return hipSuccess;
   f32_to_bf16_kernel<<<grid_for(n), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+hipError_t transpose_bf16(hipStream_t s, const bf16_t* src, bf16_t* dst, int R, int C) {
+  dim3 grid((C + 31) / 32, (R + 31) / 32);
+  transpose_kernel<<<grid, 256, 0, s>>>(src, dst, R, C);
   return hipGetLastError();
 }
 hipError_t bf16_to_f32(hipStream_t s, const bf16_t* src, float* dst, size_t n) {

@@ -73,9 +73,10 @@ int conv_wgrad_split_count(const ConvGeom& g);
 hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
                                    const ConvGeom& g);
 // g = sum of the partials in split order; m <- mu*m + g; master <- master - lr*m; ring <- bf16(master).
-hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t n_w, int n_b, float* master_w,
-                               float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b, bf16_t* ring_b, float lr,
-                               float mu);
+// Partial s starts at part + s*stride (stride 0 = n_w + n_b); n_b may be 0 to leave the bias alone.
+hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t stride, size_t n_w, int n_b,
+                               float* master_w, float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b,
+                               bf16_t* ring_b, float lr, float mu);
 hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, int N, int H, int W, int C);
 // dx = dy routed to the first maximum of each window (row-major), times (x > 0) if relu_mask
 hipError_t maxpool2x2_backward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* y, const bf16_t* dy, bf16_t* dx, int N,
@@ -111,6 +112,7 @@ hipError_t linear_wgrad_update_f32(hipStream_t s, const float* dz, const float* 
 hipError_t copy_bytes(hipStream_t s, const void* src, void* dst, size_t bytes);  // bytes % 4 == 0 or any
 hipError_t fill_zero(hipStream_t s, void* dst, size_t bytes);
 hipError_t f32_to_bf16(hipStream_t s, const float* src, bf16_t* dst, size_t n);
+hipError_t transpose_bf16(hipStream_t s, const bf16_t* src, bf16_t* dst, int R, int C);  // dst[C][R] = src[R][C]^T
 hipError_t bf16_to_f32(hipStream_t s, const bf16_t* src, float* dst, size_t n);
 // dz = dy .* (y > 0)   (bf16 or fp32 elements, n elements)
 hipError_t relu_mask(hipStream_t s, const void* dy, const void* y, void* dz, size_t n, bool is_bf16);

@@ -82,6 +82,14 @@ int emit_schedule(int depth, int M, pd_op* out, size_t cap, size_t* n_out) {
 
 enum { K_LINEAR = 0, K_CONV = 1, K_POOL = 2, K_LSTM = 3 };
 
+// From this many rows on, a Linear/LSTM weight gradient is formed by the large-reduction kernel (fp32 partial
+// sums over row ranges, then a fused reduce + update) instead of the kernel built for minibatch-sized reductions.
+constexpr int kBigRows = 512;
+
+pd::ConvGeom rows_as_pixels(int rows, int k, int n) {  // y[rows][n] = x[rows][k] w[n][k]^T seen as a 1x1 convolution
+  return pd::ConvGeom{rows, 1, 1, k, 1, 1, n, 1, 1, 1, 0, 0};
+}
+
 // One compute layer of the stage.  Activations are [minibatch][h][w][c] (NHWC); a Linear sees its input
 // flattened in that order: in = ih*iw*ic, out = oc with oh = ow = 1.
 struct Layer {
@@ -98,7 +106,9 @@ struct Layer {
   size_t y_off = 0;           // byte offset of this layer's output inside a stash slot
   size_t dz_off = 0;          // Linear: byte offset of dL/d(pre-activation) inside the gradient workspace
   size_t part_off = 0;        // conv: byte offset of the weight-gradient partial sums
-  int splits = 0;             // conv: number of partial sums
+  int splits = 0;             // conv: number of partial sums (also Linear/LSTM layers with many rows, see kBigRows)
+  size_t part2_off = 0;       // LSTM with many rows: partial sums of the W_hh gradient
+  int splits2 = 0;
   size_t g_off = 0, c_off = 0;  // LSTM: byte offsets inside a stash slot of the gate values [T][B][4H] fp32 and
                                 // the cell states [T+1][B][H] fp32 (slot 0 = zeros); y_off holds [T+1][B][H] hidden
                                 // states (slot 0 = zeros), the layer's output starts at slot 1
@@ -287,6 +297,17 @@ int make_plan(const pd_stage_config* c, Plan& p) {
         L.b_off = dev; dev = align_up(dev + L.n_b, 128);
       }
       if (!L.rows) L.rows = p.B;
+      if (p.bf16 && L.rows >= kBigRows && (L.kind == K_LINEAR || L.kind == K_LSTM)) {
+        const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
+        L.splits = pd::conv_wgrad_split_count(rows_as_pixels(L.rows, L.in, n_out));
+        L.part_off = part_off; part_off = align_up(part_off + (size_t)L.splits * ((size_t)n_out * L.in + n_out) * 4, 256);
+        if (L.kind == K_LSTM) {
+          L.splits2 = pd::conv_wgrad_split_count(rows_as_pixels(L.rows, L.out, n_out));
+          L.part2_off = part_off;
+          part_off = align_up(part_off + (size_t)L.splits2 * ((size_t)n_out * L.out + n_out) * 4, 256);
+        }
+      }
+      if (L.kind == K_LSTM && (size_t)4 * L.out * L.out * 2 > p.wt_bytes) p.wt_bytes = align_up((size_t)4 * L.out * L.out * 2, 256);
       if (L.kind == K_LSTM) {
         L.y_off = y_off; y_off = align_up(y_off + (size_t)(L.T + 1) * p.B * L.out * 2, 256);
         L.g_off = y_off; y_off = align_up(y_off + (size_t)L.rows * 4 * L.out * 4, 256);
@@ -317,6 +338,8 @@ int make_plan(const pd_stage_config* c, Plan& p) {
       size_t w = pd::gemm_bf16_workspace_bytes(L.rows, L.kind == K_LSTM ? 4 * L.out : L.out, L.in);
       if (L.kind == K_LSTM) {  // the per-step recurrent products always leave partial sums in the workspace
         size_t r = pd::gemm_bf16_workspace_bytes(p.B, 4 * L.out, L.out);
+        const size_t r2 = pd::gemm_bf16_workspace_bytes(p.B, L.out, 4 * L.out);
+        if (r2 > r) r = r2;
         const size_t one = (size_t)p.B * 4 * L.out * 4;
         if (r < one) r = one;
         if (r > w) w = r;
@@ -762,11 +785,15 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
       const float* cbuf = reinterpret_cast<const float*>(slot + L.c_off);
       const pd::bf16_t* dh_out = reinterpret_cast<const pd::bf16_t*>(cur);
       PD_HIP(pd::fill_zero(s, dc, (size_t)B * H * 4));
+      // dh_{t} needs da_{t+1} W_hh: with W_hh^T laid out [H][4H] that is the same reduction-contiguous product as
+      // in the forward pass, so transpose once per backward pass instead of transposing tiles at every step
+      pd::bf16_t* whh_t = reinterpret_cast<pd::bf16_t*>(st->wt);
+      PD_HIP(pd::transpose_bf16(s, whh, whh_t, 4 * H, H));
       for (int t = L.T - 1; t >= 0; --t) {
         const float* rec = nullptr;
         int splits = 0;
         if (t < L.T - 1) {
-          PD_HIP(pd::gemm_partial_bf16(s, true, dG + (size_t)(t + 1) * B * 4 * H, 4 * H, whh, B, H, 4 * H, st->ws,
+          PD_HIP(pd::gemm_partial_bf16(s, false, dG + (size_t)(t + 1) * B * 4 * H, 4 * H, whh_t, B, H, 4 * H, st->ws,
                                        st->ws_bytes, &splits));
           rec = st->ws;
         }
@@ -841,14 +868,33 @@ int pd_update(pd_stage* st) {
     if (L.kind == K_POOL) continue;
     if (L.kind == K_CONV) {  // partial sums left by pd_backward -> momentum-SGD step into the next ring slot
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
-      PD_HIP(pd::wgrad_reduce_update(s, reinterpret_cast<const float*>(st->part + L.part_off), L.splits, L.n_w,
+      PD_HIP(pd::wgrad_reduce_update(s, reinterpret_cast<const float*>(st->part + L.part_off), L.splits, 0, L.n_w,
                                      (int)L.n_b, st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
                                      st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr, st->mu));
       continue;
     }
     const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
     const char* x = l == 0 ? st->in_slot(mb) : st->out_of(slot, l - 1);
-    if (st->bf16) {
+    if (st->bf16 && L.splits > 0) {  // many rows: partial sums over row ranges, then reduce + update
+      pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
+      const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
+      float* part = reinterpret_cast<float*>(st->part + L.part_off);
+      const size_t n_w1 = (size_t)n_out * L.in;
+      PD_HIP(pd::conv_wgrad_partial_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz), reinterpret_cast<const pd::bf16_t*>(x),
+                                         part, L.splits, rows_as_pixels(L.rows, L.in, n_out)));
+      PD_HIP(pd::wgrad_reduce_update(s, part, L.splits, 0, n_w1, n_out, st->master + L.w_off, st->mom + L.w_off,
+                                     ro + L.w_off, st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr,
+                                     st->mu));
+      if (L.kind == K_LSTM) {
+        float* part2 = reinterpret_cast<float*>(st->part + L.part2_off);
+        const size_t n_w2 = (size_t)n_out * L.out, o2 = L.w_off + n_w1;
+        PD_HIP(pd::conv_wgrad_partial_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
+                                           reinterpret_cast<const pd::bf16_t*>(slot + L.y_off), part2, L.splits2,
+                                           rows_as_pixels(L.rows, L.out, n_out)));
+        PD_HIP(pd::wgrad_reduce_update(s, part2, L.splits2, n_w2 + n_out, n_w2, 0, st->master + o2, st->mom + o2, ro + o2,
+                                       nullptr, nullptr, nullptr, st->lr, st->mu));
+      }
+    } else if (st->bf16) {
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
       auto flush_if_full = [&]() -> hipError_t {
         if (batch.count < pd::kMaxWgradLayers) return hipSuccess;
@@ -1075,7 +1121,7 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
   hipStream_t s = static_cast<hipStream_t>(stream);
   PD_HIP(pd::conv_wgrad_partial_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
                                      part_scratch, splits, g));
-  PD_HIP(pd::wgrad_reduce_update(s, part_scratch, splits, (size_t)g.Co * g.kh * g.kw * g.Ci, g.Co, master_w, mom_w,
+  PD_HIP(pd::wgrad_reduce_update(s, part_scratch, splits, 0, (size_t)g.Co * g.kh * g.kw * g.Ci, g.Co, master_w, mom_w,
                                  static_cast<pd::bf16_t*>(ring_out_w), master_b, mom_b,
                                  static_cast<pd::bf16_t*>(ring_out_b), lr, momentum));
   return PD_OK;

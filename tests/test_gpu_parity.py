@@ -383,6 +383,12 @@ def test_lstm_two_stacked_in_one_stage_free_running():
               noam=1, M=2, depth_override=2, mode="free")
 
 
+def test_lstm_many_rows_uses_partial_sum_weight_gradient():
+    # seq_len * minibatch = 512 rows: the weight gradients go through the large-reduction kernel
+    _seq_case([[("lstm", 24, 16, 16), ("linear", 16, 40, False), ("softmax_xent", 40)]], B=32, T=16, noam=1, M=3,
+              depth_override=2)
+
+
 def test_s2vt_shaped_two_stage_pipeline():
     # the two-stage sequence model at reduced widths: ragged against every tile size
     sl = gen.config4_s2vt(input_size=136, hidden=72, vocab=200, seq_len=7)
@@ -393,9 +399,9 @@ def test_s2vt_shaped_two_stage_pipeline():
 def test_config4_s2vt_full_width_reduced_vocab_and_length():
     # hidden 1000 and input 4096 as configured, minibatch 64; vocabulary and sequence length reduced so the
     # oracle finishes in seconds
-    print("config 4 widths (4096 -> 1000 -> 1000), T = 6, vocab 2000", flush=True)
-    sl = gen.config4_s2vt(vocab=2000, seq_len=6)
-    _seq_case(sl, B=64, T=6, noam=2, M=3, lr=0.01, verbose=True)
+    print("config 4 widths (4096 -> 1000 -> 1000), T = 8, vocab 2000", flush=True)
+    sl = gen.config4_s2vt(vocab=2000, seq_len=8)
+    _seq_case(sl, B=64, T=8, noam=2, M=3, lr=0.01, verbose=True)
 
 
 # ---------------------------------------------------------------------------------------------
