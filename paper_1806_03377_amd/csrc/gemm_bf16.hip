@@ -93,15 +93,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int i = 0; i < BCH; ++i) {
         const int c = t + kThreads * i, row = c / G, rr = r0 + (c % G) * 8, cc = c0 + row;
-        r.b[i] = (live && cc < C && rr < R) ? ldg16(Bm + (size_t)cc * R + rr) : zero16();
+        r.b[i] = (live && cc < C && rr < R) ? ldg16_stream(Bm + (size_t)cc * R + rr) : zero16();
       }
     } else {
 #pragma unroll
       for (int i = 0; i < BCH / 2; ++i) {
         const int b = t + kThreads * i, cch = b % (BN_ / 8), pair = b / (BN_ / 8);
         const int rr = r0 + 2 * pair, cc = c0 + 8 * cch;
-        r.b[2 * i] = (live && rr < R && cc < C) ? ldg16(Bm + (size_t)rr * C + cc) : zero16();
-        r.b[2 * i + 1] = (live && rr + 1 < R && cc < C) ? ldg16(Bm + (size_t)(rr + 1) * C + cc) : zero16();
+        r.b[2 * i] = (live && rr < R && cc < C) ? ldg16_stream(Bm + (size_t)rr * C + cc) : zero16();
+        r.b[2 * i + 1] = (live && rr + 1 < R && cc < C) ? ldg16_stream(Bm + (size_t)(rr + 1) * C + cc) : zero16();
       }
     }
   };
@@ -225,6 +225,16 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __res
 // ------------------------------------------------------------------------------------------------
 constexpr int MC = 64;  // minibatch rows per reduction chunk
 
+typedef float vf4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float* p) {
+  const vf4_t v = __builtin_nontemporal_load(reinterpret_cast<const vf4_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float* p, float4 v) {
+  const vf4_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<vf4_t*>(p));
+}
+
 template <int TN, int TK, bool NFAST, bool PREFETCH>
 __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch) {
   // which layer this workgroup belongs to (all layers of a stage are updated by one launch)
@@ -267,8 +277,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
       const int f = t + kThreads * q, row = f / (TK / 4), k = k0 + (f % (TK / 4)) * 4, n = n0 + row;
       if (n < N && k < K) {
         const size_t off = (size_t)n * K + k;
-        pw[q] = *reinterpret_cast<const float4*>(master + off);
-        pm[q] = *reinterpret_cast<const float4*>(mom + off);
+        pw[q] = nt_load4(master + off);
+        pm[q] = nt_load4(mom + off);
       } else {
         pw[q] = make_float4(0.f, 0.f, 0.f, 0.f);
         pm[q] = pw[q];
@@ -364,12 +374,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
       }
       m.x = mu * m.x + g.x; m.y = mu * m.y + g.y; m.z = mu * m.z + g.z; m.w = mu * m.w + g.w;
       wv.x -= lr * m.x; wv.y -= lr * m.y; wv.z -= lr * m.z; wv.w -= lr * m.w;
-      *reinterpret_cast<float4*>(mom + off) = m;
-      *reinterpret_cast<float4*>(master + off) = wv;
+      nt_store4(mom + off, m);     // streamed once per step: keep these lines out of the caches
+      nt_store4(master + off, wv);
       uint2 pk;
       pk.x = (uint32_t)f2bf(wv.x) | ((uint32_t)f2bf(wv.y) << 16);
       pk.y = (uint32_t)f2bf(wv.z) | ((uint32_t)f2bf(wv.w) << 16);
-      *reinterpret_cast<uint2*>(ring + off) = pk;
+      *reinterpret_cast<uint2*>(ring + off) = pk;  // read back by the next forward pass: ordinary store (measured:
+                                                    // a non-temporal store here costs the update more than the forward gains)
     }
   }
 

@@ -23,6 +23,13 @@ constexpr int kThreads = 256;
 
 __device__ __forceinline__ uint4 ldg16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
+// 16-byte load of data that is read once per kernel (a weight stream): non-temporal, so that it does not push
+// reusable lines (activations, partial sums) out of the caches
+typedef unsigned int vu4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldg16_stream(const bf16_t* p) {
+  const vu4_t v = __builtin_nontemporal_load(reinterpret_cast<const vu4_t*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // XOR swizzle of the 16-byte groups of an LDS row that holds 8*G reduction elements of one output row/column
 // (G groups).  Spreads both the transposing 4-byte writes (lanes differ in their column chunk and reduction
