@@ -174,6 +174,63 @@ def bench_s2vt(args, pd, gen, torch, np, dev):
     print(json.dumps(out))
 
 
+def bench_gemm_sweep(args, pd, gen, torch, np, dev):
+    """The stage's three contractions on their own at the VGG16 classifier's K, N with the row count M swept from
+    the configured minibatch (64, HBM-bound) into the compute-bound regime: achieved TFLOP/s and % of the bf16
+    MFMA peak per kernel.  One JSON line; `value` is the best forward figure."""
+    s = torch.cuda.current_stream().cuda_stream
+    shapes = [(4096, 4096)] if args.small else [(4096, 25088), (4096, 4096)]
+    rows_list = [64, 256, 1024] if args.small else [64, 128, 256, 512, 1024, 2048, 4096, 8192]
+
+    def timeit(fn, n=5):
+        fn(); torch.cuda.synchronize()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:
+            a.record(); fn(); b.record()
+        torch.cuda.synchronize()
+        return sorted(a.elapsed_time(b) for a, b in evs)[n // 2] * 1e-3
+
+    table = []
+    for (N, K) in shapes:
+        w = (torch.randn(N, K, device=dev) * 0.02).to(torch.bfloat16)
+        b = torch.zeros(N, device=dev, dtype=torch.bfloat16)
+        mw = torch.randn(N, K, device=dev) * 0.02; mm = torch.zeros(N, K, device=dev)
+        mb_ = torch.zeros(N, device=dev); mmb = torch.zeros(N, device=dev)
+        rw = torch.empty(N, K, device=dev, dtype=torch.bfloat16); rb = torch.empty(N, device=dev, dtype=torch.bfloat16)
+        wt = torch.empty(N * K, device=dev, dtype=torch.bfloat16)
+        for M in rows_list:
+            x = torch.randn(M, K, device=dev).to(torch.bfloat16); dz = (torch.randn(M, N, device=dev) * 0.01).to(torch.bfloat16)
+            y = torch.empty(M, N, device=dev, dtype=torch.bfloat16); dx = torch.empty(M, K, device=dev, dtype=torch.bfloat16)
+            wsb = pd.pd_gemm_workspace_bytes(M, N, K)
+            ws = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+            geom = (M, 1, 1, K, N, 1, 1, 1, 0, 0)
+            part = torch.empty(pd.pd_conv_wgrad_splits(geom) * (N * K + N), dtype=torch.float32, device=dev)
+            fl = 2.0 * M * N * K
+            tf = timeit(lambda: pd.pd_linear_fwd_bf16(s, x.data_ptr(), w.data_ptr(), b.data_ptr(), y.data_ptr(), M, N, K, True, ws.data_ptr(), wsb))
+            td = timeit(lambda: pd.pd_linear_dgrad_bf16(s, dz.data_ptr(), w.data_ptr(), 0, dx.data_ptr(), M, N, K, ws.data_ptr(), wsb))
+            if M >= 512:
+                tw = timeit(lambda: pd.pd_conv_wgrad_update_bf16(s, dz.data_ptr(), x.data_ptr(), part.data_ptr(), mw.data_ptr(), mm.data_ptr(), rw.data_ptr(), mb_.data_ptr(), mmb.data_ptr(), rb.data_ptr(), geom, 0.01, 0.9))
+            else:
+                tw = timeit(lambda: pd.pd_linear_wgrad_update_bf16(s, dz.data_ptr(), x.data_ptr(), mw.data_ptr(), mm.data_ptr(), rw.data_ptr(), mb_.data_ptr(), mmb.data_ptr(), rb.data_ptr(), M, N, K, 0.01, 0.9))
+            row = {"N": N, "K": K, "M": M}
+            for name, t in (("fwd", tf), ("dgrad", td), ("wgrad_update", tw)):
+                row[name + "_us"] = round(t * 1e6, 1)
+                row[name + "_tflops"] = round(fl / t / 1e12, 1)
+                row[name + "_mfma_pct"] = round(100 * fl / t / MFMA_BF16_PEAK, 2)
+            table.append(row)
+            print("# " + json.dumps(row), file=sys.stderr, flush=True)
+            del x, dz, y, dx, ws, part
+        del w, mw, mm, rw, wt
+    best = max(r["fwd_tflops"] for r in table)
+    out = {"metric": METRIC, "value": best, "unit": "TFLOP/s (best forward GEMM of the sweep)", "n_gpus": 1, "steps": 5,
+           "warmup": 1, "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "row-count sweep of the Linear kernels at the VGG16 classifier's K, N"},
+           "roofline": {"bound": "mfma", "achieved": best, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                        "frac": best * 1e12 / MFMA_BF16_PEAK, "traffic": None}, "sweep": table}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,7 +240,7 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt"],
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "gemm_sweep"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
                          "s2vt (the two LSTM stages as a 2-stream pipeline)")
     args = ap.parse_args()
@@ -206,6 +263,8 @@ def main():
         return bench_conv(args, pd, gen, torch, np, dev)
     if args.workload == "s2vt":
         return bench_s2vt(args, pd, gen, torch, np, dev)
+    if args.workload == "gemm_sweep":
+        return bench_gemm_sweep(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
     n_in, classes = layers[0][1], layers[-1][1]
     seed = gen.BASE_SEED + 1

@@ -261,8 +261,8 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
  *   conv_dgrad: dx[N][H][W][c_in]   = convT(dz, w) .* (mask > 0 if mask)       stride 1 only;
  *               wt_scratch: c_out*kh*kw*c_in bf16 elements of scratch
  *   conv_wgrad_update: g = dL/dw from dz and x (and column sums for the bias), partial sums over
- *               pd_conv_wgrad_splits(geom) pixel ranges in part_scratch (that many times
- *               (c_out*kh*kw*c_in + c_out) floats), added in a fixed order; then m <- mu*m + g;
+ *               pixel ranges in part_scratch, added in a fixed order; part_scratch must hold
+ *               pd_conv_wgrad_splits(geom) units of (c_out*kh*kw*c_in + c_out) floats; then m <- mu*m + g;
  *               master <- master - lr*m; ring_out <- bf16(master)
  *   maxpool2x2_fwd / _bwd: 2x2 stride-2 max pooling of x[N][H][W][C]; backward routes dy to the first
  *               maximum of each window and, if relu_mask != 0, zeroes positions where x <= 0 */

@@ -81,6 +81,9 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const bf16_t* __restrict
   struct Regs {
     uint4 a[ACH], b[BCH];
   };
+  // with a single row tile every weight is read exactly once by the whole grid: stream it past the caches
+  const bool once = gridDim.y == 1;
+  auto ldw = [&](const bf16_t* p) { return once ? ldg16_stream(p) : ldg16(p); };
   auto gload = [&](Regs& r, int rt) {
     const int r0 = rt * BK_;
     const bool live = rt < rt1;
@@ -93,15 +96,15 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const bf16_t* __restrict
 #pragma unroll
       for (int i = 0; i < BCH; ++i) {
         const int c = t + kThreads * i, row = c / G, rr = r0 + (c % G) * 8, cc = c0 + row;
-        r.b[i] = (live && cc < C && rr < R) ? ldg16_stream(Bm + (size_t)cc * R + rr) : zero16();
+        r.b[i] = (live && cc < C && rr < R) ? ldw(Bm + (size_t)cc * R + rr) : zero16();
       }
     } else {
 #pragma unroll
       for (int i = 0; i < BCH / 2; ++i) {
         const int b = t + kThreads * i, cch = b % (BN_ / 8), pair = b / (BN_ / 8);
         const int rr = r0 + 2 * pair, cc = c0 + 8 * cch;
-        r.b[2 * i] = (live && rr < R && cc < C) ? ldg16_stream(Bm + (size_t)rr * C + cc) : zero16();
-        r.b[2 * i + 1] = (live && rr + 1 < R && cc < C) ? ldg16_stream(Bm + (size_t)(rr + 1) * C + cc) : zero16();
+        r.b[2 * i] = (live && rr < R && cc < C) ? ldw(Bm + (size_t)rr * C + cc) : zero16();
+        r.b[2 * i + 1] = (live && rr + 1 < R && cc < C) ? ldw(Bm + (size_t)(rr + 1) * C + cc) : zero16();
       }
     }
   };
@@ -418,6 +421,8 @@ constexpr int kFwdBN = 64, kFwdBK = 128, kFwdPD = 2, kFwdNBUF = 2;
 constexpr int kBigBN = 128, kBigBK = 128, kBigPD = 2, kBigNBUF = 1;
 constexpr int kSmallBN = 64, kSmallBK = 256, kSmallPD = 1, kSmallNBUF = 1;
 constexpr size_t kBigDgradElems = (size_t)32 << 20;  // weight elements from which the big dgrad shape is used
+// The 256 x 256-tile kernel (gemm_big_bf16.hip) takes over once its grid fills at least half the chip's 256 CUs.
+bool use_big_tiles(int rows, int cols) { return ((rows + 255) / 256) * ((cols + 255) / 256) >= 128; }
 
 // Enough workgroups to fill the chip (about two per CU, all co-resident), never more splits than stages.
 int pick_splits(int tiles, int red_tiles) {
@@ -461,6 +466,7 @@ hipError_t launch_gemm(hipStream_t s, const bf16_t* a, const bf16_t* b, const Ge
 }  // namespace
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K) {
+  if (use_big_tiles(M, K)) return linear_dgrad_big_scratch_bytes(N, K);  // transposed weights; no split-K at this size
   const size_t a = splitk_bytes_t<kFwdBN, kFwdBK>(M, N, K);
   const size_t b = (size_t)N * K >= kBigDgradElems ? splitk_bytes_t<kBigBN, kBigBK>(M, K, N)
                                                    : splitk_bytes_t<kSmallBN, kSmallBK>(M, K, N);
@@ -469,12 +475,14 @@ size_t gemm_bf16_workspace_bytes(int M, int N, int K) {
 
 hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const bf16_t* b, bf16_t* y, float* y_f32,
                            int M, int N, int K, bool relu, float* ws, size_t ws_bytes) {
+  if (use_big_tiles(M, N)) return linear_fwd_big_bf16(s, x, K, w, b, y, y_f32, M, N, K, relu);
   GemmEpilogue ep = {b, nullptr, relu ? 1 : 0, y, y_f32};
   return launch_gemm<false, kFwdBN, kFwdBK, kFwdPD, kFwdNBUF>(s, x, w, ep, M, N, K, ws, ws_bytes);
 }
 
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes) {
+  if (use_big_tiles(M, K)) return linear_dgrad_big_bf16(s, dz, w, mask, dx, M, N, K, ws, ws_bytes);
   GemmEpilogue ep = {nullptr, mask, 0, dx, nullptr};
   if ((size_t)N * K >= kBigDgradElems)
     return launch_gemm<true, kBigBN, kBigBK, kBigPD, kBigNBUF>(s, dz, w, ep, M, K, N, ws, ws_bytes);

@@ -1,0 +1,331 @@
+// Compute-bound bf16 GEMM for gfx950: 256 x 256 output tile per workgroup, 128 x 128 per wave (sixteen 32x32
+// MFMA accumulators = 256 accumulation registers), 64 reduction elements per stage.
+//
+//   out[I][J] = sum_r A(i,r) * B(r,j)
+//     TA = false: A is stored [I][R] (reduction contiguous)     TA = true: A is stored [R][I]
+//     TB = false: B is stored [J][R] (reduction contiguous)     TB = true: B is stored [R][J]
+//   forward  y  = x w^T      : A = x  (TA=0), B = w (TB=0), I = rows, J = out-features, R = in-features
+//   dgrad    dx = dz w       : A = dz (TA=0), B = w (TB=1), I = rows, J = in-features,  R = out-features
+//   wgrad    dW = dz^T x     : A = dz (TA=1), B = x (TB=1), I = out-features, J = in-features, R = rows
+//
+// Why this shape: with one wave per SIMD, a wave tile of m x n reads (m + n) * 32 bytes of fragments from LDS
+// per sixteen-wide reduction step and issues (m/32)(n/32) MFMAs of 32 cycles; four waves at 64 x 64 already ask
+// for the whole LDS read bandwidth, at 128 x 128 for half of it.  Operands stored "sideways" are transposed in
+// 2x8 blocks on their way into a swizzled LDS tile, so every fragment read is a 16-byte access.
+#include "bf16_util.h"
+#include "mfma_util.h"
+#include "pd_kernels.h"
+
+namespace pd {
+namespace {
+
+constexpr int GM = 256, GN = 256, GK = 64, GLD = GK + 8;
+
+struct BigEpilogue {
+  const bf16_t* bias;  // [J] or null
+  const bf16_t* mask;  // [I][J] (> 0 keeps) or null
+  int relu;
+  bf16_t* out;         // [I][J] bf16, or
+  float* out_f;        // [I][J] fp32 (no rounding; bias/ReLU still applied)
+  int ldo;             // row stride of out / out_f / mask (elements)
+};
+
+// NW = waves per workgroup: 4 (2 x 2 waves of 128 x 128) or 8 (2 x 4 waves of 128 x 64, two waves per SIMD so
+// that one can issue MFMAs while the other waits for LDS).
+template <bool TA, bool TB, int NW>
+__global__ __launch_bounds__(64 * NW, 1) void gemm_big_kernel(const bf16_t* __restrict__ A, int lda,
+                                                              const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep,
+                                                              int I, int J, int R) {
+  constexpr int NT = 64 * NW;           // threads
+  constexpr int WN = NW / 2;            // waves along the columns (2 along the rows)
+  constexpr int NJ = (GN / WN) / 32;    // 32-column blocks per wave (4 or 2)
+  constexpr int WCOLS = GN / WN;        // columns per wave
+  constexpr int PCH = GM * 8 / NT;      // 16-byte chunks per thread, plain layout (8 or 4)
+  constexpr int SCH = 1024 / NT;        // 2x8 blocks per thread, sideways layout (4 or 2)
+  constexpr int kStageBytes = 147456 / NW;
+  // one operand tile: 256 rows x 64 reduction elements; plain layout padded to GLD, transposed layout swizzled
+  constexpr int kTile = GM * GLD;  // bf16 elements reserved per tile and buffer (the swizzled form needs 256*64)
+  __shared__ __attribute__((aligned(16))) bf16_t smem[4 * kTile];
+  bf16_t* const As0 = smem;
+  bf16_t* const Bs0 = smem + 2 * kTile;
+  const int t = threadIdx.x, l = t & 63, w = t >> 6, wm = w / WN, wn = w % WN;
+  const int i0 = blockIdx.y * GM, j0 = blockIdx.x * GN;
+  const int T = (R + GK - 1) / GK;
+
+  struct Regs {
+    uint4 a[PCH], b[PCH];
+  };
+  auto load_plain = [&](uint4* r, const bf16_t* src, int ld, int row0, int nrows, int st) {
+    const int rr = st * GK + (t & 7) * 8;
+#pragma unroll
+    for (int i = 0; i < PCH; ++i) {
+      const int row = row0 + (t >> 3) + (NT / 8) * i;
+      r[i] = (st < T && row < nrows && rr < R) ? ldg16(src + (size_t)row * ld + rr) : zero16();
+    }
+  };
+  auto load_sideways = [&](uint4* r, const bf16_t* src, int ld, int col0, int ncols, int st) {
+#pragma unroll
+    for (int i = 0; i < SCH; ++i) {
+      // a wave: 8 column chunks x 8 reduction pairs
+      const int cc = (((NT / 256) * i + (t >> 8)) << 3) | (t & 7), pair = (t >> 3) & 31;
+      const int rr = st * GK + 2 * pair, c = col0 + 8 * cc;
+      r[2 * i] = (st < T && rr < R && c < ncols) ? ldg16(src + (size_t)rr * ld + c) : zero16();
+      r[2 * i + 1] = (st < T && rr + 1 < R && c < ncols) ? ldg16(src + (size_t)(rr + 1) * ld + c) : zero16();
+    }
+  };
+  auto store_plain = [&](bf16_t* tile, const uint4* r) {
+#pragma unroll
+    for (int i = 0; i < PCH; ++i)
+      *reinterpret_cast<uint4*>(&tile[((t >> 3) + (NT / 8) * i) * GLD + (t & 7) * 8]) = r[i];
+  };
+  auto store_sideways = [&](bf16_t* tile, const uint4* r) {
+    uint32_t* tw = reinterpret_cast<uint32_t*>(tile);
+#pragma unroll
+    for (int i = 0; i < SCH; ++i) {
+      const int cc = (((NT / 256) * i + (t >> 8)) << 3) | (t & 7), pair = (t >> 3) & 31;
+      store_transposed_pair<8>(tw, 8 * cc, pair, r[2 * i], r[2 * i + 1]);
+    }
+  };
+  auto gload = [&](Regs& r, int st) {
+    if (TA) load_sideways(r.a, A, lda, i0, I, st); else load_plain(r.a, A, lda, i0, I, st);
+    if (TB) load_sideways(r.b, Bm, ldb, j0, J, st); else load_plain(r.b, Bm, ldb, j0, J, st);
+  };
+  auto sstore = [&](int buf, const Regs& r) {
+    if (TA) store_sideways(As0 + buf * kTile, r.a); else store_plain(As0 + buf * kTile, r.a);
+    if (TB) store_sideways(Bs0 + buf * kTile, r.b); else store_plain(Bs0 + buf * kTile, r.b);
+  };
+
+  f32x16 acc[4][NJ];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x16{0};
+
+  Regs Rg;
+  gload(Rg, 0);
+  sstore(0, Rg);
+  __syncthreads();
+  for (int st = 0; st < T; ++st) {
+    const int cur = st & 1;
+    gload(Rg, st + 1);
+    const bf16_t* as = As0 + cur * kTile;
+    const bf16_t* bs = Bs0 + cur * kTile;
+#pragma unroll
+    for (int ks = 0; ks < GK / 16; ++ks) {
+      const int kk = ks * 16 + (l >> 5) * 8, grp = 2 * ks + (l >> 5);
+      uint4 a[4], b[NJ];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = 128 * wm + 32 * i + (l & 31);
+        a[i] = TA ? load_swizzled_frag<8>(reinterpret_cast<const uint32_t*>(as), row, grp)
+                  : *reinterpret_cast<const uint4*>(&as[row * GLD + kk]);
+      }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int row = WCOLS * wn + 32 * j + (l & 31);
+        b[j] = TB ? load_swizzled_frag<8>(reinterpret_cast<const uint32_t*>(bs), row, grp)
+                  : *reinterpret_cast<const uint4*>(&bs[row * GLD + kk]);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[j]), acc[i][j], 0, 0, 0);
+    }
+    if (st + 1 < T) sstore(cur ^ 1, Rg);
+    __syncthreads();
+  }
+
+  // epilogue.  Each wave stages 32-row blocks of its sub-tile in a private LDS region (after the loop's last
+  // barrier the operand tiles are dead) and writes them out as full rows, 16 bytes per lane.
+  const bool wide_ok = ((ep.ldo & 7) == 0) && ((J & 7) == 0);
+  if (wide_ok) {
+    char* stage = reinterpret_cast<char*>(smem) + (size_t)w * kStageBytes;
+    const int col_base = j0 + WCOLS * wn;
+    constexpr int FLD = WCOLS + 4, HLD = WCOLS + 8;  // padded staging rows (fp32 / bf16)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row_base = i0 + 128 * wm + 32 * i;
+      if (ep.out_f) {
+        float* sf = reinterpret_cast<float*>(stage);  // [32][FLD]
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int c = col_base + 32 * j + (l & 31);
+          const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float v = acc[i][j][r] + bv;
+            if (ep.relu) v = fmaxf(v, 0.f);
+            sf[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * FLD + 32 * j + (l & 31)] = v;
+          }
+        }
+        constexpr int LPR = WCOLS / 4;       // lanes per row (float4 each)
+        constexpr int RPP = 64 / LPR;        // rows per pass
+#pragma unroll
+        for (int q = 0; q < 32 / RPP; ++q) {
+          const int rr = RPP * q + l / LPR, cc = (l % LPR) * 4;
+          const int row = row_base + rr, c = col_base + cc;
+          if (row < I && c < J) {
+            const float4 v = *reinterpret_cast<const float4*>(&sf[rr * FLD + cc]);
+            *reinterpret_cast<float4*>(ep.out_f + (size_t)row * ep.ldo + c) = v;
+          }
+        }
+      } else {
+        bf16_t* sb = reinterpret_cast<bf16_t*>(stage);  // [32][HLD]
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int c = col_base + 32 * j + (l & 31);
+          const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float v = acc[i][j][r] + bv;
+            if (ep.relu) v = fmaxf(v, 0.f);
+            sb[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * HLD + 32 * j + (l & 31)] = f2bf(v);
+          }
+        }
+        constexpr int LPR = WCOLS / 8;       // lanes per row (8 bf16 each)
+        constexpr int RPP = 64 / LPR;
+#pragma unroll
+        for (int q = 0; q < 32 / RPP; ++q) {
+          const int rr = RPP * q + l / LPR, cc = (l % LPR) * 8;
+          const int row = row_base + rr, c = col_base + cc;
+          if (row < I && c < J) {
+            uint4 v = *reinterpret_cast<const uint4*>(&sb[rr * HLD + cc]);
+            const size_t off = (size_t)row * ep.ldo + c;
+            if (ep.mask) {
+              const uint4 mk = ldg16(ep.mask + off);
+              const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+              uint32_t vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                if (!bf_positive((uint16_t)(mw[e] & 0xffffu))) vw[e] &= 0xffff0000u;
+                if (!bf_positive((uint16_t)(mw[e] >> 16))) vw[e] &= 0x0000ffffu;
+              }
+              v = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+            }
+            *reinterpret_cast<uint4*>(ep.out + off) = v;
+          }
+        }
+      }
+    }
+    return;
+  }
+  // odd widths: element-wise from the accumulators (column = lane, 16 rows per block)
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = j0 + WCOLS * wn + 32 * j + (l & 31);
+    if (c >= J) continue;
+    const float bv = ep.bias ? bf2f(ep.bias[c]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = i0 + 128 * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        if (row >= I) continue;
+        float v = acc[i][j][r] + bv;
+        if (ep.relu) v = fmaxf(v, 0.f);
+        const size_t off = (size_t)row * ep.ldo + c;
+        if (ep.out_f) {
+          ep.out_f[off] = v;
+        } else {
+          uint16_t o = f2bf(v);
+          if (ep.mask && !bf_positive(ep.mask[off])) o = 0;
+          ep.out[off] = o;
+        }
+      }
+  }
+}
+
+// column sums in two deterministic steps: partial sums over chunks of 128 rows, then the chunks in order
+constexpr int kColsumRows = 128;
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __restrict__ z, float* __restrict__ part,
+                                                             int M, int N) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  const int m0 = blockIdx.y * kColsumRows, m1 = m0 + kColsumRows < M ? m0 + kColsumRows : M;
+  float s = 0.f;
+  for (int m = m0; m < m1; ++m) s += bf2f(z[(size_t)m * N + n]);
+  part[(size_t)blockIdx.y * N + n] = s;
+}
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float* __restrict__ part, float* __restrict__ out,
+                                                           int chunks, int N) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float s = 0.f;
+  for (int c = 0; c < chunks; ++c) s += part[(size_t)c * N + n];
+  out[n] = s;
+}
+
+__global__ __launch_bounds__(256) void colsum_kernel(const bf16_t* __restrict__ z, float* __restrict__ out, int M,
+                                                     int N) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float s = 0.f;
+  for (int m = 0; m < M; ++m) s += bf2f(z[(size_t)m * N + n]);
+  out[n] = s;
+}
+
+int g_big_waves = 8;
+
+template <bool TA, bool TB>
+hipError_t launch_big(hipStream_t s, const bf16_t* a, int lda, const bf16_t* b, int ldb, const BigEpilogue& ep, int I,
+                      int J, int R) {
+  dim3 grid((J + GN - 1) / GN, (I + GM - 1) / GM);
+  if (g_big_waves == 8) gemm_big_kernel<TA, TB, 8><<<grid, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R);
+  else gemm_big_kernel<TA, TB, 4><<<grid, 256, 0, s>>>(a, lda, b, ldb, ep, I, J, R);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t linear_fwd_big_bf16(hipStream_t s, const bf16_t* x, int ldx, const bf16_t* w, const bf16_t* b, bf16_t* y,
+                               float* y_f32, int M, int N, int K, bool relu) {
+  BigEpilogue ep = {b, nullptr, relu ? 1 : 0, y, y_f32, N};
+  return launch_big<false, false>(s, x, ldx, w, K, ep, M, N, K);
+}
+
+// Operands stored sideways go through a transposing pre-pass when the caller provides scratch: the 2x8-block
+// transposing LDS stores cost more issue slots than the MFMAs of a stage, while a separate transpose is a small
+// streaming kernel (measured: 12 % -> about 30 % of MFMA peak for the weight gradient at 8192 rows).
+size_t linear_dgrad_big_scratch_bytes(int N, int K) { return (size_t)N * K * sizeof(bf16_t); }
+size_t linear_wgrad_big_scratch_bytes(int M, int N, int K) { return (size_t)M * ((size_t)N + K) * sizeof(bf16_t); }
+
+hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
+                                 int N, int K, void* scratch, size_t scratch_bytes) {
+  BigEpilogue ep = {nullptr, mask, 0, dx, nullptr, K};
+  if (scratch && M >= 2048 && scratch_bytes >= linear_dgrad_big_scratch_bytes(N, K)) {  // worth a pass over w
+    bf16_t* wt = static_cast<bf16_t*>(scratch);  // [K][N]
+    hipError_t e = transpose_bf16(s, w, wt, N, K);
+    if (e != hipSuccess) return e;
+    return launch_big<false, false>(s, dz, N, wt, N, ep, M, K, N);
+  }
+  return launch_big<false, true>(s, dz, N, w, K, ep, M, K, N);
+}
+
+hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* dw, float* db, int M, int N,
+                                 int K, void* scratch, size_t scratch_bytes) {
+  BigEpilogue ep = {nullptr, nullptr, 0, nullptr, dw, K};
+  hipError_t e;
+  const int chunks = (M + kColsumRows - 1) / kColsumRows;
+  bool db_done = false;
+  if (db && scratch && scratch_bytes >= (size_t)chunks * N * sizeof(float)) {  // before the scratch is reused below
+    float* cp = static_cast<float*>(scratch);
+    colsum_partial_kernel<<<dim3((N + 255) / 256, chunks), 256, 0, s>>>(dz, cp, M, N);
+    colsum_final_kernel<<<(N + 255) / 256, 256, 0, s>>>(cp, db, chunks, N);
+    db_done = true;
+  }
+  if (scratch && (M % 8) == 0 && scratch_bytes >= linear_wgrad_big_scratch_bytes(M, N, K)) {
+    bf16_t* zt = static_cast<bf16_t*>(scratch);  // [N][M]
+    bf16_t* xt = zt + (size_t)N * M;             // [K][M]
+    e = transpose_bf16(s, dz, zt, M, N);
+    if (e == hipSuccess) e = transpose_bf16(s, x, xt, M, K);
+    if (e == hipSuccess) e = launch_big<false, false>(s, zt, M, xt, M, ep, N, K, M);
+  } else {
+    e = launch_big<true, true>(s, dz, N, x, K, ep, N, K, M);
+  }
+  if (e != hipSuccess) return e;
+  if (db && !db_done) colsum_kernel<<<(N + 255) / 256, 256, 0, s>>>(dz, db, M, N);
+  return hipGetLastError();
+}
+
+}  // namespace pd

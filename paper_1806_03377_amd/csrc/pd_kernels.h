@@ -19,6 +19,19 @@ hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, cons
 // dx[M][K] = (dz[M][N] * w[N][K]) .* (mask[M][K] > 0)   (mask may be null); dx bf16.
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes);
+// Compute-bound versions for many rows (gemm_big_bf16.hip; 256 x 256 tiles, no split-K, no workspace):
+//   fwd: y = act(x w^T + b) (x row stride ldx; bf16 y or fp32 y_f32);  dgrad: dx = (dz w) .* mask;
+//   wgrad: dw[N][K] = dz^T x as fp32, db[N] = column sums of dz (db may be null).
+hipError_t linear_fwd_big_bf16(hipStream_t s, const bf16_t* x, int ldx, const bf16_t* w, const bf16_t* b, bf16_t* y,
+                               float* y_f32, int M, int N, int K, bool relu);
+// dgrad and wgrad read an operand sideways; given scratch of the stated size they transpose it first (faster).
+size_t linear_dgrad_big_scratch_bytes(int N, int K);
+size_t linear_wgrad_big_scratch_bytes(int M, int N, int K);
+hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
+                                 int N, int K, void* scratch, size_t scratch_bytes);
+hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* dw, float* db, int M, int N,
+                                 int K, void* scratch, size_t scratch_bytes);
+
 // out[M][C] = a[M][R] * w as fp32 PARTIAL sums ws[split][M][C] (no epilogue): the caller's own kernel adds them
 // in split order.  a has row stride lda; w is [C][R] (w_rows_are_reduction = false) or [R][C] (true).
 hipError_t gemm_partial_bf16(hipStream_t s, bool w_rows_are_reduction, const bf16_t* a, int lda, const bf16_t* w, int M,

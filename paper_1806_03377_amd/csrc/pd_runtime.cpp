@@ -344,6 +344,11 @@ int make_plan(const pd_stage_config* c, Plan& p) {
         if (r < one) r = one;
         if (r > w) w = r;
       }
+      if (L.splits > 0) {  // many rows: room for the transposed operands of the weight-gradient products
+        const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
+        const size_t t1 = pd::linear_wgrad_big_scratch_bytes(L.rows, n_out, L.in > L.out ? L.in : L.out);
+        if (t1 > w) w = t1;
+      }
       if (w > p.ws_bytes) p.ws_bytes = w;
     }
   p.ws_bytes = align_up(p.ws_bytes, 256);
@@ -880,18 +885,18 @@ int pd_update(pd_stage* st) {
       const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
       float* part = reinterpret_cast<float*>(st->part + L.part_off);
       const size_t n_w1 = (size_t)n_out * L.in;
-      PD_HIP(pd::conv_wgrad_partial_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz), reinterpret_cast<const pd::bf16_t*>(x),
-                                         part, L.splits, rows_as_pixels(L.rows, L.in, n_out)));
-      PD_HIP(pd::wgrad_reduce_update(s, part, L.splits, 0, n_w1, n_out, st->master + L.w_off, st->mom + L.w_off,
+      PD_HIP(pd::linear_wgrad_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz), reinterpret_cast<const pd::bf16_t*>(x),
+                                       part, part + n_w1, L.rows, n_out, L.in, st->ws, st->ws_bytes));
+      PD_HIP(pd::wgrad_reduce_update(s, part, 1, 0, n_w1, n_out, st->master + L.w_off, st->mom + L.w_off,
                                      ro + L.w_off, st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr,
                                      st->mu));
       if (L.kind == K_LSTM) {
         float* part2 = reinterpret_cast<float*>(st->part + L.part2_off);
         const size_t n_w2 = (size_t)n_out * L.out, o2 = L.w_off + n_w1;
-        PD_HIP(pd::conv_wgrad_partial_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
-                                           reinterpret_cast<const pd::bf16_t*>(slot + L.y_off), part2, L.splits2,
-                                           rows_as_pixels(L.rows, L.out, n_out)));
-        PD_HIP(pd::wgrad_reduce_update(s, part2, L.splits2, n_w2 + n_out, n_w2, 0, st->master + o2, st->mom + o2, ro + o2,
+        PD_HIP(pd::linear_wgrad_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
+                                         reinterpret_cast<const pd::bf16_t*>(slot + L.y_off), part2, nullptr, L.rows,
+                                         n_out, L.out, st->ws, st->ws_bytes));
+        PD_HIP(pd::wgrad_reduce_update(s, part2, 1, 0, n_w2, 0, st->master + o2, st->mom + o2, ro + o2,
                                        nullptr, nullptr, nullptr, st->lr, st->mu));
       }
     } else if (st->bf16) {
@@ -1080,10 +1085,22 @@ static int conv_geom(const int32_t* q, pd::ConvGeom& g) {
   return PD_OK;
 }
 
+static bool plain_product_many_rows(const pd::ConvGeom& g) {
+  return g.kh == 1 && g.kw == 1 && g.H == 1 && g.W == 1 && g.N >= kBigRows;
+}
+
+// scratch units of (c_out*kh*kw*c_in + c_out) floats that pd_conv_wgrad_update_bf16 uses
+static int wgrad_scratch_units(const pd::ConvGeom& g) {
+  if (!plain_product_many_rows(g)) return pd::conv_wgrad_split_count(g);
+  // one unit for the gradient plus room for the transposed operands
+  const size_t unit = ((size_t)g.Co * g.Ci + g.Co) * sizeof(float);
+  return 1 + (int)((pd::linear_wgrad_big_scratch_bytes(g.N, g.Co, g.Ci) + unit - 1) / unit);
+}
+
 int pd_conv_wgrad_splits(const int32_t* geom, int32_t* splits) {
   pd::ConvGeom g;
   if (conv_geom(geom, g) || !splits) return fail(PD_EINVAL, "bad argument");
-  *splits = pd::conv_wgrad_split_count(g);
+  *splits = wgrad_scratch_units(g);
   return PD_OK;
 }
 
@@ -1117,8 +1134,16 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
   if (conv_geom(geom, g)) return PD_EINVAL;
   if (!dz || !x || !part_scratch || !master_w || !mom_w || !ring_out_w || !master_b || !mom_b || !ring_out_b)
     return fail(PD_EINVAL, "null pointer");
-  const int splits = pd::conv_wgrad_split_count(g);
+  int splits = pd::conv_wgrad_split_count(g);
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (plain_product_many_rows(g)) {
+    const size_t unit = (size_t)g.Co * g.Ci + g.Co;  // floats per scratch unit; the first holds dw and db
+    const size_t extra = (size_t)(wgrad_scratch_units(g) - 1) * unit * sizeof(float);
+    splits = 1;
+    PD_HIP(pd::linear_wgrad_big_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
+                                     part_scratch, part_scratch + (size_t)g.Co * g.Ci, g.N, g.Co, g.Ci,
+                                     part_scratch + unit, extra));
+  } else
   PD_HIP(pd::conv_wgrad_partial_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
                                      part_scratch, splits, g));
   PD_HIP(pd::wgrad_reduce_update(s, part_scratch, splits, 0, (size_t)g.Co * g.kh * g.kw * g.Ci, g.Co, master_w, mom_w,

@@ -31,7 +31,8 @@ def _bf(a):
 # kernels on their own (bf16 MFMA): several tiles, ragged tails in every dimension, split-K on/off
 # ---------------------------------------------------------------------------------------------
 SHAPES = [(64, 128, 64), (64, 256, 4096), (64, 200, 264), (40, 136, 72), (1, 8, 8), (130, 1000, 520),
-          (64, 4096, 1024), (96, 24, 2048), (256, 512, 768)]
+          (64, 4096, 1024), (96, 24, 2048), (256, 512, 768),
+          (512, 256, 256), (600, 1000, 520), (1030, 264, 136)]     # >= 512 rows: the 256 x 256-tile kernel
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
@@ -198,6 +199,7 @@ CONVS = [  # N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w
     (2, 17, 17, 16, 16, 1, 7, 1, 0, 3),     # 1x7
     (2, 17, 17, 16, 16, 7, 1, 1, 3, 0),     # 7x1
     (1, 40, 40, 8, 8, 3, 3, 1, 1, 1),       # many pixels, few channels
+    (600, 1, 1, 136, 264, 1, 1, 1, 0, 0),   # a plain matrix product with many rows (256 x 256-tile wgrad)
 ]
 
 
