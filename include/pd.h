@@ -246,6 +246,11 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
  * disables split-K.
  * stream: hipStream_t.  All pointers device. */
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
+/* Tuning knob (process-wide, not thread-safe): forward and dgrad products whose output has at least `min_tiles`
+ * tiles of 256 x 256 run on the compute-bound large-tile kernels, smaller ones on the split-K kernels built for
+ * minibatch-sized row counts.  Default 128.  Returns the previous value; min_tiles < 1 only queries.  Set it
+ * before pd_gemm_workspace_bytes / pd_stage_query_bytes: the workspace size depends on it. */
+int pd_set_big_tile_threshold(int32_t min_tiles);
 int pd_linear_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, int32_t M, int32_t N,
                        int32_t K, int32_t relu, void* workspace_dev, size_t workspace_bytes);
 int pd_linear_dgrad_bf16(void* stream, const void* dz, const void* w, const void* mask, void* dx, int32_t M,

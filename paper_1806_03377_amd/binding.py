@@ -89,8 +89,10 @@ _lib.pd_last_error.restype = C.c_char_p
 _lib.pd_last_error.argtypes = []
 _lib.pd_gemm_workspace_bytes.restype = _sz
 _lib.pd_gemm_workspace_bytes.argtypes = [_i32, _i32, _i32]
+_lib.pd_set_big_tile_threshold.restype = C.c_int
+_lib.pd_set_big_tile_threshold.argtypes = [_i32]
 
-EXPORTED = sorted(list(_SIGS) + ["pd_last_error", "pd_gemm_workspace_bytes"])
+EXPORTED = sorted(list(_SIGS) + ["pd_last_error", "pd_gemm_workspace_bytes", "pd_set_big_tile_threshold"])
 
 
 def pd_last_error() -> str:
@@ -284,6 +286,10 @@ def pd_pipeline_run(stages: Sequence[int], num_minibatches: int, inputs_dev: int
                     losses_dev: int = 0):
     arr = (_vp * len(stages))(*stages)
     _check(_lib.pd_pipeline_run(arr, len(stages), num_minibatches, inputs_dev, labels_dev, losses_dev or None))
+
+
+def pd_set_big_tile_threshold(min_tiles: int) -> int:
+    return _lib.pd_set_big_tile_threshold(min_tiles)
 
 
 def pd_gemm_workspace_bytes(M: int, N: int, K: int) -> int:

@@ -422,7 +422,8 @@ constexpr int kBigBN = 128, kBigBK = 128, kBigPD = 2, kBigNBUF = 1;
 constexpr int kSmallBN = 64, kSmallBK = 256, kSmallPD = 1, kSmallNBUF = 1;
 constexpr size_t kBigDgradElems = (size_t)32 << 20;  // weight elements from which the big dgrad shape is used
 // The 256 x 256-tile kernel (gemm_big_bf16.hip) takes over once its grid fills at least half the chip's 256 CUs.
-bool use_big_tiles(int rows, int cols) { return ((rows + 255) / 256) * ((cols + 255) / 256) >= 128; }
+int g_big_min_tiles = 128;
+bool use_big_tiles(int rows, int cols) { return ((rows + 255) / 256) * ((cols + 255) / 256) >= g_big_min_tiles; }
 
 // Enough workgroups to fill the chip (about two per CU, all co-resident), never more splits than stages.
 int pick_splits(int tiles, int red_tiles) {
@@ -464,6 +465,12 @@ hipError_t launch_gemm(hipStream_t s, const bf16_t* a, const bf16_t* b, const Ge
 }
 
 }  // namespace
+
+int set_big_tile_threshold(int min_tiles) {
+  const int old = g_big_min_tiles;
+  if (min_tiles >= 1) g_big_min_tiles = min_tiles;
+  return old;
+}
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K) {
   if (use_big_tiles(M, K)) return linear_dgrad_big_scratch_bytes(N, K);  // transposed weights; no split-K at this size

@@ -30,6 +30,108 @@ struct BigEpilogue {
   int ldo;             // row stride of out / out_f / mask (elements)
 };
 
+// Epilogue of one wave's 128 x WCOLS sub-tile (accumulators acc[4][NJ], top-left corner row0, col_base): bias,
+// ReLU, rounding, mask.  The wave stages 32-row blocks in its private LDS region `stage` (the operand tiles are
+// dead by then) and writes them out as full rows, 16 bytes per lane.
+template <int NJ, int WCOLS>
+__device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpilogue& ep, char* stage, int row0,
+                                             int col_base, int l, int I, int J) {
+  const bool wide_ok = ((ep.ldo & 7) == 0) && ((J & 7) == 0);
+  if (wide_ok) {
+    constexpr int FLD = WCOLS + 4, HLD = WCOLS + 8;  // padded staging rows (fp32 / bf16)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row_base = row0 + 32 * i;
+      if (ep.out_f) {
+        float* sf = reinterpret_cast<float*>(stage);  // [32][FLD]
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int c = col_base + 32 * j + (l & 31);
+          const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float v = acc[i][j][r] + bv;
+            if (ep.relu) v = fmaxf(v, 0.f);
+            sf[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * FLD + 32 * j + (l & 31)] = v;
+          }
+        }
+        constexpr int LPR = WCOLS / 4;       // lanes per row (float4 each)
+        constexpr int RPP = 64 / LPR;        // rows per pass
+#pragma unroll
+        for (int q = 0; q < 32 / RPP; ++q) {
+          const int rr = RPP * q + l / LPR, cc = (l % LPR) * 4;
+          const int row = row_base + rr, c = col_base + cc;
+          if (row < I && c < J) {
+            const float4 v = *reinterpret_cast<const float4*>(&sf[rr * FLD + cc]);
+            *reinterpret_cast<float4*>(ep.out_f + (size_t)row * ep.ldo + c) = v;
+          }
+        }
+      } else {
+        bf16_t* sb = reinterpret_cast<bf16_t*>(stage);  // [32][HLD]
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          const int c = col_base + 32 * j + (l & 31);
+          const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            float v = acc[i][j][r] + bv;
+            if (ep.relu) v = fmaxf(v, 0.f);
+            sb[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * HLD + 32 * j + (l & 31)] = f2bf(v);
+          }
+        }
+        constexpr int LPR = WCOLS / 8;       // lanes per row (8 bf16 each)
+        constexpr int RPP = 64 / LPR;
+#pragma unroll
+        for (int q = 0; q < 32 / RPP; ++q) {
+          const int rr = RPP * q + l / LPR, cc = (l % LPR) * 8;
+          const int row = row_base + rr, c = col_base + cc;
+          if (row < I && c < J) {
+            uint4 v = *reinterpret_cast<const uint4*>(&sb[rr * HLD + cc]);
+            const size_t off = (size_t)row * ep.ldo + c;
+            if (ep.mask) {
+              const uint4 mk = ldg16(ep.mask + off);
+              const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+              uint32_t vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                if (!bf_positive((uint16_t)(mw[e] & 0xffffu))) vw[e] &= 0xffff0000u;
+                if (!bf_positive((uint16_t)(mw[e] >> 16))) vw[e] &= 0x0000ffffu;
+              }
+              v = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+            }
+            *reinterpret_cast<uint4*>(ep.out + off) = v;
+          }
+        }
+      }
+    }
+    return;
+  }
+  // odd widths: element-wise from the accumulators (column = lane, 16 rows per block)
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = col_base + 32 * j + (l & 31);
+    if (c >= J) continue;
+    const float bv = ep.bias ? bf2f(ep.bias[c]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = row0 + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        if (row >= I) continue;
+        float v = acc[i][j][r] + bv;
+        if (ep.relu) v = fmaxf(v, 0.f);
+        const size_t off = (size_t)row * ep.ldo + c;
+        if (ep.out_f) {
+          ep.out_f[off] = v;
+        } else {
+          uint16_t o = f2bf(v);
+          if (ep.mask && !bf_positive(ep.mask[off])) o = 0;
+          ep.out[off] = o;
+        }
+      }
+  }
+}
+
 // NW = waves per workgroup: 4 (2 x 2 waves of 128 x 128) or 8 (2 x 4 waves of 128 x 64, two waves per SIMD so
 // that one can issue MFMAs while the other waits for LDS).
 template <bool TA, bool TB, int NW>
@@ -136,104 +238,182 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_big_kernel(const bf16_t* __re
     __syncthreads();
   }
 
-  // epilogue.  Each wave stages 32-row blocks of its sub-tile in a private LDS region (after the loop's last
-  // barrier the operand tiles are dead) and writes them out as full rows, 16 bytes per lane.
-  const bool wide_ok = ((ep.ldo & 7) == 0) && ((J & 7) == 0);
-  if (wide_ok) {
-    char* stage = reinterpret_cast<char*>(smem) + (size_t)w * kStageBytes;
-    const int col_base = j0 + WCOLS * wn;
-    constexpr int FLD = WCOLS + 4, HLD = WCOLS + 8;  // padded staging rows (fp32 / bf16)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row_base = i0 + 128 * wm + 32 * i;
-      if (ep.out_f) {
-        float* sf = reinterpret_cast<float*>(stage);  // [32][FLD]
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-          const int c = col_base + 32 * j + (l & 31);
-          const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float v = acc[i][j][r] + bv;
-            if (ep.relu) v = fmaxf(v, 0.f);
-            sf[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * FLD + 32 * j + (l & 31)] = v;
-          }
-        }
-        constexpr int LPR = WCOLS / 4;       // lanes per row (float4 each)
-        constexpr int RPP = 64 / LPR;        // rows per pass
-#pragma unroll
-        for (int q = 0; q < 32 / RPP; ++q) {
-          const int rr = RPP * q + l / LPR, cc = (l % LPR) * 4;
-          const int row = row_base + rr, c = col_base + cc;
-          if (row < I && c < J) {
-            const float4 v = *reinterpret_cast<const float4*>(&sf[rr * FLD + cc]);
-            *reinterpret_cast<float4*>(ep.out_f + (size_t)row * ep.ldo + c) = v;
-          }
-        }
-      } else {
-        bf16_t* sb = reinterpret_cast<bf16_t*>(stage);  // [32][HLD]
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-          const int c = col_base + 32 * j + (l & 31);
-          const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            float v = acc[i][j][r] + bv;
-            if (ep.relu) v = fmaxf(v, 0.f);
-            sb[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * HLD + 32 * j + (l & 31)] = f2bf(v);
-          }
-        }
-        constexpr int LPR = WCOLS / 8;       // lanes per row (8 bf16 each)
-        constexpr int RPP = 64 / LPR;
-#pragma unroll
-        for (int q = 0; q < 32 / RPP; ++q) {
-          const int rr = RPP * q + l / LPR, cc = (l % LPR) * 8;
-          const int row = row_base + rr, c = col_base + cc;
-          if (row < I && c < J) {
-            uint4 v = *reinterpret_cast<const uint4*>(&sb[rr * HLD + cc]);
-            const size_t off = (size_t)row * ep.ldo + c;
-            if (ep.mask) {
-              const uint4 mk = ldg16(ep.mask + off);
-              const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
-              uint32_t vw[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                if (!bf_positive((uint16_t)(mw[e] & 0xffffu))) vw[e] &= 0xffff0000u;
-                if (!bf_positive((uint16_t)(mw[e] >> 16))) vw[e] &= 0x0000ffffu;
-              }
-              v = make_uint4(vw[0], vw[1], vw[2], vw[3]);
-            }
-            *reinterpret_cast<uint4*>(ep.out + off) = v;
-          }
-        }
-      }
-    }
-    return;
+  big_epilogue<NJ, WCOLS>(acc, ep, reinterpret_cast<char*>(smem) + (size_t)w * kStageBytes, i0 + 128 * wm,
+                          j0 + WCOLS * wn, l, I, J);
+}
+
+// ---- both operands reduction-contiguous: global -> LDS without passing through registers --------------------
+// Same 256 x 256 tile and 2 x 4 waves of 128 x 64, but 32 reduction elements per stage and four stages in LDS.
+// Each lane's 16-byte chunk goes straight from global memory into LDS (global_load_lds_dwordx4); the hardware
+// places lane L's chunk at M0 + 16 L, so a wave-wide load fills 16 consecutive 64-byte tile rows and the XOR
+// swizzle of a row's four 16-byte slots is applied on the global side (lane L fetches the k-group that belongs in
+// its slot).  The loads of stage st+3 are spread between the MFMAs of stage st; the barrier at the end of stage
+// st publishes stage st+2, and the first fragments of stage st+1 are already in registers when it is reached.
+// The loads are written as inline assembly: for the builtin the compiler inserts a wait for ALL outstanding loads
+// before every LDS read, which serialises the pipeline.  A reduction length that is not a multiple of 32 is
+// handled by one zero-padded stage that goes through registers before the pipeline starts.
+constexpr int DK = 32, DNS = 4, DROWB = DK * 2, DTILE = 256 * DROWB, DSTAGE = 2 * DTILE;
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+__device__ __forceinline__ int dma_swz(int row) { return (row >> 2) & 3; }
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma_load16(const bf16_t* uniform_base, uint32_t lane_byte_offset, char* uniform_lds_dst) {
+  const uint32_t lds_addr =
+      __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(uniform_lds_dst));
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_byte_offset), "s"(uniform_base), "s"(lds_addr)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+__global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restrict__ A, int lda,
+                                                          const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep,
+                                                          int I, int J, int R, int tiles_i, int tiles_j) {
+  constexpr int NW = 8, NI = 4, NJ = 2, KS = DK / 16, D = DNS - 1;
+  constexpr int QN = 256 / 16 / NW;        // wave-wide loads per operand and stage (2)
+  constexpr int LPS = 2 * QN, LPK = LPS / KS, MF = NI * NJ;
+  __shared__ __attribute__((aligned(1024))) char smem[DNS * DSTAGE];
+  const int t = threadIdx.x, l = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): renumber so that an XCD works on a
+  // contiguous run of tiles, and walk the tiles in bands of four tile rows so that the tiles in flight on one XCD
+  // share a few A and B panels.
+  int bid = blockIdx.x;
+  {
+    const int per = gridDim.x >> 3;
+    if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
   }
-  // odd widths: element-wise from the accumulators (column = lane, 16 rows per block)
+  int ti, tj;
+  {
+    constexpr int BAND = 4;
+    const int per_band = BAND * tiles_j, band = bid / per_band, rem = bid - band * per_band;
+    const int rows_in = tiles_i - band * BAND < BAND ? tiles_i - band * BAND : BAND;
+    ti = band * BAND + rem % rows_in;
+    tj = rem / rows_in;
+  }
+  const int i0 = ti * GM, j0 = tj * GN;
+  const int T = R / DK, tail = R - T * DK;  // T >= 1 (checked by the launcher)
+
+  // byte offsets of this lane's chunk for each of the stage's loads (A loads first); rows beyond the matrix are
+  // clamped to its last row: they only feed outputs that are never stored
+  uint32_t off[LPS];
+#pragma unroll
+  for (int q = 0; q < QN; ++q) {
+    const int row = (q * NW + w) * 16 + (l >> 2), g = (l & 3) ^ dma_swz(row);
+    const int ra = i0 + row < I ? i0 + row : I - 1, rb = j0 + row < J ? j0 + row : J - 1;
+    off[q] = ((uint32_t)ra * (uint32_t)lda + g * 8) * 2u;
+    off[QN + q] = ((uint32_t)rb * (uint32_t)ldb + g * 8) * 2u;
+  }
+  auto load1 = [&](int q, char* stage, int k0) {  // q-th load of the stage that starts at reduction index k0
+    dma_load16((q < QN ? A : Bm) + k0, off[q], stage + (q < QN ? 0 : DTILE) + ((q % QN) * NW + w) * 1024);
+  };
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x16{0};
+  // byte offsets of this lane's fragments inside a stage for k-step 0; k-step 1 flips bit 5 (two slots further)
+  int fa[NI], fb[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int row = 128 * wm + 32 * i + (l & 31);
+    fa[i] = row * DROWB + (((l >> 5) ^ dma_swz(row)) << 4);
+  }
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
-    const int c = j0 + WCOLS * wn + 32 * j + (l & 31);
-    if (c >= J) continue;
-    const float bv = ep.bias ? bf2f(ep.bias[c]) : 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = i0 + 128 * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-        if (row >= I) continue;
-        float v = acc[i][j][r] + bv;
-        if (ep.relu) v = fmaxf(v, 0.f);
-        const size_t off = (size_t)row * ep.ldo + c;
-        if (ep.out_f) {
-          ep.out_f[off] = v;
-        } else {
-          uint16_t o = f2bf(v);
-          if (ep.mask && !bf_positive(ep.mask[off])) o = 0;
-          ep.out[off] = o;
-        }
-      }
+    const int row = 64 * wn + 32 * j + (l & 31);
+    fb[j] = DTILE + row * DROWB + (((l >> 5) ^ dma_swz(row)) << 4);
   }
+  auto ldf = [&](const char* stage, int o, int ks) { return *reinterpret_cast<const uint4*>(stage + (o ^ (ks << 5))); };
+
+#pragma unroll
+  for (int d = 0; d < D; ++d) {
+    const int sc = d < T ? d : T - 1;
+#pragma unroll
+    for (int q = 0; q < LPS; ++q) load1(q, smem + d * DSTAGE, sc * DK);
+  }
+  if (tail) {  // ragged end of the reduction: through registers with zero fill, into the stage the pipeline fills last
+    char* st = smem + D * DSTAGE;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = t + 512 * i, row = c >> 2, g = c & 3, k = T * DK + g * 8;
+      const int ra = i0 + row < I ? i0 + row : I - 1, rb = j0 + row < J ? j0 + row : J - 1;
+      const uint4 va = k < R ? ldg16(A + (size_t)ra * lda + k) : zero16();
+      const uint4 vb = k < R ? ldg16(Bm + (size_t)rb * ldb + k) : zero16();
+      const int o = row * DROWB + ((g ^ dma_swz(row)) << 4);
+      *reinterpret_cast<uint4*>(st + o) = va;
+      *reinterpret_cast<uint4*>(st + DTILE + o) = vb;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 a[NI], b[NJ];
+#pragma unroll
+      for (int i = 0; i < NI; ++i) a[i] = ldf(st, fa[i], ks);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) b[j] = ldf(st, fb[j], ks);
+#pragma unroll
+      for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[j]), acc[i][j], 0, 0, 0);
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");  // stages 0 and 1 have landed
+  __syncthreads();  // (also: every wave is done with the ragged stage before the loop's first loads overwrite it)
+  uint4 a[2][NI], b[2][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) a[0][i] = ldf(smem, fa[i], 0);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) b[0][j] = ldf(smem, fb[j], 0);
+  int cur = 0, fill = D;  // LDS stage of reduction stage st; LDS stage this iteration's loads go to
+  for (int st = 0; st < T; ++st) {
+    const char* sc = smem + cur * DSTAGE;
+    cur = cur + 1 == DNS ? 0 : cur + 1;
+    const char* sn = smem + cur * DSTAGE;
+    char* sl = smem + fill * DSTAGE;
+    fill = fill + 1 == DNS ? 0 : fill + 1;
+    const int k0 = (st + D < T ? st + D : T - 1) * DK;  // past the end: reload the last stage (never read)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) a[n][i] = ldf(sc, fa[i], ks + 1);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[n][j] = ldf(sc, fb[j], ks + 1);
+      } else {  // next stage's first fragments (published by the previous barrier)
+#pragma unroll
+        for (int i = 0; i < NI; ++i) a[n][i] = ldf(sn, fa[i], 0);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[n][j] = ldf(sn, fb[j], 0);
+      }
+#pragma unroll
+      for (int m = 0; m < MF; ++m) {
+        const int i = m / NJ, j = m % NJ;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
+#pragma unroll
+        for (int x = 0; x < LPK; ++x)
+          if (m == x * MF / LPK + 1) {
+            __builtin_amdgcn_sched_barrier(0);
+            load1(ks * LPK + x, sl, k0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      }
+    }
+    // this wave's loads of stage st+2 have landed (those of stage st+3 may still be in flight); after the barrier
+    // every wave's have, and every wave is done reading stage st
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  big_epilogue<NJ, 64>(acc, ep, smem + (size_t)w * (DNS * DSTAGE / NW), i0 + 128 * wm, j0 + 64 * wn, l, I, J);
 }
 
 // column sums in two deterministic steps: partial sums over chunks of 128 rows, then the chunks in order
@@ -271,6 +451,12 @@ template <bool TA, bool TB>
 hipError_t launch_big(hipStream_t s, const bf16_t* a, int lda, const bf16_t* b, int ldb, const BigEpilogue& ep, int I,
                       int J, int R) {
   dim3 grid((J + GN - 1) / GN, (I + GM - 1) / GM);
+  if (!TA && !TB && R >= DK && (R % 8) == 0 && (lda % 8) == 0 && (ldb % 8) == 0 &&
+      ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0 &&
+      (size_t)I * lda < ((size_t)1 << 31) && (size_t)J * ldb < ((size_t)1 << 31)) {  // 32-bit byte offsets
+    gemm_dma_kernel<<<grid.x * grid.y, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R, (int)grid.y, (int)grid.x);
+    return hipGetLastError();
+  }
   if (g_big_waves == 8) gemm_big_kernel<TA, TB, 8><<<grid, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R);
   else gemm_big_kernel<TA, TB, 4><<<grid, 256, 0, s>>>(a, lda, b, ldb, ep, I, J, R);
   return hipGetLastError();

@@ -19,6 +19,9 @@ hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, cons
 // dx[M][K] = (dz[M][N] * w[N][K]) .* (mask[M][K] > 0)   (mask may be null); dx bf16.
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes);
+// Output tiles (256 x 256) from which forward/dgrad go to the compute-bound kernels below (default 128: half the
+// chip's compute units); returns the previous value, values < 1 only query.
+int set_big_tile_threshold(int min_tiles);
 // Compute-bound versions for many rows (gemm_big_bf16.hip; 256 x 256 tiles, no split-K, no workspace):
 //   fwd: y = act(x w^T + b) (x row stride ldx; bf16 y or fp32 y_f32);  dgrad: dx = (dz w) .* mask;
 //   wgrad: dw[N][K] = dz^T x as fp32, db[N] = column sums of dz (db may be null).

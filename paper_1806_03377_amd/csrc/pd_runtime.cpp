@@ -1025,6 +1025,8 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
   return PD_OK;
 }
 
+int pd_set_big_tile_threshold(int32_t min_tiles) { return pd::set_big_tile_threshold(min_tiles); }
+
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) { return pd::gemm_bf16_workspace_bytes(M, N, K); }
 
 static int check_gemm(const void* a, const void* b, const void* c, int M, int N, int K) {

@@ -32,7 +32,27 @@ def _bf(a):
 # ---------------------------------------------------------------------------------------------
 SHAPES = [(64, 128, 64), (64, 256, 4096), (64, 200, 264), (40, 136, 72), (1, 8, 8), (130, 1000, 520),
           (64, 4096, 1024), (96, 24, 2048), (256, 512, 768),
-          (512, 256, 256), (600, 1000, 520), (1030, 264, 136)]     # >= 512 rows: the 256 x 256-tile kernel
+          (512, 256, 256), (600, 1000, 520), (1030, 264, 136)]     # >= 512 rows: the 256 x 256-tile weight gradient
+# the same products forced onto the large-tile kernels (threshold 1 tile): several tiles, ragged rows/columns, a
+# reduction length that is a multiple of 32, one that is not, one shorter than a stage
+BIG_SHAPES = [(512, 256, 256), (600, 1000, 520), (1030, 264, 136), (300, 520, 1000), (257, 8, 24), (700, 776, 4128), (2080, 264, 136)]
+
+
+@pytest.fixture
+def big_tiles():
+    old = pd.pd_set_big_tile_threshold(1)
+    yield
+    pd.pd_set_big_tile_threshold(old)
+
+
+@pytest.mark.parametrize("M,N,K", BIG_SHAPES)
+def test_linear_fwd_bf16_big_tiles(M, N, K, big_tiles):
+    test_linear_fwd_bf16(M, N, K)
+
+
+@pytest.mark.parametrize("M,N,K", BIG_SHAPES)
+def test_linear_dgrad_bf16_big_tiles(M, N, K, big_tiles):
+    test_linear_dgrad_bf16(M, N, K)
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
