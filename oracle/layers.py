@@ -10,7 +10,11 @@ the standard definition written out:
   Conv2d          cross-correlation, NHWC activations, W[c_out][kh][kw][c_in], zero padding,
                   y[n,i,j,o] = b[o] + sum_{a,b,c} x[n, i*s + a - ph, j*s + b - pw, c] W[o,a,b,c]
   MaxPool2d       window k, stride s, no padding; the gradient goes to the FIRST maximum of the
-                  window in row-major order (ties do occur among bf16 values)
+                  window in row-major order (ties do occur among bf16 values); where windows overlap
+                  an input position sums what it receives
+  AvgPool2d       window k, stride s, zero padding p counted in the divisor: y = (sum over the window)/k^2
+  Concat block    parallel branches over one input, outputs joined along the channel axis (branch 0
+                  first); dL/dx = sum over branches of each branch's input gradient
   LSTM            time-major sequences x[T][B][I] -> h[T][B][H]; gates (i, f, g, o) =
                   x_t W_ih^T + h_{t-1} W_hh^T + b with W_ih[4H][I], W_hh[4H][H]; i, f, o = sigmoid,
                   g = tanh; c_t = f c_{t-1} + i g; h_t = o tanh(c_t); h_{-1} = c_{-1} = 0; backward is
@@ -180,6 +184,31 @@ def maxpool2d_backward(x, y, dy, k, stride):
             dx[:, a:a + (ho - 1) * stride + 1:stride, b:b + (wo - 1) * stride + 1:stride, :] += np.where(hit, dy, 0.0)
             taken |= hit
     return dx
+
+
+# ---- AvgPool2d, NHWC ----------------------------------------------------------
+
+def avgpool2d_forward(x, k, stride, pad, q):
+    """Mean over k x k windows; padded positions are zeros and count in the divisor."""
+    N, H, Wd, C = x.shape
+    ho, wo = _conv_out(H, k, stride, pad), _conv_out(Wd, k, stride, pad)
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
+    y = np.zeros((N, ho, wo, C))
+    for a in range(k):
+        for b in range(k):
+            y += _tap_view(xp, a, b, ho, wo, stride)
+    return q(y / (k * k))
+
+
+def avgpool2d_backward(x_shape, dy, k, stride, pad, q):
+    """Transpose of the averaging operator: every window spreads dy / k^2 over its positions."""
+    N, H, Wd, C = x_shape
+    ho, wo = dy.shape[1], dy.shape[2]
+    dxp = np.zeros((N, H + 2 * pad, Wd + 2 * pad, C))
+    for a in range(k):
+        for b in range(k):
+            _tap_view(dxp, a, b, ho, wo, stride)[...] += dy / (k * k)
+    return q(dxp[:, pad:pad + H, pad:pad + Wd, :])
 
 
 # ---- LSTM, time-major -----------------------------------------------------------

@@ -46,13 +46,34 @@ def _split_params(layers, flat):
             W_hh = flat[o:o + 4 * H * H].reshape(4 * H, H); o += 4 * H * H
             b = flat[o:o + 4 * H]; o += 4 * H
             out.append((W_ih, W_hh, b))
+        elif ly[0] == "concat":                      # branches in order, each a layer list of its own
+            views = []
+            for br in ly[1]:
+                n = _count(br)
+                views.append(_split_params(br, flat[o:o + n])); o += n
+            out.append(views)
         else:
             out.append(None)
     assert o == flat.size, "parameter vector does not match the layer list"
     return out
 
 
+def _count(layers):
+    n = 0
+    for ly in layers:
+        if ly[0] == "linear":
+            n += ly[1] * ly[2] + ly[2]
+        elif ly[0] == "conv2d":
+            n += ly[2] * ly[3] * ly[4] * ly[1] + ly[2]
+        elif ly[0] == "lstm":
+            n += 4 * ly[2] * (ly[1] + ly[2]) + 4 * ly[2]
+        elif ly[0] == "concat":
+            n += sum(_count(br) for br in ly[1])
+    return n
+
+
 _LSTM_CACHE = {}   # id(stored h sequence) -> gate/cell values of its forward pass, until its backward
+_BLOCK_CACHE = {}  # id(stored block output) -> per branch, the stored activations [input, layer outputs...]
 
 
 def _layer_forward(layers, li, p, a, q):
@@ -73,6 +94,18 @@ def _layer_forward(layers, li, p, a, q):
         return L.conv2d_forward(a, p[0], p[1], ly[5], ly[6], ly[7], ly[8], q)
     if ly[0] == "maxpool2d":
         return L.maxpool2d_forward(a, ly[1], ly[2])
+    if ly[0] == "avgpool2d":
+        return L.avgpool2d_forward(a, ly[1], ly[2], ly[3], q)
+    if ly[0] == "concat":
+        per_branch = []
+        for br, bp in zip(ly[1], p):
+            acts = [a]
+            for si in range(len(br)):
+                acts.append(_layer_forward(br, si, bp[si], acts[-1], q))
+            per_branch.append(acts)
+        y = np.concatenate([acts[-1] for acts in per_branch], axis=-1)
+        _BLOCK_CACHE[id(y)] = per_branch
+        return y
     raise NotImplementedError(ly[0])
 
 
@@ -92,11 +125,36 @@ def _layer_backward(layers, li, p, x, y, d, need_dx, q):
     if ly[0] == "conv2d":
         return L.conv2d_backward(x, p[0], y, d, ly[5], ly[6], ly[7], ly[8], need_dx, q)
     if ly[0] == "maxpool2d":
-        return (L.maxpool2d_backward(x, y, d, ly[1], ly[2]) if need_dx else None), None, None
+        return (q(L.maxpool2d_backward(x, y, d, ly[1], ly[2])) if need_dx else None), None, None
+    if ly[0] == "avgpool2d":
+        return (L.avgpool2d_backward(x.shape, d, ly[1], ly[2], ly[3], q) if need_dx else None), None, None
+    if ly[0] == "concat":
+        per_branch = _BLOCK_CACHE.pop(id(y))
+        d = d.reshape(y.shape)
+        grads, dx_sum, c0 = [], None, 0
+        for br, bp, acts in zip(ly[1], p, per_branch):
+            c1 = c0 + acts[-1].shape[-1]
+            db_ = d[..., c0:c1]                          # this branch's channel slice of dL/d(output)
+            c0 = c1
+            g = [None] * len(br)
+            for si in range(len(br) - 1, -1, -1):
+                dx_b, dW, db = _layer_backward(br, si, bp[si], acts[si], acts[si + 1], db_, need_dx or si > 0, q)
+                g[si] = None if dW is None else (dW, db)
+                db_ = dx_b
+            grads.append(g)
+            if need_dx:                                  # each branch's input gradient is a stored tensor
+                dx_sum = db_ if dx_sum is None else dx_sum + db_
+        return (q(dx_sum) if need_dx else None), grads, None
     raise NotImplementedError(ly[0])
 
 
 def _store_grad(views, dW, db):
+    if isinstance(dW, list):           # concat block: per branch, per layer (dW, db) or None
+        for bviews, bgrads in zip(views, dW):
+            for v, g in zip(bviews, bgrads):
+                if g is not None:
+                    _store_grad(v, g[0], g[1])
+        return
     if isinstance(dW, tuple):          # LSTM: (dW_ih, dW_hh), bias last
         views[0][...] = dW[0]
         views[1][...] = dW[1]
@@ -149,7 +207,18 @@ class Stage:
                 acts.append(_layer_forward(self.layers, li, p, acts[-1], self.q))
         self.stash[mb] = dict(version=v, acts=acts, labels=labels, probs=probs)
         if self.log is not None:
-            self.log[mb] = dict(version=v, acts=acts, loss=loss)
+            # "flat": the stored output of every compute layer in description order, a block contributing its
+            # branch layers (branch 0 first) and then its concatenated output
+            flat, k = [], 1
+            for ly in self.layers:
+                if ly[0] == "softmax_xent":
+                    continue
+                if ly[0] == "concat":
+                    for bacts in _BLOCK_CACHE[id(acts[k])]:
+                        flat.extend(bacts[1:])
+                flat.append(acts[k])
+                k += 1
+            self.log[mb] = dict(version=v, acts=acts, loss=loss, flat=flat)
         self.max_in_flight = max(self.max_in_flight, len(self.stash))
         self.trace.append(Op(OP_F, mb, v, v % self.depth))
         return acts[-1], loss

@@ -89,6 +89,9 @@ def labels(seed: int, name: str, shape, num_classes: int) -> np.ndarray:
 #   ("conv2d", c_in, c_out, kh, kw, stride, pad_h, pad_w, relu: bool)   (NHWC)
 #   ("maxpool2d", k, stride)
 #   ("lstm", input_size, hidden, seq_len)
+#   ("avgpool2d", k, stride, pad)
+#   ("concat", [branch, branch, ...])   each branch a list of conv2d / maxpool2d / avgpool2d tuples over the
+#                                       same input; outputs joined along the channel axis, branch 0 first
 # ----------------------------------------------------------------------------
 
 def param_count(layers) -> int:
@@ -100,6 +103,8 @@ def param_count(layers) -> int:
             n += L[2] * L[3] * L[4] * L[1] + L[2]
         elif L[0] == "lstm":
             n += 4 * L[2] * (L[1] + L[2]) + 4 * L[2]
+        elif L[0] == "concat":
+            n += sum(param_count(br) for br in L[1])
     return n
 
 
@@ -127,6 +132,9 @@ def init_params(seed: int, name: str, layers) -> np.ndarray:
             parts.append(uniform(seed, tag + "/Wih", (4 * L[2] * L[1],), -bound, bound))
             parts.append(uniform(seed, tag + "/Whh", (4 * L[2] * L[2],), -bound, bound))
             parts.append(np.zeros(4 * L[2], dtype=np.float32))
+        elif L[0] == "concat":
+            for b, br in enumerate(L[1]):
+                parts.append(init_params(seed, f"{tag}/B{b}", br))
     if not parts:
         return np.zeros(0, dtype=np.float32)
     return np.concatenate(parts).astype(np.float32)
