@@ -174,6 +174,63 @@ def bench_s2vt(args, pd, gen, torch, np, dev):
     print(json.dumps(out))
 
 
+def bench_inception(args, pd, gen, torch, np, dev):
+    """Secondary workload: the Inception-shaped network (299 x 299 images, blocks of parallel 1x1 / 3x3 / 5x5 /
+    1x7 / 7x1 / pooling branches joined by channel concatenation) split into four stages on four streams
+    (pd_pipeline_run, NOAM 4).  A step = one minibatch through all four stages (F, B, U on each)."""
+    B, K, W = args.minibatch, args.steps, args.warmup
+    width, classes = (0.25, 16) if args.small else (1.0, 1000)
+    sl, sizes = gen.config5_inception(classes, width)
+    S = len(sl)
+    seed = gen.BASE_SEED + 4
+    streams = [torch.cuda.Stream(device=dev) for _ in range(S)]
+    hs, arenas = [], []
+    fwd = []
+    for s in range(S):
+        cfg = pd.make_config(sl[s], stage_index=s, num_stages=S, noam=S, minibatch=B, precision=pd.PD_BF16_F32ACC,
+                             lr=1e-3, momentum=0.9, stream=streams[s].cuda_stream, in_hw=sizes[s])
+        nbytes = pd.pd_stage_query_bytes(cfg)
+        arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
+        pd.pd_stage_set_params(h, gen.init_params(seed, f"s{s}", sl[s]))
+        hs.append(h); arenas.append(arena)
+        fwd.append(gen.forward_flops(sl[s], sizes[s], B)[0])
+    M = W + K
+    n_pool = 2
+    x1 = torch.from_numpy(gen.normal(seed, "x", (n_pool, B, 299, 299, 3))).to(dev).to(torch.bfloat16)
+    l1 = torch.from_numpy(gen.labels(seed, "y", (n_pool, B), classes)).to(dev)
+    xs = x1.repeat((M + n_pool - 1) // n_pool, 1, 1, 1, 1)[:M].contiguous()
+    ls = l1.repeat((M + n_pool - 1) // n_pool, 1)[:M].contiguous()
+    losses = torch.zeros(M, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    if W:
+        pd.pd_pipeline_run(hs, W, xs.data_ptr(), ls.data_ptr(), losses.data_ptr())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pd.pd_pipeline_run(hs, K, xs[W:].data_ptr(), ls[W:].data_ptr(), losses[W:].data_ptr())
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / K
+    # forward + weight gradient + input gradient; the first convolution needs no input gradient
+    first = 2.0 * B * 149 * 149 * sl[0][0][2] * 27
+    f = 3.0 * sum(fwd) - first
+    out = {"metric": METRIC, "value": B / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": ("REDUCED " if args.small else "") + f"Inception-shaped 4-stage pipeline on 3x299x299 images (width x{width}, "
+                      f"{classes} classes), bf16 w/ fp32 accum, minibatch {B}, NOAM 4, four streams; step = one minibatch "
+                      "through all stages (drained pipeline of `steps` minibatches)", "minibatch": B,
+                      "stage_forward_gflop": [round(v / 1e9, 1) for v in fwd],
+                      "stage_params": [gen.param_count(l) for l in sl]},
+           "step_gflop": f / 1e9, "mfma_util_pct": 100.0 * f / (ms * 1e-3) / MFMA_BF16_PEAK,
+           "roofline": {"bound": "mfma", "kernel": "whole step", "achieved": f / (ms * 1e-3) / 1e12,
+                        "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s", "frac": f / (ms * 1e-3) / MFMA_BF16_PEAK,
+                        "traffic": None},
+           "final_loss": float(losses[-1].item())}
+    for h in hs:
+        pd.pd_stage_destroy(h)
+    print(json.dumps(out))
+
+
 def bench_gemm_sweep(args, pd, gen, torch, np, dev):
     """The stage's three contractions on their own at the VGG16 classifier's K, N with the row count M swept from
     the configured minibatch (64, HBM-bound) into the compute-bound regime: achieved TFLOP/s and % of the bf16
@@ -240,9 +297,10 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "gemm_sweep"],
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
-                         "s2vt (the two LSTM stages as a 2-stream pipeline)")
+                         "s2vt (the two LSTM stages as a 2-stream pipeline), inception (four stages of branched "
+                         "convolution blocks as a 4-stream pipeline), gemm_sweep (the Linear kernels over row counts)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs all pipeline stages on ONE GPU; --gpus must be 1", file=sys.stderr)
@@ -263,6 +321,8 @@ def main():
         return bench_conv(args, pd, gen, torch, np, dev)
     if args.workload == "s2vt":
         return bench_s2vt(args, pd, gen, torch, np, dev)
+    if args.workload == "inception":
+        return bench_inception(args, pd, gen, torch, np, dev)
     if args.workload == "gemm_sweep":
         return bench_gemm_sweep(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()

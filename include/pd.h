@@ -82,12 +82,12 @@ typedef enum {
                           p[0]=c_in p[1]=c_out p[2]=kh p[3]=kw p[4]=stride p[5]=pad_h p[6]=pad_w
                           p[7]=1: fused ReLU  p[8]=in_h p[9]=in_w.  PD_BF16_F32ACC only; c_out and c_in
                           divisible by 8, except that a layer with kh*kw*c_in <= 32 and c_out <= 64 (the
-                          first layer of an image network) may have any c_in.  dL/d(input) is built for
-                          stride 1.                                                                */
-  PD_MAXPOOL2D = 3,    /* p[0]=window p[1]=stride p[2]=channels p[3]=in_h p[4]=in_w; only window 2,
-                          stride 2 (even in_h, in_w; channels divisible by 8).  The gradient goes to the
-                          first maximum of a window in row-major order.                            */
-  PD_LSTM = 4          /* p[0]=input_size p[1]=hidden p[2]=seq_len.  Sequences are TIME-MAJOR:
+                          first layer of an image network) may have any c_in.                      */
+  PD_MAXPOOL2D = 3,    /* p[0]=window p[1]=stride p[2]=channels p[3]=in_h p[4]=in_w; no padding, channels
+                          divisible by 8, output size (in - window)/stride + 1.  The gradient of a window goes
+                          to its first maximum in row-major order; where windows overlap, an input position
+                          sums what it receives.  (Window 2, stride 2 on even sizes has a faster kernel.)     */
+  PD_LSTM = 4,         /* p[0]=input_size p[1]=hidden p[2]=seq_len.  Sequences are TIME-MAJOR:
                           x[seq_len][minibatch][input_size] -> h[seq_len][minibatch][hidden]; gates in the
                           order i, f, g, o = x_t W_ih^T + h_{t-1} W_hh^T + b, c_t = f c_{t-1} + i g,
                           h_t = o tanh(c_t), zero initial state; backward = full back-propagation through
@@ -95,6 +95,20 @@ typedef enum {
                           or follow another LSTM; layers after it see seq_len*minibatch rows (a Linear
                           acts on every time step; the loss is the mean over all of them, labels
                           [seq_len][minibatch]).  PD_BF16_F32ACC only; sizes divisible by 8.          */
+  PD_AVGPOOL2D = 5,    /* p[0]=window p[1]=stride p[2]=pad p[3]=channels p[4]=in_h p[5]=in_w: mean over the
+                          window, zero padding counted in the divisor (window*window); pad < window.  A window
+                          equal to the input size with stride 1 and pad 0 is global average pooling.          */
+  /* A block of parallel branches joined by channel concatenation (Inception-style):
+   *   PD_CONCAT_BEGIN, then per branch PD_BRANCH followed by its layers (PD_CONV2D / PD_MAXPOOL2D /
+   *   PD_AVGPOOL2D only, at least one), then PD_CONCAT_END.
+   * Every branch reads the block's input (the output of the layer before PD_CONCAT_BEGIN, or the stage input);
+   * all branches must end with the same height and width; the block's output is [rows][h][w][sum of branch
+   * channels], branch 0 first.  Backward: each branch receives its channel slice of dL/d(output); dL/d(input) is
+   * the sum of the branches' input gradients (each stored as bf16, added in fp32 in branch order, rounded once).
+   * Blocks do not nest; at most 8 branches.  The three markers take no parameters.  PD_BF16_F32ACC only.      */
+  PD_CONCAT_BEGIN = 6,
+  PD_BRANCH = 7,
+  PD_CONCAT_END = 8
 } pd_layer_kind;
 
 typedef struct {
@@ -183,13 +197,20 @@ int pd_stage_grad_slot(pd_stage* st, int32_t mb_id, void** dev_ptr);
 
 /* Test/debug aid: copies one of the stage's intermediate tensors to the host as fp32
  * (synchronises the stream).  what = 0: stored output of compute layer number `layer` (0-based, the
- * loss not counted) for in-flight minibatch mb_id, [minibatch][out]; 1: the stage's input
+ * loss not counted; inside a block of branches the branch layers count in description order and
+ * PD_CONCAT_END counts as one more layer whose output is the concatenation; the markers PD_CONCAT_BEGIN
+ * and PD_BRANCH do not count) for in-flight minibatch mb_id, [minibatch][out]; 1: the stage's input
  * slot for mb_id, [minibatch][in]; 2: the output-gradient slot for mb_id, [minibatch][out_last];
  * 3: dL/d(pre-activation) of layer `layer` left by the last pd_backward, [minibatch][out] (Linear layers
  * only: convolution and pooling layers do not keep theirs);
  * 4: the stashed dL/dlogits of in-flight minibatch mb_id (loss stages).  n must equal the tensor's
  * element count.  No state check is made on mb_id beyond >= 0: the caller reads what the slot holds. */
 int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, float* host_out, size_t n);
+/* Test/debug aid, the reverse direction: overwrites a stored tensor of in-flight minibatch mb_id with host values
+ * (fp32, rounded to bfloat16 where the tensor is bfloat16; synchronises the stream).  what = 0: the stored output
+ * of compute layer `layer` (not an LSTM); 1: the stage's input slot.  Lets a test drive the backward pass of a deep
+ * stage on exactly the activations (and therefore the ReLU and max-pooling decisions) of a reference run. */
+int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, const float* host_in, size_t n);
 
 /* --- the step (Sections 3.3, 3.4, 4) -------------------------------------------------------
  * pd_forward: F for minibatch mb_id.  Reads the LATEST weight version and records it in the
@@ -263,14 +284,17 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
  * geom = {N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w} (10 ints, host); output size
  * Ho = (H + 2 pad_h - kh)/stride + 1, Wo likewise.  Shape rules as for PD_CONV2D / PD_MAXPOOL2D.
  *   conv_fwd  : y[N][Ho][Wo][c_out] = act(conv(x, w) + b)                      (b may be NULL)
- *   conv_dgrad: dx[N][H][W][c_in]   = convT(dz, w) .* (mask > 0 if mask)       stride 1 only;
+ *   conv_dgrad: dx[N][H][W][c_in]   = convT(dz, w) .* (mask > 0 if mask)       any stride;
  *               wt_scratch: c_out*kh*kw*c_in bf16 elements of scratch
  *   conv_wgrad_update: g = dL/dw from dz and x (and column sums for the bias), partial sums over
  *               pixel ranges in part_scratch, added in a fixed order; part_scratch must hold
  *               pd_conv_wgrad_splits(geom) units of (c_out*kh*kw*c_in + c_out) floats; then m <- mu*m + g;
  *               master <- master - lr*m; ring_out <- bf16(master)
  *   maxpool2x2_fwd / _bwd: 2x2 stride-2 max pooling of x[N][H][W][C]; backward routes dy to the first
- *               maximum of each window and, if relu_mask != 0, zeroes positions where x <= 0 */
+ *               maximum of each window and, if relu_mask != 0, zeroes positions where x <= 0
+ *   pool2d_fwd / _bwd: pooling with any window, stride and padding (is_max != 0: max, padding never wins, pad
+ *               must be 0 < window; else average with divisor window*window); pgeom = {N, H, W, C, window,
+ *               stride, pad} (7 ints, host); backward as for PD_MAXPOOL2D / PD_AVGPOOL2D */
 int pd_conv_wgrad_splits(const int32_t* geom, int32_t* splits);
 int pd_conv_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, const int32_t* geom,
                      int32_t relu);
@@ -282,6 +306,9 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
 int pd_maxpool2x2_fwd_bf16(void* stream, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C);
 int pd_maxpool2x2_bwd_bf16(void* stream, const void* x, const void* y, const void* dy, void* dx, int32_t N, int32_t H,
                            int32_t W, int32_t C, int32_t relu_mask);
+int pd_pool2d_fwd_bf16(void* stream, int32_t is_max, const void* x, void* y, const int32_t* pgeom);
+int pd_pool2d_bwd_bf16(void* stream, int32_t is_max, const void* x, const void* y, const void* dy, void* dx,
+                       const int32_t* pgeom, int32_t relu_mask);
 
 const char* pd_last_error(void); /* thread-local, static storage, never NULL */
 

@@ -25,6 +25,7 @@ PD_OK, PD_EINVAL, PD_ESTATE, PD_ENOMEM, PD_EHIP = 0, -1, -2, -3, -4
 PD_F32, PD_BF16_F32ACC = 0, 1
 PD_OP_F, PD_OP_B, PD_OP_U = 0, 1, 2
 PD_LINEAR, PD_SOFTMAX_XENT, PD_CONV2D, PD_MAXPOOL2D, PD_LSTM = 0, 1, 2, 3, 4
+PD_AVGPOOL2D, PD_CONCAT_BEGIN, PD_BRANCH, PD_CONCAT_END = 5, 6, 7, 8
 
 
 class PdError(RuntimeError):
@@ -67,6 +68,7 @@ _SIGS = {
     "pd_stage_input_slot": [_vp, _i32, C.POINTER(_vp)],
     "pd_stage_grad_slot": [_vp, _i32, C.POINTER(_vp)],
     "pd_stage_debug_read": [_vp, _i32, _i32, _i32, _vp, _sz],
+    "pd_stage_debug_write": [_vp, _i32, _i32, _i32, _vp, _sz],
     "pd_forward": [_vp, _i32, _vp, _vp, _vp, _vp],
     "pd_backward": [_vp, _i32, _vp, _vp],
     "pd_update": [_vp],
@@ -80,6 +82,8 @@ _SIGS = {
     "pd_conv_wgrad_update_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(_i32), _f32, _f32],
     "pd_maxpool2x2_fwd_bf16": [_vp, _vp, _vp, _i32, _i32, _i32, _i32],
     "pd_maxpool2x2_bwd_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32],
+    "pd_pool2d_fwd_bf16": [_vp, _i32, _vp, _vp, C.POINTER(_i32)],
+    "pd_pool2d_bwd_bf16": [_vp, _i32, _vp, _vp, _vp, _vp, C.POINTER(_i32), _i32],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -128,38 +132,62 @@ def layer_descs(layers: Sequence[tuple], in_hw=None):
     """Translate the neutral layer tuples of pd_inputs into pd_layer_desc records.
 
     ``in_hw`` = (height, width) of the stage's input images, needed when the stage has
-    convolution or pooling layers (their descriptors carry the input size)."""
-    arr = (pd_layer_desc * len(layers))()
-    hw = tuple(in_hw) if in_hw else None
-    ch = None
-    for i, L in enumerate(layers):
+    convolution or pooling layers (their descriptors carry the input size); a stage that starts with
+    a pooling layer or a block whose branch starts with one also needs ``in_hw`` = (h, w, channels)."""
+    recs = []
+    state = {"hw": tuple(in_hw[:2]) if in_hw else None, "ch": (in_hw[2] if in_hw and len(in_hw) > 2 else None)}
+
+    def emit(kind, *vals):
+        recs.append((kind, [int(v) for v in vals]))
+
+    def one(L):
+        hw, ch = state["hw"], state["ch"]
         if L[0] == "linear":
-            arr[i].kind = PD_LINEAR
-            arr[i].p[0], arr[i].p[1], arr[i].p[2] = int(L[1]), int(L[2]), int(bool(L[3]))
+            emit(PD_LINEAR, L[1], L[2], int(bool(L[3])))
         elif L[0] == "softmax_xent":
-            arr[i].kind = PD_SOFTMAX_XENT
-            arr[i].p[0] = int(L[1])
+            emit(PD_SOFTMAX_XENT, L[1])
         elif L[0] == "conv2d":
             if hw is None:
                 raise ValueError("in_hw is required for stages with convolutions")
             _, c_in, c_out, kh, kw, stride, ph, pw, relu = L
-            arr[i].kind = PD_CONV2D
-            for j, v in enumerate((c_in, c_out, kh, kw, stride, ph, pw, int(bool(relu)), hw[0], hw[1])):
-                arr[i].p[j] = int(v)
-            hw = ((hw[0] + 2 * ph - kh) // stride + 1, (hw[1] + 2 * pw - kw) // stride + 1)
-            ch = c_out
+            emit(PD_CONV2D, c_in, c_out, kh, kw, stride, ph, pw, int(bool(relu)), hw[0], hw[1])
+            state["hw"] = ((hw[0] + 2 * ph - kh) // stride + 1, (hw[1] + 2 * pw - kw) // stride + 1)
+            state["ch"] = c_out
         elif L[0] == "maxpool2d":
             if hw is None or ch is None:
-                raise ValueError("a pooling layer must follow a convolution in this description")
-            arr[i].kind = PD_MAXPOOL2D
-            for j, v in enumerate((L[1], L[2], ch, hw[0], hw[1])):
-                arr[i].p[j] = int(v)
-            hw = ((hw[0] - L[1]) // L[2] + 1, (hw[1] - L[1]) // L[2] + 1)
+                raise ValueError("a pooling layer needs the input size and channel count (in_hw = (h, w, c))")
+            emit(PD_MAXPOOL2D, L[1], L[2], ch, hw[0], hw[1])
+            state["hw"] = ((hw[0] - L[1]) // L[2] + 1, (hw[1] - L[1]) // L[2] + 1)
+        elif L[0] == "avgpool2d":
+            if hw is None or ch is None:
+                raise ValueError("a pooling layer needs the input size and channel count (in_hw = (h, w, c))")
+            k, stride, pad = L[1], L[2], L[3]
+            emit(PD_AVGPOOL2D, k, stride, pad, ch, hw[0], hw[1])
+            state["hw"] = ((hw[0] + 2 * pad - k) // stride + 1, (hw[1] + 2 * pad - k) // stride + 1)
+        elif L[0] == "concat":
+            emit(PD_CONCAT_BEGIN)
+            start = dict(state)
+            total = 0
+            for br in L[1]:
+                emit(PD_BRANCH)
+                state.update(start)
+                for sub in br:
+                    one(sub)
+                total += state["ch"]
+            emit(PD_CONCAT_END)
+            state["ch"] = total
         elif L[0] == "lstm":
-            arr[i].kind = PD_LSTM
-            arr[i].p[0], arr[i].p[1], arr[i].p[2] = int(L[1]), int(L[2]), int(L[3])
+            emit(PD_LSTM, L[1], L[2], L[3])
         else:
             raise ValueError(f"layer kind {L[0]!r} is not supported by this build")
+
+    for L in layers:
+        one(L)
+    arr = (pd_layer_desc * len(recs))()
+    for i, (kind, vals) in enumerate(recs):
+        arr[i].kind = kind
+        for j, v in enumerate(vals):
+            arr[i].p[j] = v
     return arr
 
 
@@ -167,7 +195,7 @@ def make_config(layers, *, stage_index=0, num_stages=1, noam=1, in_flight_overri
                 precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None):
     descs = layer_descs(layers, in_hw)
     cfg = pd_stage_config(stage_index, num_stages, noam, in_flight_override, minibatch, precision, lr, momentum,
-                          len(layers), descs, stream)
+                          len(descs), descs, stream)
     cfg._keepalive = descs
     return cfg
 
@@ -270,6 +298,11 @@ def pd_stage_debug_read(stage: int, what: int, mb_id: int, layer: int, shape) ->
     return out
 
 
+def pd_stage_debug_write(stage: int, what: int, mb_id: int, layer: int, values: np.ndarray):
+    a = _host_f32(values)
+    _check(_lib.pd_stage_debug_write(stage, what, mb_id, layer, a.ctypes.data, a.size))
+
+
 def pd_forward(stage: int, mb_id: int, x_dev: int, labels_dev: int = 0, y_dev: int = 0, loss_dev: int = 0):
     _check(_lib.pd_forward(stage, mb_id, x_dev, labels_dev or None, y_dev or None, loss_dev or None))
 
@@ -338,3 +371,15 @@ def pd_maxpool2x2_fwd_bf16(stream, x, y, N, H, W, Cn):
 
 def pd_maxpool2x2_bwd_bf16(stream, x, y, dy, dx, N, H, W, Cn, relu_mask):
     _check(_lib.pd_maxpool2x2_bwd_bf16(stream, x, y, dy, dx, N, H, W, Cn, int(relu_mask)))
+
+
+def _pgeom(N, H, W, Cn, k, stride, pad):
+    return (_i32 * 7)(N, H, W, Cn, k, stride, pad)
+
+
+def pd_pool2d_fwd_bf16(stream, is_max, x, y, pgeom):
+    _check(_lib.pd_pool2d_fwd_bf16(stream, int(is_max), x, y, _pgeom(*pgeom)))
+
+
+def pd_pool2d_bwd_bf16(stream, is_max, x, y, dy, dx, pgeom, relu_mask):
+    _check(_lib.pd_pool2d_bwd_bf16(stream, int(is_max), x, y, dy, dx, _pgeom(*pgeom), int(relu_mask)))

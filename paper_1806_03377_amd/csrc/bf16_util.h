@@ -14,4 +14,18 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
 __device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 __device__ __forceinline__ bool bf_positive(uint16_t h) { return (h & 0x8000u) == 0 && (h & 0x7fffu) != 0; }
 
+// eight bf16 values <-> one 16-byte register quad
+__device__ __forceinline__ void unpack8(uint4 v, uint16_t* o) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    o[2 * q] = (uint16_t)(w[q] & 0xffffu);
+    o[2 * q + 1] = (uint16_t)(w[q] >> 16);
+  }
+}
+__device__ __forceinline__ uint4 pack8(const uint16_t* o) {
+  return make_uint4(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16), o[4] | ((uint32_t)o[5] << 16),
+                    o[6] | ((uint32_t)o[7] << 16));
+}
+
 }  // namespace pd

@@ -36,7 +36,7 @@ __device__ __forceinline__ void store_out(const ConvEpilogue& ep, float v, size_
 // ------------------------------------------------------------------------------------------------
 constexpr int CK = 64, CLD = CK + 8, CPD = 2;
 
-template <int WMW, int WNW>
+template <int WMW, int WNW, bool UP>
 __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __restrict__ X,
                                                               const bf16_t* __restrict__ Wg, ConvGeom g,
                                                               ConvEpilogue ep) {
@@ -57,6 +57,8 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __re
   const int col = t & 7, trow = t >> 3;
   const bool aligned_ci = (g.Ci % CK) == 0;  // then a stage lies inside one tap
   const int per_tap = aligned_ci ? g.Ci / CK : 1;
+  // UP: the input is the zero-upsampled tensor; Hl x Wl is its logical size
+  const int Hl = UP ? (g.H - 1) * g.up + 1 : g.H, Wl = UP ? (g.W - 1) * g.up + 1 : g.W;
 
   // the pixel rows this thread loads in every stage
   int hi0[ACH], wi0[ACH], nbase[ACH];
@@ -96,8 +98,14 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __re
     const int ta = tap / g.kw, tb = tap - ta * g.kw;
 #pragma unroll
     for (int i = 0; i < ACH; ++i) {
-      const int hi = hi0[i] + ta, wi = wi0[i] + tb;
-      const bool ok = live && nbase[i] >= 0 && (unsigned)hi < (unsigned)g.H && (unsigned)wi < (unsigned)g.W;
+      int hi = hi0[i] + ta, wi = wi0[i] + tb;
+      bool ok = live && nbase[i] >= 0 && (unsigned)hi < (unsigned)Hl && (unsigned)wi < (unsigned)Wl;
+      if (UP && ok) {  // only every up-th logical position holds data
+        const int hq = hi / g.up, wq = wi / g.up;
+        ok = hq * g.up == hi && wq * g.up == wi;
+        hi = hq;
+        wi = wq;
+      }
       r.a[i] = ok ? ldg16(X + (nbase[i] + (hi * g.W + wi) * g.Ci + ci)) : zero16();
     }
 #pragma unroll
@@ -211,12 +219,15 @@ hipError_t launch_igemm(hipStream_t s, const bf16_t* x, const bf16_t* w, const C
   const long long P = (long long)g.N * g.Ho * g.Wo;
   if ((long long)g.N * g.H * g.W * g.Ci >= (1ll << 31) || P * g.Co >= (1ll << 31) || (g.Ci % 8))
     return hipErrorInvalidValue;
+  const bool up = g.up > 1;
   if (g.Co <= 64) {
     dim3 grid(1, (unsigned)((P + 255) / 256));
-    conv_igemm_kernel<4, 1><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    if (up) conv_igemm_kernel<4, 1, true><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    else conv_igemm_kernel<4, 1, false><<<grid, kThreads, 0, s>>>(x, w, g, ep);
   } else {
     dim3 grid((g.Co + 127) / 128, (unsigned)((P + 127) / 128));
-    conv_igemm_kernel<2, 2><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    if (up) conv_igemm_kernel<2, 2, true><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    else conv_igemm_kernel<2, 2, false><<<grid, kThreads, 0, s>>>(x, w, g, ep);
   }
   return hipGetLastError();
 }
@@ -554,19 +565,6 @@ __global__ __launch_bounds__(kThreads) void conv_smallk_wgrad_kernel(const bf16_
 // ------------------------------------------------------------------------------------------------
 // 2x2 / stride-2 max pooling over NHWC, 8 channels (16 bytes) per thread.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void unpack8(uint4 v, uint16_t* o) {
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    o[2 * q] = (uint16_t)(w[q] & 0xffffu);
-    o[2 * q + 1] = (uint16_t)(w[q] >> 16);
-  }
-}
-__device__ __forceinline__ uint4 pack8(const uint16_t* o) {
-  return make_uint4(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16), o[4] | ((uint32_t)o[5] << 16),
-                    o[6] | ((uint32_t)o[7] << 16));
-}
-
 __global__ __launch_bounds__(256) void maxpool2x2_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
                                                              int N, int H, int W, int C) {
   const int Ho = H / 2, Wo = W / 2, C8 = C / 8;
@@ -669,12 +667,16 @@ hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, co
 
 hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf16_t* wt_scratch, const ConvGeom& g,
                            const ConvEpilogue& ep) {
-  if (g.stride != 1 || (g.Co % 8)) return hipErrorInvalidValue;
+  if (g.stride < 1 || (g.Co % 8)) return hipErrorInvalidValue;
   const size_t n = (size_t)g.Co * g.kh * g.kw * g.Ci;
   flip_transpose_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(w, wt_scratch, g.Co, g.kh, g.kw, g.Ci);
-  ConvGeom t = g;  // the transposed convolution: dL/dy [N][Ho][Wo][Co] -> dL/dx [N][H][W][Ci]
+  // the transposed convolution: dL/dy [N][Ho][Wo][Co] (zero-upsampled by the stride) -> dL/dx [N][H][W][Ci], a
+  // stride-1 convolution with the flipped weights and padding k-1-p; input rows/columns the forward pass never
+  // touched (when (H + 2p - k) % stride != 0) fall outside the upsampled tensor and come out as zero
+  ConvGeom t = g;
   t.H = g.Ho; t.W = g.Wo; t.Ci = g.Co; t.Ho = g.H; t.Wo = g.W; t.Co = g.Ci;
   t.ph = g.kh - 1 - g.ph; t.pw = g.kw - 1 - g.pw;
+  t.stride = 1; t.up = g.stride;
   return launch_igemm(s, dz, wt_scratch, t, ep);
 }
 

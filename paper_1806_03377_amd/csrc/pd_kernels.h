@@ -68,6 +68,9 @@ struct ConvGeom {
   int N, H, W, Ci;   // input  [N][H][W][Ci]
   int Ho, Wo, Co;    // output [N][Ho][Wo][Co]
   int kh, kw, stride, ph, pw;
+  int up;            // > 1: the input is read as if zero-upsampled by this factor (logical size (H-1)*up+1 by
+                     // (W-1)*up+1, data only at multiples of `up`); 0 or 1: plain.  Used by the gradient of a
+                     // strided convolution.
 };
 struct ConvEpilogue {
   const bf16_t* bias;  // [Co] or null
@@ -80,7 +83,8 @@ bool conv_is_smallk(const ConvGeom& g);
 // y = act(conv(x, w) + b); w[Co][kh][kw][Ci].  Needs Ci % 8 == 0 unless conv_is_smallk.
 hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g,
                              const ConvEpilogue& ep);
-// dx = convT(dz, w) .* mask, stride 1 only; wt_scratch holds Co*kh*kw*Ci elements (flipped, transposed weights).
+// dx = convT(dz, w) .* mask; wt_scratch holds Co*kh*kw*Ci elements (flipped, transposed weights).  For stride s > 1
+// the transposed convolution reads dz zero-upsampled by s (taps that fall between samples contribute nothing).
 hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf16_t* wt_scratch, const ConvGeom& g,
                            const ConvEpilogue& ep);
 // Number of partial sums the weight-gradient kernel produces for this geometry, and the kernel itself:
@@ -93,6 +97,26 @@ hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t
 hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t stride, size_t n_w, int n_b,
                                float* master_w, float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b,
                                bf16_t* ring_b, float lr, float mu);
+// General pooling over NHWC (window k x k, stride, zero padding `pad` on every side; C % 8 == 0):
+//   max: padding never wins; backward sends dy to the FIRST maximum of each window in row-major order and sums,
+//        per input position, the contributions of the windows that cover it in row-major window order
+//   avg: sum of the window (padding counts as zeros) divided by k*k; backward = the transposed operator
+// relu_mask (backward): additionally zero dx where x <= 0.
+struct PoolGeom {
+  int N, H, W, C, k, stride, pad, Ho, Wo;
+};
+hipError_t pool2d_forward_bf16(hipStream_t s, bool is_max, const bf16_t* x, bf16_t* y, const PoolGeom& g);
+hipError_t pool2d_backward_bf16(hipStream_t s, bool is_max, const bf16_t* x, const bf16_t* y, const bf16_t* dy,
+                                bf16_t* dx, const PoolGeom& g, bool relu_mask);
+// Channel concatenation helpers for [pixels][channels] bf16 tensors (all channel counts % 8 == 0):
+//   copy_channels: dst[p][dst_off .. dst_off+c) = src[p][src_off .. src_off+c)   (row strides ld_dst, ld_src);
+//                  with mask != null (same layout as dst) values are zeroed where mask <= 0
+//   sum_tensors:   dst = bf16(sum_i src[i]) in index order (fp32), times (mask > 0) if mask != null; n elements
+hipError_t copy_channels_bf16(hipStream_t s, const bf16_t* src, int ld_src, int src_off, bf16_t* dst, int ld_dst,
+                              int dst_off, const bf16_t* mask, size_t pixels, int c);
+constexpr int kMaxBranches = 8;
+hipError_t sum_tensors_bf16(hipStream_t s, const bf16_t* const* src, int count, const bf16_t* mask, bf16_t* dst,
+                            size_t n);
 hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, int N, int H, int W, int C);
 // dx = dy routed to the first maximum of each window (row-major), times (x > 0) if relu_mask
 hipError_t maxpool2x2_backward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* y, const bf16_t* dy, bf16_t* dx, int N,

@@ -80,7 +80,10 @@ int emit_schedule(int depth, int M, pd_op* out, size_t cap, size_t* n_out) {
   return PD_OK;
 }
 
-enum { K_LINEAR = 0, K_CONV = 1, K_POOL = 2, K_LSTM = 3 };
+enum { K_LINEAR = 0, K_CONV = 1, K_POOL = 2, K_LSTM = 3, K_GPOOL = 4, K_CONCAT = 5 };
+// K_POOL: the 2x2/stride-2 max pooling fast path; K_GPOOL: any other max or average pooling; K_CONCAT: the
+// channel concatenation that closes a block of parallel branches (a layer without parameters whose output is
+// assembled from the branch outputs).
 
 // From this many rows on, a Linear/LSTM weight gradient is formed by the large-reduction kernel (fp32 partial
 // sums over row ranges, then a fused reduce + update) instead of the kernel built for minibatch-sized reductions.
@@ -113,6 +116,19 @@ struct Layer {
                                 // the cell states [T+1][B][H] fp32 (slot 0 = zeros); y_off holds [T+1][B][H] hidden
                                 // states (slot 0 = zeros), the layer's output starts at slot 1
   size_t dc_off = 0;          // LSTM: byte offset of dL/dc [B][H] fp32 inside the gradient workspace
+  // data flow: the layer whose stored output this layer reads (-1: the stage input).  In a chain that is the
+  // layer before; the first layer of every branch of a block reads the block's input.
+  int src = -1;
+  bool is_max = false;        // K_GPOOL: max (true) or average pooling
+  int block = -1;             // index of the K_CONCAT layer closing the block this layer is in (-1: none)
+  bool br_first = false, br_last = false;
+  size_t bdy_off = 0;         // last layer of a branch: where its slice of the block's output gradient is staged
+  size_t bdx_off = 0;         // first layer of a branch: where its contribution to the block's input gradient goes
+  // K_CONCAT: the branches (first and last layer, channel offset and count of each slice), the block's input
+  int nbr = 0, b_first[pd::kMaxBranches] = {}, b_last[pd::kMaxBranches] = {}, b_coff[pd::kMaxBranches] = {},
+      b_c[pd::kMaxBranches] = {};
+  int blk_src = -1;
+  size_t blk_in_elems = 0;    // elements of the block's input (rows * features)
 };
 typedef Layer Linear;  // (historic name used below for "a layer")
 
@@ -148,6 +164,9 @@ struct pd_stage {
   char* pp = nullptr;        // two ping-pong activation-gradient buffers (conv/pool layers)
   char* part = nullptr;      // conv weight-gradient partial sums, all layers
   char* wt = nullptr;        // flipped/transposed conv weights for dgrad (largest layer)
+  char* blk_dy = nullptr;    // block backward: the output gradient split into per-branch contiguous tensors
+  char* blk_dx = nullptr;    // block backward: one input-gradient tensor per branch, summed afterwards
+  size_t blk_dx_stride = 0;
   float* ws = nullptr;
   size_t ws_bytes = 0;
   float* row_loss = nullptr;
@@ -180,6 +199,7 @@ struct Plan {
   int classes = 0, depth = 1, in_depth = 1, B = 0;
   size_t esz = 4, n_params = 0, p_pad = 0, in_bytes = 0, out_bytes = 0, stash_slot_bytes = 0, dlogits_off = 0;
   size_t ws_bytes = 0, dz_bytes = 0, pp_bytes = 0, part_bytes = 0, wt_bytes = 0;
+  size_t blk_dy_bytes = 0, blk_dx_bytes = 0, blk_dx_stride = 0, o_blk_dy = 0, o_blk_dx = 0;
   // arena offsets
   size_t o_ring = 0, o_master = 0, o_mom = 0, o_in = 0, o_stash = 0, o_dz = 0, o_grad = 0, o_ws = 0, o_rowloss = 0;
   size_t o_pp = 0, o_part = 0, o_wt = 0;
@@ -204,9 +224,83 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   int ch = 0, hh = 1, ww = 1;   // its NHWC shape
   int rows = p.B;               // rows of the current activation matrix
   size_t x_off = 0;             // LSTM extras inside a stash slot
+  int next_src = -1;            // the layer whose output the next compute layer reads (-1: stage input)
+  // an open block of parallel branches
+  bool in_block = false, branch_open = false, branch_first_pending = false;
+  int blk_src = -1, blk_width = -1, blk_ch = 0, blk_hh = 1, blk_ww = 1, nbr = 0, coff = 0, blk_oh = 0, blk_ow = 0;
+  int b_first[pd::kMaxBranches], b_last[pd::kMaxBranches], b_coff[pd::kMaxBranches], b_c[pd::kMaxBranches];
+  auto close_branch = [&](int i) -> int {
+    if ((int)p.lin.size() == 0 || b_first[nbr] > (int)p.lin.size() - 1)
+      return fail(PD_EINVAL, "layer %d: a branch needs at least one layer", i);
+    if (nbr > 0 && (hh != blk_oh || ww != blk_ow))
+      return fail(PD_EINVAL, "layer %d: branch %d ends at %dx%d, the others at %dx%d", i, nbr, hh, ww, blk_oh, blk_ow);
+    blk_oh = hh; blk_ow = ww;
+    b_last[nbr] = (int)p.lin.size() - 1;
+    b_coff[nbr] = coff; b_c[nbr] = ch;
+    p.lin[b_last[nbr]].br_last = true;
+    coff += ch;
+    ++nbr;
+    branch_open = false;
+    return PD_OK;
+  };
   for (int i = 0; i < c->n_layers; ++i) {
     const pd_layer_desc& d = c->layers[i];
     if (p.has_loss) return fail(PD_EINVAL, "PD_SOFTMAX_XENT must be the last layer");
+    if (d.kind == PD_CONCAT_BEGIN || d.kind == PD_BRANCH || d.kind == PD_CONCAT_END) {
+      if (!p.bf16) return fail(PD_EINVAL, "layer %d: branched blocks are only built for PD_BF16_F32ACC", i);
+      if (d.kind == PD_CONCAT_BEGIN) {
+        if (in_block) return fail(PD_EINVAL, "layer %d: blocks do not nest", i);
+        if (rows != p.B) return fail(PD_EINVAL, "layer %d: a block cannot follow an LSTM", i);
+        in_block = true; branch_open = false; nbr = 0; coff = 0;
+        blk_src = next_src; blk_width = width; blk_ch = ch; blk_hh = hh; blk_ww = ww;
+      } else if (d.kind == PD_BRANCH) {
+        if (!in_block) return fail(PD_EINVAL, "layer %d: PD_BRANCH outside a block", i);
+        if (branch_open) { const int rc = close_branch(i); if (rc) return rc; }
+        if (nbr >= pd::kMaxBranches) return fail(PD_EINVAL, "layer %d: more than %d branches", i, pd::kMaxBranches);
+        branch_open = true; branch_first_pending = true;
+        b_first[nbr] = (int)p.lin.size();
+        next_src = blk_src; width = blk_width; ch = blk_ch; hh = blk_hh; ww = blk_ww;
+      } else {
+        if (!in_block || !branch_open) return fail(PD_EINVAL, "layer %d: PD_CONCAT_END without an open branch", i);
+        const int rc = close_branch(i); if (rc) return rc;
+        Layer L;
+        L.kind = K_CONCAT;
+        L.ih = L.oh = blk_oh; L.iw = L.ow = blk_ow; L.ic = L.oc = coff;
+        L.in = L.out = blk_oh * blk_ow * coff;
+        L.rows = p.B; L.src = -1; L.nbr = nbr; L.blk_src = blk_src;
+        const int me = (int)p.lin.size();
+        size_t dyo = 0;
+        for (int b = 0; b < nbr; ++b) {
+          L.b_first[b] = b_first[b]; L.b_last[b] = b_last[b]; L.b_coff[b] = b_coff[b]; L.b_c[b] = b_c[b];
+          for (int q = b_first[b]; q <= b_last[b]; ++q) p.lin[q].block = me;
+          p.lin[b_last[b]].bdy_off = dyo;
+          dyo += align_up((size_t)p.B * blk_oh * blk_ow * b_c[b] * 2, 256);
+        }
+        if (dyo > p.blk_dy_bytes) p.blk_dy_bytes = dyo;
+        // stage input width is known only once a layer has stated it: take it from the branch's first layer
+        L.blk_in_elems = (size_t)p.lin[b_first[0]].rows * p.lin[b_first[0]].in;
+        const size_t stride = align_up(L.blk_in_elems * 2, 256);
+        for (int b = 0; b < nbr; ++b) {
+          if ((size_t)p.lin[b_first[b]].in != (size_t)p.lin[b_first[0]].in)
+            return fail(PD_EINVAL, "layer %d: the branches disagree on the block's input size", i);
+          p.lin[b_first[b]].bdx_off = (size_t)b * stride;
+        }
+        if (stride > p.blk_dx_stride) p.blk_dx_stride = stride;
+        if (stride * nbr > p.blk_dx_bytes) p.blk_dx_bytes = stride * nbr;
+        p.lin.push_back(L);
+        in_block = false;
+        width = L.out; ch = coff; hh = blk_oh; ww = blk_ow;
+        next_src = me;
+        Layer& C = p.lin.back();
+        C.y_off = y_off; y_off = align_up(y_off + (size_t)C.rows * C.out * 4, 256);
+        const size_t ab = align_up((size_t)C.rows * C.out * p.esz, 256);
+        if (ab > p.pp_bytes) p.pp_bytes = ab;
+      }
+      continue;
+    }
+    if (in_block && !branch_open) return fail(PD_EINVAL, "layer %d: a layer inside a block must follow PD_BRANCH", i);
+    if (in_block && d.kind != PD_CONV2D && d.kind != PD_MAXPOOL2D && d.kind != PD_AVGPOOL2D)
+      return fail(PD_EINVAL, "layer %d: only convolution and pooling layers may sit inside a block", i);
     if (d.kind == PD_LINEAR) {
       Layer L;
       L.kind = K_LINEAR;
@@ -264,15 +358,21 @@ int make_plan(const pd_stage_config* c, Plan& p) {
       if (L.n_w * 2 > p.wt_bytes) p.wt_bytes = align_up(L.n_w * 2, 256);
       width = L.out; ch = L.oc; hh = L.oh; ww = L.ow;
       p.lin.push_back(L);
-    } else if (d.kind == PD_MAXPOOL2D) {
+    } else if (d.kind == PD_MAXPOOL2D || d.kind == PD_AVGPOOL2D) {
       Layer L;
-      L.kind = K_POOL;
-      L.kh = L.kw = d.p[0]; L.stride = d.p[1]; L.ic = L.oc = d.p[2]; L.ih = d.p[3]; L.iw = d.p[4];
+      const bool is_max = d.kind == PD_MAXPOOL2D;
+      L.kh = L.kw = d.p[0]; L.stride = d.p[1];
+      L.ph = L.pw = is_max ? 0 : d.p[2];
+      const int* q = is_max ? d.p + 2 : d.p + 3;
+      L.ic = L.oc = q[0]; L.ih = q[1]; L.iw = q[2];
+      L.is_max = is_max;
       if (!p.bf16) return fail(PD_EINVAL, "layer %d: pooling is only built for PD_BF16_F32ACC", i);
-      if (L.kh != 2 || L.stride != 2) return fail(PD_EINVAL, "layer %d: only 2x2 / stride-2 max pooling is built", i);
-      if (L.ic < 8 || L.ic % 8 || L.ih < 2 || L.iw < 2 || (L.ih % 2) || (L.iw % 2))
-        return fail(PD_EINVAL, "layer %d: pooling needs channels divisible by 8 and even height/width", i);
-      L.oh = L.ih / 2; L.ow = L.iw / 2;
+      if (L.kh < 1 || L.stride < 1 || L.ph < 0 || L.ph >= L.kh || L.ic < 8 || (L.ic % 8) || L.ih + 2 * L.ph < L.kh ||
+          L.iw + 2 * L.pw < L.kh)
+        return fail(PD_EINVAL, "layer %d: pooling needs window >= 1, stride >= 1, 0 <= pad < window <= padded input, "
+                    "channels divisible by 8", i);
+      L.kind = (is_max && L.kh == 2 && L.stride == 2 && !(L.ih % 2) && !(L.iw % 2)) ? K_POOL : K_GPOOL;
+      L.oh = (L.ih + 2 * L.ph - L.kh) / L.stride + 1; L.ow = (L.iw + 2 * L.pw - L.kw) / L.stride + 1;
       L.in = L.ih * L.iw * L.ic; L.out = L.oh * L.ow * L.oc;
       if (width >= 0 && (L.in != width || L.ic != ch || L.ih != hh || L.iw != ww))
         return fail(PD_EINVAL, "layer %d: pooling input does not match the previous output", i);
@@ -290,6 +390,9 @@ int make_plan(const pd_stage_config* c, Plan& p) {
     }
     if (d.kind != PD_SOFTMAX_XENT) {
       Layer& L = p.lin.back();
+      L.src = next_src;
+      next_src = (int)p.lin.size() - 1;
+      if (in_block && branch_first_pending) { L.br_first = true; branch_first_pending = false; }
       if (L.n_w) {
         L.flat_w = flat; flat += L.n_w;
         L.flat_b = flat; flat += L.n_b;
@@ -322,6 +425,7 @@ int make_plan(const pd_stage_config* c, Plan& p) {
       (void)x_off;
     }
   }
+  if (in_block) return fail(PD_EINVAL, "a block is still open at the end of the layer list");
   if (p.lin.empty()) return fail(PD_EINVAL, "stage has no compute layer");
   p.part_bytes = part_off;
   p.n_params = flat;
@@ -364,6 +468,8 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   p.o_pp = o; o += 2 * p.pp_bytes;
   p.o_part = o; o += p.part_bytes;
   p.o_wt = o; o += p.wt_bytes;
+  p.o_blk_dy = o; o += p.blk_dy_bytes;
+  p.o_blk_dx = o; o += p.blk_dx_bytes;
   p.o_rowloss = o; o += align_up((size_t)p.lin.back().rows * 4, 256);
   p.total = o;
   return PD_OK;
@@ -425,6 +531,7 @@ int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena
   st->ws = reinterpret_cast<float*>(a + p.o_ws); st->ws_bytes = p.ws_bytes;
   st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
   st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
+  st->blk_dy = a + p.o_blk_dy; st->blk_dx = a + p.o_blk_dx; st->blk_dx_stride = p.blk_dx_stride;
   hipError_t e = pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
   for (int d = 0; d < st->depth && e == hipSuccess; ++d)
     for (const Linear& L : st->lin)
@@ -659,6 +766,41 @@ int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer
   return PD_OK;
 }
 
+int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, const float* host_in, size_t n) {
+  if (check_stage(st) || !host_in || mb_id < 0) return fail(PD_EINVAL, "bad argument");
+  const int nl = (int)st->lin.size();
+  char* dst = nullptr;
+  size_t cnt = 0;
+  bool as_f32 = !st->bf16;
+  if (what == 0) {
+    if (layer < 0 || layer >= nl) return fail(PD_EINVAL, "layer %d out of range", layer);
+    if (st->lin[layer].kind == K_LSTM) return fail(PD_ESTATE, "an LSTM's stored state cannot be overwritten piecemeal");
+    dst = st->out_of(st->stash_slot(mb_id), layer);
+    cnt = (size_t)st->lin[layer].rows * st->lin[layer].out;
+    if (st->has_loss && layer == nl - 1) as_f32 = true;  // logits
+  } else if (what == 1) {
+    dst = st->in_slot(mb_id);
+    cnt = (size_t)st->lin.front().rows * st->lin.front().in;
+  } else {
+    return fail(PD_EINVAL, "unknown tensor selector %d", what);
+  }
+  if (n != cnt) return fail(PD_EINVAL, "tensor has %zu elements, caller gave %zu", cnt, n);
+  PD_HIP(hipStreamSynchronize(st->stream));
+  if (as_f32) {
+    PD_HIP(hipMemcpy(dst, host_in, cnt * 4, hipMemcpyHostToDevice));
+    return PD_OK;
+  }
+  std::vector<uint16_t> tmp(cnt);
+  for (size_t i = 0; i < cnt; ++i) {  // round to nearest even (the values are expected to be bfloat16 already)
+    uint32_t u;
+    memcpy(&u, host_in + i, 4);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    tmp[i] = (uint16_t)(u >> 16);
+  }
+  PD_HIP(hipMemcpy(dst, tmp.data(), cnt * 2, hipMemcpyHostToDevice));
+  return PD_OK;
+}
+
 int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
                float* loss_dev) {
   if (check_stage(st)) return PD_EINVAL;
@@ -677,10 +819,10 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
   char* slot = st->stash_slot(mb_id);
   const char* w = st->ring_slot(v);
   if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->lin.front().rows * st->lin.front().in * st->esz));
-  const char* a = in;
   for (int li = 0; li < (int)st->lin.size(); ++li) {
     const Layer& L = st->lin[li];
     char* y = st->out_of(slot, li);
+    const char* a = L.src < 0 ? in : st->out_of(slot, L.src);
     if (L.kind == K_LINEAR) {
       if (st->bf16) {
         const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
@@ -721,12 +863,21 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
       const pd::ConvGeom g = {st->B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
       const pd::ConvEpilogue ep = {wp + L.b_off, nullptr, L.relu ? 1 : 0, reinterpret_cast<pd::bf16_t*>(y)};
       PD_HIP(pd::conv_forward_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, g, ep));
-    } else {
+    } else if (L.kind == K_POOL) {
       PD_HIP(pd::maxpool2x2_forward_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), reinterpret_cast<pd::bf16_t*>(y),
                                          st->B, L.ih, L.iw, L.ic));
+    } else if (L.kind == K_GPOOL) {
+      const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
+      PD_HIP(pd::pool2d_forward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(a),
+                                     reinterpret_cast<pd::bf16_t*>(y), g));
+    } else {  // K_CONCAT: assemble the block's output from the branch outputs, branch 0 first
+      const size_t pixels = (size_t)st->B * L.oh * L.ow;
+      for (int b = 0; b < L.nbr; ++b)
+        PD_HIP(pd::copy_channels_bf16(s, reinterpret_cast<const pd::bf16_t*>(st->out_of(slot, L.b_last[b])), L.b_c[b], 0,
+                                      reinterpret_cast<pd::bf16_t*>(y), L.oc, L.b_coff[b], nullptr, pixels, L.b_c[b]));
     }
-    a = y;
   }
+  const char* a = st->out_of(slot, (int)st->lin.size() - 1);
   if (y_dev) PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->lin.back().rows * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
   if (st->has_loss)
     PD_HIP(pd::softmax_xent(s, reinterpret_cast<const float*>(a), labels_dev, slot + st->dlogits_off, st->row_loss,
@@ -773,7 +924,22 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   }
   for (int l = nl - 1; l >= 0; --l) {
     const Layer& L = st->lin[l];
-    const char* x = l == 0 ? st->in_slot(mb_id) : st->out_of(slot, l - 1);
+    if (L.kind == K_CONCAT) {
+      // `cur` is dL/d(block output).  Split it into one contiguous tensor per branch, applying the ReLU mask of
+      // the branch's last layer on the way; the branches are then walked one after the other (they sit at the
+      // indices below this one), each starting from its own slice.
+      const size_t pixels = (size_t)st->B * L.oh * L.ow;
+      for (int b = 0; b < L.nbr; ++b) {
+        const Layer& E = st->lin[L.b_last[b]];
+        const char* mask = E.relu ? st->out_of(slot, L.b_last[b]) : nullptr;
+        PD_HIP(pd::copy_channels_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur), L.oc, L.b_coff[b],
+                                      reinterpret_cast<pd::bf16_t*>(st->blk_dy + E.bdy_off), L.b_c[b], 0,
+                                      reinterpret_cast<const pd::bf16_t*>(mask), pixels, L.b_c[b]));
+      }
+      continue;
+    }
+    if (L.br_last) cur = st->blk_dy + L.bdy_off;
+    const char* x = L.src < 0 ? st->in_slot(mb_id) : st->out_of(slot, L.src);
     if (L.kind == K_CONV) {  // weight-gradient partial sums; pd_update reduces them and applies the update
       const pd::ConvGeom g = {st->B, L.ih, L.iw, L.ic, L.oh, L.ow, L.oc, L.kh, L.kw, L.stride, L.ph, L.pw};
       PD_HIP(pd::conv_wgrad_partial_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur),
@@ -809,9 +975,18 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
     }
     char* out;
     const char* mask = nullptr;
-    if (l > 0) {
-      out = buffer_for(l - 1);
-      if (st->lin[l - 1].relu) mask = st->out_of(slot, l - 1);
+    // where the block's summed input gradient goes (first layer of a branch): null = nobody wants it
+    const Layer* blk = L.block >= 0 ? &st->lin[L.block] : nullptr;
+    const bool blk_wanted = blk && (blk->blk_src >= 0 || dx_dev);
+    if (L.br_first) {
+      if (!blk_wanted) {
+        if (l == 0) break;
+        continue;
+      }
+      out = st->blk_dx + L.bdx_off;  // unmasked: the mask of the block's producer is applied to the sum
+    } else if (L.src >= 0) {
+      out = buffer_for(L.src);
+      if (st->lin[L.src].relu) mask = st->out_of(slot, L.src);
     } else {
       if (!dx_dev) break;
       out = static_cast<char*>(dx_dev);
@@ -843,13 +1018,36 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
                                    reinterpret_cast<pd::bf16_t*>(out)};
       PD_HIP(pd::conv_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur), wp + L.w_off,
                                  reinterpret_cast<pd::bf16_t*>(st->wt), g, ep));
-    } else {
+    } else if (L.kind == K_POOL) {
       PD_HIP(pd::maxpool2x2_backward_bf16(s, reinterpret_cast<const pd::bf16_t*>(x),
                                           reinterpret_cast<const pd::bf16_t*>(slot + L.y_off),
                                           reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out),
                                           st->B, L.ih, L.iw, L.ic, mask != nullptr));
+    } else {  // K_GPOOL (the pooling kernels take the mask as "x > 0", x being the stored output of the producer)
+      const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
+      PD_HIP(pd::pool2d_backward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(x),
+                                      reinterpret_cast<const pd::bf16_t*>(slot + L.y_off),
+                                      reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out), g,
+                                      mask != nullptr));
     }
     cur = out;
+    if (L.br_first && l == blk->b_first[0]) {
+      // every branch has left its input gradient: add them up in branch order, apply the producer's ReLU mask
+      const pd::bf16_t* parts[pd::kMaxBranches];
+      for (int b = 0; b < blk->nbr; ++b)
+        parts[b] = reinterpret_cast<const pd::bf16_t*>(st->blk_dx + st->lin[blk->b_first[b]].bdx_off);
+      char* sum_out;
+      const char* sum_mask = nullptr;
+      if (blk->blk_src >= 0) {
+        sum_out = buffer_for(blk->blk_src);
+        if (st->lin[blk->blk_src].relu) sum_mask = st->out_of(slot, blk->blk_src);
+      } else {
+        sum_out = static_cast<char*>(dx_dev);
+      }
+      PD_HIP(pd::sum_tensors_bf16(s, parts, blk->nbr, reinterpret_cast<const pd::bf16_t*>(sum_mask),
+                                  reinterpret_cast<pd::bf16_t*>(sum_out), blk->blk_in_elems));
+      cur = sum_out;
+    }
   }
   st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
   st->grad_pending = true;
@@ -870,7 +1068,7 @@ int pd_update(pd_stage* st) {
   batch.count = 0; batch.M = st->B; batch.lr = st->lr; batch.mu = st->mu;
   for (int l = 0; l < nl; ++l) {
     const Layer& L = st->lin[l];
-    if (L.kind == K_POOL) continue;
+    if (!L.n_w) continue;  // pooling, concatenation
     if (L.kind == K_CONV) {  // partial sums left by pd_backward -> momentum-SGD step into the next ring slot
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
       PD_HIP(pd::wgrad_reduce_update(s, reinterpret_cast<const float*>(st->part + L.part_off), L.splits, 0, L.n_w,
@@ -879,7 +1077,7 @@ int pd_update(pd_stage* st) {
       continue;
     }
     const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
-    const char* x = l == 0 ? st->in_slot(mb) : st->out_of(slot, l - 1);
+    const char* x = L.src < 0 ? st->in_slot(mb) : st->out_of(slot, L.src);
     if (st->bf16 && L.splits > 0) {  // many rows: partial sums over row ranges, then reduce + update
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
       const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
@@ -1074,6 +1272,7 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
 
 static int conv_geom(const int32_t* q, pd::ConvGeom& g) {
   if (!q) return fail(PD_EINVAL, "geom is null");
+  g = pd::ConvGeom{};
   g.N = q[0]; g.H = q[1]; g.W = q[2]; g.Ci = q[3]; g.Co = q[4]; g.kh = q[5]; g.kw = q[6]; g.stride = q[7];
   g.ph = q[8]; g.pw = q[9];
   if (g.N < 1 || g.H < 1 || g.W < 1 || g.Ci < 1 || g.Co < 1 || g.kh < 1 || g.kw < 1 || g.stride < 1 || g.ph < 0 ||
@@ -1122,7 +1321,6 @@ int pd_conv_dgrad_bf16(void* stream, const void* dz, const void* w, const void* 
   pd::ConvGeom g;
   if (conv_geom(geom, g)) return PD_EINVAL;
   if (!dz || !w || !dx || !wt_scratch) return fail(PD_EINVAL, "null pointer");
-  if (g.stride != 1) return fail(PD_EINVAL, "dgrad is built for stride 1 only");
   const pd::ConvEpilogue ep = {nullptr, static_cast<const pd::bf16_t*>(mask), 0, static_cast<pd::bf16_t*>(dx)};
   PD_HIP(pd::conv_dgrad_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(dz),
                              static_cast<const pd::bf16_t*>(w), static_cast<pd::bf16_t*>(wt_scratch), g, ep));
@@ -1169,6 +1367,38 @@ int pd_maxpool2x2_bwd_bf16(void* stream, const void* x, const void* y, const voi
   PD_HIP(pd::maxpool2x2_backward_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(x),
                                       static_cast<const pd::bf16_t*>(y), static_cast<const pd::bf16_t*>(dy),
                                       static_cast<pd::bf16_t*>(dx), N, H, W, C, relu_mask != 0));
+  return PD_OK;
+}
+
+static int pool_geom(const int32_t* q, pd::PoolGeom& g, int is_max) {
+  if (!q) return fail(PD_EINVAL, "pgeom is null");
+  g = pd::PoolGeom{q[0], q[1], q[2], q[3], q[4], q[5], q[6], 0, 0};
+  if (g.N < 1 || g.H < 1 || g.W < 1 || g.C < 8 || (g.C % 8) || g.k < 1 || g.stride < 1 || g.pad < 0 || g.pad >= g.k ||
+      g.H + 2 * g.pad < g.k || g.W + 2 * g.pad < g.k || (is_max && g.pad != 0))
+    return fail(PD_EINVAL, "pooling needs channels divisible by 8, window/stride >= 1, 0 <= pad < window <= padded "
+                "input (max pooling: pad 0)");
+  g.Ho = (g.H + 2 * g.pad - g.k) / g.stride + 1;
+  g.Wo = (g.W + 2 * g.pad - g.k) / g.stride + 1;
+  return PD_OK;
+}
+
+int pd_pool2d_fwd_bf16(void* stream, int32_t is_max, const void* x, void* y, const int32_t* pgeom) {
+  pd::PoolGeom g;
+  if (pool_geom(pgeom, g, is_max)) return PD_EINVAL;
+  if (!x || !y) return fail(PD_EINVAL, "null pointer");
+  PD_HIP(pd::pool2d_forward_bf16(static_cast<hipStream_t>(stream), is_max != 0, static_cast<const pd::bf16_t*>(x),
+                                 static_cast<pd::bf16_t*>(y), g));
+  return PD_OK;
+}
+
+int pd_pool2d_bwd_bf16(void* stream, int32_t is_max, const void* x, const void* y, const void* dy, void* dx,
+                       const int32_t* pgeom, int32_t relu_mask) {
+  pd::PoolGeom g;
+  if (pool_geom(pgeom, g, is_max)) return PD_EINVAL;
+  if (!x || !y || !dy || !dx) return fail(PD_EINVAL, "null pointer");
+  PD_HIP(pd::pool2d_backward_bf16(static_cast<hipStream_t>(stream), is_max != 0, static_cast<const pd::bf16_t*>(x),
+                                  static_cast<const pd::bf16_t*>(y), static_cast<const pd::bf16_t*>(dy),
+                                  static_cast<pd::bf16_t*>(dx), g, relu_mask != 0));
   return PD_OK;
 }
 

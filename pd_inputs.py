@@ -176,3 +176,98 @@ def config4_s2vt(input_size=4096, hidden=1000, vocab=30000, seq_len=80):
     vocabulary projection on every time step, softmax cross-entropy over all seq_len * minibatch tokens."""
     return [[("lstm", input_size, hidden, seq_len)],
             [("lstm", hidden, hidden, seq_len), ("linear", hidden, vocab, False), ("softmax_xent", vocab)]]
+
+
+def config5_inception(classes: int = 1000, width: float = 1.0):
+    """Inception-v3-shaped network on 299 x 299 x 3 images, split into four pipeline stages.
+
+    The paper cites Inception-v3 without printing its layer table; this one is the build's own, with the
+    features the benchmark configuration names: a stem of strided and unstrided 3x3 convolutions with
+    overlapping 3x3/2 max pooling down to a 35 x 35 grid; blocks of parallel 1x1 | 1x1-5x5 | 1x1-3x3-3x3 |
+    avgpool-1x1 branches at 35 x 35; a grid reduction to 17 x 17; blocks with factorised 1x7 / 7x1
+    convolutions at 17 x 17; a reduction to 8 x 8; a block at 8 x 8 with 1x3 / 3x1 convolutions; global average
+    pooling and a Linear classifier.  Convolution + bias + ReLU everywhere (no batch normalisation, no
+    auxiliary head).  ``width`` scales every channel count (kept a multiple of 8) for reduced test cases.
+    Returns (stages, input sizes) with input sizes (h, w, channels) per stage.
+    """
+    def c(n):
+        return max(8, int(round(n * width / 8.0)) * 8)
+
+    def conv(ci, co, kh, kw, stride=1, ph=0, pw=0):
+        return ("conv2d", ci, co, kh, kw, stride, ph, pw, True)
+
+    def block_a(ci, pool_proj):
+        return ("concat", [[conv(ci, c(64), 1, 1)],
+                           [conv(ci, c(48), 1, 1), conv(c(48), c(64), 5, 5, 1, 2, 2)],
+                           [conv(ci, c(64), 1, 1), conv(c(64), c(96), 3, 3, 1, 1, 1), conv(c(96), c(96), 3, 3, 1, 1, 1)],
+                           [("avgpool2d", 3, 1, 1), conv(ci, pool_proj, 1, 1)]]), c(64) + c(64) + c(96) + pool_proj
+
+    def reduce_b(ci):
+        return ("concat", [[conv(ci, c(384), 3, 3, 2)],
+                           [conv(ci, c(64), 1, 1), conv(c(64), c(96), 3, 3, 1, 1, 1), conv(c(96), c(96), 3, 3, 2)],
+                           [("maxpool2d", 3, 2)]]), c(384) + c(96) + ci
+
+    def block_c(ci, m):
+        return ("concat", [[conv(ci, c(192), 1, 1)],
+                           [conv(ci, m, 1, 1), conv(m, m, 1, 7, 1, 0, 3), conv(m, c(192), 7, 1, 1, 3, 0)],
+                           [conv(ci, m, 1, 1), conv(m, m, 7, 1, 1, 3, 0), conv(m, m, 1, 7, 1, 0, 3),
+                            conv(m, m, 7, 1, 1, 3, 0), conv(m, c(192), 1, 7, 1, 0, 3)],
+                           [("avgpool2d", 3, 1, 1), conv(ci, c(192), 1, 1)]]), 4 * c(192)
+
+    def reduce_d(ci):
+        return ("concat", [[conv(ci, c(192), 1, 1), conv(c(192), c(320), 3, 3, 2)],
+                           [conv(ci, c(192), 1, 1), conv(c(192), c(192), 1, 7, 1, 0, 3), conv(c(192), c(192), 7, 1, 1, 3, 0),
+                            conv(c(192), c(192), 3, 3, 2)],
+                           [("maxpool2d", 3, 2)]]), c(320) + c(192) + ci
+
+    def block_e(ci):
+        return ("concat", [[conv(ci, c(320), 1, 1)],
+                           [conv(ci, c(384), 1, 1), conv(c(384), c(384), 1, 3, 1, 0, 1)],
+                           [conv(ci, c(448), 1, 1), conv(c(448), c(384), 3, 3, 1, 1, 1), conv(c(384), c(384), 3, 1, 1, 1, 0)],
+                           [("avgpool2d", 3, 1, 1), conv(ci, c(192), 1, 1)]]), c(320) + 2 * c(384) + c(192)
+
+    stem = [conv(3, c(32), 3, 3, 2), conv(c(32), c(32), 3, 3), conv(c(32), c(64), 3, 3, 1, 1, 1), ("maxpool2d", 3, 2),
+            conv(c(64), c(80), 1, 1), conv(c(80), c(192), 3, 3), ("maxpool2d", 3, 2)]
+    ch = c(192)
+    a1, ch1 = block_a(ch, c(32))
+    a2, ch2 = block_a(ch1, c(64))
+    a3, ch3 = block_a(ch2, c(64))
+    rb, ch4 = reduce_b(ch3)
+    c1, ch5 = block_c(ch4, c(128))
+    c2, ch6 = block_c(ch5, c(160))
+    c3, ch7 = block_c(ch6, c(160))
+    c4, ch8 = block_c(ch7, c(192))
+    rd, ch9 = reduce_d(ch8)
+    e1, ch10 = block_e(ch9)
+    head = [("avgpool2d", 8, 1, 0), ("linear", ch10, classes, False), ("softmax_xent", classes)]
+    stages = [stem, [a1, a2, a3], [rb, c1, c2], [c3, c4, rd, e1] + head]
+    sizes = [(299, 299, 3), (35, 35, ch), (35, 35, ch3), (17, 17, ch6)]
+    return stages, sizes
+
+
+def forward_flops(layers, hwc, rows: int = 1):
+    """(multiply-add flops x2 of one forward pass for `rows` images, output (h, w, c)) of a layer list."""
+    h, w, ch = hwc
+    total = 0
+
+    def walk(ls, h, w, ch):
+        nonlocal total
+        for L in ls:
+            if L[0] == "conv2d":
+                h, w = (h + 2 * L[6] - L[3]) // L[5] + 1, (w + 2 * L[7] - L[4]) // L[5] + 1
+                total += 2 * rows * h * w * L[2] * L[3] * L[4] * L[1]
+                ch = L[2]
+            elif L[0] == "maxpool2d":
+                h, w = (h - L[1]) // L[2] + 1, (w - L[1]) // L[2] + 1
+            elif L[0] == "avgpool2d":
+                h, w = (h + 2 * L[3] - L[1]) // L[2] + 1, (w + 2 * L[3] - L[1]) // L[2] + 1
+            elif L[0] == "linear":
+                total += 2 * rows * L[1] * L[2]
+                h, w, ch = 1, 1, L[2]
+            elif L[0] == "concat":
+                outs = [walk(br, h, w, ch) for br in L[1]]
+                h, w, ch = outs[0][0], outs[0][1], sum(o[2] for o in outs)
+        return h, w, ch
+
+    out = walk(layers, h, w, ch)
+    return total, out

@@ -41,8 +41,19 @@ TOUCHED_UPDATE = 2.5   # factor for an update whose minibatch had a touched row 
 
 
 def _linears(layers):
-    """The compute layers of a stage (everything but the loss), in order."""
-    return [l for l in layers if l[0] != "softmax_xent"]
+    """The compute layers of a stage (everything but the loss) in the order the runtime numbers them: a
+    branched block contributes its branch layers (branch 0 first) and then one entry for its concatenated output."""
+    out = []
+    for l in layers:
+        if l[0] == "softmax_xent":
+            continue
+        if l[0] == "concat":
+            for br in l[1]:
+                out.extend(br)
+            out.append(("concat_out",))
+        else:
+            out.append(l)
+    return out
 
 
 def _relu(L):
@@ -87,7 +98,13 @@ def _global_order(S, noam, M, depth_override):
 
 
 def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=0, out_grads=None,
-             lr=0.01, mu=0.9, mode="free", compare=True, verbose=False, in_hw=None, minibatch=None):
+             lr=0.01, mu=0.9, mode="free", compare=True, verbose=False, in_hw=None, minibatch=None,
+             force_acts=False):
+    """force_acts (deep image stages): after every forward pass has been compared, the GPU stage's stored layer
+    outputs -- and the next stage's input slot -- are overwritten with the oracle's (oracle -> GPU only).  In a
+    deep bf16 chain one-ulp differences compound layer by layer into differing ReLU / max-pooling decisions; with
+    the stored activations forced, every backward pass and update is compared on identical decisions and must
+    meet the tolerance in full, while each forward pass is still the GPU's own from the stage input on."""
     bf16 = precision == pd.PD_BF16_F32ACC
     omode = "bf16" if bf16 else "f32"
     tol = TOL_BF16 if bf16 else TOL_F32
@@ -100,9 +117,13 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
     if compare:
         for o in os_:
             o.log = {}
-    assert in_hw is None or S == 1, "image stages are driven one at a time here"
+    # in_hw: (h, w[, c]) of the input images of a single image stage, or one such tuple (or None) per stage
+    hws = [in_hw] if (in_hw is None or not isinstance(in_hw[0], (tuple, list, type(None)))) else list(in_hw)
+    if len(hws) == 1 and S > 1:
+        assert in_hw is None, "give one input size per stage"
+        hws = [None] * S
     gs = [GpuStage(stage_layers[s], params[s], minibatch=B, precision=precision, stage_index=s, num_stages=S,
-                   noam=noam, in_flight_override=depth_override, lr=lr, momentum=mu, in_hw=in_hw) for s in range(S)]
+                   noam=noam, in_flight_override=depth_override, lr=lr, momentum=mu, in_hw=hws[s]) for s in range(S)]
     keep = []          # device tensors that must outlive the enqueued work
     losses = torch.zeros(M, dtype=torch.float32, device=dev())
     o_losses = [None] * M
@@ -141,9 +162,10 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                     continue
                 assert o.trace[-1] == (OP_F, mb, op.version, op.slot)
                 acts_o = o.log[mb]["acts"]
+                flat_o = o.log[mb]["flat"]
                 rows, units = set(), {}
                 for li, L in enumerate(lin):
-                    y_o = acts_o[li + 1].reshape(B, -1)
+                    y_o = flat_o[li].reshape(B, -1)
                     y_g = pd.pd_stage_debug_read(g.h, 0, mb, li, y_o.shape).astype(np.float64)
                     assert rel_err(y_g, y_o) <= tol, ("forward", s, mb, li, rel_err(y_g, y_o))
                     if _relu(L):
@@ -162,6 +184,13 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                     shp = acts_o[-1].reshape(B, -1).shape
                     nxt = pd.pd_stage_debug_read(gs[s + 1].h, 1, mb, 0, shp)
                     assert np.array_equal(nxt, pd.pd_stage_debug_read(g.h, 0, mb, len(lin) - 1, shp))
+                if force_acts:
+                    for li, L in enumerate(lin):
+                        if L[0] != "lstm":
+                            pd.pd_stage_debug_write(g.h, 0, mb, li, flat_o[li])
+                    if s < S - 1:
+                        pd.pd_stage_debug_write(gs[s + 1].h, 1, mb, 0, flat_o[-1])
+                    flips_at[(s, mb)], units_at[(s, mb)] = set(), {}     # decisions are now the oracle's on both sides
                 if verbose:
                     print(f"F stage {s} mb {mb} v{op.version}: rows with ambiguous ReLU decisions {len(rows)} "
                           f"(total elements {n_flips}/{n_elems})", flush=True)

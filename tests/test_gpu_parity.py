@@ -369,6 +369,162 @@ def test_config3_vgg_conv_full_geometry_reduced_batch():
 
 
 # ---------------------------------------------------------------------------------------------
+# strided-convolution gradient, general pooling, branched blocks (the pieces of Inception-shaped stages)
+# ---------------------------------------------------------------------------------------------
+STRIDED = [(2, 13, 13, 16, 32, 3, 3, 2, 1, 1), (2, 12, 12, 8, 16, 3, 3, 2, 0, 0), (1, 35, 35, 24, 40, 3, 3, 2, 0, 0),
+           (2, 9, 10, 16, 8, 1, 1, 2, 0, 0), (1, 17, 17, 136, 72, 3, 3, 2, 0, 0), (2, 11, 11, 8, 8, 5, 5, 3, 2, 2)]
+
+
+@pytest.mark.parametrize("geom", STRIDED)
+def test_conv_dgrad_strided_bf16(geom):
+    test_conv_dgrad_bf16(geom)
+
+
+@pytest.mark.parametrize("is_max,N,H,W,Cn,k,stride,pad", [
+    (True, 2, 9, 7, 8, 3, 2, 0), (True, 1, 35, 35, 24, 3, 2, 0), (True, 2, 6, 6, 16, 3, 1, 0), (True, 2, 8, 8, 8, 2, 2, 0),
+    (False, 2, 7, 6, 8, 3, 1, 1), (False, 1, 17, 17, 40, 3, 1, 1), (False, 3, 8, 8, 16, 8, 1, 0), (False, 2, 9, 9, 8, 3, 2, 1)])
+def test_pool2d_bf16(is_max, N, H, W, Cn, k, stride, pad):
+    # coarse grid of values so that ties inside max windows are common
+    x = _bf(np.round(gen.normal(SEED, "gx", (N, H, W, Cn)) * 4) / 4)
+    s = torch.cuda.current_stream().cuda_stream
+    xd = to_dev(x, True)
+    y_ref = OL.maxpool2d_forward(x, k, stride) if is_max else OL.avgpool2d_forward(x, k, stride, pad, OL.round_bf16)
+    y = torch.empty(y_ref.shape, dtype=torch.bfloat16, device=dev())
+    pg = (N, H, W, Cn, k, stride, pad)
+    pd.pd_pool2d_fwd_bf16(s, is_max, xd.data_ptr(), y.data_ptr(), pg)
+    if is_max:
+        assert np.array_equal(to_host(y), y_ref)
+    else:
+        assert rel_err(to_host(y), y_ref) <= 2 ** -8
+    dy = _bf(gen.normal(SEED, "gdy", y_ref.shape))
+    dyd = to_dev(dy, True)
+    yd = to_dev(y_ref, True)
+    for relu_mask in (False, True):
+        ref = (OL.round_bf16(OL.maxpool2d_backward(x, y_ref, dy, k, stride)) if is_max
+               else OL.avgpool2d_backward(x.shape, dy, k, stride, pad, OL.round_bf16))
+        if relu_mask:
+            ref = ref * (x > 0)
+        dx = torch.empty(x.shape, dtype=torch.bfloat16, device=dev())
+        pd.pd_pool2d_bwd_bf16(s, is_max, xd.data_ptr(), yd.data_ptr(), dyd.data_ptr(), dx.data_ptr(), pg, relu_mask)
+        got = to_host(dx)
+        # routing is exact; sums of up to k*k bf16 terms may round one step apart (fp32 vs fp64 accumulation)
+        if is_max:
+            assert np.array_equal(got == 0, ref == 0), relu_mask
+        assert np.all(np.abs(got - ref) <= 2 ** -7 * np.abs(ref) + 1e-6), relu_mask
+
+
+def _inception_like(c0=8):
+    """Stem conv, a four-branch block (1x1 | 1x1-3x3 | 1x7-7x1 | avgpool-1x1), a reduction block (strided 3x3 |
+    1x1-strided 3x3 | overlapping max pool), global average pooling, classifier."""
+    blk1 = ("concat", [[("conv2d", 16, 16, 1, 1, 1, 0, 0, True)],
+                       [("conv2d", 16, 8, 1, 1, 1, 0, 0, True), ("conv2d", 8, 24, 3, 3, 1, 1, 1, True)],
+                       [("conv2d", 16, 8, 1, 7, 1, 0, 3, True), ("conv2d", 8, 8, 7, 1, 1, 3, 0, True)],
+                       [("avgpool2d", 3, 1, 1), ("conv2d", 16, 8, 1, 1, 1, 0, 0, True)]])
+    blk2 = ("concat", [[("conv2d", 56, 24, 3, 3, 2, 0, 0, True)],
+                       [("conv2d", 56, 16, 1, 1, 1, 0, 0, True), ("conv2d", 16, 16, 3, 3, 2, 0, 0, True)],
+                       [("maxpool2d", 3, 2)]])
+    return [("conv2d", c0, 16, 3, 3, 1, 1, 1, True), blk1, blk2, ("avgpool2d", 4, 1, 0), ("linear", 96, 16, False),
+            ("softmax_xent", 16)]
+
+
+def test_block_stage_with_loss():
+    _image_stage_case(_inception_like(), B=3, hw=(9, 9), c_in=8, depth=2, M=4, lr=0.05)
+
+
+def test_block_first_in_stage_and_last_no_loss():
+    # the stage starts with a block (its branches read the stage input; dL/d(input) is the sum over branches) and
+    # ends with one (the output gradient is split over the branches)
+    blk = ("concat", [[("conv2d", 8, 16, 1, 1, 1, 0, 0, True)],
+                      [("conv2d", 8, 8, 3, 3, 1, 1, 1, True), ("conv2d", 8, 8, 3, 3, 1, 1, 1, False)],
+                      [("avgpool2d", 3, 1, 1), ("conv2d", 8, 8, 1, 1, 1, 0, 0, True)]])
+    blk_b = ("concat", [[("conv2d", 32, 8, 1, 1, 1, 0, 0, True)], [("maxpool2d", 3, 1), ("conv2d", 32, 16, 1, 1, 1, 1, 1, True)]])
+    _image_stage_case([blk, blk_b], B=2, hw=(10, 10, 8), c_in=8, depth=3, M=4, with_loss=False)
+
+
+def test_block_stage_free_running_short():
+    _image_stage_case(_inception_like()[:3], B=2, hw=(9, 9), c_in=8, depth=2, M=2, with_loss=False, mode="free")
+
+
+def test_inception_like_four_stage_pipeline():
+    """Four image stages with blocks on four streams through pd_pipeline_run, free-running, against the oracle's
+    pipeline: op traces and version ids bit-exact, losses and final weights at tolerance."""
+    full = _inception_like()
+    st = [[full[0]], [full[1]], [full[2]], full[3:]]
+    hws = [(9, 9, 8), (9, 9, 16), (9, 9, 56), (4, 4, 96)]
+    S, B, M, seed = 4, 3, 6, SEED + 9
+    params = []
+    for s, ly in enumerate(st):
+        p = gen.init_params(seed, f"i{s}", ly)
+        params.append(p + 0.01 * gen.normal(seed, f"ib{s}", p.shape))
+    xs = gen.normal(seed, "X", (M, B, 9, 9, 8))
+    labs = gen.labels(seed, "Y", (M, B), 16)
+    streams = [torch.cuda.Stream(device=dev()) for _ in range(S)]
+    gs = [GpuStage(st[s], params[s], minibatch=B, precision=pd.PD_BF16_F32ACC, stage_index=s, num_stages=S, noam=S,
+                   lr=0.02, stream=streams[s], in_hw=hws[s]) for s in range(S)]
+    try:
+        xd = to_dev(xs.reshape(M * B, -1), True)
+        ld = labels_dev(labs)
+        losses = torch.zeros(M, dtype=torch.float32, device=dev())
+        torch.cuda.synchronize()
+        pd.pd_pipeline_run([g.h for g in gs], M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+        torch.cuda.synchronize()
+        ost, ol = run_pipeline(st, params, [x.astype(np.float64) for x in xs], list(labs), S, mode="bf16", lr=0.02)
+        for s in range(S):
+            assert pd.pd_stage_trace(gs[s].h) == [tuple(t) for t in ost[s].trace]
+        assert np.all(np.abs(to_host(losses) - np.array(ol)) <= TOL_BF16 * np.abs(np.array(ol)))
+        for s in range(S):
+            assert rel_err(pd.pd_stage_get_params(gs[s].h), ost[s].master) <= TOL_BF16
+            assert rel_err(pd.pd_stage_get_momentum(gs[s].h), ost[s].mom) <= 5 * TOL_BF16
+    finally:
+        for g in gs:
+            g.close()
+
+
+@pytest.mark.timeout(900)
+def test_config5_inception_full_geometry_reduced_batch():
+    # the Inception-shaped four-stage split at its real geometry (299 x 299 images, full channel counts) with two
+    # images per minibatch, the size the oracle finishes in seconds; every op compared in lockstep
+    print("config 5 geometry, minibatch 2: oracle + GPU", flush=True)
+    st, sizes = gen.config5_inception(1000, 1.0)
+    seed, M, B = SEED + 5, 3, 2
+    params = [gen.init_params(seed, f"s{s}", ly) for s, ly in enumerate(st)]
+    xs = list(gen.normal(seed, "X", (M, B, 299, 299, 3)))
+    labs = list(gen.labels(seed, "Y", (M, B), 1000))
+    out = run_case(st, params, xs, labs, noam=4, precision=pd.PD_BF16_F32ACC, lr=1e-3, mode="forced", in_hw=sizes,
+                   verbose=True, force_acts=True)
+    print("ambiguous ReLU decisions:", out["flips"], "updates compared (strict, all):", out["updates_compared"], flush=True)
+
+
+def test_config5_reduced_width_pipeline_run():
+    """The same four stages at a quarter of the channel counts, on four streams through pd_pipeline_run, free-running
+    for a short stream (bf16 trajectories separate with length): traces bit-exact, losses at tolerance."""
+    st, sizes = gen.config5_inception(16, 0.25)
+    S, B, M, seed = 4, 2, 3, SEED + 6
+    params = [gen.init_params(seed, f"w{s}", ly) for s, ly in enumerate(st)]
+    xs = gen.normal(seed, "X", (M, B, 299, 299, 3))
+    labs = gen.labels(seed, "Y", (M, B), 16)
+    streams = [torch.cuda.Stream(device=dev()) for _ in range(S)]
+    gs = [GpuStage(st[s], params[s], minibatch=B, precision=pd.PD_BF16_F32ACC, stage_index=s, num_stages=S, noam=S,
+                   lr=1e-3, stream=streams[s], in_hw=sizes[s]) for s in range(S)]
+    try:
+        xd = to_dev(xs.reshape(M * B, -1), True)
+        ld = labels_dev(labs)
+        losses = torch.zeros(M, dtype=torch.float32, device=dev())
+        torch.cuda.synchronize()
+        pd.pd_pipeline_run([g.h for g in gs], M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+        torch.cuda.synchronize()
+        ost, ol = run_pipeline(st, params, [x.astype(np.float64) for x in xs], list(labs), S, mode="bf16", lr=1e-3)
+        for s in range(S):
+            assert pd.pd_stage_trace(gs[s].h) == [tuple(t) for t in ost[s].trace]
+        assert np.all(np.abs(to_host(losses) - np.array(ol)) <= TOL_BF16 * np.abs(np.array(ol))), (to_host(losses), ol)
+        for s in range(S):
+            assert rel_err(pd.pd_stage_get_params(gs[s].h), ost[s].master) <= TOL_BF16
+    finally:
+        for g in gs:
+            g.close()
+
+
+# ---------------------------------------------------------------------------------------------
 # LSTM stages (bf16, time-major sequences): input projection GEMM, per-step recurrent GEMM + cell kernel,
 # back-propagation through time, the two weight matrices updated from dG
 # ---------------------------------------------------------------------------------------------
