@@ -215,10 +215,243 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_kernel(const bf16_t* __re
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// implicit GEMM with direct global -> LDS loads.  256 output pixels x BN output channels per workgroup, four
+// waves (BN = 128: 2 x 2 waves of 128 x 64; BN = 64: 4 x 1 waves of 64 x 64), 32 reduction elements per stage,
+// three stages in LDS, two workgroups per compute unit (their barriers are independent, so one keeps the matrix
+// cores busy while the other waits).  Every lane fetches one 16-byte chunk (8 channels of one tap of one pixel,
+// or 8 reduction elements of one filter) per load instruction straight into LDS; the hardware places lane L's
+// chunk at M0 + 16 L, i.e. a wave-wide load fills 16 consecutive 64-byte tile rows, and the XOR swizzle of a
+// row's four slots is applied by choosing which chunk a lane fetches.  Chunks that fall into the zero padding,
+// past the end of the reduction, or beyond the last pixel / channel are fetched from a 16-byte block of zeros, so
+// neither padding nor ragged shapes need a second code path.  The loads of stage st+2 are spread between the
+// MFMAs of stage st.  (The loads are inline assembly: with the builtin the compiler waits for all outstanding
+// loads before every LDS read.)
+// ------------------------------------------------------------------------------------------------
+__device__ __attribute__((aligned(16))) const uint32_t g_zero16[4] = {0u, 0u, 0u, 0u};
+typedef __attribute__((address_space(3))) void lds_void_t;
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma16(const bf16_t* lane_src, char* uniform_lds_dst) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(uniform_lds_dst));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(lane_src), "s"(lds_addr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+constexpr int DK = 32, DNS = 3, DROWB = DK * 2;
+
+template <int BN, bool UP, bool ALIGNED>
+__global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __restrict__ X,
+                                                               const bf16_t* __restrict__ Wg, ConvGeom g,
+                                                               ConvEpilogue ep) {
+  constexpr int BM_ = 256;
+  constexpr int WNW = BN / 64, WMW = 4 / WNW;         // waves along channels / pixels
+  constexpr int TM = BM_ / WMW, NI = TM / 32, NJ = 2;  // wave tile TM x 64
+  constexpr int QA = 4, QB = BN / 64, LPS = QA + QB;   // wave-wide loads per stage
+  constexpr int ATILE = BM_ * DROWB, STAGE = (BM_ + BN) * DROWB;
+  constexpr int OLD = BN + 8;
+  constexpr int kSmem = DNS * STAGE > BM_ * OLD * 2 ? DNS * STAGE : BM_ * OLD * 2;
+  constexpr int KS = DK / 16, MF = NI * NJ;
+  __shared__ __attribute__((aligned(1024))) char smem[kSmem];
+  const int t = threadIdx.x, l = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w / WNW, wn = w % WNW;
+  const int co0 = blockIdx.x * BN;
+  const int P = g.N * g.Ho * g.Wo;
+  const int p0 = blockIdx.y * BM_;
+  const int K = g.kh * g.kw * g.Ci;
+  const int T = (K + DK - 1) / DK;
+  const int Hl = UP ? (g.H - 1) * g.up + 1 : g.H, Wl = UP ? (g.W - 1) * g.up + 1 : g.W;
+  const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_zero16);
+  const int kg = ((l & 3) ^ ((l >> 4) & 3)) * 8;  // the reduction offset (within a stage) this lane fetches
+
+  int hi0[QA], wi0[QA], nbase[QA];
+#pragma unroll
+  for (int q = 0; q < QA; ++q) {
+    const int p = p0 + (q * 4 + w) * 16 + (l >> 2);
+    if (p < P) {
+      const unsigned pq = (unsigned)p / (unsigned)g.Wo;
+      const int wo = p - (int)pq * g.Wo;
+      const unsigned n = pq / (unsigned)g.Ho;
+      const int ho = (int)pq - (int)n * g.Ho;
+      nbase[q] = (int)n * g.H * g.W * g.Ci;
+      hi0[q] = ho * g.stride - g.ph;
+      wi0[q] = wo * g.stride - g.pw;
+    } else {
+      nbase[q] = -1;
+      hi0[q] = wi0[q] = 0;
+    }
+  }
+  int wrow[QB];  // element offset of this lane's filter row, or -1
+#pragma unroll
+  for (int q = 0; q < QB; ++q) {
+    const int co = co0 + (q * 4 + w) * 16 + (l >> 2);
+    wrow[q] = co < g.Co ? co * K : -1;
+  }
+  // q-th load of the stage whose reduction range starts at kk (A loads first)
+  auto load1 = [&](int q, char* stage, int kk) {
+    const int k = kk + kg;
+    const bf16_t* src = zero;
+    if (q < QA) {
+      int tap, ci;
+      if (ALIGNED) {  // a stage lies inside one tap: wave-uniform decode
+        const int tu = kk / g.Ci;
+        tap = tu;
+        ci = kk - tu * g.Ci + kg;
+      } else {
+        tap = k / g.Ci;
+        ci = k - tap * g.Ci;
+      }
+      const int ta = tap / g.kw, tb = tap - ta * g.kw;
+      int hi = hi0[q] + ta, wi = wi0[q] + tb;
+      bool ok = k < K && nbase[q] >= 0 && (unsigned)hi < (unsigned)Hl && (unsigned)wi < (unsigned)Wl;
+      if (UP && ok) {
+        const int hq = hi / g.up, wq = wi / g.up;
+        ok = hq * g.up == hi && wq * g.up == wi;
+        hi = hq;
+        wi = wq;
+      }
+      if (ok) src = X + (nbase[q] + (hi * g.W + wi) * g.Ci + ci);
+      dma16(src, stage + (q * 4 + w) * 1024);
+    } else {
+      const int qb = q - QA;
+      if (k < K && wrow[qb] >= 0) src = Wg + ((size_t)wrow[qb] + k);
+      dma16(src, stage + ATILE + (qb * 4 + w) * 1024);
+    }
+  };
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x16{0};
+  int fa[NI], fb[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int row = TM * wm + 32 * i + (l & 31);
+    fa[i] = row * DROWB + (((l >> 5) ^ ((row >> 2) & 3)) << 4);
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = 64 * wn + 32 * j + (l & 31);
+    fb[j] = ATILE + row * DROWB + (((l >> 5) ^ ((row >> 2) & 3)) << 4);
+  }
+  auto ldf = [&](const char* stage, int o, int ks) { return *reinterpret_cast<const uint4*>(stage + (o ^ (ks << 5))); };
+
+#pragma unroll
+  for (int d = 0; d < 2; ++d)
+#pragma unroll
+    for (int q = 0; q < LPS; ++q) load1(q, smem + d * STAGE, d * DK);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");  // stage 0 has landed
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  int cur = 0, fill = 2;
+  for (int st = 0; st < T; ++st) {
+    const char* sc = smem + cur * STAGE;
+    cur = cur == DNS - 1 ? 0 : cur + 1;
+    char* sl = smem + fill * STAGE;
+    fill = fill == DNS - 1 ? 0 : fill + 1;
+    const int kk = (st + 2) * DK;  // past the end of the reduction every chunk comes from the zero block
+    uint4 a[2][NI], b[2][NJ];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) a[0][i] = ldf(sc, fa[i], 0);
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) b[0][j] = ldf(sc, fb[j], 0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) a[n][i] = ldf(sc, fa[i], ks + 1);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[n][j] = ldf(sc, fb[j], ks + 1);
+      }
+      // this k-step's share of the stage's loads: q = ks, ks + KS, ks + 2 KS, ... placed after every other MFMA
+#pragma unroll
+      for (int m = 0; m < MF; ++m) {
+        const int i = m / NJ, j = m % NJ;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
+        constexpr int kGap = MF >= 8 ? 2 : 1;
+        if (m % kGap == kGap - 1) {
+          const int q = ks + KS * (m / kGap);
+          if (q < LPS) {
+            __builtin_amdgcn_sched_barrier(0);
+            load1(q, sl, kk);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");  // stage st+1 has landed; st+2 may be in flight
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  // bias / ReLU / rounding in registers, then through LDS so that global traffic is 16 bytes per lane
+  bf16_t* ot = reinterpret_cast<bf16_t*>(smem);  // [BM_][OLD]
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int cl = 64 * wn + 32 * j + (l & 31), cch = co0 + cl;
+    const float bv = (ep.bias && cch < g.Co) ? bf2f(ep.bias[cch]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = acc[i][j][r] + bv;
+        if (ep.relu) v = fmaxf(v, 0.f);
+        ot[(TM * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * OLD + cl] = f2bf(v);
+      }
+  }
+  __syncthreads();
+  constexpr int CPR = BN / 8;
+#pragma unroll
+  for (int i = 0; i < BM_ * CPR / kThreads; ++i) {
+    const int c = t + kThreads * i, row = c / CPR, cc = c % CPR;
+    const int p = p0 + row, co = co0 + cc * 8;
+    if (p >= P || co >= g.Co) continue;
+    uint4 v = *reinterpret_cast<const uint4*>(&ot[row * OLD + cc * 8]);
+    const size_t off = (size_t)p * g.Co + co;
+    if (ep.mask) {
+      const uint4 mk = ldg16(ep.mask + off);
+      const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+      uint32_t vw[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        if (!bf_positive((uint16_t)(mw[q] & 0xffffu))) vw[q] &= 0xffff0000u;
+        if (!bf_positive((uint16_t)(mw[q] >> 16))) vw[q] &= 0x0000ffffu;
+      }
+      v = make_uint4(vw[0], vw[1], vw[2], vw[3]);
+    }
+    *reinterpret_cast<uint4*>(ep.out + off) = v;
+  }
+}
+
+template <int BN>
+void launch_dma(hipStream_t s, dim3 grid, const bf16_t* x, const bf16_t* w, const ConvGeom& g, const ConvEpilogue& ep) {
+  const bool up = g.up > 1, aligned = (g.Ci % DK) == 0;
+  if (up) {
+    if (aligned) conv_dma_kernel<BN, true, true><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    else conv_dma_kernel<BN, true, false><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+  } else {
+    if (aligned) conv_dma_kernel<BN, false, true><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    else conv_dma_kernel<BN, false, false><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+  }
+}
+
+bool g_conv_dma = true;
+
 hipError_t launch_igemm(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g, const ConvEpilogue& ep) {
   const long long P = (long long)g.N * g.Ho * g.Wo;
   if ((long long)g.N * g.H * g.W * g.Ci >= (1ll << 31) || P * g.Co >= (1ll << 31) || (g.Ci % 8))
     return hipErrorInvalidValue;
+  if (g_conv_dma && (g.Co % 8) == 0 && (long long)g.Co * g.kh * g.kw * g.Ci < (1ll << 31) &&
+      ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w)) & 15) == 0) {
+    if (g.Co <= 64) launch_dma<64>(s, dim3(1, (unsigned)((P + 255) / 256)), x, w, g, ep);
+    else launch_dma<128>(s, dim3((g.Co + 127) / 128, (unsigned)((P + 255) / 256)), x, w, g, ep);
+    return hipGetLastError();
+  }
   const bool up = g.up > 1;
   if (g.Co <= 64) {
     dim3 grid(1, (unsigned)((P + 255) / 256));
