@@ -132,6 +132,14 @@ hipError_t lstm_cell_forward(hipStream_t s, float* gates, const float* rec_part,
 hipError_t lstm_cell_backward(hipStream_t s, const bf16_t* dh_out, const float* rec_part, int splits, float* dc,
                               const float* gates, const float* c, const float* c_prev, bf16_t* da, int B, int H);
 
+// The same two steps with the recurrent product fused in (one launch per time step):
+//   forward : gates += h_prev[B][H] * whh[4H][H]^T, then as lstm_cell_forward        (h_prev not null)
+//   backward: dh = dh_out + da_next[B][4H] * whh_t[H][4H]^T, then as lstm_cell_backward  (da_next not null)
+hipError_t lstm_step_forward(hipStream_t s, float* gates, const bf16_t* h_prev, const bf16_t* whh, const float* c_prev,
+                             float* c, bf16_t* h, int B, int H);
+hipError_t lstm_step_backward(hipStream_t s, const bf16_t* dh_out, const bf16_t* da_next, const bf16_t* whh_t, float* dc,
+                              const float* gates, const float* c, const float* c_prev, bf16_t* da, int B, int H);
+
 // ---- stand-alone update (update.hip) ---------------------------------------------------------------
 // m <- mu*m + g; w_out <- w_in - lr*m; ring <- bf16(w_out) if ring is not null.  g null = zero gradient.
 // All arrays 16-byte aligned.  grid_blocks <= 0 picks the default grid.

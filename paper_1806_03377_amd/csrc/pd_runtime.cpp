@@ -848,15 +848,12 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
       PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wih, wp + L.b_off, nullptr, gates, L.rows,
                                  4 * H, L.in, false, st->ws, st->ws_bytes));
       for (int t = 0; t < L.T; ++t) {
-        const float* rec = nullptr;
-        int splits = 0;
-        if (t > 0) {
-          PD_HIP(pd::gemm_partial_bf16(s, false, hbuf + (size_t)t * B * H, H, whh, B, 4 * H, H, st->ws, st->ws_bytes,
-                                       &splits));
-          rec = st->ws;
-        }
-        PD_HIP(pd::lstm_cell_forward(s, gates + (size_t)t * B * 4 * H, rec, splits, cbuf + (size_t)t * B * H,
-                                     cbuf + (size_t)(t + 1) * B * H, hbuf + (size_t)(t + 1) * B * H, B, H));
+        if (t == 0)
+          PD_HIP(pd::lstm_cell_forward(s, gates, nullptr, 0, cbuf, cbuf + (size_t)B * H, hbuf + (size_t)B * H, B, H));
+        else
+          PD_HIP(pd::lstm_step_forward(s, gates + (size_t)t * B * 4 * H, hbuf + (size_t)t * B * H, whh,
+                                       cbuf + (size_t)t * B * H, cbuf + (size_t)(t + 1) * B * H,
+                                       hbuf + (size_t)(t + 1) * B * H, B, H));
       }
     } else if (L.kind == K_CONV) {
       const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
@@ -961,16 +958,14 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
       pd::bf16_t* whh_t = reinterpret_cast<pd::bf16_t*>(st->wt);
       PD_HIP(pd::transpose_bf16(s, whh, whh_t, 4 * H, H));
       for (int t = L.T - 1; t >= 0; --t) {
-        const float* rec = nullptr;
-        int splits = 0;
-        if (t < L.T - 1) {
-          PD_HIP(pd::gemm_partial_bf16(s, false, dG + (size_t)(t + 1) * B * 4 * H, 4 * H, whh_t, B, H, 4 * H, st->ws,
-                                       st->ws_bytes, &splits));
-          rec = st->ws;
-        }
-        PD_HIP(pd::lstm_cell_backward(s, dh_out + (size_t)t * B * H, rec, splits, dc, gates + (size_t)t * B * 4 * H,
-                                      cbuf + (size_t)(t + 1) * B * H, cbuf + (size_t)t * B * H,
-                                      dG + (size_t)t * B * 4 * H, B, H));
+        if (t == L.T - 1)
+          PD_HIP(pd::lstm_cell_backward(s, dh_out + (size_t)t * B * H, nullptr, 0, dc, gates + (size_t)t * B * 4 * H,
+                                        cbuf + (size_t)(t + 1) * B * H, cbuf + (size_t)t * B * H,
+                                        dG + (size_t)t * B * 4 * H, B, H));
+        else
+          PD_HIP(pd::lstm_step_backward(s, dh_out + (size_t)t * B * H, dG + (size_t)(t + 1) * B * 4 * H, whh_t, dc,
+                                        gates + (size_t)t * B * 4 * H, cbuf + (size_t)(t + 1) * B * H,
+                                        cbuf + (size_t)t * B * H, dG + (size_t)t * B * 4 * H, B, H));
       }
     }
     char* out;
