@@ -12,12 +12,16 @@ Modules
                and the bf16 rounding points of the mixed-precision mode
   pipeline  -- stage state (version ring, stash, momentum), F / B / U, the
                pipeline run, and the flat-loop form of the staleness equation
+  partition -- the layer partitioner of Section 3.2: stage time, boundary cost,
+               the dynamic program over (layers, machines), NOAM
 
 Pins (tests/test_oracle_*.py): the paper's 4-stage worked example (Section 3.4),
 the closed-form version rule read off the staleness equation of Section 3.4,
 reduction to sequential minibatch SGD for one stage / one active minibatch
 (checked against torch autograd + torch.optim.SGD), finite differences for every
 layer's backward, the no-idle steady state under unit costs (Section 3.3), and a
-no-stashing negative control.  Start-up slot positions of the timeline figure
+no-stashing negative control; for the partitioner, exhaustive enumeration of
+every pipeline on small problems, closed-form special cases and a hand-worked
+example.  Start-up slot positions of the timeline figure
 (Figure "example pipeline") are parity unpinned: the figure is not available.
 """
