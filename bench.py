@@ -288,6 +288,72 @@ def bench_gemm_sweep(args, pd, gen, torch, np, dev):
     print(json.dumps(out))
 
 
+def bench_partition(args, pd, gen, torch, np, dev):
+    """The step before the pipeline: profile every layer of VGG16 (minibatch 64, the build's own kernels), then run
+    the partitioner for several worker counts and link bandwidths.  Prints the profile and the chosen stages."""
+    B, K, W = args.minibatch, min(args.steps, 20), min(args.warmup, 3)
+    hw = (64, 64) if args.small else (224, 224)
+    layers = gen.vgg16_full()
+    if args.small:
+        layers = [("linear", 2 * 2 * 512, L[2], L[3]) if (L[0] == "linear" and L[1] == 25088) else L for L in layers]
+    seed = gen.BASE_SEED + 6
+    params = gen.init_params(seed, "vgg16", layers)
+    stream = torch.cuda.Stream(device=dev)
+    cfg = pd.make_config(layers, in_flight_override=1, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=0.01,
+                         momentum=0.9, stream=stream.cuda_stream, in_hw=hw)
+    nbytes = pd.pd_stage_query_bytes(cfg)
+    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
+    pd.pd_stage_set_params(h, params)
+    x = torch.from_numpy(gen.normal(seed, "x", (B, hw[0], hw[1], 3))).to(dev).to(torch.bfloat16)
+    lab = torch.from_numpy(gen.labels(seed, "y", (B,), 1000)).to(dev)
+    mb = 0
+
+    def step():
+        nonlocal mb
+        pd.pd_forward(h, mb, x.data_ptr(), lab.data_ptr(), 0, 0)
+        pd.pd_backward(h, mb, 0, 0)
+        pd.pd_update(h)
+        mb += 1
+
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    pd.pd_stage_profile(h, True)
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / K
+    prof = pd.pd_stage_profile_read(h)
+    pd.pd_stage_profile(h, False)
+    pd.pd_stage_destroy(h)
+    compute = [L for L in layers if L[0] != "softmax_xent"]
+    T = [u["fwd_ms"] + u["bwd_ms"] + u["upd_ms"] for u in prof]
+    a = [u["act_bytes"] for u in prof]
+    w = [u["param_bytes"] for u in prof]
+    links = {"10 Gbit/s Ethernet": 1.25e6, "25 Gbit/s Ethernet": 3.125e6, "one xGMI link (153 GB/s)": 1.53e8}  # bytes per ms
+    parts = []
+    for name, bw in links.items():
+        for M in (4, 8, 16):
+            best, stages, noam = pd.pd_partition(T, a, w, M, bw)
+            parts.append({"link": name, "workers": M, "slowest_stage_ms": best, "noam": noam,
+                          "config": "-".join(str(r) for _, _, r in stages),
+                          "stages": [{"layers": [f, l], "replicas": r} for f, l, r in stages],
+                          "samples_per_s": B / (best * 1e-3)})
+    out = {"metric": "layer profile + partition (Section 3.2)", "unit": "ms", "n_gpus": 1, "steps": K, "warmup": W,
+           "value": sum(T), "ms_per_step": ms, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": ("REDUCED " if args.small else "") + f"VGG16 (13 conv, 5 pool, 3 Linear) on 3x{hw[0]}x{hw[1]} "
+                      f"images, minibatch {B}, one stage of depth 1 with the layer profiler on"},
+           "profile": [{"layer": compute[u["first_layer"]][0] + (f" {compute[u['first_layer']][1]}->{compute[u['first_layer']][2]}"
+                                                                 if compute[u["first_layer"]][0] != "maxpool2d" else ""),
+                        "T_ms": round(t, 4), "fwd_ms": round(u["fwd_ms"], 4), "bwd_ms": round(u["bwd_ms"], 4),
+                        "upd_ms": round(u["upd_ms"], 4), "a_bytes": u["act_bytes"], "w_bytes": u["param_bytes"]}
+                       for u, t in zip(prof, T)],
+           "partitions": parts}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -297,10 +363,11 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep"],
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
                          "s2vt (the two LSTM stages as a 2-stream pipeline), inception (four stages of branched "
-                         "convolution blocks as a 4-stream pipeline), gemm_sweep (the Linear kernels over row counts)")
+                         "convolution blocks as a 4-stream pipeline), gemm_sweep (the Linear kernels over row counts), "
+                         "partition (layer profile of all of VGG16 on the device, then the partitioner)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs all pipeline stages on ONE GPU; --gpus must be 1", file=sys.stderr)
@@ -325,6 +392,8 @@ def main():
         return bench_inception(args, pd, gen, torch, np, dev)
     if args.workload == "gemm_sweep":
         return bench_gemm_sweep(args, pd, gen, torch, np, dev)
+    if args.workload == "partition":
+        return bench_partition(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
     n_in, classes = layers[0][1], layers[-1][1]
     seed = gen.BASE_SEED + 1

@@ -256,6 +256,45 @@ int pd_update(pd_stage* st);
 int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_minibatches,
                     const void* inputs_dev, const int32_t* labels_dev, float* losses_dev);
 
+/* --- profiling and partitioning (Section 3.2) -----------------------------------------------
+ * The step before the pipeline runs: measure every layer on the device, then choose the stages.
+ *
+ * pd_stage_profile: enable != 0 clears earlier records and makes every pd_forward / pd_backward / pd_update
+ * of this stage drop a HIP event after each layer's kernels; 0 stops recording.  pd_stage_profile_read waits
+ * for the stream and reports one entry per profile UNIT in stage order: a compute layer outside any block of
+ * branches, or a whole block (a pipeline can only be cut between units).  first_layer / last_layer use the
+ * compute-layer numbering of pd_stage_debug_read.  fwd_ms, bwd_ms, upd_ms = mean time per recorded F, B, U
+ * (the time of a launch that updates several Linear layers at once is shared out by parameter count); the
+ * paper's T_l is their sum (its backward pass includes the weight gradient, which here is formed in
+ * pd_update).  act_bytes = a_l: bytes of the unit's output for one minibatch (also the size of the gradient
+ * that comes back); param_bytes = |w_l| as fp32.  Writes up to cap entries, the count to *n_out
+ * (PD_ENOMEM if cap is too small, n_out still set). */
+typedef struct {
+  int32_t first_layer, last_layer;
+  double fwd_ms, bwd_ms, upd_ms;
+  double act_bytes, param_bytes;
+} pd_layer_profile;
+int pd_stage_profile(pd_stage* st, int32_t enable);
+int pd_stage_profile_read(pd_stage* st, pd_layer_profile* out, size_t cap, size_t* n_out);
+
+/* pd_partition (pure host, no GPU touched): the dynamic program of Section 3.2 over n_layers profile units and
+ * n_machines workers.  t_layer[l] = T_l (any time unit), act_bytes[l] = a_l, param_bytes[l] = |w_l| (host
+ * arrays of n_layers doubles, all >= 0); bandwidth in bytes per that time unit, > 0.  A stage holding layers
+ * i..j replicated over m workers costs max(sum T_l, sum W_l^m) / m with W_l^m = 4 (m-1) |w_l| / (m bandwidth);
+ * a boundary after layer i costs 2 a_i / bandwidth; the pipeline's cost is its slowest stage or boundary, all
+ * n_machines workers are used.  Outputs (each may be NULL except stages_out when cap > 0): *slowest_out = the
+ * optimum A(N, M); stages_out[k] = {first_layer, last_layer (0-based, inclusive), replicas} in pipeline order,
+ * *n_stages_out their count; *noam_out = ceil(n_machines / replicas of the input stage), the number of
+ * minibatches to keep in flight.  Among partitions of equal cost the one found first wins (split points and
+ * replica counts of the last stage in increasing order).  PD_EINVAL on bad arguments; PD_ENOMEM if cap is too
+ * small (counts still set). */
+typedef struct {
+  int32_t first_layer, last_layer, replicas;
+} pd_stage_assign;
+int pd_partition(int32_t n_layers, int32_t n_machines, const double* t_layer, const double* act_bytes,
+                 const double* param_bytes, double bandwidth, double* slowest_out, pd_stage_assign* stages_out,
+                 size_t cap, size_t* n_stages_out, int32_t* noam_out);
+
 /* --- stand-alone kernels of the step, for measurement at other shapes ----------------------
  * The same GEMM kernels the stage uses, callable on caller buffers (bf16 data, fp32
  * accumulate), so that MFMA utilisation can be measured at any minibatch size.

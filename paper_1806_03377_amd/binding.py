@@ -42,6 +42,16 @@ class pd_layer_desc(C.Structure):
     _fields_ = [("kind", C.c_int32), ("p", C.c_int32 * 12)]
 
 
+class pd_layer_profile(C.Structure):
+    _fields_ = [("first_layer", C.c_int32), ("last_layer", C.c_int32), ("fwd_ms", C.c_double),
+                ("bwd_ms", C.c_double), ("upd_ms", C.c_double), ("act_bytes", C.c_double),
+                ("param_bytes", C.c_double)]
+
+
+class pd_stage_assign(C.Structure):
+    _fields_ = [("first_layer", C.c_int32), ("last_layer", C.c_int32), ("replicas", C.c_int32)]
+
+
 class pd_stage_config(C.Structure):
     _fields_ = [("stage_index", C.c_int32), ("num_stages", C.c_int32), ("noam", C.c_int32),
                 ("in_flight_override", C.c_int32), ("minibatch", C.c_int32), ("precision", C.c_int32),
@@ -73,6 +83,10 @@ _SIGS = {
     "pd_backward": [_vp, _i32, _vp, _vp],
     "pd_update": [_vp],
     "pd_pipeline_run": [C.POINTER(_vp), _i32, _i32, _vp, _vp, _vp],
+    "pd_stage_profile": [_vp, _i32],
+    "pd_stage_profile_read": [_vp, C.POINTER(pd_layer_profile), _sz, C.POINTER(_sz)],
+    "pd_partition": [_i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double,
+                     C.POINTER(C.c_double), C.POINTER(pd_stage_assign), _sz, C.POINTER(_sz), C.POINTER(_i32)],
     "pd_linear_fwd_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _sz],
     "pd_linear_dgrad_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _sz],
     "pd_linear_wgrad_update_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _f32],
@@ -319,6 +333,33 @@ def pd_pipeline_run(stages: Sequence[int], num_minibatches: int, inputs_dev: int
                     losses_dev: int = 0):
     arr = (_vp * len(stages))(*stages)
     _check(_lib.pd_pipeline_run(arr, len(stages), num_minibatches, inputs_dev, labels_dev, losses_dev or None))
+
+
+def pd_stage_profile(stage: int, enable: bool):
+    _check(_lib.pd_stage_profile(stage, 1 if enable else 0))
+
+
+def pd_stage_profile_read(stage: int):
+    """One dict per profile unit: first_layer, last_layer, fwd_ms, bwd_ms, upd_ms, act_bytes, param_bytes."""
+    n = _sz(0)
+    rc = _lib.pd_stage_profile_read(stage, None, 0, C.byref(n))
+    if rc != PD_ENOMEM:
+        _check(rc)
+    arr = (pd_layer_profile * max(1, n.value))()
+    _check(_lib.pd_stage_profile_read(stage, arr, n.value, C.byref(n)))
+    return [{name: getattr(arr[i], name) for name, _ in pd_layer_profile._fields_} for i in range(n.value)]
+
+
+def pd_partition(t_layer, act_bytes, param_bytes, n_machines: int, bandwidth: float):
+    """Returns (slowest stage time, [(first_layer, last_layer, replicas), ...], NOAM)."""
+    n = len(t_layer)
+    dbl = C.c_double * max(1, n)
+    t, a, w = dbl(*map(float, t_layer)), dbl(*map(float, act_bytes)), dbl(*map(float, param_bytes))
+    cap = max(1, min(n, int(n_machines)))
+    out = (pd_stage_assign * cap)()
+    best, ns, noam = C.c_double(0), _sz(0), _i32(0)
+    _check(_lib.pd_partition(n, n_machines, t, a, w, bandwidth, C.byref(best), out, cap, C.byref(ns), C.byref(noam)))
+    return best.value, [(out[k].first_layer, out[k].last_layer, out[k].replicas) for k in range(ns.value)], noam.value
 
 
 def pd_set_big_tile_threshold(min_tiles: int) -> int:

@@ -14,12 +14,14 @@
 #include <vector>
 
 #include "../../include/pd.h"
+#include "pd_error.h"
 #include "pd_kernels.h"
 
 namespace {
-
 thread_local std::string g_err;
+}
 
+namespace pd {
 int fail(int code, const char* fmt, ...) {
   char buf[512];
   va_list ap;
@@ -29,6 +31,11 @@ int fail(int code, const char* fmt, ...) {
   g_err = buf;
   return code;
 }
+}  // namespace pd
+
+namespace {
+using pd::fail;
+
 #define PD_HIP(expr)                                                                           \
   do {                                                                                         \
     hipError_t e_ = (expr);                                                                    \
@@ -179,6 +186,21 @@ struct pd_stage {
   std::vector<pd_op> trace;
   // events of pd_pipeline_run (grown on demand, reused)
   std::vector<hipEvent_t> ev_f, ev_b, ev_u;
+  // layer profiler (Section 3.2): while `profiling`, every op drops an event after each layer's kernels; the time
+  // between two consecutive marks belongs to the layer named by the later one (the stream runs kernels in order)
+  struct Mark { int phase, layer; hipEvent_t ev; };  // phase: -1 = start of an op, 0 F, 1 B, 2 U, 3 U of the batch
+  bool profiling = false;
+  std::vector<Mark> marks;
+  std::vector<hipEvent_t> mark_pool;
+  int prof_ops[3] = {0, 0, 0};
+  hipError_t mark(int phase, int layer) {
+    if (!profiling) return hipSuccess;
+    hipEvent_t e;
+    if (!mark_pool.empty()) { e = mark_pool.back(); mark_pool.pop_back(); }
+    else { const hipError_t rc = hipEventCreate(&e); if (rc != hipSuccess) return rc; }
+    marks.push_back({phase, layer, e});
+    return hipEventRecord(e, stream);
+  }
 
   char* ring_slot(int version) const { return ring + (size_t)(version % depth) * p_pad * esz; }
   char* in_slot(int mb) const { return in_ring + (size_t)(mb % in_depth) * in_bytes; }
@@ -550,8 +572,9 @@ int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena
 
 int pd_stage_destroy(pd_stage* st) {
   if (!st) return PD_OK;
-  for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u})
+  for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u, &st->mark_pool})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
+  for (const pd_stage::Mark& m : st->marks) (void)hipEventDestroy(m.ev);
   delete st;
   return PD_OK;
 }
@@ -819,7 +842,9 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
   char* slot = st->stash_slot(mb_id);
   const char* w = st->ring_slot(v);
   if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->lin.front().rows * st->lin.front().in * st->esz));
+  PD_HIP(st->mark(-1, 0));
   for (int li = 0; li < (int)st->lin.size(); ++li) {
+    if (li > 0) PD_HIP(st->mark(0, li - 1));
     const Layer& L = st->lin[li];
     char* y = st->out_of(slot, li);
     const char* a = L.src < 0 ? in : st->out_of(slot, L.src);
@@ -879,6 +904,8 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
   if (st->has_loss)
     PD_HIP(pd::softmax_xent(s, reinterpret_cast<const float*>(a), labels_dev, slot + st->dlogits_off, st->row_loss,
                             loss_dev, st->lin.back().rows, st->classes, st->bf16));
+  PD_HIP(st->mark(0, (int)st->lin.size() - 1));  // (the loss and the copy of the output count for the last layer)
+  if (st->profiling) ++st->prof_ops[0];
   st->in_flight.push_back({mb_id, v});
   st->last_fwd = mb_id;
   st->trace.push_back({PD_OP_F, mb_id, v, v % st->depth});
@@ -910,6 +937,7 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
     return b;
   };
   const char* cur;
+  PD_HIP(st->mark(-1, 0));
   if (st->has_loss) {
     cur = slot + st->dlogits_off;
   } else {
@@ -919,7 +947,10 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
     else PD_HIP(pd::copy_bytes(s, dy_dev, b, n * st->esz));
     cur = b;
   }
+  int prof_l = nl - 1;  // the layer whose kernels were enqueued since the last mark
   for (int l = nl - 1; l >= 0; --l) {
+    if (l < nl - 1) PD_HIP(st->mark(1, prof_l));
+    prof_l = l;
     const Layer& L = st->lin[l];
     if (L.kind == K_CONCAT) {
       // `cur` is dL/d(block output).  Split it into one contiguous tensor per branch, applying the ReLU mask of
@@ -1044,6 +1075,8 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
       cur = sum_out;
     }
   }
+  PD_HIP(st->mark(1, prof_l));
+  if (st->profiling) ++st->prof_ops[1];
   st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
   st->grad_pending = true;
   st->pending_mb = mb_id;
@@ -1061,6 +1094,7 @@ int pd_update(pd_stage* st) {
   const int nv = st->latest + 1;
   pd::WgradBatch batch;
   batch.count = 0; batch.M = st->B; batch.lr = st->lr; batch.mu = st->mu;
+  PD_HIP(st->mark(-1, 0));
   for (int l = 0; l < nl; ++l) {
     const Layer& L = st->lin[l];
     if (!L.n_w) continue;  // pooling, concatenation
@@ -1069,6 +1103,7 @@ int pd_update(pd_stage* st) {
       PD_HIP(pd::wgrad_reduce_update(s, reinterpret_cast<const float*>(st->part + L.part_off), L.splits, 0, L.n_w,
                                      (int)L.n_b, st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
                                      st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr, st->mu));
+      PD_HIP(st->mark(2, l));
       continue;
     }
     const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
@@ -1092,12 +1127,14 @@ int pd_update(pd_stage* st) {
         PD_HIP(pd::wgrad_reduce_update(s, part2, 1, 0, n_w2, 0, st->master + o2, st->mom + o2, ro + o2,
                                        nullptr, nullptr, nullptr, st->lr, st->mu));
       }
+      PD_HIP(st->mark(2, l));
     } else if (st->bf16) {
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
       auto flush_if_full = [&]() -> hipError_t {
         if (batch.count < pd::kMaxWgradLayers) return hipSuccess;
-        const hipError_t e = pd::linear_wgrad_update_bf16(s, batch);
+        hipError_t e = pd::linear_wgrad_update_bf16(s, batch);
         batch.count = 0;
+        if (e == hipSuccess) e = st->mark(3, -1);
         return e;
       };
       pd::WgradLayer& W = batch.layer[batch.count++];
@@ -1122,12 +1159,93 @@ int pd_update(pd_stage* st) {
       PD_HIP(pd::linear_wgrad_update_f32(s, reinterpret_cast<const float*>(dz), reinterpret_cast<const float*>(x),
                                          wi + L.w_off, wo + L.w_off, st->mom + L.w_off, wi + L.b_off, wo + L.b_off,
                                          st->mom + L.b_off, L.rows, L.out, L.in, st->lr, st->mu));
+      PD_HIP(st->mark(2, l));
     }
   }
-  if (batch.count) PD_HIP(pd::linear_wgrad_update_bf16(s, batch));  // all Linear layers of the stage in one launch
+  if (batch.count) {  // all Linear layers of the stage in one launch
+    PD_HIP(pd::linear_wgrad_update_bf16(s, batch));
+    PD_HIP(st->mark(3, -1));
+  }
+  if (st->profiling) ++st->prof_ops[2];
   st->latest = nv;
   st->grad_pending = false;
   st->trace.push_back({PD_OP_U, mb, nv, nv % st->depth});
+  return PD_OK;
+}
+
+// ---- layer profiler (Section 3.2, "Profiling the DNN model") ---------------------------------------------
+int pd_stage_profile(pd_stage* st, int32_t enable) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (enable) {
+    for (const pd_stage::Mark& m : st->marks) st->mark_pool.push_back(m.ev);
+    st->marks.clear();
+    st->prof_ops[0] = st->prof_ops[1] = st->prof_ops[2] = 0;
+  }
+  st->profiling = enable != 0;
+  return PD_OK;
+}
+
+int pd_stage_profile_read(pd_stage* st, pd_layer_profile* out, size_t cap, size_t* n_out) {
+  if (check_stage(st)) return PD_EINVAL;
+  const int nl = (int)st->lin.size();
+  // profile units: a layer outside any block is one unit; a block of branches (its branch layers and the
+  // concatenation that closes it) is one unit, because a pipeline can only be cut between units
+  std::vector<int> unit_of(nl, 0);
+  std::vector<pd_layer_profile> units;
+  for (int l = 0; l < nl; ++l) {
+    const Layer& L = st->lin[l];
+    const int closing = L.kind == K_CONCAT ? l : L.block;  // index of the K_CONCAT layer, -1 outside blocks
+    if (closing >= 0 && !units.empty() && units.back().last_layer == closing) {
+      unit_of[l] = (int)units.size() - 1;
+      continue;
+    }
+    pd_layer_profile u;
+    memset(&u, 0, sizeof u);
+    u.first_layer = l;
+    u.last_layer = closing >= 0 ? closing : l;
+    unit_of[l] = (int)units.size();
+    units.push_back(u);
+  }
+  for (int l = 0; l < nl; ++l) {
+    const Layer& L = st->lin[l];
+    pd_layer_profile& u = units[unit_of[l]];
+    u.param_bytes += 4.0 * (double)(L.n_w + L.n_b);  // fp32: what replicas of the stage would exchange
+    if (l == u.last_layer) {
+      const bool logits = st->has_loss && l == nl - 1;
+      u.act_bytes = (double)L.rows * L.out * (logits ? 4 : st->esz);
+    }
+  }
+  if (n_out) *n_out = units.size();
+  if (units.size() > cap) return fail(PD_ENOMEM, "profile has %zu units, capacity %zu", units.size(), cap);
+  if (!out) return fail(PD_EINVAL, "out is null");
+  PD_HIP(hipStreamSynchronize(st->stream));
+  // parameters updated by the one multi-layer launch: its time is shared out by parameter count (the launch
+  // streams master weights and momentum once, so its time is proportional to them)
+  double batch_params = 0;
+  for (const Layer& L : st->lin)
+    if (L.n_w && L.kind != K_CONV && st->bf16 && L.splits == 0) batch_params += (double)(L.n_w + L.n_b);
+  for (size_t i = 1; i < st->marks.size(); ++i) {
+    const pd_stage::Mark& m = st->marks[i];
+    if (m.phase < 0) continue;  // start of an op: the time since the previous mark is not this stage's work
+    float ms = 0.f;
+    PD_HIP(hipEventElapsedTime(&ms, st->marks[i - 1].ev, m.ev));
+    if (m.phase == 3) {
+      for (int l = 0; l < nl; ++l) {
+        const Layer& L = st->lin[l];
+        if (L.n_w && L.kind != K_CONV && st->bf16 && L.splits == 0)
+          units[unit_of[l]].upd_ms += ms * (double)(L.n_w + L.n_b) / batch_params;
+      }
+    } else {
+      pd_layer_profile& u = units[unit_of[m.layer]];
+      (m.phase == 0 ? u.fwd_ms : m.phase == 1 ? u.bwd_ms : u.upd_ms) += ms;
+    }
+  }
+  for (pd_layer_profile& u : units) {
+    if (st->prof_ops[0]) u.fwd_ms /= st->prof_ops[0];
+    if (st->prof_ops[1]) u.bwd_ms /= st->prof_ops[1];
+    if (st->prof_ops[2]) u.upd_ms /= st->prof_ops[2];
+  }
+  memcpy(out, units.data(), units.size() * sizeof(pd_layer_profile));
   return PD_OK;
 }
 

@@ -171,6 +171,17 @@ def config3_vgg_conv(widths=(64, 128, 256)):
             conv(b, c), conv(c, c), conv(c, c), ("maxpool2d", 2, 2)]
 
 
+def vgg16_full(classes: int = 1000):
+    """All of VGG16 as one layer list (13 convolutions, 5 poolings, 3 Linear layers, loss) on 3x224x224 images:
+    the model the layer profiler and the partitioner are run on."""
+    def conv(ci, co):
+        return ("conv2d", ci, co, 3, 3, 1, 1, 1, True)
+
+    pool = ("maxpool2d", 2, 2)
+    return (config3_vgg_conv() + [conv(256, 512), conv(512, 512), conv(512, 512), pool,
+                                  conv(512, 512), conv(512, 512), conv(512, 512), pool] + config2_vgg_fc(classes=classes))
+
+
 def config4_s2vt(input_size=4096, hidden=1000, vocab=30000, seq_len=80):
     """S2VT-shaped two-stage sequence model: stage 0 = LSTM(input -> hidden); stage 1 = LSTM(hidden -> hidden),
     vocabulary projection on every time step, softmax cross-entropy over all seq_len * minibatch tokens."""
