@@ -882,6 +882,7 @@ bool conv_is_smallk(const ConvGeom& g) { return g.kh * g.kw * g.Ci <= SK && g.Co
 int conv_wgrad_split_count(const ConvGeom& g) {
   const long long P = (long long)g.N * g.Ho * g.Wo;
   if (conv_is_smallk(g)) return wgrad_splits((P + 255) / 256, 1);
+  if (const int tr = conv_wgrad_tr_partials(g)) return tr;
   const int TC = (g.Co >= 128 && g.Ci >= 128) ? 128 : 64;
   const int tiles = ((g.Co + TC - 1) / TC) * ((g.Ci + TC - 1) / TC) * g.kh * g.kw;
   return wgrad_splits((P + 63) / 64, tiles);
@@ -922,6 +923,7 @@ hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t
     return hipGetLastError();
   }
   if ((g.Ci % 8) || (g.Co % 8)) return hipErrorInvalidValue;
+  if (conv_wgrad_tr_partials(g)) return conv_wgrad_tr_partial_bf16(s, dz, x, part, splits, g);
   const long long chunks = (P + 63) / 64;
   const int cps = (int)((chunks + splits - 1) / splits);
   if (g.Co >= 128 && g.Ci >= 128) {

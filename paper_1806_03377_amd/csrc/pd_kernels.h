@@ -92,6 +92,13 @@ hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf1
 int conv_wgrad_split_count(const ConvGeom& g);
 hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
                                    const ConvGeom& g);
+// The same partial sums for stride-1, size-preserving convolutions (conv_wgrad_tr_bf16.hip: all taps of a group of
+// filter rows in one workgroup, operands fetched with transposing LDS reads).  conv_wgrad_tr_partials returns the
+// number of partials that kernel writes for this geometry, or 0 if the geometry is not covered;
+// conv_wgrad_split_count / conv_wgrad_partial_bf16 above choose between the two kernels themselves.
+int conv_wgrad_tr_partials(const ConvGeom& g);
+hipError_t conv_wgrad_tr_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int partials,
+                                      const ConvGeom& g);
 // g = sum of the partials in split order; m <- mu*m + g; master <- master - lr*m; ring <- bf16(master).
 // Partial s starts at part + s*stride (stride 0 = n_w + n_b); n_b may be 0 to leave the bias alone.
 hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t stride, size_t n_w, int n_b,

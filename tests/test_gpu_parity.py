@@ -220,6 +220,15 @@ CONVS = [  # N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w
     (2, 17, 17, 16, 16, 7, 1, 1, 3, 0),     # 7x1
     (1, 40, 40, 8, 8, 3, 3, 1, 1, 1),       # many pixels, few channels
     (600, 1, 1, 136, 264, 1, 1, 1, 0, 0),   # a plain matrix product with many rows (256 x 256-tile wgrad)
+    # size-preserving stride-1 layers with >= 32 input channels: the all-taps-per-workgroup weight-gradient kernel
+    (2, 17, 17, 32, 40, 1, 7, 1, 0, 3),     # 1x7, <= 64 output channels (pixel halves as separate partials)
+    (2, 17, 17, 40, 72, 7, 1, 1, 3, 0),     # 7x1: filter rows in groups of 3, 3, 1
+    (2, 9, 9, 48, 64, 5, 5, 1, 2, 2),       # 5x5: one filter row per workgroup
+    (3, 8, 8, 64, 136, 1, 3, 1, 0, 1),      # 1x3, ragged output-channel tile
+    (3, 8, 8, 72, 48, 3, 1, 1, 1, 0),       # 3x1, ragged input-channel tile
+    (70, 4, 4, 32, 32, 1, 1, 1, 0, 0),      # images smaller than one 64-pixel stage
+    (4, 35, 35, 64, 96, 3, 3, 1, 1, 1),     # several pixel ranges per tile
+    (3, 20, 28, 160, 256, 3, 3, 1, 1, 1),   # several channel tiles on both sides
 ]
 
 
