@@ -612,18 +612,28 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(const bf16_t* __re
   if (do_bias && t < TC && co0 + t < g.Co) out[n_w + co0 + t] = bsum;
 }
 
-// g[e] = sum over splits of part[s][e] in split order; then m <- mu*m + g; w <- w - lr*m; ring <- bf16(w).
-// e < n_w addresses the weights, e >= n_w the bias.
+// g[e] = sum over splits of part[s][e]; then m <- mu*m + g; w <- w - lr*m; ring <- bf16(w).
+// e < n_w addresses the weights, e >= n_w the bias.  G adjacent lanes share one element: lane j adds the splits
+// j, j + G, j + 2G, ... in that order, then the G sums are combined pairwise (a fixed tree), so the result depends
+// only on (splits, G).  G = 1 is the plain sequential sum; larger G keeps the chip busy when a layer has few
+// parameters but many partial sums.
+template <int G>
 __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* __restrict__ part, int splits,
                                                                   size_t stride, size_t n_w, int n_b, float* __restrict__ master_w,
                                                                   float* __restrict__ mom_w, bf16_t* __restrict__ ring_w,
                                                                   float* __restrict__ master_b, float* __restrict__ mom_b,
                                                                   bf16_t* __restrict__ ring_b, float lr, float mu) {
-  const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t e = tid / G;
+  const int j = (int)(tid % G);
   const size_t n = n_w + n_b;
-  if (e >= n) return;
+  const bool live = e < n;  // (whole groups of G lanes are live or not: 256 % G == 0)
   float gsum = 0.f;
-  for (int s = 0; s < splits; ++s) gsum += part[(size_t)s * stride + e];
+  if (live)
+    for (int s = j; s < splits; s += G) gsum += part[(size_t)s * stride + e];
+#pragma unroll
+  for (int d = 1; d < G; d <<= 1) gsum += __shfl_xor(gsum, d, 64);
+  if (!live || j != 0) return;
   float* ms = e < n_w ? master_w + e : master_b + (e - n_w);
   float* mm = e < n_w ? mom_w + e : mom_b + (e - n_w);
   bf16_t* rr = e < n_w ? ring_w + e : ring_b + (e - n_w);
@@ -941,8 +951,23 @@ hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, siz
                                bf16_t* ring_b, float lr, float mu) {
   const size_t n = n_w + n_b;
   if (!stride) stride = n;
-  wgrad_reduce_update_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(part, splits, stride, n_w, n_b, master_w, mom_w,
-                                                                         ring_w, master_b, mom_b, ring_b, lr, mu);
+  // lanes per element: enough threads to fill the chip, never more than there are partial sums
+  int G = 1;
+  while (G < 64 && 2 * G <= splits && n * (size_t)(2 * G) <= ((size_t)1 << 19)) G *= 2;
+  const unsigned blocks = (unsigned)((n * G + 255) / 256);
+#define PD_REDUCE(GG)                                                                                              \
+  wgrad_reduce_update_kernel<GG><<<blocks, 256, 0, s>>>(part, splits, stride, n_w, n_b, master_w, mom_w, ring_w, \
+                                                        master_b, mom_b, ring_b, lr, mu)
+  switch (G) {
+    case 1: PD_REDUCE(1); break;
+    case 2: PD_REDUCE(2); break;
+    case 4: PD_REDUCE(4); break;
+    case 8: PD_REDUCE(8); break;
+    case 16: PD_REDUCE(16); break;
+    case 32: PD_REDUCE(32); break;
+    default: PD_REDUCE(64); break;
+  }
+#undef PD_REDUCE
   return hipGetLastError();
 }
 
