@@ -265,7 +265,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_zero16);
   const int kg = ((l & 3) ^ ((l >> 4) & 3)) * 8;  // the reduction offset (within a stage) this lane fetches
 
+  constexpr bool FAST = ALIGNED && !UP;  // every stage lies inside one tap and the input is read plainly
   int hi0[QA], wi0[QA], nbase[QA];
+  // FAST: per pixel, the element offset of tap (0, 0), channel kg, and one validity bit per tap
+  int aoff[QA];
+  uint32_t amask[QA];
 #pragma unroll
   for (int q = 0; q < QA; ++q) {
     const int p = p0 + (q * 4 + w) * 16 + (l >> 2);
@@ -281,6 +285,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
       nbase[q] = -1;
       hi0[q] = wi0[q] = 0;
     }
+    aoff[q] = nbase[q] + (hi0[q] * g.W + wi0[q]) * g.Ci + kg;
+    amask[q] = 0;
+    if (FAST && nbase[q] >= 0)
+      for (int ta = 0; ta < g.kh; ++ta)
+        for (int tb = 0; tb < g.kw; ++tb)
+          if ((unsigned)(hi0[q] + ta) < (unsigned)g.H && (unsigned)(wi0[q] + tb) < (unsigned)g.W)
+            amask[q] |= 1u << (ta * g.kw + tb);
   }
   int wrow[QB];  // element offset of this lane's filter row, or -1
 #pragma unroll
@@ -288,8 +299,36 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
     const int co = co0 + (q * 4 + w) * 16 + (l >> 2);
     wrow[q] = co < g.Co ? co * K : -1;
   }
+  // FAST: the tap and channel range of the stage being loaded, kept in scalars and advanced once per stage
+  int l_kk = 0, l_tap = 0, l_ci = 0, l_ta = 0, l_tb = 0, l_off = 0;
+  auto advance_stage = [&]() {
+    l_kk += DK;
+    l_ci += DK;
+    if (l_ci >= g.Ci) {
+      l_ci = 0;
+      ++l_tap;
+      if (++l_tb == g.kw) {
+        l_tb = 0;
+        ++l_ta;
+      }
+    }
+    l_off = (l_ta * g.W + l_tb) * g.Ci + l_ci;
+  };
   // q-th load of the stage whose reduction range starts at kk (A loads first)
   auto load1 = [&](int q, char* stage, int kk) {
+    if (FAST) {
+      if (q < QA) {
+        const bool ok = l_kk < K && ((amask[q] >> l_tap) & 1u);  // past the end of the reduction: zeros
+        const bf16_t* cand = X + (aoff[q] + l_off);
+        dma16(ok ? cand : zero, stage + (q * 4 + w) * 1024);
+      } else {
+        const int qb = q - QA;
+        const bool ok = l_kk < K && wrow[qb] >= 0;
+        const bf16_t* cand = Wg + (wrow[qb] + l_kk + kg);
+        dma16(ok ? cand : zero, stage + ATILE + (qb * 4 + w) * 1024);
+      }
+      return;
+    }
     const int k = kk + kg;
     const bf16_t* src = zero;
     if (q < QA) {
@@ -339,9 +378,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
   auto ldf = [&](const char* stage, int o, int ks) { return *reinterpret_cast<const uint4*>(stage + (o ^ (ks << 5))); };
 
 #pragma unroll
-  for (int d = 0; d < 2; ++d)
+  for (int d = 0; d < 2; ++d) {
 #pragma unroll
     for (int q = 0; q < LPS; ++q) load1(q, smem + d * STAGE, d * DK);
+    advance_stage();
+  }
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");  // stage 0 has landed
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
@@ -382,6 +423,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
         }
       }
     }
+    advance_stage();
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");  // stage st+1 has landed; st+2 may be in flight
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -430,7 +472,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
 
 template <int BN>
 void launch_dma(hipStream_t s, dim3 grid, const bf16_t* x, const bf16_t* w, const ConvGeom& g, const ConvEpilogue& ep) {
-  const bool up = g.up > 1, aligned = (g.Ci % DK) == 0;
+  const bool up = g.up > 1, aligned = (g.Ci % DK) == 0 && g.kh * g.kw <= 32;
   if (up) {
     if (aligned) conv_dma_kernel<BN, true, true><<<grid, kThreads, 0, s>>>(x, w, g, ep);
     else conv_dma_kernel<BN, true, false><<<grid, kThreads, 0, s>>>(x, w, g, ep);
