@@ -7,8 +7,8 @@
 //                            are read "sideways" (reduction index = pixel), so 2x8 blocks are transposed on the
 //                            way into LDS; the pixel range is split over workgroups, partial sums go to memory
 //   wgrad_reduce_update      sums the partials in split order and applies the momentum-SGD update
-//   conv_smallk_*            first layer of an image network (kh*kw*Ci <= 32, e.g. 3x3x3): the 27 inputs of an
-//                            output pixel are gathered into one 32-wide reduction row
+//   (conv_smallk_bf16.hip)   first layer of an image network (kh*kw*Ci <= 32, e.g. 3x3x3)
+//   (conv_wgrad_tr_bf16.hip) weight gradient of stride-1, size-preserving layers
 //   maxpool2x2_*             2x2/stride-2 max-pooling; backward sends the gradient to the first maximum in
 //                            row-major window order and applies the ReLU mask of the layer below
 #include "bf16_util.h"
@@ -687,167 +687,6 @@ __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* _
 }
 
 // ------------------------------------------------------------------------------------------------
-// convolutions with a tiny reduction (kh*kw*Ci <= 32): one 32-wide reduction row per output pixel.
-// Forward: 256 pixels per workgroup, all Co <= 64 channels.
-// ------------------------------------------------------------------------------------------------
-constexpr int SK = 32, SLD = SK + 8;
-
-__device__ __forceinline__ void gather_pixel_row(const bf16_t* __restrict__ X, const ConvGeom& g, long long p,
-                                                 long long P, bf16_t* row /* SK entries in LDS, stride 1 */) {
-  const int K = g.kh * g.kw * g.Ci;
-  int ho = 0, wo = 0;
-  long long nb = 0;
-  const bool live = p < P;
-  if (live) {
-    wo = (int)(p % g.Wo);
-    const long long q = p / g.Wo;
-    ho = (int)(q % g.Ho);
-    nb = (q / g.Ho) * (long long)g.H * g.W * g.Ci;
-  }
-  int k = 0;
-  for (int a = 0; a < g.kh; ++a) {
-    const int hi = ho * g.stride - g.ph + a;
-    for (int b = 0; b < g.kw; ++b) {
-      const int wi = wo * g.stride - g.pw + b;
-      const bool ok = live && hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
-      const bf16_t* src = X + nb + ((long long)hi * g.W + wi) * g.Ci;
-      for (int c = 0; c < g.Ci; ++c, ++k) row[k] = ok ? src[c] : (bf16_t)0;
-    }
-  }
-  for (; k < SK; ++k) row[k] = 0;
-  (void)K;
-}
-
-__global__ __launch_bounds__(kThreads) void conv_smallk_fwd_kernel(const bf16_t* __restrict__ X,
-                                                                   const bf16_t* __restrict__ Wg, ConvGeom g,
-                                                                   ConvEpilogue ep) {
-  __shared__ __attribute__((aligned(16))) bf16_t As[256 * SLD];
-  __shared__ __attribute__((aligned(16))) bf16_t Bs[64 * SLD];
-  const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const long long P = (long long)g.N * g.Ho * g.Wo;
-  const long long p0 = (long long)blockIdx.x * 256;
-  const int K = g.kh * g.kw * g.Ci;
-  gather_pixel_row(X, g, p0 + t, P, &As[t * SLD]);
-  for (int e = t; e < 64 * SK; e += kThreads) {
-    const int co = e / SK, k = e % SK;
-    Bs[co * SLD + k] = (co < g.Co && k < K) ? Wg[(size_t)co * K + k] : (bf16_t)0;
-  }
-  __syncthreads();
-  f32x16 acc[2][2] = {{f32x16{0}, f32x16{0}}, {f32x16{0}, f32x16{0}}};
-#pragma unroll
-  for (int ks = 0; ks < SK / 16; ++ks) {
-    const int kk = ks * 16 + (l >> 5) * 8;
-    uint4 a[2], b[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const uint4*>(&As[(64 * w + 32 * i + (l & 31)) * SLD + kk]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const uint4*>(&Bs[(32 * j + (l & 31)) * SLD + kk]);
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[j]), acc[i][j], 0, 0, 0);
-  }
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int c = 32 * j + (l & 31);
-    if (c >= g.Co) continue;
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const long long p = p0 + 64 * w + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-        if (p < P) store_out(ep, acc[i][j][r], (size_t)p * g.Co + c, c);
-      }
-  }
-}
-
-// Weight gradient of the tiny-reduction convolution.  grid.x = splits; each workgroup walks chunks of 256
-// pixels; wave w reduces pixels 64w..64w+63 of every chunk; the four waves' sums are added in wave order.
-// part[split][e] with e = co*K + k (K = kh*kw*Ci) for the weights and n_w + co for the bias.
-__global__ __launch_bounds__(kThreads) void conv_smallk_wgrad_kernel(const bf16_t* __restrict__ dZ,
-                                                                     const bf16_t* __restrict__ X,
-                                                                     float* __restrict__ part, ConvGeom g,
-                                                                     int chunks_per_split) {
-  __shared__ __attribute__((aligned(16))) bf16_t Arow[256 * SLD];   // gathered inputs, [pixel][k]
-  __shared__ __attribute__((aligned(16))) uint32_t Zt[4][64 * 32];  // per wave: [co][64 pixels], swizzled
-  __shared__ __attribute__((aligned(16))) uint32_t At[4][32 * 32];  // per wave: [k][64 pixels], swizzled
-  __shared__ float red[4][64 * 33];
-  __shared__ float bred[4][64];
-  const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const long long P = (long long)g.N * g.Ho * g.Wo;
-  const int K = g.kh * g.kw * g.Ci;
-  const long long nchunks_total = (P + 255) / 256;
-  const long long chunk0 = (long long)blockIdx.x * chunks_per_split;
-  long long chunk1 = chunk0 + chunks_per_split;
-  if (chunk1 > nchunks_total) chunk1 = nchunks_total;
-  f32x16 acc[2] = {f32x16{0}, f32x16{0}};  // [co block][k 0..31]
-  float bsum = 0.f;
-  for (long long ch = chunk0; ch < chunk1; ++ch) {
-    const long long p0 = ch * 256;
-    gather_pixel_row(X, g, p0 + t, P, &Arow[t * SLD]);
-    // dz of this wave's 64 pixels, transposed: 32 pixel pairs x 8 channel chunks = 256 blocks, 4 per lane
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int b = l + 64 * i, cc = b & 7, pair = b >> 3;
-      const long long p = p0 + 64 * w + 2 * pair;
-      const int co = 8 * cc;
-      const uint4 z0 = (p < P && co < g.Co) ? ldg16(dZ + (size_t)p * g.Co + co) : zero16();
-      const uint4 z1 = (p + 1 < P && co < g.Co) ? ldg16(dZ + (size_t)(p + 1) * g.Co + co) : zero16();
-      store_transposed_pair<8>(Zt[w], 8 * cc, pair, z0, z1);
-    }
-    __syncthreads();
-    // gathered rows of this wave's pixels, transposed: At[k][pixel]
-    for (int e = l; e < 32 * 32; e += 64) {
-      const int k = e >> 5, pair = e & 31;
-      const uint32_t lo = Arow[(64 * w + 2 * pair) * SLD + k], hi = Arow[(64 * w + 2 * pair + 1) * SLD + k];
-      At[w][k * 32 + swz<8>(k, pair >> 2) * 4 + (pair & 3)] = lo | (hi << 16);
-    }
-    __syncthreads();
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      const int grp = 2 * ks + (l >> 5);
-      const uint4 b = load_swizzled_frag<8>(At[w], (l & 31), grp);
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const uint4 a = load_swizzled_frag<8>(Zt[w], 32 * i + (l & 31), grp);
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a), frag(b), acc[i], 0, 0, 0);
-      }
-    }
-    {  // bias: lane = channel, this wave's 64 pixels in order
-#pragma unroll
-      for (int grp = 0; grp < 8; ++grp) {
-        const uint4 v = load_swizzled_frag<8>(Zt[w], l, grp);
-        const uint32_t ww[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          bsum += bf2f((uint16_t)(ww[q] & 0xffffu));
-          bsum += bf2f((uint16_t)(ww[q] >> 16));
-        }
-      }
-    }
-    __syncthreads();
-  }
-  // cross-wave reduction in wave order
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int co = 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-      red[w][co * 33 + (l & 31)] = acc[i][r];
-    }
-  bred[w][l] = bsum;
-  __syncthreads();
-  const size_t n_w = (size_t)g.Co * K;
-  float* out = part + (size_t)blockIdx.x * (n_w + g.Co);
-  for (int e = t; e < 64 * 32; e += kThreads) {
-    const int co = e >> 5, k = e & 31;
-    if (co < g.Co && k < K) out[(size_t)co * K + k] = ((red[0][co * 33 + k] + red[1][co * 33 + k]) + red[2][co * 33 + k]) + red[3][co * 33 + k];
-  }
-  if (t < 64 && t < g.Co) out[n_w + t] = ((bred[0][t] + bred[1][t]) + bred[2][t]) + bred[3][t];
-}
-
-// ------------------------------------------------------------------------------------------------
 // 2x2 / stride-2 max pooling over NHWC, 8 channels (16 bytes) per thread.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void maxpool2x2_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
@@ -929,7 +768,6 @@ int wgrad_splits(long long chunks, int tiles) {
 
 }  // namespace
 
-bool conv_is_smallk(const ConvGeom& g) { return g.kh * g.kw * g.Ci <= SK && g.Co <= 64; }
 
 int conv_wgrad_split_count(const ConvGeom& g) {
   const long long P = (long long)g.N * g.Ho * g.Wo;
@@ -943,12 +781,9 @@ int conv_wgrad_split_count(const ConvGeom& g) {
 hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g,
                              const ConvEpilogue& ep) {
   const long long P = (long long)g.N * g.Ho * g.Wo;
-  if (conv_is_smallk(g)) {
-    conv_smallk_fwd_kernel<<<(unsigned)((P + 255) / 256), kThreads, 0, s>>>(x, w, g, ep);
-  } else {
-    return launch_igemm(s, x, w, g, ep);
-  }
-  return hipGetLastError();
+  (void)P;
+  if (conv_is_smallk(g)) return conv_smallk_forward_bf16(s, x, w, g, ep);
+  return launch_igemm(s, x, w, g, ep);
 }
 
 hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf16_t* wt_scratch, const ConvGeom& g,
@@ -969,11 +804,7 @@ hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf1
 hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
                                    const ConvGeom& g) {
   const long long P = (long long)g.N * g.Ho * g.Wo;
-  if (conv_is_smallk(g)) {
-    const long long chunks = (P + 255) / 256;
-    conv_smallk_wgrad_kernel<<<splits, kThreads, 0, s>>>(dz, x, part, g, (int)((chunks + splits - 1) / splits));
-    return hipGetLastError();
-  }
+  if (conv_is_smallk(g)) return conv_smallk_wgrad_partial_bf16(s, dz, x, part, splits, g);
   if ((g.Ci % 8) || (g.Co % 8)) return hipErrorInvalidValue;
   if (conv_wgrad_tr_partials(g)) return conv_wgrad_tr_partial_bf16(s, dz, x, part, splits, g);
   const long long chunks = (P + 63) / 64;

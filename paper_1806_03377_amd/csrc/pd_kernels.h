@@ -80,6 +80,11 @@ struct ConvEpilogue {
 };
 // kh*kw*Ci <= 32 and Co <= 64 (first layer of an image network): handled by the gather kernels
 bool conv_is_smallk(const ConvGeom& g);
+// The two kernels of that case (conv_smallk_bf16.hip); conv_forward_bf16 / conv_wgrad_partial_bf16 dispatch to them.
+hipError_t conv_smallk_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g,
+                                    const ConvEpilogue& ep);
+hipError_t conv_smallk_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
+                                          const ConvGeom& g);
 // y = act(conv(x, w) + b); w[Co][kh][kw][Ci].  Needs Ci % 8 == 0 unless conv_is_smallk.
 hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g,
                              const ConvEpilogue& ep);
