@@ -69,13 +69,25 @@ __global__ __launch_bounds__(256) void lstm_cell_bwd_kernel(const bf16_t* __rest
 // memory latency, not by bandwidth or flops.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  The recurrent weights are re-read at every
+// time step, so the tiles are renumbered such that an XCD always works on the same contiguous range of hidden
+// units (all row groups of a unit group together): its share of the weights (1/8) then stays in its L2 from
+// step to step instead of every XCD streaming half of the matrix through a cache it does not fit in.
+__device__ __forceinline__ void xcd_tile(int n_row_groups, int& unit_group, int& row_group) {
+  const int total = gridDim.x, per = total >> 3;
+  int id = blockIdx.x;
+  if (id < per * 8) id = (id & 7) * per + (id >> 3);
+  unit_group = id / n_row_groups;
+  row_group = id - unit_group * n_row_groups;
+}
+
 // acc += A[row0 + (l & 15)][k0..k1) * brow[k0..k1)^T for one wave; k0, k1 multiples of 8.
+template <int STEPS>
 __device__ __forceinline__ void wave_skinny_gemm16(const bf16_t* __restrict__ arow /* this lane's A row or null */,
                                                    const bf16_t* __restrict__ brow /* this lane's B row or null */,
                                                    int k0, int k1, int l, f32x4& acc) {
-  // eight reduction steps at a time: all their fragment loads are issued before the first MFMA, so the wave pays
+  // STEPS reduction steps at a time: all their fragment loads are issued before the first MFMA, so the wave pays
   // the memory latency once per batch instead of once per step
-  constexpr int STEPS = 8;
   for (int kb = k0; kb < k1; kb += 32 * STEPS) {
     uint4 a[STEPS], b[STEPS];
 #pragma unroll
@@ -92,14 +104,16 @@ __device__ __forceinline__ void wave_skinny_gemm16(const bf16_t* __restrict__ ar
 }
 
 // Forward: a workgroup owns 4 hidden units (their 4 x 4 = 16 gate columns) for 16 minibatch rows; grid =
-// (ceil(H / 4), ceil(B / 16)); 4 waves split the reduction over H.
+// ceil(H / 4) * ceil(B / 16) workgroups (see xcd_tile); 4 waves split the reduction over H.
 __global__ __launch_bounds__(256) void lstm_step_fwd_kernel(float* __restrict__ gates, const bf16_t* __restrict__ h_prev,
                                                             const bf16_t* __restrict__ whh,
                                                             const float* __restrict__ c_prev, float* __restrict__ c,
                                                             bf16_t* __restrict__ h, int B, int H) {
   __shared__ float red[4][16][17];
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int u0 = blockIdx.x * 4, r0 = blockIdx.y * 16;
+  int ug, rg;
+  xcd_tile((B + 15) / 16, ug, rg);
+  const int u0 = ug * 4, r0 = rg * 16;
   const int kq = ((H + 127) / 128) * 32;  // reduction elements per wave (multiple of 32)
   const int k0 = w * kq, k1 = (k0 + kq) < H ? (k0 + kq) : H;
   const int cl = l & 15, unit = u0 + (cl & 3);
@@ -115,7 +129,7 @@ __global__ __launch_bounds__(256) void lstm_step_fwd_kernel(float* __restrict__ 
     if (c_prev) cprev = c_prev[(size_t)(r0 + erow) * H + u0 + euu];
   }
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (k0 < k1) wave_skinny_gemm16(arow, brow, k0, k1, l, acc);
+  if (k0 < k1) wave_skinny_gemm16<8>(arow, brow, k0, k1, l, acc);
 #pragma unroll
   for (int r = 0; r < 4; ++r) red[w][4 * (l >> 4) + r][cl] = acc[r];
   __syncthreads();
@@ -141,7 +155,7 @@ __global__ __launch_bounds__(256) void lstm_step_fwd_kernel(float* __restrict__ 
 }
 
 // Backward: dh = dh_out + da_next * W_hh with W_hh^T stored [H][4H]; a workgroup owns 16 hidden units for 16
-// minibatch rows; grid = (ceil(H / 16), ceil(B / 16)); 8 waves split the reduction over 4H.
+// minibatch rows; grid = ceil(H / 16) * ceil(B / 16) workgroups; 8 waves split the reduction over 4H.
 __global__ __launch_bounds__(512) void lstm_step_bwd_kernel(const bf16_t* __restrict__ dh_out,
                                                             const bf16_t* __restrict__ da_next,
                                                             const bf16_t* __restrict__ whh_t, float* __restrict__ dc,
@@ -150,7 +164,9 @@ __global__ __launch_bounds__(512) void lstm_step_bwd_kernel(const bf16_t* __rest
                                                             int B, int H) {
   __shared__ float red[8][16][17];
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
-  const int j0 = blockIdx.x * 16, r0 = blockIdx.y * 16;
+  int ug, rg;
+  xcd_tile((B + 15) / 16, ug, rg);
+  const int j0 = ug * 16, r0 = rg * 16;
   const int K = 4 * H;
   const int kq = ((K + 255) / 256) * 32;
   const int k0 = w * kq, k1 = (k0 + kq) < K ? (k0 + kq) : K;
@@ -169,7 +185,7 @@ __global__ __launch_bounds__(512) void lstm_step_bwd_kernel(const bf16_t* __rest
     if (dh_out) dho = bf2f(dh_out[idx]);
   }
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (k0 < k1) wave_skinny_gemm16(arow, brow, k0, k1, l, acc);
+  if (k0 < k1) wave_skinny_gemm16<16>(arow, brow, k0, k1, l, acc);  // 4H / 8 waves = 16 steps: one batch
 #pragma unroll
   for (int r = 0; r < 4; ++r) red[w][4 * (l >> 4) + r][cl] = acc[r];
   __syncthreads();
@@ -212,15 +228,15 @@ hipError_t lstm_cell_backward(hipStream_t s, const bf16_t* dh_out, const float* 
 hipError_t lstm_step_forward(hipStream_t s, float* gates, const bf16_t* h_prev, const bf16_t* whh, const float* c_prev,
                              float* c, bf16_t* h, int B, int H) {
   if ((H % 8) || !h_prev) return hipErrorInvalidValue;
-  lstm_step_fwd_kernel<<<dim3((H + 3) / 4, (B + 15) / 16), 256, 0, s>>>(gates, h_prev, whh, c_prev, c, h, B, H);
+  lstm_step_fwd_kernel<<<((H + 3) / 4) * ((B + 15) / 16), 256, 0, s>>>(gates, h_prev, whh, c_prev, c, h, B, H);
   return hipGetLastError();
 }
 
 hipError_t lstm_step_backward(hipStream_t s, const bf16_t* dh_out, const bf16_t* da_next, const bf16_t* whh_t, float* dc,
                               const float* gates, const float* c, const float* c_prev, bf16_t* da, int B, int H) {
   if ((H % 8) || !da_next) return hipErrorInvalidValue;
-  lstm_step_bwd_kernel<<<dim3((H + 15) / 16, (B + 15) / 16), 512, 0, s>>>(dh_out, da_next, whh_t, dc, gates, c, c_prev,
-                                                                        da, B, H);
+  lstm_step_bwd_kernel<<<((H + 15) / 16) * ((B + 15) / 16), 512, 0, s>>>(dh_out, da_next, whh_t, dc, gates, c, c_prev,
+                                                                       da, B, H);
   return hipGetLastError();
 }
 
