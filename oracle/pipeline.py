@@ -174,9 +174,10 @@ def _out_quantiser(layers, li, q):
 
 class Stage:
     def __init__(self, layers, params_fp32, depth: int, mode: str = "f32",
-                 lr: float = 0.01, momentum: float = 0.9, stashing: bool = True):
+                 lr: float = 0.01, momentum: float = 0.9, stashing: bool = True, ring_depth: int = 0):
         self.layers = list(layers)
         self.depth = int(depth)
+        self.ring = int(ring_depth) if ring_depth else self.depth   # versions kept (vertical sync: the input stage's)
         self.mode = mode
         self.q = L.quantiser(mode)
         self.lr, self.mu = float(lr), float(momentum)
@@ -193,10 +194,14 @@ class Stage:
                                               # ("acts"), the incoming gradient ("dy") and the result ("dx")
 
     # -- F ---------------------------------------------------------------------
-    def forward(self, mb: int, x, labels=None):
+    def forward(self, mb: int, x, labels=None, version: Optional[int] = None):
         if len(self.stash) >= self.depth:
             raise RuntimeError("more minibatches in flight than the stage's depth")
-        v = self.latest                                           # latest version available
+        # default semantics: the latest version available; vertical sync (Section 3.4): the version the
+        # minibatch was tagged with at the input stage, which this stage must still hold
+        v = self.latest if version is None else version
+        if not (self.latest - self.ring < v <= self.latest):
+            raise RuntimeError("requested weight version is not held by the stage")
         P = _split_params(self.layers, self.versions[v])
         acts = [self.q(x)]
         loss, probs = None, None
@@ -220,7 +225,7 @@ class Stage:
                 k += 1
             self.log[mb] = dict(version=v, acts=acts, loss=loss, flat=flat)
         self.max_in_flight = max(self.max_in_flight, len(self.stash))
-        self.trace.append(Op(OP_F, mb, v, v % self.depth))
+        self.trace.append(Op(OP_F, mb, v, v % self.ring))
         return acts[-1], loss
 
     # -- B ---------------------------------------------------------------------
@@ -248,7 +253,7 @@ class Stage:
                 d = dx
                 k -= 1
         self.grad = g
-        self.trace.append(Op(OP_B, mb, v, v % self.depth))
+        self.trace.append(Op(OP_B, mb, v, v % self.ring))
         if self.log is not None:
             self.log[mb]["dx"] = d
         return d
@@ -262,7 +267,7 @@ class Stage:
         self.grad = None
         self.latest += 1
         self.versions.append(self.q(self.master))
-        self.trace.append(Op(OP_U, mb, self.latest, self.latest % self.depth))
+        self.trace.append(Op(OP_U, mb, self.latest, self.latest % self.ring))
 
     def live_versions(self):
         """Versions some in-flight minibatch still needs, plus the latest."""
@@ -272,7 +277,8 @@ class Stage:
 def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels, noam_: int,
                  mode: str = "f32", lr: float = 0.01, momentum: float = 0.9,
                  stashing: bool = True, depth_override: int = 0, keep_log: bool = False,
-                 out_grads=None, order: Optional[list] = None, input_grad: bool = False):
+                 out_grads=None, order: Optional[list] = None, input_grad: bool = False,
+                 vertical_sync: bool = False):
     """All stages, each following its own static op list, run as soon as their data exists.
 
     inputs[i] / labels[i] belong to minibatch i.  Returns (stages, losses).  Any
@@ -283,16 +289,20 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
     does not end in the loss (a stage or sub-pipeline studied on its own).  ``order``,
     if a list, receives the (stage, Op) pairs in the order they were executed.
     ``input_grad``: also form dL/d(input) of stage 0 (only visible through the log).
+    ``vertical_sync`` (Section 3.4): the version the input stage's forward read travels with the
+    minibatch, and every later stage uses that version of its own weights instead of its latest.
     """
     S, M = len(stage_layers), len(inputs)
     depths = [depth_override or in_flight_depth(S, noam_, s) for s in range(S)]
-    stages = [Stage(stage_layers[s], stage_params[s], depths[s], mode, lr, momentum, stashing)
+    stages = [Stage(stage_layers[s], stage_params[s], depths[s], mode, lr, momentum, stashing,
+                    ring_depth=depths[0] if vertical_sync else 0)
               for s in range(S)]
     if keep_log:
         for st in stages:
             st.log = {}
-    lists = [schedule_1f1b(S, noam_, M, s, depth_override) for s in range(S)]
+    lists = [schedule_1f1b(S, noam_, M, s, depth_override, vertical_sync) for s in range(S)]
     pos = [0] * S
+    tag = {}     # vertical sync: mb -> version read by the input stage's forward, carried with the activation
     act = {}     # (mb, producing stage) -> activation for the next stage
     grad = {}    # (mb, producing stage) -> gradient for the previous stage
     losses: List[Optional[float]] = [None] * M
@@ -307,7 +317,10 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                     if s > 0 and (op.mb, s - 1) not in act:
                         break
                     x = inputs[op.mb] if s == 0 else act.pop((op.mb, s - 1))
-                    y, loss = st.forward(op.mb, x, labels[op.mb] if (s == S - 1 and labels is not None) else None)
+                    y, loss = st.forward(op.mb, x, labels[op.mb] if (s == S - 1 and labels is not None) else None,
+                                         version=tag[op.mb] if (vertical_sync and s > 0) else None)
+                    if s == 0:
+                        tag[op.mb] = st.trace[-1].version
                     if s == S - 1:
                         losses[op.mb] = loss
                     else:

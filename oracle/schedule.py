@@ -39,7 +39,7 @@ def in_flight_depth(num_stages: int, noam_: int, stage: int) -> int:
 
 
 def schedule_1f1b(num_stages: int, noam_: int, num_minibatches: int, stage: int,
-                  depth_override: int = 0) -> List[Op]:
+                  depth_override: int = 0, vertical_sync: bool = False) -> List[Op]:
     """The static op list of one stage, built by walking the policy of Section 3.3.
 
     Start-up: forwards until ``depth`` minibatches are in flight.  Then the stage
@@ -48,9 +48,23 @@ def schedule_1f1b(num_stages: int, noam_: int, num_minibatches: int, stage: int,
     the end of the stream the remaining backwards drain in arrival order.
     Versions are produced by carrying the stage's ``latest`` counter through the
     walk, as the runtime would, not from a formula.
+
+    ``vertical_sync`` (Section 3.4): a minibatch is tagged with the version the INPUT
+    stage's forward read, and every stage uses that version of its own weights for
+    the minibatch's forward and backward pass.  The op order is unchanged; only the
+    versions of F and B differ, and a stage then has to keep as many versions as
+    the input stage (its ring has the input stage's depth, which sets ``slot``).
     """
     M = num_minibatches
     depth = depth_override if depth_override > 0 else in_flight_depth(num_stages, noam_, stage)
+    if vertical_sync:
+        ring = depth_override if depth_override > 0 else in_flight_depth(num_stages, noam_, 0)
+        tags = {o.mb: o.version for o in schedule_1f1b(num_stages, noam_, M, 0, depth_override) if o.kind == OP_F}
+        out = []
+        for o in schedule_1f1b(num_stages, noam_, M, stage, depth_override):
+            v = o.version if o.kind == OP_U else tags[o.mb]
+            out.append(Op(o.kind, o.mb, v, v % ring))
+        return out
     ops: List[Op] = []
     latest = 0
     stashed = {}          # mb -> version its forward used

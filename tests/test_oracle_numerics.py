@@ -252,3 +252,70 @@ def test_update_applies_to_latest_not_stashed():
     m2 = 0.5 * m1 + g1; w2 = w1 - 0.1 * m2
     assert np.allclose(st.master, w2, rtol=1e-14)
     assert [o.version for o in st.trace if o.kind in (OP_F, OP_B)] == [0, 0, 0, 0]
+
+
+# ---- vertical sync (Section 3.4): one version per minibatch across all stages --------------------
+
+@pytest.mark.parametrize("S,NOAM", [(4, 4), (3, 3), (4, 2), (2, 2), (3, 1)])
+def test_vertical_sync_equals_its_staleness_equation(S, NOAM):
+    # with vertical sync the update uses w^(t-n+1) on EVERY stage: the flat loops with one common delay
+    sl = _mlp(stages=S)
+    params = _params(sl)
+    M = 14
+    xs, ys = _data(M, 6, 12, 5)
+    common = [in_flight_depth(S, NOAM, 0)] * S
+    stages, losses = run_pipeline(sl, params, xs, ys, NOAM, lr=0.05, momentum=0.9, vertical_sync=True)
+    ref_p, ref_l = _torch_flat_loop(sl, params, xs, ys, common, 0.05, 0.9)
+    assert np.allclose(losses, ref_l, rtol=1e-11)
+    for st, rp in zip(stages, ref_p):
+        assert np.allclose(st.master, rp, rtol=1e-10, atol=1e-13)
+    hist, l2 = flat_loop(sl, params, xs, ys, common, lr=0.05, momentum=0.9)
+    assert l2 == losses
+    for s, st in enumerate(stages):
+        for a, b in zip(hist[s], st.versions):
+            assert np.array_equal(a, b)
+    # every stage read the SAME version for a given minibatch, forward and backward
+    for mb in range(M):
+        seen = {o.version for st in stages for o in st.trace if o.mb == mb and o.kind in (0, 1)}
+        assert len(seen) == 1
+    if S > 1 and NOAM > 1:   # and it is a different iteration from plain weight stashing
+        plain, _ = run_pipeline(sl, params, xs, ys, NOAM, lr=0.05, momentum=0.9)
+        assert not np.allclose(plain[-1].master, stages[-1].master, rtol=1e-9, atol=0)
+
+
+def test_vertical_sync_worked_example_and_ring():
+    # Section 3.4's example: with vertical sync, minibatch 5 uses the parameters updated by minibatch 1
+    # on all machines (4 stages, NOAM 4; 0-based: minibatch 4 reads version 1 everywhere)
+    from oracle.schedule import schedule_1f1b
+    S, NOAM, M = 4, 4, 12
+    for s in range(S):
+        ops = schedule_1f1b(S, NOAM, M, s, vertical_sync=True)
+        plain = schedule_1f1b(S, NOAM, M, s)
+        assert [(o.kind, o.mb) for o in ops] == [(o.kind, o.mb) for o in plain]      # same op order
+        for o in ops:
+            if o.kind in (0, 1):
+                assert o.version == max(0, o.mb - NOAM + 1)
+                if o.mb == 4:
+                    assert o.version == 1
+        # a ring of NOAM slots never overwrites a version that is still needed
+        held = {}
+        for o in ops:
+            if o.kind == 2:
+                held[o.version % NOAM] = o.version
+            elif o.version > 0:
+                assert held[o.slot] == o.version
+    # the stage refuses a version it no longer holds
+    sl = _mlp(stages=2)
+    st = Stage(sl[0], _params(sl)[0], depth=1, ring_depth=2)
+    x, _ = _data(1, 6, 12, 5)
+    for mb in range(3):
+        st.forward(mb, x[0])
+        st.backward(mb, np.zeros((6, 12)), need_dx=False)
+        st.update(mb)
+    st.forward(3, x[0], version=2)
+    st.backward(3, np.zeros((6, 12)), need_dx=False)
+    st.update(3)
+    with pytest.raises(RuntimeError):
+        st.forward(4, x[0], version=2)      # latest is 4, the ring holds 3 and 4
+    with pytest.raises(RuntimeError):
+        st.forward(4, x[0], version=5)
