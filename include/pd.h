@@ -129,6 +129,10 @@ typedef struct {
   int32_t n_layers;
   const pd_layer_desc* layers; /* host; copied at create                                          */
   void* stream;               /* hipStream_t, borrowed; all of the stage's kernels run on it      */
+  int32_t vertical_sync;      /* != 0: vertical sync (Section 3.4).  The stage keeps as many weight versions as the
+                                 INPUT stage (max(1, noam), or in_flight_override) so that a forward pass may ask
+                                 for the version its minibatch was tagged with there (pd_forward_versioned);
+                                 the in-flight depth is unchanged                                  */
 } pd_stage_config;
 
 /* --- schedule (pure host, no GPU touched) -------------------------------------------------
@@ -142,6 +146,10 @@ typedef struct {
  * PD_ENOMEM if cap is too small (n_out still set); PD_EINVAL on bad arguments. */
 int pd_schedule_1f1b(int32_t num_stages, int32_t noam, int32_t num_minibatches, int32_t stage_index,
                      pd_op* out, size_t cap, size_t* n_out);
+/* The list of the same stage under vertical sync (Section 3.4): same op order; F and B carry the version the
+ * INPUT stage's forward of that minibatch read, and slot = version mod (depth of the input stage). */
+int pd_schedule_1f1b_vertical_sync(int32_t num_stages, int32_t noam, int32_t num_minibatches, int32_t stage_index,
+                                   pd_op* out, size_t cap, size_t* n_out);
 /* Same list for an explicitly given in-flight depth (>= 1). */
 int pd_schedule_1f1b_depth(int32_t depth, int32_t num_minibatches, pd_op* out, size_t cap, size_t* n_out);
 
@@ -159,6 +167,9 @@ int pd_stage_destroy(pd_stage* st);
 /* Number of parameters (length of the flat vector), in-flight depth, input-ring depth. */
 int pd_stage_num_params(const pd_stage* st, size_t* n);
 int pd_stage_depth(const pd_stage* st, int32_t* depth, int32_t* input_ring_depth);
+/* Number of weight versions the stage keeps (= depth, or the input stage's depth under vertical sync);
+ * ring slot of a version = version mod this. */
+int pd_stage_ring_depth(const pd_stage* st, int32_t* ring_depth);
 
 /* Resets the stage to version 0 with these weights (host, fp32, flat layout above), zero
  * momentum, nothing in flight.  In bf16 mode ring slot 0 = round-to-nearest-even of them. */
@@ -240,6 +251,12 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
  * and the same step applied.  PD_ESTATE without a pending gradient. */
 int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
                float* loss_dev);
+/* pd_forward with the weight version given by the caller (vertical sync, Section 3.4: the version travels with the
+ * minibatch from the input stage).  version = -1 means the latest (identical to pd_forward); otherwise it must
+ * still be in the ring (latest - ring depth < version <= latest), else PD_ESTATE.  The minibatch's backward pass
+ * uses the same version, as always.  pd_pipeline_run does this by itself for stages created with vertical_sync. */
+int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const void* x_dev, const int32_t* labels_dev,
+                         void* y_dev, float* loss_dev);
 int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev);
 int pd_update(pd_stage* st);
 

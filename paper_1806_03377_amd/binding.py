@@ -56,13 +56,16 @@ class pd_stage_config(C.Structure):
     _fields_ = [("stage_index", C.c_int32), ("num_stages", C.c_int32), ("noam", C.c_int32),
                 ("in_flight_override", C.c_int32), ("minibatch", C.c_int32), ("precision", C.c_int32),
                 ("lr", C.c_float), ("momentum", C.c_float), ("n_layers", C.c_int32),
-                ("layers", C.POINTER(pd_layer_desc)), ("stream", C.c_void_p)]
+                ("layers", C.POINTER(pd_layer_desc)), ("stream", C.c_void_p), ("vertical_sync", C.c_int32)]
 
 
 _vp, _sz, _i32, _f32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_float
 _SIGS = {
     "pd_schedule_1f1b": [_i32, _i32, _i32, _i32, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
     "pd_schedule_1f1b_depth": [_i32, _i32, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
+    "pd_schedule_1f1b_vertical_sync": [_i32, _i32, _i32, _i32, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
+    "pd_stage_ring_depth": [_vp, C.POINTER(_i32)],
+    "pd_forward_versioned": [_vp, _i32, _i32, _vp, _vp, _vp, _vp],
     "pd_stage_query_bytes": [C.POINTER(pd_stage_config), C.POINTER(_sz)],
     "pd_stage_create": [C.POINTER(pd_stage_config), _vp, _sz, C.POINTER(_vp)],
     "pd_stage_destroy": [_vp],
@@ -131,6 +134,14 @@ def pd_schedule_1f1b(num_stages: int, noam: int, num_minibatches: int, stage_ind
     arr = (pd_op * cap)()
     n = _sz(0)
     _check(_lib.pd_schedule_1f1b(num_stages, noam, num_minibatches, stage_index, arr, cap, C.byref(n)))
+    return _ops(arr, n.value)
+
+
+def pd_schedule_1f1b_vertical_sync(num_stages: int, noam: int, num_minibatches: int, stage_index: int):
+    cap = max(1, 3 * max(0, num_minibatches))
+    arr = (pd_op * cap)()
+    n = _sz(0)
+    _check(_lib.pd_schedule_1f1b_vertical_sync(num_stages, noam, num_minibatches, stage_index, arr, cap, C.byref(n)))
     return _ops(arr, n.value)
 
 
@@ -206,10 +217,10 @@ def layer_descs(layers: Sequence[tuple], in_hw=None):
 
 
 def make_config(layers, *, stage_index=0, num_stages=1, noam=1, in_flight_override=0, minibatch=1,
-                precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None):
+                precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None, vertical_sync=False):
     descs = layer_descs(layers, in_hw)
     cfg = pd_stage_config(stage_index, num_stages, noam, in_flight_override, minibatch, precision, lr, momentum,
-                          len(descs), descs, stream)
+                          len(descs), descs, stream, 1 if vertical_sync else 0)
     cfg._keepalive = descs
     return cfg
 
@@ -319,6 +330,17 @@ def pd_stage_debug_write(stage: int, what: int, mb_id: int, layer: int, values: 
 
 def pd_forward(stage: int, mb_id: int, x_dev: int, labels_dev: int = 0, y_dev: int = 0, loss_dev: int = 0):
     _check(_lib.pd_forward(stage, mb_id, x_dev, labels_dev or None, y_dev or None, loss_dev or None))
+
+
+def pd_forward_versioned(stage: int, mb_id: int, version: int, x_dev: int, labels_dev: int = 0, y_dev: int = 0,
+                         loss_dev: int = 0):
+    _check(_lib.pd_forward_versioned(stage, mb_id, version, x_dev, labels_dev, y_dev, loss_dev))
+
+
+def pd_stage_ring_depth(stage: int) -> int:
+    d = _i32(0)
+    _check(_lib.pd_stage_ring_depth(stage, C.byref(d)))
+    return d.value
 
 
 def pd_backward(stage: int, mb_id: int, dy_dev: int = 0, dx_dev: int = 0):

@@ -148,6 +148,8 @@ struct InFlight {
 struct pd_stage {
   int stage_index = 0, num_stages = 1, noam = 1;
   int depth = 1, in_depth = 1;
+  int ring_depth = 1;        // weight versions kept: depth, or the input stage's depth under vertical sync
+  bool vsync = false;
   int B = 0;
   bool bf16 = false;
   bool has_loss = false;
@@ -202,7 +204,7 @@ struct pd_stage {
     return hipEventRecord(e, stream);
   }
 
-  char* ring_slot(int version) const { return ring + (size_t)(version % depth) * p_pad * esz; }
+  char* ring_slot(int version) const { return ring + (size_t)(version % ring_depth) * p_pad * esz; }
   char* in_slot(int mb) const { return in_ring + (size_t)(mb % in_depth) * in_bytes; }
   char* stash_slot(int mb) const { return stash + (size_t)(mb % depth) * stash_slot_bytes; }
   char* grad_slot(int mb) const { return grad_in + (size_t)(mb & 1) * out_bytes; }
@@ -218,7 +220,7 @@ namespace {
 struct Plan {
   std::vector<Linear> lin;
   bool has_loss = false, bf16 = false;
-  int classes = 0, depth = 1, in_depth = 1, B = 0;
+  int classes = 0, depth = 1, in_depth = 1, ring_depth = 1, B = 0;
   size_t esz = 4, n_params = 0, p_pad = 0, in_bytes = 0, out_bytes = 0, stash_slot_bytes = 0, dlogits_off = 0;
   size_t ws_bytes = 0, dz_bytes = 0, pp_bytes = 0, part_bytes = 0, wt_bytes = 0;
   size_t blk_dy_bytes = 0, blk_dx_bytes = 0, blk_dx_stride = 0, o_blk_dy = 0, o_blk_dx = 0;
@@ -241,6 +243,10 @@ int make_plan(const pd_stage_config* c, Plan& p) {
   p.B = c->minibatch;
   p.depth = c->in_flight_override > 0 ? c->in_flight_override : stage_depth(c->num_stages, c->noam, c->stage_index);
   p.in_depth = c->stage_index > 0 ? p.depth + 1 : p.depth;
+  // vertical sync (Section 3.4): a minibatch may ask for a version as old as the input stage's oldest
+  p.ring_depth = c->vertical_sync ? (c->in_flight_override > 0 ? c->in_flight_override : stage_depth(c->num_stages, c->noam, 0))
+                                  : p.depth;
+  if (p.ring_depth < p.depth) p.ring_depth = p.depth;
   size_t flat = 0, dev = 0, y_off = 0, dz_off = 0, part_off = 0;
   int width = -1;               // features per row produced so far (-1: stage input not yet known)
   int ch = 0, hh = 1, ww = 1;   // its NHWC shape
@@ -479,7 +485,7 @@ int make_plan(const pd_stage_config* c, Plan& p) {
     }
   p.ws_bytes = align_up(p.ws_bytes, 256);
   size_t o = 0;
-  p.o_ring = o; o += align_up((size_t)p.depth * p.p_pad * p.esz, 256);
+  p.o_ring = o; o += align_up((size_t)p.ring_depth * p.p_pad * p.esz, 256);
   if (p.bf16) { p.o_master = o; o += align_up(p.p_pad * 4, 256); }
   p.o_mom = o; o += align_up(p.p_pad * 4, 256);
   p.o_in = o; o += (size_t)p.in_depth * p.in_bytes;
@@ -512,6 +518,31 @@ int pd_schedule_1f1b(int32_t num_stages, int32_t noam, int32_t num_minibatches, 
   return emit_schedule(stage_depth(num_stages, noam, stage_index), num_minibatches, out, cap, n_out);
 }
 
+int pd_schedule_1f1b_vertical_sync(int32_t num_stages, int32_t noam, int32_t num_minibatches, int32_t stage_index,
+                                   pd_op* out, size_t cap, size_t* n_out) {
+  if (num_stages < 1 || noam < 1 || num_minibatches < 0 || stage_index < 0 || stage_index >= num_stages)
+    return fail(PD_EINVAL, "bad schedule arguments (S=%d noam=%d M=%d s=%d)", num_stages, noam, num_minibatches, stage_index);
+  // same op order as the stage's own list; F and B carry the version the INPUT stage's forward read
+  std::vector<pd_op> own, first;
+  const int ring = stage_depth(num_stages, noam, 0);
+  build_schedule(stage_depth(num_stages, noam, stage_index), num_minibatches, own);
+  build_schedule(ring, num_minibatches, first);
+  std::vector<int> tag(num_minibatches > 0 ? num_minibatches : 0, 0);
+  for (const pd_op& o : first)
+    if (o.kind == PD_OP_F) tag[o.mb_id] = o.version;
+  for (pd_op& o : own) {
+    if (o.kind != PD_OP_U) o.version = tag[o.mb_id];
+    o.slot = o.version % ring;
+  }
+  if (n_out) *n_out = own.size();
+  if (own.size() > cap) return fail(PD_ENOMEM, "schedule needs %zu entries, capacity %zu", own.size(), cap);
+  if (!own.empty()) {
+    if (!out) return fail(PD_EINVAL, "out is null");
+    memcpy(out, own.data(), own.size() * sizeof(pd_op));
+  }
+  return PD_OK;
+}
+
 int pd_schedule_1f1b_depth(int32_t depth, int32_t num_minibatches, pd_op* out, size_t cap, size_t* n_out) {
   if (depth < 1 || num_minibatches < 0) return fail(PD_EINVAL, "bad schedule arguments (depth=%d M=%d)", depth, num_minibatches);
   return emit_schedule(depth, num_minibatches, out, cap, n_out);
@@ -539,7 +570,8 @@ int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena
   if (!st) return fail(PD_ENOMEM, "host allocation failed");
   char* a = static_cast<char*>(device_arena);
   st->stage_index = cfg->stage_index; st->num_stages = cfg->num_stages; st->noam = cfg->noam;
-  st->depth = p.depth; st->in_depth = p.in_depth; st->B = p.B; st->bf16 = p.bf16; st->has_loss = p.has_loss;
+  st->depth = p.depth; st->in_depth = p.in_depth; st->ring_depth = p.ring_depth; st->vsync = cfg->vertical_sync != 0;
+  st->B = p.B; st->bf16 = p.bf16; st->has_loss = p.has_loss;
   st->classes = p.classes; st->lr = cfg->lr; st->mu = cfg->momentum;
   st->stream = static_cast<hipStream_t>(cfg->stream);
   st->lin = p.lin; st->esz = p.esz; st->n_params = p.n_params; st->p_pad = p.p_pad;
@@ -592,6 +624,12 @@ int pd_stage_depth(const pd_stage* st, int32_t* depth, int32_t* input_ring_depth
   return PD_OK;
 }
 
+int pd_stage_ring_depth(const pd_stage* st, int32_t* ring_depth) {
+  if (check_stage(st) || !ring_depth) return fail(PD_EINVAL, "null argument");
+  *ring_depth = st->ring_depth;
+  return PD_OK;
+}
+
 int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   if (check_stage(st) || !host_params) return fail(PD_EINVAL, "null argument");
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu parameters, got %zu", st->n_params, n);
@@ -617,8 +655,8 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
   if (check_stage(st) || !host_out) return fail(PD_EINVAL, "null argument");
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu parameters, got %zu", st->n_params, n);
   if (version < 0) version = st->latest;
-  if (version > st->latest || version <= st->latest - st->depth)
-    return fail(PD_ESTATE, "version %d is not in the ring (latest %d, depth %d)", version, st->latest, st->depth);
+  if (version > st->latest || version <= st->latest - st->ring_depth)
+    return fail(PD_ESTATE, "version %d is not in the ring (latest %d, depth %d)", version, st->latest, st->ring_depth);
   PD_HIP(hipStreamSynchronize(st->stream));
   const bool from_master = st->bf16 && version == st->latest && !ring_copy;
   if (!st->bf16 || from_master) {
@@ -826,7 +864,15 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
 
 int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
                float* loss_dev) {
+  return pd_forward_versioned(st, mb_id, -1, x_dev, labels_dev, y_dev, loss_dev);
+}
+
+int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const void* x_dev, const int32_t* labels_dev,
+                         void* y_dev, float* loss_dev) {
   if (check_stage(st)) return PD_EINVAL;
+  if (version >= 0 && (version > st->latest || version <= st->latest - st->ring_depth))
+    return fail(PD_ESTATE, "forward of minibatch %d asks for version %d, the stage holds %d..%d", mb_id, version,
+                st->latest - st->ring_depth + 1 > 0 ? st->latest - st->ring_depth + 1 : 0, st->latest);
   if (!x_dev) return fail(PD_EINVAL, "x_dev is null");
   if (mb_id < 0) return fail(PD_EINVAL, "mb_id must be >= 0");
   if (st->has_loss && !labels_dev) return fail(PD_EINVAL, "labels_dev is required on a stage that ends in the loss");
@@ -837,7 +883,8 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
     return fail(PD_ESTATE, "forward of minibatch %d after %d: ids must be consecutive", mb_id, st->last_fwd);
 
   hipStream_t s = st->stream;
-  const int v = st->latest;  // forward reads the latest version and stashes its id
+  // forward reads the latest version (or, under vertical sync, the one the minibatch carries) and stashes its id
+  const int v = version >= 0 ? version : st->latest;
   char* in = st->in_slot(mb_id);
   char* slot = st->stash_slot(mb_id);
   const char* w = st->ring_slot(v);
@@ -908,7 +955,7 @@ int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* la
   if (st->profiling) ++st->prof_ops[0];
   st->in_flight.push_back({mb_id, v});
   st->last_fwd = mb_id;
-  st->trace.push_back({PD_OP_F, mb_id, v, v % st->depth});
+  st->trace.push_back({PD_OP_F, mb_id, v, v % st->ring_depth});
   return PD_OK;
 }
 
@@ -1080,7 +1127,7 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
   st->grad_pending = true;
   st->pending_mb = mb_id;
-  st->trace.push_back({PD_OP_B, mb_id, v, v % st->depth});
+  st->trace.push_back({PD_OP_B, mb_id, v, v % st->ring_depth});
   return PD_OK;
 }
 
@@ -1169,7 +1216,7 @@ int pd_update(pd_stage* st) {
   if (st->profiling) ++st->prof_ops[2];
   st->latest = nv;
   st->grad_pending = false;
-  st->trace.push_back({PD_OP_U, mb, nv, nv % st->depth});
+  st->trace.push_back({PD_OP_U, mb, nv, nv % st->ring_depth});
   return PD_OK;
 }
 
@@ -1266,7 +1313,12 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
     if (st->has_loss != (s == S - 1)) return fail(PD_EINVAL, "only the last stage may (and must) end in the loss");
     if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "stage %d has minibatches in flight", s);
     if (st->last_fwd != stages[0]->last_fwd) return fail(PD_ESTATE, "stages disagree on the next minibatch id");
+    if (st->vsync != stages[0]->vsync) return fail(PD_EINVAL, "stage %d: vertical sync must be set on all stages or none", s);
+    if (st->vsync && st->latest != stages[0]->latest)
+      return fail(PD_ESTATE, "vertical sync: stage %d is at version %d, the input stage at %d", s, st->latest, stages[0]->latest);
   }
+  const bool vsync = stages[0]->vsync;
+  std::vector<int> tag(num_minibatches, -1);  // vertical sync: the version the input stage's forward read
   const int base = stages[0]->last_fwd + 1;
   std::vector<std::vector<pd_op>> ops(S);
   for (int s = 0; s < S; ++s) {
@@ -1305,7 +1357,8 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
           void* y = s < S - 1 ? stages[s + 1]->in_slot(mb) : nullptr;
           const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->lin.back().rows : nullptr;
           float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
-          const int rc = pd_forward(st, mb, x, lab, y, loss);
+          if (vsync && s == 0) tag[i] = st->latest;
+          const int rc = pd_forward_versioned(st, mb, vsync ? tag[i] : -1, x, lab, y, loss);
           if (rc != PD_OK) return rc;
           PD_HIP(hipEventRecord(st->ev_f[i], st->stream));
           f_rec[s][i] = 1;

@@ -41,6 +41,18 @@ def test_schedule_matches_oracle_bit_exact(S):
                 assert got == ref, (S, noam, M, s)
 
 
+@pytest.mark.parametrize("S", range(1, 6))
+def test_vertical_sync_schedule_matches_oracle_bit_exact(S):
+    for noam in range(1, S + 1):
+        for M in (0, 1, 2, 5, 3 * S, 40):
+            for s in range(S):
+                got = pd.pd_schedule_1f1b_vertical_sync(S, noam, M, s)
+                ref = [tuple(o) for o in schedule_1f1b(S, noam, M, s, vertical_sync=True)] if M else []
+                assert got == ref, (S, noam, M, s)
+    with pytest.raises(pd.PdError):
+        pd.pd_schedule_1f1b_vertical_sync(3, 3, 4, 3)
+
+
 def test_schedule_with_forced_depth():
     for depth in (1, 2, 4, 7):
         for M in (1, 3, 4, 9, 20):

@@ -640,6 +640,67 @@ def test_pipeline_shapes_f32(S, noam, M):
     _pipeline_case(gen.config1_mlp(40, 6, S), B=6, noam=noam, M=M, precision=pd.PD_F32, lr=0.05)
 
 
+@pytest.mark.parametrize("S,noam,M,precision", [(4, 4, 12, pd.PD_F32), (3, 2, 9, pd.PD_F32), (2, 2, 5, pd.PD_F32),
+                                                (3, 3, 6, pd.PD_BF16_F32ACC)])
+def test_vertical_sync_pipeline(S, noam, M, precision):
+    # Section 3.4, vertical sync: every stage uses the version the input stage's forward read.  Compared with the
+    # oracle's pipeline in the same mode: op traces bit for bit, numbers within the precision's tolerance.
+    bf16 = precision == pd.PD_BF16_F32ACC
+    width, classes, B = (64, 16, 8) if bf16 else (40, 6, 6)
+    sl = gen.config1_mlp(width, classes, S)
+    params = [gen.init_params(SEED + 9, f"v{s}", ly) for s, ly in enumerate(sl)]
+    xs = gen.normal(SEED + 9, "X", (M, B, width)); labs = gen.labels(SEED + 9, "Y", (M, B), classes)
+    ostages, olosses = run_pipeline(sl, params, [x.astype(np.float64) for x in xs], list(labs), noam,
+                                    mode="bf16" if bf16 else "f32", lr=0.05, momentum=0.9, vertical_sync=True)
+    gs = [GpuStage(sl[s], params[s], minibatch=B, precision=precision, stage_index=s, num_stages=S, noam=noam, lr=0.05,
+                   momentum=0.9, stream=torch.cuda.Stream(), vertical_sync=True) for s in range(S)]
+    try:
+        xd = to_dev(xs.reshape(M * B, width), bf16); ld = labels_dev(labs)
+        losses = torch.zeros(M, dtype=torch.float32, device=dev())
+        torch.cuda.synchronize()
+        pd.pd_pipeline_run([g.h for g in gs], M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+        torch.cuda.synchronize()
+        tol = TOL_BF16 if bf16 else TOL_F32
+        lg = to_host(losses)
+        for i in range(M):
+            assert abs(lg[i] - olosses[i]) <= tol * abs(olosses[i]), i
+        ring = max(1, noam)
+        for s in range(S):
+            assert pd.pd_stage_ring_depth(gs[s].h) == ring and pd.pd_stage_depth(gs[s].h)[0] == max(1, noam - s)
+            trace = pd.pd_stage_trace(gs[s].h)
+            assert trace == pd.pd_schedule_1f1b_vertical_sync(S, noam, M, s)
+            assert trace == [tuple(o) for o in ostages[s].trace]
+            assert rel_err(pd.pd_stage_get_params(gs[s].h), ostages[s].master) <= tol, s
+            assert rel_err(pd.pd_stage_get_momentum(gs[s].h), ostages[s].mom) <= (5 * tol if bf16 else tol), s
+    finally:
+        for g in gs:
+            g.close()
+
+
+def test_forward_versioned_protocol():
+    layers = [("linear", 16, 16, True)]
+    g = GpuStage(layers, gen.init_params(SEED, "pv", layers), minibatch=4, precision=pd.PD_F32, stage_index=1,
+                 num_stages=2, noam=3, vertical_sync=True)   # in-flight depth 2, ring of 3 versions
+    try:
+        assert pd.pd_stage_depth(g.h)[0] == 2 and pd.pd_stage_ring_depth(g.h) == 3
+        x = torch.zeros(4, 16, device=dev()); dy = torch.zeros(4, 16, device=dev())
+        for mb in range(4):                                  # four updates: versions 2, 3, 4 are held
+            pd.pd_forward_versioned(g.h, mb, -1, x.data_ptr())
+            pd.pd_backward(g.h, mb, dy.data_ptr(), 0)
+            pd.pd_update(g.h)
+        for bad in (1, 5):
+            with pytest.raises(pd.PdError) as e:
+                pd.pd_forward_versioned(g.h, 4, bad, x.data_ptr())
+            assert e.value.status == pd.PD_ESTATE
+        pd.pd_forward_versioned(g.h, 4, 2, x.data_ptr())     # the oldest one still in the ring
+        assert pd.pd_stage_version(g.h, 4) == 2 and pd.pd_stage_trace(g.h)[-1] == (pd.PD_OP_F, 4, 2, 2)
+        pd.pd_backward(g.h, 4, dy.data_ptr(), 0)
+        assert pd.pd_stage_trace(g.h)[-1] == (pd.PD_OP_B, 4, 2, 2)
+        pd.pd_update(g.h)
+    finally:
+        g.close()
+
+
 def test_pipeline_run_twice_continues_ids():
     sl = gen.config1_mlp(32, 8, 3)
     B, M = 4, 5
