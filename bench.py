@@ -29,8 +29,9 @@ UPDATE_BYTES_PER_PARAM = 18  # read fp32 master + momentum, write both, write th
 MEASURED_TRAFFIC_BYTES = 2.236e9
 
 
-def cpu_baseline(layers, params, xs, labs, depth, budget_s=20.0, max_steps=3):
-    """The oracle, as it stands, on the host cores: same stage, same step, a bounded number of steps."""
+def cpu_baseline(layers, params, xs, labs, depth, budget_s=12.0, max_steps=16):
+    """The oracle, as it stands, on the host cores: same stage, same step, a bounded number of steps (about 10 s of
+    work; the oracle keeps every weight version it produces, about 1 GB each at this size, hence the step cap)."""
     import numpy as np
     from oracle.pipeline import Stage
     try:
