@@ -89,13 +89,23 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
   const int cb0 = AI * wrow;                         // first 32-channel block of this wave inside the co tile
   const int taps = g.kh * g.kw;
   const int ci_tiles = (g.Ci + 63) / 64;
-  const int tg = blockIdx.x % tap_groups;
-  const int ci0 = ((blockIdx.x / tap_groups) % ci_tiles) * 64;
-  const int co0 = (blockIdx.x / tap_groups / ci_tiles) * COT;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): renumber them so that all tiles of a
+  // pixel range -- they read the same dz and x -- run on the same XCD, one range after the other.
+  int tile_id, split_id;
+  {
+    const int tiles = gridDim.x, total = tiles * gridDim.y, per = total >> 3;
+    int id = blockIdx.x + tiles * blockIdx.y;
+    if (id < per * 8) id = (id & 7) * per + (id >> 3);
+    split_id = id / tiles;
+    tile_id = id - split_id * tiles;
+  }
+  const int tg = tile_id % tap_groups;
+  const int ci0 = ((tile_id / tap_groups) % ci_tiles) * 64;
+  const int co0 = (tile_id / tap_groups / ci_tiles) * COT;
   const int ta0 = tg * GR;
   const int Wp = g.W + g.pw, NH = g.N * g.H;
   const int nchunks = (NH * Wp + kPix - 1) / kPix;
-  const int chunk0 = blockIdx.y * chunks_per_split;
+  const int chunk0 = split_id * chunks_per_split;
   const int chunk1 = chunk0 + chunks_per_split < nchunks ? chunk0 + chunks_per_split : nchunks;
   const int q64 = kPix / Wp, r64 = kPix - q64 * Wp, qH = q64 % g.H;
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_zero_block);
@@ -170,16 +180,15 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
   // ---- fragment addresses (bytes inside a stage) for reduction step 0, low half ---------------------------
   const int pixl = 8 * (l >> 5) + ((l >> 2) & 3);
   const int chb = (16 * ((l >> 4) & 1) + 4 * (l & 3)) * 2;
-  int aoff[AI], boff[KW];
+  int aoff[AI], boff0;
 #pragma unroll
   for (int i = 0; i < AI; ++i) {
     if (COT == 128) aoff[i] = pixl * ZRB + 64 * ((cb0 + i) ^ (pixl & 3)) + chb;
     else aoff[i] = (32 * wh + pixl) * ZRB + 64 * ((cb0 + i) ^ ((pixl >> 1) & 1)) + chb;
   }
-#pragma unroll
-  for (int tb = 0; tb < KW; ++tb) {
-    const int j = (COT == 128 ? 0 : 32 * wh) + pixl + tb;
-    boff[tb] = ZT + j * kXRow + 64 * (wc ^ ((j >> 1) & 1)) + chb;
+  {
+    const int j = (COT == 128 ? 0 : 32 * wh) + pixl;
+    boff0 = ZT + j * kXRow + 64 * (wc ^ ((j >> 1) & 1)) + chb;
   }
 
   f32x16 acc[AI][NT], accb[AI];
@@ -206,19 +215,53 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
       cur = cur == NS - 1 ? 0 : cur + 1;
       lds_char_t* sl = smem + fill * STAGE;
       fill = fill == NS - 1 ? 0 : fill + 1;
-#pragma unroll
-      for (int ks = 0; ks < KSW; ++ks) {
+      // The KW taps of a filter row read overlapping windows of the same band: this lane's 8 + KW - 1 consecutive
+      // input positions are fetched once (NR transposing reads of 4 positions each) and every tap's operand is cut
+      // out of that window in registers.  The windows are software-pipelined by hand: the reads of row r + 2 (two
+      // filter rows ahead, across reduction steps) are issued, and pinned, before the MFMAs of row r, so that the
+      // LDS latency is covered by two rows of MFMAs.
+      constexpr int NR = (KW + 7 + 3) / 4, ROWS = KSW * GR, PF = 2;
+      uint32_t wv[PF + 1][2 * NR];
+      bf16x8 a[PF + 1][AI];  // (a row at most PF ahead is at most PF reduction steps ahead)
+      auto read_row = [&](int r, int buf) {
+        const int ks = r / GR, ta = r % GR;
         const int za = 16 * ks * ZRB, xa = 16 * ks * kXRow;
-        bf16x8 a[AI];
+        if (ta == 0) {
 #pragma unroll
-        for (int i = 0; i < AI; ++i) a[i] = tr_frag(sc + aoff[i] + za, sc + aoff[i] + za + 4 * ZRB);
+          for (int i = 0; i < AI; ++i) a[ks % (PF + 1)][i] = tr_frag(sc + aoff[i] + za, sc + aoff[i] + za + 4 * ZRB);
+        }
 #pragma unroll
-        for (int n = 0; n < NT; ++n) {
-          const int ta = n / KW, tb = n % KW;
-          const bf16x8 b = tr_frag(sc + boff[tb] + ta * XB + xa, sc + boff[tb] + ta * XB + xa + 4 * kXRow);
+        for (int h = 0; h < NR; ++h) {
+          const v4i16_t rr = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4i16_t*)(sc + boff0 + ta * XB + xa + 4 * h * kXRow));
+          const uint2 rw = __builtin_bit_cast(uint2, rr);
+          wv[buf][2 * h] = rw.x;
+          wv[buf][2 * h + 1] = rw.y;
+        }
+      };
+#pragma unroll
+      for (int r = 0; r < PF && r < ROWS; ++r) read_row(r, r);
+#pragma unroll
+      for (int r = 0; r < ROWS; ++r) {
+        const int ks = r / GR, ta = r % GR, cb = r % (PF + 1);
+        if (r + PF < ROWS) read_row(r + PF, (r + PF) % (PF + 1));
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int tb = 0; tb < KW; ++tb) {
+          const int n = ta * KW + tb;
+          uint4 o;
+          if (tb % 2 == 0) {
+            o = make_uint4(wv[cb][tb / 2], wv[cb][tb / 2 + 1], wv[cb][tb / 2 + 2], wv[cb][tb / 2 + 3]);
+          } else {
+            const int q = (tb - 1) / 2;
+            o = make_uint4(__builtin_amdgcn_alignbit(wv[cb][q + 1], wv[cb][q], 16),
+                           __builtin_amdgcn_alignbit(wv[cb][q + 2], wv[cb][q + 1], 16),
+                           __builtin_amdgcn_alignbit(wv[cb][q + 3], wv[cb][q + 2], 16),
+                           __builtin_amdgcn_alignbit(wv[cb][q + 4], wv[cb][q + 3], 16));
+          }
+          const bf16x8 b = frag(o);
 #pragma unroll
           for (int i = 0; i < AI; ++i) {
-            acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b, acc[i][n], 0, 0, 0);
+            acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % (PF + 1)][i], b, acc[i][n], 0, 0, 0);
             const int m = (ks * NT + n) * AI + i;
             if (m % GAP == GAP - 1 && m / GAP < LPS) {
               __builtin_amdgcn_sched_barrier(0);
@@ -227,9 +270,10 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
             }
           }
         }
-        if (do_bias) {
+        if (do_bias && ta == GR - 1) {
 #pragma unroll
-          for (int i = 0; i < AI; ++i) accb[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], ones, accb[i], 0, 0, 0);
+          for (int i = 0; i < AI; ++i)
+            accb[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks % (PF + 1)][i], ones, accb[i], 0, 0, 0);
         }
       }
       // this wave's loads of the next stage have landed (those of the one after may be in flight); after the
@@ -242,7 +286,7 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
   }
 
   const size_t n_w = (size_t)g.Co * taps * g.Ci;
-  const int sp = COT == 128 ? blockIdx.y : 2 * blockIdx.y + wh;
+  const int sp = COT == 128 ? split_id : 2 * split_id + wh;
   float* out = part + (size_t)sp * (n_w + g.Co);
   const int ci = ci0 + 32 * wc + (l & 31);
   const int cob = co0 + 32 * cb0;
