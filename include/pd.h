@@ -190,6 +190,22 @@ int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n);
  * PD_ESTATE while a gradient is pending (between pd_backward and pd_update). */
 int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const float* host_mom, size_t n);
 
+/* Per-stage checkpoint (Section 4, "Checkpointing": every stage dumps its own parameters when it has done the
+ * backward pass -- here: the update -- of an epoch's last minibatch; no coordination between stages).
+ * save: writes the LATEST fp32 weights, the momentum and the version id to `path` (host file; synchronises the
+ *       stream).  Minibatches may be in flight; PD_ESTATE between pd_backward and pd_update.
+ * load: restores them into a stage of the same shape and precision: nothing in flight, version id as saved (the
+ *       weights go into that version's ring slot, in bf16 mode rounded from the fp32 values), any next minibatch id.
+ *       PD_EINVAL for a missing, truncated or corrupt file (header, size and checksum are verified) or a mismatch.
+ * info: header of a checkpoint file (verifies it as load does); pure host, no GPU touched.
+ * File layout: "PDCKPT1\0", u32 precision, u32 0, u64 n_params, i64 version, u64 checksum, n_params floats of
+ * weights, n_params floats of momentum (flat parameter layout, little-endian); checksum over both arrays taken
+ * 8 bytes at a time, h = (h ^ word) * 0x100000001b3 from h = 0xcbf29ce484222325 (an odd tail word is zero-extended
+ * per array). */
+int pd_stage_checkpoint_save(pd_stage* st, const char* path);
+int pd_stage_checkpoint_load(pd_stage* st, const char* path);
+int pd_checkpoint_info(const char* path, size_t* n_params, int32_t* latest, int32_t* precision);
+
 /* Version bookkeeping: mb_id = -1 -> latest version; otherwise the version stashed for that
  * in-flight minibatch (PD_ESTATE if it is not in flight). */
 int pd_stage_version(const pd_stage* st, int32_t mb_id, int32_t* version);

@@ -14,6 +14,8 @@ Modules
                pipeline run, and the flat-loop form of the staleness equation
   partition -- the layer partitioner of Section 3.2: stage time, boundary cost,
                the dynamic program over (layers, machines), NOAM
+  checkpoint-- the per-stage checkpoint file (Section 4): layout and checksum
+               written out in plain Python; pinned by hand-computed checksums
 
 Pins (tests/test_oracle_*.py): the paper's 4-stage worked example (Section 3.4),
 the closed-form version rule read off the staleness equation of Section 3.4,

@@ -86,6 +86,9 @@ _SIGS = {
     "pd_backward": [_vp, _i32, _vp, _vp],
     "pd_update": [_vp],
     "pd_pipeline_run": [C.POINTER(_vp), _i32, _i32, _vp, _vp, _vp],
+    "pd_stage_checkpoint_save": [_vp, C.c_char_p],
+    "pd_stage_checkpoint_load": [_vp, C.c_char_p],
+    "pd_checkpoint_info": [C.c_char_p, C.POINTER(_sz), C.POINTER(_i32), C.POINTER(_i32)],
     "pd_stage_profile": [_vp, _i32],
     "pd_stage_profile_read": [_vp, C.POINTER(pd_layer_profile), _sz, C.POINTER(_sz)],
     "pd_partition": [_i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double,
@@ -355,6 +358,21 @@ def pd_pipeline_run(stages: Sequence[int], num_minibatches: int, inputs_dev: int
                     losses_dev: int = 0):
     arr = (_vp * len(stages))(*stages)
     _check(_lib.pd_pipeline_run(arr, len(stages), num_minibatches, inputs_dev, labels_dev, losses_dev or None))
+
+
+def pd_stage_checkpoint_save(stage: int, path: str):
+    _check(_lib.pd_stage_checkpoint_save(stage, os.fsencode(path)))
+
+
+def pd_stage_checkpoint_load(stage: int, path: str):
+    _check(_lib.pd_stage_checkpoint_load(stage, os.fsencode(path)))
+
+
+def pd_checkpoint_info(path: str):
+    """(n_params, version, precision) of a checkpoint file; raises PdError if the file does not verify."""
+    n, v, p = _sz(0), _i32(0), _i32(0)
+    _check(_lib.pd_checkpoint_info(os.fsencode(path), C.byref(n), C.byref(v), C.byref(p)))
+    return n.value, v.value, p.value
 
 
 def pd_stage_profile(stage: int, enable: bool):

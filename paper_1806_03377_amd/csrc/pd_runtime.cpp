@@ -713,6 +713,110 @@ int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n) {
   return PD_OK;
 }
 
+// ---- per-stage checkpoint (Section 4, "Checkpointing") ----------------------------------------------------
+// File: 8 bytes "PDCKPT1\0"; u32 precision; u32 0; u64 n_params; i64 latest version; u64 checksum; then n_params
+// floats of the fp32 (master) weights and n_params floats of momentum, flat layout, little-endian.  The checksum
+// runs over the two arrays, 8 bytes at a time: h = (h ^ word) * 0x100000001b3 starting from 0xcbf29ce484222325.
+namespace {
+constexpr char kCkptMagic[8] = {'P', 'D', 'C', 'K', 'P', 'T', '1', '\0'};
+struct CkptHeader {
+  char magic[8];
+  uint32_t precision, zero;
+  uint64_t n_params;
+  int64_t latest;
+  uint64_t checksum;
+};
+uint64_t ckpt_hash(uint64_t h, const float* p, size_t n) {  // n even or odd: the odd tail is widened with zero
+  const size_t pairs = n / 2;
+  for (size_t i = 0; i < pairs; ++i) {
+    uint64_t w;
+    memcpy(&w, p + 2 * i, 8);
+    h = (h ^ w) * 0x100000001b3ull;
+  }
+  if (n & 1) {
+    uint32_t t;
+    memcpy(&t, p + n - 1, 4);
+    h = (h ^ (uint64_t)t) * 0x100000001b3ull;
+  }
+  return h;
+}
+int ckpt_read(const char* path, CkptHeader& hd, std::vector<float>* w, std::vector<float>* m) {
+  if (!path) return fail(PD_EINVAL, "checkpoint: path is null");
+  FILE* f = fopen(path, "rb");
+  if (!f) return fail(PD_EINVAL, "checkpoint: cannot open %s", path);
+  int rc = PD_OK;
+  std::vector<float> bw, bm;
+  if (fread(&hd, sizeof hd, 1, f) != 1 || memcmp(hd.magic, kCkptMagic, 8) != 0 || hd.zero != 0 || hd.precision > 1 ||
+      hd.latest < 0 || hd.latest > 0x7fffffff || hd.n_params > ((uint64_t)1 << 40)) {
+    rc = fail(PD_EINVAL, "checkpoint: %s has no valid header", path);
+  } else {
+    bw.resize(hd.n_params);
+    bm.resize(hd.n_params);
+    char extra;
+    if (fread(bw.data(), 4, bw.size(), f) != bw.size() || fread(bm.data(), 4, bm.size(), f) != bm.size() ||
+        fread(&extra, 1, 1, f) != 0)
+      rc = fail(PD_EINVAL, "checkpoint: %s is truncated or has trailing bytes", path);
+    else if (ckpt_hash(ckpt_hash(0xcbf29ce484222325ull, bw.data(), bw.size()), bm.data(), bm.size()) != hd.checksum)
+      rc = fail(PD_EINVAL, "checkpoint: %s fails its checksum", path);
+  }
+  fclose(f);
+  if (rc == PD_OK && w) w->swap(bw);
+  if (rc == PD_OK && m) m->swap(bm);
+  return rc;
+}
+}  // namespace
+
+int pd_checkpoint_info(const char* path, size_t* n_params, int32_t* latest, int32_t* precision) {
+  CkptHeader hd;
+  const int rc = ckpt_read(path, hd, nullptr, nullptr);
+  if (rc != PD_OK) return rc;
+  if (n_params) *n_params = (size_t)hd.n_params;
+  if (latest) *latest = (int32_t)hd.latest;
+  if (precision) *precision = (int32_t)hd.precision;
+  return PD_OK;
+}
+
+int pd_stage_checkpoint_save(pd_stage* st, const char* path) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (!path) return fail(PD_EINVAL, "checkpoint: path is null");
+  if (st->grad_pending) return fail(PD_ESTATE, "checkpoint: a gradient is pending (save after pd_update)");
+  std::vector<float> w(st->n_params), m(st->n_params);
+  int rc = pd_stage_get_params(st, -1, 0, w.data(), w.size());
+  if (rc == PD_OK) rc = pd_stage_get_momentum(st, m.data(), m.size());
+  if (rc != PD_OK) return rc;
+  CkptHeader hd;
+  memcpy(hd.magic, kCkptMagic, 8);
+  hd.precision = st->bf16 ? 1u : 0u;
+  hd.zero = 0;
+  hd.n_params = st->n_params;
+  hd.latest = st->latest;
+  hd.checksum = ckpt_hash(ckpt_hash(0xcbf29ce484222325ull, w.data(), w.size()), m.data(), m.size());
+  FILE* f = fopen(path, "wb");
+  if (!f) return fail(PD_EINVAL, "checkpoint: cannot create %s", path);
+  const bool ok = fwrite(&hd, sizeof hd, 1, f) == 1 && fwrite(w.data(), 4, w.size(), f) == w.size() &&
+                  fwrite(m.data(), 4, m.size(), f) == m.size();
+  if (fclose(f) != 0 || !ok) return fail(PD_EINVAL, "checkpoint: writing %s failed", path);
+  return PD_OK;
+}
+
+int pd_stage_checkpoint_load(pd_stage* st, const char* path) {
+  if (check_stage(st)) return PD_EINVAL;
+  CkptHeader hd;
+  std::vector<float> w, m;
+  int rc = ckpt_read(path, hd, &w, &m);
+  if (rc != PD_OK) return rc;
+  if (hd.n_params != st->n_params) return fail(PD_EINVAL, "checkpoint: %llu parameters, the stage has %zu", (unsigned long long)hd.n_params, st->n_params);
+  if ((hd.precision == 1) != st->bf16) return fail(PD_EINVAL, "checkpoint: precision differs from the stage's");
+  rc = pd_stage_set_params(st, w.data(), w.size());  // version 0 in ring slot 0, nothing in flight
+  if (rc == PD_OK) rc = pd_stage_set_momentum(st, m.data(), m.size());
+  if (rc != PD_OK) return rc;
+  const int v = (int)hd.latest;
+  if (v % st->ring_depth != 0)  // the weights belong in the ring slot of their version
+    PD_HIP(hipMemcpy(st->ring_slot(v), st->ring_slot(0), st->p_pad * st->esz, hipMemcpyDeviceToDevice));
+  st->latest = v;
+  return PD_OK;
+}
+
 int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const float* host_mom, size_t n) {
   if (check_stage(st)) return PD_EINVAL;
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
