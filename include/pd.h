@@ -341,7 +341,8 @@ int pd_partition(int32_t n_layers, int32_t n_machines, const double* t_layer, co
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
 /* Tuning knob (process-wide, not thread-safe): forward and dgrad products whose output has at least `min_tiles`
  * tiles of 256 x 256 run on the compute-bound large-tile kernels, smaller ones on the split-K kernels built for
- * minibatch-sized row counts.  Default 128.  Returns the previous value; min_tiles < 1 only queries.  Set it
+ * minibatch-sized row counts.  Default 128.  The same knob (times two) decides from how many 256 x 256 output tiles
+ * a convolution with >= 256 output channels uses its wide-tile kernel.  Returns the previous value; min_tiles < 1 only queries.  Set it
  * before pd_gemm_workspace_bytes / pd_stage_query_bytes: the workspace size depends on it. */
 int pd_set_big_tile_threshold(int32_t min_tiles);
 int pd_linear_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, int32_t M, int32_t N,

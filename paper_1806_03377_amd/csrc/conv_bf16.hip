@@ -239,16 +239,20 @@ __device__ __forceinline__ void dma16(const bf16_t* lane_src, char* uniform_lds_
 }
 #pragma clang diagnostic pop
 
-constexpr int DK = 32, DNS = 3, DROWB = DK * 2;
+constexpr int DK = 32, DROWB = DK * 2;
 
+// BN = 64, 128: four waves, three stages, two workgroups per compute unit.  BN = 256 (layers with >= 256 output
+// channels): eight waves of 128 x 64 on a 256 x 256 tile, four stages (loads three stages ahead), one workgroup
+// per compute unit -- a third fewer operand bytes per MFMA through L2 and LDS than 256 x 128.
 template <int BN, bool UP, bool ALIGNED>
-__global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __restrict__ X,
+__global__ __launch_bounds__(BN == 256 ? 512 : 256, BN == 256 ? 1 : 2) void conv_dma_kernel(const bf16_t* __restrict__ X,
                                                                const bf16_t* __restrict__ Wg, ConvGeom g,
                                                                ConvEpilogue ep) {
   constexpr int BM_ = 256;
-  constexpr int WNW = BN / 64, WMW = 4 / WNW;         // waves along channels / pixels
+  constexpr int NWV = BN == 256 ? 8 : 4, NT_ = 64 * NWV, DNS = BN == 256 ? 4 : 3, D = DNS - 1;
+  constexpr int WNW = BN / 64, WMW = NWV / WNW;       // waves along channels / pixels
   constexpr int TM = BM_ / WMW, NI = TM / 32, NJ = 2;  // wave tile TM x 64
-  constexpr int QA = 4, QB = BN / 64, LPS = QA + QB;   // wave-wide loads per stage
+  constexpr int QA = 16 / NWV, QB = (BN / 16) / NWV, LPS = QA + QB;   // wave-wide loads per wave and stage
   constexpr int ATILE = BM_ * DROWB, STAGE = (BM_ + BN) * DROWB;
   constexpr int OLD = BN + 8;
   constexpr int kSmem = DNS * STAGE > BM_ * OLD * 2 ? DNS * STAGE : BM_ * OLD * 2;
@@ -256,9 +260,19 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
   __shared__ __attribute__((aligned(1024))) char smem[kSmem];
   const int t = threadIdx.x, l = t & 63;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w / WNW, wn = w % WNW;
-  const int co0 = blockIdx.x * BN;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): renumber them so that an XCD works on a
+  // contiguous run of pixel tiles and the channel tiles of one pixel tile -- they read the same input -- share it.
+  int tile_x, tile_y;
+  {
+    const int ntx = gridDim.x, total = ntx * gridDim.y, per = total >> 3;
+    int id = blockIdx.x + ntx * blockIdx.y;
+    if (id < per * 8) id = (id & 7) * per + (id >> 3);
+    tile_y = id / ntx;
+    tile_x = id - tile_y * ntx;
+  }
+  const int co0 = tile_x * BN;
   const int P = g.N * g.Ho * g.Wo;
-  const int p0 = blockIdx.y * BM_;
+  const int p0 = tile_y * BM_;
   const int K = g.kh * g.kw * g.Ci;
   const int T = (K + DK - 1) / DK;
   const int Hl = UP ? (g.H - 1) * g.up + 1 : g.H, Wl = UP ? (g.W - 1) * g.up + 1 : g.W;
@@ -272,7 +286,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
   uint32_t amask[QA];
 #pragma unroll
   for (int q = 0; q < QA; ++q) {
-    const int p = p0 + (q * 4 + w) * 16 + (l >> 2);
+    const int p = p0 + (q * NWV + w) * 16 + (l >> 2);
     if (p < P) {
       const unsigned pq = (unsigned)p / (unsigned)g.Wo;
       const int wo = p - (int)pq * g.Wo;
@@ -296,7 +310,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
   int wrow[QB];  // element offset of this lane's filter row, or -1
 #pragma unroll
   for (int q = 0; q < QB; ++q) {
-    const int co = co0 + (q * 4 + w) * 16 + (l >> 2);
+    const int co = co0 + (q * NWV + w) * 16 + (l >> 2);
     wrow[q] = co < g.Co ? co * K : -1;
   }
   // FAST: the tap and channel range of the stage being loaded, kept in scalars and advanced once per stage
@@ -320,12 +334,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
       if (q < QA) {
         const bool ok = l_kk < K && ((amask[q] >> l_tap) & 1u);  // past the end of the reduction: zeros
         const bf16_t* cand = X + (aoff[q] + l_off);
-        dma16(ok ? cand : zero, stage + (q * 4 + w) * 1024);
+        dma16(ok ? cand : zero, stage + (q * NWV + w) * 1024);
       } else {
         const int qb = q - QA;
         const bool ok = l_kk < K && wrow[qb] >= 0;
         const bf16_t* cand = Wg + (wrow[qb] + l_kk + kg);
-        dma16(ok ? cand : zero, stage + ATILE + (qb * 4 + w) * 1024);
+        dma16(ok ? cand : zero, stage + ATILE + (qb * NWV + w) * 1024);
       }
       return;
     }
@@ -351,11 +365,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
         wi = wq;
       }
       if (ok) src = X + (nbase[q] + (hi * g.W + wi) * g.Ci + ci);
-      dma16(src, stage + (q * 4 + w) * 1024);
+      dma16(src, stage + (q * NWV + w) * 1024);
     } else {
       const int qb = q - QA;
       if (k < K && wrow[qb] >= 0) src = Wg + ((size_t)wrow[qb] + k);
-      dma16(src, stage + ATILE + (qb * 4 + w) * 1024);
+      dma16(src, stage + ATILE + (qb * NWV + w) * 1024);
     }
   };
 
@@ -378,21 +392,21 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
   auto ldf = [&](const char* stage, int o, int ks) { return *reinterpret_cast<const uint4*>(stage + (o ^ (ks << 5))); };
 
 #pragma unroll
-  for (int d = 0; d < 2; ++d) {
+  for (int d = 0; d < D; ++d) {
 #pragma unroll
     for (int q = 0; q < LPS; ++q) load1(q, smem + d * STAGE, d * DK);
     advance_stage();
   }
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");  // stage 0 has landed
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 1) * LPS) : "memory");  // stage 0 has landed
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  int cur = 0, fill = 2;
+  int cur = 0, fill = D;
   for (int st = 0; st < T; ++st) {
     const char* sc = smem + cur * STAGE;
     cur = cur == DNS - 1 ? 0 : cur + 1;
     char* sl = smem + fill * STAGE;
     fill = fill == DNS - 1 ? 0 : fill + 1;
-    const int kk = (st + 2) * DK;  // past the end of the reduction every chunk comes from the zero block
+    const int kk = (st + D) * DK;  // past the end of the reduction every chunk comes from the zero block
     uint4 a[2][NI], b[2][NJ];
 #pragma unroll
     for (int i = 0; i < NI; ++i) a[0][i] = ldf(sc, fa[i], 0);
@@ -424,7 +438,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
       }
     }
     advance_stage();
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPS) : "memory");  // stage st+1 has landed; st+2 may be in flight
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 1) * LPS) : "memory");  // stage st+1 has landed; later ones may be in flight
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
   }
@@ -449,8 +463,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
   __syncthreads();
   constexpr int CPR = BN / 8;
 #pragma unroll
-  for (int i = 0; i < BM_ * CPR / kThreads; ++i) {
-    const int c = t + kThreads * i, row = c / CPR, cc = c % CPR;
+  for (int i = 0; i < BM_ * CPR / NT_; ++i) {
+    const int c = t + NT_ * i, row = c / CPR, cc = c % CPR;
     const int p = p0 + row, co = co0 + cc * 8;
     if (p >= P || co >= g.Co) continue;
     uint4 v = *reinterpret_cast<const uint4*>(&ot[row * OLD + cc * 8]);
@@ -473,16 +487,18 @@ __global__ __launch_bounds__(kThreads, 2) void conv_dma_kernel(const bf16_t* __r
 template <int BN>
 void launch_dma(hipStream_t s, dim3 grid, const bf16_t* x, const bf16_t* w, const ConvGeom& g, const ConvEpilogue& ep) {
   const bool up = g.up > 1, aligned = (g.Ci % DK) == 0 && g.kh * g.kw <= 32;
+  constexpr int threads = BN == 256 ? 512 : 256;
   if (up) {
-    if (aligned) conv_dma_kernel<BN, true, true><<<grid, kThreads, 0, s>>>(x, w, g, ep);
-    else conv_dma_kernel<BN, true, false><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    if (aligned) conv_dma_kernel<BN, true, true><<<grid, threads, 0, s>>>(x, w, g, ep);
+    else conv_dma_kernel<BN, true, false><<<grid, threads, 0, s>>>(x, w, g, ep);
   } else {
-    if (aligned) conv_dma_kernel<BN, false, true><<<grid, kThreads, 0, s>>>(x, w, g, ep);
-    else conv_dma_kernel<BN, false, false><<<grid, kThreads, 0, s>>>(x, w, g, ep);
+    if (aligned) conv_dma_kernel<BN, false, true><<<grid, threads, 0, s>>>(x, w, g, ep);
+    else conv_dma_kernel<BN, false, false><<<grid, threads, 0, s>>>(x, w, g, ep);
   }
 }
 
 bool g_conv_dma = true;
+int g_conv_wide_min_tiles = 256;  // 256 x 256 output tiles from which the wide kernel is used (one per compute unit)
 
 hipError_t launch_igemm(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g, const ConvEpilogue& ep) {
   const long long P = (long long)g.N * g.Ho * g.Wo;
@@ -490,7 +506,11 @@ hipError_t launch_igemm(hipStream_t s, const bf16_t* x, const bf16_t* w, const C
     return hipErrorInvalidValue;
   if (g_conv_dma && (g.Co % 8) == 0 && (long long)g.Co * g.kh * g.kw * g.Ci < (1ll << 31) &&
       ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w)) & 15) == 0) {
+    // 256-wide tiles only when they fill the chip about as well as 128-wide ones would
+    const long long tiles256 = ((g.Co + 255) / 256) * ((P + 255) / 256);
     if (g.Co <= 64) launch_dma<64>(s, dim3(1, (unsigned)((P + 255) / 256)), x, w, g, ep);
+    else if (g.Co >= 256 && (g.Co % 256 == 0 || g.Co > 512) && tiles256 >= g_conv_wide_min_tiles)
+      launch_dma<256>(s, dim3((g.Co + 255) / 256, (unsigned)((P + 255) / 256)), x, w, g, ep);
     else launch_dma<128>(s, dim3((g.Co + 127) / 128, (unsigned)((P + 255) / 256)), x, w, g, ep);
     return hipGetLastError();
   }
@@ -768,6 +788,10 @@ int wgrad_splits(long long chunks, int tiles) {
 
 }  // namespace
 
+
+void set_conv_wide_min_tiles(int min_tiles) {
+  if (min_tiles >= 1) g_conv_wide_min_tiles = min_tiles;
+}
 
 int conv_wgrad_split_count(const ConvGeom& g) {
   const long long P = (long long)g.N * g.Ho * g.Wo;

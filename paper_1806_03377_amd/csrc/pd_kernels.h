@@ -92,6 +92,9 @@ hipError_t conv_forward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, co
 // the transposed convolution reads dz zero-upsampled by s (taps that fall between samples contribute nothing).
 hipError_t conv_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, bf16_t* wt_scratch, const ConvGeom& g,
                            const ConvEpilogue& ep);
+// Output tiles (256 x 256) from which forward / input-gradient convolutions with >= 256 output channels use the
+// wide-tile kernel (default 256: one tile per compute unit).
+void set_conv_wide_min_tiles(int min_tiles);
 // Number of partial sums the weight-gradient kernel produces for this geometry, and the kernel itself:
 // part[split][Co*kh*kw*Ci + Co] (weights in w's layout, then the bias gradient).
 int conv_wgrad_split_count(const ConvGeom& g);

@@ -1493,7 +1493,10 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
   return PD_OK;
 }
 
-int pd_set_big_tile_threshold(int32_t min_tiles) { return pd::set_big_tile_threshold(min_tiles); }
+int pd_set_big_tile_threshold(int32_t min_tiles) {
+  pd::set_conv_wide_min_tiles(2 * min_tiles);  // same rule for the convolutions' 256 x 256 tiles (default 2 x 128)
+  return pd::set_big_tile_threshold(min_tiles);
+}
 
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) { return pd::gemm_bf16_workspace_bytes(M, N, K); }
 

@@ -254,6 +254,21 @@ def test_conv_fwd_bf16(geom):
         assert np.max(np.abs(to_host(y) - ref) / np.maximum(np.abs(ref), 1e-2)) < 2 ** -6   # at most one bf16 step
 
 
+# layers with >= 256 channels on the output side of the product, forced onto the 256 x 256-tile kernel
+WIDE_CONVS = [(2, 12, 12, 64, 256, 3, 3, 1, 1, 1), (1, 20, 20, 32, 768, 1, 1, 1, 0, 0), (2, 9, 9, 40, 520, 3, 3, 1, 1, 1),
+              (2, 12, 12, 256, 64, 3, 3, 1, 1, 1), (2, 9, 9, 512, 48, 1, 7, 1, 0, 3)]
+
+
+@pytest.mark.parametrize("geom", WIDE_CONVS)
+def test_conv_fwd_bf16_wide_tiles(geom, big_tiles):
+    test_conv_fwd_bf16(geom)
+
+
+@pytest.mark.parametrize("geom", WIDE_CONVS)
+def test_conv_dgrad_bf16_wide_tiles(geom, big_tiles):
+    test_conv_dgrad_bf16(geom)
+
+
 @pytest.mark.parametrize("geom", CONVS)
 def test_conv_dgrad_bf16(geom):
     N, H, W, ci, co, kh, kw, stride, ph, pw = geom
