@@ -107,6 +107,64 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
   if (t == 0) row_loss[r] = logf(sum) + mx - ld(lab);
 }
 
+// The same for wide rows (a vocabulary): the row is read ONCE, 16 bytes per lane, and stays in registers
+// (NV float4 per thread, classes <= 1024 NV) for the maximum, the sum and the result; bf16 results leave as 8-byte
+// stores.  Needs classes % 4 == 0 and 16-byte aligned rows.
+template <bool BF, int NV>
+__global__ __launch_bounds__(256) void softmax_xent_wide_kernel(const float* __restrict__ logits,
+                                                                const int32_t* __restrict__ labels,
+                                                                void* __restrict__ dlogits, float* __restrict__ row_loss,
+                                                                int rows, int classes) {
+  __shared__ float sh[256];
+  const int r = blockIdx.x, t = threadIdx.x;
+  const size_t base = (size_t)r * classes;
+  const int nq = classes >> 2;  // float4 per row
+  float4 v[NV];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int q = t + 256 * i;
+    if (q < nq) {
+      v[i] = *reinterpret_cast<const float4*>(logits + base + 4 * q);
+      mx = fmaxf(fmaxf(mx, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+    }
+  }
+  mx = block_reduce(mx, sh, true);
+  int lab = labels[r];
+  lab = lab < 0 ? 0 : (lab >= classes ? classes - 1 : lab);
+  float sum = 0.f, zlab = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int q = t + 256 * i;
+    if (q < nq) {
+      if ((lab >> 2) == q) zlab = (lab & 3) == 0 ? v[i].x : (lab & 3) == 1 ? v[i].y : (lab & 3) == 2 ? v[i].z : v[i].w;
+      v[i].x = expf(v[i].x - mx); v[i].y = expf(v[i].y - mx); v[i].z = expf(v[i].z - mx); v[i].w = expf(v[i].w - mx);
+      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+  }
+  sum = block_reduce(sum, sh, false);
+  const float inv = 1.f / sum, invr = 1.f / (float)rows;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int q = t + 256 * i;
+    if (q < nq) {
+      float d[4] = {v[i].x * inv, v[i].y * inv, v[i].z * inv, v[i].w * inv};
+      if ((lab >> 2) == q) d[lab & 3] -= 1.f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) d[e] *= invr;
+      if (BF) {
+        uint2 o;
+        o.x = f2bf(d[0]) | ((uint32_t)f2bf(d[1]) << 16);
+        o.y = f2bf(d[2]) | ((uint32_t)f2bf(d[3]) << 16);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(dlogits) + base + 4 * q) = o;
+      } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(dlogits) + base + 4 * q) = make_float4(d[0], d[1], d[2], d[3]);
+      }
+    }
+  }
+  if ((lab >> 2) % 256 == t) row_loss[r] = logf(sum) + mx - zlab;  // the thread that holds the label's logit
+}
+
 __global__ __launch_bounds__(256) void mean_kernel(const float* __restrict__ v, int n, float* __restrict__ out) {
   __shared__ float sh[256];
   float s = 0.f;
@@ -159,7 +217,11 @@ hipError_t relu_mask(hipStream_t s, const void* dy, const void* y, void* dz, siz
 }
 hipError_t softmax_xent(hipStream_t s, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
                         float* loss, int rows, int classes, bool dlogits_bf16) {
-  if (dlogits_bf16) softmax_xent_kernel<true><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
+  const bool aligned = (classes % 4) == 0 && ((reinterpret_cast<uintptr_t>(logits) | reinterpret_cast<uintptr_t>(dlogits)) & 15) == 0;
+  if (aligned && classes > 2048 && classes <= 1024 * 32) {  // wide rows: one pass over the logits, row kept in registers
+    if (dlogits_bf16) softmax_xent_wide_kernel<true, 32><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
+    else softmax_xent_wide_kernel<false, 32><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
+  } else if (dlogits_bf16) softmax_xent_kernel<true><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
   else softmax_xent_kernel<false><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
   if (loss) mean_kernel<<<1, 256, 0, s>>>(row_loss, rows, loss);
   return hipGetLastError();

@@ -199,6 +199,15 @@ def test_config2_vgg_fc_full_size():
     print("ambiguous ReLU decisions:", out["flips"], flush=True)
 
 
+def test_stage_wide_softmax_rows():
+    # more than 2048 classes: the loss runs on the single-pass kernel that keeps a row in registers
+    # (4104 = 1026 float4: four full rounds of 256 lanes and a ragged fifth; 32768 = the widest row it takes)
+    for classes, precision in ((4104, pd.PD_F32), (4104, pd.PD_BF16_F32ACC), (32768, pd.PD_BF16_F32ACC),
+                               (32776, pd.PD_BF16_F32ACC)):   # the last one is too wide: three-pass kernel
+        layers = [("linear", 40, classes, False), ("softmax_xent", classes)]
+        _single_stage_case(layers, B=6, depth=2, M=4, precision=precision, lr=0.05)
+
+
 def test_one_row_minibatch_and_depth_one():
     layers = [("linear", 24, 16, True), ("linear", 16, 8, False), ("softmax_xent", 8)]
     _single_stage_case(layers, B=1, depth=1, M=4, precision=pd.PD_BF16_F32ACC)
