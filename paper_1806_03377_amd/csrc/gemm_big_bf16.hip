@@ -416,6 +416,156 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restri
   big_epilogue<NJ, 64>(acc, ep, smem + (size_t)w * (DNS * DSTAGE / NW), i0 + 128 * wm, j0 + 64 * wn, l, I, J);
 }
 
+// ---- both operands stored with the reduction index as their slow axis (the weight gradient) --------------------
+//   out[n][k] = sum over rows m of z[m][n] * x[m][k]          z: [M][N], x: [M][K], out: [N][K] fp32
+// The tiles go into LDS as they lie in memory ([32 rows][256 columns] per operand and stage, straight from global
+// memory, 16 bytes per lane) and the MFMA operands are fetched with the transposing LDS read ds_read_b64_tr_b16:
+// in a group of 16 lanes, source lane j supplies the address of 4 columns (j % 4) of row (j / 4), lane i receives
+// column i of those 4 rows -- "column i, 4 reduction elements" of a 32x32x16 operand.  No transposing pre-pass, no
+// transposing stores.  256 x 256 output tile, 8 waves of 128 x 64, four stages, loads three stages ahead; rows past
+// M and columns past N / K are fetched from a block of zeros.  A row of a tile is 512 bytes = 8 slots of 64 bytes
+// (32 columns); slot s of row r holds column block s ^ (r & 3), so that the 4 rows one transposing read touches
+// fall into different banks.
+__device__ __attribute__((aligned(16))) const uint32_t g_tn_zero[4] = {0u, 0u, 0u, 0u};
+typedef short tn_v4i16_t __attribute__((ext_vector_type(4)));
+typedef short tn_v8i16_t __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) tn_v4i16_t tn_lds_v4i16_t;
+
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma_chunk64(const bf16_t* lane_src, char* uniform_lds_dst) {
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(uniform_lds_dst));
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(lane_src), "s"(lds_addr) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ bf16x8 tn_frag(const char* lo, const char* hi) {
+  const tn_v4i16_t a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tn_lds_v4i16_t*)lo);
+  const tn_v4i16_t b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tn_lds_v4i16_t*)hi);
+  const tn_v8i16_t v = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+__global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restrict__ Z, int ldz,
+                                                         const bf16_t* __restrict__ X, int ldx, BigEpilogue ep, int M,
+                                                         int N, int K, int tiles_n, int tiles_k) {
+  constexpr int NW = 8, NI = 4, NJ = 2, TR = 32, KS = TR / 16, NS = 4, D = NS - 1;
+  constexpr int ROWB = 512, TILE = TR * ROWB, STAGE = 2 * TILE;  // 16 KB per operand and stage
+  constexpr int LPS = 2 * TILE / 1024 / NW;                      // wave-wide loads per wave and stage (4)
+  constexpr int MF = NI * NJ;
+  __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
+  const int t = threadIdx.x, l = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
+  int bid = blockIdx.x;
+  {
+    const int per = gridDim.x >> 3;
+    if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
+  }
+  int tn, tk;
+  {
+    constexpr int BAND = 4;
+    const int per_band = BAND * tiles_k, band = bid / per_band, rem = bid - band * per_band;
+    const int rows_in = tiles_n - band * BAND < BAND ? tiles_n - band * BAND : BAND;
+    tn = band * BAND + rem % rows_in;
+    tk = rem / rows_in;
+  }
+  const int n0 = tn * GM, k0 = tk * GN;
+  const int T = (M + TR - 1) / TR;
+  const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_tn_zero);
+
+  // loads: per stage 16 wave-loads per operand, each two tile rows of 512 bytes; wave w issues numbers w, w + 8, ...
+  const bf16_t* lp[LPS];  // this lane's source for stage 0 (null: column outside the matrix)
+  int lrow[LPS], ldst[LPS];
+  size_t lstep[LPS];
+#pragma unroll
+  for (int q = 0; q < LPS; ++q) {
+    const int id = q * NW + w;                 // 0..15: z, 16..31: x
+    const bool is_x = id >= 16;
+    const int r = 2 * (id & 15) + (l >> 5);    // tile row (reduction index inside the stage)
+    const int s16 = l & 31, blk = (s16 >> 2) ^ (r & 3);
+    const int col = (is_x ? k0 : n0) + 32 * blk + 8 * (s16 & 3);
+    const int ld = is_x ? ldx : ldz;
+    lp[q] = col < (is_x ? K : N) ? (is_x ? X : Z) + (size_t)r * ld + col : nullptr;
+    lrow[q] = r;
+    lstep[q] = (size_t)TR * ld;
+    ldst[q] = (is_x ? TILE : 0) + (id & 15) * 1024;
+  }
+  auto issue = [&](int q, char* stage) {  // q-th load of this wave for the next stage to be fetched; advances
+    const bool ok = lp[q] != nullptr && lrow[q] < M;
+    dma_chunk64(ok ? lp[q] : zero, stage + ldst[q]);
+    if (lp[q] != nullptr) lp[q] += lstep[q];
+    lrow[q] += TR;
+  };
+
+  const int mrow = 8 * (l >> 5) + ((l >> 2) & 3);
+  const int chb = (16 * ((l >> 4) & 1) + 4 * (l & 3)) * 2;
+  int fa[NI], fb[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) fa[i] = mrow * ROWB + 64 * ((4 * wm + i) ^ (mrow & 3)) + chb;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) fb[j] = TILE + mrow * ROWB + 64 * ((2 * wn + j) ^ (mrow & 3)) + chb;
+  auto lda_ = [&](const char* stage, int o, int ks) { return tn_frag(stage + o + 16 * ks * ROWB, stage + o + (16 * ks + 4) * ROWB); };
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x16{0};
+
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+#pragma unroll
+    for (int q = 0; q < LPS; ++q) issue(q, smem + d * STAGE);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");  // stages 0 and 1 have landed
+  __syncthreads();
+  bf16x8 a[2][NI], b[2][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) a[0][i] = lda_(smem, fa[i], 0);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) b[0][j] = lda_(smem, fb[j], 0);
+  int cur = 0, fill = D;
+  for (int st = 0; st < T; ++st) {
+    const char* sc = smem + cur * STAGE;
+    cur = cur + 1 == NS ? 0 : cur + 1;
+    const char* sn = smem + cur * STAGE;
+    char* sl = smem + fill * STAGE;
+    fill = fill + 1 == NS ? 0 : fill + 1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) a[n][i] = lda_(sc, fa[i], ks + 1);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[n][j] = lda_(sc, fb[j], ks + 1);
+      } else {  // next stage's first fragments (published by the previous barrier)
+#pragma unroll
+        for (int i = 0; i < NI; ++i) a[n][i] = lda_(sn, fa[i], 0);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[n][j] = lda_(sn, fb[j], 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int m = 0; m < MF; ++m) {
+        const int i = m / NJ, j = m % NJ;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+        if (m == 2 || m == 6) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue(ks * 2 + (m == 6), sl);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    // this wave's loads of stage st+2 have landed (those of stage st+3 may still be in flight); after the barrier
+    // every wave's have, and every wave is done reading stage st
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  big_epilogue<NJ, 64>(acc, ep, smem + (size_t)w * (NS * STAGE / NW), n0 + 128 * wm, k0 + 64 * wn, l, N, K);
+}
+
 // column sums in two deterministic steps: partial sums over chunks of 128 rows, then the chunks in order
 constexpr int kColsumRows = 128;
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __restrict__ z, float* __restrict__ part,
@@ -446,6 +596,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const bf16_t* __restrict__ 
 }
 
 int g_big_waves = 8;
+bool g_wgrad_tn = true;
 
 template <bool TA, bool TB>
 hipError_t launch_big(hipStream_t s, const bf16_t* a, int lda, const bf16_t* b, int ldb, const BigEpilogue& ep, int I,
@@ -500,7 +651,13 @@ hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
     colsum_final_kernel<<<(N + 255) / 256, 256, 0, s>>>(cp, db, chunks, N);
     db_done = true;
   }
-  if (scratch && (M % 8) == 0 && scratch_bytes >= linear_wgrad_big_scratch_bytes(M, N, K)) {
+  if (g_wgrad_tn && (N % 8) == 0 && (K % 8) == 0 &&
+      ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(x)) & 15) == 0) {
+    // operands as they are: transposing LDS reads instead of a transposing pre-pass
+    const int tn = (N + GM - 1) / GM, tk = (K + GN - 1) / GN;
+    gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk);
+    e = hipGetLastError();
+  } else if (scratch && (M % 8) == 0 && scratch_bytes >= linear_wgrad_big_scratch_bytes(M, N, K)) {
     bf16_t* zt = static_cast<bf16_t*>(scratch);  // [N][M]
     bf16_t* xt = zt + (size_t)N * M;             // [K][M]
     e = transpose_bf16(s, dz, zt, M, N);
