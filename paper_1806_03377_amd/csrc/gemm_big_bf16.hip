@@ -566,6 +566,147 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
   big_epilogue<NJ, 64>(acc, ep, smem + (size_t)w * (NS * STAGE / NW), n0 + 128 * wm, k0 + 64 * wn, l, N, K);
 }
 
+// ---- A reduction-contiguous, B with the reduction index as its slow axis (the input gradient) -----------------
+//   out[i][j] = sum over r of a[i][r] * b[r][j]        a: [I][R] (dz), b: [R][J] (w as stored), out: [I][J]
+// The A side is gemm_dma_kernel's (64-byte tile rows, 16-byte fragment reads), the B side gemm_tn_kernel's
+// ([32 reduction rows][256 columns] as in memory, transposing reads): no transposed copy of the weights is made.
+// Needs R % 32 == 0.
+__global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restrict__ A, int lda,
+                                                         const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep, int I,
+                                                         int J, int R, int tiles_i, int tiles_j) {
+  constexpr int NW = 8, NI = 4, NJ = 2, KS = DK / 16, NS = 4, D = NS - 1;
+  constexpr int ATILE = 256 * DROWB, BROWB = 512, BTILE = DK * BROWB, STAGE = ATILE + BTILE;  // 16 KB + 16 KB
+  constexpr int QA = 2, QB = 2, LPS = QA + QB, MF = NI * NJ;
+  __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
+  const int t = threadIdx.x, l = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
+  int bid = blockIdx.x;
+  {
+    const int per = gridDim.x >> 3;
+    if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
+  }
+  int ti, tj;
+  {
+    constexpr int BAND = 4;
+    const int per_band = BAND * tiles_j, band = bid / per_band, rem = bid - band * per_band;
+    const int rows_in = tiles_i - band * BAND < BAND ? tiles_i - band * BAND : BAND;
+    ti = band * BAND + rem % rows_in;
+    tj = rem / rows_in;
+  }
+  const int i0 = ti * GM, j0 = tj * GN;
+  const int T = R / DK;
+  const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_tn_zero);
+
+  uint32_t aoffs[QA];  // A: byte offset of this lane's chunk, rows clamped (they only feed outputs never stored)
+#pragma unroll
+  for (int q = 0; q < QA; ++q) {
+    const int row = (q * NW + w) * 16 + (l >> 2), g = (l & 3) ^ dma_swz(row);
+    const int ra = i0 + row < I ? i0 + row : I - 1;
+    aoffs[q] = ((uint32_t)ra * (uint32_t)lda + g * 8) * 2u;
+  }
+  const bf16_t* bp[QB];  // B: this lane's source for stage 0 (null: column outside the matrix)
+#pragma unroll
+  for (int q = 0; q < QB; ++q) {
+    const int id = q * NW + w, r = 2 * id + (l >> 5);
+    const int s16 = l & 31, blk = (s16 >> 2) ^ (r & 3);
+    const int col = j0 + 32 * blk + 8 * (s16 & 3);
+    bp[q] = col < J ? Bm + (size_t)r * ldb + col : nullptr;
+  }
+  const size_t bstep = (size_t)DK * ldb;
+  int a_st = 0;  // reduction stage the next A loads fetch (clamped: the surplus is never read)
+  auto issue = [&](int q, char* stage) {
+    if (q < QA) {
+      const int k0 = (a_st < T ? a_st : T - 1) * DK;
+      dma_load16(A + k0, aoffs[q], stage + (q * NW + w) * 1024);
+      if (q == QA - 1) ++a_st;
+    } else {
+      const int qb = q - QA;
+      dma_chunk64(bp[qb] != nullptr ? bp[qb] : zero, stage + ATILE + (qb * NW + w) * 1024);
+      if (bp[qb] != nullptr) bp[qb] += bstep;
+    }
+  };
+  // (B loads of stages past the end read rows >= R of w: redirect them too)
+  int b_left[QB];
+#pragma unroll
+  for (int q = 0; q < QB; ++q) b_left[q] = T;
+  auto issue_checked = [&](int q, char* stage) {
+    if (q >= QA) {
+      const int qb = q - QA;
+      if (b_left[qb] <= 0) {
+        dma_chunk64(zero, stage + ATILE + (qb * NW + w) * 1024);
+        return;
+      }
+      --b_left[qb];
+    }
+    issue(q, stage);
+  };
+
+  int fa[NI], fb[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int row = 128 * wm + 32 * i + (l & 31);
+    fa[i] = row * DROWB + (((l >> 5) ^ dma_swz(row)) << 4);
+  }
+  const int mrow = 8 * (l >> 5) + ((l >> 2) & 3);
+  const int chb = (16 * ((l >> 4) & 1) + 4 * (l & 3)) * 2;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) fb[j] = ATILE + mrow * BROWB + 64 * ((2 * wn + j) ^ (mrow & 3)) + chb;
+  auto lda_ = [&](const char* stage, int o, int ks) { return frag(*reinterpret_cast<const uint4*>(stage + (o ^ (ks << 5)))); };
+  auto ldb_ = [&](const char* stage, int o, int ks) { return tn_frag(stage + o + 16 * ks * BROWB, stage + o + (16 * ks + 4) * BROWB); };
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x16{0};
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+#pragma unroll
+    for (int q = 0; q < LPS; ++q) issue_checked(q, smem + d * STAGE);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");
+  __syncthreads();
+  bf16x8 a[2][NI], b[2][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) a[0][i] = lda_(smem, fa[i], 0);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) b[0][j] = ldb_(smem, fb[j], 0);
+  int cur = 0, fill = D;
+  for (int st = 0; st < T; ++st) {
+    const char* sc = smem + cur * STAGE;
+    cur = cur + 1 == NS ? 0 : cur + 1;
+    const char* sn = smem + cur * STAGE;
+    char* sl = smem + fill * STAGE;
+    fill = fill + 1 == NS ? 0 : fill + 1;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      const char* src = ks + 1 < KS ? sc : sn;  // next step's fragments; the next stage was published a barrier ago
+      const int kn = ks + 1 < KS ? ks + 1 : 0;
+#pragma unroll
+      for (int i = 0; i < NI; ++i) a[n][i] = lda_(src, fa[i], kn);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) b[n][j] = ldb_(src, fb[j], kn);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int m = 0; m < MF; ++m) {
+        const int i = m / NJ, j = m % NJ;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
+        if (m == 2 || m == 6) {
+          __builtin_amdgcn_sched_barrier(0);
+          issue_checked(ks * 2 + (m == 6), sl);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  big_epilogue<NJ, 64>(acc, ep, smem + (size_t)w * (NS * STAGE / NW), i0 + 128 * wm, j0 + 64 * wn, l, I, J);
+}
+
 // column sums in two deterministic steps: partial sums over chunks of 128 rows, then the chunks in order
 constexpr int kColsumRows = 128;
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const bf16_t* __restrict__ z, float* __restrict__ part,
@@ -630,6 +771,12 @@ size_t linear_wgrad_big_scratch_bytes(int M, int N, int K) { return (size_t)M * 
 hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                                  int N, int K, void* scratch, size_t scratch_bytes) {
   BigEpilogue ep = {nullptr, mask, 0, dx, nullptr, K};
+  if (g_wgrad_tn && (N % DK) == 0 && (K % 8) == 0 && ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(w)) & 15) == 0 &&
+      (size_t)M * N < ((size_t)1 << 31)) {  // w as stored: transposing LDS reads on the B side
+    const int ti = (M + GM - 1) / GM, tj = (K + GN - 1) / GN;
+    gemm_nt_kernel<<<ti * tj, 512, 0, s>>>(dz, N, w, K, ep, M, K, N, ti, tj);
+    return hipGetLastError();
+  }
   if (scratch && M >= 2048 && scratch_bytes >= linear_dgrad_big_scratch_bytes(N, K)) {  // worth a pass over w
     bf16_t* wt = static_cast<bf16_t*>(scratch);  // [K][N]
     hipError_t e = transpose_bf16(s, w, wt, N, K);
