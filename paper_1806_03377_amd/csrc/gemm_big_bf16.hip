@@ -28,6 +28,12 @@ struct BigEpilogue {
   bf16_t* out;         // [I][J] bf16, or
   float* out_f;        // [I][J] fp32 (no rounding; bias/ReLU still applied)
   int ldo;             // row stride of out / out_f / mask (elements)
+  // Momentum-SGD step fused into the store (weight gradients): the result g is not written; instead
+  // m <- mu*m + g; w <- w - lr*m; ring <- bf16(w) on [I][J] arrays with row stride ldo.  Null: off.
+  float* upd_master;
+  float* upd_mom;
+  bf16_t* upd_ring;
+  float lr, mu;
 };
 
 // Epilogue of one wave's 128 x WCOLS sub-tile (accumulators acc[4][NJ], top-left corner row0, col_base): bias,
@@ -42,7 +48,7 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row_base = row0 + 32 * i;
-      if (ep.out_f) {
+      if (ep.out_f || ep.upd_master) {
         float* sf = reinterpret_cast<float*>(stage);  // [32][FLD]
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
@@ -63,7 +69,21 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
           const int row = row_base + rr, c = col_base + cc;
           if (row < I && c < J) {
             const float4 v = *reinterpret_cast<const float4*>(&sf[rr * FLD + cc]);
-            *reinterpret_cast<float4*>(ep.out_f + (size_t)row * ep.ldo + c) = v;
+            const size_t off = (size_t)row * ep.ldo + c;
+            if (ep.upd_master) {
+              float4 mm = *reinterpret_cast<const float4*>(ep.upd_mom + off);
+              float4 ms = *reinterpret_cast<const float4*>(ep.upd_master + off);
+              mm.x = ep.mu * mm.x + v.x; mm.y = ep.mu * mm.y + v.y; mm.z = ep.mu * mm.z + v.z; mm.w = ep.mu * mm.w + v.w;
+              ms.x -= ep.lr * mm.x; ms.y -= ep.lr * mm.y; ms.z -= ep.lr * mm.z; ms.w -= ep.lr * mm.w;
+              *reinterpret_cast<float4*>(ep.upd_mom + off) = mm;
+              *reinterpret_cast<float4*>(ep.upd_master + off) = ms;
+              uint2 o;
+              o.x = f2bf(ms.x) | ((uint32_t)f2bf(ms.y) << 16);
+              o.y = f2bf(ms.z) | ((uint32_t)f2bf(ms.w) << 16);
+              *reinterpret_cast<uint2*>(ep.upd_ring + off) = o;
+            } else {
+              *reinterpret_cast<float4*>(ep.out_f + off) = v;
+            }
           }
         }
       } else {
@@ -121,7 +141,13 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
         float v = acc[i][j][r] + bv;
         if (ep.relu) v = fmaxf(v, 0.f);
         const size_t off = (size_t)row * ep.ldo + c;
-        if (ep.out_f) {
+        if (ep.upd_master) {
+          const float m = ep.mu * ep.upd_mom[off] + v;
+          const float wv = ep.upd_master[off] - ep.lr * m;
+          ep.upd_mom[off] = m;
+          ep.upd_master[off] = wv;
+          ep.upd_ring[off] = f2bf(wv);
+        } else if (ep.out_f) {
           ep.out_f[off] = v;
         } else {
           uint16_t o = f2bf(v);
@@ -815,6 +841,45 @@ hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
   }
   if (e != hipSuccess) return e;
   if (db && !db_done) colsum_kernel<<<(N + 255) / 256, 256, 0, s>>>(dz, db, M, N);
+  return hipGetLastError();
+}
+
+
+// g = dz^T x fused with the momentum-SGD step (see BigEpilogue) when the transposing-read kernel applies; otherwise
+// g goes to `part` (N*K + N floats) and the separate reduce + update kernel applies the step.  The bias uses the
+// column sums of dz either way.  part may be null only if the fused kernel is known to apply.
+hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int M, int N,
+                                        int K, float* master_w, float* mom_w, bf16_t* ring_w, float* master_b,
+                                        float* mom_b, bf16_t* ring_b, float lr, float mu, void* scratch,
+                                        size_t scratch_bytes) {
+  const size_t n_w = (size_t)N * K;
+  const bool fused = g_wgrad_tn && (N % 8) == 0 && (K % 8) == 0 &&
+                     ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(x) |
+                       reinterpret_cast<uintptr_t>(master_w) | reinterpret_cast<uintptr_t>(mom_w)) & 15) == 0 &&
+                     (reinterpret_cast<uintptr_t>(ring_w) & 7) == 0;
+  if (!fused) {
+    if (!part) return hipErrorInvalidValue;
+    hipError_t e = linear_wgrad_big_bf16(s, dz, x, part, master_b ? part + n_w : nullptr, M, N, K, scratch, scratch_bytes);
+    if (e != hipSuccess) return e;
+    return wgrad_reduce_update(s, part, 1, 0, n_w, master_b ? N : 0, master_w, mom_w, ring_w, master_b, mom_b, ring_b, lr, mu);
+  }
+  if (master_b) {  // bias first: its column sums use the scratch
+    if (!part) return hipErrorInvalidValue;
+    float* db = part + n_w;
+    const int chunks = (M + kColsumRows - 1) / kColsumRows;
+    if (scratch && scratch_bytes >= (size_t)chunks * N * sizeof(float)) {
+      float* cp = static_cast<float*>(scratch);
+      colsum_partial_kernel<<<dim3((N + 255) / 256, chunks), 256, 0, s>>>(dz, cp, M, N);
+      colsum_final_kernel<<<(N + 255) / 256, 256, 0, s>>>(cp, db, chunks, N);
+    } else {
+      colsum_kernel<<<(N + 255) / 256, 256, 0, s>>>(dz, db, M, N);
+    }
+    hipError_t e = wgrad_reduce_update(s, db, 1, 0, 0, N, nullptr, nullptr, nullptr, master_b, mom_b, ring_b, lr, mu);
+    if (e != hipSuccess) return e;
+  }
+  BigEpilogue ep = {nullptr, nullptr, 0, nullptr, nullptr, K, master_w, mom_w, ring_w, lr, mu};
+  const int tn = (N + GM - 1) / GM, tk = (K + GN - 1) / GN;
+  gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk);
   return hipGetLastError();
 }
 

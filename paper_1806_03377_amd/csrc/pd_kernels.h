@@ -35,6 +35,15 @@ hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
 hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* dw, float* db, int M, int N,
                                  int K, void* scratch, size_t scratch_bytes);
 
+// The weight gradient of a many-row product fused with the momentum-SGD step: g = dz^T x (+ column sums of dz for
+// the bias); m <- mu*m + g; master <- master - lr*m; ring <- bf16(master).  `part` (N*K + N floats) receives g only
+// when the fused kernel does not apply (odd sizes or alignment); the bias gradient always passes through part + N*K.
+// master_b may be null (no bias).  scratch as for linear_wgrad_big_bf16.
+hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int M, int N,
+                                        int K, float* master_w, float* mom_w, bf16_t* ring_w, float* master_b,
+                                        float* mom_b, bf16_t* ring_b, float lr, float mu, void* scratch,
+                                        size_t scratch_bytes);
+
 // out[M][C] = a[M][R] * w as fp32 PARTIAL sums ws[split][M][C] (no epilogue): the caller's own kernel adds them
 // in split order.  a has row stride lda; w is [C][R] (w_rows_are_reduction = false) or [R][C] (true).
 hipError_t gemm_partial_bf16(hipStream_t s, bool w_rows_are_reduction, const bf16_t* a, int lda, const bf16_t* w, int M,

@@ -1264,19 +1264,19 @@ int pd_update(pd_stage* st) {
       const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
       float* part = reinterpret_cast<float*>(st->part + L.part_off);
       const size_t n_w1 = (size_t)n_out * L.in;
-      PD_HIP(pd::linear_wgrad_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz), reinterpret_cast<const pd::bf16_t*>(x),
-                                       part, part + n_w1, L.rows, n_out, L.in, st->ws, st->ws_bytes));
-      PD_HIP(pd::wgrad_reduce_update(s, part, 1, 0, n_w1, n_out, st->master + L.w_off, st->mom + L.w_off,
-                                     ro + L.w_off, st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr,
-                                     st->mu));
+      PD_HIP(pd::linear_wgrad_update_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
+                                              reinterpret_cast<const pd::bf16_t*>(x), part, L.rows, n_out, L.in,
+                                              st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
+                                              st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr, st->mu,
+                                              st->ws, st->ws_bytes));
       if (L.kind == K_LSTM) {
         float* part2 = reinterpret_cast<float*>(st->part + L.part2_off);
         const size_t n_w2 = (size_t)n_out * L.out, o2 = L.w_off + n_w1;
-        PD_HIP(pd::linear_wgrad_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
-                                         reinterpret_cast<const pd::bf16_t*>(slot + L.y_off), part2, nullptr, L.rows,
-                                         n_out, L.out, st->ws, st->ws_bytes));
-        PD_HIP(pd::wgrad_reduce_update(s, part2, 1, 0, n_w2, 0, st->master + o2, st->mom + o2, ro + o2,
-                                       nullptr, nullptr, nullptr, st->lr, st->mu));
+        (void)n_w2;
+        PD_HIP(pd::linear_wgrad_update_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
+                                                reinterpret_cast<const pd::bf16_t*>(slot + L.y_off), part2, L.rows,
+                                                n_out, L.out, st->master + o2, st->mom + o2, ro + o2, nullptr, nullptr,
+                                                nullptr, st->lr, st->mu, st->ws, st->ws_bytes));
       }
       PD_HIP(st->mark(2, l));
     } else if (st->bf16) {
@@ -1612,11 +1612,13 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
   if (plain_product_many_rows(g)) {
     const size_t unit = (size_t)g.Co * g.Ci + g.Co;  // floats per scratch unit; the first holds dw and db
     const size_t extra = (size_t)(wgrad_scratch_units(g) - 1) * unit * sizeof(float);
-    splits = 1;
-    PD_HIP(pd::linear_wgrad_big_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
-                                     part_scratch, part_scratch + (size_t)g.Co * g.Ci, g.N, g.Co, g.Ci,
-                                     part_scratch + unit, extra));
-  } else
+    PD_HIP(pd::linear_wgrad_update_big_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
+                                            part_scratch, g.N, g.Co, g.Ci, master_w, mom_w,
+                                            static_cast<pd::bf16_t*>(ring_out_w), master_b, mom_b,
+                                            static_cast<pd::bf16_t*>(ring_out_b), lr, momentum, part_scratch + unit,
+                                            extra));
+    return PD_OK;
+  }
   PD_HIP(pd::conv_wgrad_partial_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
                                      part_scratch, splits, g));
   PD_HIP(pd::wgrad_reduce_update(s, part_scratch, splits, 0, (size_t)g.Co * g.kh * g.kw * g.Ci, g.Co, master_w, mom_w,
