@@ -232,6 +232,52 @@ def bench_inception(args, pd, gen, torch, np, dev):
     print(json.dumps(out))
 
 
+def bench_mlp4(args, pd, gen, torch, np, dev):
+    """Config 1, the parity configuration: 4-stage MLP in fp32 (Linear 256->256 + ReLU per stage, the last stage
+    Linear 256->10 + loss), minibatch 32, NOAM 4, 64 minibatches through pd_pipeline_run on four streams.  The
+    work per op is tiny (12.6 MFLOP per hidden stage and step): this measures launch and event latency, so the
+    result is reported as microseconds per op, not against a roofline."""
+    B, M = 32, 64
+    reps = max(1, min(args.steps, 50))
+    sl = gen.config1_mlp(256, 10, 4)
+    S = len(sl)
+    seed = gen.BASE_SEED + 0
+    streams = [torch.cuda.Stream(device=dev) for _ in range(S)]
+    hs, arenas = [], []
+    for s in range(S):
+        cfg = pd.make_config(sl[s], stage_index=s, num_stages=S, noam=4, minibatch=B, precision=pd.PD_F32, lr=0.01,
+                             momentum=0.9, stream=streams[s].cuda_stream)
+        nbytes = pd.pd_stage_query_bytes(cfg)
+        arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        hs.append(pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)); arenas.append(arena)
+        pd.pd_stage_set_params(hs[-1], gen.init_params(seed, f"s{s}", sl[s]))
+    xs = torch.from_numpy(gen.normal(seed, "X", (M, B, 256))).to(dev)
+    ls = torch.from_numpy(gen.labels(seed, "Y", (M, B), 10)).to(dev)
+    losses = torch.zeros(M, dtype=torch.float32, device=dev)
+    for _ in range(max(1, min(args.warmup, 3))):
+        pd.pd_pipeline_run(hs, M, xs.data_ptr(), ls.data_ptr(), losses.data_ptr())
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        pd.pd_pipeline_run(hs, M, xs.data_ptr(), ls.data_ptr(), losses.data_ptr())
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / (reps * M)   # per minibatch through all four stages
+    ops = 3 * S                                          # F, B, U on each stage
+    out = {"metric": METRIC, "value": B / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": reps * M, "warmup": M,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+           "data": "synthetic",
+           "config": {"workload": "4-stage MLP (Linear 256->256 + ReLU x3, Linear 256->10 + loss), fp32, minibatch 32, NOAM 4, "
+                      "64 minibatches per pipeline run on four streams; step = one minibatch through all stages",
+                      "minibatch": B, "minibatches_per_run": M},
+           "us_per_op": 1e3 * ms / ops, "ops_per_minibatch": ops,
+           "roofline": {"bound": "latency", "kernel": "none dominates: 12 ops of a few microseconds per minibatch",
+                        "achieved": None, "peak": None, "unit": None, "frac": None, "traffic": None},
+           "final_loss": float(losses[-1].item())}
+    for h in hs:
+        pd.pd_stage_destroy(h)
+    print(json.dumps(out))
+
+
 def bench_gemm_sweep(args, pd, gen, torch, np, dev):
     """The stage's three contractions on their own at the VGG16 classifier's K, N with the row count M swept from
     the configured minibatch (64, HBM-bound) into the compute-bound regime: achieved TFLOP/s and % of the bf16
@@ -364,11 +410,12 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition"],
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition", "mlp4"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
                          "s2vt (the two LSTM stages as a 2-stream pipeline), inception (four stages of branched "
                          "convolution blocks as a 4-stream pipeline), gemm_sweep (the Linear kernels over row counts), "
-                         "partition (layer profile of all of VGG16 on the device, then the partitioner)")
+                         "partition (layer profile of all of VGG16 on the device, then the partitioner), mlp4 (the 4-stage fp32 MLP, "
+                         "a launch-latency case)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs all pipeline stages on ONE GPU; --gpus must be 1", file=sys.stderr)
@@ -395,6 +442,8 @@ def main():
         return bench_gemm_sweep(args, pd, gen, torch, np, dev)
     if args.workload == "partition":
         return bench_partition(args, pd, gen, torch, np, dev)
+    if args.workload == "mlp4":
+        return bench_mlp4(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
     n_in, classes = layers[0][1], layers[-1][1]
     seed = gen.BASE_SEED + 1
