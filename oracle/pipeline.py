@@ -174,13 +174,19 @@ def _out_quantiser(layers, li, q):
 
 class Stage:
     def __init__(self, layers, params_fp32, depth: int, mode: str = "f32",
-                 lr: float = 0.01, momentum: float = 0.9, stashing: bool = True, ring_depth: int = 0):
+                 lr: float = 0.01, momentum: float = 0.9, stashing: bool = True, ring_depth: int = 0,
+                 optimizer: str = "sgd", eps: float = 1.0):
         self.layers = list(layers)
         self.depth = int(depth)
         self.ring = int(ring_depth) if ring_depth else self.depth   # versions kept (vertical sync: the input stage's)
         self.mode = mode
         self.q = L.quantiser(mode)
         self.lr, self.mu = float(lr), float(momentum)
+        # "sgd": momentum SGD (Section 5.1, VGG16 and S2VT).  "rmsprop" (Section 5.1, Inception-v3; the paper names
+        # the optimiser and its learning rate only): the common library form, with `momentum` as the decay a --
+        #     v <- a v + (1 - a) g^2 ;  w <- w - lr g / (sqrt(v) + eps)
+        # one state buffer per stage either way (self.mom holds v)
+        self.optimizer, self.eps = optimizer, float(eps)
         self.stashing = stashing              # False = the naive pipeline of Section 3.4 (negative control)
         self.master = np.asarray(params_fp32, dtype=np.float64).copy()
         self.versions = [self.q(self.master)]  # versions[v] = weights as the layers read them
@@ -262,8 +268,14 @@ class Stage:
     def update(self, mb: int = -1):
         if self.grad is None:
             raise RuntimeError("update without a pending gradient")
-        self.mom = self.mu * self.mom + self.grad
-        self.master = self.master - self.lr * self.mom            # onto the latest weights
+        if self.optimizer == "sgd":
+            self.mom = self.mu * self.mom + self.grad
+            self.master = self.master - self.lr * self.mom        # onto the latest weights
+        elif self.optimizer == "rmsprop":
+            self.mom = self.mu * self.mom + (1.0 - self.mu) * self.grad * self.grad
+            self.master = self.master - self.lr * self.grad / (np.sqrt(self.mom) + self.eps)
+        else:
+            raise ValueError(self.optimizer)
         self.grad = None
         self.latest += 1
         self.versions.append(self.q(self.master))
@@ -278,7 +290,7 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                  mode: str = "f32", lr: float = 0.01, momentum: float = 0.9,
                  stashing: bool = True, depth_override: int = 0, keep_log: bool = False,
                  out_grads=None, order: Optional[list] = None, input_grad: bool = False,
-                 vertical_sync: bool = False):
+                 vertical_sync: bool = False, optimizer: str = "sgd", eps: float = 1.0):
     """All stages, each following its own static op list, run as soon as their data exists.
 
     inputs[i] / labels[i] belong to minibatch i.  Returns (stages, losses).  Any
@@ -295,7 +307,7 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
     S, M = len(stage_layers), len(inputs)
     depths = [depth_override or in_flight_depth(S, noam_, s) for s in range(S)]
     stages = [Stage(stage_layers[s], stage_params[s], depths[s], mode, lr, momentum, stashing,
-                    ring_depth=depths[0] if vertical_sync else 0)
+                    ring_depth=depths[0] if vertical_sync else 0, optimizer=optimizer, eps=eps)
               for s in range(S)]
     if keep_log:
         for st in stages:

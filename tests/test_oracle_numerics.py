@@ -319,3 +319,31 @@ def test_vertical_sync_worked_example_and_ring():
         st.forward(4, x[0], version=2)      # latest is 4, the ring holds 3 and 4
     with pytest.raises(RuntimeError):
         st.forward(4, x[0], version=5)
+
+
+# ---- RMSProp (the paper's optimiser for Inception-v3, Section 5.1): library routine on the sequential case ----
+
+@pytest.mark.parametrize("alpha,eps", [(0.9, 1.0), (0.99, 1e-8)])
+def test_rmsprop_reduces_to_the_library_routine(alpha, eps):
+    sl = [[("linear", 12, 12, True), ("linear", 12, 5, False), ("softmax_xent", 5)]]
+    params = _params(sl)
+    xs, ys = _data(9, 6, 12, 5)
+    stages, losses = run_pipeline(sl, params, xs, ys, 1, lr=0.045, momentum=alpha, optimizer="rmsprop", eps=eps)
+    tps = [torch.tensor(p, requires_grad=True) for p in params]
+    opt = torch.optim.RMSprop(tps, lr=0.045, alpha=alpha, eps=eps)
+    ref_l = []
+    for x, y in zip(xs, ys):
+        opt.zero_grad()
+        l = _torch_model_loss(tps, sl, torch.tensor(x), torch.tensor(y, dtype=torch.long))
+        l.backward()
+        opt.step()
+        ref_l.append(l.item())
+    assert np.allclose(losses, ref_l, rtol=1e-10)
+    assert np.allclose(stages[0].master, tps[0].detach().numpy(), rtol=1e-9, atol=1e-12)
+    # hand value of one step: v = (1 - a) g^2, w' = w - lr g / (sqrt(v) + eps)
+    st = Stage(sl[0], params[0], depth=1, lr=0.045, momentum=alpha, optimizer="rmsprop", eps=eps)
+    st.forward(0, xs[0], ys[0]); st.backward(0, None, need_dx=False)
+    g = st.grad.copy()
+    st.update(0)
+    assert np.allclose(st.mom, (1 - alpha) * g * g, rtol=1e-15)
+    assert np.allclose(st.master, params[0] - 0.045 * g / (np.sqrt((1 - alpha) * g * g) + eps), rtol=1e-14)
