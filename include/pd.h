@@ -65,6 +65,14 @@ typedef enum { PD_F32 = 0, PD_BF16_F32ACC = 1 } pd_precision;
 
 typedef enum { PD_OP_F = 0, PD_OP_B = 1, PD_OP_U = 2 } pd_op_kind;
 
+/* The update rule of a stage (Section 5.1: SGD with momentum for VGG16 and S2VT, RMSProp for Inception-v3), applied
+ * to the fp32 latest weights w with gradient g and ONE fp32 state value per parameter (what pd_stage_get_momentum
+ * returns):
+ *   PD_OPT_SGD_MOMENTUM  m <- momentum*m + g ;                      w <- w - lr*m
+ *   PD_OPT_RMSPROP       v <- momentum*v + (1 - momentum)*g*g ;     w <- w - lr*g / (sqrt(v) + eps)
+ *                        (the `momentum` field is the decay of the squared-gradient average) */
+typedef enum { PD_OPT_SGD_MOMENTUM = 0, PD_OPT_RMSPROP = 1 } pd_optimizer;
+
 /* One entry of a stage's static schedule (integers only).
  * F, B: `version` = weight version read; U: `version` = weight version produced.
  * `slot` = version mod depth (ring slot read, or written for U). */
@@ -125,7 +133,7 @@ typedef struct {
   int32_t minibatch;          /* rows per minibatch                                              */
   int32_t precision;          /* pd_precision                                                    */
   float lr;                   /* learning rate (constant)                                        */
-  float momentum;             /* mu in  m <- mu*m + g ; w <- w - lr*m  (Section 5.1: 0.9, 0.01)  */
+  float momentum;             /* mu in  m <- mu*m + g ; w <- w - lr*m  (Section 5.1: 0.9, 0.01); RMSProp: decay  */
   int32_t n_layers;
   const pd_layer_desc* layers; /* host; copied at create                                          */
   void* stream;               /* hipStream_t, borrowed; all of the stage's kernels run on it      */
@@ -133,6 +141,8 @@ typedef struct {
                                  INPUT stage (max(1, noam), or in_flight_override) so that a forward pass may ask
                                  for the version its minibatch was tagged with there (pd_forward_versioned);
                                  the in-flight depth is unchanged                                  */
+  int32_t optimizer;          /* pd_optimizer; 0 = momentum SGD (the default of a zeroed field)                 */
+  float eps;                  /* RMSProp: added to sqrt(v); must be > 0 there, ignored otherwise               */
 } pd_stage_config;
 
 /* --- schedule (pure host, no GPU touched) -------------------------------------------------

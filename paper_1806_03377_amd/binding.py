@@ -24,6 +24,7 @@ _lib = C.CDLL(LIB_PATH)
 PD_OK, PD_EINVAL, PD_ESTATE, PD_ENOMEM, PD_EHIP = 0, -1, -2, -3, -4
 PD_F32, PD_BF16_F32ACC = 0, 1
 PD_OP_F, PD_OP_B, PD_OP_U = 0, 1, 2
+PD_OPT_SGD_MOMENTUM, PD_OPT_RMSPROP = 0, 1
 PD_LINEAR, PD_SOFTMAX_XENT, PD_CONV2D, PD_MAXPOOL2D, PD_LSTM = 0, 1, 2, 3, 4
 PD_AVGPOOL2D, PD_CONCAT_BEGIN, PD_BRANCH, PD_CONCAT_END = 5, 6, 7, 8
 
@@ -56,7 +57,8 @@ class pd_stage_config(C.Structure):
     _fields_ = [("stage_index", C.c_int32), ("num_stages", C.c_int32), ("noam", C.c_int32),
                 ("in_flight_override", C.c_int32), ("minibatch", C.c_int32), ("precision", C.c_int32),
                 ("lr", C.c_float), ("momentum", C.c_float), ("n_layers", C.c_int32),
-                ("layers", C.POINTER(pd_layer_desc)), ("stream", C.c_void_p), ("vertical_sync", C.c_int32)]
+                ("layers", C.POINTER(pd_layer_desc)), ("stream", C.c_void_p), ("vertical_sync", C.c_int32),
+                ("optimizer", C.c_int32), ("eps", C.c_float)]
 
 
 _vp, _sz, _i32, _f32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_float
@@ -220,10 +222,11 @@ def layer_descs(layers: Sequence[tuple], in_hw=None):
 
 
 def make_config(layers, *, stage_index=0, num_stages=1, noam=1, in_flight_override=0, minibatch=1,
-                precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None, vertical_sync=False):
+                precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None, vertical_sync=False,
+                optimizer=PD_OPT_SGD_MOMENTUM, eps=0.0):
     descs = layer_descs(layers, in_hw)
     cfg = pd_stage_config(stage_index, num_stages, noam, in_flight_override, minibatch, precision, lr, momentum,
-                          len(descs), descs, stream, 1 if vertical_sync else 0)
+                          len(descs), descs, stream, 1 if vertical_sync else 0, optimizer, eps)
     cfg._keepalive = descs
     return cfg
 

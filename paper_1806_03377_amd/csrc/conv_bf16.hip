@@ -684,7 +684,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* _
                                                                   size_t stride, size_t n_w, int n_b, float* __restrict__ master_w,
                                                                   float* __restrict__ mom_w, bf16_t* __restrict__ ring_w,
                                                                   float* __restrict__ master_b, float* __restrict__ mom_b,
-                                                                  bf16_t* __restrict__ ring_b, float lr, float mu) {
+                                                                  bf16_t* __restrict__ ring_b, UpdateRule rule) {
   const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t e = tid / G;
   const int j = (int)(tid % G);
@@ -699,8 +699,8 @@ __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* _
   float* ms = e < n_w ? master_w + e : master_b + (e - n_w);
   float* mm = e < n_w ? mom_w + e : mom_b + (e - n_w);
   bf16_t* rr = e < n_w ? ring_w + e : ring_b + (e - n_w);
-  const float m = mu * *mm + gsum;
-  const float wv = *ms - lr * m;
+  float m = *mm, wv = *ms;
+  apply_update(rule, gsum, m, wv);
   *mm = m;
   *ms = wv;
   *rr = f2bf(wv);
@@ -845,7 +845,7 @@ hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t
 
 hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t stride, size_t n_w, int n_b,
                                float* master_w, float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b,
-                               bf16_t* ring_b, float lr, float mu) {
+                               bf16_t* ring_b, UpdateRule rule) {
   const size_t n = n_w + n_b;
   if (!stride) stride = n;
   // lanes per element: enough threads to fill the chip, never more than there are partial sums
@@ -854,7 +854,7 @@ hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, siz
   const unsigned blocks = (unsigned)((n * G + 255) / 256);
 #define PD_REDUCE(GG)                                                                                              \
   wgrad_reduce_update_kernel<GG><<<blocks, 256, 0, s>>>(part, splits, stride, n_w, n_b, master_w, mom_w, ring_w, \
-                                                        master_b, mom_b, ring_b, lr, mu)
+                                                        master_b, mom_b, ring_b, rule)
   switch (G) {
     case 1: PD_REDUCE(1); break;
     case 2: PD_REDUCE(2); break;

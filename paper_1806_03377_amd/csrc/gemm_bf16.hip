@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
   float* __restrict__ mom_b = L.mom_b;
   bf16_t* __restrict__ ring_b = L.ring_b;
   const int M = L.M ? L.M : batch.M, N = L.N, K = L.K;
-  const float lr = batch.lr, mu = batch.mu;
+  const UpdateRule rule = batch.rule;
   constexpr int GLD = TK + 4;
   constexpr int kSlots = TN * TK / 4 / kThreads;  // float4 elements per thread in phase 2
   constexpr int NB = TN / 32;                     // 32-row MFMA blocks per wave (waves split the k columns)
@@ -375,8 +375,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
         m = *reinterpret_cast<const float4*>(mom + off);
         wv = *reinterpret_cast<const float4*>(master + off);
       }
-      m.x = mu * m.x + g.x; m.y = mu * m.y + g.y; m.z = mu * m.z + g.z; m.w = mu * m.w + g.w;
-      wv.x -= lr * m.x; wv.y -= lr * m.y; wv.z -= lr * m.z; wv.w -= lr * m.w;
+      apply_update(rule, g.x, m.x, wv.x); apply_update(rule, g.y, m.y, wv.y);
+      apply_update(rule, g.z, m.z, wv.z); apply_update(rule, g.w, m.w, wv.w);
       nt_store4(mom + off, m);     // streamed once per step: keep these lines out of the caches
       nt_store4(master + off, wv);
       uint2 pk;
@@ -393,8 +393,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
     if (n < N) {
       float g = 0.f;
       for (int m = 0; m < M; ++m) g += bf2f(dZ[(size_t)m * N + n]);
-      const float mv = mu * mom_b[n] + g;
-      const float bv = master_b[n] - lr * mv;
+      float mv = mom_b[n], bv = master_b[n];
+      apply_update(rule, g, mv, bv);
       mom_b[n] = mv;
       master_b[n] = bv;
       ring_b[n] = f2bf(bv);

@@ -33,7 +33,7 @@ struct BigEpilogue {
   float* upd_master;
   float* upd_mom;
   bf16_t* upd_ring;
-  float lr, mu;
+  UpdateRule rule;
 };
 
 // Epilogue of one wave's 128 x WCOLS sub-tile (accumulators acc[4][NJ], top-left corner row0, col_base): bias,
@@ -73,8 +73,8 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
             if (ep.upd_master) {
               float4 mm = *reinterpret_cast<const float4*>(ep.upd_mom + off);
               float4 ms = *reinterpret_cast<const float4*>(ep.upd_master + off);
-              mm.x = ep.mu * mm.x + v.x; mm.y = ep.mu * mm.y + v.y; mm.z = ep.mu * mm.z + v.z; mm.w = ep.mu * mm.w + v.w;
-              ms.x -= ep.lr * mm.x; ms.y -= ep.lr * mm.y; ms.z -= ep.lr * mm.z; ms.w -= ep.lr * mm.w;
+              apply_update(ep.rule, v.x, mm.x, ms.x); apply_update(ep.rule, v.y, mm.y, ms.y);
+              apply_update(ep.rule, v.z, mm.z, ms.z); apply_update(ep.rule, v.w, mm.w, ms.w);
               *reinterpret_cast<float4*>(ep.upd_mom + off) = mm;
               *reinterpret_cast<float4*>(ep.upd_master + off) = ms;
               uint2 o;
@@ -142,8 +142,8 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
         if (ep.relu) v = fmaxf(v, 0.f);
         const size_t off = (size_t)row * ep.ldo + c;
         if (ep.upd_master) {
-          const float m = ep.mu * ep.upd_mom[off] + v;
-          const float wv = ep.upd_master[off] - ep.lr * m;
+          float m = ep.upd_mom[off], wv = ep.upd_master[off];
+          apply_update(ep.rule, v, m, wv);
           ep.upd_mom[off] = m;
           ep.upd_master[off] = wv;
           ep.upd_ring[off] = f2bf(wv);
@@ -850,7 +850,7 @@ hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
 // column sums of dz either way.  part may be null only if the fused kernel is known to apply.
 hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int M, int N,
                                         int K, float* master_w, float* mom_w, bf16_t* ring_w, float* master_b,
-                                        float* mom_b, bf16_t* ring_b, float lr, float mu, void* scratch,
+                                        float* mom_b, bf16_t* ring_b, UpdateRule rule, void* scratch,
                                         size_t scratch_bytes) {
   const size_t n_w = (size_t)N * K;
   const bool fused = g_wgrad_tn && (N % 8) == 0 && (K % 8) == 0 &&
@@ -861,7 +861,7 @@ hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const b
     if (!part) return hipErrorInvalidValue;
     hipError_t e = linear_wgrad_big_bf16(s, dz, x, part, master_b ? part + n_w : nullptr, M, N, K, scratch, scratch_bytes);
     if (e != hipSuccess) return e;
-    return wgrad_reduce_update(s, part, 1, 0, n_w, master_b ? N : 0, master_w, mom_w, ring_w, master_b, mom_b, ring_b, lr, mu);
+    return wgrad_reduce_update(s, part, 1, 0, n_w, master_b ? N : 0, master_w, mom_w, ring_w, master_b, mom_b, ring_b, rule);
   }
   if (master_b) {  // bias first: its column sums use the scratch
     if (!part) return hipErrorInvalidValue;
@@ -874,10 +874,10 @@ hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const b
     } else {
       colsum_kernel<<<(N + 255) / 256, 256, 0, s>>>(dz, db, M, N);
     }
-    hipError_t e = wgrad_reduce_update(s, db, 1, 0, 0, N, nullptr, nullptr, nullptr, master_b, mom_b, ring_b, lr, mu);
+    hipError_t e = wgrad_reduce_update(s, db, 1, 0, 0, N, nullptr, nullptr, nullptr, master_b, mom_b, ring_b, rule);
     if (e != hipSuccess) return e;
   }
-  BigEpilogue ep = {nullptr, nullptr, 0, nullptr, nullptr, K, master_w, mom_w, ring_w, lr, mu};
+  BigEpilogue ep = {nullptr, nullptr, 0, nullptr, nullptr, K, master_w, mom_w, ring_w, rule};
   const int tn = (N + GM - 1) / GM, tk = (K + GN - 1) / GN;
   gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk);
   return hipGetLastError();

@@ -23,7 +23,7 @@ struct EpiArgs {
   float* mom_b;
   const float* dz;     // UPDATE: dz[M][N] for the bias column sums
   int M;
-  float lr, mu;
+  UpdateRule rule;
 };
 
 // C[i][j] = sum_r A(i,r) B(r,j) with A(i,r) = a[i*a_is + r*a_rs], B(r,j) = b[r*b_rs + j*b_js]
@@ -73,9 +73,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     } else if (EPI == EPI_DGRAD) {
       e.out[off] = (e.mask && !(e.mask[off] > 0.f)) ? 0.f : acc[q];
     } else {
-      const float m = e.mu * e.mom[off] + acc[q];
+      float m = e.mom[off], wv = e.w_in[off];
+      apply_update(e.rule, acc[q], m, wv);
       e.mom[off] = m;
-      e.w_out[off] = e.w_in[off] - e.lr * m;
+      e.w_out[off] = wv;
     }
   }
   if (EPI == EPI_UPDATE && blockIdx.x == 0 && e.b_in && t < T32) {
@@ -83,9 +84,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     if (n < I) {
       float g = 0.f;
       for (int m = 0; m < e.M; ++m) g += e.dz[(size_t)m * I + n];
-      const float mv = e.mu * e.mom_b[n] + g;
+      float mv = e.mom_b[n], bv = e.b_in[n];
+      apply_update(e.rule, g, mv, bv);
       e.mom_b[n] = mv;
-      e.b_out[n] = e.b_in[n] - e.lr * mv;
+      e.b_out[n] = bv;
     }
   }
 }
@@ -114,10 +116,10 @@ hipError_t linear_dgrad_f32(hipStream_t s, const float* dz, const float* w, cons
 
 hipError_t linear_wgrad_update_f32(hipStream_t s, const float* dz, const float* x, const float* w_in, float* w_out,
                                    float* mom_w, const float* b_in, float* b_out, float* mom_b, int M, int N, int K,
-                                   float lr, float mu) {
+                                   UpdateRule rule) {
   EpiArgs e = {};
   e.w_in = w_in; e.w_out = w_out; e.mom = mom_w; e.b_in = b_in; e.b_out = b_out; e.mom_b = mom_b;
-  e.dz = dz; e.M = M; e.lr = lr; e.mu = mu;
+  e.dz = dz; e.M = M; e.rule = rule;
   dim3 grid((K + T32 - 1) / T32, (N + T32 - 1) / T32);
   // g[n][k] = sum_m dz[m][n] x[m][k]
   gemm_f32_kernel<EPI_UPDATE><<<grid, 256, 0, s>>>(dz, 1, N, x, K, 1, N, K, M, e);

@@ -9,6 +9,23 @@ namespace pd {
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
 
+// The step applied to a parameter w with gradient g and its one state value s (Section 5.1 names the optimisers):
+//   kind 0, momentum SGD:  s <- a s + g ;            w <- w - lr s
+//   kind 1, RMSProp:       s <- a s + (1 - a) g^2 ;  w <- w - lr g / (sqrt(s) + eps)
+struct UpdateRule {
+  float lr, a, eps;
+  int kind;
+};
+__host__ __device__ __forceinline__ void apply_update(const UpdateRule& u, float g, float& s, float& w) {
+  if (u.kind == 0) {
+    s = u.a * s + g;
+    w -= u.lr * s;
+  } else {
+    s = u.a * s + (1.f - u.a) * g * g;
+    w -= u.lr * g / (sqrtf(s) + u.eps);
+  }
+}
+
 // ---- bf16 x bf16 -> fp32-accumulate MFMA GEMMs (gemm_bf16.hip) ---------------------------------
 // Bytes of split-K scratch the fwd/dgrad launchers may use for this shape.
 size_t gemm_bf16_workspace_bytes(int M, int N, int K);
@@ -41,7 +58,7 @@ hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
 // master_b may be null (no bias).  scratch as for linear_wgrad_big_bf16.
 hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int M, int N,
                                         int K, float* master_w, float* mom_w, bf16_t* ring_w, float* master_b,
-                                        float* mom_b, bf16_t* ring_b, float lr, float mu, void* scratch,
+                                        float* mom_b, bf16_t* ring_b, UpdateRule rule, void* scratch,
                                         size_t scratch_bytes);
 
 // out[M][C] = a[M][R] * w as fp32 PARTIAL sums ws[split][M][C] (no epilogue): the caller's own kernel adds them
@@ -68,7 +85,7 @@ struct WgradLayer {
 struct WgradBatch {
   WgradLayer layer[kMaxWgradLayers];
   int count, M;
-  float lr, mu;
+  UpdateRule rule;
 };
 hipError_t linear_wgrad_update_bf16(hipStream_t s, const WgradBatch& batch);
 
@@ -120,7 +137,7 @@ hipError_t conv_wgrad_tr_partial_bf16(hipStream_t s, const bf16_t* dz, const bf1
 // Partial s starts at part + s*stride (stride 0 = n_w + n_b); n_b may be 0 to leave the bias alone.
 hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t stride, size_t n_w, int n_b,
                                float* master_w, float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b,
-                               bf16_t* ring_b, float lr, float mu);
+                               bf16_t* ring_b, UpdateRule rule);
 // General pooling over NHWC (window k x k, stride, zero padding `pad` on every side; C % 8 == 0):
 //   max: padding never wins; backward sends dy to the FIRST maximum of each window in row-major order and sums,
 //        per input position, the contributions of the windows that cover it in row-major window order
@@ -178,7 +195,7 @@ hipError_t linear_dgrad_f32(hipStream_t s, const float* dz, const float* w, cons
 // w_out <- w_in - lr*(m <- mu*m + dz^T x); w_in may equal w_out.
 hipError_t linear_wgrad_update_f32(hipStream_t s, const float* dz, const float* x, const float* w_in, float* w_out,
                                    float* mom_w, const float* b_in, float* b_out, float* mom_b, int M, int N, int K,
-                                   float lr, float mu);
+                                   UpdateRule rule);
 
 // ---- element-wise and loss kernels (misc_kernels.hip) --------------------------------------------
 hipError_t copy_bytes(hipStream_t s, const void* src, void* dst, size_t bytes);  // bytes % 4 == 0 or any

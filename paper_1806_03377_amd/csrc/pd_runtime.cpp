@@ -154,7 +154,7 @@ struct pd_stage {
   bool bf16 = false;
   bool has_loss = false;
   int classes = 0;
-  float lr = 0.f, mu = 0.f;
+  pd::UpdateRule rule = {0.f, 0.f, 0.f, 0};
   hipStream_t stream = nullptr;
   std::vector<Linear> lin;
   size_t esz = 4;
@@ -232,6 +232,8 @@ struct Plan {
 
 int make_plan(const pd_stage_config* c, Plan& p) {
   if (!c) return fail(PD_EINVAL, "config is null");
+  if (c->optimizer != PD_OPT_SGD_MOMENTUM && c->optimizer != PD_OPT_RMSPROP) return fail(PD_EINVAL, "unknown optimizer %d", c->optimizer);
+  if (c->optimizer == PD_OPT_RMSPROP && !(c->eps > 0.f)) return fail(PD_EINVAL, "RMSProp needs eps > 0");
   if (c->num_stages < 1 || c->stage_index < 0 || c->stage_index >= c->num_stages)
     return fail(PD_EINVAL, "stage_index %d outside [0, %d)", c->stage_index, c->num_stages);
   if (c->noam < 1) return fail(PD_EINVAL, "noam must be >= 1");
@@ -572,7 +574,8 @@ int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena
   st->stage_index = cfg->stage_index; st->num_stages = cfg->num_stages; st->noam = cfg->noam;
   st->depth = p.depth; st->in_depth = p.in_depth; st->ring_depth = p.ring_depth; st->vsync = cfg->vertical_sync != 0;
   st->B = p.B; st->bf16 = p.bf16; st->has_loss = p.has_loss;
-  st->classes = p.classes; st->lr = cfg->lr; st->mu = cfg->momentum;
+  st->classes = p.classes;
+  st->rule = pd::UpdateRule{cfg->lr, cfg->momentum, cfg->eps, cfg->optimizer};
   st->stream = static_cast<hipStream_t>(cfg->stream);
   st->lin = p.lin; st->esz = p.esz; st->n_params = p.n_params; st->p_pad = p.p_pad;
   st->in_bytes = p.in_bytes; st->out_bytes = p.out_bytes; st->stash_slot_bytes = p.stash_slot_bytes;
@@ -1244,7 +1247,7 @@ int pd_update(pd_stage* st) {
   const int nl = (int)st->lin.size();
   const int nv = st->latest + 1;
   pd::WgradBatch batch;
-  batch.count = 0; batch.M = st->B; batch.lr = st->lr; batch.mu = st->mu;
+  batch.count = 0; batch.M = st->B; batch.rule = st->rule;
   PD_HIP(st->mark(-1, 0));
   for (int l = 0; l < nl; ++l) {
     const Layer& L = st->lin[l];
@@ -1253,7 +1256,7 @@ int pd_update(pd_stage* st) {
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
       PD_HIP(pd::wgrad_reduce_update(s, reinterpret_cast<const float*>(st->part + L.part_off), L.splits, 0, L.n_w,
                                      (int)L.n_b, st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
-                                     st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr, st->mu));
+                                     st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->rule));
       PD_HIP(st->mark(2, l));
       continue;
     }
@@ -1267,7 +1270,7 @@ int pd_update(pd_stage* st) {
       PD_HIP(pd::linear_wgrad_update_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
                                               reinterpret_cast<const pd::bf16_t*>(x), part, L.rows, n_out, L.in,
                                               st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
-                                              st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->lr, st->mu,
+                                              st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->rule,
                                               st->ws, st->ws_bytes));
       if (L.kind == K_LSTM) {
         float* part2 = reinterpret_cast<float*>(st->part + L.part2_off);
@@ -1276,7 +1279,7 @@ int pd_update(pd_stage* st) {
         PD_HIP(pd::linear_wgrad_update_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
                                                 reinterpret_cast<const pd::bf16_t*>(slot + L.y_off), part2, L.rows,
                                                 n_out, L.out, st->master + o2, st->mom + o2, ro + o2, nullptr, nullptr,
-                                                nullptr, st->lr, st->mu, st->ws, st->ws_bytes));
+                                                nullptr, st->rule, st->ws, st->ws_bytes));
       }
       PD_HIP(st->mark(2, l));
     } else if (st->bf16) {
@@ -1309,7 +1312,7 @@ int pd_update(pd_stage* st) {
       float* wo = reinterpret_cast<float*>(st->ring_slot(nv));
       PD_HIP(pd::linear_wgrad_update_f32(s, reinterpret_cast<const float*>(dz), reinterpret_cast<const float*>(x),
                                          wi + L.w_off, wo + L.w_off, st->mom + L.w_off, wi + L.b_off, wo + L.b_off,
-                                         st->mom + L.b_off, L.rows, L.out, L.in, st->lr, st->mu));
+                                         st->mom + L.b_off, L.rows, L.out, L.in, st->rule));
       PD_HIP(st->mark(2, l));
     }
   }
@@ -1533,7 +1536,7 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
   if (!mom_w || !ring_out_w) return fail(PD_EINVAL, "null pointer");
   if (master_b && (!mom_b || !ring_out_b)) return fail(PD_EINVAL, "bias buffers must be given together");
   pd::WgradBatch batch;
-  batch.count = 1; batch.M = M; batch.lr = lr; batch.mu = momentum;
+  batch.count = 1; batch.M = M; batch.rule = pd::UpdateRule{lr, momentum, 0.f, 0};
   pd::WgradLayer& W = batch.layer[0];
   W.dz = static_cast<const pd::bf16_t*>(dz); W.x = static_cast<const pd::bf16_t*>(x);
   W.master_w = master_w; W.mom_w = mom_w; W.ring_w = static_cast<pd::bf16_t*>(ring_out_w);
@@ -1615,7 +1618,7 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
     PD_HIP(pd::linear_wgrad_update_big_bf16(s, static_cast<const pd::bf16_t*>(dz), static_cast<const pd::bf16_t*>(x),
                                             part_scratch, g.N, g.Co, g.Ci, master_w, mom_w,
                                             static_cast<pd::bf16_t*>(ring_out_w), master_b, mom_b,
-                                            static_cast<pd::bf16_t*>(ring_out_b), lr, momentum, part_scratch + unit,
+                                            static_cast<pd::bf16_t*>(ring_out_b), pd::UpdateRule{lr, momentum, 0.f, 0}, part_scratch + unit,
                                             extra));
     return PD_OK;
   }
@@ -1623,7 +1626,7 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
                                      part_scratch, splits, g));
   PD_HIP(pd::wgrad_reduce_update(s, part_scratch, splits, 0, (size_t)g.Co * g.kh * g.kw * g.Ci, g.Co, master_w, mom_w,
                                  static_cast<pd::bf16_t*>(ring_out_w), master_b, mom_b,
-                                 static_cast<pd::bf16_t*>(ring_out_b), lr, momentum));
+                                 static_cast<pd::bf16_t*>(ring_out_b), pd::UpdateRule{lr, momentum, 0.f, 0}));
   return PD_OK;
 }
 

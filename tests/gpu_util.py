@@ -40,13 +40,14 @@ class GpuStage:
     """One stage created through pd_stage_create on an arena owned by a torch tensor."""
 
     def __init__(self, layers, params, *, minibatch, precision, stage_index=0, num_stages=1, noam=1,
-                 in_flight_override=0, lr=0.01, momentum=0.9, stream=None, in_hw=None, vertical_sync=False):
+                 in_flight_override=0, lr=0.01, momentum=0.9, stream=None, in_hw=None, vertical_sync=False,
+                 optimizer=0, eps=0.0):
         self.bf16 = precision == pd.PD_BF16_F32ACC
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         self.cfg = pd.make_config(layers, stage_index=stage_index, num_stages=num_stages, noam=noam,
                                   in_flight_override=in_flight_override, minibatch=minibatch, precision=precision,
                                   lr=lr, momentum=momentum, stream=self.stream.cuda_stream, in_hw=in_hw,
-                                  vertical_sync=vertical_sync)
+                                  vertical_sync=vertical_sync, optimizer=optimizer, eps=eps)
         self.bytes = pd.pd_stage_query_bytes(self.cfg)
         self.arena = torch.empty(self.bytes + 256, dtype=torch.uint8, device=dev())
         base = (self.arena.data_ptr() + 255) // 256 * 256

@@ -99,7 +99,7 @@ def _global_order(S, noam, M, depth_override):
 
 def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=0, out_grads=None,
              lr=0.01, mu=0.9, mode="free", compare=True, verbose=False, in_hw=None, minibatch=None,
-             force_acts=False):
+             force_acts=False, optimizer="sgd", eps=1.0):
     """force_acts (deep image stages): after every forward pass has been compared, the GPU stage's stored layer
     outputs -- and the next stage's input slot -- are overwritten with the oracle's (oracle -> GPU only).  In a
     deep bf16 chain one-ulp differences compound layer by layer into differing ReLU / max-pooling decisions; with
@@ -113,7 +113,8 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
     has_loss = stage_layers[-1][-1][0] == "softmax_xent"
     depths = [depth_override or in_flight_depth(S, noam, s) for s in range(S)]
     order = _global_order(S, noam, M, depth_override)
-    os_ = [Stage(stage_layers[s], params[s], depths[s], omode, lr, mu) for s in range(S)] if compare else None
+    os_ = [Stage(stage_layers[s], params[s], depths[s], omode, lr, mu, optimizer=optimizer, eps=eps)
+           for s in range(S)] if compare else None
     if compare:
         for o in os_:
             o.log = {}
@@ -123,7 +124,8 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
         assert in_hw is None, "give one input size per stage"
         hws = [None] * S
     gs = [GpuStage(stage_layers[s], params[s], minibatch=B, precision=precision, stage_index=s, num_stages=S,
-                   noam=noam, in_flight_override=depth_override, lr=lr, momentum=mu, in_hw=hws[s]) for s in range(S)]
+                   noam=noam, in_flight_override=depth_override, lr=lr, momentum=mu, in_hw=hws[s],
+                   optimizer=1 if optimizer == "rmsprop" else 0, eps=eps) for s in range(S)]
     keep = []          # device tensors that must outlive the enqueued work
     losses = torch.zeros(M, dtype=torch.float32, device=dev())
     o_losses = [None] * M

@@ -97,3 +97,13 @@ def test_query_bytes_and_config_errors():
     bad = pd.make_config([("linear", 8, 8, False)], minibatch=4, stage_index=2, num_stages=2)
     with pytest.raises(pd.PdError):
         pd.pd_stage_query_bytes(bad)
+    bad = pd.make_config([("linear", 8, 8, False)], minibatch=4, optimizer=7)
+    with pytest.raises(pd.PdError) as e:
+        pd.pd_stage_query_bytes(bad)
+    assert e.value.status == pd.PD_EINVAL and "optimizer" in str(e.value)
+    bad = pd.make_config([("linear", 8, 8, False)], minibatch=4, optimizer=pd.PD_OPT_RMSPROP, eps=0.0)
+    with pytest.raises(pd.PdError) as e:
+        pd.pd_stage_query_bytes(bad)
+    assert e.value.status == pd.PD_EINVAL and "eps" in str(e.value)
+    ok = pd.make_config([("linear", 8, 8, False)], minibatch=4, optimizer=pd.PD_OPT_RMSPROP, eps=1.0)
+    assert pd.pd_stage_query_bytes(ok) > 0

@@ -208,6 +208,30 @@ def test_stage_wide_softmax_rows():
         _single_stage_case(layers, B=6, depth=2, M=4, precision=precision, lr=0.05)
 
 
+@pytest.mark.parametrize("precision", [pd.PD_F32, pd.PD_BF16_F32ACC])
+def test_rmsprop_stages(precision):
+    # RMSProp (the paper's optimiser for Inception-v3) through every update kernel: the fused minibatch-sized Linear
+    # update, the partial-sum reduce + update of convolutions, the many-row product with the step in its store
+    bf16 = precision == pd.PD_BF16_F32ACC
+    kw = dict(optimizer="rmsprop", eps=1.0, lr=0.045, mu=0.9)
+    layers = [("linear", 40, 48, True), ("linear", 48, 16, False), ("softmax_xent", 16)]
+    params, xs, labs, _ = _make([layers], 8, 6, SEED + 21)
+    run_case([layers], params, xs, labs, noam=1, precision=precision, depth_override=3, mode="forced" if bf16 else "free", **kw)
+    if not bf16:
+        return
+    conv = [("conv2d", 8, 16, 3, 3, 1, 1, 1, True), ("maxpool2d", 2, 2), ("conv2d", 16, 32, 1, 1, 1, 0, 0, True),
+            ("linear", 4 * 4 * 32, 16, False), ("softmax_xent", 16)]
+    params = [gen.init_params(SEED + 22, "rc", conv)]
+    xs = list(gen.normal(SEED + 22, "X", (4, 4, 8, 8, 8)))
+    labs = list(gen.labels(SEED + 22, "Y", (4, 4), 16))
+    run_case([conv], params, xs, labs, noam=1, precision=precision, depth_override=2, mode="forced", in_hw=(8, 8), **kw)
+    many = [("lstm", 32, 24, 24), ("linear", 24, 40, False), ("softmax_xent", 40)]   # 24 steps x 24 rows = 576 rows
+    params = [gen.init_params(SEED + 23, "rl", many)]
+    xs = list(gen.normal(SEED + 23, "X", (3, 24, 24, 32)))
+    labs = list(gen.labels(SEED + 23, "Y", (3, 24, 24), 40))
+    run_case([many], params, xs, labs, noam=1, precision=precision, depth_override=2, mode="forced", minibatch=24, **kw)
+
+
 def test_one_row_minibatch_and_depth_one():
     layers = [("linear", 24, 16, True), ("linear", 16, 8, False), ("softmax_xent", 8)]
     _single_stage_case(layers, B=1, depth=1, M=4, precision=pd.PD_BF16_F32ACC)
