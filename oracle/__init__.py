@@ -14,6 +14,8 @@ Modules
                pipeline run, and the flat-loop form of the staleness equation
   partition -- the layer partitioner of Section 3.2: stage time, boundary cost,
                the dynamic program over (layers, machines), NOAM
+  replicated-- a stage replicated over several machines (Sections 3.3 and 4): round-robin
+               routing, the parameter server's summed update, a pipeline with such stages
   checkpoint-- the per-stage checkpoint file (Section 4): layout and checksum
                written out in plain Python; pinned by hand-computed checksums
 
@@ -24,6 +26,8 @@ reduction to sequential minibatch SGD for one stage / one active minibatch
 layer's backward, the no-idle steady state under unit costs (Section 3.3), and a
 no-stashing negative control; for the partitioner, exhaustive enumeration of
 every pipeline on small problems, closed-form special cases and a hand-worked
-example.  Start-up slot positions of the timeline figure
+example; for replicated stages, synchronous data-parallel SGD in torch (Section 4's
+special case), a hand-worked example and a torch flat loop of the staleness rule.
+Start-up slot positions of the timeline figure
 (Figure "example pipeline") are parity unpinned: the figure is not available.
 """
