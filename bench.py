@@ -123,6 +123,105 @@ def bench_conv(args, pd, gen, torch, np, dev):
     print(json.dumps(out))
 
 
+def bench_replicated(args, pd, gen, torch, np, dev):
+    """Secondary workload: the VGG16 conv stage REPLICATED (the stage the paper replicates in its VGG16
+    configuration), r replicas on r streams sharing one parameter state.  A step is one round: B on every replica,
+    the joint update (gradients summed over the replicas), F of the round `depth` later on every replica.  The same
+    stage without replication is timed beside it (ms per minibatch) to show what the replication machinery costs."""
+    B, depth, K, W, r = args.minibatch, args.depth, args.steps, args.warmup, args.replicas
+    hw = (64, 64) if args.small else (224, 224)
+    layers = gen.config3_vgg_conv()
+    seed = gen.BASE_SEED + 2
+    params = gen.init_params(seed, "vgg_conv", layers)
+    n_pool = 2
+    xd = [torch.from_numpy(gen.normal(seed, f"x{i}", (B, hw[0], hw[1], 3))).to(dev).to(torch.bfloat16) for i in range(n_pool)]
+    oh, ow = hw[0] // 8, hw[1] // 8
+    dyd = [(torch.from_numpy(gen.normal(seed, f"dy{i}", (B, oh, ow, 256))) * 0.01).to(dev).to(torch.bfloat16) for i in range(n_pool)]
+
+    def make(replicas):
+        streams = [torch.cuda.Stream(device=dev) for _ in range(max(1, replicas))]
+        cfg = pd.make_config(layers, in_flight_override=depth, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=0.01,
+                             momentum=0.9, stream=streams[0].cuda_stream, in_hw=hw, replicas=replicas)
+        arenas, hs = [], []
+        n = pd.pd_stage_query_bytes(cfg)
+        arenas.append(torch.empty(n + 256, dtype=torch.uint8, device=dev))
+        hs.append(pd.pd_stage_create(cfg, (arenas[0].data_ptr() + 255) // 256 * 256, n))
+        pd.pd_stage_set_params(hs[0], params)
+        for q in range(1, replicas):
+            n = pd.pd_stage_replica_query_bytes(cfg)
+            arenas.append(torch.empty(n + 256, dtype=torch.uint8, device=dev))
+            torch.cuda.synchronize()
+            hs.append(pd.pd_stage_create_replica(hs[0], streams[q].cuda_stream, (arenas[q].data_ptr() + 255) // 256 * 256, n))
+        return hs, arenas, streams, cfg
+
+    def run(hs):
+        n = len(hs)
+        nxt = 0
+
+        def fwd_round():
+            nonlocal nxt
+            for q, h in enumerate(hs):
+                pd.pd_forward(h, nxt, xd[(nxt + q) % n_pool].data_ptr(), 0, 0, 0)
+            nxt += 1
+
+        def step(k):
+            for q, h in enumerate(hs):
+                pd.pd_backward(h, k, dyd[(k + q) % n_pool].data_ptr(), 0)
+            if n > 1:
+                pd.pd_update_replicated(hs)
+            else:
+                pd.pd_update(hs[0])
+            fwd_round()
+
+        for _ in range(depth):
+            fwd_round()
+        k = 0
+        for _ in range(W):
+            step(k); k += 1
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            step(k); k += 1
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / K
+
+    torch.cuda.synchronize()
+    hs1, a1, s1, _ = make(0)
+    ms_single = run(hs1)
+    pd.pd_stage_destroy(hs1[0])
+    del a1
+    hs, arenas, streams, cfg = make(r)
+    ms = run(hs)
+    P = pd.pd_stage_num_params(hs[0])
+    for h in reversed(hs):
+        pd.pd_stage_destroy(h)
+    f, h_, w_ = 0.0, hw[0], hw[1]
+    for L in layers:
+        if L[0] == "conv2d":
+            fl = 2.0 * B * h_ * w_ * 9 * L[1] * L[2]
+            f += 3 * fl
+            if L[1] == 3:
+                f -= fl
+        else:
+            h_, w_ = h_ // 2, w_ // 2
+    f *= r
+    out = {"metric": METRIC, "value": r * B / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": ("REDUCED " if args.small else "") + f"VGG16 conv stage on 3x{hw[0]}x{hw[1]} images replicated x{r} "
+                      f"({r} streams, one parameter state), bf16 w/ fp32 accum, minibatch {B} per replica, depth {depth}; "
+                      f"step = one round: B on every replica, summed update, F on every replica",
+                      "minibatch": B, "replicas": r, "ring_depth": depth, "params": P},
+           "ms_per_minibatch": ms / r, "ms_per_minibatch_unreplicated": ms_single,
+           "replication_overhead": ms / r / ms_single - 1.0,
+           "step_gflop": f / 1e9, "mfma_util_pct": 100.0 * f / (ms * 1e-3) / MFMA_BF16_PEAK,
+           "roofline": {"bound": "mfma", "kernel": "whole round (the convolution kernels dominate; the summed update "
+                        f"streams {4 * r + 18} bytes per parameter)",
+                        "achieved": f / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
+                        "frac": f / (ms * 1e-3) / MFMA_BF16_PEAK, "traffic": None}}
+    print(json.dumps(out))
+
+
 def bench_s2vt(args, pd, gen, torch, np, dev):
     """Secondary workload: the S2VT-shaped model (LSTM 4096->1000 | LSTM 1000->1000 + vocab 30000 + loss), seq 80,
     minibatch 64, as a 2-stage pipeline on two streams (pd_pipeline_run, NOAM 2).  A step = one minibatch through
@@ -410,12 +509,13 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition", "mlp4"],
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition", "mlp4", "replicated"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
                          "s2vt (the two LSTM stages as a 2-stream pipeline), inception (four stages of branched "
                          "convolution blocks as a 4-stream pipeline), gemm_sweep (the Linear kernels over row counts), "
                          "partition (layer profile of all of VGG16 on the device, then the partitioner), mlp4 (the 4-stage fp32 MLP, "
-                         "a launch-latency case)")
+                         "a launch-latency case), replicated (the VGG16 conv stage as --replicas replicas on as many streams)")
+    ap.add_argument("--replicas", type=int, default=2, help="workload replicated: replicas of the stage (2..8)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs all pipeline stages on ONE GPU; --gpus must be 1", file=sys.stderr)
@@ -444,6 +544,8 @@ def main():
         return bench_partition(args, pd, gen, torch, np, dev)
     if args.workload == "mlp4":
         return bench_mlp4(args, pd, gen, torch, np, dev)
+    if args.workload == "replicated":
+        return bench_replicated(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
     n_in, classes = layers[0][1], layers[-1][1]
     seed = gen.BASE_SEED + 1

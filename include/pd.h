@@ -143,6 +143,9 @@ typedef struct {
                                  the in-flight depth is unchanged                                  */
   int32_t optimizer;          /* pd_optimizer; 0 = momentum SGD (the default of a zeroed field)                 */
   float eps;                  /* RMSProp: added to sqrt(v); must be > 0 there, ignored otherwise               */
+  int32_t replicas;           /* 0 or 1: an ordinary stage.  2..8: the stage is replicated (Section 3.3); this
+                                 object is its primary replica and keeps a gradient buffer of one parameter set;
+                                 see pd_stage_create_replica and pd_update_replicated.  Not with vertical_sync  */
 } pd_stage_config;
 
 /* --- schedule (pure host, no GPU touched) -------------------------------------------------
@@ -173,6 +176,36 @@ int pd_schedule_1f1b_depth(int32_t depth, int32_t num_minibatches, pd_op* out, s
 int pd_stage_query_bytes(const pd_stage_config* cfg, size_t* device_bytes);
 int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena_bytes, pd_stage** out);
 int pd_stage_destroy(pd_stage* st);
+
+/* --- replicated stage (Section 3.3: deterministic round-robin over the replicas of a stage; Section 4, "Data
+ * Parallelism": the replicas' gradients are aggregated before new parameters are handed out) -----------------------
+ * On one GPU the replicas of a stage are pd_stage objects that SHARE one parameter state (version ring, fp32 latest
+ * weights, optimiser state: the primary's, created by pd_stage_create with cfg.replicas = r >= 2) and each own a
+ * stash, scratch, a gradient buffer and a stream.  What the paper leaves open is read as follows: minibatch i goes to
+ * replica i mod r as that replica's round i div r (pd_replica_route); every replica follows the stage's ordinary 1F1B
+ * list over its rounds, with `mb_id` = round in pd_forward / pd_backward; the gradients of one round are SUMMED in
+ * replica order and applied in one step (pd_update_replicated), after the backward passes of the round on all
+ * replicas and before any replica's next forward pass, so weight version = rounds completed; replicas without a
+ * minibatch in the last round of a stream only receive the new version.
+ *
+ * pd_replica_route: pure host arithmetic; PD_EINVAL if mb_id < 0 or n_replicas < 1.
+ * pd_stage_replica_query_bytes: arena bytes of one FURTHER replica (no parameter state) for the primary's config.
+ * pd_stage_create_replica: a further replica of `primary` on `stream` (borrowed; may equal the primary's), carved
+ *   from `device_arena` (256-byte aligned, caller-owned, outlives the replica).  Created in replica order 1..r-1,
+ *   with nothing in flight on the primary.  Calls that write the parameter state (pd_stage_set_params,
+ *   pd_stage_set_momentum, pd_stage_overwrite_latest, pd_stage_checkpoint_load) are made on the primary only
+ *   (PD_ESTATE otherwise) and reset/advance every replica with it; reads work on any replica.  Destroy the further
+ *   replicas before the primary (PD_ESTATE otherwise).
+ * pd_update_replicated: `replicas` = host array {primary, replica 1, ..., replica r-1}.  Every replica that has a
+ *   pending gradient (pd_backward since the last update) contributes; at least one must (PD_ESTATE otherwise).  Its
+ *   gradient kernels run on that replica's stream; the summed step runs on the primary's stream once every replica's
+ *   stream has reached this call, and every replica's stream waits for it, so no host synchronisation is needed
+ *   between the call and the next pd_forward.  pd_update on a replicated stage returns PD_ESTATE; pd_pipeline_run
+ *   does not take replicated stages (PD_EINVAL). */
+int pd_replica_route(int32_t mb_id, int32_t n_replicas, int32_t* replica, int32_t* round);
+int pd_stage_replica_query_bytes(const pd_stage_config* cfg, size_t* device_bytes);
+int pd_stage_create_replica(pd_stage* primary, void* stream, void* device_arena, size_t arena_bytes, pd_stage** out);
+int pd_update_replicated(pd_stage* const* replicas, int32_t n_replicas);
 
 /* Number of parameters (length of the flat vector), in-flight depth, input-ring depth. */
 int pd_stage_num_params(const pd_stage* st, size_t* n);

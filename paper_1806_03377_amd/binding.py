@@ -58,7 +58,7 @@ class pd_stage_config(C.Structure):
                 ("in_flight_override", C.c_int32), ("minibatch", C.c_int32), ("precision", C.c_int32),
                 ("lr", C.c_float), ("momentum", C.c_float), ("n_layers", C.c_int32),
                 ("layers", C.POINTER(pd_layer_desc)), ("stream", C.c_void_p), ("vertical_sync", C.c_int32),
-                ("optimizer", C.c_int32), ("eps", C.c_float)]
+                ("optimizer", C.c_int32), ("eps", C.c_float), ("replicas", C.c_int32)]
 
 
 _vp, _sz, _i32, _f32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_float
@@ -71,6 +71,10 @@ _SIGS = {
     "pd_stage_query_bytes": [C.POINTER(pd_stage_config), C.POINTER(_sz)],
     "pd_stage_create": [C.POINTER(pd_stage_config), _vp, _sz, C.POINTER(_vp)],
     "pd_stage_destroy": [_vp],
+    "pd_replica_route": [_i32, _i32, C.POINTER(_i32), C.POINTER(_i32)],
+    "pd_stage_replica_query_bytes": [C.POINTER(pd_stage_config), C.POINTER(_sz)],
+    "pd_stage_create_replica": [_vp, _vp, _vp, _sz, C.POINTER(_vp)],
+    "pd_update_replicated": [C.POINTER(_vp), _i32],
     "pd_stage_num_params": [_vp, C.POINTER(_sz)],
     "pd_stage_depth": [_vp, C.POINTER(_i32), C.POINTER(_i32)],
     "pd_stage_set_params": [_vp, _vp, _sz],
@@ -223,10 +227,10 @@ def layer_descs(layers: Sequence[tuple], in_hw=None):
 
 def make_config(layers, *, stage_index=0, num_stages=1, noam=1, in_flight_override=0, minibatch=1,
                 precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None, vertical_sync=False,
-                optimizer=PD_OPT_SGD_MOMENTUM, eps=0.0):
+                optimizer=PD_OPT_SGD_MOMENTUM, eps=0.0, replicas=0):
     descs = layer_descs(layers, in_hw)
     cfg = pd_stage_config(stage_index, num_stages, noam, in_flight_override, minibatch, precision, lr, momentum,
-                          len(descs), descs, stream, 1 if vertical_sync else 0, optimizer, eps)
+                          len(descs), descs, stream, 1 if vertical_sync else 0, optimizer, eps, replicas)
     cfg._keepalive = descs
     return cfg
 
@@ -245,6 +249,30 @@ def pd_stage_create(cfg, device_arena: int, arena_bytes: int) -> int:
 
 def pd_stage_destroy(stage: int):
     _check(_lib.pd_stage_destroy(stage))
+
+
+def pd_replica_route(mb_id: int, n_replicas: int) -> Tuple[int, int]:
+    """(replica, round) of a minibatch of a replicated stage."""
+    q, k = _i32(0), _i32(0)
+    _check(_lib.pd_replica_route(mb_id, n_replicas, C.byref(q), C.byref(k)))
+    return q.value, k.value
+
+
+def pd_stage_replica_query_bytes(cfg) -> int:
+    n = _sz(0)
+    _check(_lib.pd_stage_replica_query_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def pd_stage_create_replica(primary: int, stream: int, device_arena: int, arena_bytes: int) -> int:
+    h = _vp(0)
+    _check(_lib.pd_stage_create_replica(primary, stream, device_arena, arena_bytes, C.byref(h)))
+    return h.value
+
+
+def pd_update_replicated(replicas):
+    arr = (_vp * len(replicas))(*replicas)
+    _check(_lib.pd_update_replicated(arr, len(replicas)))
 
 
 def pd_stage_num_params(stage: int) -> int:

@@ -699,6 +699,10 @@ __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* _
   float* ms = e < n_w ? master_w + e : master_b + (e - n_w);
   float* mm = e < n_w ? mom_w + e : mom_b + (e - n_w);
   bf16_t* rr = e < n_w ? ring_w + e : ring_b + (e - n_w);
+  if (rule.kind == kRuleGradOnly) {  // replicated stage: the sum over replicas comes first
+    *ms = gsum;
+    return;
+  }
   float m = *mm, wv = *ms;
   apply_update(rule, gsum, m, wv);
   *mm = m;

@@ -375,6 +375,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
         m = *reinterpret_cast<const float4*>(mom + off);
         wv = *reinterpret_cast<const float4*>(master + off);
       }
+      if (rule.kind == kRuleGradOnly) {  // replicated stage: the sum over replicas comes first
+        *reinterpret_cast<float4*>(master + off) = g;
+        continue;
+      }
       apply_update(rule, g.x, m.x, wv.x); apply_update(rule, g.y, m.y, wv.y);
       apply_update(rule, g.z, m.z, wv.z); apply_update(rule, g.w, m.w, wv.w);
       nt_store4(mom + off, m);     // streamed once per step: keep these lines out of the caches
@@ -393,6 +397,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
     if (n < N) {
       float g = 0.f;
       for (int m = 0; m < M; ++m) g += bf2f(dZ[(size_t)m * N + n]);
+      if (rule.kind == kRuleGradOnly) {
+        master_b[n] = g;
+        return;
+      }
       float mv = mom_b[n], bv = master_b[n];
       apply_update(rule, g, mv, bv);
       mom_b[n] = mv;

@@ -73,6 +73,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     } else if (EPI == EPI_DGRAD) {
       e.out[off] = (e.mask && !(e.mask[off] > 0.f)) ? 0.f : acc[q];
     } else {
+      if (e.rule.kind == kRuleGradOnly) {  // replicated stage: the sum over replicas comes first
+        e.w_out[off] = acc[q];
+        continue;
+      }
       float m = e.mom[off], wv = e.w_in[off];
       apply_update(e.rule, acc[q], m, wv);
       e.mom[off] = m;
@@ -84,6 +88,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
     if (n < I) {
       float g = 0.f;
       for (int m = 0; m < e.M; ++m) g += e.dz[(size_t)m * I + n];
+      if (e.rule.kind == kRuleGradOnly) {
+        e.b_out[n] = g;
+        return;
+      }
       float mv = e.mom_b[n], bv = e.b_in[n];
       apply_update(e.rule, g, mv, bv);
       e.mom_b[n] = mv;

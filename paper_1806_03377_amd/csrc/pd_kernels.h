@@ -12,10 +12,15 @@ typedef uint16_t bf16_t;  // raw bfloat16 bits
 // The step applied to a parameter w with gradient g and its one state value s (Section 5.1 names the optimisers):
 //   kind 0, momentum SGD:  s <- a s + g ;            w <- w - lr s
 //   kind 1, RMSProp:       s <- a s + (1 - a) g^2 ;  w <- w - lr g / (sqrt(s) + eps)
+//   kind 2, gradient only: the kernel stores g where it would have stored w and touches neither the state nor
+//           the bf16 ring copy (their pointers are still read, so they must be valid).  Used by replicated stages,
+//           whose gradients are summed over the replicas before the step (replica_sum_update below).
 struct UpdateRule {
   float lr, a, eps;
   int kind;
 };
+constexpr int kRuleGradOnly = 2;
+constexpr int kMaxReplicas = 8;
 __host__ __device__ __forceinline__ void apply_update(const UpdateRule& u, float g, float& s, float& w) {
   if (u.kind == 0) {
     s = u.a * s + g;
@@ -181,11 +186,15 @@ hipError_t lstm_step_forward(hipStream_t s, float* gates, const bf16_t* h_prev, 
 hipError_t lstm_step_backward(hipStream_t s, const bf16_t* dh_out, const bf16_t* da_next, const bf16_t* whh_t, float* dc,
                               const float* gates, const float* c, const float* c_prev, bf16_t* da, int B, int H);
 
-// ---- stand-alone update (update.hip) ---------------------------------------------------------------
-// m <- mu*m + g; w_out <- w_in - lr*m; ring <- bf16(w_out) if ring is not null.  g null = zero gradient.
-// All arrays 16-byte aligned.  grid_blocks <= 0 picks the default grid.
-hipError_t sgd_momentum_update(hipStream_t s, const float* g, const float* w_in, float* w_out, float* mom,
-                               bf16_t* ring, size_t n, float lr, float mu, int grid_blocks);
+// ---- update of a replicated stage (update.hip) ---------------------------------------------------
+// g = grads.g[0] + grads.g[1] + ... (in that order), then the step of `rule` on (w_in -> w_out, state) and
+// ring <- bf16(w_out) if ring is not null.  All arrays 16-byte aligned, n elements each.
+struct ReplicaGrads {
+  const float* g[kMaxReplicas];
+  int count;
+};
+hipError_t replica_sum_update(hipStream_t s, const ReplicaGrads& grads, const float* w_in, float* w_out, float* state,
+                              bf16_t* ring, size_t n, UpdateRule rule);
 
 // ---- fp32 path (linear_f32.hip) ------------------------------------------------------------------
 hipError_t linear_fwd_f32(hipStream_t s, const float* x, const float* w, const float* b, float* y, int M, int N, int K,

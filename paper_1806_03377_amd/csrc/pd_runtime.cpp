@@ -5,6 +5,8 @@
 // and the enqueue order of the HIP kernels.  No arithmetic of the method happens on the host.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -179,6 +181,16 @@ struct pd_stage {
   float* ws = nullptr;
   size_t ws_bytes = 0;
   float* row_loss = nullptr;
+  // replicated stage (Section 3.3, Section 4 "Data Parallelism"): every replica is a pd_stage of its own (stash,
+  // scratch, stream); ring, master and mom of a secondary replica point into the primary's arena, and each replica
+  // leaves the fp32 gradient of its minibatch in gradbuf (laid out like one parameter set) for the summed update
+  int n_replicas = 1;
+  float* gradbuf = nullptr;
+  pd_stage* primary = nullptr;          // null on the primary itself
+  std::vector<pd_stage*> secondaries;   // primary only
+  hipEvent_t ev_rep = nullptr;          // this replica's stream has reached the joint update / the update is done
+  pd_stage_config cfg = {};
+  std::vector<pd_layer_desc> cfg_layers;
   // protocol state
   int latest = 0;
   int last_fwd = -1;
@@ -226,12 +238,18 @@ struct Plan {
   size_t blk_dy_bytes = 0, blk_dx_bytes = 0, blk_dx_stride = 0, o_blk_dy = 0, o_blk_dx = 0;
   // arena offsets
   size_t o_ring = 0, o_master = 0, o_mom = 0, o_in = 0, o_stash = 0, o_dz = 0, o_grad = 0, o_ws = 0, o_rowloss = 0;
-  size_t o_pp = 0, o_part = 0, o_wt = 0;
+  size_t o_pp = 0, o_part = 0, o_wt = 0, o_gradbuf = 0;
+  int replicas = 1;
   size_t total = 0;
 };
 
-int make_plan(const pd_stage_config* c, Plan& p) {
+// secondary: lay out the arena of a further replica of a replicated stage (no parameter state of its own)
+int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
   if (!c) return fail(PD_EINVAL, "config is null");
+  if (c->replicas < 0 || c->replicas > pd::kMaxReplicas) return fail(PD_EINVAL, "replicas must be 0..%d (got %d)", pd::kMaxReplicas, c->replicas);
+  p.replicas = c->replicas > 1 ? c->replicas : 1;
+  if (p.replicas > 1 && c->vertical_sync) return fail(PD_EINVAL, "vertical sync is not available for a replicated stage");
+  if (secondary && p.replicas < 2) return fail(PD_EINVAL, "the stage is not configured as replicated");
   if (c->optimizer != PD_OPT_SGD_MOMENTUM && c->optimizer != PD_OPT_RMSPROP) return fail(PD_EINVAL, "unknown optimizer %d", c->optimizer);
   if (c->optimizer == PD_OPT_RMSPROP && !(c->eps > 0.f)) return fail(PD_EINVAL, "RMSProp needs eps > 0");
   if (c->num_stages < 1 || c->stage_index < 0 || c->stage_index >= c->num_stages)
@@ -487,9 +505,12 @@ int make_plan(const pd_stage_config* c, Plan& p) {
     }
   p.ws_bytes = align_up(p.ws_bytes, 256);
   size_t o = 0;
-  p.o_ring = o; o += align_up((size_t)p.ring_depth * p.p_pad * p.esz, 256);
-  if (p.bf16) { p.o_master = o; o += align_up(p.p_pad * 4, 256); }
-  p.o_mom = o; o += align_up(p.p_pad * 4, 256);
+  if (!secondary) {
+    p.o_ring = o; o += align_up((size_t)p.ring_depth * p.p_pad * p.esz, 256);
+    if (p.bf16) { p.o_master = o; o += align_up(p.p_pad * 4, 256); }
+    p.o_mom = o; o += align_up(p.p_pad * 4, 256);
+  }
+  if (p.replicas > 1) { p.o_gradbuf = o; o += align_up(p.p_pad * 4, 256); }
   p.o_in = o; o += (size_t)p.in_depth * p.in_bytes;
   p.o_stash = o; o += (size_t)p.depth * p.stash_slot_bytes;
   p.o_dz = o; o += p.dz_bytes;
@@ -506,6 +527,77 @@ int make_plan(const pd_stage_config* c, Plan& p) {
 }
 
 int check_stage(const pd_stage* st) { return st ? PD_OK : fail(PD_EINVAL, "stage is null"); }
+
+// The parameter state of a replicated stage lives with its primary: calls that write it go there.
+int check_owner(const pd_stage* st) {
+  if (check_stage(st)) return PD_EINVAL;
+  return st->primary ? fail(PD_ESTATE, "this is a secondary replica: the parameter state belongs to its primary") : PD_OK;
+}
+
+// primary == null: an ordinary stage (or the primary of a replicated one); otherwise a further replica of it
+int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, void* device_arena, size_t arena_bytes,
+                 pd_stage** out) {
+  if (!out) return fail(PD_EINVAL, "out is null");
+  *out = nullptr;
+  Plan p;
+  const int rc = make_plan(cfg, p, primary != nullptr);
+  if (rc != PD_OK) return rc;
+  if (!device_arena) return fail(PD_EINVAL, "device_arena is null");
+  if (reinterpret_cast<uintptr_t>(device_arena) & 255u) return fail(PD_EINVAL, "device_arena must be 256-byte aligned");
+  if (arena_bytes < p.total) return fail(PD_ENOMEM, "arena has %zu bytes, stage needs %zu", arena_bytes, p.total);
+  pd_stage* st = new (std::nothrow) pd_stage();
+  if (!st) return fail(PD_ENOMEM, "host allocation failed");
+  char* a = static_cast<char*>(device_arena);
+  st->cfg = *cfg;
+  st->cfg_layers.assign(cfg->layers, cfg->layers + cfg->n_layers);
+  st->cfg.layers = st->cfg_layers.data();
+  st->stage_index = cfg->stage_index; st->num_stages = cfg->num_stages; st->noam = cfg->noam;
+  st->depth = p.depth; st->in_depth = p.in_depth; st->ring_depth = p.ring_depth; st->vsync = cfg->vertical_sync != 0;
+  st->B = p.B; st->bf16 = p.bf16; st->has_loss = p.has_loss;
+  st->classes = p.classes;
+  st->rule = pd::UpdateRule{cfg->lr, cfg->momentum, cfg->eps, cfg->optimizer};
+  st->stream = static_cast<hipStream_t>(stream);
+  st->cfg.stream = stream;
+  st->lin = p.lin; st->esz = p.esz; st->n_params = p.n_params; st->p_pad = p.p_pad;
+  st->in_bytes = p.in_bytes; st->out_bytes = p.out_bytes; st->stash_slot_bytes = p.stash_slot_bytes;
+  st->dlogits_off = p.dlogits_off;
+  st->n_replicas = p.replicas;
+  if (primary) {
+    st->primary = primary;
+    st->ring = primary->ring; st->master = primary->master; st->mom = primary->mom;
+    st->latest = primary->latest;
+  } else {
+    st->ring = a + p.o_ring;
+    st->master = p.bf16 ? reinterpret_cast<float*>(a + p.o_master) : nullptr;
+    st->mom = reinterpret_cast<float*>(a + p.o_mom);
+  }
+  st->gradbuf = p.replicas > 1 ? reinterpret_cast<float*>(a + p.o_gradbuf) : nullptr;
+  st->in_ring = a + p.o_in; st->stash = a + p.o_stash; st->dz = a + p.o_dz;
+  st->grad_in = p.has_loss ? nullptr : a + p.o_grad;
+  st->ws = reinterpret_cast<float*>(a + p.o_ws); st->ws_bytes = p.ws_bytes;
+  st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
+  st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
+  st->blk_dy = a + p.o_blk_dy; st->blk_dx = a + p.o_blk_dx; st->blk_dx_stride = p.blk_dx_stride;
+  hipError_t e = primary ? hipSuccess : pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
+  // padding between layers inside the gradient buffer is never written by a gradient kernel: keep it at zero
+  if (e == hipSuccess && st->gradbuf) e = pd::fill_zero(st->stream, st->gradbuf, p.p_pad * 4);
+  if (e == hipSuccess && st->gradbuf) e = hipEventCreateWithFlags(&st->ev_rep, hipEventDisableTiming);
+  for (int d = 0; d < st->depth && e == hipSuccess; ++d)
+    for (const Linear& L : st->lin)
+      if (L.kind == K_LSTM && e == hipSuccess) {
+        char* slot = st->stash + (size_t)d * st->stash_slot_bytes;
+        e = pd::fill_zero(st->stream, slot + L.y_off, (size_t)st->B * L.out * 2);
+        if (e == hipSuccess) e = pd::fill_zero(st->stream, slot + L.c_off, (size_t)st->B * L.out * 4);
+      }
+  if (e != hipSuccess) {
+    if (st->ev_rep) (void)hipEventDestroy(st->ev_rep);
+    delete st;
+    return fail(PD_EHIP, "clearing momentum and initial states: %s", hipGetErrorString(e));
+  }
+  if (primary) primary->secondaries.push_back(st);
+  *out = st;
+  return PD_OK;
+}
 
 }  // namespace
 
@@ -560,53 +652,45 @@ int pd_stage_query_bytes(const pd_stage_config* cfg, size_t* device_bytes) {
 }
 
 int pd_stage_create(const pd_stage_config* cfg, void* device_arena, size_t arena_bytes, pd_stage** out) {
-  if (!out) return fail(PD_EINVAL, "out is null");
-  *out = nullptr;
-  Plan p;
-  const int rc = make_plan(cfg, p);
-  if (rc != PD_OK) return rc;
-  if (!device_arena) return fail(PD_EINVAL, "device_arena is null");
-  if (reinterpret_cast<uintptr_t>(device_arena) & 255u) return fail(PD_EINVAL, "device_arena must be 256-byte aligned");
-  if (arena_bytes < p.total) return fail(PD_ENOMEM, "arena has %zu bytes, stage needs %zu", arena_bytes, p.total);
-  pd_stage* st = new (std::nothrow) pd_stage();
-  if (!st) return fail(PD_ENOMEM, "host allocation failed");
-  char* a = static_cast<char*>(device_arena);
-  st->stage_index = cfg->stage_index; st->num_stages = cfg->num_stages; st->noam = cfg->noam;
-  st->depth = p.depth; st->in_depth = p.in_depth; st->ring_depth = p.ring_depth; st->vsync = cfg->vertical_sync != 0;
-  st->B = p.B; st->bf16 = p.bf16; st->has_loss = p.has_loss;
-  st->classes = p.classes;
-  st->rule = pd::UpdateRule{cfg->lr, cfg->momentum, cfg->eps, cfg->optimizer};
-  st->stream = static_cast<hipStream_t>(cfg->stream);
-  st->lin = p.lin; st->esz = p.esz; st->n_params = p.n_params; st->p_pad = p.p_pad;
-  st->in_bytes = p.in_bytes; st->out_bytes = p.out_bytes; st->stash_slot_bytes = p.stash_slot_bytes;
-  st->dlogits_off = p.dlogits_off;
-  st->ring = a + p.o_ring;
-  st->master = p.bf16 ? reinterpret_cast<float*>(a + p.o_master) : nullptr;
-  st->mom = reinterpret_cast<float*>(a + p.o_mom);
-  st->in_ring = a + p.o_in; st->stash = a + p.o_stash; st->dz = a + p.o_dz;
-  st->grad_in = p.has_loss ? nullptr : a + p.o_grad;
-  st->ws = reinterpret_cast<float*>(a + p.o_ws); st->ws_bytes = p.ws_bytes;
-  st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
-  st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
-  st->blk_dy = a + p.o_blk_dy; st->blk_dx = a + p.o_blk_dx; st->blk_dx_stride = p.blk_dx_stride;
-  hipError_t e = pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
-  for (int d = 0; d < st->depth && e == hipSuccess; ++d)
-    for (const Linear& L : st->lin)
-      if (L.kind == K_LSTM && e == hipSuccess) {
-        char* slot = st->stash + (size_t)d * st->stash_slot_bytes;
-        e = pd::fill_zero(st->stream, slot + L.y_off, (size_t)st->B * L.out * 2);
-        if (e == hipSuccess) e = pd::fill_zero(st->stream, slot + L.c_off, (size_t)st->B * L.out * 4);
-      }
-  if (e != hipSuccess) {
-    delete st;
-    return fail(PD_EHIP, "clearing momentum and initial states: %s", hipGetErrorString(e));
-  }
-  *out = st;
+  if (!cfg) return fail(PD_EINVAL, "config is null");
+  return create_stage(cfg, nullptr, cfg->stream, device_arena, arena_bytes, out);
+}
+
+int pd_replica_route(int32_t mb_id, int32_t n_replicas, int32_t* replica, int32_t* round) {
+  if (mb_id < 0 || n_replicas < 1) return fail(PD_EINVAL, "bad routing arguments (minibatch %d, %d replicas)", mb_id, n_replicas);
+  if (replica) *replica = mb_id % n_replicas;
+  if (round) *round = mb_id / n_replicas;
   return PD_OK;
+}
+
+int pd_stage_replica_query_bytes(const pd_stage_config* cfg, size_t* device_bytes) {
+  if (!device_bytes) return fail(PD_EINVAL, "device_bytes is null");
+  Plan p;
+  const int rc = make_plan(cfg, p, true);
+  if (rc != PD_OK) return rc;
+  *device_bytes = p.total;
+  return PD_OK;
+}
+
+int pd_stage_create_replica(pd_stage* primary, void* stream, void* device_arena, size_t arena_bytes, pd_stage** out) {
+  if (out) *out = nullptr;
+  if (check_stage(primary)) return PD_EINVAL;
+  if (primary->primary) return fail(PD_EINVAL, "replicas are created from the primary");
+  if (primary->n_replicas < 2) return fail(PD_EINVAL, "the stage is not configured as replicated");
+  if ((int)primary->secondaries.size() + 1 >= primary->n_replicas)
+    return fail(PD_ESTATE, "the stage already has its %d replicas", primary->n_replicas);
+  if (!primary->in_flight.empty() || primary->grad_pending) return fail(PD_ESTATE, "minibatches in flight");
+  return create_stage(&primary->cfg, primary, stream, device_arena, arena_bytes, out);
 }
 
 int pd_stage_destroy(pd_stage* st) {
   if (!st) return PD_OK;
+  if (!st->secondaries.empty()) return fail(PD_ESTATE, "destroy the %zu further replicas of this stage first", st->secondaries.size());
+  if (st->primary) {
+    auto& v = st->primary->secondaries;
+    v.erase(std::remove(v.begin(), v.end(), st), v.end());
+  }
+  if (st->ev_rep) (void)hipEventDestroy(st->ev_rep);
   for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u, &st->mark_pool})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   for (const pd_stage::Mark& m : st->marks) (void)hipEventDestroy(m.ev);
@@ -635,8 +719,13 @@ int pd_stage_ring_depth(const pd_stage* st, int32_t* ring_depth) {
 
 int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   if (check_stage(st) || !host_params) return fail(PD_EINVAL, "null argument");
+  if (check_owner(st)) return PD_ESTATE;
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu parameters, got %zu", st->n_params, n);
   PD_HIP(hipStreamSynchronize(st->stream));
+  for (pd_stage* r : st->secondaries) {  // they read the same weights and restart with them
+    PD_HIP(hipStreamSynchronize(r->stream));
+    r->latest = 0; r->last_fwd = -1; r->in_flight.clear(); r->grad_pending = false; r->trace.clear();
+  }
   float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(st->ring);
   for (const Linear& L : st->lin) {
     if (!L.n_w) continue;
@@ -693,6 +782,7 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
 
 int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n) {
   if (check_stage(st) || !host_mom) return fail(PD_EINVAL, "null argument");
+  if (check_owner(st)) return PD_ESTATE;
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "minibatches in flight");
   PD_HIP(hipStreamSynchronize(st->stream));
@@ -817,11 +907,17 @@ int pd_stage_checkpoint_load(pd_stage* st, const char* path) {
   if (v % st->ring_depth != 0)  // the weights belong in the ring slot of their version
     PD_HIP(hipMemcpy(st->ring_slot(v), st->ring_slot(0), st->p_pad * st->esz, hipMemcpyDeviceToDevice));
   st->latest = v;
+  for (pd_stage* r : st->secondaries) r->latest = v;
   return PD_OK;
 }
 
 int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const float* host_mom, size_t n) {
   if (check_stage(st)) return PD_EINVAL;
+  if (check_owner(st)) return PD_ESTATE;
+  for (pd_stage* r : st->secondaries) {
+    if (r->grad_pending) return fail(PD_ESTATE, "a gradient is pending on a replica: call pd_update_replicated first");
+    PD_HIP(hipStreamSynchronize(r->stream));
+  }
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   if (st->grad_pending) return fail(PD_ESTATE, "a gradient is pending: call pd_update first");
   PD_HIP(hipStreamSynchronize(st->stream));
@@ -1238,25 +1334,31 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   return PD_OK;
 }
 
-int pd_update(pd_stage* st) {
-  if (check_stage(st)) return PD_EINVAL;
-  if (!st->grad_pending) return fail(PD_ESTATE, "no pending gradient");
+}  // extern "C"
+
+namespace {
+
+// The kernels of U for the pending minibatch of `st`.  grad_only = false: weight gradient fused with the step of the
+// stage's rule into ring slot `nv`.  grad_only = true (a replica of a replicated stage): the same kernels leave the
+// fp32 gradient in st->gradbuf, laid out like a parameter set, and change nothing else.
+int run_update_kernels(pd_stage* st, int nv, bool grad_only) {
   hipStream_t s = st->stream;
   const int mb = st->pending_mb;
   char* slot = st->stash_slot(mb);
   const int nl = (int)st->lin.size();
-  const int nv = st->latest + 1;
+  const pd::UpdateRule rule = grad_only ? pd::UpdateRule{0.f, 0.f, 0.f, pd::kRuleGradOnly} : st->rule;
+  float* const w32 = grad_only ? st->gradbuf : st->master;  // bf16 mode: where the fp32 result of a kernel goes
   pd::WgradBatch batch;
-  batch.count = 0; batch.M = st->B; batch.rule = st->rule;
+  batch.count = 0; batch.M = st->B; batch.rule = rule;
   PD_HIP(st->mark(-1, 0));
   for (int l = 0; l < nl; ++l) {
     const Layer& L = st->lin[l];
     if (!L.n_w) continue;  // pooling, concatenation
-    if (L.kind == K_CONV) {  // partial sums left by pd_backward -> momentum-SGD step into the next ring slot
+    if (L.kind == K_CONV) {  // partial sums left by pd_backward -> step into the next ring slot
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
       PD_HIP(pd::wgrad_reduce_update(s, reinterpret_cast<const float*>(st->part + L.part_off), L.splits, 0, L.n_w,
-                                     (int)L.n_b, st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
-                                     st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->rule));
+                                     (int)L.n_b, w32 + L.w_off, st->mom + L.w_off, ro + L.w_off,
+                                     w32 + L.b_off, st->mom + L.b_off, ro + L.b_off, rule));
       PD_HIP(st->mark(2, l));
       continue;
     }
@@ -1266,20 +1368,27 @@ int pd_update(pd_stage* st) {
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
       const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
       float* part = reinterpret_cast<float*>(st->part + L.part_off);
-      const size_t n_w1 = (size_t)n_out * L.in;
-      PD_HIP(pd::linear_wgrad_update_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
-                                              reinterpret_cast<const pd::bf16_t*>(x), part, L.rows, n_out, L.in,
+      const size_t n_w1 = (size_t)n_out * L.in, o2 = L.w_off + n_w1;
+      const pd::bf16_t* dzp = reinterpret_cast<const pd::bf16_t*>(dz);
+      const pd::bf16_t* h_prev = reinterpret_cast<const pd::bf16_t*>(slot + L.y_off);  // LSTM: hidden states, shifted
+      if (grad_only) {
+        PD_HIP(pd::linear_wgrad_big_bf16(s, dzp, reinterpret_cast<const pd::bf16_t*>(x), w32 + L.w_off, w32 + L.b_off,
+                                         L.rows, n_out, L.in, st->ws, st->ws_bytes));
+        if (L.kind == K_LSTM)
+          PD_HIP(pd::linear_wgrad_big_bf16(s, dzp, h_prev, w32 + o2, nullptr, L.rows, n_out, L.out, st->ws,
+                                           st->ws_bytes));
+        PD_HIP(st->mark(2, l));
+        continue;
+      }
+      PD_HIP(pd::linear_wgrad_update_big_bf16(s, dzp, reinterpret_cast<const pd::bf16_t*>(x), part, L.rows, n_out, L.in,
                                               st->master + L.w_off, st->mom + L.w_off, ro + L.w_off,
-                                              st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, st->rule,
+                                              st->master + L.b_off, st->mom + L.b_off, ro + L.b_off, rule,
                                               st->ws, st->ws_bytes));
       if (L.kind == K_LSTM) {
         float* part2 = reinterpret_cast<float*>(st->part + L.part2_off);
-        const size_t n_w2 = (size_t)n_out * L.out, o2 = L.w_off + n_w1;
-        (void)n_w2;
-        PD_HIP(pd::linear_wgrad_update_big_bf16(s, reinterpret_cast<const pd::bf16_t*>(dz),
-                                                reinterpret_cast<const pd::bf16_t*>(slot + L.y_off), part2, L.rows,
-                                                n_out, L.out, st->master + o2, st->mom + o2, ro + o2, nullptr, nullptr,
-                                                nullptr, st->rule, st->ws, st->ws_bytes));
+        PD_HIP(pd::linear_wgrad_update_big_bf16(s, dzp, h_prev, part2, L.rows, n_out, L.out, st->master + o2,
+                                                st->mom + o2, ro + o2, nullptr, nullptr, nullptr, rule, st->ws,
+                                                st->ws_bytes));
       }
       PD_HIP(st->mark(2, l));
     } else if (st->bf16) {
@@ -1293,8 +1402,8 @@ int pd_update(pd_stage* st) {
       };
       pd::WgradLayer& W = batch.layer[batch.count++];
       W.dz = reinterpret_cast<const pd::bf16_t*>(dz); W.x = reinterpret_cast<const pd::bf16_t*>(x);
-      W.master_w = st->master + L.w_off; W.mom_w = st->mom + L.w_off; W.ring_w = ro + L.w_off;
-      W.master_b = st->master + L.b_off; W.mom_b = st->mom + L.b_off; W.ring_b = ro + L.b_off;
+      W.master_w = w32 + L.w_off; W.mom_w = st->mom + L.w_off; W.ring_w = ro + L.w_off;
+      W.master_b = w32 + L.b_off; W.mom_b = st->mom + L.b_off; W.ring_b = ro + L.b_off;
       W.M = L.rows; W.N = L.kind == K_LSTM ? 4 * L.out : L.out; W.K = L.in; W.tile_end = 0;
       PD_HIP(flush_if_full());
       if (L.kind == K_LSTM) {  // second matrix: W_hh, whose "input" is the hidden sequence shifted by one step
@@ -1302,17 +1411,17 @@ int pd_update(pd_stage* st) {
         pd::WgradLayer& V = batch.layer[batch.count++];
         V.dz = reinterpret_cast<const pd::bf16_t*>(dz);
         V.x = reinterpret_cast<const pd::bf16_t*>(slot + L.y_off);
-        V.master_w = st->master + o2; V.mom_w = st->mom + o2; V.ring_w = ro + o2;
+        V.master_w = w32 + o2; V.mom_w = st->mom + o2; V.ring_w = ro + o2;
         V.master_b = nullptr; V.mom_b = nullptr; V.ring_b = nullptr;
         V.M = L.rows; V.N = 4 * L.out; V.K = L.out; V.tile_end = 0;
         PD_HIP(flush_if_full());
       }
     } else {
       const float* wi = reinterpret_cast<const float*>(st->ring_slot(st->latest));
-      float* wo = reinterpret_cast<float*>(st->ring_slot(nv));
+      float* wo = grad_only ? st->gradbuf : reinterpret_cast<float*>(st->ring_slot(nv));
       PD_HIP(pd::linear_wgrad_update_f32(s, reinterpret_cast<const float*>(dz), reinterpret_cast<const float*>(x),
                                          wi + L.w_off, wo + L.w_off, st->mom + L.w_off, wi + L.b_off, wo + L.b_off,
-                                         st->mom + L.b_off, L.rows, L.out, L.in, st->rule));
+                                         st->mom + L.b_off, L.rows, L.out, L.in, rule));
       PD_HIP(st->mark(2, l));
     }
   }
@@ -1321,9 +1430,74 @@ int pd_update(pd_stage* st) {
     PD_HIP(st->mark(3, -1));
   }
   if (st->profiling) ++st->prof_ops[2];
+  return PD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pd_update(pd_stage* st) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (st->n_replicas > 1) return fail(PD_ESTATE, "replicated stage: its replicas are updated together by pd_update_replicated");
+  if (!st->grad_pending) return fail(PD_ESTATE, "no pending gradient");
+  const int nv = st->latest + 1;
+  const int rc = run_update_kernels(st, nv, false);
+  if (rc != PD_OK) return rc;
   st->latest = nv;
   st->grad_pending = false;
-  st->trace.push_back({PD_OP_U, mb, nv, nv % st->ring_depth});
+  st->trace.push_back({PD_OP_U, st->pending_mb, nv, nv % st->ring_depth});
+  return PD_OK;
+}
+
+// Replicated stage (Section 3.3; Section 4 "Data Parallelism"): every replica with a pending gradient forms it on
+// its own stream; the primary's stream waits for all replicas, sums the gradients in replica order and takes the one
+// step on the shared parameter state; every replica's stream then waits for that step.
+int pd_update_replicated(pd_stage* const* replicas, int32_t n_replicas) {
+  if (!replicas || n_replicas < 1) return fail(PD_EINVAL, "need the replicas of the stage");
+  pd_stage* p0 = replicas[0];
+  if (check_stage(p0)) return PD_EINVAL;
+  if (p0->primary) return fail(PD_EINVAL, "replicas[0] must be the primary");
+  if (p0->n_replicas < 2) return fail(PD_EINVAL, "the stage is not configured as replicated");
+  if (n_replicas != p0->n_replicas || (int)p0->secondaries.size() + 1 != n_replicas)
+    return fail(PD_EINVAL, "the stage is configured for %d replicas, %zu exist, %d were passed", p0->n_replicas,
+                p0->secondaries.size() + 1, n_replicas);
+  for (int q = 1; q < n_replicas; ++q)
+    if (replicas[q] != p0->secondaries[q - 1]) return fail(PD_EINVAL, "replicas must be passed in the order they were created (entry %d)", q);
+  pd::ReplicaGrads grads;
+  grads.count = 0;
+  for (int q = 0; q < n_replicas; ++q) {
+    if (replicas[q]->latest != p0->latest) return fail(PD_ESTATE, "replica %d is at another weight version", q);
+    if (replicas[q]->grad_pending) grads.g[grads.count++] = replicas[q]->gradbuf;
+  }
+  if (!grads.count) return fail(PD_ESTATE, "no pending gradient on any replica");
+  const int nv = p0->latest + 1;
+  for (int q = 0; q < n_replicas; ++q) {
+    pd_stage* r = replicas[q];
+    if (r->grad_pending) {
+      const int rc = run_update_kernels(r, nv, true);
+      if (rc != PD_OK) return rc;
+    }
+    if (q > 0 && r->stream != p0->stream) {  // also a replica without a gradient may still be reading old versions
+      PD_HIP(hipEventRecord(r->ev_rep, r->stream));
+      PD_HIP(hipStreamWaitEvent(p0->stream, r->ev_rep, 0));
+    }
+  }
+  if (p0->bf16) {
+    PD_HIP(pd::replica_sum_update(p0->stream, grads, p0->master, p0->master, p0->mom,
+                                  reinterpret_cast<pd::bf16_t*>(p0->ring_slot(nv)), p0->p_pad, p0->rule));
+  } else {
+    PD_HIP(pd::replica_sum_update(p0->stream, grads, reinterpret_cast<const float*>(p0->ring_slot(p0->latest)),
+                                  reinterpret_cast<float*>(p0->ring_slot(nv)), p0->mom, nullptr, p0->p_pad, p0->rule));
+  }
+  PD_HIP(hipEventRecord(p0->ev_rep, p0->stream));
+  for (int q = 0; q < n_replicas; ++q) {
+    pd_stage* r = replicas[q];
+    if (q > 0 && r->stream != p0->stream) PD_HIP(hipStreamWaitEvent(r->stream, p0->ev_rep, 0));
+    r->latest = nv;
+    if (r->grad_pending) r->trace.push_back({PD_OP_U, r->pending_mb, nv, nv % r->ring_depth});
+    r->grad_pending = false;
+  }
   return PD_OK;
 }
 
@@ -1414,6 +1588,7 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
     pd_stage* st = stages[s];
     if (!st) return fail(PD_EINVAL, "stage %d is null", s);
     if (st->stage_index != s || st->num_stages != S) return fail(PD_EINVAL, "stage %d has index %d of %d", s, st->stage_index, st->num_stages);
+    if (st->n_replicas > 1) return fail(PD_EINVAL, "stage %d is replicated: its replicas are driven op by op", s);
     if (st->B != stages[0]->B || st->bf16 != stages[0]->bf16) return fail(PD_EINVAL, "stage %d: minibatch/precision differ", s);
     if (s > 0 && (st->lin.front().in != stages[s - 1]->lin.back().out || st->lin.front().rows != stages[s - 1]->lin.back().rows))
       return fail(PD_EINVAL, "stage %d input shape mismatch", s);

@@ -1,27 +1,33 @@
-// Stand-alone momentum-SGD update into the version ring, for parameters whose gradient was
-// materialised by another kernel:  m <- mu*m + g ;  w <- w_in - lr*m ;  ring <- bf16(w).
-// Pure streaming work: per parameter it reads g, w, m (12 bytes) and writes w, m and the bf16 ring copy
-// (10 bytes) in bf16 mode; in fp32 mode w_in is the ring slot of the latest version and w_out the next one.
+// The update of a replicated stage (Section 3.3 round-robin replicas; Section 4: new parameters are handed out once
+// the gradients of all replicas have been aggregated): the replicas leave their fp32 gradients of one round in
+// separate buffers, and this kernel adds them up in replica order, takes the optimiser step on the one shared
+// parameter state and writes the next slot of the version ring.
+// Pure streaming work: per parameter it reads `count` gradients, w and the state (4*count + 8 bytes) and writes w,
+// the state and, in bf16 mode, the ring copy (8 + 2 bytes).  In fp32 mode w_in is the ring slot of the latest
+// version and w_out the next one; in bf16 mode w_in = w_out = the fp32 master copy.
 #include "bf16_util.h"
 #include "pd_kernels.h"
 
 namespace pd {
 namespace {
 
-
-__global__ __launch_bounds__(256) void sgd_momentum_kernel(const float* __restrict__ g, const float* w_in,
-                                                           float* w_out, float* __restrict__ mom,
-                                                           bf16_t* __restrict__ ring, size_t n, float lr, float mu) {
+__global__ __launch_bounds__(256) void replica_sum_update_kernel(ReplicaGrads grads, const float* w_in, float* w_out,
+                                                                 float* __restrict__ state, bf16_t* __restrict__ ring,
+                                                                 size_t n, UpdateRule rule) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t n4 = n / 4;
   for (size_t i = tid; i < n4; i += stride) {
-    const float4 gv = g ? reinterpret_cast<const float4*>(g)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 m = reinterpret_cast<const float4*>(mom)[i];
+    float4 g = reinterpret_cast<const float4*>(grads.g[0])[i];
+    for (int q = 1; q < grads.count; ++q) {
+      const float4 h = reinterpret_cast<const float4*>(grads.g[q])[i];
+      g.x += h.x; g.y += h.y; g.z += h.z; g.w += h.w;
+    }
+    float4 m = reinterpret_cast<const float4*>(state)[i];
     float4 w = reinterpret_cast<const float4*>(w_in)[i];
-    m.x = mu * m.x + gv.x; m.y = mu * m.y + gv.y; m.z = mu * m.z + gv.z; m.w = mu * m.w + gv.w;
-    w.x -= lr * m.x; w.y -= lr * m.y; w.z -= lr * m.z; w.w -= lr * m.w;
-    reinterpret_cast<float4*>(mom)[i] = m;
+    apply_update(rule, g.x, m.x, w.x); apply_update(rule, g.y, m.y, w.y);
+    apply_update(rule, g.z, m.z, w.z); apply_update(rule, g.w, m.w, w.w);
+    reinterpret_cast<float4*>(state)[i] = m;
     reinterpret_cast<float4*>(w_out)[i] = w;
     if (ring) {
       uint2 pk;
@@ -31,9 +37,11 @@ __global__ __launch_bounds__(256) void sgd_momentum_kernel(const float* __restri
     }
   }
   for (size_t i = n4 * 4 + tid; i < n; i += stride) {
-    const float m = mu * mom[i] + (g ? g[i] : 0.f);
-    const float w = w_in[i] - lr * m;
-    mom[i] = m;
+    float g = grads.g[0][i];
+    for (int q = 1; q < grads.count; ++q) g += grads.g[q][i];
+    float m = state[i], w = w_in[i];
+    apply_update(rule, g, m, w);
+    state[i] = m;
     w_out[i] = w;
     if (ring) ring[i] = f2bf(w);
   }
@@ -41,14 +49,14 @@ __global__ __launch_bounds__(256) void sgd_momentum_kernel(const float* __restri
 
 }  // namespace
 
-hipError_t sgd_momentum_update(hipStream_t s, const float* g, const float* w_in, float* w_out, float* mom,
-                               bf16_t* ring, size_t n, float lr, float mu, int grid_blocks) {
+hipError_t replica_sum_update(hipStream_t s, const ReplicaGrads& grads, const float* w_in, float* w_out, float* state,
+                              bf16_t* ring, size_t n, UpdateRule rule) {
   if (n == 0) return hipSuccess;
+  if (grads.count < 1 || grads.count > kMaxReplicas || rule.kind == kRuleGradOnly) return hipErrorInvalidValue;
   size_t blocks = (n / 4 + 255) / 256;
-  const size_t cap = grid_blocks > 0 ? (size_t)grid_blocks : 8192;
-  if (blocks > cap) blocks = cap;
+  if (blocks > 8192) blocks = 8192;  // 32 workgroups per compute unit; the loop strides over the rest
   if (blocks < 1) blocks = 1;
-  sgd_momentum_kernel<<<(unsigned)blocks, 256, 0, s>>>(g, w_in, w_out, mom, ring, n, lr, mu);
+  replica_sum_update_kernel<<<(unsigned)blocks, 256, 0, s>>>(grads, w_in, w_out, state, ring, n, rule);
   return hipGetLastError();
 }
 

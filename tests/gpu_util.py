@@ -41,13 +41,13 @@ class GpuStage:
 
     def __init__(self, layers, params, *, minibatch, precision, stage_index=0, num_stages=1, noam=1,
                  in_flight_override=0, lr=0.01, momentum=0.9, stream=None, in_hw=None, vertical_sync=False,
-                 optimizer=0, eps=0.0):
+                 optimizer=0, eps=0.0, replicas=0):
         self.bf16 = precision == pd.PD_BF16_F32ACC
         self.stream = stream if stream is not None else torch.cuda.current_stream()
         self.cfg = pd.make_config(layers, stage_index=stage_index, num_stages=num_stages, noam=noam,
                                   in_flight_override=in_flight_override, minibatch=minibatch, precision=precision,
                                   lr=lr, momentum=momentum, stream=self.stream.cuda_stream, in_hw=in_hw,
-                                  vertical_sync=vertical_sync, optimizer=optimizer, eps=eps)
+                                  vertical_sync=vertical_sync, optimizer=optimizer, eps=eps, replicas=replicas)
         self.bytes = pd.pd_stage_query_bytes(self.cfg)
         self.arena = torch.empty(self.bytes + 256, dtype=torch.uint8, device=dev())
         base = (self.arena.data_ptr() + 255) // 256 * 256
@@ -61,6 +61,58 @@ class GpuStage:
             self.stream.synchronize()
             pd.pd_stage_destroy(self.h)
             self.h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class GpuReplica:
+    """A further replica of a replicated stage (pd_stage_create_replica): own arena and stream, shared parameters."""
+
+    def __init__(self, primary: GpuStage, stream=None):
+        self.bf16 = primary.bf16
+        self.stream = stream if stream is not None else torch.cuda.Stream()
+        self.bytes = pd.pd_stage_replica_query_bytes(primary.cfg)
+        self.arena = torch.empty(self.bytes + 256, dtype=torch.uint8, device=dev())
+        base = (self.arena.data_ptr() + 255) // 256 * 256
+        torch.cuda.synchronize()
+        self.h = pd.pd_stage_create_replica(primary.h, self.stream.cuda_stream, base, self.bytes)
+
+    def close(self):
+        if self.h:
+            self.stream.synchronize()
+            pd.pd_stage_destroy(self.h)
+            self.h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class GpuReplicatedStage:
+    """Primary + further replicas; `rep[q].h` are the handles in replica order."""
+
+    def __init__(self, layers, params, replicas, *, same_stream=False, **kw):
+        self.r = replicas
+        first = GpuStage(layers, params, replicas=replicas, **kw)
+        self.rep = [first] + [GpuReplica(first, first.stream if same_stream else None) for _ in range(replicas - 1)]
+        self.h = first.h
+        self.bf16 = first.bf16
+
+    def handles(self):
+        return [g.h for g in self.rep]
+
+    def update(self):
+        pd.pd_update_replicated(self.handles())
+
+    def close(self):
+        for g in reversed(self.rep):     # further replicas first
+            g.close()
 
     def __del__(self):
         try:

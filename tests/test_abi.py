@@ -107,3 +107,25 @@ def test_query_bytes_and_config_errors():
     assert e.value.status == pd.PD_EINVAL and "eps" in str(e.value)
     ok = pd.make_config([("linear", 8, 8, False)], minibatch=4, optimizer=pd.PD_OPT_RMSPROP, eps=1.0)
     assert pd.pd_stage_query_bytes(ok) > 0
+
+
+def test_replica_routing_and_config():
+    assert [pd.pd_replica_route(i, 3) for i in range(7)] == [(0, 0), (1, 0), (2, 0), (0, 1), (1, 1), (2, 1), (0, 2)]
+    for bad in ((-1, 2), (3, 0)):
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_replica_route(*bad)
+        assert e.value.status == pd.PD_EINVAL
+    layers = [("linear", 64, 32, True), ("linear", 32, 16, False)]
+    one = pd.pd_stage_query_bytes(pd.make_config(layers, minibatch=8, in_flight_override=2))
+    cfg = pd.make_config(layers, minibatch=8, in_flight_override=2, replicas=2)
+    first, more = pd.pd_stage_query_bytes(cfg), pd.pd_stage_replica_query_bytes(cfg)
+    n_par = 64 * 32 + 32 + 32 * 16 + 16
+    # the primary adds one gradient buffer; a further replica has no ring (2 versions) and no optimiser state
+    assert 4 * n_par <= first - one <= 4 * n_par + 1024
+    assert 3 * 4 * n_par <= first - more <= 3 * 4 * n_par + 4096
+    for kw in (dict(replicas=9), dict(replicas=-1), dict(replicas=2, vertical_sync=True)):
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_stage_query_bytes(pd.make_config(layers, minibatch=8, **kw))
+        assert e.value.status == pd.PD_EINVAL
+    with pytest.raises(pd.PdError):      # a further replica of a stage that is not replicated
+        pd.pd_stage_replica_query_bytes(pd.make_config(layers, minibatch=8))
