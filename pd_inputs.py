@@ -68,6 +68,15 @@ def normal(seed: int, name: str, shape, dtype=np.float32) -> np.ndarray:
     return z[:n].reshape(shape).astype(dtype)
 
 
+def normal_bulk(seed: int, name: str, shape) -> np.ndarray:
+    """N(0,1) float32 samples for tensors of 10^8 elements and more, where the element-addressable generator above
+    would take minutes: numpy's Philox bit generator keyed by the same (seed, name) hash.  Seeded and reproducible,
+    but not element-addressable."""
+    key = int(_stream_base(seed, name))
+    rng = np.random.Generator(np.random.Philox(key=key))
+    return rng.standard_normal(int(np.prod(shape)), dtype=np.float32).reshape(shape)
+
+
 def uniform(seed: int, name: str, shape, lo: float, hi: float, dtype=np.float32) -> np.ndarray:
     n = int(np.prod(shape))
     u = uniform01(seed, name, n)

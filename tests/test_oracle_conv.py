@@ -132,3 +132,18 @@ def test_conv_finite_differences():
         fm = Stage(layers, p0 - e, depth=1).forward(0, x, y)[1]
         fd = (fp - fm) / (2 * h)
         assert abs(fd - st.grad[k]) < 2e-7 * max(1.0, abs(fd)), k
+
+
+def test_sampled_patches_equal_the_whole_convolution():
+    # the helpers the full-size GPU tests use to get single outputs from the oracle, against the oracle run whole
+    from sampling import conv_dx_at, conv_y_at, positions
+    N, H, W, ci, co = 3, 6, 7, 5, 4
+    x = L.round_bf16(gen.normal(SEED, "sx", (N, H, W, ci)))
+    w = L.round_bf16(gen.uniform(SEED, "sw", (co, 3, 3, ci), -0.3, 0.3))
+    b = L.round_bf16(gen.normal(SEED, "sb", (co,)))
+    dz = L.round_bf16(gen.normal(SEED, "sd", (N, H, W, co)))
+    y = L.conv2d_forward(x, w, b, 1, 1, 1, True, L.round_bf16)
+    dx, _, _ = L.conv2d_backward(x, w, np.ones_like(y), dz, 1, 1, 1, False, True, L.round_bf16)
+    for n, h, ww in positions(N, H, W, 40, SEED):
+        assert np.array_equal(conv_y_at(x, w, b, n, h, ww, True), y[n, h, ww])
+        assert np.allclose(conv_dx_at(dz, w, n, h, ww), dx[n, h, ww], rtol=0, atol=2.0 ** -8 * np.abs(dx).max())
