@@ -551,10 +551,6 @@ def main():
     seed = gen.BASE_SEED + 1
     params = gen.init_params(seed, "vgg_fc", layers)
     P = int(params.size)
-    n_pool = 8
-    xs = [gen.normal(seed, f"x{i}", (B, n_in)) for i in range(n_pool)]
-    labs = [gen.labels(seed, f"y{i}", (B,), classes) for i in range(n_pool)]
-
     stream = torch.cuda.Stream(device=dev)
     cfg = pd.make_config(layers, in_flight_override=depth, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=0.01,
                          momentum=0.9, stream=stream.cuda_stream)
@@ -562,6 +558,10 @@ def main():
     arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
     h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
     pd.pd_stage_set_params(h, params)
+    in_ring = pd.pd_stage_depth(h)[1]     # slots of the stage's input ring
+    n_pool = in_ring                      # one synthetic minibatch per slot: slot mb % in_ring always holds pool entry mb % n_pool
+    xs = [gen.normal(seed, f"x{i}", (B, n_in)) for i in range(n_pool)]
+    labs = [gen.labels(seed, f"y{i}", (B,), classes) for i in range(n_pool)]
     xd = [torch.from_numpy(x).to(dev).to(torch.bfloat16).contiguous() for x in xs]
     ld = [torch.from_numpy(l).to(dev) for l in labs]
     dx = torch.empty((B, n_in), dtype=torch.bfloat16, device=dev)
@@ -570,32 +570,35 @@ def main():
 
     mb_next = 0
 
-    def fwd():
+    def fwd(in_place=False):
+        # in_place: the minibatch already lies in the stage's input ring, where an upstream stage (or the data
+        # loader) leaves it; pd_forward then reads it there instead of copying it in first
         nonlocal mb_next
         i = mb_next % n_pool
-        pd.pd_forward(h, mb_next, xd[i].data_ptr(), ld[i].data_ptr(), 0, loss.data_ptr())
+        x_ptr = pd.pd_stage_input_slot(h, mb_next) if in_place else xd[i].data_ptr()
+        pd.pd_forward(h, mb_next, x_ptr, ld[i].data_ptr(), 0, loss.data_ptr())
         mb_next += 1
 
-    def step(k, ev=None):
+    def step(k, ev=None, in_place=False):
         pd.pd_backward(h, k, 0, dx.data_ptr())
         if ev is not None:
             ev[0].record(stream)
         pd.pd_update(h)
         if ev is not None:
             ev[1].record(stream)
-        fwd()
+        fwd(in_place)
 
     for _ in range(depth):
         fwd()
     k = 0
-    for _ in range(W):
+    for _ in range(max(W, in_ring)):      # (every slot of the input ring has received a minibatch after this)
         step(k)
         k += 1
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for j in range(K):
-        step(k, evs[j])
+        step(k, evs[j], in_place=True)
         k += 1
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -615,7 +618,7 @@ def main():
         "config": {"workload": ("REDUCED " if args.small else "") +
                    f"VGG16-FC-shaped stage: Linear {n_in}-{layers[0][2]}-{layers[1][2]}-{classes} + ReLU + "
                    f"softmax-xent, bf16 w/ fp32 accum, minibatch {B}, weight-version ring depth {depth}, "
-                   "step = B(k) U(k) F(k+depth)",
+                   "step = B(k) U(k) F(k+depth), inputs resident in the stage's input ring",
                    "params": P, "minibatch": B, "ring_depth": depth},
         "mfma_util_pct": 100.0 * flops / (ms_per_step * 1e-3) / MFMA_BF16_PEAK,
         "step_gflop": flops / 1e9,

@@ -238,7 +238,8 @@ __device__ __forceinline__ void nt_store4(float* p, float4 v) {
   __builtin_nontemporal_store(t, reinterpret_cast<vf4_t*>(p));
 }
 
-template <int TN, int TK, bool NFAST, bool PREFETCH>
+// KIND: the update rule (UpdateRule::kind) as a compile-time constant.
+template <int TN, int TK, bool NFAST, bool PREFETCH, int KIND>
 __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch) {
   // which layer this workgroup belongs to (all layers of a stage are updated by one launch)
   int li = 0;
@@ -375,12 +376,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
         m = *reinterpret_cast<const float4*>(mom + off);
         wv = *reinterpret_cast<const float4*>(master + off);
       }
-      if (rule.kind == kRuleGradOnly) {  // replicated stage: the sum over replicas comes first
+      if (KIND == kRuleGradOnly) {  // replicated stage: the sum over replicas comes first
         *reinterpret_cast<float4*>(master + off) = g;
         continue;
       }
-      apply_update(rule, g.x, m.x, wv.x); apply_update(rule, g.y, m.y, wv.y);
-      apply_update(rule, g.z, m.z, wv.z); apply_update(rule, g.w, m.w, wv.w);
+      apply_update_as<KIND>(rule, g.x, m.x, wv.x); apply_update_as<KIND>(rule, g.y, m.y, wv.y);
+      apply_update_as<KIND>(rule, g.z, m.z, wv.z); apply_update_as<KIND>(rule, g.w, m.w, wv.w);
       nt_store4(mom + off, m);     // streamed once per step: keep these lines out of the caches
       nt_store4(master + off, wv);
       uint2 pk;
@@ -397,12 +398,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
     if (n < N) {
       float g = 0.f;
       for (int m = 0; m < M; ++m) g += bf2f(dZ[(size_t)m * N + n]);
-      if (rule.kind == kRuleGradOnly) {
+      if (KIND == kRuleGradOnly) {
         master_b[n] = g;
         return;
       }
       float mv = mom_b[n], bv = master_b[n];
-      apply_update(rule, g, mv, bv);
+      apply_update_as<KIND>(rule, g, mv, bv);
       mom_b[n] = mv;
       master_b[n] = bv;
       ring_b[n] = f2bf(bv);
@@ -418,7 +419,12 @@ hipError_t launch_wgrad_update(hipStream_t s, WgradBatch batch) {
     batch.layer[i].tile_end = tiles;
   }
   if (tiles == 0) return hipSuccess;
-  wgrad_update_kernel<TN, TK, NFAST, PREFETCH><<<tiles, kThreads, 0, s>>>(batch);
+  switch (batch.rule.kind) {
+    case 0: wgrad_update_kernel<TN, TK, NFAST, PREFETCH, 0><<<tiles, kThreads, 0, s>>>(batch); break;
+    case 1: wgrad_update_kernel<TN, TK, NFAST, PREFETCH, 1><<<tiles, kThreads, 0, s>>>(batch); break;
+    case kRuleGradOnly: wgrad_update_kernel<TN, TK, NFAST, false, kRuleGradOnly><<<tiles, kThreads, 0, s>>>(batch); break;
+    default: return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 
@@ -479,6 +485,8 @@ int set_big_tile_threshold(int min_tiles) {
   if (min_tiles >= 1) g_big_min_tiles = min_tiles;
   return old;
 }
+
+bool linear_fwd_uses_big_tiles(int M, int N) { return use_big_tiles(M, N); }
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K) {
   if (use_big_tiles(M, K)) return linear_dgrad_big_scratch_bytes(N, K);  // transposed weights; no split-K at this size

@@ -107,6 +107,83 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restri
   if (t == 0) row_loss[r] = logf(sum) + mx - ld(lab);
 }
 
+// The loss of a stage whose last Linear layer left split-K partial sums: logits = bias + sum over the partials (in
+// split order), written out once (fp32) for the backward pass and for readers of the stage's output, and the
+// softmax / cross-entropy of the row taken from registers in the same pass.  classes <= 256 * NV.
+template <bool BF, int NV>
+__global__ __launch_bounds__(256) void softmax_xent_partials_kernel(const float* __restrict__ part, int splits,
+                                                                    const bf16_t* __restrict__ bias,
+                                                                    float* __restrict__ logits,
+                                                                    const int32_t* __restrict__ labels,
+                                                                    void* __restrict__ dlogits, float* __restrict__ row_loss,
+                                                                    int rows, int classes) {
+  __shared__ float sh[256];
+  const int r = blockIdx.x, t = threadIdx.x;
+  const size_t base = (size_t)r * classes, stride = (size_t)rows * classes;
+  int lab = labels[r];
+  lab = lab < 0 ? 0 : (lab >= classes ? classes - 1 : lab);
+  float v[NV];
+  float mx = -INFINITY, zlab = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) v[i] = 0.f;
+  // Partial sums in split order.  A workgroup per row leaves few waves to hide the latency of dependent loads, so
+  // the loads of eight splits are issued together and only then added; columns past the row read element 0 of the
+  // row and are ignored later, splits past the last one re-read the last split and are multiplied by zero.
+  for (int q0 = 0; q0 < splits; q0 += 8) {
+    float p[8][NV];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int q = q0 + u < splits ? q0 + u : splits - 1;
+      const float* src = part + (size_t)q * stride + base;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = t + 256 * i;
+        p[u][i] = src[c < classes ? c : 0];
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);  // all loads first: the scheduler otherwise pairs every load with its add
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float keep = q0 + u < splits ? 1.f : 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) v[i] = fmaf(keep, p[u][i], v[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = t + 256 * i;
+    if (c < classes) {
+      const float z = v[i] + (bias ? bf2f(bias[c]) : 0.f);
+      logits[base + c] = z;
+      v[i] = z;
+      mx = fmaxf(mx, z);
+      if (c == lab) zlab = z;
+    }
+  }
+  mx = block_reduce(mx, sh, true);
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    if (t + 256 * i < classes) {
+      v[i] = expf(v[i] - mx);
+      sum += v[i];
+    }
+  sum = block_reduce(sum, sh, false);
+  const float inv = 1.f / sum, invr = 1.f / (float)rows;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = t + 256 * i;
+    if (c < classes) {
+      float d = v[i] * inv;
+      if (c == lab) d -= 1.f;
+      d *= invr;
+      if (BF) static_cast<uint16_t*>(dlogits)[base + c] = f2bf(d);
+      else static_cast<float*>(dlogits)[base + c] = d;
+    }
+  }
+  if (lab % 256 == t) row_loss[r] = logf(sum) + mx - zlab;  // the thread that holds the label's logit
+}
+
 // The same for wide rows (a vocabulary): the row is read ONCE, 16 bytes per lane, and stays in registers
 // (NV float4 per thread, classes <= 1024 NV) for the maximum, the sum and the result; bf16 results leave as 8-byte
 // stores.  Needs classes % 4 == 0 and 16-byte aligned rows.
@@ -223,6 +300,18 @@ hipError_t softmax_xent(hipStream_t s, const float* logits, const int32_t* label
     else softmax_xent_wide_kernel<false, 32><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
   } else if (dlogits_bf16) softmax_xent_kernel<true><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
   else softmax_xent_kernel<false><<<rows, 256, 0, s>>>(logits, labels, dlogits, row_loss, rows, classes);
+  if (loss) mean_kernel<<<1, 256, 0, s>>>(row_loss, rows, loss);
+  return hipGetLastError();
+}
+
+hipError_t softmax_xent_partials(hipStream_t s, const float* part, int splits, const bf16_t* bias, float* logits,
+                                 const int32_t* labels, void* dlogits, float* row_loss, float* loss, int rows,
+                                 int classes, bool dlogits_bf16) {
+  if (classes > kFusedLossMaxClasses || splits < 1) return hipErrorInvalidValue;
+  if (dlogits_bf16)
+    softmax_xent_partials_kernel<true, kFusedLossMaxClasses / 256><<<rows, 256, 0, s>>>(part, splits, bias, logits, labels, dlogits, row_loss, rows, classes);
+  else
+    softmax_xent_partials_kernel<false, kFusedLossMaxClasses / 256><<<rows, 256, 0, s>>>(part, splits, bias, logits, labels, dlogits, row_loss, rows, classes);
   if (loss) mean_kernel<<<1, 256, 0, s>>>(row_loss, rows, loss);
   return hipGetLastError();
 }

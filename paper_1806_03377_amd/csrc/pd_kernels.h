@@ -21,14 +21,20 @@ struct UpdateRule {
 };
 constexpr int kRuleGradOnly = 2;
 constexpr int kMaxReplicas = 8;
-__host__ __device__ __forceinline__ void apply_update(const UpdateRule& u, float g, float& s, float& w) {
-  if (u.kind == 0) {
+// (the rule as a compile-time constant, for kernels whose inner loop should not carry the choice)
+template <int KIND>
+__host__ __device__ __forceinline__ void apply_update_as(const UpdateRule& u, float g, float& s, float& w) {
+  if (KIND == 0) {
     s = u.a * s + g;
     w -= u.lr * s;
   } else {
     s = u.a * s + (1.f - u.a) * g * g;
     w -= u.lr * g / (sqrtf(s) + u.eps);
   }
+}
+__host__ __device__ __forceinline__ void apply_update(const UpdateRule& u, float g, float& s, float& w) {
+  if (u.kind == 0) apply_update_as<0>(u, g, s, w);
+  else apply_update_as<1>(u, g, s, w);
 }
 
 // ---- bf16 x bf16 -> fp32-accumulate MFMA GEMMs (gemm_bf16.hip) ---------------------------------
@@ -219,5 +225,14 @@ hipError_t relu_mask(hipStream_t s, const void* dy, const void* y, void* dz, siz
 // logits are always fp32; dlogits are bf16 if dlogits_bf16, else fp32.
 hipError_t softmax_xent(hipStream_t s, const float* logits, const int32_t* labels, void* dlogits, float* row_loss,
                         float* loss, int rows, int classes, bool dlogits_bf16);
+// The same when the logits still are split-K partial sums part[split][rows][classes] (+ bias[classes], may be null):
+// adds them up in split order, writes the fp32 logits once, and takes the loss from registers.  classes <=
+// kFusedLossMaxClasses.
+constexpr int kFusedLossMaxClasses = 2048;
+hipError_t softmax_xent_partials(hipStream_t s, const float* part, int splits, const bf16_t* bias, float* logits,
+                                 const int32_t* labels, void* dlogits, float* row_loss, float* loss, int rows,
+                                 int classes, bool dlogits_bf16);
+// Whether linear_fwd_bf16 would hand this shape to the compute-bound large-tile kernel (which has no split-K).
+bool linear_fwd_uses_big_tiles(int M, int N);
 
 }  // namespace pd

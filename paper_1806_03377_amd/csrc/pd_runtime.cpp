@@ -496,6 +496,10 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
         if (r < one) r = one;
         if (r > w) w = r;
       }
+      if (p.has_loss && &L == &p.lin.back()) {  // the logits may be left as partial sums for the loss kernel
+        const size_t one = (size_t)L.rows * L.out * 4;
+        if (one > w) w = one;
+      }
       if (L.splits > 0) {  // many rows: room for the transposed operands of the weight-gradient products
         const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
         const size_t t1 = pd::linear_wgrad_big_scratch_bytes(L.rows, n_out, L.in > L.out ? L.in : L.out);
@@ -1093,6 +1097,8 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
   const char* w = st->ring_slot(v);
   if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->lin.front().rows * st->lin.front().in * st->esz));
   PD_HIP(st->mark(-1, 0));
+  int loss_splits = 0;                    // > 0: the last Linear layer left this many partial sums in the workspace
+  const pd::bf16_t* loss_bias = nullptr;
   for (int li = 0; li < (int)st->lin.size(); ++li) {
     if (li > 0) PD_HIP(st->mark(0, li - 1));
     const Layer& L = st->lin[li];
@@ -1102,6 +1108,14 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
       if (st->bf16) {
         const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
         const bool logits = st->has_loss && &L == &st->lin.back();  // logits go to the loss unrounded (fp32)
+        if (logits && L.out <= pd::kFusedLossMaxClasses && !pd::linear_fwd_uses_big_tiles(L.rows, L.out) &&
+            (size_t)L.rows * L.out * 4 <= st->ws_bytes) {
+          // leave the split-K partial sums: the loss kernel adds them up, writes the logits and takes the loss
+          PD_HIP(pd::gemm_partial_bf16(s, false, reinterpret_cast<const pd::bf16_t*>(a), 0, wp + L.w_off, L.rows,
+                                       L.out, L.in, st->ws, st->ws_bytes, &loss_splits));
+          loss_bias = wp + L.b_off;
+          continue;
+        }
         PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, wp + L.b_off,
                                    reinterpret_cast<pd::bf16_t*>(y), logits ? reinterpret_cast<float*>(y) : nullptr,
                                    L.rows, L.out, L.in, L.relu, st->ws, st->ws_bytes));
@@ -1149,11 +1163,17 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
                                       reinterpret_cast<pd::bf16_t*>(y), L.oc, L.b_coff[b], nullptr, pixels, L.b_c[b]));
     }
   }
-  const char* a = st->out_of(slot, (int)st->lin.size() - 1);
+  char* a = st->out_of(slot, (int)st->lin.size() - 1);
+  if (st->has_loss) {
+    if (loss_splits > 0)
+      PD_HIP(pd::softmax_xent_partials(s, st->ws, loss_splits, loss_bias, reinterpret_cast<float*>(a), labels_dev,
+                                       slot + st->dlogits_off, st->row_loss, loss_dev, st->lin.back().rows, st->classes,
+                                       st->bf16));
+    else
+      PD_HIP(pd::softmax_xent(s, reinterpret_cast<const float*>(a), labels_dev, slot + st->dlogits_off, st->row_loss,
+                              loss_dev, st->lin.back().rows, st->classes, st->bf16));
+  }
   if (y_dev) PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->lin.back().rows * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
-  if (st->has_loss)
-    PD_HIP(pd::softmax_xent(s, reinterpret_cast<const float*>(a), labels_dev, slot + st->dlogits_off, st->row_loss,
-                            loss_dev, st->lin.back().rows, st->classes, st->bf16));
   PD_HIP(st->mark(0, (int)st->lin.size() - 1));  // (the loss and the copy of the output count for the last layer)
   if (st->profiling) ++st->prof_ops[0];
   st->in_flight.push_back({mb_id, v});
