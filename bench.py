@@ -26,7 +26,7 @@ MFMA_BF16_PEAK = 2.5e15
 UPDATE_BYTES_PER_PARAM = 18  # read fp32 master + momentum, write both, write the bf16 ring copy
 # HBM bytes per launch of the dominant kernel at the default workload, from the rocprofv3 counter runs
 # summarised in profiles/wgrad_update_vgg16fc_mb64.txt (FETCH_SIZE x 1.986 + WRITE_SIZE x 1.000)
-MEASURED_TRAFFIC_BYTES = 2.236e9
+MEASURED_TRAFFIC_BYTES = 2.238e9
 
 
 def cpu_baseline(layers, params, xs, labs, depth, budget_s=12.0, max_steps=16):
