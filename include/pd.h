@@ -201,7 +201,7 @@ int pd_stage_destroy(pd_stage* st);
  *   gradient kernels run on that replica's stream; the summed step runs on the primary's stream once every replica's
  *   stream has reached this call, and every replica's stream waits for it, so no host synchronisation is needed
  *   between the call and the next pd_forward.  pd_update on a replicated stage returns PD_ESTATE; pd_pipeline_run
- *   does not take replicated stages (PD_EINVAL). */
+ *   does not take replicated stages (PD_EINVAL): pd_pipeline_run_replicated does. */
 int pd_replica_route(int32_t mb_id, int32_t n_replicas, int32_t* replica, int32_t* round);
 int pd_stage_replica_query_bytes(const pd_stage_config* cfg, size_t* device_bytes);
 int pd_stage_create_replica(pd_stage* primary, void* stream, void* device_arena, size_t arena_bytes, pd_stage** out);
@@ -331,6 +331,18 @@ int pd_update(pd_stage* st);
  * ids continue from each stage's last forward (or 0). */
 int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_minibatches,
                     const void* inputs_dev, const int32_t* labels_dev, float* losses_dev);
+/* The same for a pipeline whose stages may be replicated (Section 3.3: the 1F1B policy and the round-robin routing are
+ * both static, so every replica's op list is known in advance).  `replicas` lists all stage objects stage by stage,
+ * each stage's primary first and its further replicas in creation order; replicas_per_stage[s] = r_s (1 for a stage
+ * that is not replicated).  Minibatch i is round i div r_s of replica i mod r_s in stage s; each replica follows the
+ * stage's 1F1B list over its rounds on its own stream; the update of a round is joint (pd_update_replicated) and waits
+ * for the round's backward passes on every replica that has a minibatch in it.  Hand-off as in pd_pipeline_run, into
+ * the input / gradient slot of the replica that holds the minibatch in the neighbouring stage.  All stages must be
+ * freshly initialised (nothing run since pd_stage_set_params); no vertical sync.  inputs_dev, labels_dev and losses_dev
+ * are indexed by minibatch i as above. */
+int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replicas_per_stage, int32_t num_stages,
+                               int32_t num_minibatches, const void* inputs_dev, const int32_t* labels_dev,
+                               float* losses_dev);
 
 /* --- profiling and partitioning (Section 3.2) -----------------------------------------------
  * The step before the pipeline runs: measure every layer on the device, then choose the stages.

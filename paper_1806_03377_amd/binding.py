@@ -92,6 +92,7 @@ _SIGS = {
     "pd_backward": [_vp, _i32, _vp, _vp],
     "pd_update": [_vp],
     "pd_pipeline_run": [C.POINTER(_vp), _i32, _i32, _vp, _vp, _vp],
+    "pd_pipeline_run_replicated": [C.POINTER(_vp), C.POINTER(_i32), _i32, _i32, _vp, _vp, _vp],
     "pd_stage_checkpoint_save": [_vp, C.c_char_p],
     "pd_stage_checkpoint_load": [_vp, C.c_char_p],
     "pd_checkpoint_info": [C.c_char_p, C.POINTER(_sz), C.POINTER(_i32), C.POINTER(_i32)],
@@ -389,6 +390,16 @@ def pd_pipeline_run(stages: Sequence[int], num_minibatches: int, inputs_dev: int
                     losses_dev: int = 0):
     arr = (_vp * len(stages))(*stages)
     _check(_lib.pd_pipeline_run(arr, len(stages), num_minibatches, inputs_dev, labels_dev, losses_dev or None))
+
+
+def pd_pipeline_run_replicated(replicas_by_stage: Sequence[Sequence[int]], num_minibatches: int, inputs_dev: int,
+                               labels_dev: int, losses_dev: int = 0):
+    """replicas_by_stage[s] = the handles of stage s, primary first."""
+    flat = [h for st in replicas_by_stage for h in st]
+    arr = (_vp * len(flat))(*flat)
+    per = (_i32 * len(replicas_by_stage))(*[len(st) for st in replicas_by_stage])
+    _check(_lib.pd_pipeline_run_replicated(arr, per, len(replicas_by_stage), num_minibatches, inputs_dev, labels_dev,
+                                           losses_dev or None))
 
 
 def pd_stage_checkpoint_save(stage: int, path: str):

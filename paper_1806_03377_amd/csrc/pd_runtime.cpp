@@ -1691,6 +1691,141 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
   return PD_OK;
 }
 
+// A pipeline whose stages may be replicated (Section 3.3: both the 1F1B policy and the round-robin routing are static,
+// so every replica's op list is known in advance).  Replica q of stage s works on minibatches i with i mod r_s == q,
+// as its round k = i div r_s; the update of round k of a replicated stage is joint.
+int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replicas_per_stage, int32_t num_stages,
+                               int32_t num_minibatches, const void* inputs_dev, const int32_t* labels_dev,
+                               float* losses_dev) {
+  if (!replicas || !replicas_per_stage || num_stages < 1) return fail(PD_EINVAL, "no stages");
+  if (num_minibatches < 0) return fail(PD_EINVAL, "num_minibatches < 0");
+  if (num_minibatches == 0) return PD_OK;
+  if (!inputs_dev || !labels_dev) return fail(PD_EINVAL, "inputs_dev / labels_dev is null");
+  const int S = num_stages, M = num_minibatches;
+  std::vector<int> r(S), first(S);  // replicas of stage s: replicas[first[s] .. first[s] + r[s] - 1]
+  for (int s = 0, n = 0; s < S; ++s) {
+    r[s] = replicas_per_stage[s];
+    if (r[s] < 1 || r[s] > pd::kMaxReplicas) return fail(PD_EINVAL, "stage %d: %d replicas", s, r[s]);
+    first[s] = n;
+    n += r[s];
+  }
+  auto rep = [&](int s, int q) { return replicas[first[s] + q]; };
+  auto rounds = [&](int s, int q) { return q < M ? (M - q + r[s] - 1) / r[s] : 0; };  // minibatches routed to (s, q)
+  for (int s = 0; s < S; ++s) {
+    pd_stage* p0 = rep(s, 0);
+    if (!p0) return fail(PD_EINVAL, "stage %d is null", s);
+    if (p0->primary) return fail(PD_EINVAL, "stage %d: its first entry must be the primary", s);
+    if ((p0->n_replicas > 1 ? p0->n_replicas : 1) != r[s] || (int)p0->secondaries.size() + 1 != r[s])
+      return fail(PD_EINVAL, "stage %d is configured for %d replicas, %zu exist, %d were passed", s, p0->n_replicas,
+                  p0->secondaries.size() + 1, r[s]);
+    for (int q = 0; q < r[s]; ++q) {
+      pd_stage* st = rep(s, q);
+      if (!st || (q > 0 && st != p0->secondaries[q - 1])) return fail(PD_EINVAL, "stage %d: replicas must be passed in the order they were created", s);
+      if (st->stage_index != s || st->num_stages != S) return fail(PD_EINVAL, "stage %d has index %d of %d", s, st->stage_index, st->num_stages);
+      if (st->B != replicas[0]->B || st->bf16 != replicas[0]->bf16) return fail(PD_EINVAL, "stage %d: minibatch/precision differ", s);
+      if (st->vsync) return fail(PD_EINVAL, "vertical sync is not available in a pipeline with replicated stages");
+      if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "stage %d has minibatches in flight", s);
+      if (st->last_fwd != -1 || st->latest != p0->latest) return fail(PD_ESTATE, "stage %d: start from freshly set parameters", s);
+      if (st->profiling) return fail(PD_ESTATE, "stage %d: stop the layer profiler first", s);
+    }
+    if (s > 0 && (p0->lin.front().in != rep(s - 1, 0)->lin.back().out || p0->lin.front().rows != rep(s - 1, 0)->lin.back().rows))
+      return fail(PD_EINVAL, "stage %d input shape mismatch", s);
+    if (p0->has_loss != (s == S - 1)) return fail(PD_EINVAL, "only the last stage may (and must) end in the loss");
+  }
+  // op lists and events per replica (ev_f / ev_b by round; ev_u of the primary by round = the joint update)
+  std::vector<std::vector<std::vector<pd_op>>> ops(S);
+  std::vector<std::vector<size_t>> pos(S);
+  std::vector<std::vector<std::vector<char>>> f_rec(S), b_rec(S);
+  std::vector<std::vector<char>> u_rec(S);
+  size_t remaining = 0;
+  for (int s = 0; s < S; ++s) {
+    ops[s].resize(r[s]); pos[s].assign(r[s], 0); f_rec[s].resize(r[s]); b_rec[s].resize(r[s]);
+    u_rec[s].assign(rounds(s, 0), 0);
+    for (int q = 0; q < r[s]; ++q) {
+      pd_stage* st = rep(s, q);
+      const int n = rounds(s, q);
+      build_schedule(st->depth, n, ops[s][q]);
+      remaining += ops[s][q].size();
+      f_rec[s][q].assign(n, 0); b_rec[s][q].assign(n, 0);
+      for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u})
+        while ((int)v->size() < n) {
+          hipEvent_t e;
+          PD_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+          v->push_back(e);
+        }
+    }
+  }
+  const size_t in_elems = (size_t)replicas[0]->lin.front().rows * replicas[0]->lin.front().in * replicas[0]->esz;
+  // An op is enqueued only after every event it waits for has been recorded (in host order), which makes the host's
+  // enqueue order a valid global order.
+  while (remaining) {
+    bool progressed = false;
+    for (int s = 0; s < S; ++s)
+      for (int q = 0; q < r[s]; ++q) {
+        pd_stage* st = rep(s, q);
+        while (pos[s][q] < ops[s][q].size()) {
+          const pd_op op = ops[s][q][pos[s][q]];
+          const int k = op.mb_id, i = k * r[s] + q;  // round of this replica, minibatch of the stream
+          // neighbours of minibatch i: the replica and round that hold it in the stages before and after
+          const int qp = s > 0 ? i % r[s - 1] : 0, kp = s > 0 ? i / r[s - 1] : 0;
+          const int qn = s < S - 1 ? i % r[s + 1] : 0, kn = s < S - 1 ? i / r[s + 1] : 0;
+          if (op.kind == PD_OP_F) {
+            int reuse = -1;  // the round whose input last occupied the slot this forward's output goes into
+            if (s > 0 && !f_rec[s - 1][qp][kp]) break;
+            if (s < S - 1) {
+              reuse = kn - rep(s + 1, qn)->in_depth;
+              if (reuse >= 0 && !u_rec[s + 1][reuse]) break;  // its last reader is that round's update
+            }
+            if (s > 0) PD_HIP(hipStreamWaitEvent(st->stream, rep(s - 1, qp)->ev_f[kp], 0));
+            if (reuse >= 0) PD_HIP(hipStreamWaitEvent(st->stream, rep(s + 1, 0)->ev_u[reuse], 0));
+            const void* x = s == 0 ? static_cast<const char*>(inputs_dev) + (size_t)i * in_elems : st->in_slot(k);
+            void* y = s < S - 1 ? rep(s + 1, qn)->in_slot(kn) : nullptr;
+            const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->lin.back().rows : nullptr;
+            float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
+            const int rc = pd_forward(st, k, x, lab, y, loss);
+            if (rc != PD_OK) return rc;
+            PD_HIP(hipEventRecord(st->ev_f[k], st->stream));
+            f_rec[s][q][k] = 1;
+          } else if (op.kind == PD_OP_B) {
+            if (s < S - 1 && !b_rec[s + 1][qn][kn]) break;
+            if (s > 0 && kp >= 2 && !b_rec[s - 1][qp][kp - 2]) break;  // the gradient slot this backward writes into
+            if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, rep(s + 1, qn)->ev_b[kn], 0));
+            if (s > 0 && kp >= 2) PD_HIP(hipStreamWaitEvent(st->stream, rep(s - 1, qp)->ev_b[kp - 2], 0));
+            const void* dy = s < S - 1 ? st->grad_slot(k) : nullptr;
+            void* dx = s > 0 ? rep(s - 1, qp)->grad_slot(kp) : nullptr;
+            const int rc = pd_backward(st, k, dy, dx);
+            if (rc != PD_OK) return rc;
+            PD_HIP(hipEventRecord(st->ev_b[k], st->stream));
+            b_rec[s][q][k] = 1;
+          } else {
+            // joint update of round k: every replica with a minibatch in it must have reached it
+            bool ready = true;
+            for (int p = 0; p < r[s] && ready; ++p) {
+              if (rounds(s, p) <= k) continue;
+              const size_t at = pos[s][p];
+              ready = at < ops[s][p].size() && ops[s][p][at].kind == PD_OP_U && ops[s][p][at].mb_id == k;
+            }
+            if (!ready) break;
+            const int rc = r[s] > 1 ? pd_update_replicated(replicas + first[s], r[s]) : pd_update(st);
+            if (rc != PD_OK) return rc;
+            PD_HIP(hipEventRecord(rep(s, 0)->ev_u[k], rep(s, 0)->stream));
+            u_rec[s][k] = 1;
+            for (int p = 0; p < r[s]; ++p)
+              if (p != q && rounds(s, p) > k) {
+                ++pos[s][p];
+                --remaining;
+              }
+          }
+          ++pos[s][q];
+          --remaining;
+          progressed = true;
+        }
+      }
+    if (!progressed) return fail(PD_ESTATE, "pipeline cannot make progress (dependency cycle)");
+  }
+  return PD_OK;
+}
+
 int pd_set_big_tile_threshold(int32_t min_tiles) {
   pd::set_conv_wide_min_tiles(2 * min_tiles);  // same rule for the convolutions' 256 x 256 tiles (default 2 x 128)
   return pd::set_big_tile_threshold(min_tiles);

@@ -236,6 +236,52 @@ def test_pipeline_with_replicated_input_stage_f32():
         g1.close()
 
 
+@pytest.mark.parametrize("reps,depths,M", [([2, 1], [2, 1], 11), ([3, 1], [1, 1], 7), ([1, 2], [2, 1], 9),
+                                           ([2, 2, 1], [2, 2, 1], 13), ([2, 1], [1, 1], 1)])
+def test_library_driven_pipeline_with_replicated_stages_f32(reps, depths, M):
+    # pd_pipeline_run_replicated enqueues the whole stream with events only; nothing is read back before the end
+    S, B = len(reps), 6
+    sl = [[("linear", 24, 32, True)]] + [[("linear", 32, 32, True)] for _ in range(S - 2)] + \
+         [[("linear", 32, 10, False), ("softmax_xent", 10)]]
+    params = [gen.init_params(SEED + 8, f"s{s}", ly) for s, ly in enumerate(sl)]
+    xs = gen.normal(SEED + 8, "X", (M, B, 24))
+    labs = gen.labels(SEED + 8, "Y", (M, B), 10)
+    o_stages, o_losses = run_replicated_pipeline(sl, params, reps, [np.asarray(x, dtype=np.float64) for x in xs],
+                                                 list(labs), depths, lr=0.05, momentum=0.9)
+    gs = []
+    try:
+        for s in range(S):
+            kw = dict(minibatch=B, precision=pd.PD_F32, stage_index=s, num_stages=S, in_flight_override=depths[s],
+                      lr=0.05, momentum=0.9)
+            if reps[s] > 1:
+                gs.append(GpuReplicatedStage(sl[s], params[s], reps[s], stream=torch.cuda.Stream(), **kw))
+            else:
+                gs.append(GpuStage(sl[s], params[s], stream=torch.cuda.Stream(), **kw))
+        handles = [g.handles() if isinstance(g, GpuReplicatedStage) else [g.h] for g in gs]
+        x_d, l_d = to_dev(xs, False), labels_dev(labs)
+        losses = torch.zeros(M, dtype=torch.float32, device=dev())
+        torch.cuda.synchronize()
+        pd.pd_pipeline_run_replicated(handles, M, x_d.data_ptr(), l_d.data_ptr(), losses.data_ptr())
+        torch.cuda.synchronize()
+        got = to_host(losses)
+        for i in range(M):
+            assert abs(got[i] - o_losses[i]) <= 1e-4 * abs(o_losses[i]), ("loss", i, got[i], o_losses[i])
+        for s in range(S):
+            h0 = handles[s][0]
+            assert rel_err(pd.pd_stage_get_params(h0), o_stages[s].rep[0].master) <= 1e-4, ("weights", s)
+            assert rel_err(pd.pd_stage_get_momentum(h0), o_stages[s].rep[0].mom) <= 1e-4, ("momentum", s)
+            assert pd.pd_stage_version(h0) == -(-M // reps[s])
+            for q, h in enumerate(handles[s]):      # every replica ran exactly its own static list
+                want = [(op.kind, op.mb, op.version, op.slot) for op in o_stages[s].rep[q].trace
+                        if not (op.kind == OP_U and op.mb >= rounds_of(q, reps[s], M))]
+                assert pd.pd_stage_trace(h) == want, ("trace", s, q)
+        with pytest.raises(pd.PdError):              # not freshly initialised any more
+            pd.pd_pipeline_run_replicated(handles, M, x_d.data_ptr(), l_d.data_ptr(), losses.data_ptr())
+    finally:
+        for g in gs:
+            g.close()
+
+
 def test_replicated_protocol_errors():
     p, xs, labs = _mlp_data(2, 8, SEED + 7)
     g = GpuReplicatedStage(MLP, p, 2, minibatch=8, precision=pd.PD_F32, in_flight_override=1)

@@ -168,49 +168,48 @@ def test_rows_of_a_round_act_as_one_minibatch_when_there_is_no_loss():
             b.forward(k + W, cat(xs, k + W))
 
 
-def _torch_replicated_flat_loop(stage_layers, params, xs, ys, r0, depths, lr, mu):
-    """Staleness rule of a 2-stage pipeline whose input stage has r0 replicas, as a loop with no schedule:
-    minibatch i sees the input stage after max(0, i div r0 - W0 + 1) updates (one per round, summed gradient) and
-    the output stage after max(0, i - W1 + 1) updates (one per minibatch)."""
+def _torch_replicated_flat_loop(stage_layers, params, xs, ys, reps, depths, lr, mu):
+    """Staleness rule of a pipeline whose stage s has reps[s] replicas, as a loop with no schedule: minibatch i sees
+    stage s after max(0, i div r_s - W_s + 1) updates; a stage takes one momentum step per round of r_s minibatches,
+    with the sum of the round's gradients (the last round may be incomplete)."""
+    S, M = len(stage_layers), len(xs)
     cur = [torch.tensor(p) for p in params]
     hist = [[c.clone()] for c in cur]
     mom = [torch.zeros_like(c) for c in cur]
-    acc = torch.zeros_like(cur[0])
+    acc = [torch.zeros_like(c) for c in cur]
     losses = []
-    M = len(xs)
     for i in range(M):
-        v0 = max(0, i // r0 - depths[0] + 1)
-        v1 = max(0, i - depths[1] + 1)
-        comp = [hist[0][v0].clone().requires_grad_(True), hist[1][v1].clone().requires_grad_(True)]
+        comp = [hist[s][max(0, i // reps[s] - depths[s] + 1)].clone().requires_grad_(True) for s in range(S)]
         l = _torch_model_loss(comp, stage_layers, torch.tensor(xs[i]), torch.tensor(ys[i], dtype=torch.long))
         l.backward()
         losses.append(l.item())
-        mom[1] = mu * mom[1] + comp[1].grad
-        cur[1] = cur[1] - lr * mom[1]
-        hist[1].append(cur[1].clone())
-        acc = acc + comp[0].grad
-        if i % r0 == r0 - 1 or i == M - 1:
-            mom[0] = mu * mom[0] + acc
-            cur[0] = cur[0] - lr * mom[0]
-            hist[0].append(cur[0].clone())
-            acc = torch.zeros_like(cur[0])
+        for s in range(S):
+            acc[s] = acc[s] + comp[s].grad
+            if i % reps[s] == reps[s] - 1 or i == M - 1:
+                mom[s] = mu * mom[s] + acc[s]
+                cur[s] = cur[s] - lr * mom[s]
+                hist[s].append(cur[s].clone())
+                acc[s] = torch.zeros_like(cur[s])
     return [c.numpy() for c in cur], losses
 
 
-@pytest.mark.parametrize("r0,W0,M", [(2, 2, 12), (2, 1, 7), (3, 2, 11)])
-def test_replicated_input_stage_pipeline_equals_its_staleness_rule(r0, W0, M):
-    sl = [[("linear", 12, 12, True), ("linear", 12, 12, True)], [("linear", 12, 5, False), ("softmax_xent", 5)]]
+@pytest.mark.parametrize("reps,depths,M", [([2, 1], [2, 1], 12), ([2, 1], [1, 1], 7), ([3, 1], [2, 1], 11),
+                                           ([1, 2], [2, 1], 9), ([2, 2, 1], [2, 2, 1], 13), ([2, 3], [2, 1], 10)])
+def test_replicated_pipeline_equals_its_staleness_rule(reps, depths, M):
+    S = len(reps)
+    sl = [[("linear", 12, 12, True), ("linear", 12, 12, True)]] + [[("linear", 12, 12, True)] for _ in range(S - 2)] + \
+         [[("linear", 12, 5, False), ("softmax_xent", 5)]]
     params = _params(sl, SEED)
     xs, ys = _data(M, 4, 12, 5, SEED)
     order = []
-    stages, losses = run_replicated_pipeline(sl, params, [r0, 1], xs, ys, [W0, 1], lr=0.05, momentum=0.9, order=order)
-    ref_p, ref_l = _torch_replicated_flat_loop(sl, params, xs, ys, r0, [W0, 1], 0.05, 0.9)
+    stages, losses = run_replicated_pipeline(sl, params, reps, xs, ys, depths, lr=0.05, momentum=0.9, order=order)
+    ref_p, ref_l = _torch_replicated_flat_loop(sl, params, xs, ys, reps, depths, 0.05, 0.9)
     assert np.allclose(losses, ref_l, rtol=1e-11)
-    assert np.allclose(stages[0].rep[0].master, ref_p[0], rtol=1e-10, atol=1e-13)
-    assert np.allclose(stages[1].rep[0].master, ref_p[1], rtol=1e-10, atol=1e-13)
-    # every op ran exactly once; the input stage made one update per round
-    assert sum(1 for o in order if o[0] == 0 and o[2] == OP_U) == -(-M // r0)
-    assert sorted(o[3] for o in order if o[0] == 0 and o[2] == OP_F) == list(range(M))
+    for s in range(S):
+        assert np.allclose(stages[s].rep[0].master, ref_p[s], rtol=1e-10, atol=1e-13)
+        # every op ran exactly once; one update per round
+        assert sum(1 for o in order if o[0] == s and o[2] == OP_U) == -(-M // reps[s])
+        assert sorted(o[3] for o in order if o[0] == s and o[2] == OP_F) == list(range(M))
 
 
 def test_without_replication_it_is_the_plain_pipeline():
