@@ -222,6 +222,82 @@ def bench_replicated(args, pd, gen, torch, np, dev):
     print(json.dumps(out))
 
 
+def bench_vgg16_pipeline(args, pd, gen, torch, np, dev):
+    """Secondary workload: ALL of VGG16 (13 convolutions, 5 poolings, 3 Linear layers, loss) as the paper's kind of
+    configuration for it, a replicated convolutional stage feeding one classifier stage (its Table 1 lists 15-1 on 16
+    machines; here r-1 on one GPU, every replica and the classifier on a stream of its own), run by
+    pd_pipeline_run_replicated.  NOAM = ceil((r + 1) / r) = 2 for r >= 1: depth 2 on the input stage, 1 on the output stage.
+    The unreplicated 1-1 pipeline is timed beside it."""
+    B, K, W, r = args.minibatch, args.steps, args.warmup, args.replicas
+    hw = (64, 64) if args.small else (224, 224)
+    full = gen.vgg16_full()
+    n_conv = len(gen.config3_vgg_conv()) + 8          # the conv/pool part (18 layers)
+    conv, fc = full[:n_conv], full[n_conv:]
+    if args.small:
+        fc = gen.config2_vgg_fc((hw[0] // 32) * (hw[1] // 32) * 512)
+    seed = gen.BASE_SEED + 6
+    LR = 1e-4   # (N(0,1) pixels through 16 unnormalised layers: the paper's 0.01 diverges on such inputs)
+    p_conv, p_fc = gen.init_params(seed, "conv", conv), gen.init_params(seed, "fc", fc)
+    M = max(K, 2)
+    x = torch.from_numpy(gen.normal_bulk(seed, "x", (M, B, hw[0], hw[1], 3))).to(dev).to(torch.bfloat16)
+    lab = torch.from_numpy(gen.labels(seed, "y", (M, B), 1000)).to(dev)
+    losses = torch.zeros(M, dtype=torch.float32, device=dev)
+
+    def build(reps):
+        keep, handles = [], []
+        def arena(n):
+            t = torch.empty(n + 256, dtype=torch.uint8, device=dev); keep.append(t)
+            return (t.data_ptr() + 255) // 256 * 256
+        streams = [torch.cuda.Stream(device=dev) for _ in range(reps + 1)]; keep.append(streams)
+        c0 = pd.make_config(conv, stage_index=0, num_stages=2, noam=2, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=LR,
+                            momentum=0.9, stream=streams[0].cuda_stream, in_hw=hw, replicas=reps if reps > 1 else 0)
+        n = pd.pd_stage_query_bytes(c0)
+        h0 = pd.pd_stage_create(c0, arena(n), n)
+        hs0 = [h0]
+        for q in range(1, reps):
+            n = pd.pd_stage_replica_query_bytes(c0)
+            a = arena(n)
+            torch.cuda.synchronize()
+            hs0.append(pd.pd_stage_create_replica(h0, streams[q].cuda_stream, a, n))
+        c1 = pd.make_config(fc, stage_index=1, num_stages=2, noam=2, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=LR,
+                            momentum=0.9, stream=streams[reps].cuda_stream)
+        n = pd.pd_stage_query_bytes(c1)
+        h1 = pd.pd_stage_create(c1, arena(n), n)
+        return [hs0, [h1]], keep
+
+    def run(handles, m):
+        pd.pd_stage_set_params(handles[0][0], p_conv)     # (also resets every replica: the driver wants fresh stages)
+        pd.pd_stage_set_params(handles[1][0], p_fc)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pd.pd_pipeline_run_replicated(handles, m, x.data_ptr(), lab.data_ptr(), losses.data_ptr())
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3
+
+    res = {}
+    for reps in (1, r):
+        handles, keep = build(reps)
+        run(handles, max(2, min(W, M)))
+        res[reps] = run(handles, M)
+        for hs in reversed(handles):
+            for h in reversed(hs):
+                pd.pd_stage_destroy(h)
+        del keep
+    ms = res[r] / M
+    P = int(p_conv.size + p_fc.size)
+    out = {"metric": METRIC, "value": B / (ms * 1e-3), "unit": "samples/s", "n_gpus": 1, "steps": M, "warmup": W,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": ("REDUCED " if args.small else "") + f"VGG16 (all 16 weight layers) on 3x{hw[0]}x{hw[1]} images as a "
+                      f"{r}-1 pipeline: convolutional stage replicated x{r} + classifier stage, {r + 1} streams, "
+                      f"bf16 w/ fp32 accum, minibatch {B}, NOAM 2; step = one minibatch through the whole pipeline "
+                      f"(wall time of {M} minibatches incl. start-up and drain)",
+                      "minibatch": B, "replicas": r, "params": P},
+           "ms_per_minibatch_1_1_pipeline": res[1] / M, "first_loss": float(losses[0].item()),
+           "final_loss": float(losses[-1].item())}
+    print(json.dumps(out))
+
+
 def bench_s2vt(args, pd, gen, torch, np, dev):
     """Secondary workload: the S2VT-shaped model (LSTM 4096->1000 | LSTM 1000->1000 + vocab 30000 + loss), seq 80,
     minibatch 64, as a 2-stage pipeline on two streams (pd_pipeline_run, NOAM 2).  A step = one minibatch through
@@ -509,12 +585,13 @@ def main():
     ap.add_argument("--depth", type=int, default=4)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
-    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition", "mlp4", "replicated"],
+    ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition", "mlp4", "replicated", "vgg16_pipeline"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
                          "s2vt (the two LSTM stages as a 2-stream pipeline), inception (four stages of branched "
                          "convolution blocks as a 4-stream pipeline), gemm_sweep (the Linear kernels over row counts), "
                          "partition (layer profile of all of VGG16 on the device, then the partitioner), mlp4 (the 4-stage fp32 MLP, "
-                         "a launch-latency case), replicated (the VGG16 conv stage as --replicas replicas on as many streams)")
+                         "a launch-latency case), replicated (the VGG16 conv stage as --replicas replicas on as many streams), vgg16_pipeline (all of VGG16 as "
+                         "an r-1 pipeline: replicated conv stage + classifier stage)")
     ap.add_argument("--replicas", type=int, default=2, help="workload replicated: replicas of the stage (2..8)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -546,6 +623,8 @@ def main():
         return bench_mlp4(args, pd, gen, torch, np, dev)
     if args.workload == "replicated":
         return bench_replicated(args, pd, gen, torch, np, dev)
+    if args.workload == "vgg16_pipeline":
+        return bench_vgg16_pipeline(args, pd, gen, torch, np, dev)
     layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
     n_in, classes = layers[0][1], layers[-1][1]
     seed = gen.BASE_SEED + 1
