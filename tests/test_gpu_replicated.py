@@ -318,3 +318,53 @@ def test_replicated_protocol_errors():
     finally:
         g.close()
         plain.close()
+
+
+def test_checkpoint_of_a_replicated_stage(tmp_path):
+    # the parameter state of a replicated stage is one copy: saved from the primary after a joint update, loaded
+    # into the primary of another replicated stage, which restarts every replica at the saved version
+    import torch
+    p, xs, labs = _mlp_data(4, 8, SEED + 9)
+    path = str(tmp_path / "replicated.ckpt")
+    a = GpuReplicatedStage(MLP, p, 2, minibatch=8, precision=pd.PD_BF16_F32ACC, in_flight_override=1, optimizer=1, eps=1.0,
+                           lr=0.045)
+    b = GpuReplicatedStage(MLP, None, 2, minibatch=8, precision=pd.PD_BF16_F32ACC, in_flight_override=1, optimizer=1,
+                           eps=1.0, lr=0.045)
+    try:
+        x_t = [to_dev(x, True) for x in xs]
+        l_t = [labels_dev(l) for l in labs]
+        loss = torch.zeros(4, dtype=torch.float32, device=dev())
+        torch.cuda.synchronize()
+
+        def round_(g, k):
+            for q in range(2):
+                i = 2 * k + q
+                pd.pd_forward(g.rep[q].h, k, x_t[i].data_ptr(), l_t[i].data_ptr(), 0, loss[i:].data_ptr())
+            for q in range(2):
+                pd.pd_backward(g.rep[q].h, k, 0, 0)
+            g.update()
+
+        round_(a, 0)
+        with pytest.raises(pd.PdError) as e:
+            pd.pd_stage_checkpoint_load(a.rep[1].h, path)          # the state belongs to the primary
+        assert e.value.status in (pd.PD_ESTATE, pd.PD_EINVAL)
+        pd.pd_stage_checkpoint_save(a.h, path)
+        assert pd.pd_checkpoint_info(path)[1] == 1
+        pd.pd_stage_checkpoint_load(b.h, path)
+        assert [pd.pd_stage_version(h) for h in b.handles()] == [1, 1]
+        assert np.array_equal(pd.pd_stage_get_params(b.rep[1].h), pd.pd_stage_get_params(a.h))
+        assert np.array_equal(pd.pd_stage_get_momentum(b.h), pd.pd_stage_get_momentum(a.h))
+        # both continue identically: a with round 1, b (fresh replicas at version 1) with its own round 0 of the same data
+        round_(a, 1)
+        for q in range(2):
+            i = 2 + q
+            pd.pd_forward(b.rep[q].h, 0, x_t[i].data_ptr(), l_t[i].data_ptr(), 0, loss[i:].data_ptr())
+        for q in range(2):
+            pd.pd_backward(b.rep[q].h, 0, 0, 0)
+        b.update()
+        assert np.array_equal(pd.pd_stage_get_params(b.h), pd.pd_stage_get_params(a.h))
+        assert np.array_equal(pd.pd_stage_get_momentum(b.h), pd.pd_stage_get_momentum(a.h))
+        assert pd.pd_stage_version(b.h) == 2 == pd.pd_stage_version(a.h)
+    finally:
+        a.close()
+        b.close()
