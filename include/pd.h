@@ -224,6 +224,10 @@ int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n);
 int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float* host_out, size_t n);
 /* Momentum buffer (fp32, flat layout).  set requires nothing in flight. */
 int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n);
+/* Learning rate of the following updates (Section 5.1: Inception-v3's rate is decayed per epoch; the schedule itself is
+ * the caller's).  Host-side only: updates already enqueued keep the rate they were launched with.  On the primary of a
+ * replicated stage (PD_ESTATE on a further replica).  PD_EINVAL unless finite and >= 0. */
+int pd_stage_set_lr(pd_stage* st, float lr);
 int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n);
 
 /* Overwrites the LATEST version in place: fp32 master <- host_params, its ring slot <- their bf16

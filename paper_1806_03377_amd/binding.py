@@ -80,6 +80,7 @@ _SIGS = {
     "pd_stage_set_params": [_vp, _vp, _sz],
     "pd_stage_get_params": [_vp, _i32, _i32, _vp, _sz],
     "pd_stage_set_momentum": [_vp, _vp, _sz],
+    "pd_stage_set_lr": [_vp, _f32],
     "pd_stage_get_momentum": [_vp, _vp, _sz],
     "pd_stage_overwrite_latest": [_vp, _vp, _vp, _sz],
     "pd_stage_version": [_vp, _i32, C.POINTER(_i32)],
@@ -307,6 +308,10 @@ def pd_stage_get_params(stage: int, version: int = -1, ring_copy: bool = False) 
 def pd_stage_set_momentum(stage: int, mom: np.ndarray):
     a = _host_f32(mom)
     _check(_lib.pd_stage_set_momentum(stage, a.ctypes.data, a.size))
+
+
+def pd_stage_set_lr(stage: int, lr: float):
+    _check(_lib.pd_stage_set_lr(stage, lr))
 
 
 def pd_stage_get_momentum(stage: int) -> np.ndarray:

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 
 #include <cstdarg>
 #include <cstdio>
@@ -781,6 +782,16 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
     PD_HIP(widen(L.w_off, L.flat_w, L.n_w));
     PD_HIP(widen(L.b_off, L.flat_b, L.n_b));
   }
+  return PD_OK;
+}
+
+int pd_stage_set_lr(pd_stage* st, float lr) {
+  if (check_stage(st)) return PD_EINVAL;
+  if (check_owner(st)) return PD_ESTATE;
+  if (!(lr >= 0.f) || !std::isfinite(lr)) return fail(PD_EINVAL, "learning rate must be finite and >= 0");
+  st->rule.lr = lr;  // read by the next update's launch; updates already enqueued keep the value they were launched with
+  st->cfg.lr = lr;
+  for (pd_stage* r : st->secondaries) { r->rule.lr = lr; r->cfg.lr = lr; }
   return PD_OK;
 }
 

@@ -232,6 +232,41 @@ def test_rmsprop_stages(precision):
     run_case([many], params, xs, labs, noam=1, precision=precision, depth_override=2, mode="forced", minibatch=24, **kw)
 
 
+def test_learning_rate_schedule_f32():
+    # the rate of a stage is changed between updates (Section 5.1: Inception-v3's rate decays per epoch); the oracle
+    # stage gets the same schedule by assignment
+    from gpu_util import GpuStage
+    from oracle.pipeline import Stage
+    layers = [("linear", 24, 32, True), ("linear", 32, 10, False), ("softmax_xent", 10)]
+    p = gen.init_params(SEED + 31, "lr", layers)
+    M, B = 9, 6
+    xs = gen.normal(SEED + 31, "X", (M, B, 24)); labs = gen.labels(SEED + 31, "Y", (M, B), 10)
+    o = Stage(layers, p, 1, "f32", 0.045, 0.9, optimizer="rmsprop", eps=1.0)
+    g = GpuStage(layers, p, minibatch=B, precision=pd.PD_F32, in_flight_override=1, lr=0.045, momentum=0.9, optimizer=1, eps=1.0)
+    try:
+        xd, ld = to_dev(xs, False), labels_dev(labs)
+        loss = torch.zeros(M, dtype=torch.float32, device=dev())
+        lr = 0.045
+        for i in range(M):
+            if i and i % 3 == 0:                      # an "epoch" of three minibatches: decay by 0.94
+                lr *= 0.94
+                o.lr = lr
+                pd.pd_stage_set_lr(g.h, lr)
+            _, l_o = o.forward(i, xs[i].astype(np.float64), labs[i]); o.backward(i, None, need_dx=False); o.update(i)
+            pd.pd_forward(g.h, i, xd[i].data_ptr(), ld[i].data_ptr(), 0, loss[i:].data_ptr())
+            pd.pd_backward(g.h, i, 0, 0); pd.pd_update(g.h)
+            torch.cuda.synchronize()
+            assert abs(loss[i].item() - l_o) <= TOL_F32 * abs(l_o)
+        assert rel_err(pd.pd_stage_get_params(g.h), o.master) <= TOL_F32
+        assert rel_err(pd.pd_stage_get_momentum(g.h), o.mom) <= TOL_F32
+        with pytest.raises(pd.PdError):
+            pd.pd_stage_set_lr(g.h, float("nan"))
+        with pytest.raises(pd.PdError):
+            pd.pd_stage_set_lr(g.h, -1.0)
+    finally:
+        g.close()
+
+
 def test_one_row_minibatch_and_depth_one():
     layers = [("linear", 24, 16, True), ("linear", 16, 8, False), ("softmax_xent", 8)]
     _single_stage_case(layers, B=1, depth=1, M=4, precision=pd.PD_BF16_F32ACC)
