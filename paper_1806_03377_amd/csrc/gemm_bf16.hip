@@ -217,6 +217,139 @@ __global__ __launch_bounds__(256) void splitk_epilogue_kernel(const float* __res
 }
 
 // ------------------------------------------------------------------------------------------------
+// Forward product of a minibatch-sized layer with both tiles going straight from global memory into LDS.
+//   ws[z][m][c] = sum over the z-th slice of the reduction of A[m][r] * W[c][r]       (fp32 partial sums)
+// 64 x BN output tile, 128 reduction elements per stage, NS stages in LDS with the loads NS - 1 stages ahead of the
+// MFMAs.  A tile row is 256 bytes = 16 slots of 16 bytes; a wave-wide load fills 4 consecutive rows (lane L lands
+// at 16 L) and slot s of row r holds reduction group s ^ (r & 15), applied on the global side, so that the 16-byte
+// fragment reads of 16 consecutive rows cover all banks.  The four waves split the eight 16-wide reduction steps
+// of a stage between them (each fragment is read from LDS once, not once per wave sharing a row or column block)
+// and every wave accumulates the whole 64 x BN tile; the four partial tiles are added through LDS at the end, in
+// wave order.  The loads are unconditional (rows past the matrix are clamped to its last row and feed outputs that
+// are never stored; stages past the slice re-read its last stage into a buffer that is never read), so the number
+// of loads in flight is fixed and the waits are explicit counts.
+// Requires R % 128 == 0, 16-byte aligned rows, operands below 4 GiB (32-bit byte offsets).
+// ------------------------------------------------------------------------------------------------
+template <int BN, int NS>
+__global__ __launch_bounds__(kThreads) void skinny_dma_kernel(const bf16_t* __restrict__ A, int lda,
+                                                              const bf16_t* __restrict__ W, float* __restrict__ ws,
+                                                              int M, int C, int R, int splits) {
+  constexpr int SK = 128, ROWB = SK * 2, ATILE = BM * ROWB, STAGE = (BM + BN) * ROWB;
+  constexpr int QA = BM / 16, QB = BN / 16, LPS = QA + QB;  // wave-wide loads per wave and stage (4 rows each)
+  constexpr int NI = BM / 32, NJ = BN / 32;
+  constexpr int RED = 4 * BM * BN * 4, SMEM = NS * STAGE > RED ? NS * STAGE : RED;  // stages, then the four partial tiles
+  static_assert(NS >= 2 && SMEM <= 160 * 1024, "LDS budget");
+  __shared__ __attribute__((aligned(1024))) char smem[SMEM];
+  const int t = threadIdx.x, l = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int c0 = blockIdx.x * BN, m0 = blockIdx.y * BM, z = blockIdx.z;
+  const int T = R / SK;
+  const int rt0 = (int)((long long)z * T / splits), rt1 = (int)((long long)(z + 1) * T / splits), n = rt1 - rt0;
+
+  uint32_t off[LPS];
+#pragma unroll
+  for (int q = 0; q < LPS; ++q) {
+    const int row = ((q < QA ? q : q - QA) * 4 + w) * 4 + (l >> 4), g = (l & 15) ^ (row & 15);
+    if (q < QA) {
+      const int ra = m0 + row < M ? m0 + row : M - 1;
+      off[q] = ((uint32_t)ra * (uint32_t)lda + g * 8) * 2u;
+    } else {
+      const int rb = c0 + row < C ? c0 + row : C - 1;
+      off[q] = ((uint32_t)rb * (uint32_t)R + g * 8) * 2u;
+    }
+  }
+  auto load_stage = [&](int buf, int sc) {  // sc: stage of this slice, clamped by the caller
+    const size_t k0 = (size_t)(rt0 + sc) * SK;
+    char* st = smem + buf * STAGE;
+#pragma unroll
+    for (int q = 0; q < LPS; ++q) {
+      char* dst = st + (q < QA ? 0 : ATILE) + ((q < QA ? q : q - QA) * 4 + w) * 1024;
+      if (q < QA) dma_load16(A + k0, off[q], dst);
+      else if (gridDim.y == 1) dma_load16_stream(W + k0, off[q], dst);  // every weight is read once by the whole grid
+      else dma_load16(W + k0, off[q], dst);
+    }
+  };
+  // this wave's reduction steps are 2w and 2w + 1: groups 4w + (l >> 5) and, two slots on, the same with bit 1 set
+  int fa[NI], fb[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int row = 32 * i + (l & 31);
+    fa[i] = row * ROWB + (((4 * w + (l >> 5)) ^ (row & 15)) << 4);
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = 32 * j + (l & 31);
+    fb[j] = ATILE + row * ROWB + (((4 * w + (l >> 5)) ^ (row & 15)) << 4);
+  }
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x16{0};
+
+  if (n > 0) {
+#pragma unroll
+    for (int d = 0; d < NS - 1; ++d) load_stage(d, d < n ? d : n - 1);
+    int cur = 0, fill = NS - 1;
+    for (int st = 0; st < n; ++st) {
+      // this wave's loads of stage st have landed (NS - 2 later stages may be in flight); after the barrier every
+      // wave's have, and every wave is done reading the buffer that is filled next
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * LPS) : "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      load_stage(fill, st + NS - 1 < n ? st + NS - 1 : n - 1);
+      const char* sc = smem + cur * STAGE;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        uint4 a[NI], b[NJ];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) a[i] = *reinterpret_cast<const uint4*>(sc + (fa[i] ^ (h << 5)));
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[j] = *reinterpret_cast<const uint4*>(sc + (fb[j] ^ (h << 5)));
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+          for (int j = 0; j < NJ; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[j]), acc[i][j], 0, 0, 0);
+      }
+      cur = cur + 1 == NS ? 0 : cur + 1;
+      fill = fill + 1 == NS ? 0 : fill + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the trailing re-reads still write LDS
+  }
+  __syncthreads();
+  float* red = reinterpret_cast<float*>(smem);  // [wave][row][column]
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+        red[((size_t)w * BM + row) * BN + 32 * j + (l & 31)] = acc[i][j][r];
+      }
+  __syncthreads();
+  for (int idx = t; idx < BM * BN / 4; idx += kThreads) {
+    const int row = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+    float4 s = *reinterpret_cast<const float4*>(&red[(size_t)row * BN + c4]);
+#pragma unroll
+    for (int k = 1; k < 4; ++k) {
+      const float4 p = *reinterpret_cast<const float4*>(&red[((size_t)k * BM + row) * BN + c4]);
+      s.x += p.x; s.y += p.y; s.z += p.z; s.w += p.w;
+    }
+    const int m = m0 + row, c = c0 + c4;
+    if (m >= M || c >= C) continue;
+    float* o = ws + ((size_t)z * M + m) * C + c;
+    if (c + 3 < C && (C & 3) == 0) {
+      *reinterpret_cast<float4*>(o) = s;
+    } else {
+      const float v[4] = {s.x, s.y, s.z, s.w};
+      for (int k = 0; k < 4 && c + k < C; ++k) o[k] = v[k];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // wgrad + momentum-SGD update.  One workgroup owns a TN x TK tile of w[N][K]:
 //   phase 0  start the loads of the tile's fp32 master weights and momentum (they stay in registers
 //            while the gradient tile is formed, which hides most of the HBM latency)
@@ -428,9 +561,10 @@ hipError_t launch_wgrad_update(hipStream_t s, WgradBatch batch) {
   return hipGetLastError();
 }
 
-// Launch shapes, picked from sweeps at the VGG16 classifier's sizes on MI355X (minibatch 64).  Forward:
-// 64-column tiles, 128 reduction elements per stage, two stages of loads in flight, two LDS buffers.  Dgrad
-// of a large matrix: 128 x 128 tiles (fewer, longer transposing stages); of a small one: 64 x 256.
+// Launch shapes of the register-staged kernel, picked from sweeps at the VGG16 classifier's sizes on MI355X
+// (minibatch 64).  Forward (shapes the direct-to-LDS kernel does not take): 64-column tiles, 128 reduction
+// elements per stage, two stages of loads in flight, two LDS buffers.  Dgrad of a large matrix: 128 x 128 tiles
+// (fewer, longer transposing stages); of a small one: 64 x 256.
 constexpr int kFwdBN = 64, kFwdBK = 128, kFwdPD = 2, kFwdNBUF = 2;
 constexpr int kBigBN = 128, kBigBK = 128, kBigPD = 2, kBigNBUF = 1;
 constexpr int kSmallBN = 64, kSmallBK = 256, kSmallPD = 1, kSmallNBUF = 1;
@@ -457,9 +591,43 @@ size_t splitk_bytes_t(int rows, int cols, int red) {
 
 // lda = row stride of A (0: dense, = R).  splits_out != null: leave the fp32 partial sums ws[split][M][C]
 // (at least one) for the caller's own epilogue and report how many there are.
+// The direct-to-LDS forward kernel, when the shape allows it (see the kernel) and the workspace holds its partial
+// sums.  Returns false if the register-staged kernel has to do the job.  Measured at 64 x 4096 x 25088 on MI355X,
+// epilogue launch (4.7 us) included, with cached weight loads, which repeated calls partly serve from the 256 MB
+// memory-side cache: 64 columns and 3 stages on 256 workgroups 39.6 us, 4 stages 40.1, 2 stages on 512 workgroups
+// 41.9, 128 columns and 3 stages 42.9.  With the non-temporal weight loads the kernel uses (cached ones made the
+// update kernel later in the step 6 % slower) the chosen shape takes 46.0 us against 49.1 for the register-staged
+// kernel; a kernel that only streams the weights takes 32.6, one that also fetches the activation tiles 41.2.
+constexpr int kDmaBN = 64, kDmaNS = 3, kDmaWgs = 256;
+template <int BN, int NS>
+bool launch_skinny_dma(hipStream_t s, const bf16_t* a, const bf16_t* w, const GemmEpilogue& ep, int M, int C, int R,
+                       float* ws, size_t ws_bytes, int lda, int* splits_out, int target_wgs) {
+  constexpr int SK = 128;
+  if (R % SK != 0 || lda % 8 != 0 || !ws) return false;
+  if ((size_t)M * lda * 2 >= ((size_t)1 << 32) || (size_t)C * R * 2 >= ((size_t)1 << 32)) return false;
+  if ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(w)) & 15) return false;
+  const int tc = (C + BN - 1) / BN, tm = (M + BM - 1) / BM, T = R / SK;
+  int splits = target_wgs / (tc * tm);
+  if (splits > T / 2) splits = T / 2;
+  if (splits > 32) splits = 32;
+  const size_t fit = ws_bytes / ((size_t)M * C * sizeof(float));
+  if ((size_t)splits > fit) splits = (int)fit;
+  if (splits < 2) return false;
+  skinny_dma_kernel<BN, NS><<<dim3(tc, tm, splits), kThreads, 0, s>>>(a, lda, w, ws, M, C, R, splits);
+  if (splits_out) {
+    *splits_out = splits;
+    return true;
+  }
+  const size_t total4 = (size_t)M * C / 4;
+  splitk_epilogue_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(ws, splits, M, C, ep);
+  return true;
+}
+
 template <bool BT, int BN_, int BK_, int PD, int NBUF>
 hipError_t launch_gemm(hipStream_t s, const bf16_t* a, const bf16_t* b, const GemmEpilogue& ep, int M, int C, int R,
                        float* ws, size_t ws_bytes, int lda = 0, int* splits_out = nullptr) {
+  if (!BT && launch_skinny_dma<kDmaBN, kDmaNS>(s, a, b, ep, M, C, R, ws, ws_bytes, lda ? lda : R, splits_out, kDmaWgs))
+    return hipGetLastError();
   const int tc = (C + BN_ - 1) / BN_, tm = (M + BM - 1) / BM;
   int splits = pick_splits(tc * tm, (R + BK_ - 1) / BK_);
   if (splits > 1 && (!ws || (size_t)splits * M * C * sizeof(float) > ws_bytes)) splits = 1;

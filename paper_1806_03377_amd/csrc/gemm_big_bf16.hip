@@ -279,21 +279,7 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_big_kernel(const bf16_t* __re
 // before every LDS read, which serialises the pipeline.  A reduction length that is not a multiple of 32 is
 // handled by one zero-padded stage that goes through registers before the pipeline starts.
 constexpr int DK = 32, DNS = 4, DROWB = DK * 2, DTILE = 256 * DROWB, DSTAGE = 2 * DTILE;
-typedef __attribute__((address_space(3))) void lds_void_t;
-
 __device__ __forceinline__ int dma_swz(int row) { return (row >> 2) & 3; }
-
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void dma_load16(const bf16_t* uniform_base, uint32_t lane_byte_offset, char* uniform_lds_dst) {
-  const uint32_t lds_addr =
-      __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(uniform_lds_dst));
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(lane_byte_offset), "s"(uniform_base), "s"(lds_addr)
-               : "memory", "m0");
-}
-#pragma clang diagnostic pop
 
 __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restrict__ A, int lda,
                                                           const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep,

@@ -31,6 +31,34 @@ __device__ __forceinline__ uint4 ldg16_stream(const bf16_t* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// One wave-wide 16-byte-per-lane load straight from global memory into LDS (global_load_lds_dwordx4): lane L's
+// chunk, read from `uniform_base` + `lane_byte_offset`, lands at `uniform_lds_dst` + 16 L.  Written as inline
+// assembly: for the builtin the compiler inserts a wait for ALL outstanding loads before every LDS read, which
+// serialises a pipeline; the caller waits with an explicit s_waitcnt vmcnt(n) instead.
+typedef __attribute__((address_space(3))) void lds_void_t;
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma_load16(const bf16_t* uniform_base, uint32_t lane_byte_offset, char* uniform_lds_dst) {
+  const uint32_t lds_addr =
+      __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(uniform_lds_dst));
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_byte_offset), "s"(uniform_base), "s"(lds_addr)
+               : "memory", "m0");
+}
+// the same for data that is read once per kernel (a weight stream): non-temporal, so that it is not kept in the
+// caches at the expense of reusable lines
+__device__ __forceinline__ void dma_load16_stream(const bf16_t* uniform_base, uint32_t lane_byte_offset,
+                                                  char* uniform_lds_dst) {
+  const uint32_t lds_addr =
+      __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(uniform_lds_dst));
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+               :
+               : "v"(lane_byte_offset), "s"(uniform_base), "s"(lds_addr)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
 // XOR swizzle of the 16-byte groups of an LDS row that holds 8*G reduction elements of one output row/column
 // (G groups).  Spreads both the transposing 4-byte writes (lanes differ in their column chunk and reduction
 // pair) and the 16-byte fragment reads (lanes differ in their row) over all banks.

@@ -32,6 +32,7 @@ def _bf(a):
 # ---------------------------------------------------------------------------------------------
 SHAPES = [(64, 128, 64), (64, 256, 4096), (64, 200, 264), (40, 136, 72), (1, 8, 8), (130, 1000, 520),
           (64, 4096, 1024), (96, 24, 2048), (256, 512, 768),
+          (50, 1000, 1536), (64, 72, 512), (1, 8, 1024),   # reduction a multiple of 128: the direct-to-LDS forward
           (512, 256, 256), (600, 1000, 520), (1030, 264, 136)]     # >= 512 rows: the 256 x 256-tile weight gradient
 # the same products forced onto the large-tile kernels (threshold 1 tile): several tiles, ragged rows/columns, a
 # reduction length that is a multiple of 32, one that is not, one shorter than a stage
