@@ -570,6 +570,10 @@ constexpr int kBigBN = 128, kBigBK = 128, kBigPD = 2, kBigNBUF = 1;
 constexpr int kSmallBN = 64, kSmallBK = 256, kSmallPD = 1, kSmallNBUF = 1;
 constexpr size_t kBigDgradElems = (size_t)32 << 20;  // weight elements from which the big dgrad shape is used
 // The 256 x 256-tile kernel (gemm_big_bf16.hip) takes over once its grid fills at least half the chip's 256 CUs.
+// Timed alone the large tiles already win from 48-64 tiles on (at 80 tiles, 5120 x 4000 x 1000: forward 90 vs
+// 109 us, input gradient 106 vs 129 us), but with that threshold the two-stream LSTM pipeline, where such products
+// run next to the other stage's kernels, got slower (5.26 vs 5.02 ms per minibatch): a workgroup that holds 128 KB
+// of LDS leaves no room on its compute unit for the other stream.
 int g_big_min_tiles = 128;
 bool use_big_tiles(int rows, int cols) { return ((rows + 255) / 256) * ((cols + 255) / 256) >= g_big_min_tiles; }
 
