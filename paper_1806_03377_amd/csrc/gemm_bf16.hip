@@ -2,6 +2,8 @@
 //
 // Three contractions of a Linear layer inside a pipeline stage:
 //   forward   y  = act(x w^T + b)          reduction over in-features, both operands reduction-contiguous
+//             (skinny_dma_kernel: tiles straight from global memory into LDS; gemm_kernel<false>: through
+//             registers, for reductions that are not a multiple of 128)
 //   dgrad     dx = (dz w) .* relu'         reduction over out-features, w is read "sideways"
 //   wgrad+U   g  = dz^T x, then the momentum-SGD update of the fp32 master and the bf16 ring copy,
 //             fused in one kernel so that the weight gradient never goes to HBM
