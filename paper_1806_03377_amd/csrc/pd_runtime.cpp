@@ -1382,7 +1382,11 @@ int run_update_kernels(pd_stage* st, int nv, bool grad_only) {
   pd::WgradBatch batch;
   batch.count = 0; batch.M = st->B; batch.rule = rule;
   PD_HIP(st->mark(-1, 0));
-  for (int l = 0; l < nl; ++l) {
+  // Last layer first: the forward pass that follows the update in the 1F1B order reads the first layer's new ring
+  // copy first, and finds part of it still cached if that layer was written last.  VGG16 classifier stage on
+  // MI355X: forward product of the 25088 x 4096 layer 57.7 -> 36.5 us, update kernel 372 -> 378 us, step 0.555 ->
+  // 0.546 ms; convolution, LSTM and branched-block stages unchanged.
+  for (int l = nl - 1; l >= 0; --l) {
     const Layer& L = st->lin[l];
     if (!L.n_w) continue;  // pooling, concatenation
     if (L.kind == K_CONV) {  // partial sums left by pd_backward -> step into the next ring slot
