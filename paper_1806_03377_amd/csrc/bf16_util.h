@@ -14,6 +14,24 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
 __device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 __device__ __forceinline__ bool bf_positive(uint16_t h) { return (h & 0x8000u) == 0 && (h & 0x7fffu) != 0; }
 
+// An fp32 master weight kept as its bf16 rounding (which a weight-version ring holds anyway) plus the low 16 bits of
+// its fp32 pattern.  Rounding to nearest even is an integer add on the pattern, so upper half = bf16 - carry, and
+// the carry is 1 exactly when the low half is >= 0x8000 -- except for a tie that rounds down (low half 0x8000,
+// upper half even), which would read back as a carry.  That one case is stored with low half 0x7fff: the master
+// loses one fp32 unit in the last place there (a 2^-17 fraction of random values), and split/merge are exact inverses
+// on everything they store.  NaNs are not preserved.
+__device__ __forceinline__ void master_split1(float w, uint16_t& ring, uint16_t& rem) {
+  const uint32_t u = __float_as_uint(w);
+  ring = f2bf(w);
+  uint16_t lo = (uint16_t)(u & 0xffffu);
+  if (lo == 0x8000u && ring == (uint16_t)(u >> 16)) lo = 0x7fffu;  // tie rounded down
+  rem = lo;
+}
+__device__ __forceinline__ float master_merge1(uint16_t ring, uint16_t rem) {
+  const uint32_t up = (uint32_t)(uint16_t)(ring - (rem >= 0x8000u ? 1u : 0u));
+  return __uint_as_float((up << 16) | rem);
+}
+
 // eight bf16 values <-> one 16-byte register quad
 __device__ __forceinline__ void unpack8(uint4 v, uint16_t* o) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};

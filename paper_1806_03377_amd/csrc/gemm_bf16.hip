@@ -426,7 +426,19 @@ __device__ __forceinline__ void nt_store4(float* p, float4 v) {
 }
 
 // KIND: the update rule (UpdateRule::kind) as a compile-time constant.
-template <int TN, int TK, bool NFAST, bool PREFETCH, int KIND>
+// SPLIT: the fp32 master weights are the previous ring copy plus 16-bit remainders (WgradLayer::ring_in, rem_w)
+// instead of an fp32 array: 2 + 2 bytes read and 2 more written per parameter instead of 4 and 4.
+typedef unsigned int vu2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 nt_load_u2(const void* p) {
+  const vu2_t v = __builtin_nontemporal_load(reinterpret_cast<const vu2_t*>(p));
+  return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ void nt_store_u2(void* p, uint2 v) {
+  const vu2_t t = {v.x, v.y};
+  __builtin_nontemporal_store(t, reinterpret_cast<vu2_t*>(p));
+}
+
+template <int TN, int TK, bool NFAST, bool PREFETCH, int KIND, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch) {
   // which layer this workgroup belongs to (all layers of a stage are updated by one launch)
   int li = 0;
@@ -437,7 +449,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
   const bf16_t* __restrict__ X = L.x;
   float* __restrict__ master = L.master_w;
   float* __restrict__ mom = L.mom_w;
-  bf16_t* __restrict__ ring = L.ring_w;
+  bf16_t* ring = L.ring_w;           // (no __restrict__: with a ring of depth 1 ring_in is the same slot; every
+  const bf16_t* ring_in = L.ring_in;  // element is then read and later written by the same thread)
+  uint16_t* __restrict__ rem = L.rem_w;
   float* __restrict__ master_b = L.master_b;
   float* __restrict__ mom_b = L.mom_b;
   bf16_t* __restrict__ ring_b = L.ring_b;
@@ -461,18 +475,26 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
   const int n0 = nt * TN, k0 = kt * TK;
 
   // phase 0: prefetch master and momentum of this thread's phase-2 elements
+  static_assert(!SPLIT || PREFETCH, "the split master is only read ahead");
   float4 pw[kSlots], pm[kSlots];
+  uint2 ph[kSlots], pl[kSlots];  // SPLIT: four bf16 of the previous ring copy, four remainders
   if (PREFETCH) {
 #pragma unroll
     for (int q = 0; q < kSlots; ++q) {
       const int f = t + kThreads * q, row = f / (TK / 4), k = k0 + (f % (TK / 4)) * 4, n = n0 + row;
       if (n < N && k < K) {
         const size_t off = (size_t)n * K + k;
-        pw[q] = nt_load4(master + off);
+        if (SPLIT) {
+          ph[q] = nt_load_u2(ring_in + off);
+          pl[q] = nt_load_u2(rem + off);
+        } else {
+          pw[q] = nt_load4(master + off);
+        }
         pm[q] = nt_load4(mom + off);
       } else {
         pw[q] = make_float4(0.f, 0.f, 0.f, 0.f);
         pm[q] = pw[q];
+        ph[q] = pl[q] = make_uint2(0u, 0u);
       }
     }
   }
@@ -556,7 +578,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
       const size_t off = (size_t)n * K + k;
       const float4 g = *reinterpret_cast<const float4*>(&G[row * GLD + c4]);
       float4 m, wv;
-      if (PREFETCH) {
+      if (SPLIT) {
+        m = pm[q];
+        wv.x = master_merge1((uint16_t)(ph[q].x & 0xffffu), (uint16_t)(pl[q].x & 0xffffu));
+        wv.y = master_merge1((uint16_t)(ph[q].x >> 16), (uint16_t)(pl[q].x >> 16));
+        wv.z = master_merge1((uint16_t)(ph[q].y & 0xffffu), (uint16_t)(pl[q].y & 0xffffu));
+        wv.w = master_merge1((uint16_t)(ph[q].y >> 16), (uint16_t)(pl[q].y >> 16));
+      } else if (PREFETCH) {
         m = pm[q];
         wv = pw[q];
       } else {
@@ -570,10 +598,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
       apply_update_as<KIND>(rule, g.x, m.x, wv.x); apply_update_as<KIND>(rule, g.y, m.y, wv.y);
       apply_update_as<KIND>(rule, g.z, m.z, wv.z); apply_update_as<KIND>(rule, g.w, m.w, wv.w);
       nt_store4(mom + off, m);     // streamed once per step: keep these lines out of the caches
-      nt_store4(master + off, wv);
       uint2 pk;
-      pk.x = (uint32_t)f2bf(wv.x) | ((uint32_t)f2bf(wv.y) << 16);
-      pk.y = (uint32_t)f2bf(wv.z) | ((uint32_t)f2bf(wv.w) << 16);
+      if (SPLIT) {
+        uint16_t r[4], lo[4];
+        master_split1(wv.x, r[0], lo[0]); master_split1(wv.y, r[1], lo[1]);
+        master_split1(wv.z, r[2], lo[2]); master_split1(wv.w, r[3], lo[3]);
+        pk.x = (uint32_t)r[0] | ((uint32_t)r[1] << 16);
+        pk.y = (uint32_t)r[2] | ((uint32_t)r[3] << 16);
+        nt_store_u2(rem + off, make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16)));
+      } else {
+        nt_store4(master + off, wv);
+        pk.x = (uint32_t)f2bf(wv.x) | ((uint32_t)f2bf(wv.y) << 16);
+        pk.y = (uint32_t)f2bf(wv.z) | ((uint32_t)f2bf(wv.w) << 16);
+      }
       *reinterpret_cast<uint2*>(ring + off) = pk;  // read back by the next forward pass: ordinary store (measured:
                                                     // a non-temporal store here costs the update more than the forward gains)
     }
@@ -606,10 +643,24 @@ hipError_t launch_wgrad_update(hipStream_t s, WgradBatch batch) {
     batch.layer[i].tile_end = tiles;
   }
   if (tiles == 0) return hipSuccess;
+  int n_split = 0;
+  for (int i = 0; i < batch.count; ++i) {
+    if ((batch.layer[i].ring_in != nullptr) != (batch.layer[i].rem_w != nullptr)) return hipErrorInvalidValue;
+    n_split += batch.layer[i].rem_w != nullptr;
+  }
+  if (n_split != 0 && n_split != batch.count) return hipErrorInvalidValue;
+  if (n_split) {
+    switch (batch.rule.kind) {
+      case 0: wgrad_update_kernel<TN, TK, NFAST, true, 0, true><<<tiles, kThreads, 0, s>>>(batch); break;
+      case 1: wgrad_update_kernel<TN, TK, NFAST, true, 1, true><<<tiles, kThreads, 0, s>>>(batch); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (batch.rule.kind) {
-    case 0: wgrad_update_kernel<TN, TK, NFAST, PREFETCH, 0><<<tiles, kThreads, 0, s>>>(batch); break;
-    case 1: wgrad_update_kernel<TN, TK, NFAST, PREFETCH, 1><<<tiles, kThreads, 0, s>>>(batch); break;
-    case kRuleGradOnly: wgrad_update_kernel<TN, TK, NFAST, false, kRuleGradOnly><<<tiles, kThreads, 0, s>>>(batch); break;
+    case 0: wgrad_update_kernel<TN, TK, NFAST, PREFETCH, 0, false><<<tiles, kThreads, 0, s>>>(batch); break;
+    case 1: wgrad_update_kernel<TN, TK, NFAST, PREFETCH, 1, false><<<tiles, kThreads, 0, s>>>(batch); break;
+    case kRuleGradOnly: wgrad_update_kernel<TN, TK, NFAST, false, kRuleGradOnly, false><<<tiles, kThreads, 0, s>>>(batch); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();

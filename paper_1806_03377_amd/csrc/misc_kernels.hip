@@ -31,6 +31,23 @@ __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restric
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = f2bf(src[i]);
 }
+__global__ __launch_bounds__(256) void master_split_kernel(const float* __restrict__ master, bf16_t* __restrict__ ring,
+                                                           uint16_t* __restrict__ rem, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+    uint16_t r, lo;
+    master_split1(master[i], r, lo);
+    ring[i] = r;
+    rem[i] = lo;
+  }
+}
+__global__ __launch_bounds__(256) void master_merge_kernel(const bf16_t* __restrict__ ring,
+                                                           const uint16_t* __restrict__ rem, float* __restrict__ master,
+                                                           size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride)
+    master[i] = master_merge1(ring[i], rem[i]);
+}
 __global__ __launch_bounds__(256) void bf16_to_f32_kernel(const bf16_t* __restrict__ src, float* __restrict__ dst,
                                                           size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -274,6 +291,16 @@ hipError_t fill_zero(hipStream_t s, void* dst, size_t bytes) {
 hipError_t f32_to_bf16(hipStream_t s, const float* src, bf16_t* dst, size_t n) {
   if (n == 0) return hipSuccess;
   f32_to_bf16_kernel<<<grid_for(n), 256, 0, s>>>(src, dst, n);
+  return hipGetLastError();
+}
+hipError_t master_split(hipStream_t s, const float* master, bf16_t* ring, uint16_t* rem, size_t n) {
+  if (n == 0) return hipSuccess;
+  master_split_kernel<<<grid_for(n), 256, 0, s>>>(master, ring, rem, n);
+  return hipGetLastError();
+}
+hipError_t master_merge(hipStream_t s, const bf16_t* ring, const uint16_t* rem, float* master, size_t n) {
+  if (n == 0) return hipSuccess;
+  master_merge_kernel<<<grid_for(n), 256, 0, s>>>(ring, rem, master, n);
   return hipGetLastError();
 }
 hipError_t transpose_bf16(hipStream_t s, const bf16_t* src, bf16_t* dst, int R, int C) {

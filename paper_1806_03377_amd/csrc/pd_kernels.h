@@ -87,6 +87,11 @@ struct WgradLayer {
   float* master_w;   // [N][K]
   float* mom_w;
   bf16_t* ring_w;
+  // both non-null: the master weights are not read from / written to master_w but kept as the previous ring copy
+  // (ring_in, read) plus 16-bit remainders (rem_w, read and written): 16 instead of 18 bytes per parameter.  All
+  // layers of a batch must agree.  The bias keeps its fp32 master.
+  const bf16_t* ring_in;
+  uint16_t* rem_w;
   float* master_b;   // [N] or null
   float* mom_b;
   bf16_t* ring_b;
@@ -99,6 +104,9 @@ struct WgradBatch {
   UpdateRule rule;
 };
 hipError_t linear_wgrad_update_bf16(hipStream_t s, const WgradBatch& batch);
+// fp32 master <-> (bf16 ring copy, 16-bit remainder), n elements (misc_kernels.hip); see master_split1 in bf16_util.h
+hipError_t master_split(hipStream_t s, const float* master, bf16_t* ring, uint16_t* rem, size_t n);
+hipError_t master_merge(hipStream_t s, const bf16_t* ring, const uint16_t* rem, float* master, size_t n);
 
 // ---- bf16 convolution and pooling, NHWC (conv_bf16.hip) ------------------------------------------------
 struct ConvGeom {

@@ -120,6 +120,7 @@ struct Layer {
   size_t dz_off = 0;          // Linear: byte offset of dL/d(pre-activation) inside the gradient workspace
   size_t part_off = 0;        // conv: byte offset of the weight-gradient partial sums
   int splits = 0;             // conv: number of partial sums (also Linear/LSTM layers with many rows, see kBigRows)
+  bool split_master = false;  // bf16 Linear/LSTM layers updated by the fused kernel: master = ring copy + remainder
   size_t part2_off = 0;       // LSTM with many rows: partial sums of the W_hh gradient
   int splits2 = 0;
   size_t g_off = 0, c_off = 0;  // LSTM: byte offsets inside a stash slot of the gate values [T][B][4H] fp32 and
@@ -168,6 +169,10 @@ struct pd_stage {
   // device regions (inside the caller's arena)
   char* ring = nullptr;      // depth parameter sets (bf16 or fp32)
   float* master = nullptr;   // bf16 mode only
+  // bf16 mode, unreplicated stages: the fp32 master weights of the layers with split_master set are NOT kept in
+  // `master` but as the latest ring copy plus 16 low bits each in `rem` (see master_split1); `master` is then only
+  // the staging area through which the host reads and writes them (materialize_master / split_master_from_staging)
+  uint16_t* rem = nullptr;
   float* mom = nullptr;
   char* in_ring = nullptr;
   char* stash = nullptr;
@@ -238,6 +243,8 @@ struct Plan {
   size_t ws_bytes = 0, dz_bytes = 0, pp_bytes = 0, part_bytes = 0, wt_bytes = 0;
   size_t blk_dy_bytes = 0, blk_dx_bytes = 0, blk_dx_stride = 0, o_blk_dy = 0, o_blk_dx = 0;
   // arena offsets
+  size_t o_rem = 0;
+  bool any_split = false;
   size_t o_ring = 0, o_master = 0, o_mom = 0, o_in = 0, o_stash = 0, o_dz = 0, o_grad = 0, o_ws = 0, o_rowloss = 0;
   size_t o_pp = 0, o_part = 0, o_wt = 0, o_gradbuf = 0;
   int replicas = 1;
@@ -513,6 +520,11 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
   if (!secondary) {
     p.o_ring = o; o += align_up((size_t)p.ring_depth * p.p_pad * p.esz, 256);
     if (p.bf16) { p.o_master = o; o += align_up(p.p_pad * 4, 256); }
+    if (p.bf16 && p.replicas <= 1) {
+      for (Layer& L : p.lin)
+        if (L.n_w && L.kind != K_CONV && L.splits == 0) { L.split_master = true; p.any_split = true; }
+      if (p.any_split) { p.o_rem = o; o += align_up(p.p_pad * 2, 256); }
+    }
     p.o_mom = o; o += align_up(p.p_pad * 4, 256);
   }
   if (p.replicas > 1) { p.o_gradbuf = o; o += align_up(p.p_pad * 4, 256); }
@@ -574,6 +586,7 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
   } else {
     st->ring = a + p.o_ring;
     st->master = p.bf16 ? reinterpret_cast<float*>(a + p.o_master) : nullptr;
+    st->rem = p.any_split ? reinterpret_cast<uint16_t*>(a + p.o_rem) : nullptr;
     st->mom = reinterpret_cast<float*>(a + p.o_mom);
   }
   st->gradbuf = p.replicas > 1 ? reinterpret_cast<float*>(a + p.o_gradbuf) : nullptr;
@@ -722,6 +735,28 @@ int pd_stage_ring_depth(const pd_stage* st, int32_t* ring_depth) {
   return PD_OK;
 }
 
+// Layers whose master weights live as ring copy + remainder: fp32 values in the staging area -> version `version`'s
+// ring slot and the remainders / the other way round (always from the latest version).  Enqueued on the stage's
+// stream.
+static hipError_t split_master_from_staging(pd_stage* st, int version) {
+  pd::bf16_t* r = reinterpret_cast<pd::bf16_t*>(st->ring_slot(version));
+  for (const Linear& L : st->lin)
+    if (L.split_master) {
+      hipError_t e = pd::master_split(st->stream, st->master + L.w_off, r + L.w_off, st->rem + L.w_off, L.n_w);
+      if (e != hipSuccess) return e;
+    }
+  return hipSuccess;
+}
+static hipError_t materialize_master(pd_stage* st) {
+  const pd::bf16_t* r = reinterpret_cast<const pd::bf16_t*>(st->ring_slot(st->latest));
+  for (const Linear& L : st->lin)
+    if (L.split_master) {
+      hipError_t e = pd::master_merge(st->stream, r + L.w_off, st->rem + L.w_off, st->master + L.w_off, L.n_w);
+      if (e != hipSuccess) return e;
+    }
+  return hipSuccess;
+}
+
 int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   if (check_stage(st) || !host_params) return fail(PD_EINVAL, "null argument");
   if (check_owner(st)) return PD_ESTATE;
@@ -738,10 +773,11 @@ int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
     PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, L.n_b * 4, hipMemcpyHostToDevice));
     if (st->bf16) {
       pd::bf16_t* r = reinterpret_cast<pd::bf16_t*>(st->ring);
-      PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, L.n_w));
+      if (!L.split_master) PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, L.n_w));
       PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, L.n_b));
     }
   }
+  if (st->rem) PD_HIP(split_master_from_staging(st, 0));  // ring slot 0 = version 0
   PD_HIP(pd::fill_zero(st->stream, st->mom, st->p_pad * 4));
   PD_HIP(hipStreamSynchronize(st->stream));
   st->latest = 0; st->last_fwd = -1; st->in_flight.clear(); st->grad_pending = false; st->trace.clear();
@@ -756,6 +792,10 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
     return fail(PD_ESTATE, "version %d is not in the ring (latest %d, depth %d)", version, st->latest, st->ring_depth);
   PD_HIP(hipStreamSynchronize(st->stream));
   const bool from_master = st->bf16 && version == st->latest && !ring_copy;
+  if (from_master && st->rem) {
+    PD_HIP(materialize_master(st));
+    PD_HIP(hipStreamSynchronize(st->stream));
+  }
   if (!st->bf16 || from_master) {
     const float* src = from_master ? st->master : reinterpret_cast<const float*>(st->ring_slot(version));
     for (const Linear& L : st->lin) {
@@ -945,7 +985,7 @@ int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const floa
       PD_HIP(hipMemcpy(dst32 + L.b_off, host_params + L.flat_b, L.n_b * 4, hipMemcpyHostToDevice));
       if (st->bf16) {
         pd::bf16_t* r = reinterpret_cast<pd::bf16_t*>(slot);
-        PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, L.n_w));
+        if (!L.split_master) PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.w_off, r + L.w_off, L.n_w));
         PD_HIP(pd::f32_to_bf16(st->stream, st->master + L.b_off, r + L.b_off, L.n_b));
       }
     }
@@ -954,6 +994,7 @@ int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const floa
       PD_HIP(hipMemcpy(st->mom + L.b_off, host_mom + L.flat_b, L.n_b * 4, hipMemcpyHostToDevice));
     }
   }
+  if (host_params && st->rem) PD_HIP(split_master_from_staging(st, st->latest));
   PD_HIP(hipStreamSynchronize(st->stream));
   return PD_OK;
 }
@@ -1437,7 +1478,10 @@ int run_update_kernels(pd_stage* st, int nv, bool grad_only) {
       };
       pd::WgradLayer& W = batch.layer[batch.count++];
       W.dz = reinterpret_cast<const pd::bf16_t*>(dz); W.x = reinterpret_cast<const pd::bf16_t*>(x);
+      const pd::bf16_t* rin = reinterpret_cast<const pd::bf16_t*>(st->ring_slot(st->latest));
+      const bool split = L.split_master && !grad_only;
       W.master_w = w32 + L.w_off; W.mom_w = st->mom + L.w_off; W.ring_w = ro + L.w_off;
+      W.ring_in = split ? rin + L.w_off : nullptr; W.rem_w = split ? st->rem + L.w_off : nullptr;
       W.master_b = w32 + L.b_off; W.mom_b = st->mom + L.b_off; W.ring_b = ro + L.b_off;
       W.M = L.rows; W.N = L.kind == K_LSTM ? 4 * L.out : L.out; W.K = L.in; W.tile_end = 0;
       PD_HIP(flush_if_full());
@@ -1447,6 +1491,7 @@ int run_update_kernels(pd_stage* st, int nv, bool grad_only) {
         V.dz = reinterpret_cast<const pd::bf16_t*>(dz);
         V.x = reinterpret_cast<const pd::bf16_t*>(slot + L.y_off);
         V.master_w = w32 + o2; V.mom_w = st->mom + o2; V.ring_w = ro + o2;
+        V.ring_in = split ? rin + o2 : nullptr; V.rem_w = split ? st->rem + o2 : nullptr;
         V.master_b = nullptr; V.mom_b = nullptr; V.ring_b = nullptr;
         V.M = L.rows; V.N = 4 * L.out; V.K = L.out; V.tile_end = 0;
         PD_HIP(flush_if_full());
@@ -1885,6 +1930,7 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
   pd::WgradLayer& W = batch.layer[0];
   W.dz = static_cast<const pd::bf16_t*>(dz); W.x = static_cast<const pd::bf16_t*>(x);
   W.master_w = master_w; W.mom_w = mom_w; W.ring_w = static_cast<pd::bf16_t*>(ring_out_w);
+  W.ring_in = nullptr; W.rem_w = nullptr;
   W.master_b = master_b; W.mom_b = mom_b; W.ring_b = static_cast<pd::bf16_t*>(ring_out_b);
   W.M = M; W.N = N; W.K = K; W.tile_end = 0;
   PD_HIP(pd::linear_wgrad_update_bf16(static_cast<hipStream_t>(stream), batch));

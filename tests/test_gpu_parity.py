@@ -817,6 +817,51 @@ def test_pipeline_run_twice_continues_ids():
 # ---------------------------------------------------------------------------------------------
 # protocol errors come back as status codes and leave the stage usable
 # ---------------------------------------------------------------------------------------------
+def test_master_weights_as_ring_copy_plus_remainder_round_trip():
+    """The fp32 master weights of a bf16 stage's Linear layers are stored as the latest ring copy plus the low 16 bits
+    of their fp32 pattern.  What pd_stage_set_params / pd_stage_overwrite_latest store, pd_stage_get_params must
+    return bit for bit -- except a tie that rounds DOWN to even (low half 0x8000, upper half even), which comes back
+    one fp32 unit in the last place lower -- and the ring copy must be the round-to-nearest-even bf16 of the value."""
+    layers = [("linear", 64, 48, True), ("linear", 48, 16, False)]
+    n = sum(l[1] * l[2] + l[2] for l in layers)
+    rng = np.random.default_rng(SEED)
+    bits = rng.integers(0, 2 ** 32, size=n, dtype=np.uint64).astype(np.uint32)
+    bits &= np.uint32(0xBFFFFFFF)                      # exponent below 2: finite, no NaN / Inf
+    # special patterns: zeros of both signs, denormals, ties in both directions, low halves around 0x8000
+    special = np.array([0x00000000, 0x80000000, 0x00000001, 0x00008000, 0x00018000, 0x3F808000, 0x3F818000,
+                        0x3F807FFF, 0x3F808001, 0xBF808000, 0xBF818000, 0x3F80FFFF, 0x3F7F8000, 0x3F7FFFFF],
+                       dtype=np.uint32)
+    bits[:special.size] = special
+    params = bits.view(np.float32).copy()
+    g = GpuStage(layers, params, minibatch=8, precision=pd.PD_BF16_F32ACC)
+    try:
+        def expected(b):
+            lo, up = b & np.uint32(0xFFFF), b >> np.uint32(16)
+            tie_down = (lo == 0x8000) & ((up & 1) == 0)
+            return np.where(tie_down, b - np.uint32(1), b)
+        def rne(b):
+            b64 = b.astype(np.uint64)
+            return (((b64 + 0x7FFF + ((b64 >> 16) & 1)) >> 16) & 0xFFFF).astype(np.uint32)
+        # which entries are Linear weights (the biases keep a plain fp32 master: returned exactly)
+        is_w = np.zeros(n, dtype=bool)
+        o = 0
+        for (_, i_, o_, _) in layers:
+            is_w[o:o + i_ * o_] = True
+            o += i_ * o_ + o_
+        want = np.where(is_w, expected(bits), bits)
+        for setter in ("set", "overwrite"):
+            if setter == "overwrite":
+                pd.pd_stage_overwrite_latest(g.h, params, None)
+            got = pd.pd_stage_get_params(g.h, -1, False).view(np.uint32)
+            assert np.array_equal(got, want), setter
+            ring = pd.pd_stage_get_params(g.h, -1, True).view(np.uint32)   # the bf16 ring copy, widened
+            assert np.array_equal(ring >> np.uint32(16), rne(bits)), setter
+            assert np.all((ring & np.uint32(0xFFFF)) == 0)
+        assert int(np.sum(want != bits)) >= 3          # the planted round-down ties are in the sample
+    finally:
+        g.close()
+
+
 def test_protocol_errors():
     layers = [("linear", 16, 8, False), ("softmax_xent", 8)]
     params = gen.init_params(SEED, "p", layers)
