@@ -168,8 +168,8 @@ int pd_schedule_1f1b_depth(int32_t depth, int32_t num_minibatches, pd_op* out, s
 
 /* --- stage life cycle (Sections 3.5 and 4: static allocation at initialisation) -----------
  * pd_stage_query_bytes: bytes of device arena the configuration needs (weight-version ring,
- * fp32 master weights and momentum, activation stash for `depth` minibatches, input ring,
- * gradient and split-K workspaces).
+ * fp32 master weights and momentum, in bf16 mode 16-bit remainders of the master weights,
+ * activation stash for `depth` minibatches, input ring, gradient and split-K workspaces).
  * pd_stage_create: carves `device_arena` (256-byte aligned, >= query bytes, owned by the
  * caller, must outlive the stage; contents need not be initialised).  Parameters start
  * undefined until pd_stage_set_params; momentum starts at zero.  PD_ENOMEM if too small. */
@@ -217,7 +217,12 @@ int pd_stage_ring_depth(const pd_stage* st, int32_t* ring_depth);
 /* Resets the stage to version 0 with these weights (host, fp32, flat layout above), zero
  * momentum, nothing in flight.  In bf16 mode ring slot 0 = round-to-nearest-even of them. */
 int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n);
-/* Weights of `version` (-1 = latest) as fp32 into host_out.  Latest: the fp32 master.  An older
+/* Weights of `version` (-1 = latest) as fp32 into host_out.  Latest: the fp32 master.  (bf16 mode, unreplicated
+ * stage: the master weights of Linear and LSTM layers with minibatch-sized row counts are held as the latest bf16 ring
+ * copy plus the low 16 bits of their fp32 pattern, which is exact for every value but one kind: a value whose low
+ * half is exactly 0x8000 and whose upper half is even -- a tie that rounds down -- is held, and returned, one fp32 unit
+ * in the last place lower.  This applies to what set_params / overwrite_latest store and to what an update produces.
+ * NaNs are not preserved.)  An older
  * version must still be in the ring (version > latest - depth), else PD_ESTATE; in bf16 mode
  * an older version is its bf16 ring copy widened to float.  `ring_copy` != 0 forces the ring
  * copy also for the latest version. */
