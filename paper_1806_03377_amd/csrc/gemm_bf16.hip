@@ -14,6 +14,8 @@
 //   D (16 floats): column (l & 31), rows 8*(r / 4) + 4*(l >> 5) + (r % 4) for r = 0..15
 // A and B always take their 8 reduction elements from the same positions, so any fixed permutation
 // of the reduction index inside an instruction cancels out.
+#include <type_traits>
+
 #include "bf16_util.h"
 #include "mfma_util.h"
 #include "pd_kernels.h"
@@ -474,30 +476,28 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
   const int nt = NFAST ? (int)(tile_id % ntiles) : (int)(tile_id / ktiles);
   const int n0 = nt * TN, k0 = kt * TK;
 
-  // phase 0: prefetch master and momentum of this thread's phase-2 elements
+  // phase 0 (issued inside the first reduction chunk, AFTER that chunk's dz / x loads): master and momentum of this
+  // thread's phase-2 elements.  Loads complete in issue order as far as the wait counter is concerned, so the chunk's
+  // LDS stores can wait for dz / x alone only if these loads come later; and they are unconditional (an element
+  // outside the matrix reads a clamped address and is ignored in phase 2), because a load that only some paths issue
+  // makes the compiler wait for everything at the next use.
   static_assert(!SPLIT || PREFETCH, "the split master is only read ahead");
   float4 pw[kSlots], pm[kSlots];
   uint2 ph[kSlots], pl[kSlots];  // SPLIT: four bf16 of the previous ring copy, four remainders
-  if (PREFETCH) {
+  auto prefetch = [&]() {
 #pragma unroll
     for (int q = 0; q < kSlots; ++q) {
       const int f = t + kThreads * q, row = f / (TK / 4), k = k0 + (f % (TK / 4)) * 4, n = n0 + row;
-      if (n < N && k < K) {
-        const size_t off = (size_t)n * K + k;
-        if (SPLIT) {
-          ph[q] = nt_load_u2(ring_in + off);
-          pl[q] = nt_load_u2(rem + off);
-        } else {
-          pw[q] = nt_load4(master + off);
-        }
-        pm[q] = nt_load4(mom + off);
+      const size_t off = (size_t)(n < N ? n : N - 1) * K + (k < K ? k : K - 4);
+      if (SPLIT) {
+        ph[q] = nt_load_u2(ring_in + off);
+        pl[q] = nt_load_u2(rem + off);
       } else {
-        pw[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        pm[q] = pw[q];
-        ph[q] = pl[q] = make_uint2(0u, 0u);
+        pw[q] = nt_load4(master + off);
       }
+      pm[q] = nt_load4(mom + off);
     }
-  }
+  };
 
   // phase 1
   f32x16 acc[NB][KB];
@@ -505,7 +505,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
   for (int i = 0; i < NB; ++i)
 #pragma unroll
     for (int j = 0; j < KB; ++j) acc[i][j] = f32x16{0};
-  for (int mc = 0; mc < M; mc += MC) {
+  auto chunk = [&](int mc, auto first) {
     {
       constexpr int ZB = TN / 8 * 32 / kThreads > 0 ? TN / 8 * 32 / kThreads : 1;  // dz blocks per thread
       constexpr int XB = TK / 8 * 32 / kThreads;                                    // x blocks per thread
@@ -525,7 +525,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
         x0[i] = (mm < M && k < K) ? ldg16(X + (size_t)mm * K + k) : zero16();
         x1[i] = (mm + 1 < M && k < K) ? ldg16(X + (size_t)(mm + 1) * K + k) : zero16();
       }
-      if (mc) __syncthreads();  // previous chunk's fragments fully read
+      if (decltype(first)::value) {
+        if (PREFETCH) prefetch();
+      } else {
+        __syncthreads();  // previous chunk's fragments fully read
+      }
 #pragma unroll
       for (int i = 0; i < ZB; ++i) {
         const int b = t + kThreads * i, nc = b % (TN / 8), pair = b / (TN / 8);
@@ -552,7 +556,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_update_kernel(WgradBatch batch
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b), acc[i][j], 0, 0, 0);
       }
     }
-  }
+  };
+  chunk(0, std::true_type{});
+  for (int mc = MC; mc < M; mc += MC) chunk(mc, std::false_type{});
   __syncthreads();  // all fragment reads done before the tile memory is reused
 
   // phase 2a: accumulators -> LDS, G[n][k]
