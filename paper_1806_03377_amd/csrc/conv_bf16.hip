@@ -853,11 +853,98 @@ hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t
   return hipGetLastError();
 }
 
+// The same four elements at a time (16-byte accesses; a group of four never straddles the weight / bias border
+// because both counts are multiples of four).  Lane j of a group adds the splits j, j + G, ... in that order, as
+// above, but their loads are issued in batches of eight before the first add (unconditional loads of a clamped
+// split index, surplus terms dropped by a select), and master and momentum are requested right after the first
+// batch: the kernel is a chain of memory latencies otherwise (one 4-byte load per add, then two more loads).
+template <int G>
+__global__ __launch_bounds__(256) void wgrad_reduce_update4_kernel(const float* __restrict__ part, int splits,
+                                                                   size_t stride, size_t n_w, int n_b,
+                                                                   float* __restrict__ master_w, float* __restrict__ mom_w,
+                                                                   bf16_t* __restrict__ ring_w, float* __restrict__ master_b,
+                                                                   float* __restrict__ mom_b, bf16_t* __restrict__ ring_b,
+                                                                   UpdateRule rule) {
+  constexpr int kBatch = 8;
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t e = (tid / G) * 4;
+  const int j = (int)(tid % G);
+  const size_t n = n_w + n_b;
+  const bool live = e < n;  // (whole groups of G lanes are live or not: 256 % G == 0)
+  const size_t ec = live ? e : 0;
+  const bool is_w = ec < n_w;
+  float* ms = is_w ? master_w + ec : master_b + (ec - n_w);
+  float* mm = is_w ? mom_w + ec : mom_b + (ec - n_w);
+  bf16_t* rr = is_w ? ring_w + ec : ring_b + (ec - n_w);
+  const int terms = (splits + G - 1) / G;  // per lane, counting the ones past the end that are dropped
+  float4 g = make_float4(0.f, 0.f, 0.f, 0.f), m4 = g, w4 = g;
+  for (int i0 = 0; i0 < terms; i0 += kBatch) {
+    float4 p[kBatch];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int sx = j + (i0 + q) * G;
+      p[q] = *reinterpret_cast<const float4*>(part + (size_t)(sx < splits ? sx : j) * stride + ec);
+    }
+    if (i0 == 0 && rule.kind != kRuleGradOnly) {
+      m4 = *reinterpret_cast<const float4*>(mm);
+      w4 = *reinterpret_cast<const float4*>(ms);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const bool on = j + (i0 + q) * G < splits;
+      g.x = on ? g.x + p[q].x : g.x; g.y = on ? g.y + p[q].y : g.y;
+      g.z = on ? g.z + p[q].z : g.z; g.w = on ? g.w + p[q].w : g.w;
+    }
+  }
+#pragma unroll
+  for (int d = 1; d < G; d <<= 1) {
+    g.x += __shfl_xor(g.x, d, 64); g.y += __shfl_xor(g.y, d, 64);
+    g.z += __shfl_xor(g.z, d, 64); g.w += __shfl_xor(g.w, d, 64);
+  }
+  if (!live || j != 0) return;
+  if (rule.kind == kRuleGradOnly) {  // replicated stage: the sum over replicas comes first
+    *reinterpret_cast<float4*>(ms) = g;
+    return;
+  }
+  apply_update(rule, g.x, m4.x, w4.x); apply_update(rule, g.y, m4.y, w4.y);
+  apply_update(rule, g.z, m4.z, w4.z); apply_update(rule, g.w, m4.w, w4.w);
+  *reinterpret_cast<float4*>(mm) = m4;
+  *reinterpret_cast<float4*>(ms) = w4;
+  uint2 pk;
+  pk.x = (uint32_t)f2bf(w4.x) | ((uint32_t)f2bf(w4.y) << 16);
+  pk.y = (uint32_t)f2bf(w4.z) | ((uint32_t)f2bf(w4.w) << 16);
+  *reinterpret_cast<uint2*>(rr) = pk;
+}
+
 hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, size_t stride, size_t n_w, int n_b,
                                float* master_w, float* mom_w, bf16_t* ring_w, float* master_b, float* mom_b,
                                bf16_t* ring_b, UpdateRule rule) {
   const size_t n = n_w + n_b;
   if (!stride) stride = n;
+  const uintptr_t align16 = reinterpret_cast<uintptr_t>(part) | reinterpret_cast<uintptr_t>(master_w) |
+                            reinterpret_cast<uintptr_t>(mom_w) | reinterpret_cast<uintptr_t>(master_b) |
+                            reinterpret_cast<uintptr_t>(mom_b);
+  const uintptr_t align8 = reinterpret_cast<uintptr_t>(ring_w) | reinterpret_cast<uintptr_t>(ring_b);
+  if (splits >= 1 && (n_w % 4) == 0 && (n_b % 4) == 0 && (stride % 4) == 0 && (align16 & 15) == 0 && (align8 & 7) == 0) {
+    int G = 1;
+    while (G < 64 && 2 * G <= splits && (n / 4) * (size_t)(2 * G) <= ((size_t)1 << 19)) G *= 2;
+    const unsigned blocks = (unsigned)((n / 4 * G + 255) / 256);
+#define PD_REDUCE4(GG)                                                                                              \
+  wgrad_reduce_update4_kernel<GG><<<blocks, 256, 0, s>>>(part, splits, stride, n_w, n_b, master_w, mom_w, ring_w, \
+                                                         master_b, mom_b, ring_b, rule)
+    switch (G) {
+      case 1: PD_REDUCE4(1); break;
+      case 2: PD_REDUCE4(2); break;
+      case 4: PD_REDUCE4(4); break;
+      case 8: PD_REDUCE4(8); break;
+      case 16: PD_REDUCE4(16); break;
+      case 32: PD_REDUCE4(32); break;
+      default: PD_REDUCE4(64); break;
+    }
+#undef PD_REDUCE4
+    return hipGetLastError();
+  }
   // lanes per element: enough threads to fill the chip, never more than there are partial sums
   int G = 1;
   while (G < 64 && 2 * G <= splits && n * (size_t)(2 * G) <= ((size_t)1 << 19)) G *= 2;
