@@ -215,13 +215,19 @@ __global__ __launch_bounds__(256) void softmax_xent_wide_kernel(const float* __r
   const int nq = classes >> 2;  // float4 per row
   float4 v[NV];
   float mx = -INFINITY;
+  // all of the row's loads first, unconditionally (a piece past the end re-reads the last one and is ignored):
+  // a load under a condition, used right behind it, costs one memory latency per piece
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int q = t + 256 * i;
-    if (q < nq) {
-      v[i] = *reinterpret_cast<const float4*>(logits + base + 4 * q);
-      mx = fmaxf(fmaxf(mx, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
-    }
+    v[i] = *reinterpret_cast<const float4*>(logits + base + 4 * (q < nq ? q : nq - 1));
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int q = t + 256 * i;
+    const float m4 = fmaxf(fmaxf(v[i].x, v[i].y), fmaxf(v[i].z, v[i].w));
+    mx = q < nq ? fmaxf(mx, m4) : mx;
   }
   mx = block_reduce(mx, sh, true);
   int lab = labels[r];
