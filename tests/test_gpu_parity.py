@@ -475,6 +475,7 @@ def test_conv_dgrad_strided_bf16(geom):
 
 @pytest.mark.parametrize("is_max,N,H,W,Cn,k,stride,pad", [
     (True, 2, 9, 7, 8, 3, 2, 0), (True, 1, 35, 35, 24, 3, 2, 0), (True, 2, 6, 6, 16, 3, 1, 0), (True, 2, 8, 8, 8, 2, 2, 0),
+    (True, 1, 10, 11, 8, 3, 3, 0), (True, 3, 3, 3, 8, 3, 1, 0),
     (False, 2, 7, 6, 8, 3, 1, 1), (False, 1, 17, 17, 40, 3, 1, 1), (False, 3, 8, 8, 16, 8, 1, 0), (False, 2, 9, 9, 8, 3, 2, 1)])
 def test_pool2d_bf16(is_max, N, H, W, Cn, k, stride, pad):
     # coarse grid of values so that ties inside max windows are common
