@@ -23,7 +23,11 @@
  *     pd_stage_create (static allocation, Section 3.5).
  *   - pd_forward / pd_backward / pd_update only ENQUEUE kernels on the stage's
  *     stream and return; they never synchronise, never memset, and are safe to
- *     capture into a HIP graph.  Host-side bookkeeping (versions, stash table)
+ *     capture into a HIP graph on that stream (a recorded period of `depth`
+ *     steps replays correctly because ring and stash slots repeat with that
+ *     period; the host-side counters do not advance on replay).  The pipeline
+ *     drivers, which join several streams by events, are not meant to be
+ *     captured.  Host-side bookkeeping (versions, stash table)
  *     is advanced at call time, which is valid because a stage's op order is
  *     static.  pd_stage_set_* / pd_stage_get_* synchronise the stream.
  *   - Numbering: stages s = 0..S-1, minibatches i = 0,1,2,..., version v = number
