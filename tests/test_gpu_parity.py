@@ -159,6 +159,14 @@ def test_stage_f32_small_shapes():
     _single_stage_case(layers, B=5, depth=3, M=8, precision=pd.PD_F32, lr=0.05)
 
 
+def test_stage_f32_reductions_longer_than_a_kernel_step():
+    # the fp32 kernel walks a reduction 128 elements at a time with the next step's loads in flight: every product
+    # here has a reduction of several steps with a ragged last one (forward 300 and 150, input gradient 150 and 70,
+    # weight gradient 140 rows), and ragged 32 x 32 output tiles
+    layers = [("linear", 300, 150, True), ("linear", 150, 70, False), ("softmax_xent", 70)]
+    _single_stage_case(layers, B=140, depth=2, M=4, precision=pd.PD_F32, lr=0.05)
+
+
 def test_stage_f32_middle_stage_with_relu_output():
     layers = [("linear", 48, 40, True), ("linear", 40, 24, True)]
     _single_stage_case(layers, B=9, depth=2, M=6, precision=pd.PD_F32, lr=0.05, with_loss=False)
