@@ -1722,7 +1722,7 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
           if (vsync && s == 0) tag[i] = st->latest;
           const int rc = pd_forward_versioned(st, mb, vsync ? tag[i] : -1, x, lab, y, loss);
           if (rc != PD_OK) return rc;
-          PD_HIP(hipEventRecord(st->ev_f[i], st->stream));
+          if (s < S - 1) PD_HIP(hipEventRecord(st->ev_f[i], st->stream));  // (only the next stage waits for it)
           f_rec[s][i] = 1;
         } else if (op.kind == PD_OP_B) {
           if (s < S - 1 && !b_rec[s + 1][i]) break;
@@ -1738,7 +1738,7 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
         } else {
           const int rc = pd_update(st);
           if (rc != PD_OK) return rc;
-          PD_HIP(hipEventRecord(st->ev_u[i], st->stream));
+          if (s > 0) PD_HIP(hipEventRecord(st->ev_u[i], st->stream));  // (only the stage before waits for it: slot reuse)
           u_rec[s][i] = 1;
         }
         ++pos[s];
