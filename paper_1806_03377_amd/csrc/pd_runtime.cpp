@@ -1844,7 +1844,7 @@ int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replica
             float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
             const int rc = pd_forward(st, k, x, lab, y, loss);
             if (rc != PD_OK) return rc;
-            PD_HIP(hipEventRecord(st->ev_f[k], st->stream));
+            if (s < S - 1) PD_HIP(hipEventRecord(st->ev_f[k], st->stream));  // (only the next stage waits for it)
             f_rec[s][q][k] = 1;
           } else if (op.kind == PD_OP_B) {
             if (s < S - 1 && !b_rec[s + 1][qn][kn]) break;
@@ -1868,7 +1868,7 @@ int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replica
             if (!ready) break;
             const int rc = r[s] > 1 ? pd_update_replicated(replicas + first[s], r[s]) : pd_update(st);
             if (rc != PD_OK) return rc;
-            PD_HIP(hipEventRecord(rep(s, 0)->ev_u[k], rep(s, 0)->stream));
+            if (s > 0) PD_HIP(hipEventRecord(rep(s, 0)->ev_u[k], rep(s, 0)->stream));  // (only the stage before waits for it)
             u_rec[s][k] = 1;
             for (int p = 0; p < r[s]; ++p)
               if (p != q && rounds(s, p) > k) {
