@@ -23,15 +23,18 @@ sys.path.insert(0, ROOT)
 METRIC = "samples/sec per 1F1B stage step (bf16) + MFMA util % of MI355X peak"
 HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK = 2.5e15
-UPDATE_BYTES_PER_PARAM = 16  # read previous ring copy 2 + remainder 2 + momentum 4; write remainder 2 + momentum 4 + ring copy 2
-                             # (the fp32 master weights are the ring copy plus a 16-bit remainder; the biases, 0.007 % of the
-                             # parameters, keep an fp32 master and move 18)
+# Algorithmic HBM bytes per parameter of the fused weight-gradient + update launch.  With the fp32 master weights as an
+# array of their own: read master 4 + momentum 4, write master 4 + momentum 4 + bf16 ring copy 2 = 18.  As stored
+# here (master = latest ring copy + 16-bit remainder): read ring copy 2 + remainder 2 + momentum 4, write remainder 2 +
+# momentum 4 + ring copy 2 = 16.  The roofline object reports the kernel against both.
+SURVEY_UPDATE_BYTES_PER_PARAM = 18
+STORED_UPDATE_BYTES_PER_PARAM = 16
 # HBM bytes per launch of the dominant kernel at the default workload, from the rocprofv3 counter runs
 # summarised in profiles/wgrad_update_vgg16fc_mb64.txt (FETCH_SIZE x 1.986 + WRITE_SIZE x 1.000)
 MEASURED_TRAFFIC_BYTES = 1.988e9
 
 
-def cpu_baseline(layers, params, xs, labs, depth, budget_s=12.0, max_steps=16):
+def cpu_baseline(layers, params, xs, labs, depth, budget_s=12.0, max_steps=16, lr=0.01):
     """The oracle, as it stands, on the host cores: same stage, same step, a bounded number of steps (about 10 s of
     work; the oracle keeps every weight version it produces, about 1 GB each at this size, hence the step cap)."""
     import numpy as np
@@ -41,7 +44,7 @@ def cpu_baseline(layers, params, xs, labs, depth, budget_s=12.0, max_steps=16):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    st = Stage(layers, params, depth, "bf16")
+    st = Stage(layers, params, depth, "bf16", lr=lr)
     n = len(xs)
     for i in range(depth):
         st.forward(i, xs[i % n].astype(np.float64), labs[i % n])
@@ -122,7 +125,7 @@ def bench_conv(args, pd, gen, torch, np, dev):
                         "achieved": f / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
                         "frac": f / (ms * 1e-3) / MFMA_BF16_PEAK, "traffic": None}}
     pd.pd_stage_destroy(h)
-    print(json.dumps(out))
+    return out
 
 
 def bench_replicated(args, pd, gen, torch, np, dev):
@@ -221,7 +224,7 @@ def bench_replicated(args, pd, gen, torch, np, dev):
                         f"streams {4 * r + 18} bytes per parameter)",
                         "achieved": f / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
                         "frac": f / (ms * 1e-3) / MFMA_BF16_PEAK, "traffic": None}}
-    print(json.dumps(out))
+    return out
 
 
 def bench_vgg16_pipeline(args, pd, gen, torch, np, dev):
@@ -297,7 +300,7 @@ def bench_vgg16_pipeline(args, pd, gen, torch, np, dev):
                       "minibatch": B, "replicas": r, "params": P},
            "ms_per_minibatch_1_1_pipeline": res[1] / M, "first_loss": float(losses[0].item()),
            "final_loss": float(losses[-1].item())}
-    print(json.dumps(out))
+    return out
 
 
 def bench_s2vt(args, pd, gen, torch, np, dev):
@@ -349,7 +352,7 @@ def bench_s2vt(args, pd, gen, torch, np, dev):
            "final_loss": float(losses[-1].item())}
     for h in hs:
         pd.pd_stage_destroy(h)
-    print(json.dumps(out))
+    return out
 
 
 def bench_inception(args, pd, gen, torch, np, dev):
@@ -406,7 +409,7 @@ def bench_inception(args, pd, gen, torch, np, dev):
            "final_loss": float(losses[-1].item())}
     for h in hs:
         pd.pd_stage_destroy(h)
-    print(json.dumps(out))
+    return out
 
 
 def bench_mlp4(args, pd, gen, torch, np, dev):
@@ -452,7 +455,7 @@ def bench_mlp4(args, pd, gen, torch, np, dev):
            "final_loss": float(losses[-1].item())}
     for h in hs:
         pd.pd_stage_destroy(h)
-    print(json.dumps(out))
+    return out
 
 
 def bench_gemm_sweep(args, pd, gen, torch, np, dev):
@@ -462,6 +465,8 @@ def bench_gemm_sweep(args, pd, gen, torch, np, dev):
     s = torch.cuda.current_stream().cuda_stream
     shapes = [(4096, 4096)] if args.small else [(4096, 25088), (4096, 4096)]
     rows_list = [64, 256, 1024] if args.small else [64, 128, 256, 512, 1024, 2048, 4096, 8192]
+    if getattr(args, "rows", None):
+        rows_list = list(args.rows)
 
     def timeit(fn, n=5):
         fn(); torch.cuda.synchronize()
@@ -509,7 +514,7 @@ def bench_gemm_sweep(args, pd, gen, torch, np, dev):
            "config": {"workload": "row-count sweep of the Linear kernels at the VGG16 classifier's K, N"},
            "roofline": {"bound": "mfma", "achieved": best, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
                         "frac": best * 1e12 / MFMA_BF16_PEAK, "traffic": None}, "sweep": table}
-    print(json.dumps(out))
+    return out
 
 
 def bench_partition(args, pd, gen, torch, np, dev):
@@ -575,17 +580,265 @@ def bench_partition(args, pd, gen, torch, np, dev):
                         "upd_ms": round(u["upd_ms"], 4), "a_bytes": u["act_bytes"], "w_bytes": u["param_bytes"]}
                        for u, t in zip(prof, T)],
            "partitions": parts}
-    print(json.dumps(out))
+    return out
+
+
+def bench_vgg16_fc(args, pd, gen, torch, np, dev):
+    """The metric's workload (config 2): the VGG16 classifier as one stage, bf16 with fp32 accumulation, minibatch
+    64, weight-version ring depth 4.  Step = B(k) U(k) F(k + depth).
+
+    Inputs are NOT recycled: every minibatch of the run is a distinct synthetic one (64 x 25088 N(0,1) values and 64
+    labels), resident in HBM before the timed region starts.  The stage is configured as the second stage of a two-
+    stage pipeline, as the classifier is in the paper's VGG16 configurations, so its input ring has depth + 1 slots;
+    a producer stream plays the upstream stage and copies minibatch k + depth + 1 into the free slot while step k runs
+    (event-ordered after the update that last read that slot), exactly the hand-off pd_pipeline_run performs between
+    stages.  pd_forward then reads its input in place.
+
+    Timing: `--repetitions` (5) repetitions of `--steps` steps each, every repetition bracketed by a device
+    synchronisation on both sides (wall clock) and by HIP events recorded on the stage's stream; ms_per_step is the
+    MEDIAN repetition's wall-clock time per step, the spread of all repetitions is reported beside it.  Events recorded
+    between the ops give the time of each op and of the dominant kernel's launch (pd_update is exactly one launch)."""
+    B, depth, K, W, reps = args.minibatch, args.depth, args.steps, args.warmup, args.repetitions
+    layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
+    n_in, classes = layers[0][1], layers[-1][1]
+    seed = gen.BASE_SEED + 1
+    params = gen.init_params(seed, "vgg_fc", layers)
+    P = int(params.size)
+    stream = torch.cuda.Stream(device=dev)
+    producer = torch.cuda.Stream(device=dev)
+    cfg = pd.make_config(layers, stage_index=1, num_stages=2, noam=2, in_flight_override=depth, minibatch=B,
+                         precision=pd.PD_BF16_F32ACC, lr=args.lr, momentum=0.9, stream=stream.cuda_stream)
+    nbytes = pd.pd_stage_query_bytes(cfg)
+    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+    base = (arena.data_ptr() + 255) // 256 * 256
+    h = pd.pd_stage_create(cfg, base, nbytes)
+    pd.pd_stage_set_params(h, params)
+    in_ring = pd.pd_stage_depth(h)[1]
+    assert in_ring == depth + 1
+    n_steps = max(W, in_ring) + reps * K
+    n_mb = n_steps + depth                          # distinct minibatches of the whole run
+    x_all = torch.from_numpy(gen.normal_bulk(seed, "x", (n_mb, B, n_in))).to(dev).to(torch.bfloat16)
+    lab_all = torch.from_numpy(gen.labels(seed, "y", (n_mb, B), classes)).to(dev)
+    dx = torch.empty((B, n_in), dtype=torch.bfloat16, device=dev)
+    losses = torch.zeros(n_mb, dtype=torch.float32, device=dev)
+    off0 = pd.pd_stage_input_slot(h, 0) - arena.data_ptr()
+    slot_view = [arena[off0 + j * B * n_in * 2: off0 + (j + 1) * B * n_in * 2].view(torch.bfloat16).view(B, n_in)
+                 for j in range(in_ring)]          # (slot of minibatch i = i mod in_ring, contiguous from slot 0)
+    assert all(pd.pd_stage_input_slot(h, j) == slot_view[j].data_ptr() for j in range(in_ring))
+    filled = [torch.cuda.Event() for _ in range(in_ring)]      # producer: slot j holds its next minibatch
+    freed = [torch.cuda.Event() for _ in range(in_ring)]       # stage: the update that last read slot j is done
+    torch.cuda.synchronize()
+
+    def produce(i, wait_free):
+        """The upstream stage's part: minibatch i goes into its input slot on the producer stream."""
+        j = i % in_ring
+        with torch.cuda.stream(producer):
+            if wait_free:
+                producer.wait_event(freed[j])
+            slot_view[j].copy_(x_all[i], non_blocking=True)
+            filled[j].record(producer)
+
+    def fwd(i):
+        stream.wait_event(filled[i % in_ring])
+        pd.pd_forward(h, i, pd.pd_stage_input_slot(h, i), lab_all[i].data_ptr(), 0, losses[i:].data_ptr())
+
+    def step(k, ev=None):
+        # B(k), U(k), F(k + depth); meanwhile the producer refills the slot that U(k) frees with minibatch k + in_ring
+        if ev is not None:
+            ev[0].record(stream)
+        pd.pd_backward(h, k, 0, dx.data_ptr())
+        if ev is not None:
+            ev[1].record(stream)
+        pd.pd_update(h)
+        if ev is not None:
+            ev[2].record(stream)
+        freed[k % in_ring].record(stream)
+        if k + in_ring < n_mb:
+            produce(k + in_ring, True)
+        fwd(k + depth)
+        if ev is not None:
+            ev[3].record(stream)
+
+    for i in range(in_ring):
+        produce(i, False)
+    for i in range(depth):
+        fwd(i)
+    k = 0
+    for _ in range(max(W, in_ring)):
+        step(k)
+        k += 1
+    rep_wall, rep_evt, ops = [], [], {"B": [], "U": [], "F": []}
+    for _ in range(reps):
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for j in range(K):
+            step(k, evs[j])
+            k += 1
+        torch.cuda.synchronize()
+        rep_wall.append((time.perf_counter() - t0) * 1e3 / K)
+        rep_evt.append(evs[0][0].elapsed_time(evs[-1][3]) / K)
+        for e in evs:
+            ops["B"].append(e[0].elapsed_time(e[1])); ops["U"].append(e[1].elapsed_time(e[2])); ops["F"].append(e[2].elapsed_time(e[3]))
+    ms_per_step = float(np.median(rep_wall))
+    upd_ms_avg = float(np.mean(ops["U"]))
+    lh = losses.cpu().numpy()
+    first_loss, final_loss = float(lh[0]), float(lh[k + depth - 1])
+    # sanity of the timed trajectory: fresh minibatches with random labels cannot be memorised, so the loss stays near
+    # log(classes); a loss kernel that wrote nothing, dead units or a diverged run would all show here
+    assert np.all(np.isfinite(lh[:k + depth])) and final_loss > 0.1 and float(lh[:k + depth].min()) > 0.1, (first_loss, final_loss)
+
+    lin = [L for L in layers if L[0] == "linear"]
+    flops = 6.0 * B * sum(L[1] * L[2] for L in lin)
+    value = B / (ms_per_step * 1e-3)
+    survey, stored = SURVEY_UPDATE_BYTES_PER_PARAM, STORED_UPDATE_BYTES_PER_PARAM
+    ach = survey * P / (upd_ms_avg * 1e-3) / 1e9
+    ach_stored = stored * P / (upd_ms_avg * 1e-3) / 1e9
+    out = {
+        "metric": METRIC, "value": value, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": max(W, in_ring),
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": ("REDUCED " if args.small else "") +
+                   f"VGG16-FC-shaped stage: Linear {n_in}-{layers[0][2]}-{layers[1][2]}-{classes} + ReLU + "
+                   f"softmax-xent, bf16 w/ fp32 accum, minibatch {B}, weight-version ring depth {depth}, "
+                   f"step = B(k) U(k) F(k+depth); {n_mb} distinct minibatches resident in HBM, handed into the stage's "
+                   "input ring by a producer stream as an upstream stage would",
+                   "params": P, "minibatch": B, "ring_depth": depth, "lr": args.lr},
+        "repetitions": reps,
+        "ms_per_step_repetitions_wall": [round(v, 5) for v in rep_wall],
+        "ms_per_step_repetitions_hip_events": [round(v, 5) for v in rep_evt],
+        "ms_per_step_spread": {"min": min(rep_wall), "median": ms_per_step, "max": max(rep_wall)},
+        "per_op_ms": {name: {"mean": float(np.mean(v)), "median": float(np.median(v)), "min": float(np.min(v)),
+                             "max": float(np.max(v))} for name, v in ops.items()},
+        "mfma_util_pct": 100.0 * flops / (ms_per_step * 1e-3) / MFMA_BF16_PEAK,
+        "step_gflop": flops / 1e9,
+        # the whole step against its HBM bound: 22 B/param with an fp32 master array (2 forward + 2 input gradient +
+        # 18 update), 20 B/param as stored here
+        "step_roofline": {"bound": "hbm", "bytes_per_param_survey": 22, "bytes_per_param_stored": 20,
+                          "frac_survey": 22.0 * P / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                          "frac_stored": 20.0 * P / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": "wgrad_update_kernel (dW = dZ^T X fused with momentum-SGD into the ring)",
+                     "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "bytes_per_param_survey": survey, "bytes_per_param_stored": stored,
+                     "achieved_stored": ach_stored, "frac_stored": ach_stored / HBM_PEAK_GBS,
+                     "traffic": (MEASURED_TRAFFIC_BYTES if (not args.small and B == 64) else None),
+                     "traffic_source": "profiles/wgrad_update_vgg16fc_mb64.txt", "launches_per_step": 1,
+                     "avg_launch_ms": upd_ms_avg, "launch_ms_median": float(np.median(ops["U"])),
+                     "bytes_per_launch": survey * P, "bytes_per_launch_stored": stored * P},
+        "first_loss": first_loss, "final_loss": final_loss,
+        "loss_range": [float(lh[:k + depth].min()), float(lh[:k + depth].max())],
+    }
+    pd.pd_stage_destroy(h)
+    del arena, slot_view, x_all
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        xs = list(gen.normal_bulk(seed, "cx", (depth + 1, B, n_in)))
+        labs = list(gen.labels(seed, "cy", (depth + 1, B), classes))
+        out["cpu_baseline"] = cpu_baseline(layers, params, xs, labs, depth, lr=args.lr)
+    return out
+
+
+def _oracle_steps(stage_layers, params, xs, labs, dys, noam, budget_s, what, minibatch):
+    """The oracle's pipeline on a bounded sample: whole minibatches through all stages until the budget is used."""
+    import numpy as np
+    from oracle.pipeline import run_pipeline
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n, t0 = 0, time.time()
+    while n == 0 or time.time() - t0 < budget_s:
+        run_pipeline(stage_layers, params, [x.astype(np.float64) for x in xs], labs, noam, mode="bf16", out_grads=dys)
+        n += len(xs)
+    dt = time.time() - t0
+    return {"value": n * minibatch / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{what}: {n} minibatches of {minibatch} in {dt:.1f} s, fp64 numpy"}
+
+
+def run_extras(args, pd, gen, torch, np, dev):
+    """The secondary workloads, each timed briefly in the same run (configs 1, 3, 4, 5 and the compute-bound end of
+    the row-count sweep), each with its own roofline object and the oracle timed beside it at a reduced size."""
+    import copy
+    extras = {}
+
+    def sub(**kw):
+        a = copy.copy(args)
+        for k_, v in kw.items():
+            setattr(a, k_, v)
+        return a
+
+    def note(name, t0):
+        print(f"# extra workload {name}: {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+
+    t0 = time.time()
+    e = bench_conv(sub(steps=10, warmup=3), pd, gen, torch, np, dev)
+    if not args.no_cpu_baseline:
+        layers = gen.config3_vgg_conv()
+        p = gen.init_params(gen.BASE_SEED + 2, "vgg_conv", layers)
+        xs = [gen.normal(gen.BASE_SEED + 2, "cx", (2, 56, 56, 3))]
+        dys = [gen.normal(gen.BASE_SEED + 2, "cdy", (2, 7, 7, 256)) * 0.01]
+        e["cpu_baseline"] = _oracle_steps([layers], [p], xs, None, dys, 1, 3.0, "REDUCED: the same stage on 56 x 56 images, minibatch 2", 2)
+    extras["vgg16_conv"] = e
+    torch.cuda.empty_cache(); note("vgg16_conv", t0)
+
+    t0 = time.time()
+    e = bench_s2vt(sub(steps=8, warmup=2), pd, gen, torch, np, dev)
+    if not args.no_cpu_baseline:
+        sl = gen.config4_s2vt(256, 128, 1000, 8)
+        ps = [gen.init_params(gen.BASE_SEED + 3, f"c{s_}", ly) for s_, ly in enumerate(sl)]
+        xs = [gen.normal(gen.BASE_SEED + 3, "cx", (8, 16, 256))]
+        labs = [gen.labels(gen.BASE_SEED + 3, "cy", (8, 16), 1000)]
+        e["cpu_baseline"] = _oracle_steps(sl, ps, xs, labs, None, 2, 3.0, "REDUCED: LSTM 256->128 | LSTM 128->128 + vocabulary 1000, seq 8, minibatch 16", 16)
+    extras["s2vt"] = e
+    torch.cuda.empty_cache(); note("s2vt", t0)
+
+    t0 = time.time()
+    e = bench_inception(sub(steps=6, warmup=2), pd, gen, torch, np, dev)
+    if not args.no_cpu_baseline:
+        sl, sizes = gen.config5_inception(16, 0.25)
+        ps = [gen.init_params(gen.BASE_SEED + 4, f"c{s_}", ly) for s_, ly in enumerate(sl)]
+        xs = [gen.normal(gen.BASE_SEED + 4, "cx", (1, 299, 299, 3))]
+        labs = [gen.labels(gen.BASE_SEED + 4, "cy", (1,), 16)]
+        e["cpu_baseline"] = _oracle_steps(sl, ps, xs, labs, None, 4, 3.0, "REDUCED: a quarter of the channel counts, 16 classes, minibatch 1, 299 x 299 images", 1)
+    extras["inception"] = e
+    torch.cuda.empty_cache(); note("inception", t0)
+
+    t0 = time.time()
+    e = bench_mlp4(sub(steps=10, warmup=2), pd, gen, torch, np, dev)
+    if not args.no_cpu_baseline:
+        sl = gen.config1_mlp(256, 10, 4)
+        ps = [gen.init_params(gen.BASE_SEED, f"s{s_}", ly) for s_, ly in enumerate(sl)]
+        xs = list(gen.normal(gen.BASE_SEED, "X", (64, 32, 256)))
+        labs = list(gen.labels(gen.BASE_SEED, "Y", (64, 32), 10))
+        import numpy as _np
+        from oracle.pipeline import run_pipeline
+        t1 = time.time()
+        run_pipeline(sl, ps, [x.astype(_np.float64) for x in xs], labs, 4, mode="f32")
+        dt = time.time() - t1
+        e["cpu_baseline"] = {"value": 64 * 32 / dt, "unit": "samples/s", "cores": os.cpu_count() or 1, "kind": "oracle",
+                             "sample": f"the same configuration in full: 64 minibatches of 32 in {dt:.2f} s, fp64 numpy"}
+    extras["mlp4"] = e
+    torch.cuda.empty_cache(); note("mlp4", t0)
+
+    t0 = time.time()
+    e = bench_gemm_sweep(sub(rows=[8192]), pd, gen, torch, np, dev)
+    extras["gemm_sweep_peak_rows"] = e
+    torch.cuda.empty_cache(); note("gemm_sweep", t0)
+    return extras
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--minibatch", type=int, default=64)
     ap.add_argument("--depth", type=int, default=4)
+    ap.add_argument("--repetitions", type=int, default=5, help="default workload: repetitions of --steps steps (median reported)")
+    ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="default workload only: skip the secondary workloads appended under `extra`")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
     ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition", "mlp4", "replicated", "vgg16_pipeline"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
@@ -612,111 +865,24 @@ def main():
     dev = torch.device("cuda:0")
     B, depth, K, W = args.minibatch, args.depth, args.steps, args.warmup
     if args.workload == "vgg16_conv":
-        return bench_conv(args, pd, gen, torch, np, dev)
+        return print(json.dumps(bench_conv(args, pd, gen, torch, np, dev)))
     if args.workload == "s2vt":
-        return bench_s2vt(args, pd, gen, torch, np, dev)
+        return print(json.dumps(bench_s2vt(args, pd, gen, torch, np, dev)))
     if args.workload == "inception":
-        return bench_inception(args, pd, gen, torch, np, dev)
+        return print(json.dumps(bench_inception(args, pd, gen, torch, np, dev)))
     if args.workload == "gemm_sweep":
-        return bench_gemm_sweep(args, pd, gen, torch, np, dev)
+        return print(json.dumps(bench_gemm_sweep(args, pd, gen, torch, np, dev)))
     if args.workload == "partition":
-        return bench_partition(args, pd, gen, torch, np, dev)
+        return print(json.dumps(bench_partition(args, pd, gen, torch, np, dev)))
     if args.workload == "mlp4":
-        return bench_mlp4(args, pd, gen, torch, np, dev)
+        return print(json.dumps(bench_mlp4(args, pd, gen, torch, np, dev)))
     if args.workload == "replicated":
-        return bench_replicated(args, pd, gen, torch, np, dev)
+        return print(json.dumps(bench_replicated(args, pd, gen, torch, np, dev)))
     if args.workload == "vgg16_pipeline":
-        return bench_vgg16_pipeline(args, pd, gen, torch, np, dev)
-    layers = gen.config2_vgg_fc(1024, 512, 104) if args.small else gen.config2_vgg_fc()
-    n_in, classes = layers[0][1], layers[-1][1]
-    seed = gen.BASE_SEED + 1
-    params = gen.init_params(seed, "vgg_fc", layers)
-    P = int(params.size)
-    stream = torch.cuda.Stream(device=dev)
-    cfg = pd.make_config(layers, in_flight_override=depth, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=0.01,
-                         momentum=0.9, stream=stream.cuda_stream)
-    nbytes = pd.pd_stage_query_bytes(cfg)
-    arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
-    h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
-    pd.pd_stage_set_params(h, params)
-    in_ring = pd.pd_stage_depth(h)[1]     # slots of the stage's input ring
-    n_pool = in_ring                      # one synthetic minibatch per slot: slot mb % in_ring always holds pool entry mb % n_pool
-    xs = [gen.normal(seed, f"x{i}", (B, n_in)) for i in range(n_pool)]
-    labs = [gen.labels(seed, f"y{i}", (B,), classes) for i in range(n_pool)]
-    xd = [torch.from_numpy(x).to(dev).to(torch.bfloat16).contiguous() for x in xs]
-    ld = [torch.from_numpy(l).to(dev) for l in labs]
-    dx = torch.empty((B, n_in), dtype=torch.bfloat16, device=dev)
-    loss = torch.zeros(1, dtype=torch.float32, device=dev)
-    torch.cuda.synchronize()
-
-    mb_next = 0
-
-    def fwd(in_place=False):
-        # in_place: the minibatch already lies in the stage's input ring, where an upstream stage (or the data
-        # loader) leaves it; pd_forward then reads it there instead of copying it in first
-        nonlocal mb_next
-        i = mb_next % n_pool
-        x_ptr = pd.pd_stage_input_slot(h, mb_next) if in_place else xd[i].data_ptr()
-        pd.pd_forward(h, mb_next, x_ptr, ld[i].data_ptr(), 0, loss.data_ptr())
-        mb_next += 1
-
-    def step(k, ev=None, in_place=False):
-        pd.pd_backward(h, k, 0, dx.data_ptr())
-        if ev is not None:
-            ev[0].record(stream)
-        pd.pd_update(h)
-        if ev is not None:
-            ev[1].record(stream)
-        fwd(in_place)
-
-    for _ in range(depth):
-        fwd()
-    k = 0
-    for _ in range(max(W, in_ring)):      # (every slot of the input ring has received a minibatch after this)
-        step(k)
-        k += 1
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for j in range(K):
-        step(k, evs[j], in_place=True)
-        k += 1
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / K
-    upd_ms = [a.elapsed_time(b) for a, b in evs]
-    upd_ms_avg = float(np.mean(upd_ms))
-    n_launch = 1  # all Linear layers of the stage are updated by one launch
-    # the pool holds one synthetic minibatch per input-ring slot (4 of them); 60 steps memorise them, so the loss of
-    # the last forward pass is tiny or underflows to 0: it is reported as a sanity value (finite), not as a result
-    final_loss = float(loss.item())
-
-    flops = 6.0 * B * sum(L[1] * L[2] for L in layers if L[0] == "linear")
-    value = B / (ms_per_step * 1e-3)
-    achieved_gbs = UPDATE_BYTES_PER_PARAM * P / (upd_ms_avg * 1e-3) / 1e9
-    out = {
-        "metric": METRIC, "value": value, "unit": "samples/s", "n_gpus": 1, "steps": K, "warmup": W,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": ("REDUCED " if args.small else "") +
-                   f"VGG16-FC-shaped stage: Linear {n_in}-{layers[0][2]}-{layers[1][2]}-{classes} + ReLU + "
-                   f"softmax-xent, bf16 w/ fp32 accum, minibatch {B}, weight-version ring depth {depth}, "
-                   "step = B(k) U(k) F(k+depth), inputs resident in the stage's input ring",
-                   "params": P, "minibatch": B, "ring_depth": depth},
-        "mfma_util_pct": 100.0 * flops / (ms_per_step * 1e-3) / MFMA_BF16_PEAK,
-        "step_gflop": flops / 1e9,
-        "step_hbm_fraction": (20.0 * P / (ms_per_step * 1e-3) / 1e9) / HBM_PEAK_GBS,  # update 16 + forward 2 + input gradient 2
-        "roofline": {"bound": "hbm", "kernel": "wgrad_update_kernel (dW = dZ^T X fused with momentum-SGD into the ring)",
-                     "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved_gbs / HBM_PEAK_GBS,
-                     "traffic": (MEASURED_TRAFFIC_BYTES if (not args.small and B == 64) else None),
-                     "traffic_source": "profiles/wgrad_update_vgg16fc_mb64.txt", "launches_per_step": n_launch,
-                     "avg_launch_ms": upd_ms_avg / n_launch, "bytes_per_launch_avg": UPDATE_BYTES_PER_PARAM * P / n_launch},
-        "final_loss": final_loss,
-    }
-    pd.pd_stage_destroy(h)
-    del arena
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers, params, xs, labs, depth)
+        return print(json.dumps(bench_vgg16_pipeline(args, pd, gen, torch, np, dev)))
+    out = bench_vgg16_fc(args, pd, gen, torch, np, dev)
+    if not args.no_extra and not args.small:
+        out["extra"] = run_extras(args, pd, gen, torch, np, dev)
     print(json.dumps(out))
 
 

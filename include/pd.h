@@ -239,13 +239,6 @@ int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n);
 int pd_stage_set_lr(pd_stage* st, float lr);
 int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n);
 
-/* Overwrites the LATEST version in place: fp32 master <- host_params, its ring slot <- their bf16
- * rounding (bf16 mode), momentum <- host_mom (either may be NULL to leave it).  Version ids, the
- * stash and in-flight minibatches are untouched, so a driver can re-synchronise a running stage
- * with externally computed state (checkpoint restore mid-stream, teacher-forced tests).
- * PD_ESTATE while a gradient is pending (between pd_backward and pd_update). */
-int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const float* host_mom, size_t n);
-
 /* Per-stage checkpoint (Section 4, "Checkpointing": every stage dumps its own parameters when it has done the
  * backward pass -- here: the update -- of an epoch's last minibatch; no coordination between stages).
  * save: writes the LATEST fp32 weights, the momentum and the version id to `path` (host file; synchronises the
@@ -265,7 +258,9 @@ int pd_checkpoint_info(const char* path, size_t* n_params, int32_t* latest, int3
 /* Version bookkeeping: mb_id = -1 -> latest version; otherwise the version stashed for that
  * in-flight minibatch (PD_ESTATE if it is not in flight). */
 int pd_stage_version(const pd_stage* st, int32_t mb_id, int32_t* version);
-/* The ops executed so far, in order (same encoding as pd_schedule_1f1b). */
+/* The ops executed so far, in order (same encoding as pd_schedule_1f1b).  The stage keeps the most recent 65536
+ * ops (pd_stage_set_trace_limit in pd_debug.h changes that or switches the record off); older ones are dropped,
+ * so a long-running stage holds a bounded record. */
 int pd_stage_trace(const pd_stage* st, pd_op* out, size_t cap, size_t* n_out);
 
 /* Device address of the stage's own input slot for minibatch mb_id ([minibatch][in_features],
@@ -277,23 +272,6 @@ int pd_stage_input_slot(pd_stage* st, int32_t mb_id, void** dev_ptr);
 /* Device address of the buffer that receives dL/d(output) for the backward pass of mb_id
  * ([minibatch][out_features]); two slots, slot = mb_id mod 2. */
 int pd_stage_grad_slot(pd_stage* st, int32_t mb_id, void** dev_ptr);
-
-/* Test/debug aid: copies one of the stage's intermediate tensors to the host as fp32
- * (synchronises the stream).  what = 0: stored output of compute layer number `layer` (0-based, the
- * loss not counted; inside a block of branches the branch layers count in description order and
- * PD_CONCAT_END counts as one more layer whose output is the concatenation; the markers PD_CONCAT_BEGIN
- * and PD_BRANCH do not count) for in-flight minibatch mb_id, [minibatch][out]; 1: the stage's input
- * slot for mb_id, [minibatch][in]; 2: the output-gradient slot for mb_id, [minibatch][out_last];
- * 3: dL/d(pre-activation) of layer `layer` left by the last pd_backward, [minibatch][out] (Linear layers
- * only: convolution and pooling layers do not keep theirs);
- * 4: the stashed dL/dlogits of in-flight minibatch mb_id (loss stages).  n must equal the tensor's
- * element count.  No state check is made on mb_id beyond >= 0: the caller reads what the slot holds. */
-int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, float* host_out, size_t n);
-/* Test/debug aid, the reverse direction: overwrites a stored tensor of in-flight minibatch mb_id with host values
- * (fp32, rounded to bfloat16 where the tensor is bfloat16; synchronises the stream).  what = 0: the stored output
- * of compute layer `layer` (not an LSTM); 1: the stage's input slot.  Lets a test drive the backward pass of a deep
- * stage on exactly the activations (and therefore the ReLU and max-pooling decisions) of a reference run. */
-int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, const float* host_in, size_t n);
 
 /* --- the step (Sections 3.3, 3.4, 4) -------------------------------------------------------
  * pd_forward: F for minibatch mb_id.  Reads the LATEST weight version and records it in the
@@ -407,14 +385,20 @@ int pd_partition(int32_t n_layers, int32_t n_machines, const double* t_layer, co
  * disables split-K.
  * stream: hipStream_t.  All pointers device. */
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K);
-/* Tuning knob (process-wide, not thread-safe): forward and dgrad products whose output has at least `min_tiles`
- * tiles of 256 x 256 run on the compute-bound large-tile kernels, smaller ones on the split-K kernels built for
- * minibatch-sized row counts.  Default 128.  The same knob (times two) decides from how many 256 x 256 output tiles
- * a convolution with >= 256 output channels uses its wide-tile kernel.  Returns the previous value; min_tiles < 1 only queries.  Set it
- * before pd_gemm_workspace_bytes / pd_stage_query_bytes: the workspace size depends on it. */
-int pd_set_big_tile_threshold(int32_t min_tiles);
 int pd_linear_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, int32_t M, int32_t N,
                        int32_t K, int32_t relu, void* workspace_dev, size_t workspace_bytes);
+/* pd_linear_fwd_bf16 for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same product, same kernels, same result as
+ * pd_linear_fwd_bf16 given a workspace of 32 * M * N * 4 bytes; the split-K partial sums go into a device array that
+ * is part of the library image (pd_linear_fwd_bf16_static_max_bytes() = 32 MiB on every GPU the process uses, held
+ * until the process ends).  Allocates nothing, frees nothing, synchronises nothing; x, w, b, y are the caller's.
+ * Runs on the CURRENT device, which must be the stream's.  PD_ENOMEM if 32 * M * N * 4 exceeds the array (M * N >
+ * 262144, e.g. more than 64 rows at 4096 features): use pd_linear_fwd_bf16 there.  All calls on one GPU share the
+ * array, which keeps the previous call's contents (no call depends on them): calls on different streams of one GPU
+ * must not overlap in time, calls on one stream are ordered and safe. */
+size_t pd_linear_fwd_bf16_static_max_bytes(void);
+int pd_linear_fwd_bf16_static(void* stream, const void* x, const void* w, const void* b, void* y, int32_t M, int32_t N,
+                              int32_t K, int32_t relu);
 int pd_linear_dgrad_bf16(void* stream, const void* dz, const void* w, const void* mask, void* dx, int32_t M,
                          int32_t N, int32_t K, void* workspace_dev, size_t workspace_bytes);
 int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, float* master_w, float* mom_w,

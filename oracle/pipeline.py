@@ -290,7 +290,8 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                  mode: str = "f32", lr: float = 0.01, momentum: float = 0.9,
                  stashing: bool = True, depth_override: int = 0, keep_log: bool = False,
                  out_grads=None, order: Optional[list] = None, input_grad: bool = False,
-                 vertical_sync: bool = False, optimizer: str = "sgd", eps: float = 1.0):
+                 vertical_sync: bool = False, optimizer: str = "sgd", eps: float = 1.0,
+                 stages: Optional[list] = None):
     """All stages, each following its own static op list, run as soon as their data exists.
 
     inputs[i] / labels[i] belong to minibatch i.  Returns (stages, losses).  Any
@@ -303,12 +304,17 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
     ``input_grad``: also form dL/d(input) of stage 0 (only visible through the log).
     ``vertical_sync`` (Section 3.4): the version the input stage's forward read travels with the
     minibatch, and every later stage uses that version of its own weights instead of its latest.
+    ``stages``: drained Stage objects of an earlier call to continue with (weights, momentum and version
+    counters carry over; ``stage_params`` is then ignored and minibatch ids are relative to this call).
     """
     S, M = len(stage_layers), len(inputs)
     depths = [depth_override or in_flight_depth(S, noam_, s) for s in range(S)]
-    stages = [Stage(stage_layers[s], stage_params[s], depths[s], mode, lr, momentum, stashing,
-                    ring_depth=depths[0] if vertical_sync else 0, optimizer=optimizer, eps=eps)
-              for s in range(S)]
+    if stages is None:
+        stages = [Stage(stage_layers[s], stage_params[s], depths[s], mode, lr, momentum, stashing,
+                        ring_depth=depths[0] if vertical_sync else 0, optimizer=optimizer, eps=eps)
+                  for s in range(S)]
+    assert all(not st.stash and st.grad is None for st in stages), "continue only from a drained pipeline"
+    base = [st.latest for st in stages]   # versions in the static lists count from the start of this call
     if keep_log:
         for st in stages:
             st.log = {}
@@ -330,9 +336,9 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                         break
                     x = inputs[op.mb] if s == 0 else act.pop((op.mb, s - 1))
                     y, loss = st.forward(op.mb, x, labels[op.mb] if (s == S - 1 and labels is not None) else None,
-                                         version=tag[op.mb] if (vertical_sync and s > 0) else None)
+                                         version=tag[op.mb] + base[s] if (vertical_sync and s > 0) else None)
                     if s == 0:
-                        tag[op.mb] = st.trace[-1].version
+                        tag[op.mb] = st.trace[-1].version - base[0]
                     if s == S - 1:
                         losses[op.mb] = loss
                     else:
@@ -351,7 +357,8 @@ def run_pipeline(stage_layers: Sequence, stage_params: Sequence, inputs, labels,
                     st.update(op.mb)
                 # the stage really did what its static list said, version included
                 # (with stashing off, B deliberately reads another version than listed)
-                assert st.trace[-1] == op or (not stashing and op.kind == OP_B), (st.trace[-1], op)
+                want = Op(op.kind, op.mb, op.version + base[s], (op.version + base[s]) % st.ring)
+                assert st.trace[-1] == want or (not stashing and op.kind == OP_B), (st.trace[-1], want)
                 if order is not None:
                     order.append((s, op))
                 pos[s] += 1

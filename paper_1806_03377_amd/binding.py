@@ -1,4 +1,4 @@
-"""ctypes binding of libpd.so: same names as include/pd.h, argument marshalling only.
+"""ctypes binding of libpd.so: same names as include/pd.h and include/pd_debug.h, argument marshalling only.
 
 Device pointers are passed as integers (``tensor.data_ptr()``), streams as
 ``torch.cuda.Stream.cuda_stream``.  Every call raises ``PdError`` on a non-zero status.
@@ -85,6 +85,7 @@ _SIGS = {
     "pd_stage_overwrite_latest": [_vp, _vp, _vp, _sz],
     "pd_stage_version": [_vp, _i32, C.POINTER(_i32)],
     "pd_stage_trace": [_vp, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
+    "pd_stage_set_trace_limit": [_vp, _sz],
     "pd_stage_input_slot": [_vp, _i32, C.POINTER(_vp)],
     "pd_stage_grad_slot": [_vp, _i32, C.POINTER(_vp)],
     "pd_stage_debug_read": [_vp, _i32, _i32, _i32, _vp, _sz],
@@ -102,6 +103,7 @@ _SIGS = {
     "pd_partition": [_i32, _i32, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_double,
                      C.POINTER(C.c_double), C.POINTER(pd_stage_assign), _sz, C.POINTER(_sz), C.POINTER(_i32)],
     "pd_linear_fwd_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _sz],
+    "pd_linear_fwd_bf16_static": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32],
     "pd_linear_dgrad_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _vp, _sz],
     "pd_linear_wgrad_update_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _f32, _f32],
     "pd_conv_wgrad_splits": [C.POINTER(_i32), C.POINTER(_i32)],
@@ -121,10 +123,13 @@ _lib.pd_last_error.restype = C.c_char_p
 _lib.pd_last_error.argtypes = []
 _lib.pd_gemm_workspace_bytes.restype = _sz
 _lib.pd_gemm_workspace_bytes.argtypes = [_i32, _i32, _i32]
+_lib.pd_linear_fwd_bf16_static_max_bytes.restype = _sz
+_lib.pd_linear_fwd_bf16_static_max_bytes.argtypes = []
 _lib.pd_set_big_tile_threshold.restype = C.c_int
 _lib.pd_set_big_tile_threshold.argtypes = [_i32]
 
-EXPORTED = sorted(list(_SIGS) + ["pd_last_error", "pd_gemm_workspace_bytes", "pd_set_big_tile_threshold"])
+EXPORTED = sorted(list(_SIGS) + ["pd_last_error", "pd_gemm_workspace_bytes", "pd_set_big_tile_threshold",
+                                 "pd_linear_fwd_bf16_static_max_bytes"])
 
 
 def pd_last_error() -> str:
@@ -334,6 +339,10 @@ def pd_stage_version(stage: int, mb_id: int = -1) -> int:
     return v.value
 
 
+def pd_stage_set_trace_limit(stage: int, max_ops: int):
+    _check(_lib.pd_stage_set_trace_limit(stage, max_ops))
+
+
 def pd_stage_trace(stage: int):
     n = _sz(0)
     rc = _lib.pd_stage_trace(stage, None, 0, C.byref(n))
@@ -459,6 +468,14 @@ def pd_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
 
 def pd_linear_fwd_bf16(stream, x, w, b, y, M, N, K, relu, ws=0, ws_bytes=0):
     _check(_lib.pd_linear_fwd_bf16(stream, x, w, b or None, y, M, N, K, int(relu), ws or None, ws_bytes))
+
+
+def pd_linear_fwd_bf16_static_max_bytes() -> int:
+    return int(_lib.pd_linear_fwd_bf16_static_max_bytes())
+
+
+def pd_linear_fwd_bf16_static(stream, x, w, b, y, M, N, K, relu):
+    _check(_lib.pd_linear_fwd_bf16_static(stream, x, w, b or None, y, M, N, K, int(relu)))
 
 
 def pd_linear_dgrad_bf16(stream, dz, w, mask, dx, M, N, K, ws=0, ws_bytes=0):

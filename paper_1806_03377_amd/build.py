@@ -51,5 +51,39 @@ def build(verbose: bool = True) -> str:
     return LIB
 
 
+def build_host_sanitized(verbose: bool = False) -> str:
+    """The host side of the runtime (pd_runtime.cpp, pd_partition.cpp) compiled with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the host pass only, linked with the ordinary kernel objects and the host-only driver
+    tests/host/sanitize_main.cpp into _build/host_sanitize.  The driver calls nothing that touches a GPU."""
+    build_dir = os.path.join(HERE, "_build")
+    if not all(os.path.exists(os.path.join(build_dir, os.path.basename(s) + ".o")) for s in sources()):
+        build(verbose)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    flags = [f for f in FLAGS if f not in ("-shared", "-O3")] + ["-O1"] + san
+    main_src = os.path.join(os.path.dirname(HERE), "tests", "host", "sanitize_main.cpp")
+    objs, procs = [], []
+    for src in sources():
+        base = os.path.basename(src)
+        if src.endswith(".cpp"):
+            obj = os.path.join(build_dir, base + ".san.o")
+            procs.append((src, subprocess.Popen([HIPCC, "-x", "hip", "-c", src, "-o", obj] + flags,
+                                                stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        else:
+            obj = os.path.join(build_dir, base + ".o")
+        objs.append(obj)
+    main_obj = os.path.join(build_dir, "sanitize_main.san.o")
+    procs.append((main_src, subprocess.Popen([HIPCC, "-x", "hip", "-c", main_src, "-o", main_obj] + flags,
+                                             stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    for src, p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc failed on {src}:\n{out}")
+    exe = os.path.join(build_dir, "host_sanitize")
+    subprocess.run([HIPCC, "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-o", exe, main_obj] + objs,
+                   check=True)
+    return exe
+
+
 if __name__ == "__main__":
     build()

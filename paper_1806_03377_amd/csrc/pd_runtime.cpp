@@ -17,6 +17,7 @@
 #include <vector>
 
 #include "../../include/pd.h"
+#include "../../include/pd_debug.h"
 #include "pd_error.h"
 #include "pd_kernels.h"
 
@@ -203,8 +204,16 @@ struct pd_stage {
   std::deque<InFlight> in_flight;
   bool grad_pending = false;
   int pending_mb = -1;
-  std::vector<pd_op> trace;
-  // events of pd_pipeline_run (grown on demand, reused)
+  // the most recent trace_cap executed ops (bounded: a stage may run for the whole of training)
+  std::deque<pd_op> trace;
+  size_t trace_cap = 65536;
+  void log_op(int kind, int mb, int version) {
+    if (!trace_cap) return;
+    if (trace.size() >= trace_cap) trace.pop_front();
+    trace.push_back({kind, mb, version, version % ring_depth});
+  }
+  // events of the pipeline drivers: rings indexed by minibatch (or round) modulo their length, which depends on
+  // the in-flight depths only, never on the length of the stream; created on first use, reused by later calls
   std::vector<hipEvent_t> ev_f, ev_b, ev_u;
   // layer profiler (Section 3.2): while `profiling`, every op drops an event after each layer's kernels; the time
   // between two consecutive marks belongs to the layer named by the later one (the stream runs kernels in order)
@@ -1019,8 +1028,15 @@ int pd_stage_trace(const pd_stage* st, pd_op* out, size_t cap, size_t* n_out) {
   if (st->trace.size() > cap) return fail(PD_ENOMEM, "trace has %zu entries, capacity %zu", st->trace.size(), cap);
   if (!st->trace.empty()) {
     if (!out) return fail(PD_EINVAL, "out is null");
-    memcpy(out, st->trace.data(), st->trace.size() * sizeof(pd_op));
+    std::copy(st->trace.begin(), st->trace.end(), out);
   }
+  return PD_OK;
+}
+
+int pd_stage_set_trace_limit(pd_stage* st, size_t max_ops) {
+  if (check_stage(st)) return PD_EINVAL;
+  st->trace_cap = max_ops;
+  while (st->trace.size() > max_ops) st->trace.pop_front();
   return PD_OK;
 }
 
@@ -1141,6 +1157,14 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
   if (st->last_fwd >= 0 && mb_id != st->last_fwd + 1)
     return fail(PD_ESTATE, "forward of minibatch %d after %d: ids must be consecutive", mb_id, st->last_fwd);
 
+  // slot safety (Section 4, intermediate state): what this forward pass writes must not belong to a minibatch in flight
+  for (const InFlight& f : st->in_flight) {
+    if (f.mb % st->depth == mb_id % st->depth)
+      return fail(PD_ESTATE, "stash slot %d of minibatch %d is still held by minibatch %d", mb_id % st->depth, mb_id, f.mb);
+    if (f.mb % st->in_depth == mb_id % st->in_depth)
+      return fail(PD_ESTATE, "input slot %d of minibatch %d is still held by minibatch %d", mb_id % st->in_depth, mb_id, f.mb);
+  }
+
   hipStream_t s = st->stream;
   // forward reads the latest version (or, under vertical sync, the one the minibatch carries) and stashes its id
   const int v = version >= 0 ? version : st->latest;
@@ -1230,7 +1254,7 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
   if (st->profiling) ++st->prof_ops[0];
   st->in_flight.push_back({mb_id, v});
   st->last_fwd = mb_id;
-  st->trace.push_back({PD_OP_F, mb_id, v, v % st->ring_depth});
+  st->log_op(PD_OP_F, mb_id, v);
   return PD_OK;
 }
 
@@ -1402,7 +1426,7 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
   st->grad_pending = true;
   st->pending_mb = mb_id;
-  st->trace.push_back({PD_OP_B, mb_id, v, v % st->ring_depth});
+  st->log_op(PD_OP_B, mb_id, v);
   return PD_OK;
 }
 
@@ -1513,6 +1537,18 @@ int run_update_kernels(pd_stage* st, int nv, bool grad_only) {
   return PD_OK;
 }
 
+// Slot safety of the version ring (Section 3.4: a minibatch's backward pass reads the weights its forward pass read):
+// version nv goes into the slot that held version nv - ring_depth, so no minibatch in flight may still refer to that
+// version or an older one.  The 1F1B order guarantees it; a caller that asked pd_forward_versioned for the oldest
+// version held and then lets further updates pass does not.
+int ring_slot_is_free(const pd_stage* st, int nv) {
+  for (const InFlight& f : st->in_flight)
+    if (f.version <= nv - st->ring_depth)
+      return fail(PD_ESTATE, "the update to version %d would overwrite ring slot %d, which holds version %d, read by the "
+                  "forward pass of in-flight minibatch %d", nv, nv % st->ring_depth, f.version, f.mb);
+  return PD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1522,11 +1558,12 @@ int pd_update(pd_stage* st) {
   if (st->n_replicas > 1) return fail(PD_ESTATE, "replicated stage: its replicas are updated together by pd_update_replicated");
   if (!st->grad_pending) return fail(PD_ESTATE, "no pending gradient");
   const int nv = st->latest + 1;
+  if (ring_slot_is_free(st, nv)) return PD_ESTATE;
   const int rc = run_update_kernels(st, nv, false);
   if (rc != PD_OK) return rc;
   st->latest = nv;
   st->grad_pending = false;
-  st->trace.push_back({PD_OP_U, st->pending_mb, nv, nv % st->ring_depth});
+  st->log_op(PD_OP_U, st->pending_mb, nv);
   return PD_OK;
 }
 
@@ -1552,6 +1589,8 @@ int pd_update_replicated(pd_stage* const* replicas, int32_t n_replicas) {
   }
   if (!grads.count) return fail(PD_ESTATE, "no pending gradient on any replica");
   const int nv = p0->latest + 1;
+  for (int q = 0; q < n_replicas; ++q)
+    if (ring_slot_is_free(replicas[q], nv)) return PD_ESTATE;
   for (int q = 0; q < n_replicas; ++q) {
     pd_stage* r = replicas[q];
     if (r->grad_pending) {
@@ -1575,7 +1614,7 @@ int pd_update_replicated(pd_stage* const* replicas, int32_t n_replicas) {
     pd_stage* r = replicas[q];
     if (q > 0 && r->stream != p0->stream) PD_HIP(hipStreamWaitEvent(r->stream, p0->ev_rep, 0));
     r->latest = nv;
-    if (r->grad_pending) r->trace.push_back({PD_OP_U, r->pending_mb, nv, nv % r->ring_depth});
+    if (r->grad_pending) r->log_op(PD_OP_U, r->pending_mb, nv);
     r->grad_pending = false;
   }
   return PD_OK;
@@ -1657,6 +1696,39 @@ int pd_stage_profile_read(pd_stage* st, pd_layer_profile* out, size_t cap, size_
   return PD_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// The pipeline drivers join several streams by events; under stream capture that pulls every stage's stream into the
+// capture (a wait on an event recorded in a capturing stream forks the waiting stream into it) and nothing joins them
+// back to the stream the capture began on, which the capture rules forbid: the capture cannot be ended.  So the
+// drivers refuse to run while any of their streams is being captured.
+int refuse_capture(pd_stage* const* stages, int n) {
+  for (int k = 0; k < n; ++k) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    PD_HIP(hipStreamIsCapturing(stages[k]->stream, &cs));
+    if (cs != hipStreamCaptureStatusNone)
+      return fail(PD_ESTATE, "the stream of stage object %d is being captured: the pipeline drivers join several streams "
+                  "by events and cannot be recorded into a graph (capture pd_forward / pd_backward / pd_update of one "
+                  "stage instead)", k);
+  }
+  return PD_OK;
+}
+
+int grow_events(std::vector<hipEvent_t>& v, int n) {
+  while ((int)v.size() < n) {
+    hipEvent_t e;
+    PD_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    v.push_back(e);
+  }
+  return PD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_minibatches, const void* inputs_dev,
                     const int32_t* labels_dev, float* losses_dev) {
   if (!stages || num_stages < 1) return fail(PD_EINVAL, "no stages");
@@ -1679,67 +1751,84 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
     if (st->vsync && st->latest != stages[0]->latest)
       return fail(PD_ESTATE, "vertical sync: stage %d is at version %d, the input stage at %d", s, st->latest, stages[0]->latest);
   }
+  if (refuse_capture(stages, S)) return PD_ESTATE;
   const bool vsync = stages[0]->vsync;
-  std::vector<int> tag(num_minibatches, -1);  // vertical sync: the version the input stage's forward read
   const int base = stages[0]->last_fwd + 1;
+  // Event rings.  Minibatch i of stage s uses ev_f / ev_b / ev_u [i mod R].  R need not grow with the stream: a record
+  // of entry i + R is only ever enqueued after every wait on entry i (ev_f[s][i]: F(i, s+1), which the record of
+  // F(i + R, s) follows through the update that frees the consumer's input slot, R >= its input-ring depth;
+  // ev_b[s][i]: B(i, s-1) and B(i + 2, s+1), R >= 2; ev_u[s][i]: F(i + input-ring depth of s, s-1)).  The checks
+  // before each record below assert exactly that, with integers.
+  int R = 2;
+  for (int s = 0; s < S; ++s) R = std::max(R, stages[s]->in_depth);
+  R += 1;
   std::vector<std::vector<pd_op>> ops(S);
   for (int s = 0; s < S; ++s) {
     build_schedule(stages[s]->depth, M, ops[s]);
     for (auto* v : {&stages[s]->ev_f, &stages[s]->ev_b, &stages[s]->ev_u})
-      while ((int)v->size() < M) {
-        hipEvent_t e;
-        PD_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        v->push_back(e);
-      }
+      if (grow_events(*v, R)) return PD_EHIP;
   }
-  // f_rec[s][i] etc: the event has been recorded (in host order) -- an op is only enqueued after every
-  // event it waits for has been recorded, which makes the host's enqueue order a valid global order.
-  std::vector<std::vector<char>> f_rec(S, std::vector<char>(M, 0)), b_rec = f_rec, u_rec = f_rec;
+  // nF[s], nB[s], nU[s]: forwards, backwards, updates of stage s enqueued so far.  A stage's ops are enqueued in its
+  // list order, so "the event of op X(i, s) has been recorded" is i < nX[s].  An op is only enqueued after every event
+  // it waits for has been recorded, which makes the host's enqueue order a valid global order.
+  std::vector<int> nF(S, 0), nB(S, 0), nU(S, 0);
+  std::vector<int> tag(R + 1, -1);  // vertical sync: the version the input stage's forward read, by minibatch mod (R + 1)
   std::vector<size_t> pos(S, 0);
   const size_t in_elems = (size_t)stages[0]->lin.front().rows * stages[0]->lin.front().in * stages[0]->esz;
   size_t remaining = 0;
   for (int s = 0; s < S; ++s) remaining += ops[s].size();
+  auto ring_bug = [&](const char* what, int s, int i) {
+    return fail(PD_ESTATE, "internal: event ring of %d entries too short for %s of minibatch %d on stage %d", R, what, i, s);
+  };
   while (remaining) {
     bool progressed = false;
     for (int s = 0; s < S; ++s) {
       pd_stage* st = stages[s];
       while (pos[s] < ops[s].size()) {
         const pd_op op = ops[s][pos[s]];
-        const int i = op.mb_id, mb = base + i;
+        const int i = op.mb_id, mb = base + i, e = i % R;
         if (op.kind == PD_OP_F) {
           int reuse = -1;
-          if (s > 0 && !f_rec[s - 1][i]) break;
+          if (s > 0 && i >= nF[s - 1]) break;
           if (s < S - 1) {
             reuse = i - stages[s + 1]->in_depth;  // last minibatch that used the slot this forward writes into
-            if (reuse >= 0 && !u_rec[s + 1][reuse]) break;
+            if (reuse >= 0 && reuse >= nU[s + 1]) break;
           }
-          if (s > 0) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_f[i], 0));
-          if (reuse >= 0) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_u[reuse], 0));
+          if (s > 0) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_f[e], 0));
+          if (reuse >= 0) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_u[reuse % R], 0));
           const void* x = s == 0 ? static_cast<const char*>(inputs_dev) + (size_t)i * in_elems : st->in_slot(mb);
           void* y = s < S - 1 ? stages[s + 1]->in_slot(mb) : nullptr;
           const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->lin.back().rows : nullptr;
           float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
-          if (vsync && s == 0) tag[i] = st->latest;
-          const int rc = pd_forward_versioned(st, mb, vsync ? tag[i] : -1, x, lab, y, loss);
+          if (vsync && s == 0) tag[i % (R + 1)] = st->latest;
+          const int rc = pd_forward_versioned(st, mb, vsync ? tag[i % (R + 1)] : -1, x, lab, y, loss);
           if (rc != PD_OK) return rc;
-          if (s < S - 1) PD_HIP(hipEventRecord(st->ev_f[i], st->stream));  // (only the next stage waits for it)
-          f_rec[s][i] = 1;
+          if (s < S - 1) {  // (only the next stage waits for it)
+            if (i >= R && nF[s + 1] <= i - R) return ring_bug("the forward pass", s, i);
+            PD_HIP(hipEventRecord(st->ev_f[e], st->stream));
+          }
+          ++nF[s];
         } else if (op.kind == PD_OP_B) {
-          if (s < S - 1 && !b_rec[s + 1][i]) break;
-          if (s > 0 && i >= 2 && !b_rec[s - 1][i - 2]) break;  // the gradient slot this backward writes into
-          if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_b[i], 0));
-          if (s > 0 && i >= 2) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_b[i - 2], 0));
+          if (s < S - 1 && i >= nB[s + 1]) break;
+          if (s > 0 && i >= 2 && i - 2 >= nB[s - 1]) break;  // the gradient slot this backward writes into
+          if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_b[e], 0));
+          if (s > 0 && i >= 2) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_b[(i - 2) % R], 0));
           const void* dy = s < S - 1 ? st->grad_slot(mb) : nullptr;
           void* dx = s > 0 ? stages[s - 1]->grad_slot(mb) : nullptr;
           const int rc = pd_backward(st, mb, dy, dx);
           if (rc != PD_OK) return rc;
-          PD_HIP(hipEventRecord(st->ev_b[i], st->stream));
-          b_rec[s][i] = 1;
+          if (i >= R && ((s > 0 && nB[s - 1] <= i - R) || (s < S - 1 && nB[s + 1] <= i - R + 2)))
+            return ring_bug("the backward pass", s, i);
+          PD_HIP(hipEventRecord(st->ev_b[e], st->stream));
+          ++nB[s];
         } else {
           const int rc = pd_update(st);
           if (rc != PD_OK) return rc;
-          if (s > 0) PD_HIP(hipEventRecord(st->ev_u[i], st->stream));  // (only the stage before waits for it: slot reuse)
-          u_rec[s][i] = 1;
+          if (s > 0) {  // (only the stage before waits for it: slot reuse)
+            if (i >= R && nF[s - 1] <= i - R + st->in_depth) return ring_bug("the update", s, i);
+            PD_HIP(hipEventRecord(st->ev_u[e], st->stream));
+          }
+          ++nU[s];
         }
         ++pos[s];
         --remaining;
@@ -1792,30 +1881,47 @@ int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replica
       return fail(PD_EINVAL, "stage %d input shape mismatch", s);
     if (p0->has_loss != (s == S - 1)) return fail(PD_EINVAL, "only the last stage may (and must) end in the loss");
   }
-  // op lists and events per replica (ev_f / ev_b by round; ev_u of the primary by round = the joint update)
+  {
+    std::vector<pd_stage*> all;
+    for (int s = 0; s < S; ++s)
+      for (int q = 0; q < r[s]; ++q) all.push_back(rep(s, q));
+    if (refuse_capture(all.data(), (int)all.size())) return PD_ESTATE;
+  }
+  // Event rings, as in pd_pipeline_run: ev_f / ev_b of a replica by its round modulo R, ev_u of a stage's primary by
+  // round modulo R (the joint update).  Between neighbouring stages with different replica counts one round of the
+  // one spans up to `ratio` rounds of the other, and a replica only knows about another replica's progress through the
+  // joint updates, `depth` rounds back; R covers both, and the checks before each record assert with integers that
+  // every wait on the entry's previous occupant has been enqueued.
+  int D = 2, ratio = 1;
+  for (int s = 0; s < S; ++s) {
+    D = std::max(D, rep(s, 0)->in_depth);
+    if (s > 0) ratio = std::max(ratio, std::max((r[s] + r[s - 1] - 1) / r[s - 1], (r[s - 1] + r[s] - 1) / r[s]));
+  }
+  const int R = (2 * D + 6) * ratio;
+  // op lists per replica; nF / nB: rounds whose F / B each replica has enqueued; nU: rounds whose joint update a stage
+  // has enqueued.  A replica's ops are enqueued in its list order, so "the event of F(k) has been recorded" is k < nF.
   std::vector<std::vector<std::vector<pd_op>>> ops(S);
   std::vector<std::vector<size_t>> pos(S);
-  std::vector<std::vector<std::vector<char>>> f_rec(S), b_rec(S);
-  std::vector<std::vector<char>> u_rec(S);
+  std::vector<std::vector<int>> nF(S), nB(S);
+  std::vector<int> nU(S, 0);
   size_t remaining = 0;
   for (int s = 0; s < S; ++s) {
-    ops[s].resize(r[s]); pos[s].assign(r[s], 0); f_rec[s].resize(r[s]); b_rec[s].resize(r[s]);
-    u_rec[s].assign(rounds(s, 0), 0);
+    ops[s].resize(r[s]); pos[s].assign(r[s], 0); nF[s].assign(r[s], 0); nB[s].assign(r[s], 0);
     for (int q = 0; q < r[s]; ++q) {
       pd_stage* st = rep(s, q);
-      const int n = rounds(s, q);
-      build_schedule(st->depth, n, ops[s][q]);
+      build_schedule(st->depth, rounds(s, q), ops[s][q]);
       remaining += ops[s][q].size();
-      f_rec[s][q].assign(n, 0); b_rec[s][q].assign(n, 0);
       for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u})
-        while ((int)v->size() < n) {
-          hipEvent_t e;
-          PD_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-          v->push_back(e);
-        }
+        if (grow_events(*v, R)) return PD_EHIP;
     }
   }
   const size_t in_elems = (size_t)replicas[0]->lin.front().rows * replicas[0]->lin.front().in * replicas[0]->esz;
+  auto ring_bug = [&](const char* what, int s, int q, int k) {
+    return fail(PD_ESTATE, "internal: event ring of %d entries too short for %s of round %d on stage %d replica %d", R, what, k, s, q);
+  };
+  // has stage t enqueued the forward (backward) pass of minibatch j?
+  auto fwd_done = [&](int t, int j) { return nF[t][j % r[t]] > j / r[t]; };
+  auto bwd_done = [&](int t, int j) { return nB[t][j % r[t]] > j / r[t]; };
   // An op is enqueued only after every event it waits for has been recorded (in host order), which makes the host's
   // enqueue order a valid global order.
   while (remaining) {
@@ -1831,32 +1937,39 @@ int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replica
           const int qn = s < S - 1 ? i % r[s + 1] : 0, kn = s < S - 1 ? i / r[s + 1] : 0;
           if (op.kind == PD_OP_F) {
             int reuse = -1;  // the round whose input last occupied the slot this forward's output goes into
-            if (s > 0 && !f_rec[s - 1][qp][kp]) break;
+            if (s > 0 && !fwd_done(s - 1, i)) break;
             if (s < S - 1) {
               reuse = kn - rep(s + 1, qn)->in_depth;
-              if (reuse >= 0 && !u_rec[s + 1][reuse]) break;  // its last reader is that round's update
+              if (reuse >= 0 && reuse >= nU[s + 1]) break;  // its last reader is that round's update
             }
-            if (s > 0) PD_HIP(hipStreamWaitEvent(st->stream, rep(s - 1, qp)->ev_f[kp], 0));
-            if (reuse >= 0) PD_HIP(hipStreamWaitEvent(st->stream, rep(s + 1, 0)->ev_u[reuse], 0));
+            if (s > 0) PD_HIP(hipStreamWaitEvent(st->stream, rep(s - 1, qp)->ev_f[kp % R], 0));
+            if (reuse >= 0) PD_HIP(hipStreamWaitEvent(st->stream, rep(s + 1, 0)->ev_u[reuse % R], 0));
             const void* x = s == 0 ? static_cast<const char*>(inputs_dev) + (size_t)i * in_elems : st->in_slot(k);
             void* y = s < S - 1 ? rep(s + 1, qn)->in_slot(kn) : nullptr;
             const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->lin.back().rows : nullptr;
             float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
             const int rc = pd_forward(st, k, x, lab, y, loss);
             if (rc != PD_OK) return rc;
-            if (s < S - 1) PD_HIP(hipEventRecord(st->ev_f[k], st->stream));  // (only the next stage waits for it)
-            f_rec[s][q][k] = 1;
+            if (s < S - 1) {  // (only the next stage waits for it)
+              if (k >= R && !fwd_done(s + 1, (k - R) * r[s] + q)) return ring_bug("the forward pass", s, q, k);
+              PD_HIP(hipEventRecord(st->ev_f[k % R], st->stream));
+            }
+            ++nF[s][q];
           } else if (op.kind == PD_OP_B) {
-            if (s < S - 1 && !b_rec[s + 1][qn][kn]) break;
-            if (s > 0 && kp >= 2 && !b_rec[s - 1][qp][kp - 2]) break;  // the gradient slot this backward writes into
-            if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, rep(s + 1, qn)->ev_b[kn], 0));
-            if (s > 0 && kp >= 2) PD_HIP(hipStreamWaitEvent(st->stream, rep(s - 1, qp)->ev_b[kp - 2], 0));
+            if (s < S - 1 && !bwd_done(s + 1, i)) break;
+            if (s > 0 && kp >= 2 && kp - 2 >= nB[s - 1][qp]) break;  // the gradient slot this backward writes into
+            if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, rep(s + 1, qn)->ev_b[kn % R], 0));
+            if (s > 0 && kp >= 2) PD_HIP(hipStreamWaitEvent(st->stream, rep(s - 1, qp)->ev_b[(kp - 2) % R], 0));
             const void* dy = s < S - 1 ? st->grad_slot(k) : nullptr;
             void* dx = s > 0 ? rep(s - 1, qp)->grad_slot(kp) : nullptr;
             const int rc = pd_backward(st, k, dy, dx);
             if (rc != PD_OK) return rc;
-            PD_HIP(hipEventRecord(st->ev_b[k], st->stream));
-            b_rec[s][q][k] = 1;
+            if (k >= R) {  // the entry's previous occupant, round k - R: its two waiters
+              const int j = (k - R) * r[s] + q, j2 = (k - R + 2) * r[s] + q;
+              if ((s > 0 && !bwd_done(s - 1, j)) || (s < S - 1 && !bwd_done(s + 1, j2))) return ring_bug("the backward pass", s, q, k);
+            }
+            PD_HIP(hipEventRecord(st->ev_b[k % R], st->stream));
+            ++nB[s][q];
           } else {
             // joint update of round k: every replica with a minibatch in it must have reached it
             bool ready = true;
@@ -1868,8 +1981,15 @@ int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replica
             if (!ready) break;
             const int rc = r[s] > 1 ? pd_update_replicated(replicas + first[s], r[s]) : pd_update(st);
             if (rc != PD_OK) return rc;
-            if (s > 0) PD_HIP(hipEventRecord(rep(s, 0)->ev_u[k], rep(s, 0)->stream));  // (only the stage before waits for it)
-            u_rec[s][k] = 1;
+            if (s > 0) {  // (only the stage before waits for it)
+              if (k >= R) {  // previous occupant: round k - R, waited for by the forwards that refill its input slots
+                const int kw = k - R + rep(s, 0)->in_depth;
+                for (int j = kw * r[s]; j < (kw + 1) * r[s] && j < M; ++j)
+                  if (!fwd_done(s - 1, j)) return ring_bug("the update", s, q, k);
+              }
+              PD_HIP(hipEventRecord(rep(s, 0)->ev_u[k % R], rep(s, 0)->stream));
+            }
+            ++nU[s];
             for (int p = 0; p < r[s]; ++p)
               if (p != q && rounds(s, p) > k) {
                 ++pos[s][p];

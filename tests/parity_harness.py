@@ -87,20 +87,33 @@ def _flat_keep(layers, units):
     return np.concatenate(parts)
 
 
-def _global_order(S, noam, M, depth_override):
+def _global_order(S, noam, M, depth_override, vertical_sync=False):
     """(stage, Op) pairs in a valid global execution order."""
     if depth_override:
         assert S == 1
         return [(0, op) for op in schedule_1f1b(1, 1, M, 0, depth_override=depth_override)]
     ev = sorted(enumerate(simulate(S, noam, M)), key=lambda t: (t[1].start, t[0]))
     # simulate() already emits a valid order; sorting by start time keeps it valid (ties by emission)
-    return [(e.stage, e.op) for _, e in ev]
+    order = [(e.stage, e.op) for _, e in ev]
+    if vertical_sync:   # same op order per stage; F and B carry the input stage's version (Section 3.4)
+        lists = [schedule_1f1b(S, noam, M, s, vertical_sync=True) for s in range(S)]
+        at = [0] * S
+        for n, (s, op) in enumerate(order):
+            vs = lists[s][at[s]]
+            assert (vs.kind, vs.mb) == (op.kind, op.mb)
+            order[n] = (s, vs)
+            at[s] += 1
+    return order
 
 
 def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=0, out_grads=None,
              lr=0.01, mu=0.9, mode="free", compare=True, verbose=False, in_hw=None, minibatch=None,
-             force_acts=False, optimizer="sgd", eps=1.0):
-    """force_acts (deep image stages): after every forward pass has been compared, the GPU stage's stored layer
+             force_acts=False, optimizer="sgd", eps=1.0, vertical_sync=False):
+    """vertical_sync (Section 3.4): the version the input stage's forward pass read travels with the minibatch; every
+    later stage is asked for that version of its own weights (pd_forward_versioned) and keeps as many versions as the
+    input stage.
+
+    force_acts (deep image stages): after every forward pass has been compared, the GPU stage's stored layer
     outputs -- and the next stage's input slot -- are overwritten with the oracle's (oracle -> GPU only).  In a
     deep bf16 chain one-ulp differences compound layer by layer into differing ReLU / max-pooling decisions; with
     the stored activations forced, every backward pass and update is compared on identical decisions and must
@@ -112,8 +125,9 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
     B = minibatch or xs[0].shape[0]     # (time-major sequence inputs are [T][B][I]: pass minibatch)
     has_loss = stage_layers[-1][-1][0] == "softmax_xent"
     depths = [depth_override or in_flight_depth(S, noam, s) for s in range(S)]
-    order = _global_order(S, noam, M, depth_override)
-    os_ = [Stage(stage_layers[s], params[s], depths[s], omode, lr, mu, optimizer=optimizer, eps=eps)
+    order = _global_order(S, noam, M, depth_override, vertical_sync)
+    os_ = [Stage(stage_layers[s], params[s], depths[s], omode, lr, mu, optimizer=optimizer, eps=eps,
+                 ring_depth=depths[0] if vertical_sync else 0)
            for s in range(S)] if compare else None
     if compare:
         for o in os_:
@@ -125,7 +139,10 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
         hws = [None] * S
     gs = [GpuStage(stage_layers[s], params[s], minibatch=B, precision=precision, stage_index=s, num_stages=S,
                    noam=noam, in_flight_override=depth_override, lr=lr, momentum=mu, in_hw=hws[s],
-                   optimizer=1 if optimizer == "rmsprop" else 0, eps=eps) for s in range(S)]
+                   optimizer=1 if optimizer == "rmsprop" else 0, eps=eps, vertical_sync=vertical_sync)
+          for s in range(S)]
+    rings = [pd.pd_stage_ring_depth(g.h) for g in gs]
+    tag = {}           # vertical sync: minibatch -> version read by the input stage's forward pass
     keep = []          # device tensors that must outlive the enqueued work
     losses = torch.zeros(M, dtype=torch.float32, device=dev())
     o_losses = [None] * M
@@ -142,14 +159,20 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                 # ---- oracle ----
                 if compare:
                     xin = np.asarray(xs[mb], dtype=np.float64) if s == 0 else o_act.pop((mb, s - 1))
-                    y_o, loss_o = o.forward(mb, xin, labs[mb] if (s == S - 1 and has_loss) else None)
+                    y_o, loss_o = o.forward(mb, xin, labs[mb] if (s == S - 1 and has_loss) else None,
+                                            version=tag[mb] if (vertical_sync and s > 0) else None)
                     if s == S - 1:
                         o_losses[mb] = loss_o
                     else:
                         o_act[(mb, s)] = y_o
                         o_act_size[s + 1] = y_o.size // B
                 # ---- GPU ----
-                assert pd.pd_stage_version(g.h) == op.version
+                if vertical_sync:
+                    if s == 0:
+                        tag[mb] = pd.pd_stage_version(g.h)
+                    assert tag[mb] == op.version
+                else:
+                    assert pd.pd_stage_version(g.h) == op.version
                 if s == 0:
                     x = to_dev(xs[mb], bf16); keep.append(x); xptr = x.data_ptr()
                 else:
@@ -158,7 +181,8 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                 lab = 0
                 if s == S - 1 and has_loss:
                     l_t = labels_dev(labs[mb]); keep.append(l_t); lab = l_t.data_ptr()
-                pd.pd_forward(g.h, mb, xptr, lab, yptr, losses[mb:].data_ptr() if lab else 0)
+                pd.pd_forward_versioned(g.h, mb, tag[mb] if vertical_sync else -1, xptr, lab, yptr,
+                                        losses[mb:].data_ptr() if lab else 0)
                 assert pd.pd_stage_version(g.h, mb) == op.version
                 if not compare:
                     continue
@@ -259,7 +283,7 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                         if verbose:
                             print(f"U stage {s} mb {mb} -> v{op.version}: {name} err {e:.3e} (limit {t:.1e})", flush=True)
                         assert e <= t, (name, s, mb, e)
-                    if depths[s] >= 2 and op.version >= 1:   # an older version still held by the ring
+                    if rings[s] >= 2 and op.version >= 1:   # an older version still held by the ring
                         old = pd.pd_stage_get_params(g.h, op.version - 1, True)
                         assert rel_err(old, o.versions[op.version - 1]) <= t, ("ring history", s, mb)
                 if mode == "forced":

@@ -19,6 +19,7 @@ import torch
 import paper_1806_03377_amd as pd
 import pd_inputs as gen
 from gpu_util import dev, to_dev
+from parity_harness import run_case
 from oracle import layers as OL
 from sampling import close_bf16 as _close_bf16, conv_dx_at, conv_y_at, positions as _positions
 
@@ -162,3 +163,26 @@ def test_many_row_products_full_size_sampled():
     w_ref = w32.astype(np.float64) - lr * g
     assert np.max(np.abs(mw.cpu().numpy() - w_ref)) <= 1e-6 * float(np.abs(w_ref).max())
     assert torch.equal(rw, mw.to(torch.bfloat16))
+
+
+@pytest.mark.timeout(2400)
+def test_config4_s2vt_full_size_two_minibatches(capsys):
+    """Config 4 exactly as configured -- LSTM 4096 -> 1000 | LSTM 1000 -> 1000 + Linear 1000 -> 30000 + loss, sequence
+    length 80, minibatch 64 (5120 rows through the vocabulary layer), NOAM 2 -- for two minibatches, op by op in
+    lockstep with the oracle, which runs these sizes whole (about a minute per minibatch on the host): every stored
+    layer output (both hidden sequences, all 5120 x 30000 logits), both losses, the input gradient handed upstream
+    and, after each of the four updates, all 58 million master weights, momentum values and ring copies, at the bf16
+    tolerance.  Stage 0 has two minibatches in flight, so its second backward pass reads the stashed version 0 while
+    the latest is 1."""
+    print("config 4 at full size (T 80, minibatch 64, vocabulary 30000): oracle + GPU, two minibatches", flush=True)
+    sl = gen.config4_s2vt()
+    seed, M, T, B, I, V = SEED + 4, 2, 80, 64, 4096, 30000
+    params = [gen.init_params(seed, f"q{s}", ly) for s, ly in enumerate(sl)]
+    xs = [gen.normal_bulk(seed, f"X{i}", (T, B, I)) for i in range(M)]
+    labs = list(gen.labels(seed, "Y", (M, T, B), V))
+    with capsys.disabled():      # the oracle needs minutes here: let the per-op lines through as signs of life
+        print(flush=True)
+        out = run_case(sl, params, xs, labs, noam=2, precision=pd.PD_BF16_F32ACC, lr=0.01, mode="forced", minibatch=B,
+                       verbose=True)
+    assert out["updates_compared"] == (2 * M, 2 * M), out["updates_compared"]
+    assert all(np.isfinite(out["losses"])) and all(l > 5.0 for l in out["losses"]), out["losses"]   # ~ log(30000)

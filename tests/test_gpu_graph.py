@@ -109,3 +109,50 @@ def test_graph_replay_lstm_stage_with_vocab_projection():
     # the recurrence (one kernel per time step, forward and backward) and the many-row vocabulary product
     layers = [("lstm", 16, 24, 6), ("linear", 24, 40, False), ("softmax_xent", 40)]
     _graph_case(layers, B=4, W=2, x_shape=(6, 4, 16), n_out=40, with_loss=True, lab_shape=(6, 4))
+
+
+def test_pipeline_drivers_refuse_stream_capture():
+    """pd_pipeline_run / pd_pipeline_run_replicated join several streams by events and never join them back to one
+    stream, which stream capture does not allow: while any stage stream is being captured they return PD_ESTATE and
+    enqueue nothing.  The capture is begun and ended here directly on the HIP runtime (an empty capture)."""
+    import ctypes
+    from gpu_util import GpuReplicatedStage
+    hip = ctypes.CDLL("libamdhip64.so.7")      # the runtime instance torch and libpd.so already share
+    hip.hipStreamBeginCapture.argtypes = [ctypes.c_void_p, ctypes.c_int]
+    hip.hipStreamEndCapture.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipGraphDestroy.argtypes = [ctypes.c_void_p]
+    sl = gen.config1_mlp(32, 8, 2)
+    B, M = 4, 5
+    params = [gen.init_params(SEED, f"c{s}", ly) for s, ly in enumerate(sl)]
+    xd = to_dev(gen.normal(SEED, "CX", (M * B, 32)), False)
+    ld = labels_dev(gen.labels(SEED, "CY", (M, B), 8))
+    losses = torch.zeros(M, dtype=torch.float32, device=dev())
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    gs = [GpuStage(sl[s], params[s], minibatch=B, precision=pd.PD_F32, stage_index=s, num_stages=2, noam=2,
+                   stream=streams[s]) for s in range(2)]
+    rep = GpuReplicatedStage(sl[0], params[0], 2, minibatch=B, precision=pd.PD_F32, stage_index=0, num_stages=2, noam=2,
+                             stream=streams[2])
+    try:
+        torch.cuda.synchronize()
+        THREAD_LOCAL = 1                        # hipStreamCaptureModeThreadLocal
+        assert hip.hipStreamBeginCapture(streams[1].cuda_stream, THREAD_LOCAL) == 0
+        try:
+            with pytest.raises(pd.PdError) as e:
+                pd.pd_pipeline_run([g.h for g in gs], M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+            assert e.value.status == pd.PD_ESTATE and "captured" in str(e.value)
+            with pytest.raises(pd.PdError) as e:
+                pd.pd_pipeline_run_replicated([rep.handles(), [gs[1].h]], M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+            assert e.value.status == pd.PD_ESTATE and "captured" in str(e.value)
+        finally:
+            graph = ctypes.c_void_p()
+            assert hip.hipStreamEndCapture(streams[1].cuda_stream, ctypes.byref(graph)) == 0
+            if graph:
+                hip.hipGraphDestroy(graph)
+        assert all(pd.pd_stage_trace(g.h) == [] for g in gs)      # nothing was enqueued
+        pd.pd_pipeline_run([g.h for g in gs], M, xd.data_ptr(), ld.data_ptr(), losses.data_ptr())
+        torch.cuda.synchronize()
+        assert [pd.pd_stage_version(g.h) for g in gs] == [M, M] and bool(torch.isfinite(losses).all())
+    finally:
+        rep.close()
+        for g in gs:
+            g.close()

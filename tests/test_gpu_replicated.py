@@ -237,7 +237,10 @@ def test_pipeline_with_replicated_input_stage_f32():
 
 
 @pytest.mark.parametrize("reps,depths,M", [([2, 1], [2, 1], 11), ([3, 1], [1, 1], 7), ([1, 2], [2, 1], 9),
-                                           ([2, 2, 1], [2, 2, 1], 13), ([2, 1], [1, 1], 1)])
+                                           ([2, 2, 1], [2, 2, 1], 13), ([2, 1], [1, 1], 1),
+                                           # long streams: the drivers' event rings wrap many times
+                                           ([2, 1], [2, 1], 150), ([1, 3], [3, 1], 140), ([2, 3, 1], [3, 2, 1], 130),
+                                           ([4, 1], [1, 1], 101)])
 def test_library_driven_pipeline_with_replicated_stages_f32(reps, depths, M):
     # pd_pipeline_run_replicated enqueues the whole stream with events only; nothing is read back before the end
     S, B = len(reps), 6

@@ -146,6 +146,33 @@ def test_reduces_to_sequential_sgd(S, NOAM):
         assert np.allclose(st.master, rp, rtol=1e-10, atol=1e-13)
 
 
+def test_continuing_a_drained_pipeline_keeps_weights_momentum_and_versions():
+    """run_pipeline(stages=...) continues with drained stages.  Pin: with one stage (or NOAM 1) nothing is ever stale,
+    so two runs of 5 minibatches back to back are the sequential momentum SGD over all 10 (torch.optim.SGD); for a
+    real pipeline the second run equals a fresh run started from the first run's weights AND momentum (set by hand)."""
+    sl = [[("linear", 12, 12, True), ("linear", 12, 5, False), ("softmax_xent", 5)]]
+    params = _params(sl)
+    xs, ys = _data(10, 6, 12, 5)
+    st, l1 = run_pipeline(sl, params, xs[:5], ys[:5], 1, lr=0.05, momentum=0.9)
+    st, l2 = run_pipeline(sl, None, xs[5:], ys[5:], 1, lr=0.05, momentum=0.9, stages=st)
+    ref_p, ref_l = _torch_sequential_sgd(sl, params, xs, ys, 0.05, 0.9)
+    assert np.allclose(list(l1) + list(l2), ref_l, rtol=1e-11)
+    assert np.allclose(st[0].master, ref_p[0], rtol=1e-10, atol=1e-13) and st[0].latest == 10
+    assert [o.version for o in st[0].trace if o.kind == OP_F] == list(range(10))
+    sl = _mlp(stages=3)
+    params = _params(sl)
+    a, _ = run_pipeline(sl, params, xs[:5], ys[:5], 3, lr=0.05, momentum=0.9)
+    w, m = [x.master.copy() for x in a], [x.mom.copy() for x in a]
+    a, la = run_pipeline(sl, None, xs[5:], ys[5:], 3, lr=0.05, momentum=0.9, stages=a)
+    fresh = [Stage(sl[s], w[s], in_flight_depth(3, 3, s), "f32", 0.05, 0.9) for s in range(3)]
+    for f, mm in zip(fresh, m):
+        f.mom = mm
+    b, lb = run_pipeline(sl, None, xs[5:], ys[5:], 3, lr=0.05, momentum=0.9, stages=fresh)
+    assert la == lb
+    for x, y in zip(a, b):
+        assert np.array_equal(x.master, y.master) and np.array_equal(x.mom, y.mom) and x.latest == y.latest + 5
+
+
 # ---- the staleness equation as an independent flat loop (autograd layers) -----
 
 def _torch_flat_loop(stage_layers, params, xs, ys, depths, lr, mu):
