@@ -221,7 +221,14 @@ def run_case(stage_layers, params, xs, labs, *, noam, precision, depth_override=
                     print(f"F stage {s} mb {mb} v{op.version}: rows with ambiguous ReLU decisions {len(rows)} "
                           f"(total elements {n_flips}/{n_elems})", flush=True)
             elif op.kind == OP_B:
-                n_in = int(np.asarray(xs[0]).size // B) if s == 0 else (lin[0][1] if lin[0][0] == "linear" else int(o_act_size[s]))
+                if s == 0:
+                    n_in = int(np.asarray(xs[0]).size // B)
+                elif lin[0][0] == "linear":
+                    n_in = lin[0][1]
+                elif hws[s] is not None and len(hws[s]) == 3:
+                    n_in = int(np.prod(hws[s]))
+                else:
+                    n_in = int(o_act_size[s])
                 if compare:
                     if s == S - 1:
                         dy_o = None if has_loss else np.asarray(out_grads[mb], dtype=np.float64)
