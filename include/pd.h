@@ -315,8 +315,12 @@ int pd_update(pd_stage* st);
  * the same minibatch and precision, matching widths, the last ending in PD_SOFTMAX_XENT).  Each
  * stage follows its own pd_schedule_1f1b list on its own stream; F(i,s) waits (event) for
  * F(i,s-1), B(i,s) for B(i,s+1); every reuse of an inter-stage slot waits for its last reader.
- * Activations go directly into the consumer's input slot, gradients into the producer's grad
- * slot.  inputs_dev [num_minibatches][minibatch][in0]; labels_dev int32 [num_minibatches]
+ * Hand-off without copies: the last layer of stage s writes its output straight into the input slot
+ * of stage s+1 (and keeps no other copy: that slot stays intact until stage s has run the minibatch's
+ * backward pass); stage s+1 stores dL/d(its input) into the gradient slot of stage s with the ReLU mask
+ * of stage s's last layer already applied (the mask is stage s+1's own input), and stage s uses it where
+ * it lies, up to and including its update.  (pd_forward / pd_backward called directly copy instead:
+ * they cannot know how long the caller's buffers stay intact.)  inputs_dev [num_minibatches][minibatch][in0]; labels_dev int32 [num_minibatches]
  * [minibatch]; losses_dev float[num_minibatches] (may be NULL).  Enqueues everything and
  * returns; the caller synchronises the streams.  Stages must have nothing in flight; minibatch
  * ids continue from each stage's last forward (or 0). */

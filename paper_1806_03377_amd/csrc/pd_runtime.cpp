@@ -231,6 +231,13 @@ struct pd_stage {
     return hipEventRecord(e, stream);
   }
 
+  // Zero-copy hand-off (pd_pipeline_run): per stash slot, where the LAST layer's output of the minibatch in that slot
+  // lives when it was written straight into the consumer stage's input slot instead of the stash (null: in the stash);
+  // and, until pd_update, where dL/d(pre-activation) of the last layer lies when the consumer stage has left it, masked,
+  // in this stage's gradient slot (null: in the stage's own buffer)
+  std::vector<char*> borrowed_out;
+  const char* borrowed_dz = nullptr;
+
   char* ring_slot(int version) const { return ring + (size_t)(version % ring_depth) * p_pad * esz; }
   char* in_slot(int mb) const { return in_ring + (size_t)(mb % in_depth) * in_bytes; }
   char* stash_slot(int mb) const { return stash + (size_t)(mb % depth) * stash_slot_bytes; }
@@ -238,6 +245,10 @@ struct pd_stage {
   // stored output of layer l inside a stash slot (an LSTM keeps a zero state in front of its sequence)
   char* out_of(char* slot, int l) const {
     const Linear& L = lin[l];
+    if (l + 1 == (int)lin.size() && !borrowed_out.empty()) {
+      char* b = borrowed_out[(size_t)(slot - stash) / stash_slot_bytes];
+      if (b) return b;
+    }
     return slot + L.y_off + (L.kind == K_LSTM ? (size_t)B * L.out * 2 : 0);
   }
 };
@@ -605,6 +616,7 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
   st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
   st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
   st->blk_dy = a + p.o_blk_dy; st->blk_dx = a + p.o_blk_dx; st->blk_dx_stride = p.blk_dx_stride;
+  st->borrowed_out.assign(p.depth, nullptr);
   hipError_t e = primary ? hipSuccess : pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
   // padding between layers inside the gradient buffer is never written by a gradient kernel: keep it at zero
   if (e == hipSuccess && st->gradbuf) e = pd::fill_zero(st->stream, st->gradbuf, p.p_pad * 4);
@@ -1137,13 +1149,11 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
   return PD_OK;
 }
 
-int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
-               float* loss_dev) {
-  return pd_forward_versioned(st, mb_id, -1, x_dev, labels_dev, y_dev, loss_dev);
-}
-
-int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const void* x_dev, const int32_t* labels_dev,
-                         void* y_dev, float* loss_dev) {
+// borrow_y (the pipeline driver only): y_dev is the consumer stage's input slot and stays intact until this stage's
+// backward pass of the minibatch has run, so the last layer writes its output THERE and nowhere else: the hand-off
+// costs no copy and no launch.  Otherwise y_dev receives a copy of the stored output.
+static int forward_impl(pd_stage* st, int32_t mb_id, int32_t version, const void* x_dev, const int32_t* labels_dev,
+                        void* y_dev, float* loss_dev, bool borrow_y) {
   if (check_stage(st)) return PD_EINVAL;
   if (version >= 0 && (version > st->latest || version <= st->latest - st->ring_depth))
     return fail(PD_ESTATE, "forward of minibatch %d asks for version %d, the stage holds %d..%d", mb_id, version,
@@ -1171,6 +1181,8 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
   char* in = st->in_slot(mb_id);
   char* slot = st->stash_slot(mb_id);
   const char* w = st->ring_slot(v);
+  borrow_y = borrow_y && y_dev && !st->has_loss && st->lin.back().kind != K_LSTM;
+  st->borrowed_out[mb_id % st->depth] = borrow_y ? static_cast<char*>(y_dev) : nullptr;
   if (x_dev != in) PD_HIP(pd::copy_bytes(s, x_dev, in, (size_t)st->lin.front().rows * st->lin.front().in * st->esz));
   PD_HIP(st->mark(-1, 0));
   int loss_splits = 0;                    // > 0: the last Linear layer left this many partial sums in the workspace
@@ -1249,7 +1261,8 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
       PD_HIP(pd::softmax_xent(s, reinterpret_cast<const float*>(a), labels_dev, slot + st->dlogits_off, st->row_loss,
                               loss_dev, st->lin.back().rows, st->classes, st->bf16));
   }
-  if (y_dev) PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->lin.back().rows * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
+  if (y_dev && !borrow_y)
+    PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->lin.back().rows * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
   PD_HIP(st->mark(0, (int)st->lin.size() - 1));  // (the loss and the copy of the output count for the last layer)
   if (st->profiling) ++st->prof_ops[0];
   st->in_flight.push_back({mb_id, v});
@@ -1258,7 +1271,23 @@ int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const voi
   return PD_OK;
 }
 
-int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
+int pd_forward(pd_stage* st, int32_t mb_id, const void* x_dev, const int32_t* labels_dev, void* y_dev,
+               float* loss_dev) {
+  return forward_impl(st, mb_id, -1, x_dev, labels_dev, y_dev, loss_dev, false);
+}
+
+int pd_forward_versioned(pd_stage* st, int32_t mb_id, int32_t version, const void* x_dev, const int32_t* labels_dev,
+                         void* y_dev, float* loss_dev) {
+  return forward_impl(st, mb_id, version, x_dev, labels_dev, y_dev, loss_dev, false);
+}
+
+// The pipeline driver's variants of the gradient hand-off between two stages:
+//   dy_is_dz    dy_dev already is dL/d(pre-activation) of this stage's last layer (the consumer stage applied this
+//               stage's ReLU mask when it stored the gradient) and stays intact until pd_update: it is used where it
+//               lies, with no masking or copying launch;
+//   mask_input  the producer stage ends in a ReLU: dL/d(input) is stored with that ReLU's mask applied, taken from this
+//               stage's own input slot, which holds the producer's output.
+static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev, bool dy_is_dz, bool mask_input) {
   if (check_stage(st)) return PD_EINVAL;
   if (st->grad_pending) return fail(PD_ESTATE, "previous gradient not yet consumed by pd_update");
   if (st->in_flight.empty()) return fail(PD_ESTATE, "no minibatch in flight");
@@ -1286,6 +1315,8 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   PD_HIP(st->mark(-1, 0));
   if (st->has_loss) {
     cur = slot + st->dlogits_off;
+  } else if (dy_is_dz) {
+    cur = static_cast<const char*>(dy_dev);
   } else {
     char* b = buffer_for(nl - 1);
     const size_t n = (size_t)last.rows * last.out;
@@ -1362,6 +1393,7 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
     } else {
       if (!dx_dev) break;
       out = static_cast<char*>(dx_dev);
+      if (mask_input) mask = st->in_slot(mb_id);
     }
     if (L.kind == K_LINEAR) {
       if (st->bf16) {
@@ -1392,13 +1424,13 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
                                  reinterpret_cast<pd::bf16_t*>(st->wt), g, ep));
     } else if (L.kind == K_POOL) {
       PD_HIP(pd::maxpool2x2_backward_bf16(s, reinterpret_cast<const pd::bf16_t*>(x),
-                                          reinterpret_cast<const pd::bf16_t*>(slot + L.y_off),
+                                          reinterpret_cast<const pd::bf16_t*>(st->out_of(slot, l)),
                                           reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out),
                                           st->B, L.ih, L.iw, L.ic, mask != nullptr));
     } else {  // K_GPOOL (the pooling kernels take the mask as "x > 0", x being the stored output of the producer)
       const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
       PD_HIP(pd::pool2d_backward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(x),
-                                      reinterpret_cast<const pd::bf16_t*>(slot + L.y_off),
+                                      reinterpret_cast<const pd::bf16_t*>(st->out_of(slot, l)),
                                       reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out), g,
                                       mask != nullptr));
     }
@@ -1415,6 +1447,7 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
         if (st->lin[blk->blk_src].relu) sum_mask = st->out_of(slot, blk->blk_src);
       } else {
         sum_out = static_cast<char*>(dx_dev);
+        if (mask_input) sum_mask = st->in_slot(mb_id);
       }
       PD_HIP(pd::sum_tensors_bf16(s, parts, blk->nbr, reinterpret_cast<const pd::bf16_t*>(sum_mask),
                                   reinterpret_cast<pd::bf16_t*>(sum_out), blk->blk_in_elems));
@@ -1426,8 +1459,13 @@ int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
   st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
   st->grad_pending = true;
   st->pending_mb = mb_id;
+  st->borrowed_dz = (dy_is_dz && !st->has_loss) ? static_cast<const char*>(dy_dev) : nullptr;
   st->log_op(PD_OP_B, mb_id, v);
   return PD_OK;
+}
+
+int pd_backward(pd_stage* st, int32_t mb_id, const void* dy_dev, void* dx_dev) {
+  return backward_impl(st, mb_id, dy_dev, dx_dev, false, false);
 }
 
 }  // extern "C"
@@ -1462,7 +1500,8 @@ int run_update_kernels(pd_stage* st, int nv, bool grad_only) {
       PD_HIP(st->mark(2, l));
       continue;
     }
-    const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off : st->dz + L.dz_off;
+    const char* dz = (st->has_loss && l == nl - 1) ? slot + st->dlogits_off
+                     : (l == nl - 1 && st->borrowed_dz && L.kind == K_LINEAR) ? st->borrowed_dz : st->dz + L.dz_off;
     const char* x = L.src < 0 ? st->in_slot(mb) : st->out_of(slot, L.src);
     if (st->bf16 && L.splits > 0) {  // many rows: partial sums over row ranges, then reduce + update
       pd::bf16_t* ro = reinterpret_cast<pd::bf16_t*>(st->ring_slot(nv));
@@ -1757,7 +1796,7 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
   // Event rings.  Minibatch i of stage s uses ev_f / ev_b / ev_u [i mod R].  R need not grow with the stream: a record
   // of entry i + R is only ever enqueued after every wait on entry i (ev_f[s][i]: F(i, s+1), which the record of
   // F(i + R, s) follows through the update that frees the consumer's input slot, R >= its input-ring depth;
-  // ev_b[s][i]: B(i, s-1) and B(i + 2, s+1), R >= 2; ev_u[s][i]: F(i + input-ring depth of s, s-1)).  The checks
+  // ev_b[s][i]: B(i, s-1), R >= 2; ev_u[s][i]: F(i + input-ring depth of s, s-1) and B(i + 2, s+1)).  The checks
   // before each record below assert exactly that, with integers.
   int R = 2;
   for (int s = 0; s < S; ++s) R = std::max(R, stages[s]->in_depth);
@@ -1801,7 +1840,11 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
           const int32_t* lab = s == S - 1 ? labels_dev + (size_t)i * st->lin.back().rows : nullptr;
           float* loss = (s == S - 1 && losses_dev) ? losses_dev + i : nullptr;
           if (vsync && s == 0) tag[i % (R + 1)] = st->latest;
-          const int rc = pd_forward_versioned(st, mb, vsync ? tag[i % (R + 1)] : -1, x, lab, y, loss);
+          // zero-copy hand-off: the consumer's input slot stays intact until this stage's backward pass of the
+          // minibatch (its next writer is this stage's forward pass `in_depth` minibatches on, which the stage's own
+          // list places after that backward pass when in_depth >= depth), so the last layer writes straight into it
+          const bool borrow = s < S - 1 && stages[s + 1]->in_depth >= st->depth;
+          const int rc = forward_impl(st, mb, vsync ? tag[i % (R + 1)] : -1, x, lab, y, loss, borrow);
           if (rc != PD_OK) return rc;
           if (s < S - 1) {  // (only the next stage waits for it)
             if (i >= R && nF[s + 1] <= i - R) return ring_bug("the forward pass", s, i);
@@ -1810,12 +1853,16 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
           ++nF[s];
         } else if (op.kind == PD_OP_B) {
           if (s < S - 1 && i >= nB[s + 1]) break;
-          if (s > 0 && i >= 2 && i - 2 >= nB[s - 1]) break;  // the gradient slot this backward writes into
+          // the gradient slot this backward writes into: the stage before reads it in place (as dL/d(pre-activation)
+          // of its last layer) up to and including its update two minibatches back
+          if (s > 0 && i >= 2 && i - 2 >= nU[s - 1]) break;
           if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_b[e], 0));
-          if (s > 0 && i >= 2) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_b[(i - 2) % R], 0));
+          if (s > 0 && i >= 2) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_u[(i - 2) % R], 0));
           const void* dy = s < S - 1 ? st->grad_slot(mb) : nullptr;
           void* dx = s > 0 ? stages[s - 1]->grad_slot(mb) : nullptr;
-          const int rc = pd_backward(st, mb, dy, dx);
+          // zero-copy hand-off: this stage stores dL/d(input) with the producer's ReLU mask applied (the mask is this
+          // stage's own input), and takes what the consumer stored for it as it lies
+          const int rc = backward_impl(st, mb, dy, dx, s < S - 1, s > 0 && stages[s - 1]->lin.back().relu);
           if (rc != PD_OK) return rc;
           if (i >= R && ((s > 0 && nB[s - 1] <= i - R) || (s < S - 1 && nB[s + 1] <= i - R + 2)))
             return ring_bug("the backward pass", s, i);
@@ -1824,8 +1871,9 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
         } else {
           const int rc = pd_update(st);
           if (rc != PD_OK) return rc;
-          if (s > 0) {  // (only the stage before waits for it: slot reuse)
-            if (i >= R && nF[s - 1] <= i - R + st->in_depth) return ring_bug("the update", s, i);
+          if (S > 1) {  // (the neighbours wait for it: reuse of this stage's input slot and of its gradient slot)
+            if (i >= R && ((s > 0 && nF[s - 1] <= i - R + st->in_depth) || (s < S - 1 && nB[s + 1] <= i - R + 2)))
+              return ring_bug("the update", s, i);
             PD_HIP(hipEventRecord(st->ev_u[e], st->stream));
           }
           ++nU[s];
