@@ -45,6 +45,12 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
  * a convolution with >= 256 output channels uses its wide-tile kernel.  Returns the previous value; min_tiles < 1 only queries.  Set it
  * before pd_gemm_workspace_bytes / pd_stage_query_bytes: the workspace size depends on it. */
 int pd_set_big_tile_threshold(int32_t min_tiles);
+/* Tuning knob (process-wide, not thread-safe): variant of the large-tile forward product.  0: chosen by the
+ * reduction length (the default); 4: four waves of 128 x 128 outputs (one per SIMD); 8: eight waves of 128 x 64;
+ * 104 / 108: the same with 64-byte instead of 128-byte tile rows in LDS (32 instead of 64 reduction elements per
+ * stage).  Returns the previous value in the same encoding; any other argument only queries. */
+int pd_set_big_gemm_waves(int32_t waves);
+
 /* How many executed ops a stage remembers for pd_stage_trace: the most recent `max_ops` (default 65536; 0 switches
  * the record off and clears it).  Host-side only. */
 int pd_stage_set_trace_limit(pd_stage* st, size_t max_ops);

@@ -685,7 +685,8 @@ constexpr size_t kBigDgradElems = (size_t)32 << 20;  // weight elements from whi
 // 109 us, input gradient 106 vs 129 us), but with that threshold the two-stream LSTM pipeline, where such products
 // run next to the other stage's kernels, got slower (5.26 vs 5.02 ms per minibatch): a workgroup that holds 128 KB
 // of LDS leaves no room on its compute unit for the other stream.
-int g_big_min_tiles = 128;
+constexpr int kDefaultBigMinTiles = 128;
+int g_big_min_tiles = kDefaultBigMinTiles;
 bool use_big_tiles(int rows, int cols) { return ((rows + 255) / 256) * ((cols + 255) / 256) >= g_big_min_tiles; }
 
 // Enough workgroups to fill the chip (about two per CU, all co-resident), never more splits than stages.
@@ -769,26 +770,62 @@ int set_big_tile_threshold(int min_tiles) {
   return old;
 }
 
+// How a product with `rows` x `cols` outputs and reduction length `red` runs on the 256 x 256-tile kernels:
+//   1   the output tiles alone fill the chip;
+//   > 1 too few tiles for that, but many rows and a long reduction: the reduction is split this many ways over about
+//       one workgroup per compute unit, the fp32 partial products are added up by splitk_epilogue_kernel
+//       (`red_step`: the kernel's stage length, which the reduction must be a multiple of);
+//   0   not a case for the large tiles (the kernels built for minibatch-sized row counts take it).
+// Measured on MI355X (8192 -> 1024 rows at 4096 x 25088): the forward product of 1024 rows 459 us on the small-tile
+// split-K kernel; the input gradient of 5120 rows against 30000 x 1000 weights 129 us on an idle chip.
+int big_tile_splits(int rows, int cols, int red, int red_step) {
+  const int tiles = ((rows + 255) / 256) * ((cols + 255) / 256);
+  const int whole = tiles >= g_big_min_tiles ? 1 : 0;     // what applies if the reduction is not split
+  if (g_big_min_tiles != kDefaultBigMinTiles) return whole;  // a forced threshold means exactly that
+  if (rows < 256 || red < 2048 || (red % red_step) != 0 || (cols % 4) != 0) return whole;
+  int s = 256 / tiles;  // (also for exactly 128 tiles, which would leave half of the compute units idle)
+  if (s > red / 512) s = red / 512;
+  if (s > 16) s = 16;
+  return s >= 2 ? s : whole;
+}
+
 bool linear_fwd_uses_big_tiles(int M, int N) { return use_big_tiles(M, N); }
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K) {
-  if (use_big_tiles(M, K)) return linear_dgrad_big_scratch_bytes(N, K);  // transposed weights; no split-K at this size
-  const size_t a = splitk_bytes_t<kFwdBN, kFwdBK>(M, N, K);
-  const size_t b = (size_t)N * K >= kBigDgradElems ? splitk_bytes_t<kBigBN, kBigBK>(M, K, N)
-                                                   : splitk_bytes_t<kSmallBN, kSmallBK>(M, K, N);
+  const int sf = big_tile_splits(M, N, K, 64), sd = big_tile_splits(M, K, N, 32);
+  const size_t a = sf == 1 ? 0 : sf > 1 ? (size_t)sf * M * N * sizeof(float) : splitk_bytes_t<kFwdBN, kFwdBK>(M, N, K);
+  const size_t b = sd == 1 ? linear_dgrad_big_scratch_bytes(N, K)  // room for transposed weights
+                   : sd > 1 ? (size_t)sd * M * K * sizeof(float)
+                   : (size_t)N * K >= kBigDgradElems ? splitk_bytes_t<kBigBN, kBigBK>(M, K, N)
+                                                     : splitk_bytes_t<kSmallBN, kSmallBK>(M, K, N);
   return a > b ? a : b;
 }
 
 hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const bf16_t* b, bf16_t* y, float* y_f32,
                            int M, int N, int K, bool relu, float* ws, size_t ws_bytes) {
-  if (use_big_tiles(M, N)) return linear_fwd_big_bf16(s, x, K, w, b, y, y_f32, M, N, K, relu);
+  const int sp = big_tile_splits(M, N, K, 64);
+  if (sp == 1) return linear_fwd_big_bf16(s, x, K, w, b, y, y_f32, M, N, K, relu, 1, nullptr);
   GemmEpilogue ep = {b, nullptr, relu ? 1 : 0, y, y_f32};
+  if (sp > 1 && ws && (size_t)sp * M * N * sizeof(float) <= ws_bytes &&
+      linear_fwd_big_bf16(s, x, K, w, nullptr, nullptr, nullptr, M, N, K, false, sp, ws) == hipSuccess) {
+    const size_t total4 = (size_t)M * N / 4;
+    splitk_epilogue_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(ws, sp, M, N, ep);
+    return hipGetLastError();
+  }
   return launch_gemm<false, kFwdBN, kFwdBK, kFwdPD, kFwdNBUF>(s, x, w, ep, M, N, K, ws, ws_bytes);
 }
 
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes) {
-  if (use_big_tiles(M, K)) return linear_dgrad_big_bf16(s, dz, w, mask, dx, M, N, K, ws, ws_bytes);
+  const int sp = big_tile_splits(M, K, N, 32);
+  if (sp == 1) return linear_dgrad_big_bf16(s, dz, w, mask, dx, M, N, K, ws, ws_bytes, 1);
+  if (sp > 1 && ws && (size_t)sp * M * K * sizeof(float) <= ws_bytes &&
+      linear_dgrad_big_bf16(s, dz, w, nullptr, nullptr, M, N, K, ws, ws_bytes, sp) == hipSuccess) {
+    GemmEpilogue epr = {nullptr, mask, 0, dx, nullptr};
+    const size_t total4 = (size_t)M * K / 4;
+    splitk_epilogue_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(ws, sp, M, K, epr);
+    return hipGetLastError();
+  }
   GemmEpilogue ep = {nullptr, mask, 0, dx, nullptr};
   if ((size_t)N * K >= kBigDgradElems)
     return launch_gemm<true, kBigBN, kBigBK, kBigPD, kBigNBUF>(s, dz, w, ep, M, K, N, ws, ws_bytes);

@@ -39,9 +39,13 @@ struct BigEpilogue {
 // Epilogue of one wave's 128 x WCOLS sub-tile (accumulators acc[4][NJ], top-left corner row0, col_base): bias,
 // ReLU, rounding, mask.  The wave stages 32-row blocks in its private LDS region `stage` (the operand tiles are
 // dead by then) and writes them out as full rows, 16 bytes per lane.
-template <int NJ, int WCOLS>
-__device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpilogue& ep, char* stage, int row0,
+// (NJT = column blocks the wave holds, of which this call handles NJ starting at block J0: a wave with 128 columns
+// goes through two calls of 64, which keeps the fully unrolled body at the size the compiler still unrolls -- with
+// anything less the accumulators are indexed dynamically and end up in scratch memory.)
+template <int NJ, int WCOLS, int NJT = NJ, int J0 = 0>
+__device__ __forceinline__ void big_epilogue(f32x16 (&acc_all)[4][NJT], const BigEpilogue& ep, char* stage, int row0,
                                              int col_base, int l, int I, int J) {
+  auto acc = [&](int i, int j) -> f32x16& { return acc_all[i][J0 + j]; };
   const bool wide_ok = ((ep.ldo & 7) == 0) && ((J & 7) == 0);
   if (wide_ok) {
     constexpr int FLD = WCOLS + 4, HLD = WCOLS + 8;  // padded staging rows (fp32 / bf16)
@@ -56,7 +60,7 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
           const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float v = acc[i][j][r] + bv;
+            float v = acc(i, j)[r] + bv;
             if (ep.relu) v = fmaxf(v, 0.f);
             sf[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * FLD + 32 * j + (l & 31)] = v;
           }
@@ -94,7 +98,7 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
           const float bv = (ep.bias && c < J) ? bf2f(ep.bias[c]) : 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            float v = acc[i][j][r] + bv;
+            float v = acc(i, j)[r] + bv;
             if (ep.relu) v = fmaxf(v, 0.f);
             sb[(8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * HLD + 32 * j + (l & 31)] = f2bf(v);
           }
@@ -138,7 +142,7 @@ __device__ __forceinline__ void big_epilogue(f32x16 (&acc)[4][NJ], const BigEpil
       for (int r = 0; r < 16; ++r) {
         const int row = row0 + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
         if (row >= I) continue;
-        float v = acc[i][j][r] + bv;
+        float v = acc(i, j)[r] + bv;
         if (ep.relu) v = fmaxf(v, 0.f);
         const size_t off = (size_t)row * ep.ldo + c;
         if (ep.upd_master) {
@@ -264,8 +268,13 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_big_kernel(const bf16_t* __re
     __syncthreads();
   }
 
-  big_epilogue<NJ, WCOLS>(acc, ep, reinterpret_cast<char*>(smem) + (size_t)w * kStageBytes, i0 + 128 * wm,
-                          j0 + WCOLS * wn, l, I, J);
+  char* const est = reinterpret_cast<char*>(smem) + (size_t)w * kStageBytes;
+  if constexpr (NJ == 2) {
+    big_epilogue<2, 64>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn, l, I, J);
+  } else {
+    big_epilogue<2, 64, NJ, 0>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn, l, I, J);
+    big_epilogue<2, 64, NJ, 2>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn + 64, l, I, J);
+  }
 }
 
 // ---- both operands reduction-contiguous: global -> LDS without passing through registers --------------------
@@ -281,15 +290,22 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_big_kernel(const bf16_t* __re
 constexpr int DK = 32, DNS = 4, DROWB = DK * 2, DTILE = 256 * DROWB, DSTAGE = 2 * DTILE;
 __device__ __forceinline__ int dma_swz(int row) { return (row >> 2) & 3; }
 
-__global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restrict__ A, int lda,
-                                                          const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep,
-                                                          int I, int J, int R, int tiles_i, int tiles_j) {
-  constexpr int NW = 8, NI = 4, NJ = 2, KS = DK / 16, D = DNS - 1;
-  constexpr int QN = 256 / 16 / NW;        // wave-wide loads per operand and stage (2)
+// NW = 8: 2 x 4 waves of 128 x 64 (two waves per SIMD: one issues MFMAs while the other waits; 0.75 LDS fragment
+// reads per MFMA).  NW = 4: 2 x 2 waves of 128 x 128 (one wave per SIMD, 0.5 fragment reads per MFMA, which is what
+// the LDS read path can sustain at the full MFMA rate); with a single wave per SIMD nothing hides a stall, so the
+// order of MFMAs, fragment reads and loads inside a reduction step is pinned: one memory instruction behind each of
+// the first twelve MFMAs of the step's sixteen.
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const bf16_t* __restrict__ A, int lda,
+                                                              const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep,
+                                                              int I, int J, int R, int tiles_i, int tiles_j) {
+  constexpr int NT = 64 * NW, WN = NW / 2, WCOLS = 256 / WN;
+  constexpr int NI = 4, NJ = WCOLS / 32, KS = DK / 16, D = DNS - 1;
+  constexpr int QN = 256 / 16 / NW;        // wave-wide loads per operand and stage (2 or 4)
   constexpr int LPS = 2 * QN, LPK = LPS / KS, MF = NI * NJ;
   __shared__ __attribute__((aligned(1024))) char smem[DNS * DSTAGE];
   const int t = threadIdx.x, l = t & 63;
-  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w / WN, wn = w % WN;
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): renumber so that an XCD works on a
   // contiguous run of tiles, and walk the tiles in bands of four tile rows so that the tiles in flight on one XCD
   // share a few A and B panels.
@@ -337,7 +353,7 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restri
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
-    const int row = 64 * wn + 32 * j + (l & 31);
+    const int row = WCOLS * wn + 32 * j + (l & 31);
     fb[j] = DTILE + row * DROWB + (((l >> 5) ^ dma_swz(row)) << 4);
   }
   auto ldf = [&](const char* stage, int o, int ks) { return *reinterpret_cast<const uint4*>(stage + (o ^ (ks << 5))); };
@@ -351,8 +367,8 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restri
   if (tail) {  // ragged end of the reduction: through registers with zero fill, into the stage the pipeline fills last
     char* st = smem + D * DSTAGE;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = t + 512 * i, row = c >> 2, g = c & 3, k = T * DK + g * 8;
+    for (int i = 0; i < 1024 / NT; ++i) {
+      const int c = t + NT * i, row = c >> 2, g = c & 3, k = T * DK + g * 8;
       const int ra = i0 + row < I ? i0 + row : I - 1, rb = j0 + row < J ? j0 + row : J - 1;
       const uint4 va = k < R ? ldg16(A + (size_t)ra * lda + k) : zero16();
       const uint4 vb = k < R ? ldg16(Bm + (size_t)rb * ldb + k) : zero16();
@@ -393,28 +409,46 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restri
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const int c = ks & 1, n = c ^ 1;
-      if (ks + 1 < KS) {
+      const char* src = ks + 1 < KS ? sc : sn;  // next step's fragments; the next stage was published a barrier ago
+      const int kn = ks + 1 < KS ? ks + 1 : 0;
+      if constexpr (NW == 8) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) a[n][i] = ldf(sc, fa[i], ks + 1);
+        for (int i = 0; i < NI; ++i) a[n][i] = ldf(src, fa[i], kn);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) b[n][j] = ldf(sc, fb[j], ks + 1);
-      } else {  // next stage's first fragments (published by the previous barrier)
+        for (int j = 0; j < NJ; ++j) b[n][j] = ldf(src, fb[j], kn);
 #pragma unroll
-        for (int i = 0; i < NI; ++i) a[n][i] = ldf(sn, fa[i], 0);
+        for (int m = 0; m < MF; ++m) {
+          const int i = m / NJ, j = m % NJ;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) b[n][j] = ldf(sn, fb[j], 0);
-      }
+          for (int x = 0; x < LPK; ++x)
+            if (m == x * MF / LPK + 1) {
+              __builtin_amdgcn_sched_barrier(0);
+              load1(ks * LPK + x, sl, k0);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+      } else {
+        // sixteen MFMAs; behind MFMA m: m % 3 != 2 -> the next fragment read (eight in all), m % 3 == 2 -> the next
+        // global -> LDS load (four), m >= 12 -> nothing
 #pragma unroll
-      for (int m = 0; m < MF; ++m) {
-        const int i = m / NJ, j = m % NJ;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
-#pragma unroll
-        for (int x = 0; x < LPK; ++x)
-          if (m == x * MF / LPK + 1) {
-            __builtin_amdgcn_sched_barrier(0);
-            load1(ks * LPK + x, sl, k0);
+        for (int m = 0; m < MF; ++m) {
+          const int i = m / NJ, j = m % NJ;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (m < 12) {
+            if (m % 3 == 2) {
+              load1(ks * LPK + m / 3, sl, k0);
+            } else {
+              // in the order the next step's MFMAs need them: A0, B0..B3 (MFMAs 0-3), then A1, A2, A3
+              const int f = m - m / 3;  // 0..7
+              if (f == 0) a[n][0] = ldf(src, fa[0], kn);
+              else if (f <= NJ) b[n][f - 1] = ldf(src, fb[f - 1], kn);
+              else a[n][f - NJ] = ldf(src, fa[f - NJ], kn);
+            }
             __builtin_amdgcn_sched_barrier(0);
           }
+        }
       }
     }
     // this wave's loads of stage st+2 have landed (those of stage st+3 may still be in flight); after the barrier
@@ -425,7 +459,198 @@ __global__ __launch_bounds__(512, 1) void gemm_dma_kernel(const bf16_t* __restri
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  big_epilogue<NJ, 64>(acc, ep, smem + (size_t)w * (DNS * DSTAGE / NW), i0 + 128 * wm, j0 + 64 * wn, l, I, J);
+  char* const est = smem + (size_t)w * (DNS * DSTAGE / NW);
+  if constexpr (NJ == 2) {
+    big_epilogue<2, 64>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn, l, I, J);
+  } else {
+    big_epilogue<2, 64, NJ, 0>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn, l, I, J);
+    big_epilogue<2, 64, NJ, 2>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn + 64, l, I, J);
+  }
+}
+
+// ---- the same product with 128-byte tile rows -----------------------------------------------------------------
+// 64 reduction elements per stage: a tile row is one whole 128-byte cache line, so a wave-wide global -> LDS load
+// touches 8 lines instead of 16 (the L2 -> compute-unit path moves whole lines half as often per byte).  An operand
+// tile of a stage is 256 rows x 128 bytes = 32 KB; LDS holds a ring of five such tiles (160 KB), filled in the order
+// A(0) B(0) A(1) B(1) A(2) ...  A stage's compute reads two of them; the other three are in flight or landed.
+// The stage barrier sits in front of a stage's LAST reduction step: by then the wave holds that step's fragments in
+// registers, so the barrier both publishes stage st+1 (this wave's loads of B(st+1) have landed, A(st+1) landed a
+// stage earlier) and frees the two tiles of stage st, into which B(st+2) and A(st+3) are loaded during the last step
+// of stage st and the first three of stage st+1; the first fragments of stage st+1 are read behind the barrier, under
+// the MFMAs of the last step.  Needs R % 64 == 0 and R >= 128.
+// What bounds it (four waves, 8192 x 4096 x 25088, 56 % of the nominal peak): with the global -> LDS loads taken out
+// of the main loop the MFMAs and fragment reads alone run at 74-80 %; with the loads in, 56 %, also when every load
+// hits the same cached 64 KB, no faster with half of the fragment reads removed, and SLOWER (52 %) with B fetched
+// through registers and written with ds_write_b128 so that only A uses the direct path.  So neither L2 / HBM, nor the
+// LDS reads, nor the direct path as such: it is the vector-memory instructions in the MFMA-issuing waves themselves
+// (16 KB of operands per 64 MFMAs and compute unit, whatever way they take).
+constexpr int EK = 64, EROWB = 128, ETILE = 256 * EROWB, ERING = 5;
+
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 1) void gemm_dma64_kernel(const bf16_t* __restrict__ A, int lda,
+                                                                const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep,
+                                                                int I, int J, int R, int tiles_i, int tiles_j,
+                                                                int splits, float* __restrict__ part) {
+  constexpr int WN = NW / 2, WCOLS = 256 / WN;
+  constexpr int NI = 4, NJ = WCOLS / 32, KS = EK / 16, MF = NI * NJ;
+  constexpr int QN = 32 / NW;              // wave-wide loads per wave and operand tile (4 or 8): 8 rows each
+  constexpr int LPK = 2 * QN / KS;         // loads behind the MFMAs of one reduction step (2 or 4)
+  __shared__ __attribute__((aligned(1024))) char smem[ERING * ETILE];
+  const int t = threadIdx.x, l = t & 63;
+  const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w / WN, wn = w % WN;
+  // splits > 1: the grid holds `splits` copies of the tile grid; copy z reduces its share of the stages and leaves an
+  // fp32 partial product in part[z][I][J] (no bias, activation or rounding: the reducing kernel applies them)
+  const int n_tiles = tiles_i * tiles_j;
+  const int z = blockIdx.x / n_tiles;
+  int bid = blockIdx.x - z * n_tiles;
+  {
+    const int per = n_tiles >> 3;
+    if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
+  }
+  int ti, tj;
+  {
+    constexpr int BAND = 4;
+    const int per_band = BAND * tiles_j, band = bid / per_band, rem = bid - band * per_band;
+    const int rows_in = tiles_i - band * BAND < BAND ? tiles_i - band * BAND : BAND;
+    ti = band * BAND + rem % rows_in;
+    tj = rem / rows_in;
+  }
+  const int i0 = ti * GM, j0 = tj * GN;
+  int T = R / EK;
+  if (splits > 1) {
+    const int s0 = (int)((long long)z * T / splits), s1 = (int)((long long)(z + 1) * T / splits);
+    A += (size_t)s0 * EK;
+    Bm += (size_t)s0 * EK;
+    T = s1 - s0;
+    ep.bias = nullptr; ep.mask = nullptr; ep.relu = 0; ep.out = nullptr; ep.upd_master = nullptr;
+    ep.out_f = part + (size_t)z * I * J;
+    ep.ldo = J;
+  }
+
+  // this lane's chunk in each of a tile's loads: 8 lanes per row, the XOR swizzle of the row's eight 16-byte slots
+  // applied on the global side; rows beyond the matrix are clamped (they only feed outputs that are never stored)
+  uint32_t offa[QN], offb[QN];
+#pragma unroll
+  for (int q = 0; q < QN; ++q) {
+    const int row = (q * NW + w) * 8 + (l >> 3), g = (l & 7) ^ (row & 7);
+    const int ra = i0 + row < I ? i0 + row : I - 1, rb = j0 + row < J ? j0 + row : J - 1;
+    offa[q] = ((uint32_t)ra * (uint32_t)lda + g * 8) * 2u;
+    offb[q] = ((uint32_t)rb * (uint32_t)ldb + g * 8) * 2u;
+  }
+  auto load_a = [&](int q, int slot, int stage) {
+    dma_load16(A + (stage < T ? stage : T - 1) * EK, offa[q], smem + slot * ETILE + (q * NW + w) * 1024);
+  };
+  auto load_b = [&](int q, int slot, int stage) {
+    dma_load16(Bm + (stage < T ? stage : T - 1) * EK, offb[q], smem + slot * ETILE + (q * NW + w) * 1024);
+  };
+
+  f32x16 acc[NI][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[i][j] = f32x16{0};
+  // byte offsets of this lane's fragments inside a tile for reduction step 0; step ks flips bits 5 and 6 by ks
+  int fa[NI], fb[NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int row = 128 * wm + 32 * i + (l & 31);
+    fa[i] = row * EROWB + (((l >> 5) ^ (row & 7)) << 4);
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int row = WCOLS * wn + 32 * j + (l & 31);
+    fb[j] = row * EROWB + (((l >> 5) ^ (row & 7)) << 4);
+  }
+  auto ldf = [&](const char* tile, int o, int ks) { return *reinterpret_cast<const uint4*>(tile + (o ^ (ks << 5))); };
+
+  // prologue: A(0) B(0) A(1) and the first half of B(1) (what the last step of a stage "-1" would have issued)
+#pragma unroll
+  for (int q = 0; q < QN; ++q) load_a(q, 0, 0);
+#pragma unroll
+  for (int q = 0; q < QN; ++q) load_b(q, 1, 0);
+#pragma unroll
+  for (int q = 0; q < QN; ++q) load_a(q, 2, 1);
+#pragma unroll
+  for (int q = 0; q < LPK; ++q) load_b(q, 3, 1);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(QN + LPK) : "memory");  // A(0) and B(0) have landed
+  __syncthreads();
+  uint4 a[2][NI], b[2][NJ];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) a[0][i] = ldf(smem, fa[i], 0);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) b[0][j] = ldf(smem + ETILE, fb[j], 0);
+  int sa = 0;  // ring slot of A(st); B(st) is the next one, A(st+1) the one after, ...
+  auto ring = [](int x) { return x >= ERING ? x - ERING : x; };
+  for (int st = 0; st < T; ++st) {
+    const int sb = ring(sa + 1), sa1 = ring(sa + 2), sb1 = ring(sa + 3), sa2 = ring(sa + 4);
+    const char* ta = smem + sa * ETILE;
+    const char* tb = smem + sb * ETILE;
+    const char* ta1 = smem + sa1 * ETILE;
+    const char* tb1 = smem + sb1 * ETILE;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const int c = ks & 1, n = c ^ 1;
+      if (ks == KS - 1) {
+        // this wave holds its last fragments of stage st; its loads of B(st+1) have landed (A(st+2)'s may be in flight)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(QN) : "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+      }
+      const char* pa = ks + 1 < KS ? ta : ta1;  // where the next step's fragments lie
+      const char* pb = ks + 1 < KS ? tb : tb1;
+      const int kn = ks + 1 < KS ? ks + 1 : 0;
+      if constexpr (NW == 8) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i) a[n][i] = ldf(pa, fa[i], kn);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[n][j] = ldf(pb, fb[j], kn);
+      }
+#pragma unroll
+      for (int m = 0; m < MF; ++m) {
+        const int i = m / NJ, j = m % NJ;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
+        int x = -1;  // which of the step's loads goes behind this MFMA (-1: none)
+        if constexpr (NW == 8) {
+          if (m == 1) x = 0;
+          if (m == 5) x = 1;
+        } else {
+          __builtin_amdgcn_sched_barrier(0);
+          if (m < 12) {
+            if (m % 3 == 2) {
+              x = m / 3;
+            } else {
+              const int f = m - m / 3;  // 0..7, in the order the next step's MFMAs need them: A0, B0..B3, A1..A3
+              if (f == 0) a[n][0] = ldf(pa, fa[0], kn);
+              else if (f <= NJ) b[n][f - 1] = ldf(pb, fb[f - 1], kn);
+              else a[n][f - NJ] = ldf(pa, fa[f - NJ], kn);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
+        }
+        if (x >= 0) {
+          __builtin_amdgcn_sched_barrier(0);
+          // Loads between two barriers, in issue order: B(s+1) first half (last step of stage s-1), B(s+1) second
+          // half (step 0 of stage s), A(s+2) first half (step 1), A(s+2) second half (step 2).  With sa the slot of
+          // A(st): B(st+1) lives in ring(sa + 3), A(st+2) in ring(sa + 4), B(st+2) in ring(sa + 5) = sa.
+          if (ks == KS - 1) load_b(x, sa, st + 2);
+          else if (ks == 0) load_b(LPK + x, sb1, st + 1);
+          else if (ks == 1) load_a(x, sa2, st + 2);
+          else load_a(LPK + x, sa2, st + 2);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+    sa = sa1;
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  char* const est = smem + (size_t)w * (ERING * ETILE / NW);
+  if constexpr (NJ == 2) {
+    big_epilogue<2, 64>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn, l, I, J);
+  } else {
+    big_epilogue<2, 64, NJ, 0>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn, l, I, J);
+    big_epilogue<2, 64, NJ, 2>(acc, ep, est, i0 + 128 * wm, j0 + WCOLS * wn + 64, l, I, J);
+  }
 }
 
 // ---- both operands stored with the reduction index as their slow axis (the weight gradient) --------------------
@@ -585,16 +810,21 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
 // Needs R % 32 == 0.
 __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restrict__ A, int lda,
                                                          const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep, int I,
-                                                         int J, int R, int tiles_i, int tiles_j) {
+                                                         int J, int R, int tiles_i, int tiles_j, int splits,
+                                                         float* __restrict__ part) {
   constexpr int NW = 8, NI = 4, NJ = 2, KS = DK / 16, NS = 4, D = NS - 1;
   constexpr int ATILE = 256 * DROWB, BROWB = 512, BTILE = DK * BROWB, STAGE = ATILE + BTILE;  // 16 KB + 16 KB
   constexpr int QA = 2, QB = 2, LPS = QA + QB, MF = NI * NJ;
   __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
   const int t = threadIdx.x, l = t & 63;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
-  int bid = blockIdx.x;
+  // splits > 1: the grid holds `splits` copies of the tile grid; copy z reduces its share of the stages and leaves an
+  // fp32 partial product in part[z][I][J] (no bias, activation or rounding: the reducing kernel applies them)
+  const int n_tiles = tiles_i * tiles_j;
+  const int z = blockIdx.x / n_tiles;
+  int bid = blockIdx.x - z * n_tiles;
   {
-    const int per = gridDim.x >> 3;
+    const int per = n_tiles >> 3;
     if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
   }
   int ti, tj;
@@ -606,7 +836,16 @@ __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restric
     tj = rem / rows_in;
   }
   const int i0 = ti * GM, j0 = tj * GN;
-  const int T = R / DK;
+  int T = R / DK;
+  if (splits > 1) {
+    const int s0 = (int)((long long)z * T / splits), s1 = (int)((long long)(z + 1) * T / splits);
+    A += (size_t)s0 * DK;
+    Bm += (size_t)s0 * DK * ldb;
+    T = s1 - s0;
+    ep.bias = nullptr; ep.mask = nullptr; ep.relu = 0; ep.out = nullptr; ep.upd_master = nullptr;
+    ep.out_f = part + (size_t)z * I * J;
+    ep.ldo = J;
+  }
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_tn_zero);
 
   uint32_t aoffs[QA];  // A: byte offset of this lane's chunk, rows clamped (they only feed outputs never stored)
@@ -785,30 +1024,57 @@ __global__ __launch_bounds__(256) void colsum_kernel(const bf16_t* __restrict__ 
   out[n] = s;
 }
 
-int g_big_waves = 8;
+// Variant of the forward product.  Measured at 8192 x 4096 (MI355X, % of the nominal bf16 peak): reduction 25088 --
+// 64-byte rows, 8 waves 44-48; 128-byte rows, 8 waves 49-53; 128-byte rows, 4 waves 55-56.  Reduction 4096 -- 46-48;
+// 48-50; 45.  Hence four waves from a reduction length of 8192 on.
+int g_big_waves = 0;        // 0: by reduction length; 4 or 8: forced
+int g_big_row_bytes = 128;  // LDS tile rows of the forward product: 128 (64 reduction elements per stage) or 64
+constexpr int kFourWaveMinR = 8192;
 bool g_wgrad_tn = true;
 
+// splits > 1 (with `part`, splits * I * J floats): only the 128-byte-row forward kernel can split its reduction;
+// hipErrorInvalidValue if the shape does not let it run.
 template <bool TA, bool TB>
 hipError_t launch_big(hipStream_t s, const bf16_t* a, int lda, const bf16_t* b, int ldb, const BigEpilogue& ep, int I,
-                      int J, int R) {
+                      int J, int R, int splits = 1, float* part = nullptr) {
   dim3 grid((J + GN - 1) / GN, (I + GM - 1) / GM);
   if (!TA && !TB && R >= DK && (R % 8) == 0 && (lda % 8) == 0 && (ldb % 8) == 0 &&
       ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0 &&
       (size_t)I * lda < ((size_t)1 << 31) && (size_t)J * ldb < ((size_t)1 << 31)) {  // 32-bit byte offsets
-    gemm_dma_kernel<<<grid.x * grid.y, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R, (int)grid.y, (int)grid.x);
+    const bool wide_rows = (g_big_row_bytes == 128 || splits > 1) && (R % EK) == 0 && R >= 2 * EK * splits;
+    if (splits > 1 && !wide_rows) return hipErrorInvalidValue;
+    // four waves (one per SIMD) pay off when the reduction is long enough to amortise their slower start and end
+    const int waves = g_big_waves ? g_big_waves : ((wide_rows && R / splits >= kFourWaveMinR) ? 4 : 8);
+    const unsigned n = grid.x * grid.y * (unsigned)splits;
+    const int ty = (int)grid.y, tx = (int)grid.x;
+    if (wide_rows && waves == 4) gemm_dma64_kernel<4><<<n, 256, 0, s>>>(a, lda, b, ldb, ep, I, J, R, ty, tx, splits, part);
+    else if (wide_rows) gemm_dma64_kernel<8><<<n, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R, ty, tx, splits, part);
+    else if (waves == 4) gemm_dma_kernel<4><<<n, 256, 0, s>>>(a, lda, b, ldb, ep, I, J, R, ty, tx);
+    else gemm_dma_kernel<8><<<n, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R, ty, tx);
     return hipGetLastError();
   }
-  if (g_big_waves == 8) gemm_big_kernel<TA, TB, 8><<<grid, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R);
+  if (splits > 1) return hipErrorInvalidValue;
+  if (g_big_waves != 4) gemm_big_kernel<TA, TB, 8><<<grid, 512, 0, s>>>(a, lda, b, ldb, ep, I, J, R);
   else gemm_big_kernel<TA, TB, 4><<<grid, 256, 0, s>>>(a, lda, b, ldb, ep, I, J, R);
   return hipGetLastError();
 }
 
 }  // namespace
 
+int set_big_gemm_waves(int waves) {
+  const int old = g_big_waves + (g_big_row_bytes == 64 ? 100 : 0);
+  switch (waves) {
+    case 0: case 4: case 8: g_big_waves = waves; g_big_row_bytes = 128; break;
+    case 104: case 108: g_big_waves = waves - 100; g_big_row_bytes = 64; break;
+    default: break;
+  }
+  return old;
+}
+
 hipError_t linear_fwd_big_bf16(hipStream_t s, const bf16_t* x, int ldx, const bf16_t* w, const bf16_t* b, bf16_t* y,
-                               float* y_f32, int M, int N, int K, bool relu) {
+                               float* y_f32, int M, int N, int K, bool relu, int splits, float* part) {
   BigEpilogue ep = {b, nullptr, relu ? 1 : 0, y, y_f32, N};
-  return launch_big<false, false>(s, x, ldx, w, K, ep, M, N, K);
+  return launch_big<false, false>(s, x, ldx, w, K, ep, M, N, K, splits, part);
 }
 
 // Operands stored sideways go through a transposing pre-pass when the caller provides scratch: the 2x8-block
@@ -817,15 +1083,20 @@ hipError_t linear_fwd_big_bf16(hipStream_t s, const bf16_t* x, int ldx, const bf
 size_t linear_dgrad_big_scratch_bytes(int N, int K) { return (size_t)N * K * sizeof(bf16_t); }
 size_t linear_wgrad_big_scratch_bytes(int M, int N, int K) { return (size_t)M * ((size_t)N + K) * sizeof(bf16_t); }
 
+// splits > 1: the reduction (over the N out-features) is split; `scratch` then receives splits * M * K floats of
+// partial products instead of serving as room for transposed weights, and mask / dx are not touched (the reducing
+// kernel applies them); hipErrorInvalidValue if the shape does not allow the kernel that can do that.
 hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
-                                 int N, int K, void* scratch, size_t scratch_bytes) {
+                                 int N, int K, void* scratch, size_t scratch_bytes, int splits) {
   BigEpilogue ep = {nullptr, mask, 0, dx, nullptr, K};
   if (g_wgrad_tn && (N % DK) == 0 && (K % 8) == 0 && ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(w)) & 15) == 0 &&
-      (size_t)M * N < ((size_t)1 << 31)) {  // w as stored: transposing LDS reads on the B side
+      (size_t)M * N < ((size_t)1 << 31) && N / DK >= 4 * splits) {  // w as stored: transposing LDS reads on the B side
     const int ti = (M + GM - 1) / GM, tj = (K + GN - 1) / GN;
-    gemm_nt_kernel<<<ti * tj, 512, 0, s>>>(dz, N, w, K, ep, M, K, N, ti, tj);
+    if (splits > 1 && (!scratch || scratch_bytes < (size_t)splits * M * K * sizeof(float))) return hipErrorInvalidValue;
+    gemm_nt_kernel<<<ti * tj * splits, 512, 0, s>>>(dz, N, w, K, ep, M, K, N, ti, tj, splits, static_cast<float*>(scratch));
     return hipGetLastError();
   }
+  if (splits > 1) return hipErrorInvalidValue;
   if (scratch && M >= 2048 && scratch_bytes >= linear_dgrad_big_scratch_bytes(N, K)) {  // worth a pass over w
     bf16_t* wt = static_cast<bf16_t*>(scratch);  // [K][N]
     hipError_t e = transpose_bf16(s, w, wt, N, K);

@@ -50,16 +50,22 @@ hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, c
 // Output tiles (256 x 256) from which forward/dgrad go to the compute-bound kernels below (default 128: half the
 // chip's compute units); returns the previous value, values < 1 only query.
 int set_big_tile_threshold(int min_tiles);
+// Variant of the large-tile forward product: 0 = chosen by reduction length (the default); 4 = four waves of 128 x 128
+// outputs; 8 = eight waves of 128 x 64; 104 / 108 = the same with 64-byte instead of 128-byte LDS tile rows.  Returns the
+// old value in the same encoding.
+int set_big_gemm_waves(int waves);
 // Compute-bound versions for many rows (gemm_big_bf16.hip; 256 x 256 tiles, no split-K, no workspace):
 //   fwd: y = act(x w^T + b) (x row stride ldx; bf16 y or fp32 y_f32);  dgrad: dx = (dz w) .* mask;
 //   wgrad: dw[N][K] = dz^T x as fp32, db[N] = column sums of dz (db may be null).
+// splits > 1: the reduction is split that many ways and the fp32 partial products go to part[splits][M][N] (b, y, y_f32,
+// relu are then not used; the caller adds the parts up); hipErrorInvalidValue if the shape does not allow it.
 hipError_t linear_fwd_big_bf16(hipStream_t s, const bf16_t* x, int ldx, const bf16_t* w, const bf16_t* b, bf16_t* y,
-                               float* y_f32, int M, int N, int K, bool relu);
+                               float* y_f32, int M, int N, int K, bool relu, int splits, float* part);
 // dgrad and wgrad read an operand sideways; given scratch of the stated size they transpose it first (faster).
 size_t linear_dgrad_big_scratch_bytes(int N, int K);
 size_t linear_wgrad_big_scratch_bytes(int M, int N, int K);
 hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
-                                 int N, int K, void* scratch, size_t scratch_bytes);
+                                 int N, int K, void* scratch, size_t scratch_bytes, int splits);
 hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* dw, float* db, int M, int N,
                                  int K, void* scratch, size_t scratch_bytes);
 

@@ -2059,6 +2059,8 @@ int pd_set_big_tile_threshold(int32_t min_tiles) {
   return pd::set_big_tile_threshold(min_tiles);
 }
 
+int pd_set_big_gemm_waves(int32_t waves) { return pd::set_big_gemm_waves(waves); }
+
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) { return pd::gemm_bf16_workspace_bytes(M, N, K); }
 
 static int check_gemm(const void* a, const void* b, const void* c, int M, int N, int K) {

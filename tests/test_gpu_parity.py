@@ -33,7 +33,9 @@ def _bf(a):
 SHAPES = [(64, 128, 64), (64, 256, 4096), (64, 200, 264), (40, 136, 72), (1, 8, 8), (130, 1000, 520),
           (64, 4096, 1024), (96, 24, 2048), (256, 512, 768),
           (50, 1000, 1536), (64, 72, 512), (1, 8, 1024),   # reduction a multiple of 128: the direct-to-LDS forward
-          (512, 256, 256), (600, 1000, 520), (1030, 264, 136)]     # >= 512 rows: the 256 x 256-tile weight gradient
+          (512, 256, 256), (600, 1000, 520), (1030, 264, 136),     # >= 512 rows: the 256 x 256-tile weight gradient
+          # many rows, a long reduction, too few 256 x 256 tiles to fill the chip: large tiles with a split reduction
+          (600, 1000, 4096), (300, 264, 2112), (1030, 2048, 520), (257, 4096, 4096)]
 # the same products forced onto the large-tile kernels (threshold 1 tile): several tiles, ragged rows/columns, a
 # reduction length that is a multiple of 32, one that is not, one shorter than a stage
 BIG_SHAPES = [(512, 256, 256), (600, 1000, 520), (1030, 264, 136), (300, 520, 1000), (257, 8, 24), (700, 776, 4128), (2080, 264, 136)]
@@ -49,6 +51,19 @@ def big_tiles():
 @pytest.mark.parametrize("M,N,K", BIG_SHAPES)
 def test_linear_fwd_bf16_big_tiles(M, N, K, big_tiles):
     test_linear_fwd_bf16(M, N, K)
+
+
+# every variant of the large-tile forward kernel (pd_set_big_gemm_waves): four / eight waves, 128- / 64-byte LDS rows;
+# reductions that are a multiple of 64 (the 128-byte-row kernels), a multiple of 32 only, and ragged; ragged rows / columns
+@pytest.mark.parametrize("variant", [4, 8, 104, 108])
+@pytest.mark.parametrize("M,N,K", [(600, 1000, 512), (300, 520, 1088), (2080, 264, 136), (257, 8, 128), (700, 776, 4128),
+                                   (512, 256, 8192 + 64)])
+def test_linear_fwd_bf16_big_tile_variants(M, N, K, variant, big_tiles):
+    old = pd.pd_set_big_gemm_waves(variant)
+    try:
+        test_linear_fwd_bf16(M, N, K)
+    finally:
+        pd.pd_set_big_gemm_waves(old)
 
 
 @pytest.mark.parametrize("M,N,K", BIG_SHAPES)
