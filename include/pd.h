@@ -150,6 +150,18 @@ typedef struct {
   int32_t replicas;           /* 0 or 1: an ordinary stage.  2..8: the stage is replicated (Section 3.3); this
                                  object is its primary replica and keeps a gradient buffer of one parameter set;
                                  see pd_stage_create_replica and pd_update_replicated.  Not with vertical_sync  */
+  void* stream_backward;      /* NULL: every kernel of the stage runs on `stream`.  Otherwise a second hipStream_t
+                                 (borrowed, default priority, not `stream`) on which the kernels of pd_backward run.
+                                 In the 1F1B order F(k + depth) is followed by B(k + 1), and the two do not depend
+                                 on each other: with a stream of its own the backward pass runs next to that forward
+                                 pass instead of behind it.  The library orders what it must with events: a backward
+                                 pass starts after the update before it (whose operands it overwrites) and after its
+                                 minibatch's forward pass; pd_update starts after the backward pass.  Results are the
+                                 same bit for bit.  What pd_backward reads from the caller (dy_dev) must be complete,
+                                 or ordered by the caller on stream_backward, when it is called; what it writes
+                                 (dx_dev) is complete on stream_backward, and on `stream` after the following
+                                 pd_update.  Such a stage cannot be captured into a HIP graph, profiled per layer
+                                 (pd_stage_profile) or replicated.                                              */
 } pd_stage_config;
 
 /* --- schedule (pure host, no GPU touched) -------------------------------------------------

@@ -58,7 +58,7 @@ class pd_stage_config(C.Structure):
                 ("in_flight_override", C.c_int32), ("minibatch", C.c_int32), ("precision", C.c_int32),
                 ("lr", C.c_float), ("momentum", C.c_float), ("n_layers", C.c_int32),
                 ("layers", C.POINTER(pd_layer_desc)), ("stream", C.c_void_p), ("vertical_sync", C.c_int32),
-                ("optimizer", C.c_int32), ("eps", C.c_float), ("replicas", C.c_int32)]
+                ("optimizer", C.c_int32), ("eps", C.c_float), ("replicas", C.c_int32), ("stream_backward", C.c_void_p)]
 
 
 _vp, _sz, _i32, _f32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_float
@@ -236,10 +236,11 @@ def layer_descs(layers: Sequence[tuple], in_hw=None):
 
 def make_config(layers, *, stage_index=0, num_stages=1, noam=1, in_flight_override=0, minibatch=1,
                 precision=PD_F32, lr=0.01, momentum=0.9, stream=0, in_hw=None, vertical_sync=False,
-                optimizer=PD_OPT_SGD_MOMENTUM, eps=0.0, replicas=0):
+                optimizer=PD_OPT_SGD_MOMENTUM, eps=0.0, replicas=0, stream_backward=0):
     descs = layer_descs(layers, in_hw)
     cfg = pd_stage_config(stage_index, num_stages, noam, in_flight_override, minibatch, precision, lr, momentum,
-                          len(descs), descs, stream, 1 if vertical_sync else 0, optimizer, eps, replicas)
+                          len(descs), descs, stream, 1 if vertical_sync else 0, optimizer, eps, replicas,
+                          stream_backward or None)
     cfg._keepalive = descs
     return cfg
 

@@ -146,6 +146,7 @@ typedef Layer Linear;  // (historic name used below for "a layer")
 
 struct InFlight {
   int mb, version;
+  bool update_since_forward;  // an update has been enqueued on the stage's stream after this minibatch's forward pass
 };
 
 }  // namespace
@@ -161,6 +162,20 @@ struct pd_stage {
   int classes = 0;
   pd::UpdateRule rule = {0.f, 0.f, 0.f, 0};
   hipStream_t stream = nullptr;
+  // Backward lane (cfg.stream_backward): the kernels of pd_backward run on stream_b, next to the forward pass that the
+  // 1F1B order places before them.  ev_upd: the last update on `stream` is done (the backward pass overwrites what it
+  // read); ev_bwd: the last backward pass on stream_b is done (the update reads what it wrote); ev_fork: scratch
+  // event for "everything enqueued on `stream` so far".  ws_b: the lane's own split-K workspace.
+  hipStream_t stream_b = nullptr;
+  hipEvent_t ev_upd = nullptr, ev_bwd = nullptr, ev_fork = nullptr;
+  bool upd_recorded = false;
+  float* ws_b = nullptr;
+  hipStream_t bstream() const { return stream_b ? stream_b : stream; }
+  hipError_t sync_all() const {
+    hipError_t e = hipStreamSynchronize(stream);
+    if (e == hipSuccess && stream_b) e = hipStreamSynchronize(stream_b);
+    return e;
+  }
   std::vector<Linear> lin;
   size_t esz = 4;
   size_t n_params = 0;       // flat length
@@ -266,7 +281,8 @@ struct Plan {
   size_t o_rem = 0;
   bool any_split = false;
   size_t o_ring = 0, o_master = 0, o_mom = 0, o_in = 0, o_stash = 0, o_dz = 0, o_grad = 0, o_ws = 0, o_rowloss = 0;
-  size_t o_pp = 0, o_part = 0, o_wt = 0, o_gradbuf = 0;
+  size_t o_pp = 0, o_part = 0, o_wt = 0, o_gradbuf = 0, o_ws_b = 0;
+  bool lane_b = false;
   int replicas = 1;
   size_t total = 0;
 };
@@ -278,6 +294,9 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
   p.replicas = c->replicas > 1 ? c->replicas : 1;
   if (p.replicas > 1 && c->vertical_sync) return fail(PD_EINVAL, "vertical sync is not available for a replicated stage");
   if (secondary && p.replicas < 2) return fail(PD_EINVAL, "the stage is not configured as replicated");
+  p.lane_b = c->stream_backward != nullptr;
+  if (p.lane_b && p.replicas > 1) return fail(PD_EINVAL, "a replicated stage cannot have a backward stream of its own");
+  if (p.lane_b && c->stream_backward == c->stream) return fail(PD_EINVAL, "stream_backward must differ from stream (or be null)");
   if (c->optimizer != PD_OPT_SGD_MOMENTUM && c->optimizer != PD_OPT_RMSPROP) return fail(PD_EINVAL, "unknown optimizer %d", c->optimizer);
   if (c->optimizer == PD_OPT_RMSPROP && !(c->eps > 0.f)) return fail(PD_EINVAL, "RMSProp needs eps > 0");
   if (c->num_stages < 1 || c->stage_index < 0 || c->stage_index >= c->num_stages)
@@ -553,6 +572,7 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
   p.o_dz = o; o += p.dz_bytes;
   if (!p.has_loss) { p.o_grad = o; o += 2 * p.out_bytes; }
   p.o_ws = o; o += p.ws_bytes;
+  if (p.lane_b) { p.o_ws_b = o; o += p.ws_bytes; }
   p.o_pp = o; o += 2 * p.pp_bytes;
   p.o_part = o; o += p.part_bytes;
   p.o_wt = o; o += p.wt_bytes;
@@ -613,6 +633,10 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
   st->in_ring = a + p.o_in; st->stash = a + p.o_stash; st->dz = a + p.o_dz;
   st->grad_in = p.has_loss ? nullptr : a + p.o_grad;
   st->ws = reinterpret_cast<float*>(a + p.o_ws); st->ws_bytes = p.ws_bytes;
+  if (p.lane_b && !primary) {
+    st->stream_b = static_cast<hipStream_t>(cfg->stream_backward);
+    st->ws_b = reinterpret_cast<float*>(a + p.o_ws_b);
+  }
   st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
   st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
   st->blk_dy = a + p.o_blk_dy; st->blk_dx = a + p.o_blk_dx; st->blk_dx_stride = p.blk_dx_stride;
@@ -621,6 +645,8 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
   // padding between layers inside the gradient buffer is never written by a gradient kernel: keep it at zero
   if (e == hipSuccess && st->gradbuf) e = pd::fill_zero(st->stream, st->gradbuf, p.p_pad * 4);
   if (e == hipSuccess && st->gradbuf) e = hipEventCreateWithFlags(&st->ev_rep, hipEventDisableTiming);
+  for (hipEvent_t* ev : {&st->ev_upd, &st->ev_bwd, &st->ev_fork})
+    if (e == hipSuccess && st->stream_b) e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
   for (int d = 0; d < st->depth && e == hipSuccess; ++d)
     for (const Linear& L : st->lin)
       if (L.kind == K_LSTM && e == hipSuccess) {
@@ -629,7 +655,8 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
         if (e == hipSuccess) e = pd::fill_zero(st->stream, slot + L.c_off, (size_t)st->B * L.out * 4);
       }
   if (e != hipSuccess) {
-    if (st->ev_rep) (void)hipEventDestroy(st->ev_rep);
+    for (hipEvent_t ev : {st->ev_rep, st->ev_upd, st->ev_bwd, st->ev_fork})
+      if (ev) (void)hipEventDestroy(ev);
     delete st;
     return fail(PD_EHIP, "clearing momentum and initial states: %s", hipGetErrorString(e));
   }
@@ -729,7 +756,8 @@ int pd_stage_destroy(pd_stage* st) {
     auto& v = st->primary->secondaries;
     v.erase(std::remove(v.begin(), v.end(), st), v.end());
   }
-  if (st->ev_rep) (void)hipEventDestroy(st->ev_rep);
+  for (hipEvent_t ev : {st->ev_rep, st->ev_upd, st->ev_bwd, st->ev_fork})
+    if (ev) (void)hipEventDestroy(ev);
   for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u, &st->mark_pool})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   for (const pd_stage::Mark& m : st->marks) (void)hipEventDestroy(m.ev);
@@ -782,9 +810,9 @@ int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   if (check_stage(st) || !host_params) return fail(PD_EINVAL, "null argument");
   if (check_owner(st)) return PD_ESTATE;
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu parameters, got %zu", st->n_params, n);
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   for (pd_stage* r : st->secondaries) {  // they read the same weights and restart with them
-    PD_HIP(hipStreamSynchronize(r->stream));
+    PD_HIP(r->sync_all());
     r->latest = 0; r->last_fwd = -1; r->in_flight.clear(); r->grad_pending = false; r->trace.clear();
   }
   float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(st->ring);
@@ -800,7 +828,7 @@ int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   }
   if (st->rem) PD_HIP(split_master_from_staging(st, 0));  // ring slot 0 = version 0
   PD_HIP(pd::fill_zero(st->stream, st->mom, st->p_pad * 4));
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   st->latest = 0; st->last_fwd = -1; st->in_flight.clear(); st->grad_pending = false; st->trace.clear();
   return PD_OK;
 }
@@ -811,11 +839,11 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
   if (version < 0) version = st->latest;
   if (version > st->latest || version <= st->latest - st->ring_depth)
     return fail(PD_ESTATE, "version %d is not in the ring (latest %d, depth %d)", version, st->latest, st->ring_depth);
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   const bool from_master = st->bf16 && version == st->latest && !ring_copy;
   if (from_master && st->rem) {
     PD_HIP(materialize_master(st));
-    PD_HIP(hipStreamSynchronize(st->stream));
+    PD_HIP(st->sync_all());
   }
   if (!st->bf16 || from_master) {
     const float* src = from_master ? st->master : reinterpret_cast<const float*>(st->ring_slot(version));
@@ -861,7 +889,7 @@ int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n) {
   if (check_owner(st)) return PD_ESTATE;
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "minibatches in flight");
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   for (const Linear& L : st->lin) {
     if (!L.n_w) continue;
     PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, L.n_w * 4, hipMemcpyHostToDevice));
@@ -873,7 +901,7 @@ int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n) {
 int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n) {
   if (check_stage(st) || !host_out) return fail(PD_EINVAL, "null argument");
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   for (const Linear& L : st->lin) {
     if (!L.n_w) continue;
     PD_HIP(hipMemcpy(host_out + L.flat_w, st->mom + L.w_off, L.n_w * 4, hipMemcpyDeviceToHost));
@@ -992,11 +1020,11 @@ int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const floa
   if (check_owner(st)) return PD_ESTATE;
   for (pd_stage* r : st->secondaries) {
     if (r->grad_pending) return fail(PD_ESTATE, "a gradient is pending on a replica: call pd_update_replicated first");
-    PD_HIP(hipStreamSynchronize(r->stream));
+    PD_HIP(r->sync_all());
   }
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   if (st->grad_pending) return fail(PD_ESTATE, "a gradient is pending: call pd_update first");
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   char* slot = st->ring_slot(st->latest);
   float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(slot);
   for (const Linear& L : st->lin) {
@@ -1016,7 +1044,7 @@ int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const floa
     }
   }
   if (host_params && st->rem) PD_HIP(split_master_from_staging(st, st->latest));
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   return PD_OK;
 }
 
@@ -1100,7 +1128,7 @@ int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer
       return fail(PD_EINVAL, "unknown tensor selector %d", what);
   }
   if (n != cnt) return fail(PD_EINVAL, "tensor has %zu elements, caller gave %zu", cnt, n);
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   if (!st->bf16 || (what == 0 && st->has_loss && layer == nl - 1)) {  // logits are fp32 in either mode
     PD_HIP(hipMemcpy(host_out, src, cnt * 4, hipMemcpyDeviceToHost));
     return PD_OK;
@@ -1133,7 +1161,7 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
     return fail(PD_EINVAL, "unknown tensor selector %d", what);
   }
   if (n != cnt) return fail(PD_EINVAL, "tensor has %zu elements, caller gave %zu", cnt, n);
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   if (as_f32) {
     PD_HIP(hipMemcpy(dst, host_in, cnt * 4, hipMemcpyHostToDevice));
     return PD_OK;
@@ -1265,7 +1293,7 @@ static int forward_impl(pd_stage* st, int32_t mb_id, int32_t version, const void
     PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->lin.back().rows * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
   PD_HIP(st->mark(0, (int)st->lin.size() - 1));  // (the loss and the copy of the output count for the last layer)
   if (st->profiling) ++st->prof_ops[0];
-  st->in_flight.push_back({mb_id, v});
+  st->in_flight.push_back({mb_id, v, false});
   st->last_fwd = mb_id;
   st->log_op(PD_OP_F, mb_id, v);
   return PD_OK;
@@ -1296,7 +1324,19 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
   if (st->has_loss && dy_dev) return fail(PD_EINVAL, "dy_dev must be NULL on a stage that ends in the loss");
   if (!st->has_loss && !dy_dev) return fail(PD_EINVAL, "dy_dev is null");
 
-  hipStream_t s = st->stream;
+  hipStream_t s = st->bstream();
+  if (st->stream_b) {
+    // Backward lane: this pass needs its minibatch's forward pass and, because it overwrites the gradient buffers the
+    // last update read, that update.  If an update has been enqueued since the forward pass, the update's event covers
+    // both (they are on one stream, in that order); otherwise wait for everything enqueued on the stage's stream so far.
+    if (st->in_flight.front().update_since_forward && st->upd_recorded) {
+      PD_HIP(hipStreamWaitEvent(s, st->ev_upd, 0));
+    } else {
+      PD_HIP(hipEventRecord(st->ev_fork, st->stream));
+      PD_HIP(hipStreamWaitEvent(s, st->ev_fork, 0));
+    }
+  }
+  float* const ws = st->ws_b ? st->ws_b : st->ws;  // (the lane's own split-K workspace: a forward pass may be running)
   const int v = st->in_flight.front().version;  // the version this minibatch's forward read
   const char* w = st->ring_slot(v);
   char* slot = st->stash_slot(mb_id);
@@ -1400,7 +1440,7 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
         const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
         PD_HIP(pd::linear_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur), wp + L.w_off,
                                      reinterpret_cast<const pd::bf16_t*>(mask), reinterpret_cast<pd::bf16_t*>(out),
-                                     L.rows, L.out, L.in, st->ws, st->ws_bytes));
+                                     L.rows, L.out, L.in, ws, st->ws_bytes));
       } else {
         const float* wp = reinterpret_cast<const float*>(w);
         PD_HIP(pd::linear_dgrad_f32(s, reinterpret_cast<const float*>(cur), wp + L.w_off,
@@ -1413,7 +1453,7 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
       const pd::bf16_t* whh = wih + (size_t)4 * L.out * L.in;
       PD_HIP(pd::linear_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(st->dz + L.dz_off), wih,
                                    reinterpret_cast<const pd::bf16_t*>(mask), reinterpret_cast<pd::bf16_t*>(out), L.rows,
-                                   4 * L.out, L.in, st->ws, st->ws_bytes));
+                                   4 * L.out, L.in, ws, st->ws_bytes));
       (void)whh;
     } else if (L.kind == K_CONV) {
       const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
@@ -1456,6 +1496,7 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
   }
   PD_HIP(st->mark(1, prof_l));
   if (st->profiling) ++st->prof_ops[1];
+  if (st->stream_b) PD_HIP(hipEventRecord(st->ev_bwd, s));
   st->in_flight.pop_front();  // stash slot released; the factored gradient stays valid until pd_update
   st->grad_pending = true;
   st->pending_mb = mb_id;
@@ -1477,6 +1518,7 @@ namespace {
 // fp32 gradient in st->gradbuf, laid out like a parameter set, and change nothing else.
 int run_update_kernels(pd_stage* st, int nv, bool grad_only) {
   hipStream_t s = st->stream;
+  if (st->stream_b) PD_HIP(hipStreamWaitEvent(s, st->ev_bwd, 0));  // the pending gradient was formed on the backward lane
   const int mb = st->pending_mb;
   char* slot = st->stash_slot(mb);
   const int nl = (int)st->lin.size();
@@ -1600,6 +1642,11 @@ int pd_update(pd_stage* st) {
   if (ring_slot_is_free(st, nv)) return PD_ESTATE;
   const int rc = run_update_kernels(st, nv, false);
   if (rc != PD_OK) return rc;
+  if (st->stream_b) {
+    PD_HIP(hipEventRecord(st->ev_upd, st->stream));
+    st->upd_recorded = true;
+    for (InFlight& f : st->in_flight) f.update_since_forward = true;
+  }
   st->latest = nv;
   st->grad_pending = false;
   st->log_op(PD_OP_U, st->pending_mb, nv);
@@ -1662,6 +1709,7 @@ int pd_update_replicated(pd_stage* const* replicas, int32_t n_replicas) {
 // ---- layer profiler (Section 3.2, "Profiling the DNN model") ---------------------------------------------
 int pd_stage_profile(pd_stage* st, int32_t enable) {
   if (check_stage(st)) return PD_EINVAL;
+  if (enable && st->stream_b) return fail(PD_ESTATE, "the layer profiler times one stream: not for a stage with a backward stream of its own");
   if (enable) {
     for (const pd_stage::Mark& m : st->marks) st->mark_pool.push_back(m.ev);
     st->marks.clear();
@@ -1704,7 +1752,7 @@ int pd_stage_profile_read(pd_stage* st, pd_layer_profile* out, size_t cap, size_
   if (n_out) *n_out = units.size();
   if (units.size() > cap) return fail(PD_ENOMEM, "profile has %zu units, capacity %zu", units.size(), cap);
   if (!out) return fail(PD_EINVAL, "out is null");
-  PD_HIP(hipStreamSynchronize(st->stream));
+  PD_HIP(st->sync_all());
   // parameters updated by the one multi-layer launch: its time is shared out by parameter count (the launch
   // streams master weights and momentum once, so its time is proportional to them)
   double batch_params = 0;
@@ -1747,6 +1795,7 @@ int refuse_capture(pd_stage* const* stages, int n) {
   for (int k = 0; k < n; ++k) {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     PD_HIP(hipStreamIsCapturing(stages[k]->stream, &cs));
+    if (cs == hipStreamCaptureStatusNone && stages[k]->stream_b) PD_HIP(hipStreamIsCapturing(stages[k]->stream_b, &cs));
     if (cs != hipStreamCaptureStatusNone)
       return fail(PD_ESTATE, "the stream of stage object %d is being captured: the pipeline drivers join several streams "
                   "by events and cannot be recorded into a graph (capture pd_forward / pd_backward / pd_update of one "
@@ -1856,8 +1905,8 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
           // the gradient slot this backward writes into: the stage before reads it in place (as dL/d(pre-activation)
           // of its last layer) up to and including its update two minibatches back
           if (s > 0 && i >= 2 && i - 2 >= nU[s - 1]) break;
-          if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, stages[s + 1]->ev_b[e], 0));
-          if (s > 0 && i >= 2) PD_HIP(hipStreamWaitEvent(st->stream, stages[s - 1]->ev_u[(i - 2) % R], 0));
+          if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->bstream(), stages[s + 1]->ev_b[e], 0));
+          if (s > 0 && i >= 2) PD_HIP(hipStreamWaitEvent(st->bstream(), stages[s - 1]->ev_u[(i - 2) % R], 0));
           const void* dy = s < S - 1 ? st->grad_slot(mb) : nullptr;
           void* dx = s > 0 ? stages[s - 1]->grad_slot(mb) : nullptr;
           // zero-copy hand-off: this stage stores dL/d(input) with the producer's ReLU mask applied (the mask is this
@@ -1866,7 +1915,7 @@ int pd_pipeline_run(pd_stage* const* stages, int32_t num_stages, int32_t num_min
           if (rc != PD_OK) return rc;
           if (i >= R && ((s > 0 && nB[s - 1] <= i - R) || (s < S - 1 && nB[s + 1] <= i - R + 2)))
             return ring_bug("the backward pass", s, i);
-          PD_HIP(hipEventRecord(st->ev_b[e], st->stream));
+          PD_HIP(hipEventRecord(st->ev_b[e], st->bstream()));
           ++nB[s];
         } else {
           const int rc = pd_update(st);
@@ -2006,8 +2055,8 @@ int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replica
           } else if (op.kind == PD_OP_B) {
             if (s < S - 1 && !bwd_done(s + 1, i)) break;
             if (s > 0 && kp >= 2 && kp - 2 >= nB[s - 1][qp]) break;  // the gradient slot this backward writes into
-            if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->stream, rep(s + 1, qn)->ev_b[kn % R], 0));
-            if (s > 0 && kp >= 2) PD_HIP(hipStreamWaitEvent(st->stream, rep(s - 1, qp)->ev_b[(kp - 2) % R], 0));
+            if (s < S - 1) PD_HIP(hipStreamWaitEvent(st->bstream(), rep(s + 1, qn)->ev_b[kn % R], 0));
+            if (s > 0 && kp >= 2) PD_HIP(hipStreamWaitEvent(st->bstream(), rep(s - 1, qp)->ev_b[(kp - 2) % R], 0));
             const void* dy = s < S - 1 ? st->grad_slot(k) : nullptr;
             void* dx = s > 0 ? rep(s - 1, qp)->grad_slot(kp) : nullptr;
             const int rc = pd_backward(st, k, dy, dx);
@@ -2016,7 +2065,7 @@ int pd_pipeline_run_replicated(pd_stage* const* replicas, const int32_t* replica
               const int j = (k - R) * r[s] + q, j2 = (k - R + 2) * r[s] + q;
               if ((s > 0 && !bwd_done(s - 1, j)) || (s < S - 1 && !bwd_done(s + 1, j2))) return ring_bug("the backward pass", s, q, k);
             }
-            PD_HIP(hipEventRecord(st->ev_b[k % R], st->stream));
+            PD_HIP(hipEventRecord(st->ev_b[k % R], st->bstream()));
             ++nB[s][q];
           } else {
             // joint update of round k: every replica with a minibatch in it must have reached it

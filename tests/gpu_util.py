@@ -41,13 +41,15 @@ class GpuStage:
 
     def __init__(self, layers, params, *, minibatch, precision, stage_index=0, num_stages=1, noam=1,
                  in_flight_override=0, lr=0.01, momentum=0.9, stream=None, in_hw=None, vertical_sync=False,
-                 optimizer=0, eps=0.0, replicas=0):
+                 optimizer=0, eps=0.0, replicas=0, stream_backward=None):
         self.bf16 = precision == pd.PD_BF16_F32ACC
         self.stream = stream if stream is not None else torch.cuda.current_stream()
+        self.stream_backward = stream_backward    # a torch stream for the kernels of pd_backward, or None
         self.cfg = pd.make_config(layers, stage_index=stage_index, num_stages=num_stages, noam=noam,
                                   in_flight_override=in_flight_override, minibatch=minibatch, precision=precision,
                                   lr=lr, momentum=momentum, stream=self.stream.cuda_stream, in_hw=in_hw,
-                                  vertical_sync=vertical_sync, optimizer=optimizer, eps=eps, replicas=replicas)
+                                  vertical_sync=vertical_sync, optimizer=optimizer, eps=eps, replicas=replicas,
+                                  stream_backward=stream_backward.cuda_stream if stream_backward is not None else 0)
         self.bytes = pd.pd_stage_query_bytes(self.cfg)
         self.arena = torch.empty(self.bytes + 256, dtype=torch.uint8, device=dev())
         base = (self.arena.data_ptr() + 255) // 256 * 256
@@ -59,6 +61,8 @@ class GpuStage:
     def close(self):
         if self.h:
             self.stream.synchronize()
+            if self.stream_backward is not None:
+                self.stream_backward.synchronize()
             pd.pd_stage_destroy(self.h)
             self.h = 0
 
