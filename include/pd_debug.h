@@ -51,6 +51,11 @@ int pd_set_big_tile_threshold(int32_t min_tiles);
  * stage).  Returns the previous value in the same encoding; any other argument only queries. */
 int pd_set_big_gemm_waves(int32_t waves);
 
+/* Tuning knob (process-wide, not thread-safe): 1 (default) lets 3 x 3, stride-1, pad-1 convolutions whose input
+ * channel count is a multiple of 64 run on the kernel that keeps a tile's input and halo in LDS; 0 sends them to the
+ * implicit-GEMM kernel like every other convolution.  Returns the previous value; any other argument only queries. */
+int pd_set_conv_halo(int32_t on);
+
 /* How many executed ops a stage remembers for pd_stage_trace: the most recent `max_ops` (default 65536; 0 switches
  * the record off and clears it).  Host-side only. */
 int pd_stage_set_trace_limit(pd_stage* st, size_t max_ops);

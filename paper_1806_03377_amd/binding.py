@@ -125,13 +125,15 @@ _lib.pd_gemm_workspace_bytes.restype = _sz
 _lib.pd_gemm_workspace_bytes.argtypes = [_i32, _i32, _i32]
 _lib.pd_linear_fwd_bf16_static_max_bytes.restype = _sz
 _lib.pd_linear_fwd_bf16_static_max_bytes.argtypes = []
+_lib.pd_set_conv_halo.restype = C.c_int
+_lib.pd_set_conv_halo.argtypes = [_i32]
 _lib.pd_set_big_gemm_waves.restype = C.c_int
 _lib.pd_set_big_gemm_waves.argtypes = [_i32]
 _lib.pd_set_big_tile_threshold.restype = C.c_int
 _lib.pd_set_big_tile_threshold.argtypes = [_i32]
 
 EXPORTED = sorted(list(_SIGS) + ["pd_last_error", "pd_gemm_workspace_bytes", "pd_set_big_tile_threshold",
-                                 "pd_linear_fwd_bf16_static_max_bytes", "pd_set_big_gemm_waves"])
+                                 "pd_linear_fwd_bf16_static_max_bytes", "pd_set_big_gemm_waves", "pd_set_conv_halo"])
 
 
 def pd_last_error() -> str:
@@ -340,6 +342,10 @@ def pd_stage_version(stage: int, mb_id: int = -1) -> int:
     v = _i32(0)
     _check(_lib.pd_stage_version(stage, mb_id, C.byref(v)))
     return v.value
+
+
+def pd_set_conv_halo(on: int) -> int:
+    return int(_lib.pd_set_conv_halo(on))
 
 
 def pd_set_big_gemm_waves(waves: int) -> int:

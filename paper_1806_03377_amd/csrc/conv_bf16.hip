@@ -504,6 +504,7 @@ hipError_t launch_igemm(hipStream_t s, const bf16_t* x, const bf16_t* w, const C
   const long long P = (long long)g.N * g.Ho * g.Wo;
   if ((long long)g.N * g.H * g.W * g.Ci >= (1ll << 31) || P * g.Co >= (1ll << 31) || (g.Ci % 8))
     return hipErrorInvalidValue;
+  if (conv3x3_halo_applies(g, x, w)) return conv3x3_halo_bf16(s, x, w, g, ep);
   if (g_conv_dma && (g.Co % 8) == 0 && (long long)g.Co * g.kh * g.kw * g.Ci < (1ll << 31) &&
       ((reinterpret_cast<uintptr_t>(x) | reinterpret_cast<uintptr_t>(w)) & 15) == 0) {
     // 256-wide tiles only when they fill the chip about as well as 128-wide ones would: a launch of n equal tiles

@@ -2109,6 +2109,7 @@ int pd_set_big_tile_threshold(int32_t min_tiles) {
 }
 
 int pd_set_big_gemm_waves(int32_t waves) { return pd::set_big_gemm_waves(waves); }
+int pd_set_conv_halo(int32_t on) { return pd::set_conv_halo(on); }
 
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) { return pd::gemm_bf16_workspace_bytes(M, N, K); }
 

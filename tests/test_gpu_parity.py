@@ -351,6 +351,24 @@ WIDE_CONVS = [(2, 12, 12, 64, 256, 3, 3, 1, 1, 1), (1, 20, 20, 32, 768, 1, 1, 1,
               (2, 12, 12, 256, 64, 3, 3, 1, 1, 1), (2, 9, 9, 512, 48, 1, 7, 1, 0, 3)]
 
 
+# 3 x 3 / stride 1 / pad 1 layers with 64-channel chunks: the kernel that keeps a tile's input and halo in LDS.  Sizes
+# that are not multiples of the 8 x 32 pixel tile, one to four channel chunks, ragged output-channel tiles, several
+# images; the same shapes with that kernel switched off go through the implicit-GEMM kernel
+HALO_CONVS = [(2, 13, 37, 64, 64, 3, 3, 1, 1, 1), (1, 9, 40, 128, 72, 3, 3, 1, 1, 1), (3, 8, 8, 64, 136, 3, 3, 1, 1, 1),
+              (1, 17, 33, 256, 128, 3, 3, 1, 1, 1), (2, 5, 70, 192, 40, 3, 3, 1, 1, 1), (1, 56, 56, 64, 256, 3, 3, 1, 1, 1)]
+
+
+@pytest.mark.parametrize("halo", [1, 0])
+@pytest.mark.parametrize("geom", HALO_CONVS)
+def test_conv_fwd_and_dgrad_halo_kernel(geom, halo):
+    old = pd.pd_set_conv_halo(halo)
+    try:
+        test_conv_fwd_bf16(geom)
+        test_conv_dgrad_bf16(geom)
+    finally:
+        pd.pd_set_conv_halo(old)
+
+
 @pytest.mark.parametrize("geom", WIDE_CONVS)
 def test_conv_fwd_bf16_wide_tiles(geom, big_tiles):
     test_conv_fwd_bf16(geom)
