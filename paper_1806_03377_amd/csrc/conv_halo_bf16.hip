@@ -9,7 +9,8 @@
 // the bytes the implicit-GEMM kernel moves.
 //
 //   LDS     patch [352 pixel rows][128 bytes] (rows 340..351 never read) + weight ring [WR][BN rows][128 bytes];
-//           a row's eight 16-byte slots are XOR-swizzled by (row & 7), applied on the global side of the direct
+//           a row's eight 16-byte slots are XOR-swizzled by ((row >> 1) & 7) (16 consecutive rows, which
+//           one quarter of a 16-byte-per-lane read touches, then cover all 64 banks), applied on the global side of the direct
 //           global -> LDS loads (lane L's chunk lands at M0 + 16 L: a wave-wide load fills 8 consecutive rows)
 //   waves   four; BN = 64: wave w owns image rows 2w, 2w+1 of the patch (64 pixels) x 64 channels;
 //           BN = 128: 2 x 2 waves of 4 image rows (128 pixels) x 64 channels
@@ -41,6 +42,8 @@ constexpr int HT_H = 8, HT_W = 32, HP_W = HT_W + 2, HP_H = HT_H + 2, HP_PIX = HP
 constexpr int HCC = 64, HROWB = HCC * 2;                  // input channels per chunk, bytes per LDS row
 constexpr int HP_LOADS = 44, HP_ROWS = HP_LOADS * 8;      // wave-wide loads per patch (8 rows each), rows reserved
 constexpr int HP_BYTES = HP_ROWS * HROWB;                 // 45056
+
+__device__ __forceinline__ int halo_swz(int row) { return (row >> 1) & 7; }
 
 template <int BN>
 __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wg,
@@ -84,13 +87,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __re
     const int py = pix / HP_W, px = pix - py * HP_W;
     const int iy = y0 - 1 + py, ix = x0 - 1 + px;
     const bool ok = pix < HP_PIX && (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
-    poff[q] = ok ? ((n * g.H + iy) * g.W + ix) * g.Ci + 8 * ((l & 7) ^ (pix & 7)) : -1;
+    poff[q] = ok ? ((n * g.H + iy) * g.W + ix) * g.Ci + 8 * ((l & 7) ^ halo_swz(pix)) : -1;
   }
   int woff[WQ];  // element offset of the lane's chunk of filter row co for tap 0, channel chunk 0, or -1
 #pragma unroll
   for (int q = 0; q < WQ; ++q) {
     const int row = (q * NWV + w) * 8 + (l >> 3), co = co0 + row;
-    woff[q] = co < g.Co ? co * K9 + 8 * ((l & 7) ^ (row & 7)) : -1;
+    woff[q] = co < g.Co ? co * K9 + 8 * ((l & 7) ^ halo_swz(row)) : -1;
   }
   auto load_patch = [&](int c) {
 #pragma unroll
@@ -104,14 +107,14 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __re
   };
 
   // fragments.  A: output row r of the patch, lane's pixel (l & 31): patch pixel (r + dy) * 34 + (l & 31) + dx.
-  // B: filter row.  Slot of reduction step ks, half h: (2 ks + h) ^ (row & 7).
+  // B: filter row.  Slot of reduction step ks, half h: (2 ks + h) ^ ((row >> 1) & 7).
   int apix[NI], fb[NJ];
 #pragma unroll
   for (int i = 0; i < NI; ++i) apix[i] = (NI * wm + i) * HP_W + (l & 31);
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int row = 64 * wn + 32 * j + (l & 31);
-    fb[j] = row * HROWB + (((l >> 5) ^ (row & 7)) << 4);
+    fb[j] = row * HROWB + (((l >> 5) ^ halo_swz(row)) << 4);
   }
   auto ldf = [&](const char* base, int o, int ks) { return *reinterpret_cast<const uint4*>(base + (o ^ (ks << 5))); };
 
@@ -152,7 +155,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __re
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int pix = apix[i] + shift;
-      fa[i] = pix * HROWB + (((l >> 5) ^ (pix & 7)) << 4);
+      fa[i] = pix * HROWB + (((l >> 5) ^ halo_swz(pix)) << 4);
     }
     uint4 a[2][NI], b[2][NJ];
 #pragma unroll

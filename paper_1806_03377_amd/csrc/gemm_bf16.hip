@@ -792,7 +792,7 @@ int big_tile_splits(int rows, int cols, int red, int red_step) {
 bool linear_fwd_uses_big_tiles(int M, int N) { return use_big_tiles(M, N); }
 
 size_t gemm_bf16_workspace_bytes(int M, int N, int K) {
-  const int sf = big_tile_splits(M, N, K, 64), sd = big_tile_splits(M, K, N, 32);
+  const int sf = big_tile_splits(M, N, K, 64), sd = big_tile_splits(M, K, N, 8);
   const size_t a = sf == 1 ? 0 : sf > 1 ? (size_t)sf * M * N * sizeof(float) : splitk_bytes_t<kFwdBN, kFwdBK>(M, N, K);
   const size_t b = sd == 1 ? linear_dgrad_big_scratch_bytes(N, K)  // room for transposed weights
                    : sd > 1 ? (size_t)sd * M * K * sizeof(float)
@@ -817,7 +817,7 @@ hipError_t linear_fwd_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, cons
 
 hipError_t linear_dgrad_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                              int N, int K, float* ws, size_t ws_bytes) {
-  const int sp = big_tile_splits(M, K, N, 32);
+  const int sp = big_tile_splits(M, K, N, 8);
   if (sp == 1) return linear_dgrad_big_bf16(s, dz, w, mask, dx, M, N, K, ws, ws_bytes, 1);
   if (sp > 1 && ws && (size_t)sp * M * K * sizeof(float) <= ws_bytes &&
       linear_dgrad_big_bf16(s, dz, w, nullptr, nullptr, M, N, K, ws, ws_bytes, sp) == hipSuccess) {

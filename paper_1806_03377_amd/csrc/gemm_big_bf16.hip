@@ -485,6 +485,11 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const bf16_t* __re
 // LDS reads, nor the direct path as such: it is the vector-memory instructions in the MFMA-issuing waves themselves
 // (16 KB of operands per 64 MFMAs and compute unit, whatever way they take).
 constexpr int EK = 64, EROWB = 128, ETILE = 256 * EROWB, ERING = 5;
+// Slot swizzle of a 128-byte row.  A 16-byte-per-lane LDS read is served 16 consecutive lanes (256 bytes, all 64
+// banks) at a time; those lanes read the same logical slot of 16 consecutive rows.  Two rows fill the 64 banks, so
+// the physical slot has to differ between the eight rows of equal parity: slot ^ ((row >> 1) & 7).  (slot ^ (row & 7)
+// puts rows r and r + 8 on the same banks: measured as one bank-conflict cycle per LDS cycle.)
+__device__ __forceinline__ int e_swz(int row) { return (row >> 1) & 7; }
 
 template <int NW>
 __global__ __launch_bounds__(64 * NW, 1) void gemm_dma64_kernel(const bf16_t* __restrict__ A, int lda,
@@ -532,7 +537,7 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma64_kernel(const bf16_t* __
   uint32_t offa[QN], offb[QN];
 #pragma unroll
   for (int q = 0; q < QN; ++q) {
-    const int row = (q * NW + w) * 8 + (l >> 3), g = (l & 7) ^ (row & 7);
+    const int row = (q * NW + w) * 8 + (l >> 3), g = (l & 7) ^ e_swz(row);
     const int ra = i0 + row < I ? i0 + row : I - 1, rb = j0 + row < J ? j0 + row : J - 1;
     offa[q] = ((uint32_t)ra * (uint32_t)lda + g * 8) * 2u;
     offb[q] = ((uint32_t)rb * (uint32_t)ldb + g * 8) * 2u;
@@ -554,12 +559,12 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma64_kernel(const bf16_t* __
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int row = 128 * wm + 32 * i + (l & 31);
-    fa[i] = row * EROWB + (((l >> 5) ^ (row & 7)) << 4);
+    fa[i] = row * EROWB + (((l >> 5) ^ e_swz(row)) << 4);
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int row = WCOLS * wn + 32 * j + (l & 31);
-    fb[j] = row * EROWB + (((l >> 5) ^ (row & 7)) << 4);
+    fb[j] = row * EROWB + (((l >> 5) ^ e_swz(row)) << 4);
   }
   auto ldf = [&](const char* tile, int o, int ks) { return *reinterpret_cast<const uint4*>(tile + (o ^ (ks << 5))); };
 
@@ -807,7 +812,9 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
 //   out[i][j] = sum over r of a[i][r] * b[r][j]        a: [I][R] (dz), b: [R][J] (w as stored), out: [I][J]
 // The A side is gemm_dma_kernel's (64-byte tile rows, 16-byte fragment reads), the B side gemm_tn_kernel's
 // ([32 reduction rows][256 columns] as in memory, transposing reads): no transposed copy of the weights is made.
-// Needs R % 32 == 0.
+// Needs R % 8 == 0.  A last stage of fewer than 32 reduction elements (R % 32 != 0) takes zeros for the missing rows
+// of b; on the a side the lanes of the missing columns re-read the row's first chunk of that stage instead (inside
+// the matrix, multiplied by zeros, and a non-finite value there belongs to the same output row anyway).
 __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restrict__ A, int lda,
                                                          const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep, int I,
                                                          int J, int R, int tiles_i, int tiles_j, int splits,
@@ -836,62 +843,62 @@ __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restric
     tj = rem / rows_in;
   }
   const int i0 = ti * GM, j0 = tj * GN;
-  int T = R / DK;
+  int T = (R + DK - 1) / DK;
+  const int tail = R % DK;          // reduction elements of a partial last stage (0: none)
+  bool partial = tail != 0;         // this workgroup's last stage is that partial stage
   if (splits > 1) {
     const int s0 = (int)((long long)z * T / splits), s1 = (int)((long long)(z + 1) * T / splits);
     A += (size_t)s0 * DK;
     Bm += (size_t)s0 * DK * ldb;
     T = s1 - s0;
+    partial = partial && z == splits - 1;
     ep.bias = nullptr; ep.mask = nullptr; ep.relu = 0; ep.out = nullptr; ep.upd_master = nullptr;
     ep.out_f = part + (size_t)z * I * J;
     ep.ldo = J;
   }
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_tn_zero);
 
-  uint32_t aoffs[QA];  // A: byte offset of this lane's chunk, rows clamped (they only feed outputs never stored)
+  uint32_t aoffs[QA];   // A: byte offset of this lane's chunk, rows clamped (they only feed outputs never stored)
+  uint32_t aoffs_t[QA]; // the same for a partial last stage: chunks past the end re-read the stage's first chunk
 #pragma unroll
   for (int q = 0; q < QA; ++q) {
     const int row = (q * NW + w) * 16 + (l >> 2), g = (l & 3) ^ dma_swz(row);
     const int ra = i0 + row < I ? i0 + row : I - 1;
     aoffs[q] = ((uint32_t)ra * (uint32_t)lda + g * 8) * 2u;
+    aoffs_t[q] = ((uint32_t)ra * (uint32_t)lda + (g * 8 < tail ? g * 8 : 0)) * 2u;
   }
   const bf16_t* bp[QB];  // B: this lane's source for stage 0 (null: column outside the matrix)
+  bool bcut[QB];         // this lane's row of a stage lies past the end of a partial last stage
 #pragma unroll
   for (int q = 0; q < QB; ++q) {
     const int id = q * NW + w, r = 2 * id + (l >> 5);
     const int s16 = l & 31, blk = (s16 >> 2) ^ (r & 3);
     const int col = j0 + 32 * blk + 8 * (s16 & 3);
     bp[q] = col < J ? Bm + (size_t)r * ldb + col : nullptr;
+    bcut[q] = r >= tail;
   }
   const size_t bstep = (size_t)DK * ldb;
   int a_st = 0;  // reduction stage the next A loads fetch (clamped: the surplus is never read)
-  auto issue = [&](int q, char* stage) {
-    if (q < QA) {
-      const int k0 = (a_st < T ? a_st : T - 1) * DK;
-      dma_load16(A + k0, aoffs[q], stage + (q * NW + w) * 1024);
-      if (q == QA - 1) ++a_st;
-    } else {
-      const int qb = q - QA;
-      dma_chunk64(bp[qb] != nullptr ? bp[qb] : zero, stage + ATILE + (qb * NW + w) * 1024);
-      if (bp[qb] != nullptr) bp[qb] += bstep;
-    }
-  };
-  // (B loads of stages past the end read rows >= R of w: redirect them too)
-  int b_left[QB];
+  int b_left[QB];  // stages the B loads have still to fetch
 #pragma unroll
   for (int q = 0; q < QB; ++q) b_left[q] = T;
-  auto issue_checked = [&](int q, char* stage) {
-    if (q >= QA) {
+  auto issue = [&](int q, char* stage) {
+    if (q < QA) {
+      const int sidx = a_st < T ? a_st : T - 1;
+      dma_load16(A + sidx * DK, (partial && sidx == T - 1) ? aoffs_t[q] : aoffs[q], stage + (q * NW + w) * 1024);
+      if (q == QA - 1) ++a_st;
+    } else {
+      // (B loads of stages past the end would read rows >= R of w: zeros instead)
       const int qb = q - QA;
-      if (b_left[qb] <= 0) {
-        dma_chunk64(zero, stage + ATILE + (qb * NW + w) * 1024);
-        return;
+      const bool live = b_left[qb] > 0;
+      const bool cut = !live || bp[qb] == nullptr || (partial && b_left[qb] == 1 && bcut[qb]);
+      dma_chunk64(cut ? zero : bp[qb], stage + ATILE + (qb * NW + w) * 1024);
+      if (live) {
+        --b_left[qb];
+        if (bp[qb] != nullptr) bp[qb] += bstep;
       }
-      --b_left[qb];
     }
-    issue(q, stage);
   };
-
   int fa[NI], fb[NJ];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
@@ -913,7 +920,7 @@ __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restric
 #pragma unroll
   for (int d = 0; d < D; ++d)
 #pragma unroll
-    for (int q = 0; q < LPS; ++q) issue_checked(q, smem + d * STAGE);
+    for (int q = 0; q < LPS; ++q) issue(q, smem + d * STAGE);
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((D - 2) * LPS) : "memory");
   __syncthreads();
   bf16x8 a[2][NI], b[2][NJ];
@@ -944,7 +951,7 @@ __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restric
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[c][i], b[c][j], acc[i][j], 0, 0, 0);
         if (m == 2 || m == 6) {
           __builtin_amdgcn_sched_barrier(0);
-          issue_checked(ks * 2 + (m == 6), sl);
+          issue(ks * 2 + (m == 6), sl);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
@@ -1089,7 +1096,7 @@ size_t linear_wgrad_big_scratch_bytes(int M, int N, int K) { return (size_t)M * 
 hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                                  int N, int K, void* scratch, size_t scratch_bytes, int splits) {
   BigEpilogue ep = {nullptr, mask, 0, dx, nullptr, K};
-  if (g_wgrad_tn && (N % DK) == 0 && (K % 8) == 0 && ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(w)) & 15) == 0 &&
+  if (g_wgrad_tn && (N % 8) == 0 && (K % 8) == 0 && ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(w)) & 15) == 0 &&
       (size_t)M * N < ((size_t)1 << 31) && N / DK >= 4 * splits) {  // w as stored: transposing LDS reads on the B side
     const int ti = (M + GM - 1) / GM, tj = (K + GN - 1) / GN;
     if (splits > 1 && (!scratch || scratch_bytes < (size_t)splits * M * K * sizeof(float))) return hipErrorInvalidValue;
