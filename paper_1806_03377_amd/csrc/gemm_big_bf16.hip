@@ -689,7 +689,8 @@ __device__ __forceinline__ bf16x8 tn_frag(const char* lo, const char* hi) {
 
 __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restrict__ Z, int ldz,
                                                          const bf16_t* __restrict__ X, int ldx, BigEpilogue ep, int M,
-                                                         int N, int K, int tiles_n, int tiles_k) {
+                                                         int N, int K, int tiles_n, int tiles_k, int splits,
+                                                         float* __restrict__ part) {
   constexpr int NW = 8, NI = 4, NJ = 2, TR = 32, KS = TR / 16, NS = 4, D = NS - 1;
   constexpr int ROWB = 512, TILE = TR * ROWB, STAGE = 2 * TILE;  // 16 KB per operand and stage
   constexpr int LPS = 2 * TILE / 1024 / NW;                      // wave-wide loads per wave and stage (4)
@@ -697,9 +698,13 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
   __shared__ __attribute__((aligned(1024))) char smem[NS * STAGE];
   const int t = threadIdx.x, l = t & 63;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
-  int bid = blockIdx.x;
+  // splits > 1: the grid holds `splits` copies of the tile grid; copy z sums over its share of the rows and leaves an
+  // fp32 partial gradient in part[z][N][K] (no update: the reducing kernel applies it)
+  const int n_tiles = tiles_n * tiles_k;
+  const int z = blockIdx.x / n_tiles;
+  int bid = blockIdx.x - z * n_tiles;
   {
-    const int per = gridDim.x >> 3;
+    const int per = n_tiles >> 3;
     if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
   }
   int tn, tk;
@@ -711,7 +716,17 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
     tk = rem / rows_in;
   }
   const int n0 = tn * GM, k0 = tk * GN;
-  const int T = (M + TR - 1) / TR;
+  int T = (M + TR - 1) / TR;
+  int m_lo = 0, m_hi = M;  // this copy's rows
+  if (splits > 1) {
+    const int s0 = (int)((long long)z * T / splits), s1 = (int)((long long)(z + 1) * T / splits);
+    m_lo = s0 * TR;
+    m_hi = s1 * TR < M ? s1 * TR : M;
+    T = s1 - s0;
+    ep.bias = nullptr; ep.mask = nullptr; ep.relu = 0; ep.out = nullptr; ep.upd_master = nullptr;
+    ep.out_f = part + (size_t)z * N * K;
+    ep.ldo = K;
+  }
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_tn_zero);
 
   // loads: per stage 16 wave-loads per operand, each two tile rows of 512 bytes; wave w issues numbers w, w + 8, ...
@@ -726,13 +741,13 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
     const int s16 = l & 31, blk = (s16 >> 2) ^ (r & 3);
     const int col = (is_x ? k0 : n0) + 32 * blk + 8 * (s16 & 3);
     const int ld = is_x ? ldx : ldz;
-    lp[q] = col < (is_x ? K : N) ? (is_x ? X : Z) + (size_t)r * ld + col : nullptr;
-    lrow[q] = r;
+    lp[q] = col < (is_x ? K : N) ? (is_x ? X : Z) + (size_t)(m_lo + r) * ld + col : nullptr;
+    lrow[q] = m_lo + r;
     lstep[q] = (size_t)TR * ld;
     ldst[q] = (is_x ? TILE : 0) + (id & 15) * 1024;
   }
   auto issue = [&](int q, char* stage) {  // q-th load of this wave for the next stage to be fetched; advances
-    const bool ok = lp[q] != nullptr && lrow[q] < M;
+    const bool ok = lp[q] != nullptr && lrow[q] < m_hi;
     dma_chunk64(ok ? lp[q] : zero, stage + ldst[q]);
     if (lp[q] != nullptr) lp[q] += lstep[q];
     lrow[q] += TR;
@@ -1090,6 +1105,22 @@ hipError_t linear_fwd_big_bf16(hipStream_t s, const bf16_t* x, int ldx, const bf
 size_t linear_dgrad_big_scratch_bytes(int N, int K) { return (size_t)N * K * sizeof(bf16_t); }
 size_t linear_wgrad_big_scratch_bytes(int M, int N, int K) { return (size_t)M * ((size_t)N + K) * sizeof(bf16_t); }
 
+// A weight gradient with too few 256 x 256 tiles for the chip and many rows: the rows are split this many ways
+// (one workgroup per compute unit or so, at least 8 stages of 32 rows each); 1 = no split.  S2VT's recurrent
+// matrices (4000 x 1000 outputs, 5120 rows) are 64 tiles: 154 us on 64 compute units.
+static int wgrad_big_splits(int M, int N, int K) {
+  const int tiles = ((N + GM - 1) / GM) * ((K + GN - 1) / GN);
+  if (tiles >= 128 || (N % 4) != 0 || (K % 4) != 0 || (((size_t)N * K) % 4) != 0) return 1;
+  int sp = 256 / tiles;
+  if (sp > M / 256) sp = M / 256;
+  if (sp > 16) sp = 16;
+  return sp >= 2 ? sp : 1;
+}
+size_t linear_wgrad_update_big_scratch_bytes(int M, int N, int K) {
+  const int sp = wgrad_big_splits(M, N, K);
+  return sp > 1 ? (size_t)sp * N * K * sizeof(float) : 0;
+}
+
 // splits > 1: the reduction (over the N out-features) is split; `scratch` then receives splits * M * K floats of
 // partial products instead of serving as room for transposed weights, and mask / dx are not touched (the reducing
 // kernel applies them); hipErrorInvalidValue if the shape does not allow the kernel that can do that.
@@ -1129,7 +1160,7 @@ hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
       ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(x)) & 15) == 0) {
     // operands as they are: transposing LDS reads instead of a transposing pre-pass
     const int tn = (N + GM - 1) / GM, tk = (K + GN - 1) / GN;
-    gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk);
+    gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, 1, nullptr);
     e = hipGetLastError();
   } else if (scratch && (M % 8) == 0 && scratch_bytes >= linear_wgrad_big_scratch_bytes(M, N, K)) {
     bf16_t* zt = static_cast<bf16_t*>(scratch);  // [N][M]
@@ -1180,7 +1211,15 @@ hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const b
   }
   BigEpilogue ep = {nullptr, nullptr, 0, nullptr, nullptr, K, master_w, mom_w, ring_w, rule};
   const int tn = (N + GM - 1) / GM, tk = (K + GN - 1) / GN;
-  gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk);
+  const int sp = wgrad_big_splits(M, N, K);
+  if (sp > 1 && scratch && scratch_bytes >= (size_t)sp * n_w * sizeof(float)) {
+    float* parts = static_cast<float*>(scratch);  // (the column sums above are done with it: same stream)
+    gemm_tn_kernel<<<tn * tk * sp, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, sp, parts);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return wgrad_reduce_update(s, parts, sp, n_w, n_w, 0, master_w, mom_w, ring_w, nullptr, nullptr, nullptr, rule);
+  }
+  gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, 1, nullptr);
   return hipGetLastError();
 }
 

@@ -64,6 +64,8 @@ hipError_t linear_fwd_big_bf16(hipStream_t s, const bf16_t* x, int ldx, const bf
 // dgrad and wgrad read an operand sideways; given scratch of the stated size they transpose it first (faster).
 size_t linear_dgrad_big_scratch_bytes(int N, int K);
 size_t linear_wgrad_big_scratch_bytes(int M, int N, int K);
+// scratch that lets linear_wgrad_update_big_bf16 split the rows of a product with few output tiles (0: no split)
+size_t linear_wgrad_update_big_scratch_bytes(int M, int N, int K);
 hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* w, const bf16_t* mask, bf16_t* dx, int M,
                                  int N, int K, void* scratch, size_t scratch_bytes, int splits);
 hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* dw, float* db, int M, int N,

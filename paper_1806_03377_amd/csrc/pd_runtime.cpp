@@ -551,6 +551,12 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
         const int n_out = L.kind == K_LSTM ? 4 * L.out : L.out;
         const size_t t1 = pd::linear_wgrad_big_scratch_bytes(L.rows, n_out, L.in > L.out ? L.in : L.out);
         if (t1 > w) w = t1;
+        const size_t t2 = pd::linear_wgrad_update_big_scratch_bytes(L.rows, n_out, L.in);  // split row sums
+        if (t2 > w) w = t2;
+        if (L.kind == K_LSTM) {
+          const size_t t3 = pd::linear_wgrad_update_big_scratch_bytes(L.rows, n_out, L.out);
+          if (t3 > w) w = t3;
+        }
       }
       if (w > p.ws_bytes) p.ws_bytes = w;
     }
