@@ -509,6 +509,22 @@ def bench_gemm_sweep(args, pd, gen, torch, np, dev):
                 row[name + "_us"] = round(t * 1e6, 1)
                 row[name + "_tflops"] = round(fl / t / 1e12, 1)
                 row[name + "_mfma_pct"] = round(100 * fl / t / MFMA_BF16_PEAK, 2)
+            if M >= 1024 and not getattr(args, "no_library_reference", False):
+                # Context, not a target and not part of the product: the vendor library's plain products (torch.mm ->
+                # hipBLASLt) on the same operands, and both forward products on all-zero operands -- the chip lowers
+                # its clock under matrix load, and by how much depends on the data the multipliers see.
+                row["lib_fwd_us"] = round(timeit(lambda: torch.mm(x, w.t())) * 1e6, 1)
+                row["lib_dgrad_us"] = round(timeit(lambda: torch.mm(dz, w)) * 1e6, 1)
+                row["lib_wgrad_us"] = round(timeit(lambda: torch.mm(dz.t(), x)) * 1e6, 1)
+                for k in ("fwd", "dgrad", "wgrad"):
+                    row["lib_" + k + "_mfma_pct"] = round(100 * fl / (row["lib_" + k + "_us"] * 1e-6) / MFMA_BF16_PEAK, 2)
+                if M >= 8192:
+                    xz = torch.zeros_like(x); wz = torch.zeros_like(w)
+                    tz = timeit(lambda: pd.pd_linear_fwd_bf16(s, xz.data_ptr(), wz.data_ptr(), b.data_ptr(), y.data_ptr(), M, N, K, True, ws.data_ptr(), wsb))
+                    tlz = timeit(lambda: torch.mm(xz, wz.t()))
+                    row["fwd_zero_operands_mfma_pct"] = round(100 * fl / tz / MFMA_BF16_PEAK, 2)
+                    row["lib_fwd_zero_operands_mfma_pct"] = round(100 * fl / tlz / MFMA_BF16_PEAK, 2)
+                    del xz, wz
             table.append(row)
             print("# " + json.dumps(row), file=sys.stderr, flush=True)
             del x, dz, y, dx, ws, part
@@ -867,6 +883,9 @@ def main():
                          "every extra event hop costs more than its tiny kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="default workload only: skip the secondary workloads appended under `extra`")
+    ap.add_argument("--rows", type=int, nargs="+", default=None, help="gemm_sweep: the row counts to run (default: 64 ... 8192)")
+    ap.add_argument("--no-library-reference", action="store_true",
+                    help="gemm_sweep: leave out the vendor library's timings of the same products (context only)")
     ap.add_argument("--small", action="store_true", help="reduced widths (debugging only; result is not the metric)")
     ap.add_argument("--workload", default="vgg16_fc", choices=["vgg16_fc", "vgg16_conv", "s2vt", "inception", "gemm_sweep", "partition", "mlp4", "replicated", "vgg16_pipeline"],
                     help="vgg16_fc (default, the metric's workload); secondary: vgg16_conv (the conv stage), "
