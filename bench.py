@@ -70,8 +70,10 @@ def bench_conv(args, pd, gen, torch, np, dev):
     seed = gen.BASE_SEED + 2
     params = gen.init_params(seed, "vgg_conv", layers)
     stream = torch.cuda.Stream(device=dev)
+    bstream = None if _single_stream(args, True) else torch.cuda.Stream(device=dev)
     cfg = pd.make_config(layers, in_flight_override=depth, minibatch=B, precision=pd.PD_BF16_F32ACC, lr=0.01,
-                         momentum=0.9, stream=stream.cuda_stream, in_hw=hw)
+                         momentum=0.9, stream=stream.cuda_stream, in_hw=hw,
+                         stream_backward=bstream.cuda_stream if bstream is not None else 0)
     nbytes = pd.pd_stage_query_bytes(cfg)
     arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
     h = pd.pd_stage_create(cfg, (arena.data_ptr() + 255) // 256 * 256, nbytes)
@@ -121,7 +123,7 @@ def bench_conv(args, pd, gen, torch, np, dev):
                       f"images, bf16 w/ fp32 accum, minibatch {B}, ring depth {depth}, step = B(k) U(k) F(k+depth)",
                       "minibatch": B, "ring_depth": depth},
            "step_gflop": f / 1e9, "mfma_util_pct": 100.0 * f / (ms * 1e-3) / MFMA_BF16_PEAK,
-           "roofline": {"bound": "mfma", "kernel": "whole step (conv_igemm_kernel + conv_wgrad_kernel dominate)",
+           "roofline": {"bound": "mfma", "kernel": "whole step (conv3x3_halo_kernel + conv_wgrad_tr_kernel dominate)",
                         "achieved": f / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK / 1e12, "unit": "TFLOP/s",
                         "frac": f / (ms * 1e-3) / MFMA_BF16_PEAK, "traffic": None}}
     pd.pd_stage_destroy(h)
@@ -675,12 +677,13 @@ def bench_vgg16_fc(args, pd, gen, torch, np, dev):
 
     def step(k, ev=None):
         # B(k), U(k), F(k + depth); meanwhile the producer refills the slot that U(k) frees with minibatch k + in_ring.
-        # With a backward stream, B(k) starts when U(k - 1) is done and runs next to F(k - 1 + depth), enqueued by the
-        # previous step.  The events bracket each op on the stream it runs on, behind the same dependencies the library
-        # inserts itself (B after the previous update, U after B), so that no waiting is counted as work.
+        # With a backward stream, B(k) starts when U(k - 2) is done (the gradient buffers exist twice) and runs next to
+        # U(k - 1) and F(k - 1 + depth), enqueued by the previous step.  The events bracket each op on the stream it runs
+        # on, behind the same dependencies the library inserts itself (B after the update before the last, U after B),
+        # so that no waiting is counted as work.
         if ev is not None:
-            if k > 0:
-                stream_b.wait_event(freed[(k - 1) % in_ring])
+            if k > 1:
+                stream_b.wait_event(freed[(k - 2) % in_ring])
             ev[0].record(stream_b)
         pd.pd_backward(h, k, 0, dx.data_ptr())
         if ev is not None:
@@ -878,9 +881,9 @@ def main():
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--backward-streams", choices=["auto", "on", "off"], default="auto",
                     help="run every stage's backward passes on a stream of their own (pd_stage_config.stream_backward); auto: "
-                         "on for the VGG16 classifier stage (0.536 -> 0.515 ms per step) and the Inception-shaped pipeline "
-                         "(11.35 -> 10.59 ms), off for the LSTM pipeline (no gain) and the fp32 MLP pipeline (0.100 -> 0.158 ms: "
-                         "every extra event hop costs more than its tiny kernels)")
+                         "on for the VGG16 classifier stage (0.531 -> 0.500 ms per step), the VGG16 convolution stage (4.76 -> 4.55 ms) "
+                         "and the Inception-shaped pipeline (11.35 -> 10.43 ms), off for the LSTM pipeline (no gain) and the fp32 MLP "
+                         "pipeline (0.12 -> 0.18 ms: every extra event hop costs more than its tiny kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="default workload only: skip the secondary workloads appended under `extra`")
     ap.add_argument("--rows", type=int, nargs="+", default=None, help="gemm_sweep: the row counts to run (default: 64 ... 8192)")

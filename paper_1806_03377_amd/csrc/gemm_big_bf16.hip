@@ -481,9 +481,10 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma_kernel(const bf16_t* __re
 // What bounds it (four waves, 8192 x 4096 x 25088, 56 % of the nominal peak): with the global -> LDS loads taken out
 // of the main loop the MFMAs and fragment reads alone run at 74-80 %; with the loads in, 56 %, also when every load
 // hits the same cached 64 KB, no faster with half of the fragment reads removed, and SLOWER (52 %) with B fetched
-// through registers and written with ds_write_b128 so that only A uses the direct path.  So neither L2 / HBM, nor the
-// LDS reads, nor the direct path as such: it is the vector-memory instructions in the MFMA-issuing waves themselves
-// (16 KB of operands per 64 MFMAs and compute unit, whatever way they take).
+// through registers and written with ds_write_b128 so that only A uses the direct path.  The hardware counters add the
+// other half of the picture: the matrix pipes are busy in 77 % of the cycles, but the chip runs these launches at
+// 1.7 GHz instead of its nominal 2.4 (on all-zero operands, which draw less power, the same kernel reaches 73 % of the
+// nominal peak), so what is gained in issue efficiency is partly paid back in clock.
 constexpr int EK = 64, EROWB = 128, ETILE = 256 * EROWB, ERING = 5;
 // Slot swizzle of a 128-byte row.  A 16-byte-per-lane LDS read is served 16 consecutive lanes (256 bytes, all 64
 // banks) at a time; those lanes read the same logical slot of 16 consecutive rows.  Two rows fill the 64 banks, so

@@ -146,7 +146,6 @@ typedef Layer Linear;  // (historic name used below for "a layer")
 
 struct InFlight {
   int mb, version;
-  bool update_since_forward;  // an update has been enqueued on the stage's stream after this minibatch's forward pass
 };
 
 }  // namespace
@@ -162,13 +161,21 @@ struct pd_stage {
   int classes = 0;
   pd::UpdateRule rule = {0.f, 0.f, 0.f, 0};
   hipStream_t stream = nullptr;
-  // Backward lane (cfg.stream_backward): the kernels of pd_backward run on stream_b, next to the forward pass that the
-  // 1F1B order places before them.  ev_upd: the last update on `stream` is done (the backward pass overwrites what it
-  // read); ev_bwd: the last backward pass on stream_b is done (the update reads what it wrote); ev_fork: scratch
-  // event for "everything enqueued on `stream` so far".  ws_b: the lane's own split-K workspace.
+  // Backward lane (cfg.stream_backward): the kernels of pd_backward run on stream_b, next to the update and the forward
+  // pass that the 1F1B order places before them.  What pd_backward writes for pd_update (the factored gradient dz, the
+  // convolutions' partial sums) exists twice and consecutive backward passes alternate between the two sets, so B(k+1)
+  // only has to wait for U(k-1), the update that read the set it overwrites, not for U(k).
+  //   ev_fwd[mb % depth]  that minibatch's forward pass on `stream` is done (B reads its stash slot)
+  //   ev_upd[n & 1]       the n-th update on `stream` is done
+  //   ev_bwd              the last backward pass on stream_b is done (the update reads what it wrote)
+  //   ws_b                the lane's own split-K workspace
   hipStream_t stream_b = nullptr;
-  hipEvent_t ev_upd = nullptr, ev_bwd = nullptr, ev_fork = nullptr;
-  bool upd_recorded = false;
+  hipEvent_t ev_upd[2] = {nullptr, nullptr}, ev_bwd = nullptr;
+  std::vector<hipEvent_t> ev_fwd;
+  long long n_upd = 0;       // updates enqueued so far
+  int bwd_set = 0;           // which set of gradient buffers the next backward pass writes
+  char *dz_base = nullptr, *part_base = nullptr;
+  size_t dz_set_bytes = 0, part_set_bytes = 0;
   float* ws_b = nullptr;
   hipStream_t bstream() const { return stream_b ? stream_b : stream; }
   hipError_t sync_all() const {
@@ -575,12 +582,12 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
   if (p.replicas > 1) { p.o_gradbuf = o; o += align_up(p.p_pad * 4, 256); }
   p.o_in = o; o += (size_t)p.in_depth * p.in_bytes;
   p.o_stash = o; o += (size_t)p.depth * p.stash_slot_bytes;
-  p.o_dz = o; o += p.dz_bytes;
+  p.o_dz = o; o += p.dz_bytes * (p.lane_b ? 2 : 1);  // (two sets with a backward stream)
   if (!p.has_loss) { p.o_grad = o; o += 2 * p.out_bytes; }
   p.o_ws = o; o += p.ws_bytes;
   if (p.lane_b) { p.o_ws_b = o; o += p.ws_bytes; }
   p.o_pp = o; o += 2 * p.pp_bytes;
-  p.o_part = o; o += p.part_bytes;
+  p.o_part = o; o += p.part_bytes * (p.lane_b ? 2 : 1);
   p.o_wt = o; o += p.wt_bytes;
   p.o_blk_dy = o; o += p.blk_dy_bytes;
   p.o_blk_dx = o; o += p.blk_dx_bytes;
@@ -645,14 +652,19 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
   }
   st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
   st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
+  st->dz_base = st->dz; st->part_base = st->part;
+  st->dz_set_bytes = p.dz_bytes; st->part_set_bytes = p.part_bytes;
   st->blk_dy = a + p.o_blk_dy; st->blk_dx = a + p.o_blk_dx; st->blk_dx_stride = p.blk_dx_stride;
   st->borrowed_out.assign(p.depth, nullptr);
   hipError_t e = primary ? hipSuccess : pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
   // padding between layers inside the gradient buffer is never written by a gradient kernel: keep it at zero
   if (e == hipSuccess && st->gradbuf) e = pd::fill_zero(st->stream, st->gradbuf, p.p_pad * 4);
   if (e == hipSuccess && st->gradbuf) e = hipEventCreateWithFlags(&st->ev_rep, hipEventDisableTiming);
-  for (hipEvent_t* ev : {&st->ev_upd, &st->ev_bwd, &st->ev_fork})
+  for (hipEvent_t* ev : {&st->ev_upd[0], &st->ev_upd[1], &st->ev_bwd})
     if (e == hipSuccess && st->stream_b) e = hipEventCreateWithFlags(ev, hipEventDisableTiming);
+  if (st->stream_b) st->ev_fwd.assign(st->depth, nullptr);
+  for (hipEvent_t& ev : st->ev_fwd)
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
   for (int d = 0; d < st->depth && e == hipSuccess; ++d)
     for (const Linear& L : st->lin)
       if (L.kind == K_LSTM && e == hipSuccess) {
@@ -661,7 +673,9 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
         if (e == hipSuccess) e = pd::fill_zero(st->stream, slot + L.c_off, (size_t)st->B * L.out * 4);
       }
   if (e != hipSuccess) {
-    for (hipEvent_t ev : {st->ev_rep, st->ev_upd, st->ev_bwd, st->ev_fork})
+    for (hipEvent_t ev : {st->ev_rep, st->ev_upd[0], st->ev_upd[1], st->ev_bwd})
+      if (ev) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : st->ev_fwd)
       if (ev) (void)hipEventDestroy(ev);
     delete st;
     return fail(PD_EHIP, "clearing momentum and initial states: %s", hipGetErrorString(e));
@@ -762,9 +776,9 @@ int pd_stage_destroy(pd_stage* st) {
     auto& v = st->primary->secondaries;
     v.erase(std::remove(v.begin(), v.end(), st), v.end());
   }
-  for (hipEvent_t ev : {st->ev_rep, st->ev_upd, st->ev_bwd, st->ev_fork})
+  for (hipEvent_t ev : {st->ev_rep, st->ev_upd[0], st->ev_upd[1], st->ev_bwd})
     if (ev) (void)hipEventDestroy(ev);
-  for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u, &st->mark_pool})
+  for (auto* v : {&st->ev_f, &st->ev_b, &st->ev_u, &st->mark_pool, &st->ev_fwd})
     for (hipEvent_t e : *v) (void)hipEventDestroy(e);
   for (const pd_stage::Mark& m : st->marks) (void)hipEventDestroy(m.ev);
   delete st;
@@ -1299,7 +1313,8 @@ static int forward_impl(pd_stage* st, int32_t mb_id, int32_t version, const void
     PD_HIP(pd::copy_bytes(s, a, y_dev, (size_t)st->lin.back().rows * st->lin.back().out * (st->has_loss ? 4 : st->esz)));
   PD_HIP(st->mark(0, (int)st->lin.size() - 1));  // (the loss and the copy of the output count for the last layer)
   if (st->profiling) ++st->prof_ops[0];
-  st->in_flight.push_back({mb_id, v, false});
+  if (st->stream_b) PD_HIP(hipEventRecord(st->ev_fwd[mb_id % st->depth], st->stream));
+  st->in_flight.push_back({mb_id, v});
   st->last_fwd = mb_id;
   st->log_op(PD_OP_F, mb_id, v);
   return PD_OK;
@@ -1332,15 +1347,16 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
 
   hipStream_t s = st->bstream();
   if (st->stream_b) {
-    // Backward lane: this pass needs its minibatch's forward pass and, because it overwrites the gradient buffers the
-    // last update read, that update.  If an update has been enqueued since the forward pass, the update's event covers
-    // both (they are on one stream, in that order); otherwise wait for everything enqueued on the stage's stream so far.
-    if (st->in_flight.front().update_since_forward && st->upd_recorded) {
-      PD_HIP(hipStreamWaitEvent(s, st->ev_upd, 0));
-    } else {
-      PD_HIP(hipEventRecord(st->ev_fork, st->stream));
-      PD_HIP(hipStreamWaitEvent(s, st->ev_fork, 0));
-    }
+    // Backward lane: this pass needs its minibatch's forward pass, and it overwrites the set of gradient buffers that
+    // the update before the last one read (exactly one update lies between two backward passes).  It therefore starts
+    // as soon as that update is done and runs next to the forward pass behind it.  (Holding it back until that forward
+    // pass is done, so that it runs next to the following update instead, was slower: VGG16 classifier stage 0.522
+    // against 0.500 ms per step.)
+    PD_HIP(hipStreamWaitEvent(s, st->ev_fwd[mb_id % st->depth], 0));
+    if (st->n_upd >= 2) PD_HIP(hipStreamWaitEvent(s, st->ev_upd[st->n_upd & 1], 0));
+    st->dz = st->dz_base + (size_t)st->bwd_set * st->dz_set_bytes;
+    st->part = st->part_base + (size_t)st->bwd_set * st->part_set_bytes;
+    st->bwd_set ^= 1;
   }
   float* const ws = st->ws_b ? st->ws_b : st->ws;  // (the lane's own split-K workspace: a forward pass may be running)
   const int v = st->in_flight.front().version;  // the version this minibatch's forward read
@@ -1649,9 +1665,8 @@ int pd_update(pd_stage* st) {
   const int rc = run_update_kernels(st, nv, false);
   if (rc != PD_OK) return rc;
   if (st->stream_b) {
-    PD_HIP(hipEventRecord(st->ev_upd, st->stream));
-    st->upd_recorded = true;
-    for (InFlight& f : st->in_flight) f.update_since_forward = true;
+    PD_HIP(hipEventRecord(st->ev_upd[st->n_upd & 1], st->stream));
+    ++st->n_upd;
   }
   st->latest = nv;
   st->grad_pending = false;
