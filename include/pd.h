@@ -154,9 +154,11 @@ typedef struct {
                                  (borrowed, default priority, not `stream`) on which the kernels of pd_backward run.
                                  In the 1F1B order F(k + depth) is followed by B(k + 1), and the two do not depend
                                  on each other: with a stream of its own the backward pass runs next to that forward
-                                 pass instead of behind it.  The library orders what it must with events: a backward
-                                 pass starts after the update before it (whose operands it overwrites) and after its
-                                 minibatch's forward pass; pd_update starts after the backward pass.  Results are the
+                                 pass instead of behind it.  The library orders what it must with events: what a
+                                 backward pass leaves for pd_update exists twice in this mode and consecutive passes
+                                 alternate, so a backward pass starts after its minibatch's forward pass and after the
+                                 update BEFORE the last one (the reader of the buffers it overwrites); pd_update
+                                 starts after the backward pass.  The arena grows by those buffers and a workspace.  Results are the
                                  same bit for bit.  What pd_backward reads from the caller (dy_dev) must be complete,
                                  or ordered by the caller on stream_backward, when it is called; what it writes
                                  (dx_dev) is complete on stream_backward, and on `stream` after the following
