@@ -269,6 +269,12 @@ int pd_stage_checkpoint_save(pd_stage* st, const char* path);
 int pd_stage_checkpoint_load(pd_stage* st, const char* path);
 int pd_checkpoint_info(const char* path, size_t* n_params, int32_t* latest, int32_t* precision);
 
+/* Waits for everything the stage has enqueued (both of its streams) and reports what only the device can know: an
+ * LSTM layer whose time steps ran in one launch has workgroups that wait for each other with a bounded number of
+ * polls; if one of them gave up, this call (like every other call that synchronises: pd_stage_get_params, ...)
+ * returns PD_ESTATE once and clears the condition.  The stage's state after that minibatch is not valid. */
+int pd_stage_check(pd_stage* st);
+
 /* Version bookkeeping: mb_id = -1 -> latest version; otherwise the version stashed for that
  * in-flight minibatch (PD_ESTATE if it is not in flight). */
 int pd_stage_version(const pd_stage* st, int32_t mb_id, int32_t* version);

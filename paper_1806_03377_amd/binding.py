@@ -84,6 +84,7 @@ _SIGS = {
     "pd_stage_get_momentum": [_vp, _vp, _sz],
     "pd_stage_overwrite_latest": [_vp, _vp, _vp, _sz],
     "pd_stage_version": [_vp, _i32, C.POINTER(_i32)],
+    "pd_stage_check": [_vp],
     "pd_stage_trace": [_vp, C.POINTER(pd_op), _sz, C.POINTER(_sz)],
     "pd_stage_set_trace_limit": [_vp, _sz],
     "pd_stage_input_slot": [_vp, _i32, C.POINTER(_vp)],
@@ -127,13 +128,15 @@ _lib.pd_linear_fwd_bf16_static_max_bytes.restype = _sz
 _lib.pd_linear_fwd_bf16_static_max_bytes.argtypes = []
 _lib.pd_set_conv_halo.restype = C.c_int
 _lib.pd_set_conv_halo.argtypes = [_i32]
+_lib.pd_set_recurrence_kernel.restype = C.c_int
+_lib.pd_set_recurrence_kernel.argtypes = [_i32, C.c_uint32, C.c_uint32]
 _lib.pd_set_big_gemm_waves.restype = C.c_int
 _lib.pd_set_big_gemm_waves.argtypes = [_i32]
 _lib.pd_set_big_tile_threshold.restype = C.c_int
 _lib.pd_set_big_tile_threshold.argtypes = [_i32]
 
 EXPORTED = sorted(list(_SIGS) + ["pd_last_error", "pd_gemm_workspace_bytes", "pd_set_big_tile_threshold",
-                                 "pd_linear_fwd_bf16_static_max_bytes", "pd_set_big_gemm_waves", "pd_set_conv_halo"])
+                                 "pd_linear_fwd_bf16_static_max_bytes", "pd_set_big_gemm_waves", "pd_set_conv_halo", "pd_set_recurrence_kernel"])
 
 
 def pd_last_error() -> str:
@@ -346,6 +349,14 @@ def pd_stage_version(stage: int, mb_id: int = -1) -> int:
 
 def pd_set_conv_halo(on: int) -> int:
     return int(_lib.pd_set_conv_halo(on))
+
+
+def pd_set_recurrence_kernel(multi_step: int, spin_limit: int = 0, extra_arrivals: int = 0) -> int:
+    return int(_lib.pd_set_recurrence_kernel(multi_step, spin_limit, extra_arrivals))
+
+
+def pd_stage_check(stage: int):
+    _check(_lib.pd_stage_check(stage))
 
 
 def pd_set_big_gemm_waves(waves: int) -> int:

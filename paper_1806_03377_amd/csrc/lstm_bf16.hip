@@ -4,6 +4,10 @@
 #include "mfma_util.h"
 #include "pd_kernels.h"
 
+#include <mutex>
+#include <set>
+#include <utility>
+
 namespace pd {
 namespace {
 
@@ -210,6 +214,280 @@ __global__ __launch_bounds__(512) void lstm_step_bwd_kernel(const bf16_t* __rest
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// All time steps of a layer in ONE launch (forward, and the back-propagation through time).
+// A workgroup owns 16 minibatch rows x 16 hidden units for the whole sequence and keeps its slice of the recurrent
+// weights in LDS (forward: the 4 x 16 gate rows of W_hh, 64 x H; backward: 16 rows of W_hh^T, 16 x 4H) and its cell
+// state / cell gradient in registers.  What the workgroups of one row group exchange per step is the hidden state
+// (forward) or the gate gradients (backward) of those 16 rows: written with agent-scope stores (they go through to
+// memory instead of staying in the XCD's own L2), counted in with one agent-scope atomic per workgroup after the
+// stores have completed (s_waitcnt vmcnt(0)), and read by the others with agent-scope loads once the row group's
+// counter shows that all of its workgroups have arrived -- no cache-wide write-back or invalidate, which costs tens
+// of microseconds per step on this multi-die part (measured: 47 us per step with fences, 4-6 us this way, against
+// about 10 us for a dependent launch per step).  The grid must be resident at once: at most one workgroup per compute
+// unit (the LDS slice sees to "at most"), grid <= number of compute units (the launcher checks).  EVERY WAIT IS
+// BOUNDED: a workgroup that polls `spin_limit` times without success, or sees the status word set, sets the status
+// word and leaves; the others follow at their next poll, so the launch always ends.  The host reads the status word at
+// its next synchronisation and reports the stage as failed.
+// The arithmetic is that of the per-step kernels, in the same order (the waves split the reduction the same way and
+// their partial tiles are added in wave order), so the results are bit-identical.
+// ------------------------------------------------------------------------------------------------
+typedef unsigned int seq_v4u __attribute__((ext_vector_type(4)));
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void seq_load16_agent(seq_v4u& dst, const void* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ uint4 seq_u4(const seq_v4u& v) { return make_uint4(v.x, v.y, v.z, v.w); }
+
+// thread 0 of the workgroup waits until *counter >= want; false if it gave up (status set)
+__device__ __forceinline__ bool seq_wait(unsigned* counter, unsigned want, unsigned* status, unsigned spin_limit) {
+  unsigned spins = 0;
+  while ((int)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - want) < 0) {
+    if (++spins > spin_limit || __hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+      __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return false;
+    }
+    __builtin_amdgcn_s_sleep(1);
+  }
+  return true;
+}
+
+constexpr int kSeqMaxSteps = 8;  // reduction steps of 32 per wave: forward H <= 1024 on 4 waves
+
+// sync: [0 .. n_rg) arrival counters (zeroed by the launcher), [kSeqStatusWord] status.  extra_arrivals: test hook,
+// added to what a wait expects (a wait that can never succeed must still end).
+__global__ __launch_bounds__(256, 1) void lstm_seq_fwd_kernel(float* __restrict__ gates, bf16_t* __restrict__ hbuf,
+                                                              const bf16_t* __restrict__ whh,
+                                                              float* __restrict__ cbuf, unsigned* __restrict__ sync,
+                                                              int B, int H, int T, int row_bytes, unsigned spin_limit,
+                                                              unsigned extra_arrivals) {
+  extern __shared__ __attribute__((aligned(16))) char seq_lds[];
+  __shared__ float red[4][16][65];
+  __shared__ uint16_t hs[16][16];
+  __shared__ int give_up;
+  const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  const int n_rg = (B + 15) / 16, n_ug = gridDim.x / n_rg;
+  const int rg = blockIdx.x % n_rg, ug = blockIdx.x / n_rg;
+  const int u0 = ug * 16, r0 = rg * 16;
+  unsigned* const counter = sync + rg;
+  unsigned* const status = sync + kSeqStatusWord;
+  // W_hh slice -> LDS: row 16 q + u = gate q, unit u0 + u (zeros past H)
+  {
+    const int cpr = H / 8;  // 16-byte chunks per row
+    for (int i = t; i < 64 * cpr; i += 256) {
+      const int row = i / cpr, ch = i - row * cpr, q = row >> 4, u = u0 + (row & 15);
+      const uint4 v = u < H ? ldg16(whh + ((size_t)q * H + u) * H + ch * 8) : zero16();
+      *reinterpret_cast<uint4*>(seq_lds + (size_t)row * row_bytes + ch * 16) = v;
+    }
+  }
+  if (t == 0) give_up = 0;
+  __syncthreads();
+  const int kq = ((H + 127) / 128) * 32;  // reduction elements per wave (as in the per-step kernel)
+  const int k0 = w * kq, k1 = (k0 + kq) < H ? (k0 + kq) : H;
+  const int cl = l & 15;
+  const bool arow_ok = r0 + cl < B;
+  const int erow = t >> 4, eu = t & 15;
+  const bool eok = r0 + erow < B && u0 + eu < H;
+  const size_t BH = (size_t)B * H;
+  float cstate = eok ? cbuf[(size_t)(r0 + erow) * H + u0 + eu] : 0.f;  // c_{-1}
+  for (int step = 0; step < T; ++step) {
+    float gin[4] = {0.f, 0.f, 0.f, 0.f};
+    if (eok) {
+      const float* gp = gates + ((size_t)step * B + r0 + erow) * 4 * H + u0 + eu;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) gin[q] = gp[(size_t)q * H];
+    }
+    f32x4 acc[4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    if (step > 0) {
+      if (t == 0 && !seq_wait(counter, (unsigned)step * n_ug + extra_arrivals, status, spin_limit)) give_up = 1;
+      __syncthreads();
+      if (give_up) return;
+      // Every lane issues all of its loads, from clamped addresses; what lies outside its share is zeroed after the
+      // wait.  (A load under a condition would leave the compiler free to copy the destination register at the end
+      // of the conditional block, before the data has arrived.)
+      const bf16_t* hrow = hbuf + (size_t)step * BH + (size_t)(arow_ok ? r0 + cl : B - 1) * H;  // h_{step-1}
+      seq_v4u a[kSeqMaxSteps];
+#pragma unroll
+      for (int st = 0; st < kSeqMaxSteps; ++st) {
+        const int k = k0 + 32 * st + 8 * (l >> 4);
+        seq_load16_agent(a[st], hrow + (k < H - 8 ? k : H - 8));
+      }
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                   :
+                   : "memory");
+#pragma unroll
+      for (int st = 0; st < kSeqMaxSteps; ++st) {
+        const int k = k0 + 32 * st + 8 * (l >> 4);
+        if (k0 + 32 * st < k1) {  // (wave-uniform)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const uint4 b = k < k1 ? *reinterpret_cast<const uint4*>(seq_lds + (size_t)(16 * q + cl) * row_bytes + k * 2)
+                                   : zero16();
+            const uint4 av = (k < k1 && arow_ok) ? seq_u4(a[st]) : zero16();
+            acc[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(av), frag(b), acc[q], 0, 0, 0);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[w][4 * (l >> 4) + r][16 * q + cl] = acc[q][r];
+    __syncthreads();
+    float hval = 0.f;
+    if (eok) {
+      float a4[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = 16 * q + eu;
+        a4[q] = gin[q] + (((red[0][erow][col] + red[1][erow][col]) + red[2][erow][col]) + red[3][erow][col]);
+      }
+      const float ig = sigmoidf(a4[0]), fg = sigmoidf(a4[1]), gg = tanhf(a4[2]), og = sigmoidf(a4[3]);
+      cstate = fg * cstate + ig * gg;
+      float* gp = gates + ((size_t)step * B + r0 + erow) * 4 * H + u0 + eu;
+      gp[0] = ig; gp[(size_t)H] = fg; gp[(size_t)2 * H] = gg; gp[(size_t)3 * H] = og;
+      cbuf[(size_t)(step + 1) * BH + (size_t)(r0 + erow) * H + u0 + eu] = cstate;
+      hval = og * tanhf(cstate);
+    }
+    hs[erow][eu] = f2bf(hval);
+    __syncthreads();
+    if (t < 128) {  // h_step -> memory, two units per lane, agent scope
+      const int row = t >> 3, pr = t & 7, u = u0 + 2 * pr;
+      if (r0 + row < B && u < H) {  // (H is even: units come in pairs)
+        const uint32_t v = (uint32_t)hs[row][2 * pr] | ((uint32_t)hs[row][2 * pr + 1] << 16);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(hbuf + (size_t)(step + 1) * BH + (size_t)(r0 + row) * H + u);
+        __hip_atomic_store(dst, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+constexpr int kSeqMaxStepsBwd = 16;  // reduction steps of 32 per wave: 4H <= 4096 on 8 waves
+
+__global__ __launch_bounds__(512, 1) void lstm_seq_bwd_kernel(const bf16_t* __restrict__ dh_out, bf16_t* __restrict__ dG,
+                                                              const bf16_t* __restrict__ whh_t,
+                                                              const float* __restrict__ gates,
+                                                              const float* __restrict__ cbuf, unsigned* __restrict__ sync,
+                                                              int B, int H, int T, int row_bytes, unsigned spin_limit,
+                                                              unsigned extra_arrivals) {
+  extern __shared__ __attribute__((aligned(16))) char seq_lds[];
+  __shared__ float red[8][16][17];
+  __shared__ uint16_t das[16][4][16];
+  __shared__ int give_up;
+  const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  const int n_rg = (B + 15) / 16, n_ug = gridDim.x / n_rg;
+  const int rg = blockIdx.x % n_rg, ug = blockIdx.x / n_rg;
+  const int j0 = ug * 16, r0 = rg * 16;
+  const int K = 4 * H;
+  unsigned* const counter = sync + rg;
+  unsigned* const status = sync + kSeqStatusWord;
+  {  // W_hh^T slice -> LDS: row u = hidden unit j0 + u, 4H reduction elements (zeros past H)
+    const int cpr = K / 8;
+    for (int i = t; i < 16 * cpr; i += 512) {
+      const int row = i / cpr, ch = i - row * cpr, u = j0 + row;
+      const uint4 v = u < H ? ldg16(whh_t + (size_t)u * K + ch * 8) : zero16();
+      *reinterpret_cast<uint4*>(seq_lds + (size_t)row * row_bytes + ch * 16) = v;
+    }
+  }
+  if (t == 0) give_up = 0;
+  __syncthreads();
+  const int kq = ((K + 255) / 256) * 32;
+  const int k0 = w * kq, k1 = (k0 + kq) < K ? (k0 + kq) : K;
+  const int cl = l & 15;
+  const bool arow_ok = r0 + cl < B;
+  const int erow = (t >> 4) & 15, ecol = t & 15;
+  const bool eok = t < 256 && r0 + erow < B && j0 + ecol < H;
+  const size_t BH = (size_t)B * H;
+  float dcs = 0.f;  // running dL/dc of this thread's (row, unit)
+  for (int step = T - 1; step >= 0; --step) {
+    float ig = 0.f, fg = 0.f, gg = 0.f, og = 0.f, cc = 0.f, cp = 0.f, dho = 0.f;
+    if (eok) {
+      const size_t idx = (size_t)(r0 + erow) * H + j0 + ecol;
+      const float* gp = gates + ((size_t)step * B + r0 + erow) * 4 * H + j0 + ecol;
+      ig = gp[0]; fg = gp[(size_t)H]; gg = gp[(size_t)2 * H]; og = gp[(size_t)3 * H];
+      cc = cbuf[(size_t)(step + 1) * BH + idx];
+      cp = cbuf[(size_t)step * BH + idx];
+      if (dh_out) dho = bf2f(dh_out[(size_t)step * BH + idx]);
+    }
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (step < T - 1) {
+      if (t == 0 && !seq_wait(counter, (unsigned)(T - 1 - step) * n_ug + extra_arrivals, status, spin_limit)) give_up = 1;
+      __syncthreads();
+      if (give_up) return;
+      const bf16_t* arow = dG + ((size_t)(step + 1) * B + (arow_ok ? r0 + cl : B - 1)) * K;  // da_{step+1}
+      seq_v4u a[kSeqMaxStepsBwd];
+#pragma unroll
+      for (int st = 0; st < kSeqMaxStepsBwd; ++st) {  // (unconditional loads from clamped addresses, as in the forward kernel)
+        const int k = k0 + 32 * st + 8 * (l >> 4);
+        seq_load16_agent(a[st], arow + (k < K - 8 ? k : K - 8));
+      }
+      // (two statements: an inline-assembly statement takes at most 30 operands; volatile ones keep their order)
+      asm volatile("s_waitcnt vmcnt(0)"
+                   : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                   :
+                   : "memory");
+      asm volatile(""
+                   : "+v"(a[8]), "+v"(a[9]), "+v"(a[10]), "+v"(a[11]), "+v"(a[12]), "+v"(a[13]), "+v"(a[14]), "+v"(a[15])
+                   :
+                   : "memory");
+#pragma unroll
+      for (int st = 0; st < kSeqMaxStepsBwd; ++st) {
+        const int k = k0 + 32 * st + 8 * (l >> 4);
+        if (k0 + 32 * st < k1) {
+          const uint4 b = k < k1 ? *reinterpret_cast<const uint4*>(seq_lds + (size_t)cl * row_bytes + k * 2) : zero16();
+          const uint4 av = (k < k1 && arow_ok) ? seq_u4(a[st]) : zero16();
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(frag(av), frag(b), acc, 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[w][4 * (l >> 4) + r][cl] = acc[r];
+    __syncthreads();
+    if (t < 256) {
+      float d[4] = {0.f, 0.f, 0.f, 0.f};
+      if (eok) {
+        float rec = 0.f;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) rec += red[q][erow][ecol];
+        const float dh = step < T - 1 ? dho + rec : dho;  // (the last step has no recurrent term: keep a -0 as it is)
+        const float tc = tanhf(cc);
+        const float dcv = dcs + dh * og * (1.f - tc * tc);
+        d[0] = dcv * gg * ig * (1.f - ig);
+        d[1] = dcv * cp * fg * (1.f - fg);
+        d[2] = dcv * ig * (1.f - gg * gg);
+        d[3] = dh * tc * og * (1.f - og);
+        dcs = dcv * fg;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) das[erow][q][ecol] = f2bf(d[q]);
+    }
+    __syncthreads();
+    {  // da_step -> memory: 16 rows x 4 gates x 8 pairs of units = 512 words, one per thread, agent scope
+      const int row = t >> 5, q = (t >> 3) & 3, pr = t & 7, u = j0 + 2 * pr;
+      if (r0 + row < B && u < H) {
+        const uint32_t v = (uint32_t)das[row][q][2 * pr] | ((uint32_t)das[row][q][2 * pr + 1] << 16);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(dG + ((size_t)step * B + r0 + row) * K + (size_t)q * H + u);
+        __hip_atomic_store(dst, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// LDS row stride for a slice whose rows hold `row_data_bytes`: padded so that 16 consecutive rows, read 16 bytes per
+// lane at one reduction offset, fall into 16 different groups of four banks (stride = 16 mod 256 bytes)
+int seq_row_bytes(int row_data_bytes) { return row_data_bytes + ((16 - row_data_bytes % 256) + 256) % 256; }
+constexpr size_t kSeqLdsLimit = 160 * 1024 - 18 * 1024;  // what the kernels' static arrays leave of a compute unit's LDS
+
 }  // namespace
 
 hipError_t lstm_cell_forward(hipStream_t s, float* gates, const float* rec_part, int splits, const float* c_prev, float* c,
@@ -237,6 +515,56 @@ hipError_t lstm_step_backward(hipStream_t s, const bf16_t* dh_out, const bf16_t*
   if ((H % 8) || !da_next) return hipErrorInvalidValue;
   lstm_step_bwd_kernel<<<((H + 15) / 16) * ((B + 15) / 16), 512, 0, s>>>(dh_out, da_next, whh_t, dc, gates, c, c_prev,
                                                                        da, B, H);
+  return hipGetLastError();
+}
+
+
+// The multi-step kernels apply when the whole grid (one 16 x 16 tile of rows x units per workgroup) is resident at
+// once and a workgroup's slice of the recurrent weights fits into LDS.
+bool lstm_seq_applies(int B, int H, int T, int n_cus) {
+  if (T < 2 || (H % 8) != 0 || H > 1024 || B < 1) return false;
+  const int n_rg = (B + 15) / 16, n_ug = (H + 15) / 16;
+  if (n_rg > kSeqStatusWord || n_rg * n_ug > n_cus) return false;
+  return (size_t)64 * seq_row_bytes(2 * H) <= kSeqLdsLimit && (size_t)16 * seq_row_bytes(8 * H) <= kSeqLdsLimit;
+}
+
+static hipError_t seq_prepare(hipStream_t s, unsigned* sync, const void* kernel, size_t lds) {
+  static std::mutex mu;
+  static std::set<std::pair<int, const void*>> done;  // (device, kernel): dynamic LDS above the default limit allowed
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  {
+    std::lock_guard<std::mutex> g(mu);
+    if (!done.count({dev, kernel})) {
+      e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSeqLdsLimit);
+      if (e != hipSuccess) return e;
+      done.insert({dev, kernel});
+    }
+  }
+  (void)lds;
+  return fill_zero(s, sync, kSeqStatusWord * sizeof(unsigned));  // the arrival counters; the status word is sticky
+}
+
+hipError_t lstm_seq_forward(hipStream_t s, float* gates, bf16_t* hbuf, const bf16_t* whh, float* cbuf, unsigned* sync,
+                            int B, int H, int T, unsigned spin_limit, unsigned extra_arrivals) {
+  const int n_rg = (B + 15) / 16, n_ug = (H + 15) / 16, rb = seq_row_bytes(2 * H);
+  const size_t lds = (size_t)64 * rb;
+  hipError_t e = seq_prepare(s, sync, reinterpret_cast<const void*>(&lstm_seq_fwd_kernel), lds);
+  if (e != hipSuccess) return e;
+  lstm_seq_fwd_kernel<<<n_rg * n_ug, 256, lds, s>>>(gates, hbuf, whh, cbuf, sync, B, H, T, rb, spin_limit, extra_arrivals);
+  return hipGetLastError();
+}
+
+hipError_t lstm_seq_backward(hipStream_t s, const bf16_t* dh_out, bf16_t* dG, const bf16_t* whh_t, const float* gates,
+                             const float* cbuf, unsigned* sync, int B, int H, int T, unsigned spin_limit,
+                             unsigned extra_arrivals) {
+  const int n_rg = (B + 15) / 16, n_ug = (H + 15) / 16, rb = seq_row_bytes(8 * H);
+  const size_t lds = (size_t)16 * rb;
+  hipError_t e = seq_prepare(s, sync, reinterpret_cast<const void*>(&lstm_seq_bwd_kernel), lds);
+  if (e != hipSuccess) return e;
+  lstm_seq_bwd_kernel<<<n_rg * n_ug, 512, lds, s>>>(dh_out, dG, whh_t, gates, cbuf, sync, B, H, T, rb, spin_limit,
+                                                    extra_arrivals);
   return hipGetLastError();
 }
 

@@ -209,6 +209,15 @@ hipError_t lstm_cell_backward(hipStream_t s, const bf16_t* dh_out, const float* 
 // The same two steps with the recurrent product fused in (one launch per time step):
 //   forward : gates += h_prev[B][H] * whh[4H][H]^T, then as lstm_cell_forward        (h_prev not null)
 //   backward: dh = dh_out + da_next[B][4H] * whh_t[H][4H]^T, then as lstm_cell_backward  (da_next not null)
+// The whole sequence of a layer in one launch (see lstm_bf16.hip).  sync: kSeqSyncWords device words owned by the
+// stage (arrival counters per row group, then the sticky status word: non-zero = a workgroup gave up waiting).
+constexpr int kSeqStatusWord = 16, kSeqSyncWords = 32;
+bool lstm_seq_applies(int B, int H, int T, int n_cus);
+hipError_t lstm_seq_forward(hipStream_t s, float* gates, bf16_t* hbuf, const bf16_t* whh, float* cbuf, unsigned* sync,
+                            int B, int H, int T, unsigned spin_limit, unsigned extra_arrivals);
+hipError_t lstm_seq_backward(hipStream_t s, const bf16_t* dh_out, bf16_t* dG, const bf16_t* whh_t, const float* gates,
+                             const float* cbuf, unsigned* sync, int B, int H, int T, unsigned spin_limit,
+                             unsigned extra_arrivals);
 hipError_t lstm_step_forward(hipStream_t s, float* gates, const bf16_t* h_prev, const bf16_t* whh, const float* c_prev,
                              float* c, bf16_t* h, int B, int H);
 hipError_t lstm_step_backward(hipStream_t s, const bf16_t* dh_out, const bf16_t* da_next, const bf16_t* whh_t, float* dc,

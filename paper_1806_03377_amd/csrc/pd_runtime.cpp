@@ -14,6 +14,8 @@
 #include <deque>
 #include <new>
 #include <string>
+#include <map>
+#include <mutex>
 #include <vector>
 
 #include "../../include/pd.h"
@@ -210,6 +212,11 @@ struct pd_stage {
   float* ws = nullptr;
   size_t ws_bytes = 0;
   float* row_loss = nullptr;
+  // multi-step recurrence kernels: arrival counters + sticky status word, one block for the forward and one for the
+  // backward direction (with a backward stream the two can be in flight together)
+  unsigned* seq_sync = nullptr;
+  bool seq_used = false;     // a multi-step kernel has been enqueued since the status word was last read
+  int n_cus = 0;
   // replicated stage (Section 3.3, Section 4 "Data Parallelism"): every replica is a pd_stage of its own (stash,
   // scratch, stream); ring, master and mom of a secondary replica point into the primary's arena, and each replica
   // leaves the fp32 gradient of its minibatch in gradbuf (laid out like one parameter set) for the summed update
@@ -288,7 +295,7 @@ struct Plan {
   size_t o_rem = 0;
   bool any_split = false;
   size_t o_ring = 0, o_master = 0, o_mom = 0, o_in = 0, o_stash = 0, o_dz = 0, o_grad = 0, o_ws = 0, o_rowloss = 0;
-  size_t o_pp = 0, o_part = 0, o_wt = 0, o_gradbuf = 0, o_ws_b = 0;
+  size_t o_pp = 0, o_part = 0, o_wt = 0, o_gradbuf = 0, o_ws_b = 0, o_seq = 0;
   bool lane_b = false;
   int replicas = 1;
   size_t total = 0;
@@ -592,8 +599,79 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
   p.o_blk_dy = o; o += p.blk_dy_bytes;
   p.o_blk_dx = o; o += p.blk_dx_bytes;
   p.o_rowloss = o; o += align_up((size_t)p.lin.back().rows * 4, 256);
+  p.o_seq = o; o += align_up((size_t)2 * pd::kSeqSyncWords * sizeof(unsigned), 256);
   p.total = o;
   return PD_OK;
+}
+
+
+// ---- multi-step recurrence kernels: host side ------------------------------------------------------------------
+// Such a kernel needs its whole grid resident at once and takes almost every compute unit's LDS.  Two of them
+// dispatched together (two stages on two streams, or a stage's forward and backward lanes) could each get part of the
+// chip and wait for the rest until their spin limits expire, so all launches of one process are chained: each waits
+// for the event of the one before it, on whatever stream that was.
+int g_seq_mode = 0;                     // 0: one launch per time step (default); 1: multi-step kernels where they apply
+unsigned g_seq_spin_limit = 4000000u;   // polls (each at least a memory round trip) before a workgroup gives up
+unsigned g_seq_extra_arrivals = 0u;     // test hook: makes every wait expect arrivals that never come
+struct SeqChain {
+  std::mutex mu;
+  std::map<int, std::vector<hipEvent_t>> ring;  // per device
+  std::map<int, size_t> next;
+  std::map<int, hipEvent_t> last;
+};
+SeqChain& seq_chain() { static SeqChain c; return c; }
+constexpr size_t kSeqChainEvents = 64;
+
+// call with the launch's stream BEFORE the launch (wait for the previous multi-step kernel) ...
+hipError_t seq_chain_enter(hipStream_t s) {
+  SeqChain& c = seq_chain();
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> g(c.mu);
+  auto it = c.last.find(dev);
+  if (it != c.last.end() && it->second) e = hipStreamWaitEvent(s, it->second, 0);
+  return e;
+}
+// ... and AFTER it (this launch becomes the one to wait for)
+hipError_t seq_chain_leave(hipStream_t s) {
+  SeqChain& c = seq_chain();
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  std::lock_guard<std::mutex> g(c.mu);
+  std::vector<hipEvent_t>& ring = c.ring[dev];
+  if (ring.empty()) {
+    ring.assign(kSeqChainEvents, nullptr);
+    for (hipEvent_t& ev : ring) {
+      e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+      if (e != hipSuccess) { ring.clear(); return e; }
+    }
+  }
+  hipEvent_t ev = ring[c.next[dev]++ % kSeqChainEvents];
+  e = hipEventRecord(ev, s);
+  if (e == hipSuccess) c.last[dev] = ev;
+  return e;
+}
+
+// (Not under stream capture: the chain's events lie outside the capture, and a replayed graph would bypass the chain.)
+bool seq_wanted(const pd_stage* st, hipStream_t s, int B, int H, int T) {
+  if (g_seq_mode != 1 || !st->bf16 || !st->seq_sync || !pd::lstm_seq_applies(B, H, T, st->n_cus)) return false;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  return hipStreamIsCapturing(s, &cs) == hipSuccess && cs == hipStreamCaptureStatusNone;
+}
+
+// After a synchronisation: has a multi-step kernel of this stage given up waiting for its peers?
+int seq_check(pd_stage* st) {
+  if (!st->seq_used) return PD_OK;
+  st->seq_used = false;
+  unsigned flags[2] = {0u, 0u};
+  for (int d = 0; d < 2; ++d)
+    PD_HIP(hipMemcpy(&flags[d], st->seq_sync + d * pd::kSeqSyncWords + pd::kSeqStatusWord, sizeof(unsigned), hipMemcpyDeviceToHost));
+  if (!flags[0] && !flags[1]) return PD_OK;
+  PD_HIP(hipMemset(st->seq_sync, 0, (size_t)2 * pd::kSeqSyncWords * sizeof(unsigned)));
+  return fail(PD_ESTATE, "a multi-step recurrence kernel gave up waiting for its peer workgroups (%s pass): the stage's "
+              "activations, gradients and weights after that minibatch are not valid", flags[0] ? "forward" : "backward");
 }
 
 int check_stage(const pd_stage* st) { return st ? PD_OK : fail(PD_EINVAL, "stage is null"); }
@@ -651,12 +729,18 @@ int create_stage(const pd_stage_config* cfg, pd_stage* primary, void* stream, vo
     st->ws_b = reinterpret_cast<float*>(a + p.o_ws_b);
   }
   st->row_loss = reinterpret_cast<float*>(a + p.o_rowloss);
+  st->seq_sync = reinterpret_cast<unsigned*>(a + p.o_seq);
+  {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess) st->n_cus = n;
+  }
   st->pp = a + p.o_pp; st->pp_bytes = p.pp_bytes; st->part = a + p.o_part; st->wt = a + p.o_wt;
   st->dz_base = st->dz; st->part_base = st->part;
   st->dz_set_bytes = p.dz_bytes; st->part_set_bytes = p.part_bytes;
   st->blk_dy = a + p.o_blk_dy; st->blk_dx = a + p.o_blk_dx; st->blk_dx_stride = p.blk_dx_stride;
   st->borrowed_out.assign(p.depth, nullptr);
   hipError_t e = primary ? hipSuccess : pd::fill_zero(st->stream, st->mom, p.p_pad * 4);
+  if (e == hipSuccess) e = pd::fill_zero(st->stream, st->seq_sync, (size_t)2 * pd::kSeqSyncWords * sizeof(unsigned));
   // padding between layers inside the gradient buffer is never written by a gradient kernel: keep it at zero
   if (e == hipSuccess && st->gradbuf) e = pd::fill_zero(st->stream, st->gradbuf, p.p_pad * 4);
   if (e == hipSuccess && st->gradbuf) e = hipEventCreateWithFlags(&st->ev_rep, hipEventDisableTiming);
@@ -831,6 +915,7 @@ int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   if (check_owner(st)) return PD_ESTATE;
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu parameters, got %zu", st->n_params, n);
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   for (pd_stage* r : st->secondaries) {  // they read the same weights and restart with them
     PD_HIP(r->sync_all());
     r->latest = 0; r->last_fwd = -1; r->in_flight.clear(); r->grad_pending = false; r->trace.clear();
@@ -849,6 +934,7 @@ int pd_stage_set_params(pd_stage* st, const float* host_params, size_t n) {
   if (st->rem) PD_HIP(split_master_from_staging(st, 0));  // ring slot 0 = version 0
   PD_HIP(pd::fill_zero(st->stream, st->mom, st->p_pad * 4));
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   st->latest = 0; st->last_fwd = -1; st->in_flight.clear(); st->grad_pending = false; st->trace.clear();
   return PD_OK;
 }
@@ -860,10 +946,12 @@ int pd_stage_get_params(pd_stage* st, int32_t version, int32_t ring_copy, float*
   if (version > st->latest || version <= st->latest - st->ring_depth)
     return fail(PD_ESTATE, "version %d is not in the ring (latest %d, depth %d)", version, st->latest, st->ring_depth);
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   const bool from_master = st->bf16 && version == st->latest && !ring_copy;
   if (from_master && st->rem) {
     PD_HIP(materialize_master(st));
     PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   }
   if (!st->bf16 || from_master) {
     const float* src = from_master ? st->master : reinterpret_cast<const float*>(st->ring_slot(version));
@@ -910,6 +998,7 @@ int pd_stage_set_momentum(pd_stage* st, const float* host_mom, size_t n) {
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   if (!st->in_flight.empty() || st->grad_pending) return fail(PD_ESTATE, "minibatches in flight");
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   for (const Linear& L : st->lin) {
     if (!L.n_w) continue;
     PD_HIP(hipMemcpy(st->mom + L.w_off, host_mom + L.flat_w, L.n_w * 4, hipMemcpyHostToDevice));
@@ -922,6 +1011,7 @@ int pd_stage_get_momentum(pd_stage* st, float* host_out, size_t n) {
   if (check_stage(st) || !host_out) return fail(PD_EINVAL, "null argument");
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   for (const Linear& L : st->lin) {
     if (!L.n_w) continue;
     PD_HIP(hipMemcpy(host_out + L.flat_w, st->mom + L.w_off, L.n_w * 4, hipMemcpyDeviceToHost));
@@ -1045,6 +1135,7 @@ int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const floa
   if (n != st->n_params) return fail(PD_EINVAL, "expected %zu values, got %zu", st->n_params, n);
   if (st->grad_pending) return fail(PD_ESTATE, "a gradient is pending: call pd_update first");
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   char* slot = st->ring_slot(st->latest);
   float* dst32 = st->bf16 ? st->master : reinterpret_cast<float*>(slot);
   for (const Linear& L : st->lin) {
@@ -1065,7 +1156,14 @@ int pd_stage_overwrite_latest(pd_stage* st, const float* host_params, const floa
   }
   if (host_params && st->rem) PD_HIP(split_master_from_staging(st, st->latest));
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   return PD_OK;
+}
+
+int pd_stage_check(pd_stage* st) {
+  if (check_stage(st)) return PD_EINVAL;
+  PD_HIP(st->sync_all());
+  return seq_check(st);
 }
 
 int pd_stage_version(const pd_stage* st, int32_t mb_id, int32_t* version) {
@@ -1149,6 +1247,7 @@ int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer
   }
   if (n != cnt) return fail(PD_EINVAL, "tensor has %zu elements, caller gave %zu", cnt, n);
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   if (!st->bf16 || (what == 0 && st->has_loss && layer == nl - 1)) {  // logits are fp32 in either mode
     PD_HIP(hipMemcpy(host_out, src, cnt * 4, hipMemcpyDeviceToHost));
     return PD_OK;
@@ -1182,6 +1281,7 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
   }
   if (n != cnt) return fail(PD_EINVAL, "tensor has %zu elements, caller gave %zu", cnt, n);
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   if (as_f32) {
     PD_HIP(hipMemcpy(dst, host_in, cnt * 4, hipMemcpyHostToDevice));
     return PD_OK;
@@ -1272,13 +1372,20 @@ static int forward_impl(pd_stage* st, int32_t mb_id, int32_t version, const void
       pd::bf16_t* hbuf = reinterpret_cast<pd::bf16_t*>(slot + L.y_off);
       PD_HIP(pd::linear_fwd_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wih, wp + L.b_off, nullptr, gates, L.rows,
                                  4 * H, L.in, false, st->ws, st->ws_bytes));
-      for (int t = 0; t < L.T; ++t) {
-        if (t == 0)
-          PD_HIP(pd::lstm_cell_forward(s, gates, nullptr, 0, cbuf, cbuf + (size_t)B * H, hbuf + (size_t)B * H, B, H));
-        else
-          PD_HIP(pd::lstm_step_forward(s, gates + (size_t)t * B * 4 * H, hbuf + (size_t)t * B * H, whh,
-                                       cbuf + (size_t)t * B * H, cbuf + (size_t)(t + 1) * B * H,
-                                       hbuf + (size_t)(t + 1) * B * H, B, H));
+      if (seq_wanted(st, s, B, H, L.T)) {  // all time steps in one launch
+        PD_HIP(seq_chain_enter(s));
+        PD_HIP(pd::lstm_seq_forward(s, gates, hbuf, whh, cbuf, st->seq_sync, B, H, L.T, g_seq_spin_limit, g_seq_extra_arrivals));
+        PD_HIP(seq_chain_leave(s));
+        st->seq_used = true;
+      } else {
+        for (int t = 0; t < L.T; ++t) {
+          if (t == 0)
+            PD_HIP(pd::lstm_cell_forward(s, gates, nullptr, 0, cbuf, cbuf + (size_t)B * H, hbuf + (size_t)B * H, B, H));
+          else
+            PD_HIP(pd::lstm_step_forward(s, gates + (size_t)t * B * 4 * H, hbuf + (size_t)t * B * H, whh,
+                                         cbuf + (size_t)t * B * H, cbuf + (size_t)(t + 1) * B * H,
+                                         hbuf + (size_t)(t + 1) * B * H, B, H));
+        }
       }
     } else if (L.kind == K_CONV) {
       const pd::bf16_t* wp = reinterpret_cast<const pd::bf16_t*>(w);
@@ -1427,15 +1534,23 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
       // in the forward pass, so transpose once per backward pass instead of transposing tiles at every step
       pd::bf16_t* whh_t = reinterpret_cast<pd::bf16_t*>(st->wt);
       PD_HIP(pd::transpose_bf16(s, whh, whh_t, 4 * H, H));
-      for (int t = L.T - 1; t >= 0; --t) {
-        if (t == L.T - 1)
-          PD_HIP(pd::lstm_cell_backward(s, dh_out + (size_t)t * B * H, nullptr, 0, dc, gates + (size_t)t * B * 4 * H,
-                                        cbuf + (size_t)(t + 1) * B * H, cbuf + (size_t)t * B * H,
-                                        dG + (size_t)t * B * 4 * H, B, H));
-        else
-          PD_HIP(pd::lstm_step_backward(s, dh_out + (size_t)t * B * H, dG + (size_t)(t + 1) * B * 4 * H, whh_t, dc,
-                                        gates + (size_t)t * B * 4 * H, cbuf + (size_t)(t + 1) * B * H,
-                                        cbuf + (size_t)t * B * H, dG + (size_t)t * B * 4 * H, B, H));
+      if (seq_wanted(st, s, B, H, L.T)) {  // all time steps in one launch (the cell gradient stays in registers)
+        PD_HIP(seq_chain_enter(s));
+        PD_HIP(pd::lstm_seq_backward(s, dh_out, dG, whh_t, gates, cbuf, st->seq_sync + pd::kSeqSyncWords, B, H, L.T,
+                                     g_seq_spin_limit, g_seq_extra_arrivals));
+        PD_HIP(seq_chain_leave(s));
+        st->seq_used = true;
+      } else {
+        for (int t = L.T - 1; t >= 0; --t) {
+          if (t == L.T - 1)
+            PD_HIP(pd::lstm_cell_backward(s, dh_out + (size_t)t * B * H, nullptr, 0, dc, gates + (size_t)t * B * 4 * H,
+                                          cbuf + (size_t)(t + 1) * B * H, cbuf + (size_t)t * B * H,
+                                          dG + (size_t)t * B * 4 * H, B, H));
+          else
+            PD_HIP(pd::lstm_step_backward(s, dh_out + (size_t)t * B * H, dG + (size_t)(t + 1) * B * 4 * H, whh_t, dc,
+                                          gates + (size_t)t * B * 4 * H, cbuf + (size_t)(t + 1) * B * H,
+                                          cbuf + (size_t)t * B * H, dG + (size_t)t * B * 4 * H, B, H));
+        }
       }
     }
     char* out;
@@ -1774,6 +1889,7 @@ int pd_stage_profile_read(pd_stage* st, pd_layer_profile* out, size_t cap, size_
   if (units.size() > cap) return fail(PD_ENOMEM, "profile has %zu units, capacity %zu", units.size(), cap);
   if (!out) return fail(PD_EINVAL, "out is null");
   PD_HIP(st->sync_all());
+  if (const int seq_rc = seq_check(st)) return seq_rc;
   // parameters updated by the one multi-layer launch: its time is shared out by parameter count (the launch
   // streams master weights and momentum once, so its time is proportional to them)
   double batch_params = 0;
@@ -2131,6 +2247,13 @@ int pd_set_big_tile_threshold(int32_t min_tiles) {
 
 int pd_set_big_gemm_waves(int32_t waves) { return pd::set_big_gemm_waves(waves); }
 int pd_set_conv_halo(int32_t on) { return pd::set_conv_halo(on); }
+int pd_set_recurrence_kernel(int32_t multi_step, uint32_t spin_limit, uint32_t extra_arrivals) {
+  const int old = g_seq_mode;
+  g_seq_mode = multi_step ? 1 : 0;
+  g_seq_spin_limit = spin_limit ? spin_limit : 4000000u;
+  g_seq_extra_arrivals = extra_arrivals;
+  return old;
+}
 
 size_t pd_gemm_workspace_bytes(int32_t M, int32_t N, int32_t K) { return pd::gemm_bf16_workspace_bytes(M, N, K); }
 
