@@ -884,9 +884,9 @@ def main():
                          "on for the VGG16 classifier stage (0.531 -> 0.500 ms per step), the VGG16 convolution stage (4.76 -> 4.55 ms) "
                          "and the Inception-shaped pipeline (11.35 -> 10.43 ms), off for the LSTM pipeline (no gain) and the fp32 MLP "
                          "pipeline (0.12 -> 0.18 ms: every extra event hop costs more than its tiny kernels)")
-    ap.add_argument("--recurrence", choices=["per-step", "multi-step"], default="per-step",
-                    help="LSTM layers: one launch per time step (default) or all time steps of a pass in one launch "
-                         "(bit-identical results; S2VT pipeline 4.3 vs 4.64 ms per minibatch, a single LSTM stage 1.65 vs 1.53 ms)")
+    ap.add_argument("--recurrence", choices=["per-step", "multi-step"], default="multi-step",
+                    help="LSTM layers: all time steps of a pass in one launch (default) or one launch per time step "
+                         "(bit-identical results; a single LSTM stage 1.29 vs 1.65 ms, the S2VT pipeline 4.15 ms either way)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="default workload only: skip the secondary workloads appended under `extra`")
     ap.add_argument("--rows", type=int, nargs="+", default=None, help="gemm_sweep: the row counts to run (default: 64 ... 8192)")

@@ -60,18 +60,19 @@ int pd_set_conv_halo(int32_t on);
  * the record off and clears it).  Host-side only. */
 int pd_stage_set_trace_limit(pd_stage* st, size_t max_ops);
 
-/* The recurrence of an LSTM layer.  multi_step = 0 (the default): one launch per time step.  multi_step != 0: layers
- * whose grid of 16 x 16 tiles (rows x hidden units) fits the chip, with hidden size <= 1024, run all time steps of a
- * pass in ONE launch whose workgroups exchange the hidden state (forward) or the gate gradients (backward) through
- * memory and wait for each other per step with BOUNDED polling; results are bit-identical to the per-step kernels.
- * Measured on MI355X (hidden 1000, minibatch 64, 80 steps): 7.0 against 7.8 us per step for a stage on its own (1.53
- * against 1.65 ms per F + B + U), but 4.64 against 4.3 ms per minibatch for the two-stage pipeline, where such a launch
- * keeps the other stage's kernels off the chip for its whole duration -- hence not the default.
- * spin_limit: polls before a workgroup gives up (0: the default of 4,000,000); extra_arrivals: added to what every such
- * wait expects, so that with a small spin_limit every wait provably gives up -- for testing that the launch still ends
- * and that the failure is reported (PD_ESTATE from pd_stage_check or the stage's next synchronising call).  Returns the
- * old multi_step setting.  Process-wide, not thread-safe. */
-int pd_set_recurrence_kernel(int32_t multi_step, uint32_t spin_limit, uint32_t extra_arrivals);
+/* The recurrence of an LSTM layer.  multi_step != 0 (the default): layers whose grid of 16 x 16 tiles (rows x hidden
+ * units) fits the chip, with hidden size <= 1024, run all time steps of a pass in ONE launch whose workgroups exchange
+ * the hidden state (forward) or the gate gradients (backward) through memory and wait for each other's results per step
+ * with BOUNDED polling; other layers, and everything under stream capture, take one launch per time step.
+ * multi_step = 0: one launch per time step always.  Results are bit-identical either way.
+ * Measured on MI355X (hidden 1000, minibatch 64, 80 steps): 5.6 against 7.8 us per step for a stage on its own (1.29
+ * against 1.65 ms per F + B + U); 4.15 ms per minibatch either way for the two-stage pipeline on one GPU, where such a
+ * launch keeps the other stage's kernels off the chip for its duration and per-step launches of two stages interleave.
+ * spin_limit: fetches before a wave gives up waiting for its peers' results (0: the default of 4,000,000); starve != 0:
+ * no workgroup publishes its results, so that no wait can succeed -- for testing that the launch still ends and that
+ * the failure is reported (PD_ESTATE from pd_stage_check or the stage's next synchronising call).  Returns the old
+ * multi_step setting.  Process-wide, not thread-safe. */
+int pd_set_recurrence_kernel(int32_t multi_step, uint32_t spin_limit, uint32_t starve);
 
 #ifdef __cplusplus
 }

@@ -351,8 +351,8 @@ def pd_set_conv_halo(on: int) -> int:
     return int(_lib.pd_set_conv_halo(on))
 
 
-def pd_set_recurrence_kernel(multi_step: int, spin_limit: int = 0, extra_arrivals: int = 0) -> int:
-    return int(_lib.pd_set_recurrence_kernel(multi_step, spin_limit, extra_arrivals))
+def pd_set_recurrence_kernel(multi_step: int, spin_limit: int = 0, starve: int = 0) -> int:
+    return int(_lib.pd_set_recurrence_kernel(multi_step, spin_limit, starve))
 
 
 def pd_stage_check(stage: int):

@@ -26,6 +26,13 @@ __global__ __launch_bounds__(256) void zero_kernel(uint32_t* __restrict__ dst, s
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < words; i += stride) dst[i] = 0u;
 }
 
+// 16 bytes per lane; dst 16-byte aligned, `quads` pieces of four words
+__global__ __launch_bounds__(256) void fill_pattern_kernel(uint4* __restrict__ dst, size_t quads, uint32_t value) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const uint4 v = make_uint4(value, value, value, value);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < quads; i += stride) dst[i] = v;
+}
+
 __global__ __launch_bounds__(256) void f32_to_bf16_kernel(const float* __restrict__ src, bf16_t* __restrict__ dst,
                                                           size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -292,6 +299,12 @@ hipError_t copy_bytes(hipStream_t s, const void* src, void* dst, size_t bytes) {
 hipError_t fill_zero(hipStream_t s, void* dst, size_t bytes) {
   if (bytes == 0) return hipSuccess;
   zero_kernel<<<grid_for(bytes / 4), 256, 0, s>>>(static_cast<uint32_t*>(dst), bytes / 4);
+  return hipGetLastError();
+}
+hipError_t fill_pattern16(hipStream_t s, void* dst, size_t bytes, uint32_t value) {
+  if (bytes == 0) return hipSuccess;
+  if ((bytes % 16) != 0 || (reinterpret_cast<uintptr_t>(dst) & 15) != 0) return hipErrorInvalidValue;
+  fill_pattern_kernel<<<grid_for(bytes / 16), 256, 0, s>>>(static_cast<uint4*>(dst), bytes / 16, value);
   return hipGetLastError();
 }
 hipError_t f32_to_bf16(hipStream_t s, const float* src, bf16_t* dst, size_t n) {

@@ -210,14 +210,16 @@ hipError_t lstm_cell_backward(hipStream_t s, const bf16_t* dh_out, const float* 
 //   forward : gates += h_prev[B][H] * whh[4H][H]^T, then as lstm_cell_forward        (h_prev not null)
 //   backward: dh = dh_out + da_next[B][4H] * whh_t[H][4H]^T, then as lstm_cell_backward  (da_next not null)
 // The whole sequence of a layer in one launch (see lstm_bf16.hip).  sync: kSeqSyncWords device words owned by the
-// stage (arrival counters per row group, then the sticky status word: non-zero = a workgroup gave up waiting).
+// stage; word kSeqStatusWord is the sticky status (non-zero = a workgroup gave up waiting).  The launchers first fill
+// the part of hbuf / dG that the launch produces with the "not written yet" pattern.  starve: test hook (no workgroup
+// publishes its results, so no wait can succeed).
 constexpr int kSeqStatusWord = 16, kSeqSyncWords = 32;
 bool lstm_seq_applies(int B, int H, int T, int n_cus);
 hipError_t lstm_seq_forward(hipStream_t s, float* gates, bf16_t* hbuf, const bf16_t* whh, float* cbuf, unsigned* sync,
-                            int B, int H, int T, unsigned spin_limit, unsigned extra_arrivals);
+                            int B, int H, int T, unsigned spin_limit, unsigned starve);
 hipError_t lstm_seq_backward(hipStream_t s, const bf16_t* dh_out, bf16_t* dG, const bf16_t* whh_t, const float* gates,
                              const float* cbuf, unsigned* sync, int B, int H, int T, unsigned spin_limit,
-                             unsigned extra_arrivals);
+                             unsigned starve);
 hipError_t lstm_step_forward(hipStream_t s, float* gates, const bf16_t* h_prev, const bf16_t* whh, const float* c_prev,
                              float* c, bf16_t* h, int B, int H);
 hipError_t lstm_step_backward(hipStream_t s, const bf16_t* dh_out, const bf16_t* da_next, const bf16_t* whh_t, float* dc,
@@ -246,6 +248,8 @@ hipError_t linear_wgrad_update_f32(hipStream_t s, const float* dz, const float* 
 // ---- element-wise and loss kernels (misc_kernels.hip) --------------------------------------------
 hipError_t copy_bytes(hipStream_t s, const void* src, void* dst, size_t bytes);  // bytes % 4 == 0 or any
 hipError_t fill_zero(hipStream_t s, void* dst, size_t bytes);
+// every 32-bit word of dst[0 .. bytes) = value; dst 16-byte aligned, bytes a multiple of 16
+hipError_t fill_pattern16(hipStream_t s, void* dst, size_t bytes, uint32_t value);
 hipError_t f32_to_bf16(hipStream_t s, const float* src, bf16_t* dst, size_t n);
 hipError_t transpose_bf16(hipStream_t s, const bf16_t* src, bf16_t* dst, int R, int C);  // dst[C][R] = src[R][C]^T
 hipError_t bf16_to_f32(hipStream_t s, const bf16_t* src, float* dst, size_t n);

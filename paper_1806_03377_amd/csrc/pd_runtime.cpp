@@ -610,9 +610,9 @@ int make_plan(const pd_stage_config* c, Plan& p, bool secondary = false) {
 // dispatched together (two stages on two streams, or a stage's forward and backward lanes) could each get part of the
 // chip and wait for the rest until their spin limits expire, so all launches of one process are chained: each waits
 // for the event of the one before it, on whatever stream that was.
-int g_seq_mode = 0;                     // 0: one launch per time step (default); 1: multi-step kernels where they apply
+int g_seq_mode = 1;                     // 1: multi-step kernels where they apply (default); 0: one launch per time step
 unsigned g_seq_spin_limit = 4000000u;   // polls (each at least a memory round trip) before a workgroup gives up
-unsigned g_seq_extra_arrivals = 0u;     // test hook: makes every wait expect arrivals that never come
+unsigned g_seq_starve = 0u;     // test hook: no workgroup publishes its results
 struct SeqChain {
   std::mutex mu;
   std::map<int, std::vector<hipEvent_t>> ring;  // per device
@@ -1374,7 +1374,7 @@ static int forward_impl(pd_stage* st, int32_t mb_id, int32_t version, const void
                                  4 * H, L.in, false, st->ws, st->ws_bytes));
       if (seq_wanted(st, s, B, H, L.T)) {  // all time steps in one launch
         PD_HIP(seq_chain_enter(s));
-        PD_HIP(pd::lstm_seq_forward(s, gates, hbuf, whh, cbuf, st->seq_sync, B, H, L.T, g_seq_spin_limit, g_seq_extra_arrivals));
+        PD_HIP(pd::lstm_seq_forward(s, gates, hbuf, whh, cbuf, st->seq_sync, B, H, L.T, g_seq_spin_limit, g_seq_starve));
         PD_HIP(seq_chain_leave(s));
         st->seq_used = true;
       } else {
@@ -1537,7 +1537,7 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
       if (seq_wanted(st, s, B, H, L.T)) {  // all time steps in one launch (the cell gradient stays in registers)
         PD_HIP(seq_chain_enter(s));
         PD_HIP(pd::lstm_seq_backward(s, dh_out, dG, whh_t, gates, cbuf, st->seq_sync + pd::kSeqSyncWords, B, H, L.T,
-                                     g_seq_spin_limit, g_seq_extra_arrivals));
+                                     g_seq_spin_limit, g_seq_starve));
         PD_HIP(seq_chain_leave(s));
         st->seq_used = true;
       } else {
@@ -2247,11 +2247,11 @@ int pd_set_big_tile_threshold(int32_t min_tiles) {
 
 int pd_set_big_gemm_waves(int32_t waves) { return pd::set_big_gemm_waves(waves); }
 int pd_set_conv_halo(int32_t on) { return pd::set_conv_halo(on); }
-int pd_set_recurrence_kernel(int32_t multi_step, uint32_t spin_limit, uint32_t extra_arrivals) {
+int pd_set_recurrence_kernel(int32_t multi_step, uint32_t spin_limit, uint32_t starve) {
   const int old = g_seq_mode;
   g_seq_mode = multi_step ? 1 : 0;
   g_seq_spin_limit = spin_limit ? spin_limit : 4000000u;
-  g_seq_extra_arrivals = extra_arrivals;
+  g_seq_starve = starve;
   return old;
 }
 

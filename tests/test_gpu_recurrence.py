@@ -1,11 +1,11 @@
 """All time steps of an LSTM layer in one launch (the multi-step recurrence kernels) against one launch per step.
 
 The multi-step kernels do the per-step kernels' arithmetic in the same order, so a stage run either way must give the
-same bits: losses, input gradients, weights, momentum.  (The per-step path is the default and is what the oracle-parity tests of
-test_gpu_parity.py run; some of them are repeated here with the multi-step kernels switched on.)
+same bits: losses, input gradients, weights, momentum.  (The multi-step path is the default wherever a layer's grid fits the chip, so the oracle-parity tests of
+test_gpu_parity.py run it; some of them are repeated here with one launch per step forced.)
 
-The workgroups of a multi-step kernel wait for each other with a BOUNDED number of polls.  The last test makes every
-such wait expect an arrival that never comes, with a small poll limit: the launches must still end, and the stage must
+The workgroups of a multi-step kernel wait for each other with a BOUNDED number of polls.  The last test makes the
+workgroups withhold what their peers wait for, with a small poll limit: the launches must still end, and the stage must
 report the failure at its next synchronising call.  No kernel is made to hang: giving up is the kernel's own exit path.
 """
 import numpy as np
@@ -24,7 +24,7 @@ SEED = gen.BASE_SEED + 23
 @pytest.fixture
 def per_step_then_restore():
     yield
-    pd.pd_set_recurrence_kernel(0, 0, 0)
+    pd.pd_set_recurrence_kernel(1, 0, 0)     # the default
 
 
 def _both_ways(layers, B, T, M, depth, lane=False, with_loss=True):
@@ -69,9 +69,9 @@ def test_s2vt_widths_same_bits(per_step_then_restore):
     _both_ways([("lstm", 1000, 1000, 10)], B=64, T=10, M=3, depth=1, with_loss=False)
 
 
-def test_oracle_parity_with_multi_step_kernels(per_step_then_restore):
+def test_oracle_parity_with_one_launch_per_step(per_step_then_restore):
     from test_gpu_parity import _seq_case
-    pd.pd_set_recurrence_kernel(1, 0, 0)
+    pd.pd_set_recurrence_kernel(0, 0, 0)
     _seq_case([[("lstm", 16, 24, 6), ("linear", 24, 40, False), ("softmax_xent", 40)]], B=4, T=6, noam=1, M=4,
               depth_override=2)
     _seq_case([[("lstm", 24, 16, 16), ("linear", 16, 40, False), ("softmax_xent", 40)]], B=32, T=16, noam=1, M=3,
@@ -87,9 +87,9 @@ def test_a_wait_that_cannot_succeed_ends_and_is_reported(per_step_then_restore):
     y = torch.zeros((T * B, 64), dtype=torch.bfloat16, device=dev())
     g = GpuStage(layers, p, minibatch=B, precision=pd.PD_BF16_F32ACC, in_flight_override=1, stream=torch.cuda.Stream())
     try:
-        pd.pd_set_recurrence_kernel(1, 200, 1)      # every wait expects one arrival too many; give up after 200 polls
+        pd.pd_set_recurrence_kernel(1, 200, 1)      # nobody publishes; give up after 200 fetches
         pd.pd_forward(g.h, 0, x.data_ptr(), 0, y.data_ptr(), 0)
-        pd.pd_set_recurrence_kernel(0, 0, 0)
+        pd.pd_set_recurrence_kernel(1, 0, 0)
         with pytest.raises(pd.PdError) as e:
             pd.pd_stage_check(g.h)                  # returns: the launch ended although no wait could succeed
         assert "gave up" in str(e.value) and "forward" in str(e.value)
