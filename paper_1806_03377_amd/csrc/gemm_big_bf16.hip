@@ -543,11 +543,12 @@ __global__ __launch_bounds__(64 * NW, 1) void gemm_dma64_kernel(const bf16_t* __
     offa[q] = ((uint32_t)ra * (uint32_t)lda + g * 8) * 2u;
     offb[q] = ((uint32_t)rb * (uint32_t)ldb + g * 8) * 2u;
   }
+  const uint32_t lds0 = lds_address_of(smem) + (uint32_t)w * 1024u;  // this wave's first destination in ring slot 0
   auto load_a = [&](int q, int slot, int stage) {
-    dma_load16(A + (stage < T ? stage : T - 1) * EK, offa[q], smem + slot * ETILE + (q * NW + w) * 1024);
+    dma_load16_at(A + (stage < T ? stage : T - 1) * EK, offa[q], lds0 + (uint32_t)(slot * ETILE + q * NW * 1024));
   };
   auto load_b = [&](int q, int slot, int stage) {
-    dma_load16(Bm + (stage < T ? stage : T - 1) * EK, offb[q], smem + slot * ETILE + (q * NW + w) * 1024);
+    dma_load16_at(Bm + (stage < T ? stage : T - 1) * EK, offb[q], lds0 + (uint32_t)(slot * ETILE + q * NW * 1024));
   };
 
   f32x16 acc[NI][NJ];
@@ -680,6 +681,9 @@ __device__ __forceinline__ void dma_chunk64(const bf16_t* lane_src, char* unifor
   const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(uniform_lds_dst));
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(lane_src), "s"(lds_addr) : "memory", "m0");
 }
+__device__ __forceinline__ void dma_chunk64_at(const bf16_t* lane_src, uint32_t uniform_lds_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(lane_src), "s"(uniform_lds_addr) : "memory", "m0");
+}
 #pragma clang diagnostic pop
 __device__ __forceinline__ bf16x8 tn_frag(const char* lo, const char* hi) {
   const tn_v4i16_t a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((tn_lds_v4i16_t*)lo);
@@ -747,9 +751,10 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
     lstep[q] = (size_t)TR * ld;
     ldst[q] = (is_x ? TILE : 0) + (id & 15) * 1024;
   }
+  const uint32_t lds_base = lds_address_of(smem);
   auto issue = [&](int q, char* stage) {  // q-th load of this wave for the next stage to be fetched; advances
     const bool ok = lp[q] != nullptr && lrow[q] < m_hi;
-    dma_chunk64(ok ? lp[q] : zero, stage + ldst[q]);
+    dma_chunk64_at(ok ? lp[q] : zero, lds_base + (uint32_t)(stage - smem) + (uint32_t)ldst[q]);
     if (lp[q] != nullptr) lp[q] += lstep[q];
     lrow[q] += TR;
   };
@@ -894,6 +899,7 @@ __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restric
     bcut[q] = r >= tail;
   }
   const size_t bstep = (size_t)DK * ldb;
+  const uint32_t lds_base = lds_address_of(smem);
   int a_st = 0;  // reduction stage the next A loads fetch (clamped: the surplus is never read)
   int b_left[QB];  // stages the B loads have still to fetch
 #pragma unroll
@@ -901,14 +907,15 @@ __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restric
   auto issue = [&](int q, char* stage) {
     if (q < QA) {
       const int sidx = a_st < T ? a_st : T - 1;
-      dma_load16(A + sidx * DK, (partial && sidx == T - 1) ? aoffs_t[q] : aoffs[q], stage + (q * NW + w) * 1024);
+      dma_load16_at(A + sidx * DK, (partial && sidx == T - 1) ? aoffs_t[q] : aoffs[q],
+                    lds_base + (uint32_t)(stage - smem) + (uint32_t)((q * NW + w) * 1024));
       if (q == QA - 1) ++a_st;
     } else {
       // (B loads of stages past the end would read rows >= R of w: zeros instead)
       const int qb = q - QA;
       const bool live = b_left[qb] > 0;
       const bool cut = !live || bp[qb] == nullptr || (partial && b_left[qb] == 1 && bcut[qb]);
-      dma_chunk64(cut ? zero : bp[qb], stage + ATILE + (qb * NW + w) * 1024);
+      dma_chunk64_at(cut ? zero : bp[qb], lds_base + (uint32_t)(stage - smem) + (uint32_t)(ATILE + (qb * NW + w) * 1024));
       if (live) {
         --b_left[qb];
         if (bp[qb] != nullptr) bp[qb] += bstep;

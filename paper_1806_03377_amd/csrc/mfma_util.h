@@ -46,6 +46,18 @@ __device__ __forceinline__ void dma_load16(const bf16_t* uniform_base, uint32_t 
                : "v"(lane_byte_offset), "s"(uniform_base), "s"(lds_addr)
                : "memory", "m0");
 }
+// The same with the LDS destination given as a 32-bit LDS address that the caller has formed once (lds_address_of
+// below) plus uniform arithmetic of its own: converting a generic pointer per load costs a null check and a select
+// (four scalar instructions in front of every load, a dependent chain in a wave whose time belongs to the MFMAs).
+__device__ __forceinline__ uint32_t lds_address_of(const void* p) {
+  return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_t*)(p));
+}
+__device__ __forceinline__ void dma_load16_at(const bf16_t* uniform_base, uint32_t lane_byte_offset, uint32_t uniform_lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_byte_offset), "s"(uniform_base), "s"(uniform_lds_addr)
+               : "memory", "m0");
+}
 // the same for data that is read once per kernel (a weight stream): non-temporal, so that it is not kept in the
 // caches at the expense of reusable lines
 __device__ __forceinline__ void dma_load16_stream(const bf16_t* uniform_base, uint32_t lane_byte_offset,
