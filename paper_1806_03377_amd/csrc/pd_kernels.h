@@ -132,7 +132,7 @@ struct ConvEpilogue {
   bf16_t* out;
 };
 // 3 x 3, stride 1, pad 1 with Ci a multiple of 64: the kernel that keeps a tile's input with its halo in LDS
-// (conv_halo_bf16.hip); conv_forward_bf16 / conv_dgrad_bf16 dispatch to it.  set_conv_halo(0 / 1) switches it off / on
+// (conv_halo_bf16.hip); conv_forward_bf16 / conv_dgrad_bf16 dispatch to it.  set_conv_halo(0 / 1 / 2) switches it off / on / on without the weights-resident variant
 // (returns the previous setting; any other argument only queries).
 bool conv3x3_halo_applies(const ConvGeom& g, const bf16_t* x, const bf16_t* w);
 hipError_t conv3x3_halo_bf16(hipStream_t s, const bf16_t* x, const bf16_t* w, const ConvGeom& g, const ConvEpilogue& ep);

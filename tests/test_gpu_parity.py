@@ -358,10 +358,14 @@ WIDE_CONVS = [(2, 12, 12, 64, 256, 3, 3, 1, 1, 1), (1, 20, 20, 32, 768, 1, 1, 1,
 # that are not multiples of the 8 x 32 pixel tile, one to four channel chunks, ragged output-channel tiles, several
 # images; the same shapes with that kernel switched off go through the implicit-GEMM kernel
 HALO_CONVS = [(2, 13, 37, 64, 64, 3, 3, 1, 1, 1), (1, 9, 40, 128, 72, 3, 3, 1, 1, 1), (3, 8, 8, 64, 136, 3, 3, 1, 1, 1),
-              (1, 17, 33, 256, 128, 3, 3, 1, 1, 1), (2, 5, 70, 192, 40, 3, 3, 1, 1, 1), (1, 56, 56, 64, 256, 3, 3, 1, 1, 1)]
+              (1, 17, 33, 256, 128, 3, 3, 1, 1, 1), (2, 5, 70, 192, 40, 3, 3, 1, 1, 1), (1, 56, 56, 64, 256, 3, 3, 1, 1, 1),
+              # 64 -> at most 64 channels: the variant whose workgroups keep the weights and walk over several tiles
+              # (more tiles than compute units, so some workgroups take two; fewer filters than a tile has columns)
+              (9, 72, 100, 64, 56, 3, 3, 1, 1, 1), (3, 20, 70, 64, 40, 3, 3, 1, 1, 1)]
 
 
-@pytest.mark.parametrize("halo", [1, 0])
+# halo: 1 = on, 2 = on without the weights-resident variant, 0 = off
+@pytest.mark.parametrize("halo", [1, 2, 0])
 @pytest.mark.parametrize("geom", HALO_CONVS)
 def test_conv_fwd_and_dgrad_halo_kernel(geom, halo):
     old = pd.pd_set_conv_halo(halo)
