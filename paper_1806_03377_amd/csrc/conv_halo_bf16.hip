@@ -279,26 +279,26 @@ __global__ __launch_bounds__(256, 1) void conv3x3_halo_resident_kernel(const bf1
     const int py = pix / HP_W, px = pix - py * HP_W;
     prel[q] = (py * g.W + px) * HCC + 8 * ((l & 7) ^ halo_swz(pix0));
   }
-  auto load_patch = [&](int buf, int tl) {
-    const int tx = tl % tiles_x, r = tl / tiles_x, ty = r % tiles_y, n = r / tiles_y;
-    const int x0 = tx * HT_W, y0 = ty * HT_H;
-    // (element offset of the patch's pixel (0, 0) = image pixel (y0 - 1, x0 - 1); outside the image for border tiles,
-    // where it is only used for pixels that lie inside)
-    const long long base = (((long long)n * g.H + (y0 - 1)) * g.W + (x0 - 1)) * HCC;
-    const uint32_t dst = lds_base + (uint32_t)(buf * HP_BYTES + w * 1024);
-    if (y0 >= 1 && x0 >= 1 && y0 + HT_H < g.H && x0 + HT_W < g.W) {  // the whole patch lies inside the image
-#pragma unroll
-      for (int q = 0; q < PQ; ++q) halo_dma16_at(X + (base + prel[q]), dst + (uint32_t)(q * NWV * 1024));
+  // the q-th load of this wave for the patch of the tile at image n, pixel (y0, x0), into buffer buf.  base: element
+  // offset of the patch's pixel (0, 0) = image pixel (y0 - 1, x0 - 1) (outside the image for border tiles, where it is
+  // only used for pixels that lie inside); inside: the whole patch lies inside the image
+  auto load_patch_one = [&](int q, int buf, long long base, int y0, int x0, bool inside) {
+    const uint32_t dst = lds_base + (uint32_t)(buf * HP_BYTES + (q * NWV + w) * 1024);
+    if (inside) {
+      halo_dma16_at(X + (base + prel[q]), dst);
     } else {
-#pragma unroll
-      for (int q = 0; q < PQ; ++q) {
-        const int pix0 = (q * NWV + w) * 8 + (l >> 3), pix = pix0 < HP_PIX ? pix0 : HP_PIX - 1;
-        const int py = pix / HP_W, iy = y0 - 1 + py, ix = x0 - 1 + (pix - py * HP_W);
-        const bool ok = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
-        halo_dma16_at(ok ? X + (base + prel[q]) : zero, dst + (uint32_t)(q * NWV * 1024));
-      }
+      const int pix0 = (q * NWV + w) * 8 + (l >> 3), pix = pix0 < HP_PIX ? pix0 : HP_PIX - 1;
+      const int py = pix / HP_W, iy = y0 - 1 + py, ix = x0 - 1 + (pix - py * HP_W);
+      const bool ok = (unsigned)iy < (unsigned)g.H && (unsigned)ix < (unsigned)g.W;
+      halo_dma16_at(ok ? X + (base + prel[q]) : zero, dst);
     }
   };
+  auto tile_origin = [&](int tl, int& n, int& y0, int& x0) {
+    const int tx = tl % tiles_x, r = tl / tiles_x, ty = r % tiles_y;
+    n = r / tiles_y; y0 = ty * HT_H; x0 = tx * HT_W;
+  };
+  auto patch_base = [&](int n, int y0, int x0) { return (((long long)n * g.H + (y0 - 1)) * g.W + (x0 - 1)) * HCC; };
+  auto patch_inside = [&](int y0, int x0) { return y0 >= 1 && x0 >= 1 && y0 + HT_H < g.H && x0 + HT_W < g.W; };
   // A operands of the MFMAs (the matrix rows = output channels): filter 32 j + (l & 31), reduction elements
   // 16 ks + 8 (l >> 5) .. + 7 of every tap (zeros past Co)
   uint4 bw[9][KS][NJ];
@@ -311,7 +311,14 @@ __global__ __launch_bounds__(256, 1) void conv3x3_halo_resident_kernel(const bf1
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) bw[tap][ks][j] = co < g.Co ? ldg16(wrow + tap * HCC + 16 * ks) : zero16();
   }
-  load_patch(0, tile);
+  {
+    int n, y0, x0;
+    tile_origin(tile, n, y0, x0);
+    const long long base = patch_base(n, y0, x0);
+    const bool inside = patch_inside(y0, x0);
+#pragma unroll
+    for (int q = 0; q < PQ; ++q) load_patch_one(q, 0, base, y0, x0, inside);
+  }
 
   // B operands (the matrix columns = pixels): output row r of the patch, lane's pixel (l & 31), tap (dy, dx): patch
   // pixel (r + dy) * 34 + (l & 31) + dx.  Slot of reduction step ks, half h: (2 ks + h) ^ ((pixel >> 1) & 7).
@@ -336,7 +343,12 @@ __global__ __launch_bounds__(256, 1) void conv3x3_halo_resident_kernel(const bf1
     // the buffer the next patch goes to
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (has_next) load_patch(cur ^ 1, next_tile);
+    // the next tile's patch is requested from inside the MFMA loop below, one load every third reduction step (the
+    // address arithmetic and the issue then cost nothing: the wave is waiting for the matrix pipe there anyway)
+    int nn, ny0, nx0;
+    tile_origin(has_next ? next_tile : tile, nn, ny0, nx0);
+    const long long nbase = patch_base(nn, ny0, nx0);
+    const bool ninside = patch_inside(ny0, nx0);
 
     // acc[i][j][r]: channel 32 j + 8 (r >> 2) + 4 (l >> 5) + (r & 3) of pixel (l & 31) in patch row NI w + i
     f32x16 acc[NI][NJ];
@@ -362,6 +374,7 @@ __global__ __launch_bounds__(256, 1) void conv3x3_halo_resident_kernel(const bf1
 #pragma unroll
         for (int i = 0; i < NI; ++i)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(bw[s36 / KS][s36 % KS][j]), frag(a[s36 % 3][i]), acc[i][j], 0, 0, 0);
+      if (s36 % 3 == 1 && s36 / 3 < PQ && has_next) load_patch_one(s36 / 3, cur ^ 1, nbase, ny0, nx0, ninside);
       __builtin_amdgcn_sched_barrier(0);
     }
     // this wave's requests for the next patch have landed and its reads of this one are done; after the barrier that
