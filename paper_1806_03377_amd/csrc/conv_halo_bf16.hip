@@ -62,6 +62,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __re
   constexpr int kSmem = HP_BYTES + WR * WTILE;
   static_assert(kSmem >= HT_H * HT_W * OLD * 2, "the output staging area must fit");
   __shared__ __attribute__((aligned(1024))) char smem[kSmem];
+  __shared__ __attribute__((aligned(16))) float sbias[BN];
   char* const wring = smem + HP_BYTES;
   const int t = threadIdx.x, l = t & 63;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w / WNW, wn = w % WNW;
@@ -81,6 +82,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __re
   const int co0 = tc * BN, x0 = tx * HT_W, y0 = ty * HT_H;
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_halo_zero);
   const int K9 = 9 * g.Ci, chunks = g.Ci / HCC;
+  // (read in the epilogue, many barriers from here; fetched now so that nobody waits for it there)
+  if (t < BN) sbias[t] = (ep.bias && co0 + t < g.Co) ? bf2f(ep.bias[co0 + t]) : 0.f;
 
   // patch loads: load number q * 4 + w covers patch rows 8 (q * 4 + w) .. + 7; this lane's pixel and channel group
   int poff[PQ];  // element offset of the lane's chunk for channel chunk 0, or -1 (outside the image / the patch)
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __re
 #pragma unroll
       for (int m = 0; m < MF; ++m) {
         const int i = m / NJ, j = m % NJ;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(b[c][j]), frag(a[c][i]), acc[i][j], 0, 0, 0);
         if (m == 1 && ks < WQ) {  // one load of the tile WR-1 taps ahead behind the second MFMA of each step
           __builtin_amdgcn_sched_barrier(0);
           load_wtile(ks, tau + WR - 1);
@@ -193,21 +196,29 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(const bf16_t* __re
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   __syncthreads();
 
-  // bias / ReLU / rounding in registers, then through LDS so that global traffic is 16 bytes per lane
+  // bias / ReLU / rounding in registers, then through LDS so that global traffic is 16 bytes per lane.  The filters
+  // are the MFMA's rows, so a lane holds runs of four channels of one pixel: acc[i][j][r] = channel 64 wn + 32 j +
+  // 8 (r >> 2) + 4 (l >> 5) + (r & 3) of pixel (l & 31) in patch row NI wm + i, and a run goes to LDS as 8 bytes.
   bf16_t* ot = reinterpret_cast<bf16_t*>(smem);  // [256 pixels: image row of the patch * 32 + x][OLD]
+  const float relu_floor = ep.relu ? 0.f : -__builtin_inff();
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int cl = 64 * wn + 32 * j + (l & 31), cch = co0 + cl;
-    const float bv = (ep.bias && cch < g.Co) ? bf2f(ep.bias[cch]) : 0.f;
+  for (int j = 0; j < NJ; ++j)
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int ch = 64 * wn + 32 * j + 8 * q4 + 4 * (l >> 5);
+      const float4 b4 = *reinterpret_cast<const float4*>(&sbias[ch]);
+      const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = acc[i][j][r] + bv;
-        if (ep.relu) v = fmaxf(v, 0.f);
-        ot[((NI * wm + i) * HT_W + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * OLD + cl] = f2bf(v);
+      for (int i = 0; i < NI; ++i) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = fmaxf(acc[i][j][4 * q4 + r] + bv[r], relu_floor);
+        uint2 pk;
+        pk.x = f2bf_pair(v[0], v[1]);
+        pk.y = f2bf_pair(v[2], v[3]);
+        *reinterpret_cast<uint2*>(&ot[((NI * wm + i) * HT_W + (l & 31)) * OLD + ch]) = pk;
       }
-  }
+    }
   __syncthreads();
   constexpr int CPR = BN / 8;
 #pragma unroll
