@@ -68,6 +68,34 @@ __device__ __forceinline__ void gather_tile(const bf16_t* __restrict__ X, const 
     nrow = (q / g.Ho) * g.H;
   }
   bf16_t* row = tile + t * SLD;
+  if (staged && g.kh == 3 && g.kw == 3 && g.Ci == 3) {
+    // The usual first layer: the 27 values are fetched with every index known at compile time, packed in registers
+    // and written as four 16-byte pieces (rows 80 bytes apart: 16 consecutive lanes cover all banks) instead of 32
+    // two-byte stores that meet four to a bank.
+    const int hi0 = ho * g.stride - g.ph, wi0 = wo * g.stride - g.pw;
+    const long long e00 = ((nrow + hi0) * g.W + wi0) * 3 - e_lo;  // region index of tap (0, 0), channel 0
+    uint32_t v[32];
+#pragma unroll
+    for (int a = 0; a < 3; ++a) {
+      const bool oka = live && (unsigned)(hi0 + a) < (unsigned)g.H;
+#pragma unroll
+      for (int b = 0; b < 3; ++b) {
+        const bool ok = oka && (unsigned)(wi0 + b) < (unsigned)g.W;
+        const int idx = ok ? (int)(e00 + (a * g.W + b) * 3) : 0;  // (a pixel outside the image reads element 0 and drops it)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) v[(a * 3 + b) * 3 + c] = ok ? (uint32_t)region[idx + c] : 0u;
+      }
+    }
+#pragma unroll
+    for (int k = 27; k < 32; ++k) v[k] = 0u;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<uint4*>(row + 8 * q) =
+          make_uint4(v[8 * q] | (v[8 * q + 1] << 16), v[8 * q + 2] | (v[8 * q + 3] << 16),
+                     v[8 * q + 4] | (v[8 * q + 5] << 16), v[8 * q + 6] | (v[8 * q + 7] << 16));
+    __syncthreads();
+    return;
+  }
   int k = 0;
   for (int a = 0; a < g.kh; ++a) {
     const int hi = ho * g.stride - g.ph + a;
@@ -96,9 +124,11 @@ __global__ __launch_bounds__(kThreads) void conv_smallk_fwd_kernel(const bf16_t*
   constexpr int kBytes = kRegion + 256 * SLD * 2 > 256 * OLD * 2 ? kRegion + 256 * SLD * 2 : 256 * OLD * 2;
   __shared__ __attribute__((aligned(16))) char smem[kBytes];
   __shared__ __attribute__((aligned(16))) bf16_t Bs[64 * SLD];
+  __shared__ __attribute__((aligned(16))) float sbias[64];
   bf16_t* region = reinterpret_cast<bf16_t*>(smem);
   bf16_t* As = reinterpret_cast<bf16_t*>(smem + kRegion);
   const int t = threadIdx.x, l = t & 63, w = t >> 6;
+  if (t < 64) sbias[t] = (ep.bias && t < g.Co) ? bf2f(ep.bias[t]) : 0.f;  // (published by gather_tile's barriers)
   const long long P = (long long)g.N * g.Ho * g.Wo;
   const long long p0 = (long long)blockIdx.x * 256;
   const int K = g.kh * g.kw * g.Ci;
@@ -120,46 +150,51 @@ __global__ __launch_bounds__(kThreads) void conv_smallk_fwd_kernel(const bf16_t*
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[i]), frag(b[j]), acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(b[j]), frag(a[i]), acc[i][j], 0, 0, 0);
   }
+  // (the filters are the MFMA's rows: acc[i][j][r] = channel 32 j + 8 (r >> 2) + 4 (l >> 5) + (r & 3) of pixel
+  // 64 w + 32 i + (l & 31), runs of four channels per lane)
   if (ep.mask || (reinterpret_cast<uintptr_t>(ep.out) & 15)) {  // element-wise path (not used by the stage runtime)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int c = 32 * j + (l & 31);
-      if (c >= g.Co) continue;
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const long long p = p0 + 64 * w + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-          if (p >= P) continue;
-          float v = acc[i][j][r];
-          if (ep.bias) v += bf2f(ep.bias[c]);
+          const int c = 32 * j + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
+          const long long p = p0 + 64 * w + 32 * i + (l & 31);
+          if (c >= g.Co || p >= P) continue;
+          float v = acc[i][j][r] + sbias[c];
           if (ep.relu) v = fmaxf(v, 0.f);
           uint16_t o = f2bf(v);
           const size_t off = (size_t)p * g.Co + c;
           if (ep.mask && !bf_positive(ep.mask[off])) o = 0;
           ep.out[off] = o;
         }
-    }
     return;
   }
   // bias, ReLU and rounding in registers, then through LDS: the 256 x Co tile is one contiguous piece of y
   __syncthreads();  // every wave is done reading As
   bf16_t* ot = reinterpret_cast<bf16_t*>(smem);  // [256][OLD]
+  const float relu_floor = ep.relu ? 0.f : -__builtin_inff();
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int c = 32 * j + (l & 31);
-    const float bv = (ep.bias && c < g.Co) ? bf2f(ep.bias[c]) : 0.f;
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int ch = 32 * j + 8 * q4 + 4 * (l >> 5);
+      const float4 b4 = *reinterpret_cast<const float4*>(&sbias[ch]);
+      const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = acc[i][j][r] + bv;
-        if (ep.relu) v = fmaxf(v, 0.f);
-        ot[(64 * w + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * OLD + c] = f2bf(v);
+      for (int i = 0; i < 2; ++i) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = fmaxf(acc[i][j][4 * q4 + r] + bv[r], relu_floor);
+        uint2 pk;
+        pk.x = f2bf_pair(v[0], v[1]);
+        pk.y = f2bf_pair(v[2], v[3]);
+        *reinterpret_cast<uint2*>(&ot[(64 * w + 32 * i + (l & 31)) * OLD + ch]) = pk;
       }
-  }
+    }
   __syncthreads();
   const int cpr = g.Co / 8;  // 16-byte pieces per pixel (Co % 8 == 0)
   for (int c = t; c < 256 * cpr; c += kThreads) {
