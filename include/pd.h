@@ -441,6 +441,10 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
  *               master <- master - lr*m; ring_out <- bf16(master)
  *   maxpool2x2_fwd / _bwd: 2x2 stride-2 max pooling of x[N][H][W][C]; backward routes dy to the first
  *               maximum of each window and, if relu_mask != 0, zeroes positions where x <= 0
+ *   maxpool2x2_fwd_route / _bwd_route: the same pair with the routing recorded by the forward pass: route (device,
+ *               written by _fwd_route, read by _bwd_route; may be NULL in _fwd_route) holds
+ *               N*(H/2)*(W/2)*(C/8) 32-bit words, four bits per output element; _bwd_route gives exactly what _bwd
+ *               gives without reading x or y (this is what a stage's backward pass runs)
  *   pool2d_fwd / _bwd: pooling with any window, stride and padding (is_max != 0: max, padding never wins, pad
  *               must be 0 < window; else average with divisor window*window); pgeom = {N, H, W, C, window,
  *               stride, pad} (7 ints, host); backward as for PD_MAXPOOL2D / PD_AVGPOOL2D */
@@ -455,6 +459,10 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
 int pd_maxpool2x2_fwd_bf16(void* stream, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C);
 int pd_maxpool2x2_bwd_bf16(void* stream, const void* x, const void* y, const void* dy, void* dx, int32_t N, int32_t H,
                            int32_t W, int32_t C, int32_t relu_mask);
+int pd_maxpool2x2_fwd_route_bf16(void* stream, const void* x, void* y, uint32_t* route, int32_t N, int32_t H, int32_t W,
+                                 int32_t C);
+int pd_maxpool2x2_bwd_route_bf16(void* stream, const uint32_t* route, const void* dy, void* dx, int32_t N, int32_t H,
+                                 int32_t W, int32_t C, int32_t relu_mask);
 int pd_pool2d_fwd_bf16(void* stream, int32_t is_max, const void* x, void* y, const int32_t* pgeom);
 int pd_pool2d_bwd_bf16(void* stream, int32_t is_max, const void* x, const void* y, const void* dy, void* dx,
                        const int32_t* pgeom, int32_t relu_mask);

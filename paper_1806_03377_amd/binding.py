@@ -113,6 +113,8 @@ _SIGS = {
     "pd_conv_wgrad_update_bf16": [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, C.POINTER(_i32), _f32, _f32],
     "pd_maxpool2x2_fwd_bf16": [_vp, _vp, _vp, _i32, _i32, _i32, _i32],
     "pd_maxpool2x2_bwd_bf16": [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32],
+    "pd_maxpool2x2_fwd_route_bf16": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32],
+    "pd_maxpool2x2_bwd_route_bf16": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32],
     "pd_pool2d_fwd_bf16": [_vp, _i32, _vp, _vp, C.POINTER(_i32)],
     "pd_pool2d_bwd_bf16": [_vp, _i32, _vp, _vp, _vp, _vp, C.POINTER(_i32), _i32],
 }
@@ -540,6 +542,14 @@ def pd_maxpool2x2_fwd_bf16(stream, x, y, N, H, W, Cn):
 
 def pd_maxpool2x2_bwd_bf16(stream, x, y, dy, dx, N, H, W, Cn, relu_mask):
     _check(_lib.pd_maxpool2x2_bwd_bf16(stream, x, y, dy, dx, N, H, W, Cn, int(relu_mask)))
+
+
+def pd_maxpool2x2_fwd_route_bf16(stream, x, y, route, N, H, W, Cn):
+    _check(_lib.pd_maxpool2x2_fwd_route_bf16(stream, x, y, route, N, H, W, Cn))
+
+
+def pd_maxpool2x2_bwd_route_bf16(stream, route, dy, dx, N, H, W, Cn, relu_mask):
+    _check(_lib.pd_maxpool2x2_bwd_route_bf16(stream, route, dy, dx, N, H, W, Cn, int(relu_mask)))
 
 
 def _pgeom(N, H, W, Cn, k, stride, pad):

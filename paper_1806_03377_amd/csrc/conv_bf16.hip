@@ -725,8 +725,11 @@ __global__ __launch_bounds__(256) void wgrad_reduce_update_kernel(const float* _
 // ------------------------------------------------------------------------------------------------
 // 2x2 / stride-2 max pooling over NHWC, 8 channels (16 bytes) per thread.
 // ------------------------------------------------------------------------------------------------
+// route (optional): one 32-bit word per thread, four bits per channel: bits 0-1 = the window position (2 a + b) of
+// the first maximum, bit 2 = that maximum is positive, bit 3 = it is not a NaN.  The backward pass needs nothing else
+// of x and y: it reads the gradient and these words (an eighth of y's bytes) instead of x, y and the gradient.
 __global__ __launch_bounds__(256) void maxpool2x2_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
-                                                             int N, int H, int W, int C) {
+                                                             uint32_t* __restrict__ route, int N, int H, int W, int C) {
   const int Ho = H / 2, Wo = W / 2, C8 = C / 8;
   const size_t total = (size_t)N * Ho * Wo * C8;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -739,6 +742,7 @@ __global__ __launch_bounds__(256) void maxpool2x2_fwd_kernel(const bf16_t* __res
   const size_t n = q / Ho;
   float best[8];
   uint16_t bo[8];
+  uint32_t pos[8];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -751,10 +755,52 @@ __global__ __launch_bounds__(256) void maxpool2x2_fwd_kernel(const bf16_t* __res
         if ((a == 0 && b == 0) || f > best[j]) {
           best[j] = f;
           bo[j] = v[j];
+          pos[j] = (uint32_t)(2 * a + b);
         }
       }
     }
   *reinterpret_cast<uint4*>(y + ((n * Ho + ho) * Wo + wo) * C + 8 * c8) = pack8(bo);
+  if (route) {
+    uint32_t r = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      r |= (pos[j] | (bf_positive(bo[j]) ? 4u : 0u) | (best[j] == best[j] ? 8u : 0u)) << (4 * j);
+    route[idx] = r;
+  }
+}
+
+// The backward pass from the routing words alone: dx[window position] = dy where the position is the recorded one and
+// the maximum was not a NaN (a NaN equals nothing, so the comparing kernel below routes nothing either) and, with
+// relu_mask, was positive (x at that position IS the maximum); 0 elsewhere.
+__global__ __launch_bounds__(256) void maxpool2x2_bwd_route_kernel(const uint32_t* __restrict__ route,
+                                                                   const bf16_t* __restrict__ dy, bf16_t* __restrict__ dx,
+                                                                   int N, int H, int W, int C, int relu_mask) {
+  const int Ho = H / 2, Wo = W / 2, C8 = C / 8;
+  const size_t total = (size_t)N * Ho * Wo * C8;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c8 = (int)(idx % C8);
+  size_t q = idx / C8;
+  const int wo = (int)(q % Wo);
+  q /= Wo;
+  const int ho = (int)(q % Ho);
+  const size_t n = q / Ho;
+  uint16_t dv[8];
+  unpack8(ldg16(dy + ((n * Ho + ho) * Wo + wo) * C + 8 * c8), dv);
+  const uint32_t r = route[idx];
+  const uint32_t need = relu_mask ? 12u : 8u;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      uint16_t o[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t code = (r >> (4 * j)) & 15u;
+        o[j] = ((code & 3u) == (uint32_t)(2 * a + b) && (code & need) == need) ? dv[j] : (uint16_t)0;
+      }
+      *reinterpret_cast<uint4*>(dx + ((n * H + 2 * ho + a) * W + 2 * wo + b) * C + 8 * c8) = pack8(o);
+    }
 }
 
 // dx[window] = dy at the first position whose value equals the window maximum, else 0; with relu_mask also 0
@@ -971,10 +1017,20 @@ hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, siz
   return hipGetLastError();
 }
 
-hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, int N, int H, int W, int C) {
+hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, uint32_t* route, int N, int H, int W,
+                                   int C) {
   if ((C % 8) || (H % 2) || (W % 2)) return hipErrorInvalidValue;
   const size_t total = (size_t)N * (H / 2) * (W / 2) * (C / 8);
-  maxpool2x2_fwd_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(x, y, N, H, W, C);
+  maxpool2x2_fwd_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(x, y, route, N, H, W, C);
+  return hipGetLastError();
+}
+
+hipError_t maxpool2x2_backward_routed_bf16(hipStream_t s, const uint32_t* route, const bf16_t* dy, bf16_t* dx, int N,
+                                           int H, int W, int C, bool relu_mask) {
+  if ((C % 8) || (H % 2) || (W % 2)) return hipErrorInvalidValue;
+  const size_t total = (size_t)N * (H / 2) * (W / 2) * (C / 8);
+  maxpool2x2_bwd_route_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(route, dy, dx, N, H, W, C,
+                                                                              relu_mask ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -262,7 +262,6 @@ __global__ __launch_bounds__(256, 1) void conv3x3_halo_resident_kernel(const bf1
                                                                        ConvEpilogue ep, int tiles_x, int tiles_y) {
   constexpr int NWV = 4, BN = 64, NI = 2, NJ = 2, PQ = HP_LOADS / NWV, KS = HCC / 16;
   constexpr int OLD = BN + 8;
-  constexpr int HR_W_BYTES = 0;  // (no weights in LDS)
   static_assert(HP_BYTES >= HT_H * HT_W * OLD * 2, "the output staging area must fit");
   __shared__ __attribute__((aligned(1024))) char smem[2 * HP_BYTES];
   __shared__ __attribute__((aligned(16))) float sbias[BN];

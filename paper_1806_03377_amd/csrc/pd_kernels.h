@@ -191,7 +191,12 @@ hipError_t copy_channels_bf16(hipStream_t s, const bf16_t* src, int ld_src, int 
 constexpr int kMaxBranches = 8;
 hipError_t sum_tensors_bf16(hipStream_t s, const bf16_t* const* src, int count, const bf16_t* mask, bf16_t* dst,
                             size_t n);
-hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, int N, int H, int W, int C);
+// route: null, or N * (H/2) * (W/2) * (C/8) words that record where each maximum came from (four bits per output
+// element); maxpool2x2_backward_routed_bf16 then needs neither x nor y
+hipError_t maxpool2x2_forward_bf16(hipStream_t s, const bf16_t* x, bf16_t* y, uint32_t* route, int N, int H, int W,
+                                   int C);
+hipError_t maxpool2x2_backward_routed_bf16(hipStream_t s, const uint32_t* route, const bf16_t* dy, bf16_t* dx, int N,
+                                           int H, int W, int C, bool relu_mask);
 // dx = dy routed to the first maximum of each window (row-major), times (x > 0) if relu_mask
 hipError_t maxpool2x2_backward_bf16(hipStream_t s, const bf16_t* x, const bf16_t* y, const bf16_t* dy, bf16_t* dx, int N,
                                     int H, int W, int C, bool relu_mask);

@@ -655,6 +655,13 @@ hipError_t seq_chain_leave(hipStream_t s) {
 }
 
 // (Not under stream capture: the chain's events lie outside the capture, and a replayed graph would bypass the chain.)
+// Where a 2x2 max-pooling layer keeps the routing words of a minibatch (four bits per output element): behind its
+// bf16 output in the layer's region of the stash slot, which is laid out for four bytes per element.  (Always the
+// slot's own region, also when the stage's last output lives in a buffer borrowed from the consumer.)
+static uint32_t* pool_route(const pd_stage* st, char* slot, const Linear& L) {
+  return reinterpret_cast<uint32_t*>(slot + L.y_off + (size_t)L.rows * L.out * 2);
+}
+
 bool seq_wanted(const pd_stage* st, hipStream_t s, int B, int H, int T) {
   if (g_seq_mode != 1 || !st->bf16 || !st->seq_sync || !pd::lstm_seq_applies(B, H, T, st->n_cus)) return false;
   hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
@@ -1294,6 +1301,18 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
     tmp[i] = (uint16_t)(u >> 16);
   }
   PD_HIP(hipMemcpy(dst, tmp.data(), cnt * 2, hipMemcpyHostToDevice));
+  // a 2x2 max-pooling layer that reads this tensor has recorded where ITS maxima were: pool again, so that its
+  // routing words (and its stored output) belong to the values the tensor holds now
+  char* slot = st->stash_slot(mb_id);
+  for (int li = 0; li < nl; ++li) {
+    const Layer& L = st->lin[li];
+    if (L.kind != K_POOL || (what == 0 ? L.src != layer : L.src >= 0)) continue;
+    const char* a = L.src < 0 ? st->in_slot(mb_id) : st->out_of(slot, L.src);
+    PD_HIP(pd::maxpool2x2_forward_bf16(st->stream, reinterpret_cast<const pd::bf16_t*>(a),
+                                       reinterpret_cast<pd::bf16_t*>(st->out_of(slot, li)), pool_route(st, slot, L), st->B,
+                                       L.ih, L.iw, L.ic));
+    PD_HIP(hipStreamSynchronize(st->stream));
+  }
   return PD_OK;
 }
 
@@ -1394,7 +1413,7 @@ static int forward_impl(pd_stage* st, int32_t mb_id, int32_t version, const void
       PD_HIP(pd::conv_forward_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), wp + L.w_off, g, ep));
     } else if (L.kind == K_POOL) {
       PD_HIP(pd::maxpool2x2_forward_bf16(s, reinterpret_cast<const pd::bf16_t*>(a), reinterpret_cast<pd::bf16_t*>(y),
-                                         st->B, L.ih, L.iw, L.ic));
+                                         pool_route(st, slot, L), st->B, L.ih, L.iw, L.ic));
     } else if (L.kind == K_GPOOL) {
       const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
       PD_HIP(pd::pool2d_forward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(a),
@@ -1600,10 +1619,9 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
       PD_HIP(pd::conv_dgrad_bf16(s, reinterpret_cast<const pd::bf16_t*>(cur), wp + L.w_off,
                                  reinterpret_cast<pd::bf16_t*>(st->wt), g, ep));
     } else if (L.kind == K_POOL) {
-      PD_HIP(pd::maxpool2x2_backward_bf16(s, reinterpret_cast<const pd::bf16_t*>(x),
-                                          reinterpret_cast<const pd::bf16_t*>(st->out_of(slot, l)),
-                                          reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out),
-                                          st->B, L.ih, L.iw, L.ic, mask != nullptr));
+      PD_HIP(pd::maxpool2x2_backward_routed_bf16(s, pool_route(st, slot, L), reinterpret_cast<const pd::bf16_t*>(cur),
+                                                 reinterpret_cast<pd::bf16_t*>(out), st->B, L.ih, L.iw, L.ic,
+                                                 mask != nullptr));
     } else {  // K_GPOOL (the pooling kernels take the mask as "x > 0", x being the stored output of the producer)
       const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
       PD_HIP(pd::pool2d_backward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(x),
@@ -2386,10 +2404,25 @@ int pd_conv_wgrad_update_bf16(void* stream, const void* dz, const void* x, float
 }
 
 int pd_maxpool2x2_fwd_bf16(void* stream, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C) {
+  return pd_maxpool2x2_fwd_route_bf16(stream, x, y, nullptr, N, H, W, C);
+}
+
+int pd_maxpool2x2_fwd_route_bf16(void* stream, const void* x, void* y, uint32_t* route, int32_t N, int32_t H, int32_t W,
+                                 int32_t C) {
   if (!x || !y || N < 1 || H < 2 || W < 2 || C < 8 || (C % 8) || (H % 2) || (W % 2))
     return fail(PD_EINVAL, "pooling needs even height/width and channels divisible by 8");
   PD_HIP(pd::maxpool2x2_forward_bf16(static_cast<hipStream_t>(stream), static_cast<const pd::bf16_t*>(x),
-                                     static_cast<pd::bf16_t*>(y), N, H, W, C));
+                                     static_cast<pd::bf16_t*>(y), route, N, H, W, C));
+  return PD_OK;
+}
+
+int pd_maxpool2x2_bwd_route_bf16(void* stream, const uint32_t* route, const void* dy, void* dx, int32_t N, int32_t H,
+                                 int32_t W, int32_t C, int32_t relu_mask) {
+  if (!route || !dy || !dx || N < 1 || H < 2 || W < 2 || C < 8 || (C % 8) || (H % 2) || (W % 2))
+    return fail(PD_EINVAL, "pooling needs even height/width and channels divisible by 8");
+  PD_HIP(pd::maxpool2x2_backward_routed_bf16(static_cast<hipStream_t>(stream), route,
+                                             static_cast<const pd::bf16_t*>(dy), static_cast<pd::bf16_t*>(dx), N, H, W,
+                                             C, relu_mask != 0));
   return PD_OK;
 }
 

@@ -457,6 +457,18 @@ def test_maxpool2x2_bf16(N, H, W, Cn):
         dx = torch.empty(x.shape, dtype=torch.bfloat16, device=dev())
         pd.pd_maxpool2x2_bwd_bf16(s, xd.data_ptr(), y.data_ptr(), dyd.data_ptr(), dx.data_ptr(), N, H, W, Cn, relu_mask)
         assert np.array_equal(to_host(dx), ref), relu_mask       # pure routing: bit-exact
+    # the pair that records the routing in the forward pass (what a stage runs): same outputs, no x or y in backward
+    route = torch.zeros(N * (H // 2) * (W // 2) * (Cn // 8), dtype=torch.int32, device=dev())
+    y2 = torch.empty_like(y)
+    pd.pd_maxpool2x2_fwd_route_bf16(s, xd.data_ptr(), y2.data_ptr(), route.data_ptr(), N, H, W, Cn)
+    assert torch.equal(y, y2)
+    for relu_mask in (False, True):
+        ref = OL.maxpool2d_backward(x, y_ref, dy, 2, 2)
+        if relu_mask:
+            ref = ref * (x > 0)
+        dx = torch.full(x.shape, 7.0, dtype=torch.bfloat16, device=dev())
+        pd.pd_maxpool2x2_bwd_route_bf16(s, route.data_ptr(), dyd.data_ptr(), dx.data_ptr(), N, H, W, Cn, relu_mask)
+        assert np.array_equal(to_host(dx), ref), relu_mask
 
 
 # ---------------------------------------------------------------------------------------------
