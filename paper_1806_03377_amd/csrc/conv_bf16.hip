@@ -258,6 +258,7 @@ __global__ __launch_bounds__(BN == 256 ? 512 : 256, BN == 256 ? 1 : 2) void conv
   constexpr int kSmem = DNS * STAGE > BM_ * OLD * 2 ? DNS * STAGE : BM_ * OLD * 2;
   constexpr int KS = DK / 16, MF = NI * NJ;
   __shared__ __attribute__((aligned(1024))) char smem[kSmem];
+  __shared__ __attribute__((aligned(16))) float sbias[BN];
   const int t = threadIdx.x, l = t & 63;
   const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w / WNW, wn = w % WNW;
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): renumber them so that an XCD works on a
@@ -273,6 +274,8 @@ __global__ __launch_bounds__(BN == 256 ? 512 : 256, BN == 256 ? 1 : 2) void conv
   const int co0 = tile_x * BN;
   const int P = g.N * g.Ho * g.Wo;
   const int p0 = tile_y * BM_;
+  // (read in the epilogue, behind every barrier of the pipeline; fetched now so that nobody waits for it there)
+  if (t < BN) sbias[t] = (ep.bias && co0 + t < g.Co) ? bf2f(ep.bias[co0 + t]) : 0.f;
   const int K = g.kh * g.kw * g.Ci;
   const int T = (K + DK - 1) / DK;
   const int Hl = UP ? (g.H - 1) * g.up + 1 : g.H, Wl = UP ? (g.W - 1) * g.up + 1 : g.W;
@@ -425,7 +428,7 @@ __global__ __launch_bounds__(BN == 256 ? 512 : 256, BN == 256 ? 1 : 2) void conv
 #pragma unroll
       for (int m = 0; m < MF; ++m) {
         const int i = m / NJ, j = m % NJ;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a[c][i]), frag(b[c][j]), acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(b[c][j]), frag(a[c][i]), acc[i][j], 0, 0, 0);
         constexpr int kGap = MF >= 8 ? 2 : 1;
         if (m % kGap == kGap - 1) {
           const int q = ks + KS * (m / kGap);
@@ -445,21 +448,29 @@ __global__ __launch_bounds__(BN == 256 ? 512 : 256, BN == 256 ? 1 : 2) void conv
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
 
-  // bias / ReLU / rounding in registers, then through LDS so that global traffic is 16 bytes per lane
+  // bias / ReLU / rounding in registers, then through LDS so that global traffic is 16 bytes per lane.  The filters
+  // are the MFMA's rows, so a lane holds runs of four channels of one pixel: acc[i][j][r] = channel 64 wn + 32 j +
+  // 8 (r >> 2) + 4 (l >> 5) + (r & 3) of tile pixel TM wm + 32 i + (l & 31), and a run goes to LDS as 8 bytes.
   bf16_t* ot = reinterpret_cast<bf16_t*>(smem);  // [BM_][OLD]
+  const float relu_floor = ep.relu ? 0.f : -__builtin_inff();
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int cl = 64 * wn + 32 * j + (l & 31), cch = co0 + cl;
-    const float bv = (ep.bias && cch < g.Co) ? bf2f(ep.bias[cch]) : 0.f;
+  for (int j = 0; j < NJ; ++j)
 #pragma unroll
-    for (int i = 0; i < NI; ++i)
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int ch = 64 * wn + 32 * j + 8 * q4 + 4 * (l >> 5);
+      const float4 b4 = *reinterpret_cast<const float4*>(&sbias[ch]);
+      const float bv[4] = {b4.x, b4.y, b4.z, b4.w};
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = acc[i][j][r] + bv;
-        if (ep.relu) v = fmaxf(v, 0.f);
-        ot[(TM * wm + 32 * i + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3)) * OLD + cl] = f2bf(v);
+      for (int i = 0; i < NI; ++i) {
+        float v[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = fmaxf(acc[i][j][4 * q4 + r] + bv[r], relu_floor);
+        uint2 pk;
+        pk.x = f2bf_pair(v[0], v[1]);
+        pk.y = f2bf_pair(v[2], v[3]);
+        *reinterpret_cast<uint2*>(&ot[(TM * wm + 32 * i + (l & 31)) * OLD + ch]) = pk;
       }
-  }
+    }
   __syncthreads();
   constexpr int CPR = BN / 8;
 #pragma unroll
