@@ -447,7 +447,11 @@ int pd_linear_wgrad_update_bf16(void* stream, const void* dz, const void* x, flo
  *               gives without reading x or y (this is what a stage's backward pass runs)
  *   pool2d_fwd / _bwd: pooling with any window, stride and padding (is_max != 0: max, padding never wins, pad
  *               must be 0 < window; else average with divisor window*window); pgeom = {N, H, W, C, window,
- *               stride, pad} (7 ints, host); backward as for PD_MAXPOOL2D / PD_AVGPOOL2D */
+ *               stride, pad} (7 ints, host); backward as for PD_MAXPOOL2D / PD_AVGPOOL2D
+ *   pool2d_fwd_route / _bwd_route: max pooling with a window of at most 4 x 4 and the routing recorded by the forward
+ *               pass: route (device, 8-byte aligned, written by _fwd_route, read by _bwd_route) holds one byte per
+ *               output element, N*Ho*Wo*C bytes; _bwd_route gives exactly what _bwd gives without reading x or y
+ *               (this is what a stage's backward pass runs for such a layer); other windows: PD_EINVAL */
 int pd_conv_wgrad_splits(const int32_t* geom, int32_t* splits);
 int pd_conv_fwd_bf16(void* stream, const void* x, const void* w, const void* b, void* y, const int32_t* geom,
                      int32_t relu);
@@ -466,6 +470,9 @@ int pd_maxpool2x2_bwd_route_bf16(void* stream, const uint32_t* route, const void
 int pd_pool2d_fwd_bf16(void* stream, int32_t is_max, const void* x, void* y, const int32_t* pgeom);
 int pd_pool2d_bwd_bf16(void* stream, int32_t is_max, const void* x, const void* y, const void* dy, void* dx,
                        const int32_t* pgeom, int32_t relu_mask);
+int pd_pool2d_fwd_route_bf16(void* stream, const void* x, void* y, void* route, const int32_t* pgeom);
+int pd_pool2d_bwd_route_bf16(void* stream, const void* route, const void* dy, void* dx, const int32_t* pgeom,
+                             int32_t relu_mask);
 
 const char* pd_last_error(void); /* thread-local, static storage, never NULL */
 

@@ -36,9 +36,9 @@ int pd_stage_debug_read(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer
 /* Test/debug aid, the reverse direction: overwrites a stored tensor of in-flight minibatch mb_id with host values
  * (fp32, rounded to bfloat16 where the tensor is bfloat16; synchronises the stream).  what = 0: the stored output
  * of compute layer `layer` (not an LSTM); 1: the stage's input slot.  Lets a test drive the backward pass of a deep
- * stage on exactly the activations (and therefore the ReLU and max-pooling decisions) of a reference run.  A 2x2
- * max-pooling layer that reads the overwritten tensor pools it again, so that the routing it recorded in the forward
- * pass (and its stored output) belong to the new values. */
+ * stage on exactly the activations (and therefore the ReLU and max-pooling decisions) of a reference run.  If the
+ * minibatch's forward pass has run, a max-pooling layer that reads the overwritten tensor pools it again, so that the
+ * routing it recorded in the forward pass (and its stored output) belong to the new values. */
 int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t layer, const float* host_in, size_t n);
 
 /* Tuning knob (process-wide, not thread-safe): forward and dgrad products whose output has at least `min_tiles`

@@ -117,6 +117,8 @@ _SIGS = {
     "pd_maxpool2x2_bwd_route_bf16": [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32],
     "pd_pool2d_fwd_bf16": [_vp, _i32, _vp, _vp, C.POINTER(_i32)],
     "pd_pool2d_bwd_bf16": [_vp, _i32, _vp, _vp, _vp, _vp, C.POINTER(_i32), _i32],
+    "pd_pool2d_fwd_route_bf16": [_vp, _vp, _vp, _vp, C.POINTER(_i32)],
+    "pd_pool2d_bwd_route_bf16": [_vp, _vp, _vp, _vp, C.POINTER(_i32), _i32],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -562,3 +564,11 @@ def pd_pool2d_fwd_bf16(stream, is_max, x, y, pgeom):
 
 def pd_pool2d_bwd_bf16(stream, is_max, x, y, dy, dx, pgeom, relu_mask):
     _check(_lib.pd_pool2d_bwd_bf16(stream, int(is_max), x, y, dy, dx, _pgeom(*pgeom), int(relu_mask)))
+
+
+def pd_pool2d_fwd_route_bf16(stream, x, y, route, pgeom):
+    _check(_lib.pd_pool2d_fwd_route_bf16(stream, x, y, route, _pgeom(*pgeom)))
+
+
+def pd_pool2d_bwd_route_bf16(stream, route, dy, dx, pgeom, relu_mask):
+    _check(_lib.pd_pool2d_bwd_route_bf16(stream, route, dy, dx, _pgeom(*pgeom), int(relu_mask)))

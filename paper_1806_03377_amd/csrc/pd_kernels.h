@@ -179,7 +179,12 @@ hipError_t wgrad_reduce_update(hipStream_t s, const float* part, int splits, siz
 struct PoolGeom {
   int N, H, W, C, k, stride, pad, Ho, Wo;
 };
-hipError_t pool2d_forward_bf16(hipStream_t s, bool is_max, const bf16_t* x, bf16_t* y, const PoolGeom& g);
+// route (max pooling with a window of at most 4, else it must be null): null, or N * Ho * Wo * C bytes (8-byte
+// aligned) that record where each maximum came from; pool2d_backward_routed_bf16 then needs neither x nor y
+bool pool2d_routes(bool is_max, const PoolGeom& g);
+hipError_t pool2d_forward_bf16(hipStream_t s, bool is_max, const bf16_t* x, bf16_t* y, void* route, const PoolGeom& g);
+hipError_t pool2d_backward_routed_bf16(hipStream_t s, const void* route, const bf16_t* dy, bf16_t* dx, const PoolGeom& g,
+                                       bool relu_mask);
 hipError_t pool2d_backward_bf16(hipStream_t s, bool is_max, const bf16_t* x, const bf16_t* y, const bf16_t* dy,
                                 bf16_t* dx, const PoolGeom& g, bool relu_mask);
 // Channel concatenation helpers for [pixels][channels] bf16 tensors (all channel counts % 8 == 0):

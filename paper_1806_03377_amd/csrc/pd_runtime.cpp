@@ -655,8 +655,9 @@ hipError_t seq_chain_leave(hipStream_t s) {
 }
 
 // (Not under stream capture: the chain's events lie outside the capture, and a replayed graph would bypass the chain.)
-// Where a 2x2 max-pooling layer keeps the routing words of a minibatch (four bits per output element): behind its
-// bf16 output in the layer's region of the stash slot, which is laid out for four bytes per element.  (Always the
+// Where a max-pooling layer keeps the routing record of a minibatch (four bits per output element for the 2x2 kernel,
+// a byte for the general one): behind its bf16 output in the layer's region of the stash slot, which is laid out for
+// four bytes per element.  (Always the
 // slot's own region, also when the stage's last output lives in a buffer borrowed from the consumer.)
 static uint32_t* pool_route(const pd_stage* st, char* slot, const Linear& L) {
   return reinterpret_cast<uint32_t*>(slot + L.y_off + (size_t)L.rows * L.out * 2);
@@ -1301,16 +1302,27 @@ int pd_stage_debug_write(pd_stage* st, int32_t what, int32_t mb_id, int32_t laye
     tmp[i] = (uint16_t)(u >> 16);
   }
   PD_HIP(hipMemcpy(dst, tmp.data(), cnt * 2, hipMemcpyHostToDevice));
-  // a 2x2 max-pooling layer that reads this tensor has recorded where ITS maxima were: pool again, so that its
-  // routing words (and its stored output) belong to the values the tensor holds now
+  // a max-pooling layer that reads this tensor has recorded where ITS maxima were: pool again, so that its
+  // routing words (and its stored output) belong to the values the tensor holds now.  Only for a minibatch whose
+  // forward pass has run here (an input slot may be written before that, while an older minibatch still owns the
+  // stash slot; the forward pass then records the routing itself).
+  bool forward_done = false;
+  for (const InFlight& f : st->in_flight) forward_done = forward_done || f.mb == mb_id;
   char* slot = st->stash_slot(mb_id);
-  for (int li = 0; li < nl; ++li) {
+  for (int li = 0; forward_done && li < nl; ++li) {
     const Layer& L = st->lin[li];
-    if (L.kind != K_POOL || (what == 0 ? L.src != layer : L.src >= 0)) continue;
+    if ((L.kind != K_POOL && L.kind != K_GPOOL) || (what == 0 ? L.src != layer : L.src >= 0)) continue;
     const char* a = L.src < 0 ? st->in_slot(mb_id) : st->out_of(slot, L.src);
-    PD_HIP(pd::maxpool2x2_forward_bf16(st->stream, reinterpret_cast<const pd::bf16_t*>(a),
-                                       reinterpret_cast<pd::bf16_t*>(st->out_of(slot, li)), pool_route(st, slot, L), st->B,
-                                       L.ih, L.iw, L.ic));
+    if (L.kind == K_POOL) {
+      PD_HIP(pd::maxpool2x2_forward_bf16(st->stream, reinterpret_cast<const pd::bf16_t*>(a),
+                                         reinterpret_cast<pd::bf16_t*>(st->out_of(slot, li)), pool_route(st, slot, L),
+                                         st->B, L.ih, L.iw, L.ic));
+    } else {
+      const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
+      if (!pd::pool2d_routes(L.is_max, g)) continue;
+      PD_HIP(pd::pool2d_forward_bf16(st->stream, true, reinterpret_cast<const pd::bf16_t*>(a),
+                                     reinterpret_cast<pd::bf16_t*>(st->out_of(slot, li)), pool_route(st, slot, L), g));
+    }
     PD_HIP(hipStreamSynchronize(st->stream));
   }
   return PD_OK;
@@ -1417,7 +1429,8 @@ static int forward_impl(pd_stage* st, int32_t mb_id, int32_t version, const void
     } else if (L.kind == K_GPOOL) {
       const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
       PD_HIP(pd::pool2d_forward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(a),
-                                     reinterpret_cast<pd::bf16_t*>(y), g));
+                                     reinterpret_cast<pd::bf16_t*>(y),
+                                     pd::pool2d_routes(L.is_max, g) ? pool_route(st, slot, L) : nullptr, g));
     } else {  // K_CONCAT: assemble the block's output from the branch outputs, branch 0 first
       const size_t pixels = (size_t)st->B * L.oh * L.ow;
       for (int b = 0; b < L.nbr; ++b)
@@ -1624,10 +1637,14 @@ static int backward_impl(pd_stage* st, int32_t mb_id, const void* dy_dev, void* 
                                                  mask != nullptr));
     } else {  // K_GPOOL (the pooling kernels take the mask as "x > 0", x being the stored output of the producer)
       const pd::PoolGeom g = {st->B, L.ih, L.iw, L.ic, L.kh, L.stride, L.ph, L.oh, L.ow};
-      PD_HIP(pd::pool2d_backward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(x),
-                                      reinterpret_cast<const pd::bf16_t*>(st->out_of(slot, l)),
-                                      reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out), g,
-                                      mask != nullptr));
+      if (pd::pool2d_routes(L.is_max, g))
+        PD_HIP(pd::pool2d_backward_routed_bf16(s, pool_route(st, slot, L), reinterpret_cast<const pd::bf16_t*>(cur),
+                                               reinterpret_cast<pd::bf16_t*>(out), g, mask != nullptr));
+      else
+        PD_HIP(pd::pool2d_backward_bf16(s, L.is_max, reinterpret_cast<const pd::bf16_t*>(x),
+                                        reinterpret_cast<const pd::bf16_t*>(st->out_of(slot, l)),
+                                        reinterpret_cast<const pd::bf16_t*>(cur), reinterpret_cast<pd::bf16_t*>(out), g,
+                                        mask != nullptr));
     }
     cur = out;
     if (L.br_first && l == blk->b_first[0]) {
@@ -2453,7 +2470,30 @@ int pd_pool2d_fwd_bf16(void* stream, int32_t is_max, const void* x, void* y, con
   if (pool_geom(pgeom, g, is_max)) return PD_EINVAL;
   if (!x || !y) return fail(PD_EINVAL, "null pointer");
   PD_HIP(pd::pool2d_forward_bf16(static_cast<hipStream_t>(stream), is_max != 0, static_cast<const pd::bf16_t*>(x),
-                                 static_cast<pd::bf16_t*>(y), g));
+                                 static_cast<pd::bf16_t*>(y), nullptr, g));
+  return PD_OK;
+}
+
+int pd_pool2d_fwd_route_bf16(void* stream, const void* x, void* y, void* route, const int32_t* pgeom) {
+  pd::PoolGeom g;
+  if (pool_geom(pgeom, g, 1)) return PD_EINVAL;
+  if (!x || !y || !route) return fail(PD_EINVAL, "null pointer");
+  if (!pd::pool2d_routes(true, g)) return fail(PD_EINVAL, "the routing record covers windows of at most 4 x 4");
+  if (reinterpret_cast<uintptr_t>(route) & 7) return fail(PD_EINVAL, "route must be 8-byte aligned");
+  PD_HIP(pd::pool2d_forward_bf16(static_cast<hipStream_t>(stream), true, static_cast<const pd::bf16_t*>(x),
+                                 static_cast<pd::bf16_t*>(y), route, g));
+  return PD_OK;
+}
+
+int pd_pool2d_bwd_route_bf16(void* stream, const void* route, const void* dy, void* dx, const int32_t* pgeom,
+                             int32_t relu_mask) {
+  pd::PoolGeom g;
+  if (pool_geom(pgeom, g, 1)) return PD_EINVAL;
+  if (!route || !dy || !dx) return fail(PD_EINVAL, "null pointer");
+  if (!pd::pool2d_routes(true, g)) return fail(PD_EINVAL, "the routing record covers windows of at most 4 x 4");
+  if (reinterpret_cast<uintptr_t>(route) & 7) return fail(PD_EINVAL, "route must be 8-byte aligned");
+  PD_HIP(pd::pool2d_backward_routed_bf16(static_cast<hipStream_t>(stream), route, static_cast<const pd::bf16_t*>(dy),
+                                         static_cast<pd::bf16_t*>(dx), g, relu_mask != 0));
   return PD_OK;
 }
 

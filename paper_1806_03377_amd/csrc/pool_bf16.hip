@@ -12,9 +12,12 @@ __device__ __forceinline__ uint4 ld16(const bf16_t* p) { return *reinterpret_cas
 // One thread per (output pixel, 8 channels).  Max: the first maximum in row-major window order is kept (the
 // comparison is strict), padding is skipped.  Average: fp32 sum in row-major order over the positions inside the
 // image, divided by k*k (padding counts as zeros).
+// route (max pooling, window <= 4, optional): 8 bytes per thread, one per channel: bits 0-3 = the window position
+// a * k + b of the first maximum, bit 4 = that maximum is positive, bit 5 = it is not a NaN.  pool2d_bwd_route_kernel
+// needs nothing else of x and y.
 template <bool MAX>
 __global__ __launch_bounds__(256) void pool2d_fwd_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ y,
-                                                         PoolGeom g) {
+                                                         uint2* __restrict__ route, PoolGeom g) {
   const int C8 = g.C / 8;
   const size_t total = (size_t)g.N * g.Ho * g.Wo * C8;
   const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -27,11 +30,13 @@ __global__ __launch_bounds__(256) void pool2d_fwd_kernel(const bf16_t* __restric
   const size_t n = q / g.Ho;
   float acc[8];
   uint16_t best[8];
+  uint32_t pos[8];
   bool have = false;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     acc[j] = 0.f;
     best[j] = 0;
+    pos[j] = 0;
   }
   for (int a = 0; a < g.k; ++a) {
     const int hi = ho * g.stride - g.pad + a;
@@ -48,6 +53,7 @@ __global__ __launch_bounds__(256) void pool2d_fwd_kernel(const bf16_t* __restric
           if (!have || f > acc[j]) {
             acc[j] = f;
             best[j] = v[j];
+            pos[j] = (uint32_t)(a * g.k + b);
           }
         } else {
           acc[j] += f;
@@ -62,6 +68,59 @@ __global__ __launch_bounds__(256) void pool2d_fwd_kernel(const bf16_t* __restric
     for (int j = 0; j < 8; ++j) best[j] = f2bf(acc[j] * inv);
   }
   *reinterpret_cast<uint4*>(y + ((n * g.Ho + ho) * g.Wo + wo) * g.C + 8 * c8) = pack8(best);
+  if (MAX && route) {
+    uint32_t r[2] = {0u, 0u};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t code = (pos[j] & 15u) | (have && bf_positive(best[j]) ? 16u : 0u) | (have && acc[j] == acc[j] ? 32u : 0u);
+      r[j >> 2] |= code << (8 * (j & 3));
+    }
+    route[idx] = make_uint2(r[0], r[1]);
+  }
+}
+
+// Max pooling backward from the routing bytes: one thread per (input pixel, 8 channels) visits, in row-major order,
+// the windows that cover its pixel and adds dy where the window's recorded position is this pixel (and the maximum
+// was not a NaN and, with relu_mask, positive: the value at the recorded position IS the maximum).  Same sums in the
+// same order as the comparing kernel below, without reading x or y.
+__global__ __launch_bounds__(256) void pool2d_bwd_route_kernel(const uint2* __restrict__ route,
+                                                               const bf16_t* __restrict__ dy, bf16_t* __restrict__ dx,
+                                                               PoolGeom g, int relu_mask) {
+  const int C8 = g.C / 8;
+  const size_t total = (size_t)g.N * g.H * g.W * C8;
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= total) return;
+  const int c8 = (int)(idx % C8);
+  size_t q = idx / C8;
+  const int wi = (int)(q % g.W);
+  q /= g.W;
+  const int hi = (int)(q % g.H);
+  const size_t n = q / g.H;
+  float acc[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+  const int ho_hi = (hi + g.pad) / g.stride, wo_hi = (wi + g.pad) / g.stride;
+  int ho_lo = hi + g.pad - g.k + 1, wo_lo = wi + g.pad - g.k + 1;
+  ho_lo = ho_lo <= 0 ? 0 : (ho_lo + g.stride - 1) / g.stride;
+  wo_lo = wo_lo <= 0 ? 0 : (wo_lo + g.stride - 1) / g.stride;
+  const uint32_t need = relu_mask ? 48u : 32u;
+  for (int ho = ho_lo; ho <= ho_hi && ho < g.Ho; ++ho)
+    for (int wo = wo_lo; wo <= wo_hi && wo < g.Wo; ++wo) {
+      const size_t oidx = ((n * g.Ho + ho) * g.Wo + wo) * C8 + c8;
+      uint16_t dv[8];
+      unpack8(ld16(dy + oidx * 8), dv);
+      const uint2 r = route[oidx];
+      const uint32_t me = (uint32_t)((hi - (ho * g.stride - g.pad)) * g.k + (wi - (wo * g.stride - g.pad)));
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t code = ((j < 4 ? r.x : r.y) >> (8 * (j & 3))) & 255u;
+        if ((code & 15u) == me && (code & need) == need) acc[j] += bf2f(dv[j]);
+      }
+    }
+  uint16_t o[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) o[j] = f2bf(acc[j]);
+  *reinterpret_cast<uint4*>(dx + ((n * g.H + hi) * g.W + wi) * g.C + 8 * c8) = pack8(o);
 }
 
 // Gather form of the backward pass: one thread per (input pixel, 8 channels) visits, in row-major order, the
@@ -184,12 +243,25 @@ bool pool_geom_ok(const PoolGeom& g) {
 
 }  // namespace
 
-hipError_t pool2d_forward_bf16(hipStream_t s, bool is_max, const bf16_t* x, bf16_t* y, const PoolGeom& g) {
+bool pool2d_routes(bool is_max, const PoolGeom& g) { return is_max && g.k <= 4; }
+
+hipError_t pool2d_forward_bf16(hipStream_t s, bool is_max, const bf16_t* x, bf16_t* y, void* route, const PoolGeom& g) {
   if (!pool_geom_ok(g)) return hipErrorInvalidValue;
+  if (route && (!pool2d_routes(is_max, g) || (reinterpret_cast<uintptr_t>(route) & 7))) return hipErrorInvalidValue;
   const size_t total = (size_t)g.N * g.Ho * g.Wo * (g.C / 8);
   const unsigned blocks = (unsigned)((total + 255) / 256);
-  if (is_max) pool2d_fwd_kernel<true><<<blocks, 256, 0, s>>>(x, y, g);
-  else pool2d_fwd_kernel<false><<<blocks, 256, 0, s>>>(x, y, g);
+  if (is_max) pool2d_fwd_kernel<true><<<blocks, 256, 0, s>>>(x, y, static_cast<uint2*>(route), g);
+  else pool2d_fwd_kernel<false><<<blocks, 256, 0, s>>>(x, y, nullptr, g);
+  return hipGetLastError();
+}
+
+hipError_t pool2d_backward_routed_bf16(hipStream_t s, const void* route, const bf16_t* dy, bf16_t* dx, const PoolGeom& g,
+                                       bool relu_mask) {
+  if (!pool_geom_ok(g) || !pool2d_routes(true, g) || !route || (reinterpret_cast<uintptr_t>(route) & 7))
+    return hipErrorInvalidValue;
+  const size_t total = (size_t)g.N * g.H * g.W * (g.C / 8);
+  pool2d_bwd_route_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(static_cast<const uint2*>(route), dy, dx, g,
+                                                                          relu_mask ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -540,7 +540,7 @@ def test_conv_dgrad_strided_bf16(geom):
 
 @pytest.mark.parametrize("is_max,N,H,W,Cn,k,stride,pad", [
     (True, 2, 9, 7, 8, 3, 2, 0), (True, 1, 35, 35, 24, 3, 2, 0), (True, 2, 6, 6, 16, 3, 1, 0), (True, 2, 8, 8, 8, 2, 2, 0),
-    (True, 1, 10, 11, 8, 3, 3, 0), (True, 3, 3, 3, 8, 3, 1, 0),
+    (True, 1, 10, 11, 8, 3, 3, 0), (True, 3, 3, 3, 8, 3, 1, 0), (True, 2, 9, 9, 16, 4, 1, 0), (True, 1, 12, 12, 8, 5, 2, 0),
     (False, 2, 7, 6, 8, 3, 1, 1), (False, 1, 17, 17, 40, 3, 1, 1), (False, 3, 8, 8, 16, 8, 1, 0), (False, 2, 9, 9, 8, 3, 2, 1)])
 def test_pool2d_bf16(is_max, N, H, W, Cn, k, stride, pad):
     # coarse grid of values so that ties inside max windows are common
@@ -570,6 +570,15 @@ def test_pool2d_bf16(is_max, N, H, W, Cn, k, stride, pad):
         if is_max:
             assert np.array_equal(got == 0, ref == 0), relu_mask
         assert np.all(np.abs(got - ref) <= 2 ** -7 * np.abs(ref) + 1e-6), relu_mask
+        if is_max and k <= 4:
+            # the pair that records the routing in the forward pass (what a stage runs): the same bits as the pair above
+            route = torch.zeros(int(np.prod(y_ref.shape)), dtype=torch.uint8, device=dev())
+            y2 = torch.empty_like(yd)
+            pd.pd_pool2d_fwd_route_bf16(s, xd.data_ptr(), y2.data_ptr(), route.data_ptr(), pg)
+            assert torch.equal(y2, yd)
+            dx2 = torch.full(x.shape, 7.0, dtype=torch.bfloat16, device=dev())
+            pd.pd_pool2d_bwd_route_bf16(s, route.data_ptr(), dyd.data_ptr(), dx2.data_ptr(), pg, relu_mask)
+            assert torch.equal(dx2, dx), relu_mask
 
 
 def _inception_like(c0=8):
