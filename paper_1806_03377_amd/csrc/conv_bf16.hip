@@ -8,7 +8,7 @@
 //                            way into LDS; the pixel range is split over workgroups, partial sums go to memory
 //   wgrad_reduce_update      sums the partials in split order and applies the momentum-SGD update
 //   (conv_smallk_bf16.hip)   first layer of an image network (kh*kw*Ci <= 32, e.g. 3x3x3)
-//   (conv_wgrad_tr_bf16.hip) weight gradient of stride-1, size-preserving layers
+//   (conv_wgrad_tr_bf16.hip) weight gradient of stride-1 layers with at most "same" padding
 //   maxpool2x2_*             2x2/stride-2 max-pooling; backward sends the gradient to the first maximum in
 //                            row-major window order and applies the ReLU mask of the layer below
 #include "bf16_util.h"

@@ -1,4 +1,4 @@
-// Weight gradient of a stride-1, size-preserving bf16 convolution (NHWC, fp32 accumulate) for gfx950:
+// Weight gradient of a stride-1 bf16 convolution with at most "same" padding (NHWC, fp32 accumulate) for gfx950:
 //   dW[co][ta][tb][ci] = sum over output pixels p of dz[p][co] * x[p shifted by tap (ta, tb)][ci]
 // as partial sums over ranges of pixels (the caller adds the partials in a fixed order and applies the update).
 //
@@ -11,8 +11,9 @@
 // All taps of a group of filter rows are accumulated by ONE workgroup, so dz is read once instead of once per
 // tap.  To make every tap a constant shift of the input, pixels are numbered in a padded row-major space
 // ("virtual pixels"): rows have Wp = W + pw positions, position u of a row is input column u - pw (u < pw is the
-// zero padding, which the end of a row shares with the beginning of the next) and output column u (u >= W: no
-// output, dz is read as zero).  Tap (ta, tb) of output pixel v is then input position v + (ta - ph) Wp + tb.
+// zero padding, which the end of a row shares with the beginning of the next) and output column u (u >= Wo: no
+// output, dz is read as zero; likewise the last H - Ho rows of every image when the layer is padded less than
+// "same": pixels are numbered by input rows, a dz row is found from the count of output-less rows before it).  Tap (ta, tb) of output pixel v is then input position v + (ta - ph) Wp + tb.
 // A stage holds 64 virtual pixels: a [64][COT] tile of dz and, per filter row of the group, a band of
 // 64 + kw - 1 consecutive input positions x 64 input channels.  Whatever falls into the padding, outside the
 // image or beyond the last channel is fetched from a 16-byte block of zeros, so the inner loop has no masks.
@@ -111,7 +112,11 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_zero_block);
 
   // ---- loader state: every lane owns one 16-byte chunk of ZPW dz loads and XPW x loads per stage -----------
+  // (an unpadded or partly padded layer has fewer output rows and columns than input ones: dH input rows of every
+  // image and the last W - Wo positions of every row carry no output)
+  const int dH = g.H - g.Ho, qN = q64 / g.H;
   int zR[ZPW], zu[ZPW], zc[ZPW];  // padded row index, position in the row, first output channel (-1: none)
+  int zh[ZPW], zskip[ZPW];        // row inside its image; rows without output in the images before it
 #pragma unroll
   for (int i = 0; i < ZPW; ++i) {
     const int q = w + NWV * i;
@@ -128,6 +133,8 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
     const int v = chunk0 * kPix + row;
     zR[i] = v / Wp;
     zu[i] = v - zR[i] * Wp;
+    zh[i] = zR[i] % g.H;
+    zskip[i] = (zR[i] / g.H) * dH;
     const int co = co0 + 32 * b + 8 * piece;
     zc[i] = co < g.Co ? co : -1;
   }
@@ -152,14 +159,18 @@ __global__ __launch_bounds__(512 / AI, 1) void conv_wgrad_tr_kernel(const bf16_t
     // (addresses are formed unconditionally and selected afterwards: no branches around the loads)
     if (q < ZPW) {
       const int i = q;
-      const bool ok = zc[i] >= 0 && zR[i] < NH && zu[i] < g.W;
-      const bf16_t* cand = dZ + ((long long)(zR[i] * g.W + zu[i]) * g.Co + zc[i]);
+      const bool ok = zc[i] >= 0 && zR[i] < NH && zu[i] < g.Wo && zh[i] < g.Ho;
+      const bf16_t* cand = dZ + ((long long)((zR[i] - zskip[i]) * g.Wo + zu[i]) * g.Co + zc[i]);
       dma_chunk(ok ? cand : zero, stage + (w + NWV * i) * 1024);
       zu[i] += r64;
       zR[i] += q64;
       const int carry = zu[i] >= Wp ? 1 : 0;
       zu[i] -= carry ? Wp : 0;
       zR[i] += carry;
+      zh[i] += qH + carry;
+      const int wrap = zh[i] >= g.H ? 1 : 0;
+      zh[i] -= wrap ? g.H : 0;
+      zskip[i] += (qN + wrap) * dH;
     } else {
       const int i = q - ZPW;
       const int hi = xh[i] + xdt[i];
@@ -326,8 +337,11 @@ int rows_per_group(int kh, int kw) {
 }
 
 bool make_plan(const ConvGeom& g, TrPlan& p) {
-  if (g.stride != 1 || g.up > 1 || g.Ho != g.H || g.Wo != g.W) return false;
-  if (2 * g.ph != g.kh - 1 || 2 * g.pw != g.kw - 1) return false;
+  // stride 1 with at most "same" padding: Ho <= H, Wo <= W (the kernel numbers pixels by INPUT rows and columns and
+  // reads dz as zero where a position has no output)
+  if (g.stride != 1 || g.up > 1) return false;
+  if (g.ph < 0 || g.pw < 0 || 2 * g.ph > g.kh - 1 || 2 * g.pw > g.kw - 1) return false;
+  if (g.Ho != g.H + 2 * g.ph - g.kh + 1 || g.Wo != g.W + 2 * g.pw - g.kw + 1 || g.Ho < 1 || g.Wo < 1) return false;
   if (g.kw != 1 && g.kw != 3 && g.kw != 5 && g.kw != 7) return false;
   if ((g.Ci % 8) || (g.Co % 8) || g.Ci < 32) return false;
   const long long V = (long long)g.N * g.H * (g.W + g.pw);

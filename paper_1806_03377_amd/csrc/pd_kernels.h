@@ -159,7 +159,7 @@ void set_conv_wide_min_tiles(int min_tiles);
 int conv_wgrad_split_count(const ConvGeom& g);
 hipError_t conv_wgrad_partial_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* x, float* part, int splits,
                                    const ConvGeom& g);
-// The same partial sums for stride-1, size-preserving convolutions (conv_wgrad_tr_bf16.hip: all taps of a group of
+// The same partial sums for stride-1 convolutions with at most "same" padding (conv_wgrad_tr_bf16.hip: all taps of a group of
 // filter rows in one workgroup, operands fetched with transposing LDS reads).  conv_wgrad_tr_partials returns the
 // number of partials that kernel writes for this geometry, or 0 if the geometry is not covered;
 // conv_wgrad_split_count / conv_wgrad_partial_bf16 above choose between the two kernels themselves.

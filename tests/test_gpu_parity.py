@@ -324,6 +324,13 @@ CONVS = [  # N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w
     (70, 4, 4, 32, 32, 1, 1, 1, 0, 0),      # images smaller than one 64-pixel stage
     (4, 35, 35, 64, 96, 3, 3, 1, 1, 1),     # several pixel ranges per tile
     (3, 20, 28, 160, 256, 3, 3, 1, 1, 1),   # several channel tiles on both sides
+    # stride 1 with less than "same" padding (fewer output rows and columns than input ones): the same kernel, which
+    # numbers pixels by input rows and reads dz as zero where a position has no output
+    (2, 13, 13, 32, 40, 3, 3, 1, 0, 0),     # unpadded 3x3
+    (1, 20, 17, 80, 192, 3, 3, 1, 0, 0),    # ... several channel tiles, ragged input-channel tile
+    (5, 6, 9, 32, 32, 3, 3, 1, 0, 0),       # ... images shorter than a 64-pixel stage, several per stage
+    (2, 12, 12, 32, 16, 5, 5, 1, 1, 1),     # 5x5 padded by one
+    (2, 11, 10, 40, 24, 1, 7, 1, 0, 2),     # 1x7 padded by two
 ]
 
 
