@@ -692,10 +692,50 @@ __device__ __forceinline__ bf16x8 tn_frag(const char* lo, const char* hi) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
+// logical tile number -> tile coordinates: bands of four tile rows, walked column by column (neighbouring numbers
+// share operand panels in L2)
+__device__ __forceinline__ void tn_tile_of(int bid, int tiles_n, int tiles_k, int& tn, int& tk) {
+  constexpr int BAND = 4;
+  const int per_band = BAND * tiles_k, band = bid / per_band, rem = bid - band * per_band;
+  const int rows_in = tiles_n - band * BAND < BAND ? tiles_n - band * BAND : BAND;
+  tn = band * BAND + rem % rows_in;
+  tk = rem / rows_in;
+}
+
+// The tiles whose rows gemm_tn_kernel split (tail_splits partial tiles each): add the partial tiles in split order
+// and apply the update.  64 workgroups per tile, four elements per lane.
+__global__ __launch_bounds__(256) void tn_tail_update_kernel(const float* __restrict__ part, int n_tail, int splits,
+                                                             int tail_first, int tiles_n, int tiles_k, int N, int K,
+                                                             float* __restrict__ master, float* __restrict__ mom,
+                                                             bf16_t* __restrict__ ring, UpdateRule rule) {
+  const int t_i = blockIdx.x >> 6;
+  const int idx = ((blockIdx.x & 63) * 256 + threadIdx.x) * 4;  // element of the 256 x 256 tile
+  int tn, tk;
+  tn_tile_of(tail_first + t_i, tiles_n, tiles_k, tn, tk);
+  const int row = tn * GM + idx / GN, col = tk * GN + idx % GN;
+  if (row >= N || col >= K) return;  // (K is a multiple of 8: four columns are inside or outside together)
+  float4 g = *reinterpret_cast<const float4*>(part + (size_t)t_i * (GM * GN) + idx);
+  for (int z = 1; z < splits; ++z) {
+    const float4 p = *reinterpret_cast<const float4*>(part + ((size_t)z * n_tail + t_i) * (GM * GN) + idx);
+    g.x += p.x; g.y += p.y; g.z += p.z; g.w += p.w;
+  }
+  const size_t off = (size_t)row * K + col;
+  float4 mm = *reinterpret_cast<const float4*>(mom + off);
+  float4 ms = *reinterpret_cast<const float4*>(master + off);
+  apply_update(rule, g.x, mm.x, ms.x); apply_update(rule, g.y, mm.y, ms.y);
+  apply_update(rule, g.z, mm.z, ms.z); apply_update(rule, g.w, mm.w, ms.w);
+  *reinterpret_cast<float4*>(mom + off) = mm;
+  *reinterpret_cast<float4*>(master + off) = ms;
+  uint2 o;
+  o.x = f2bf_pair(ms.x, ms.y);
+  o.y = f2bf_pair(ms.z, ms.w);
+  *reinterpret_cast<uint2*>(ring + off) = o;
+}
+
 __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restrict__ Z, int ldz,
                                                          const bf16_t* __restrict__ X, int ldx, BigEpilogue ep, int M,
                                                          int N, int K, int tiles_n, int tiles_k, int splits,
-                                                         float* __restrict__ part) {
+                                                         float* __restrict__ part, int tail_first, int tail_splits) {
   constexpr int NW = 8, NI = 4, NJ = 2, TR = 32, KS = TR / 16, NS = 4, D = NS - 1;
   constexpr int ROWB = 512, TILE = TR * ROWB, STAGE = 2 * TILE;  // 16 KB per operand and stage
   constexpr int LPS = 2 * TILE / 1024 / NW;                      // wave-wide loads per wave and stage (4)
@@ -705,32 +745,44 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
   const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
   // splits > 1: the grid holds `splits` copies of the tile grid; copy z sums over its share of the rows and leaves an
   // fp32 partial gradient in part[z][N][K] (no update: the reducing kernel applies it)
+  // tail_splits > 1 (with splits == 1): tiles [0, tail_first) -- a whole number of rounds of the chip -- are computed
+  // as usual with the update in the store; each of the remaining tiles is computed by tail_splits workgroups over
+  // shares of the rows, which leave fp32 partial tiles in part[z][tail tile][256][256] for tn_tail_update_kernel.
+  // The last round of a launch whose tile count is a little over a multiple of the compute units would otherwise run
+  // on a fraction of the chip for a whole tile's time.
   const int n_tiles = tiles_n * tiles_k;
-  const int z = blockIdx.x / n_tiles;
-  int bid = blockIdx.x - z * n_tiles;
-  {
-    const int per = n_tiles >> 3;
+  int z, bid, my_splits = splits, tail_tile = -1;
+  if (tail_splits > 1 && (int)blockIdx.x >= tail_first) {
+    const int e = (int)blockIdx.x - tail_first, r = n_tiles - tail_first;
+    tail_tile = e % r;
+    z = e / r;
+    bid = tail_first + tail_tile;
+    my_splits = tail_splits;
+  } else {
+    const int span = tail_splits > 1 ? tail_first : n_tiles;
+    z = blockIdx.x / span;
+    bid = blockIdx.x - z * span;
+    const int per = span >> 3;
     if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
   }
   int tn, tk;
-  {
-    constexpr int BAND = 4;
-    const int per_band = BAND * tiles_k, band = bid / per_band, rem = bid - band * per_band;
-    const int rows_in = tiles_n - band * BAND < BAND ? tiles_n - band * BAND : BAND;
-    tn = band * BAND + rem % rows_in;
-    tk = rem / rows_in;
-  }
+  tn_tile_of(bid, tiles_n, tiles_k, tn, tk);
   const int n0 = tn * GM, k0 = tk * GN;
   int T = (M + TR - 1) / TR;
   int m_lo = 0, m_hi = M;  // this copy's rows
-  if (splits > 1) {
-    const int s0 = (int)((long long)z * T / splits), s1 = (int)((long long)(z + 1) * T / splits);
+  if (my_splits > 1) {
+    const int s0 = (int)((long long)z * T / my_splits), s1 = (int)((long long)(z + 1) * T / my_splits);
     m_lo = s0 * TR;
     m_hi = s1 * TR < M ? s1 * TR : M;
     T = s1 - s0;
     ep.bias = nullptr; ep.mask = nullptr; ep.relu = 0; ep.out = nullptr; ep.upd_master = nullptr;
-    ep.out_f = part + (size_t)z * N * K;
-    ep.ldo = K;
+    if (tail_tile >= 0) {  // a dense 256 x 256 tile of its own (the epilogue adds the tile's origin to its offsets)
+      ep.out_f = part + ((size_t)z * (n_tiles - tail_first) + tail_tile) * (GM * GN) - ((ptrdiff_t)n0 * GN + k0);
+      ep.ldo = GN;
+    } else {
+      ep.out_f = part + (size_t)z * N * K;
+      ep.ldo = K;
+    }
   }
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_tn_zero);
 
@@ -1124,9 +1176,40 @@ static int wgrad_big_splits(int M, int N, int K) {
   if (sp > 16) sp = 16;
   return sp >= 2 ? sp : 1;
 }
+// A weight gradient whose tile count is a little over a multiple of the compute units: the tiles of the last,
+// partly filled round have their rows split so that the round takes a fraction of a tile's time (gemm_tn_kernel's
+// tail_first / tail_splits).  first: tiles computed whole; tiles: tiles of the tail; splits: workgroups per tail tile.
+struct TailPlan {
+  int first, tiles, splits;
+  size_t bytes;
+};
+static int device_compute_units() {
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+    return 0;
+  return n;
+}
+static bool wgrad_tail_plan(int M, int N, int K, TailPlan& p) {
+  const int cus = device_compute_units();
+  const int tiles = ((N + GM - 1) / GM) * ((K + GN - 1) / GN);
+  if (cus < 8 || (cus % 8) != 0 || tiles < cus || M < 512 || (N % 8) != 0 || (K % 8) != 0) return false;
+  const int r = tiles % cus;
+  if (r == 0 || 2 * r > cus) return false;
+  int sp = cus / r;
+  if (sp > M / 256) sp = M / 256;
+  if (sp > 16) sp = 16;
+  if (sp < 2) return false;
+  p.first = tiles - r;  // (a multiple of 8: the renumbering over the XCDs covers all of it)
+  p.tiles = r;
+  p.splits = sp;
+  p.bytes = (size_t)sp * r * GM * GN * sizeof(float);
+  return true;
+}
 size_t linear_wgrad_update_big_scratch_bytes(int M, int N, int K) {
   const int sp = wgrad_big_splits(M, N, K);
-  return sp > 1 ? (size_t)sp * N * K * sizeof(float) : 0;
+  if (sp > 1) return (size_t)sp * N * K * sizeof(float);
+  TailPlan tp;
+  return wgrad_tail_plan(M, N, K, tp) ? tp.bytes : 0;
 }
 
 // splits > 1: the reduction (over the N out-features) is split; `scratch` then receives splits * M * K floats of
@@ -1168,7 +1251,7 @@ hipError_t linear_wgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
       ((reinterpret_cast<uintptr_t>(dz) | reinterpret_cast<uintptr_t>(x)) & 15) == 0) {
     // operands as they are: transposing LDS reads instead of a transposing pre-pass
     const int tn = (N + GM - 1) / GM, tk = (K + GN - 1) / GN;
-    gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, 1, nullptr);
+    gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, 1, nullptr, 0, 0);
     e = hipGetLastError();
   } else if (scratch && (M % 8) == 0 && scratch_bytes >= linear_wgrad_big_scratch_bytes(M, N, K)) {
     bf16_t* zt = static_cast<bf16_t*>(scratch);  // [N][M]
@@ -1222,12 +1305,24 @@ hipError_t linear_wgrad_update_big_bf16(hipStream_t s, const bf16_t* dz, const b
   const int sp = wgrad_big_splits(M, N, K);
   if (sp > 1 && scratch && scratch_bytes >= (size_t)sp * n_w * sizeof(float)) {
     float* parts = static_cast<float*>(scratch);  // (the column sums above are done with it: same stream)
-    gemm_tn_kernel<<<tn * tk * sp, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, sp, parts);
+    gemm_tn_kernel<<<tn * tk * sp, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, sp, parts, 0, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     return wgrad_reduce_update(s, parts, sp, n_w, n_w, 0, master_w, mom_w, ring_w, nullptr, nullptr, nullptr, rule);
   }
-  gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, 1, nullptr);
+  TailPlan tp;
+  if (wgrad_tail_plan(M, N, K, tp) && scratch && scratch_bytes >= tp.bytes &&
+      (reinterpret_cast<uintptr_t>(scratch) & 15) == 0) {
+    float* parts = static_cast<float*>(scratch);
+    gemm_tn_kernel<<<tp.first + tp.tiles * tp.splits, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, 1, parts, tp.first,
+                                                                    tp.splits);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    tn_tail_update_kernel<<<tp.tiles * 64, 256, 0, s>>>(parts, tp.tiles, tp.splits, tp.first, tn, tk, N, K, master_w,
+                                                        mom_w, ring_w, rule);
+    return hipGetLastError();
+  }
+  gemm_tn_kernel<<<tn * tk, 512, 0, s>>>(dz, N, x, K, ep, M, N, K, tn, tk, 1, nullptr, 0, 0);
   return hipGetLastError();
 }
 

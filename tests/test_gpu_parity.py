@@ -315,6 +315,7 @@ CONVS = [  # N, H, W, c_in, c_out, kh, kw, stride, pad_h, pad_w
     (2, 17, 17, 16, 16, 7, 1, 1, 3, 0),     # 7x1
     (1, 40, 40, 8, 8, 3, 3, 1, 1, 1),       # many pixels, few channels
     (600, 1, 1, 136, 264, 1, 1, 1, 0, 0),   # a plain matrix product with many rows (256 x 256-tile wgrad)
+    (600, 1, 1, 13312, 1280, 1, 1, 1, 0, 0),  # ... with 260 output tiles: four over a round of the chip, rows split
     # size-preserving stride-1 layers with >= 32 input channels: the all-taps-per-workgroup weight-gradient kernel
     (2, 17, 17, 32, 40, 1, 7, 1, 0, 3),     # 1x7, <= 64 output channels (pixel halves as separate partials)
     (2, 17, 17, 40, 72, 7, 1, 1, 3, 0),     # 7x1: filter rows in groups of 3, 3, 1
