@@ -231,17 +231,29 @@ __global__ __launch_bounds__(kThreads) void conv_smallk_wgrad_kernel(const bf16_
   // transposing reads: this lane supplies pixel 8*(l>>5) + ((l>>2)&3) (+4 for the high half) and four channels
   const int pixl = 64 * w + 8 * (l >> 5) + ((l >> 2) & 3);
   const int chb = (16 * ((l >> 4) & 1) + 4 * (l & 3)) * 2;
-  for (long long ch = chunk0; ch < chunk1; ++ch) {
+  // dz of a chunk: 8 pieces of 16 bytes per pixel and thread, requested one chunk ahead (they arrive while the MFMAs
+  // of the chunk before run: the wide tensor's memory latency is the one that matters here)
+  uint4 zreg[8];
+  auto fetch_dz = [&](long long ch) {
     const long long p0 = ch * 256;
-    // dz of the chunk: 8 pieces of 16 bytes per pixel; piece c of pixel r sits in 64-byte half (c/4) ^ ((r>>1)&1)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int c = t + kThreads * i, r = c >> 3, pc = c & 7;
       const long long p = p0 + r;
-      const uint4 v = (p < P && 8 * pc < g.Co) ? ldg16(dZ + (size_t)p * g.Co + 8 * pc) : zero16();
-      *reinterpret_cast<uint4*>(Zs + r * 128 + 64 * ((pc >> 2) ^ ((r >> 1) & 1)) + 16 * (pc & 3)) = v;
+      zreg[i] = (ch < chunk1 && p < P && 8 * pc < g.Co) ? ldg16(dZ + (size_t)p * g.Co + 8 * pc) : zero16();
+    }
+  };
+  fetch_dz(chunk0);
+  for (long long ch = chunk0; ch < chunk1; ++ch) {
+    const long long p0 = ch * 256;
+    // piece c of pixel r sits in 64-byte half (c/4) ^ ((r>>1)&1)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int c = t + kThreads * i, r = c >> 3, pc = c & 7;
+      *reinterpret_cast<uint4*>(Zs + r * 128 + 64 * ((pc >> 2) ^ ((r >> 1) & 1)) + 16 * (pc & 3)) = zreg[i];
     }
     gather_tile(X, g, p0, P, region, As);  // (its barriers also publish Zs)
+    fetch_dz(ch + 1);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int r = pixl + 16 * ks;  // ((r >> 1) & 1) does not depend on ks or on the +4 of the high half
