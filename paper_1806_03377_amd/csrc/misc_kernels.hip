@@ -211,6 +211,12 @@ __global__ __launch_bounds__(256) void softmax_xent_partials_kernel(const float*
 // The same for wide rows (a vocabulary): the row is read ONCE, 16 bytes per lane, and stays in registers
 // (NV float4 per thread, classes <= 1024 NV) for the maximum, the sum and the result; bf16 results leave as 8-byte
 // stores.  Needs classes % 4 == 0 and 16-byte aligned rows.
+// e^x for x <= 0 (a logit minus its row maximum) as 2^(x log2 e) on the hardware exponential: two instructions
+// where the library routine takes a dozen, which matters in a kernel that evaluates 30000 of them per row next to
+// 0.9 GB of traffic.  Relative error below 1e-5 over the range that contributes to the sum (the product's rounding,
+// |x| 2^-24, dominates); results under 2^-126 come out as zero.
+__device__ __forceinline__ float exp_nonpos(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896341f); }
+
 template <bool BF, int NV>
 __global__ __launch_bounds__(256) void softmax_xent_wide_kernel(const float* __restrict__ logits,
                                                                 const int32_t* __restrict__ labels,
@@ -245,7 +251,7 @@ __global__ __launch_bounds__(256) void softmax_xent_wide_kernel(const float* __r
     const int q = t + 256 * i;
     if (q < nq) {
       if ((lab >> 2) == q) zlab = (lab & 3) == 0 ? v[i].x : (lab & 3) == 1 ? v[i].y : (lab & 3) == 2 ? v[i].z : v[i].w;
-      v[i].x = expf(v[i].x - mx); v[i].y = expf(v[i].y - mx); v[i].z = expf(v[i].z - mx); v[i].w = expf(v[i].w - mx);
+      v[i].x = exp_nonpos(v[i].x - mx); v[i].y = exp_nonpos(v[i].y - mx); v[i].z = exp_nonpos(v[i].z - mx); v[i].w = exp_nonpos(v[i].w - mx);
       sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
     }
   }
