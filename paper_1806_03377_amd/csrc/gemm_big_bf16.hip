@@ -732,6 +732,36 @@ __global__ __launch_bounds__(256) void tn_tail_update_kernel(const float* __rest
   *reinterpret_cast<uint2*>(ring + off) = o;
 }
 
+// The same for an input gradient (gemm_nt_kernel's tail tiles): partial tiles added in split order, the ReLU mask of
+// the producing layer applied, rounded to bf16.
+__global__ __launch_bounds__(256) void nt_tail_store_kernel(const float* __restrict__ part, int n_tail, int splits,
+                                                            int tail_first, int tiles_i, int tiles_j, int I, int J,
+                                                            const bf16_t* __restrict__ mask, bf16_t* __restrict__ out) {
+  const int t_i = blockIdx.x >> 6;
+  const int idx = ((blockIdx.x & 63) * 256 + threadIdx.x) * 4;
+  int ti, tj;
+  tn_tile_of(tail_first + t_i, tiles_i, tiles_j, ti, tj);
+  const int row = ti * GM + idx / GN, col = tj * GN + idx % GN;
+  if (row >= I || col >= J) return;  // (J is a multiple of 8)
+  float4 g = *reinterpret_cast<const float4*>(part + (size_t)t_i * (GM * GN) + idx);
+  for (int z = 1; z < splits; ++z) {
+    const float4 p = *reinterpret_cast<const float4*>(part + ((size_t)z * n_tail + t_i) * (GM * GN) + idx);
+    g.x += p.x; g.y += p.y; g.z += p.z; g.w += p.w;
+  }
+  const size_t off = (size_t)row * J + col;
+  uint2 o;
+  o.x = f2bf_pair(g.x, g.y);
+  o.y = f2bf_pair(g.z, g.w);
+  if (mask) {
+    const uint2 mk = *reinterpret_cast<const uint2*>(mask + off);
+    if (!bf_positive((uint16_t)(mk.x & 0xffffu))) o.x &= 0xffff0000u;
+    if (!bf_positive((uint16_t)(mk.x >> 16))) o.x &= 0x0000ffffu;
+    if (!bf_positive((uint16_t)(mk.y & 0xffffu))) o.y &= 0xffff0000u;
+    if (!bf_positive((uint16_t)(mk.y >> 16))) o.y &= 0x0000ffffu;
+  }
+  *reinterpret_cast<uint2*>(out + off) = o;
+}
+
 __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restrict__ Z, int ldz,
                                                          const bf16_t* __restrict__ X, int ldx, BigEpilogue ep, int M,
                                                          int N, int K, int tiles_n, int tiles_k, int splits,
@@ -891,7 +921,7 @@ __global__ __launch_bounds__(512, 1) void gemm_tn_kernel(const bf16_t* __restric
 __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restrict__ A, int lda,
                                                          const bf16_t* __restrict__ Bm, int ldb, BigEpilogue ep, int I,
                                                          int J, int R, int tiles_i, int tiles_j, int splits,
-                                                         float* __restrict__ part) {
+                                                         float* __restrict__ part, int tail_first, int tail_splits) {
   constexpr int NW = 8, NI = 4, NJ = 2, KS = DK / 16, NS = 4, D = NS - 1;
   constexpr int ATILE = 256 * DROWB, BROWB = 512, BTILE = DK * BROWB, STAGE = ATILE + BTILE;  // 16 KB + 16 KB
   constexpr int QA = 2, QB = 2, LPS = QA + QB, MF = NI * NJ;
@@ -900,34 +930,44 @@ __global__ __launch_bounds__(512, 1) void gemm_nt_kernel(const bf16_t* __restric
   const int w = __builtin_amdgcn_readfirstlane(t >> 6), wm = w >> 2, wn = w & 3;
   // splits > 1: the grid holds `splits` copies of the tile grid; copy z reduces its share of the stages and leaves an
   // fp32 partial product in part[z][I][J] (no bias, activation or rounding: the reducing kernel applies them)
+  // tail_splits > 1 (with splits == 1): as in gemm_tn_kernel -- tiles [0, tail_first) are computed whole, each of the
+  // others by tail_splits workgroups over shares of the reduction, which leave fp32 partial tiles in
+  // part[z][tail tile][256][256] for nt_tail_store_kernel
   const int n_tiles = tiles_i * tiles_j;
-  const int z = blockIdx.x / n_tiles;
-  int bid = blockIdx.x - z * n_tiles;
-  {
-    const int per = n_tiles >> 3;
+  int z, bid, my_splits = splits, tail_tile = -1;
+  if (tail_splits > 1 && (int)blockIdx.x >= tail_first) {
+    const int e = (int)blockIdx.x - tail_first, r = n_tiles - tail_first;
+    tail_tile = e % r;
+    z = e / r;
+    bid = tail_first + tail_tile;
+    my_splits = tail_splits;
+  } else {
+    const int span = tail_splits > 1 ? tail_first : n_tiles;
+    z = blockIdx.x / span;
+    bid = blockIdx.x - z * span;
+    const int per = span >> 3;
     if (bid < per * 8) bid = (bid & 7) * per + (bid >> 3);
   }
   int ti, tj;
-  {
-    constexpr int BAND = 4;
-    const int per_band = BAND * tiles_j, band = bid / per_band, rem = bid - band * per_band;
-    const int rows_in = tiles_i - band * BAND < BAND ? tiles_i - band * BAND : BAND;
-    ti = band * BAND + rem % rows_in;
-    tj = rem / rows_in;
-  }
+  tn_tile_of(bid, tiles_i, tiles_j, ti, tj);
   const int i0 = ti * GM, j0 = tj * GN;
   int T = (R + DK - 1) / DK;
   const int tail = R % DK;          // reduction elements of a partial last stage (0: none)
   bool partial = tail != 0;         // this workgroup's last stage is that partial stage
-  if (splits > 1) {
-    const int s0 = (int)((long long)z * T / splits), s1 = (int)((long long)(z + 1) * T / splits);
+  if (my_splits > 1) {
+    const int s0 = (int)((long long)z * T / my_splits), s1 = (int)((long long)(z + 1) * T / my_splits);
     A += (size_t)s0 * DK;
     Bm += (size_t)s0 * DK * ldb;
     T = s1 - s0;
-    partial = partial && z == splits - 1;
+    partial = partial && z == my_splits - 1;
     ep.bias = nullptr; ep.mask = nullptr; ep.relu = 0; ep.out = nullptr; ep.upd_master = nullptr;
-    ep.out_f = part + (size_t)z * I * J;
-    ep.ldo = J;
+    if (tail_tile >= 0) {
+      ep.out_f = part + ((size_t)z * (n_tiles - tail_first) + tail_tile) * (GM * GN) - ((ptrdiff_t)i0 * GN + j0);
+      ep.ldo = GN;
+    } else {
+      ep.out_f = part + (size_t)z * I * J;
+      ep.ldo = J;
+    }
   }
   const bf16_t* const zero = reinterpret_cast<const bf16_t*>(g_tn_zero);
 
@@ -1189,14 +1229,13 @@ static int device_compute_units() {
     return 0;
   return n;
 }
-static bool wgrad_tail_plan(int M, int N, int K, TailPlan& p) {
+static bool tail_plan(int tiles, int max_splits, TailPlan& p) {
   const int cus = device_compute_units();
-  const int tiles = ((N + GM - 1) / GM) * ((K + GN - 1) / GN);
-  if (cus < 8 || (cus % 8) != 0 || tiles < cus || M < 512 || (N % 8) != 0 || (K % 8) != 0) return false;
+  if (cus < 8 || (cus % 8) != 0 || tiles < cus) return false;
   const int r = tiles % cus;
   if (r == 0 || 2 * r > cus) return false;
   int sp = cus / r;
-  if (sp > M / 256) sp = M / 256;
+  if (sp > max_splits) sp = max_splits;
   if (sp > 16) sp = 16;
   if (sp < 2) return false;
   p.first = tiles - r;  // (a multiple of 8: the renumbering over the XCDs covers all of it)
@@ -1204,6 +1243,10 @@ static bool wgrad_tail_plan(int M, int N, int K, TailPlan& p) {
   p.splits = sp;
   p.bytes = (size_t)sp * r * GM * GN * sizeof(float);
   return true;
+}
+static bool wgrad_tail_plan(int M, int N, int K, TailPlan& p) {
+  if (M < 512 || (N % 8) != 0 || (K % 8) != 0) return false;
+  return tail_plan(((N + GM - 1) / GM) * ((K + GN - 1) / GN), M / 256, p);
 }
 size_t linear_wgrad_update_big_scratch_bytes(int M, int N, int K) {
   const int sp = wgrad_big_splits(M, N, K);
@@ -1222,7 +1265,19 @@ hipError_t linear_dgrad_big_bf16(hipStream_t s, const bf16_t* dz, const bf16_t* 
       (size_t)M * N < ((size_t)1 << 31) && N / DK >= 4 * splits) {  // w as stored: transposing LDS reads on the B side
     const int ti = (M + GM - 1) / GM, tj = (K + GN - 1) / GN;
     if (splits > 1 && (!scratch || scratch_bytes < (size_t)splits * M * K * sizeof(float))) return hipErrorInvalidValue;
-    gemm_nt_kernel<<<ti * tj * splits, 512, 0, s>>>(dz, N, w, K, ep, M, K, N, ti, tj, splits, static_cast<float*>(scratch));
+    TailPlan tp;
+    if (splits == 1 && dx && tail_plan(ti * tj, N / DK / 8, tp) && scratch && scratch_bytes >= tp.bytes &&
+        (reinterpret_cast<uintptr_t>(scratch) & 15) == 0 && (reinterpret_cast<uintptr_t>(dx) & 7) == 0 &&
+        (!mask || (reinterpret_cast<uintptr_t>(mask) & 7) == 0)) {
+      float* parts = static_cast<float*>(scratch);
+      gemm_nt_kernel<<<tp.first + tp.tiles * tp.splits, 512, 0, s>>>(dz, N, w, K, ep, M, K, N, ti, tj, 1, parts, tp.first,
+                                                                      tp.splits);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      nt_tail_store_kernel<<<tp.tiles * 64, 256, 0, s>>>(parts, tp.tiles, tp.splits, tp.first, ti, tj, M, K, mask, dx);
+      return hipGetLastError();
+    }
+    gemm_nt_kernel<<<ti * tj * splits, 512, 0, s>>>(dz, N, w, K, ep, M, K, N, ti, tj, splits, static_cast<float*>(scratch), 0, 0);
     return hipGetLastError();
   }
   if (splits > 1) return hipErrorInvalidValue;

@@ -38,7 +38,10 @@ SHAPES = [(64, 128, 64), (64, 256, 4096), (64, 200, 264), (40, 136, 72), (1, 8, 
           (600, 1000, 4096), (300, 264, 2112), (1030, 2048, 520), (257, 4096, 4096),
           # the same with an output width that is not a multiple of 32: the input gradient's split reduction ends in a
           # partial stage (16, 24 and 8 elements)
-          (600, 2064, 1000), (300, 2072, 264), (520, 4104, 520)]
+          (600, 2064, 1000), (300, 2072, 264), (520, 4104, 520),
+          # a few output tiles more than a whole number of rounds of the chip (258 for the input gradient, 344 for the
+          # weight gradient): the tiles of the last round are split over the idle compute units
+          (600, 1024, 22016)]
 # the same products forced onto the large-tile kernels (threshold 1 tile): several tiles, ragged rows/columns, a
 # reduction length that is a multiple of 32, one that is not, one shorter than a stage
 BIG_SHAPES = [(512, 256, 256), (600, 1000, 520), (1030, 264, 136), (300, 520, 1000), (257, 8, 24), (700, 776, 4128), (2080, 264, 136)]
